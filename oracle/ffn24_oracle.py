@@ -1,0 +1,431 @@
+"""CPU oracle for the 2:4-activation-sparse Squared-ReLU FFN.  TEST INFRASTRUCTURE ONLY.
+
+This module is the slow, plain definition that the GPU library is checked against.  Only the
+tests, the smoke check and the benchmark's cpu_baseline leg may import it; the GPU product
+path never does, and this file shares no code with it.
+
+Everything is numpy.  Matrix products are taken in float64 (products of bf16/fp8 operands are
+exact there and the summation error is far below the storage precision); pointwise steps that
+decide a pruning pick are taken in the precision the kernels use (float32 arithmetic followed
+by round-to-nearest-even to the storage type), so that a pick depends on the same number on
+both sides.
+
+What the paper defines, and where (Haziza et al., "Accelerating Transformer Inference and
+Training with 2:4 Activation Sparsity"):
+  * Squared-ReLU FFN  Y3 = max(0, X1 W1)^2 W2                      -- Sec. 1, "Squared ReLU"
+  * 2:4 sparsity: at most 2 non-zeros in every 4 consecutive values -- Sec. 1, "Hardware-accelerated (2:4) sparsity"
+  * keep the 2 largest-magnitude scalars of each block of 4 of Y2    -- Sec. 2 (Approach), first paragraph
+  * A.B is accelerated when A is 2:4 along the features of a token ("token-wise"),
+    A^T.B when A is 2:4 along the tokens of a feature ("feature-wise") -- Fig. 2 caption
+  * backward graph: 6 GEMMs, those touching y2 or dy1 are the sparse ones -- Fig. 4 caption
+  * the feature-wise picks are made on top of the forward's token-wise mask -- Sec. 2, last paragraph
+  * forward order: activation, then sparsification, then FP8 quantisation -- Sec. 2, "We implemented 2 new kernels"
+
+Readings where the paper is silent (each is listed in the design notes of the repository):
+  * ties in magnitude go to the lower index; zeros take part like any value, so a group always
+    yields exactly two kept slots with i0 < i1;
+  * magnitude = the storage word with its sign bit cleared, compared as an unsigned integer;
+  * the pick is made on the activation after rounding to the storage type (bf16);
+  * metadata: one nibble i0 | (i1 << 2) per group, two groups per byte, even group in the low nibble;
+  * a per-feature bias b1 is added before the ReLU (a synthetic sparsity dial; b1 = None is the paper's FFN);
+  * one feature-wise mask, ranked on |H24|, is applied to both H24^T and dZ^T;
+  * dX uses only the token-wise mask.
+
+Parity pins live in tests/test_oracle_*.py.  Absolute output values for the benchmark shapes have
+no external pin (the paper prints none): "parity unpinned" beyond the invariants tested there.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+# --------------------------------------------------------------------------------------
+# storage-type rounding helpers (bf16, OCP fp8 e4m3)
+# --------------------------------------------------------------------------------------
+
+
+def f32_to_bf16_bits(x) -> np.ndarray:
+    """Round float32 to bfloat16 (round-to-nearest-even), returning the 16-bit words.
+
+    NaN maps to a quiet NaN with the sign preserved; infinities stay infinities.
+    """
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    u = x.view(np.uint32).astype(np.uint64)
+    lsb = (u >> np.uint64(16)) & np.uint64(1)
+    r = ((u + np.uint64(0x7FFF) + lsb) >> np.uint64(16)).astype(np.uint32)
+    nan = np.isnan(x)
+    if nan.any():
+        r = np.where(nan, (x.view(np.uint32) >> np.uint32(16)) | np.uint32(0x0040), r)
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b) -> np.ndarray:
+    b = np.ascontiguousarray(b, dtype=np.uint16)
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def round_bf16(x) -> np.ndarray:
+    """float32 -> nearest bf16 value, returned as float32."""
+    return bf16_bits_to_f32(f32_to_bf16_bits(x))
+
+
+_E4M3_MAX = 448.0
+
+
+def _e4m3_table() -> np.ndarray:
+    """Value of each of the 256 OCP e4m3 codes (bias 7, no infinities, S.1111.111 = NaN)."""
+    t = np.empty(256, dtype=np.float64)
+    for c in range(256):
+        s = -1.0 if c & 0x80 else 1.0
+        e = (c >> 3) & 0xF
+        m = c & 7
+        if e == 0xF and m == 7:
+            t[c] = np.nan
+        elif e == 0:
+            t[c] = s * (m / 8.0) * 2.0 ** (-6)
+        else:
+            t[c] = s * (1.0 + m / 8.0) * 2.0 ** (e - 7)
+    return t
+
+
+E4M3_VALUES = _e4m3_table()
+
+
+def f32_to_e4m3_bits(x) -> np.ndarray:
+    """Saturating round-to-nearest-even conversion float32 -> OCP e4m3 code.
+
+    Finite inputs beyond +-448 clamp to +-448 (codes 0x7E / 0xFE); NaN gives 0x7F | sign.
+    Written as a search over the non-negative code values (a 127-entry table), which is the
+    definition of round-to-nearest with ties to the even code.
+    """
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    a = np.abs(x.astype(np.float64))
+    pos = E4M3_VALUES[:0x7F]  # codes 0x00..0x7E, ascending, 0 .. 448
+    a_c = np.minimum(a, _E4M3_MAX)
+    hi = np.searchsorted(pos, a_c, side="left")  # first code with value >= a
+    hi = np.minimum(hi, 0x7E)
+    lo = np.maximum(hi - 1, 0)
+    d_hi = pos[hi] - a_c
+    d_lo = a_c - pos[lo]
+    pick_lo = (d_lo < d_hi) | ((d_lo == d_hi) & ((lo & 1) == 0))
+    code = np.where(pick_lo, lo, hi).astype(np.uint8)
+    code = np.where(np.isnan(x), np.uint8(0x7F), code)
+    sign = (x.view(np.uint32) >> np.uint32(31)).astype(np.uint8) << np.uint8(7)
+    return (code | sign).astype(np.uint8)
+
+
+def e4m3_bits_to_f32(b) -> np.ndarray:
+    return E4M3_VALUES[np.ascontiguousarray(b, dtype=np.uint8)].astype(np.float32)
+
+
+def round_e4m3(x) -> np.ndarray:
+    return e4m3_bits_to_f32(f32_to_e4m3_bits(x))
+
+
+# --------------------------------------------------------------------------------------
+# 2:4 pruning (Sec. 2: "keep the 2 highest magnitude scalars and drop the others")
+# --------------------------------------------------------------------------------------
+
+_MAG_MASK = {2: 0x7FFF, 1: 0x7F}
+
+
+def _as_words(h):
+    h = np.ascontiguousarray(h)
+    if h.dtype not in (np.uint16, np.uint8):
+        raise TypeError("sparsify24 works on storage words: uint16 (bf16) or uint8 (e4m3)")
+    return h
+
+
+def pick24(words: np.ndarray):
+    """For storage words of shape [rows, cols] (cols % 4 == 0) return (i0, i1), each [rows, cols/4].
+
+    Inside every group of 4 consecutive columns the entries are ordered by (magnitude descending,
+    index ascending); the first two of that order are kept and reported as i0 < i1.
+    """
+    w = _as_words(words)
+    rows, cols = w.shape
+    if cols % 4:
+        raise ValueError("cols must be a multiple of 4")
+    mag = (w & w.dtype.type(_MAG_MASK[w.dtype.itemsize])).astype(np.int64).reshape(rows, cols // 4, 4)
+    # stable sort on the negated magnitude = magnitude descending, index ascending among equals
+    order = np.argsort(-mag, axis=-1, kind="stable")
+    kept = np.sort(order[..., :2], axis=-1)
+    return kept[..., 0].astype(np.uint8), kept[..., 1].astype(np.uint8)
+
+
+def sparsify24(words: np.ndarray):
+    """2:4-compress storage words [rows, cols] along the columns.
+
+    Returns (values [rows, cols/2] of the same dtype, meta [rows, cols/8] uint8).
+    values[:, 2g], values[:, 2g+1] are the kept entries of group g in index order;
+    the nibble of group g is i0 | (i1 << 2), stored in the low half of byte g//2 for even g.
+    cols must be a multiple of 8 so that every metadata byte is whole.
+    """
+    w = _as_words(words)
+    rows, cols = w.shape
+    if cols % 8:
+        raise ValueError("cols must be a multiple of 8")
+    i0, i1 = pick24(w)
+    g = w.reshape(rows, cols // 4, 4)
+    v0 = np.take_along_axis(g, i0[..., None].astype(np.int64), axis=-1)[..., 0]
+    v1 = np.take_along_axis(g, i1[..., None].astype(np.int64), axis=-1)[..., 0]
+    values = np.stack([v0, v1], axis=-1).reshape(rows, cols // 2)
+    nib = (i0 | (i1 << np.uint8(2))).astype(np.uint8)
+    meta = (nib[:, 0::2] | (nib[:, 1::2] << np.uint8(4))).astype(np.uint8)
+    return values, meta
+
+
+def unpack_meta(meta: np.ndarray):
+    """meta [rows, cols/8] -> (i0, i1) each [rows, cols/4]."""
+    meta = np.ascontiguousarray(meta, dtype=np.uint8)
+    rows, nb = meta.shape
+    nib = np.empty((rows, nb * 2), dtype=np.uint8)
+    nib[:, 0::2] = meta & 0xF
+    nib[:, 1::2] = meta >> 4
+    return nib & 3, (nib >> 2) & 3
+
+
+def mask_from_meta(meta: np.ndarray) -> np.ndarray:
+    """Boolean keep-mask [rows, cols] described by the metadata."""
+    i0, i1 = unpack_meta(meta)
+    rows, ng = i0.shape
+    m = np.zeros((rows, ng, 4), dtype=bool)
+    np.put_along_axis(m, i0[..., None].astype(np.int64), True, axis=-1)
+    np.put_along_axis(m, i1[..., None].astype(np.int64), True, axis=-1)
+    return m.reshape(rows, ng * 4)
+
+
+def decompress24(values: np.ndarray, meta: np.ndarray) -> np.ndarray:
+    """Inverse of sparsify24 on the kept entries: a dense [rows, cols] array with zeros elsewhere."""
+    i0, i1 = unpack_meta(meta)
+    rows, ng = i0.shape
+    v = np.ascontiguousarray(values).reshape(rows, ng, 2)
+    out = np.zeros((rows, ng, 4), dtype=v.dtype)
+    np.put_along_axis(out, i0[..., None].astype(np.int64), v[..., 0:1], axis=-1)
+    np.put_along_axis(out, i1[..., None].astype(np.int64), v[..., 1:2], axis=-1)
+    return out.reshape(rows, ng * 4)
+
+
+def compress_with_meta(dense: np.ndarray, meta: np.ndarray) -> np.ndarray:
+    """Gather the entries of `dense` [rows, cols] at the positions the metadata names -> [rows, cols/2]."""
+    i0, i1 = unpack_meta(meta)
+    rows, ng = i0.shape
+    g = np.ascontiguousarray(dense).reshape(rows, ng, 4)
+    v0 = np.take_along_axis(g, i0[..., None].astype(np.int64), axis=-1)[..., 0]
+    v1 = np.take_along_axis(g, i1[..., None].astype(np.int64), axis=-1)[..., 0]
+    return np.stack([v0, v1], axis=-1).reshape(rows, ng * 2)
+
+
+def gather_matmul24(values_f: np.ndarray, meta: np.ndarray, B: np.ndarray) -> np.ndarray:
+    """(compressed A) . B computed straight from (values, metadata): for each kept entry,
+    add value * B[4*group + index, :].  float64.  Must equal decompress24(...) @ B (Fig. 2)."""
+    i0, i1 = unpack_meta(meta)
+    rows, ng = i0.shape
+    v = np.asarray(values_f, dtype=np.float64).reshape(rows, ng, 2)
+    B = np.asarray(B, dtype=np.float64)
+    base = (4 * np.arange(ng, dtype=np.int64))[None, :]
+    k0 = base + i0.astype(np.int64)
+    k1 = base + i1.astype(np.int64)
+    out = np.zeros((rows, B.shape[1]), dtype=np.float64)
+    for r in range(rows):
+        out[r] = v[r, :, 0] @ B[k0[r]] + v[r, :, 1] @ B[k1[r]]
+    return out
+
+
+# --------------------------------------------------------------------------------------
+# quantisers
+# --------------------------------------------------------------------------------------
+
+
+class Bf16:
+    """Storage type bf16: q() rounds float32 to the nearest bf16 value; words()/from_words() expose the bits."""
+
+    name = "bf16"
+
+    @staticmethod
+    def q(x):
+        return round_bf16(np.asarray(x, dtype=np.float32))
+
+    @staticmethod
+    def words(x):
+        return f32_to_bf16_bits(np.asarray(x, dtype=np.float32))
+
+    @staticmethod
+    def from_words(w):
+        return bf16_bits_to_f32(w)
+
+
+class Exact:
+    """No storage rounding (used to pin the calculus against finite differences); words() are the
+    bf16 bits of the value, which is lossless for the small-integer test inputs it is used with."""
+
+    name = "exact"
+
+    @staticmethod
+    def q(x):
+        return np.asarray(x, dtype=np.float64)
+
+    words = staticmethod(Bf16.words)
+    from_words = staticmethod(Bf16.from_words)
+
+
+# --------------------------------------------------------------------------------------
+# forward
+# --------------------------------------------------------------------------------------
+
+
+def _preact(X, W1, b1, st):
+    Xq = st.q(X).astype(np.float64)
+    W1q = st.q(W1).astype(np.float64)
+    Z = Xq @ W1q
+    if b1 is not None:
+        Z = Z + np.asarray(b1, dtype=np.float64)[None, :]
+    return Xq, W1q, Z
+
+
+def _relu2(Z, st):
+    """R = max(0, Z), H = R^2.  With a storage type the two pointwise steps run in float32, as the kernels do."""
+    if st is Exact:
+        R = np.maximum(Z, 0.0)
+        return R, R * R
+    Z32 = Z.astype(np.float32)
+    R32 = np.maximum(Z32, np.float32(0))
+    H32 = R32 * R32
+    return R32, H32
+
+
+def ffn_fwd(X, W1, b1, W2, st=Bf16):
+    """Dense Squared-ReLU FFN (Sec. 1): Y = max(0, X W1 + b1)^2 W2, with H stored in the storage type."""
+    Xq, W1q, Z = _preact(X, W1, b1, st)
+    R, H = _relu2(Z, st)
+    Hq = st.q(H)
+    W2q = st.q(W2).astype(np.float64)
+    Y = Hq.astype(np.float64) @ W2q
+    return {"Z": Z, "R": R, "Rq": st.q(R), "Hq": Hq, "Y": Y, "Xq": Xq, "W1q": W1q, "W2q": W2q}
+
+
+def ffn24_fwd(X, W1, b1, W2, st=Bf16):
+    """Squared-ReLU FFN whose second GEMM sees the 2:4-pruned activation (Sec. 2, first paragraph).
+
+    Steps: Z = X W1 + b1;  H = max(0, Z)^2;  Hq = storage rounding of H;  per token and per group of
+    4 consecutive features keep the top-2 of |Hq| (ties -> lower index);  Y = H24 W2.
+    """
+    Xq, W1q, Z = _preact(X, W1, b1, st)
+    R, H = _relu2(Z, st)
+    Hq = st.q(H)
+    Hw = st.words(Hq)
+    Hc_w, meta = sparsify24(Hw)
+    Mtok = mask_from_meta(meta)
+    H24 = np.where(Mtok, Hq, Hq.dtype.type(0))
+    W2q = st.q(W2).astype(np.float64)
+    Y = H24.astype(np.float64) @ W2q
+    Rq = st.q(R)
+    return {
+        "Z": Z, "R": R, "Rq": Rq, "Hq": Hq, "H_words": Hw, "Hc_words": Hc_w, "meta": meta, "Mtok": Mtok,
+        "H24": H24, "Hc": compress_with_meta(Hq, meta), "Rc": compress_with_meta(Rq, meta),
+        "Y": Y, "Xq": Xq, "W1q": W1q, "W2q": W2q,
+    }
+
+
+# --------------------------------------------------------------------------------------
+# backward
+# --------------------------------------------------------------------------------------
+
+
+def featurewise24(H24, st=Bf16):
+    """2:4 picks along the tokens of each feature, made on the already token-wise-pruned H24
+    (Sec. 2, last paragraph).  H24 is [T, F]; the same top-2 rule runs on H24^T [F, T] in groups of
+    4 consecutive tokens.  Returns (Hc_t words [F, T/2], meta_t [F, T/8], M_T bool [T, F])."""
+    Ht_words = st.words(np.ascontiguousarray(np.asarray(H24).T))
+    Hc_t, meta_t = sparsify24(Ht_words)
+    M_T = mask_from_meta(meta_t).T
+    return Hc_t, meta_t, M_T
+
+
+def ffn24_bwd(fwd: dict, dY, st=Bf16, wgrad_mask="featurewise"):
+    """Backward of ffn24_fwd with the masks held fixed (Fig. 4 caption; Sec. 2, backward paragraphs).
+
+      dH  = dY W2^T                                  (dense)
+      dZ  = dH * 2 max(0, Z) * M_tok                  (ReLU^2 derivative on the kept positions; stored rounded)
+      dX  = dZ W1^T                                  (sparse along features: token-wise mask only)
+      dW2 = (H24 * M_T)^T dY,  dW1 = X^T (dZ * M_T)   (sparse along tokens: feature-wise mask on top)
+
+    wgrad_mask="tokenwise" replaces M_T by M_tok in the last line: the exact gradient of the pruned
+    forward, used only to pin the calculus.
+    """
+    dYq = st.q(dY).astype(np.float64)
+    dH = dYq @ fwd["W2q"].T
+    Mtok = fwd["Mtok"]
+    if st is Exact:
+        dZ = dH * 2.0 * fwd["Rq"]
+    else:
+        dZ = dH.astype(np.float32) * (np.float32(2) * fwd["Rq"].astype(np.float32))
+    dZ = np.where(Mtok, dZ, dZ.dtype.type(0))
+    dZq = st.q(dZ)
+    dX = dZq.astype(np.float64) @ fwd["W1q"].T
+    Hc_t, meta_t, M_T = featurewise24(fwd["H24"], st)
+    Mw = M_T if wgrad_mask == "featurewise" else Mtok
+    H24m = np.where(Mw, fwd["H24"], fwd["H24"].dtype.type(0)).astype(np.float64)
+    dZm = np.where(Mw, dZq, dZq.dtype.type(0)).astype(np.float64)
+    dW2 = H24m.T @ dYq
+    dW1 = fwd["Xq"].T @ dZm
+    dZc_t = compress_with_meta(np.ascontiguousarray(dZq.T), meta_t)
+    return {
+        "dH": dH, "dZq": dZq, "dZc": compress_with_meta(dZq, fwd["meta"]), "dX": dX, "dW1": dW1, "dW2": dW2,
+        "Hc_t_words": Hc_t, "meta_t": meta_t, "M_T": M_T, "dZc_t": dZc_t,
+    }
+
+
+def ffn_bwd(fwd: dict, dY, st=Bf16):
+    """Textbook backward of the dense FFN: dZ = (dY W2^T) * 2 max(0, Z); dX = dZ W1^T; dW2 = H^T dY; dW1 = X^T dZ."""
+    dYq = st.q(dY).astype(np.float64)
+    dH = dYq @ fwd["W2q"].T
+    if st is Exact:
+        dZ = dH * 2.0 * fwd["Rq"]
+    else:
+        dZ = dH.astype(np.float32) * (np.float32(2) * fwd["Rq"].astype(np.float32))
+    dZq = st.q(dZ)
+    dX = dZq.astype(np.float64) @ fwd["W1q"].T
+    dW2 = fwd["Hq"].astype(np.float64).T @ dYq
+    dW1 = fwd["Xq"].T @ dZq.astype(np.float64)
+    return {"dZq": dZq, "dX": dX, "dW1": dW1, "dW2": dW2}
+
+
+# --------------------------------------------------------------------------------------
+# fp8 forward (order of Sec. 2: activation, sparsification, then FP8 quantisation)
+# --------------------------------------------------------------------------------------
+
+
+def ffn24_fwd_fp8(X, W1, b1, W2, sx, sw1, sh, sw2):
+    """Per-tensor-scaled e4m3 variant.  Xq = e4m3(X / sx), W1q = e4m3(W1 / sw1);
+    Z = sx sw1 (Xq W1q) + b1;  the 2:4 pick is made on bf16(H) exactly as in ffn24_fwd;
+    the kept values are then quantised, Hc8 = e4m3(Hc / sh);  Y = sh sw2 (Hc8 . e4m3(W2 / sw2))."""
+    Xq = round_e4m3(np.asarray(X, np.float32) / np.float32(sx)).astype(np.float64)
+    W1q = round_e4m3(np.asarray(W1, np.float32) / np.float32(sw1)).astype(np.float64)
+    Z = (Xq @ W1q) * (float(sx) * float(sw1))
+    if b1 is not None:
+        Z = Z + np.asarray(b1, dtype=np.float64)[None, :]
+    R, H = _relu2(Z, Bf16)
+    Hq = round_bf16(H)
+    Hc_w, meta = sparsify24(f32_to_bf16_bits(Hq))
+    Hc = bf16_bits_to_f32(Hc_w)
+    Hc8_bits = f32_to_e4m3_bits(Hc / np.float32(sh))
+    Hc8 = e4m3_bits_to_f32(Hc8_bits)
+    W2q = round_e4m3(np.asarray(W2, np.float32) / np.float32(sw2)).astype(np.float64)
+    H24_8 = decompress24(Hc8, meta).astype(np.float64)
+    Y = (H24_8 @ W2q) * (float(sh) * float(sw2))
+    return {"Z": Z, "Hq": Hq, "meta": meta, "Hc8_bits": Hc8_bits, "Y": Y}
+
+
+# --------------------------------------------------------------------------------------
+# error measure used by the parity tests
+# --------------------------------------------------------------------------------------
+
+
+def max_rel_err(y, y_ref) -> float:
+    """max_i |y_i - ref_i| / max_i |ref_i|  (per tensor; element-wise ratios are unbounded at zeros)."""
+    y = np.asarray(y, dtype=np.float64)
+    y_ref = np.asarray(y_ref, dtype=np.float64)
+    den = float(np.max(np.abs(y_ref)))
+    if den == 0.0:
+        return float(np.max(np.abs(y)))
+    return float(np.max(np.abs(y - y_ref)) / den)

@@ -1,0 +1,83 @@
+"""Seeded synthetic inputs shaped like the paper's FFN workloads.
+
+This module holds no arithmetic of the method: it only draws the random tensors (and the bias that
+dials the activation sparsity) that both the CPU oracle and the GPU library are fed with.
+Shapes follow the paper's appendix table (model dimension 2048 / 4096, FFN hidden dimension
+8192 / 16384); the sparsity range follows Fig. 1 (84-98 % zeros after Squared-ReLU).
+
+All tensors are float32 numpy arrays; each consumer rounds them to its own storage type.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+from scipy.special import ndtri
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    T: int          # tokens
+    D: int          # model dimension
+    F: int          # FFN hidden dimension
+    sparsity: object  # float target fraction of zeros, or the string "per_feature"
+    seed: int
+
+
+WORKLOADS = {
+    # small case the oracle finishes in well under a second
+    "c1": Workload("c1", 256, 512, 2048, 0.90, 1000),
+    # 1B-model FFN dims, per-feature positive fraction uniform in [2 %, 15 %]
+    "c2": Workload("c2", 8192, 2048, 8192, "per_feature", 2000),
+    # 7B-model FFN dims, four layers at 85 / 90 / 95 / 98 % zeros
+    "c3_85": Workload("c3_85", 16384, 4096, 16384, 0.85, 3000),
+    "c3_90": Workload("c3_90", 16384, 4096, 16384, 0.90, 3001),
+    "c3_95": Workload("c3_95", 16384, 4096, 16384, 0.95, 3002),
+    "c3_98": Workload("c3_98", 16384, 4096, 16384, 0.98, 3003),
+    # forward + backward at the 7B dims, 90 % zeros
+    "c4": Workload("c4", 16384, 4096, 16384, 0.90, 4000),
+    # fp8 shape
+    "c5": Workload("c5", 8192, 8192, 32768, 0.95, 5000),
+}
+
+
+def bias_for(F: int, sparsity, rng: np.random.Generator) -> np.ndarray:
+    """Per-feature bias b1 such that, for pre-activations ~ N(0, 1), the wanted fraction is negative."""
+    if isinstance(sparsity, str):
+        if sparsity != "per_feature":
+            raise ValueError(sparsity)
+        p = rng.uniform(0.02, 0.15, size=F)           # positive fraction of each feature
+        return (-ndtri(1.0 - p)).astype(np.float32)
+    return np.full(F, -ndtri(float(sparsity)), dtype=np.float32)
+
+
+def make_inputs(T: int, D: int, F: int, sparsity, seed: int, with_dy: bool = False) -> dict:
+    """X ~ N(0,1) [T,D]; W1 ~ N(0,1/D) [D,F]; W2 ~ N(0,1/F) [F,D]; b1 [F]; optionally dY ~ N(0,1) [T,D]."""
+    rng = np.random.Generator(np.random.Philox(seed))
+    out = {
+        "X": rng.standard_normal((T, D), dtype=np.float32),
+        "W1": rng.standard_normal((D, F), dtype=np.float32) * np.float32(1.0 / np.sqrt(D)),
+        "W2": rng.standard_normal((F, D), dtype=np.float32) * np.float32(1.0 / np.sqrt(F)),
+        "b1": bias_for(F, sparsity, rng),
+    }
+    if with_dy:
+        out["dY"] = rng.standard_normal((T, D), dtype=np.float32)
+    return out
+
+
+def make_workload(name: str, with_dy: bool = False, T: int | None = None) -> dict:
+    """Inputs of a named workload; T overrides the token count (a token slice of the same recipe)."""
+    w = WORKLOADS[name]
+    return make_inputs(T or w.T, w.D, w.F, w.sparsity, w.seed, with_dy)
+
+
+def random_activation_words(rows: int, cols: int, p_nonzero: float, seed: int) -> np.ndarray:
+    """bf16 words of a non-negative activation-like matrix: each entry is zero with probability
+    1 - p_nonzero, else the square of a half-normal draw (what max(0, z)^2 looks like).  The float32
+    draw is truncated to its upper 16 bits, so the words are exact and no rounding rule is involved."""
+    rng = np.random.Generator(np.random.Philox(seed))
+    z = rng.standard_normal((rows, cols), dtype=np.float32)
+    keep = rng.random((rows, cols), dtype=np.float32) < np.float32(p_nonzero)
+    h = np.where(keep, z * z, np.float32(0)).astype(np.float32)
+    return (h.view(np.uint32) >> np.uint32(16)).astype(np.uint16)

@@ -1,0 +1,394 @@
+"""Pins for the CPU oracle: each test checks it against something other than itself --
+exhaustive enumeration, an independent characterisation, a library routine (torch CPU), a closed
+form, or an invariant the paper states.  No GPU needed."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import ffn24_oracle as O
+from paper_2503_16672_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ----------------------------------------------------------------------------- storage types
+def test_bf16_decode_encode_identity_all_codes():
+    codes = np.arange(65536, dtype=np.uint16)
+    f = O.bf16_bits_to_f32(codes)
+    finite_or_inf = ~np.isnan(f)
+    back = O.f32_to_bf16_bits(f)
+    assert np.array_equal(back[finite_or_inf], codes[finite_or_inf])
+    assert np.all(np.isnan(O.bf16_bits_to_f32(back[~finite_or_inf])))
+
+
+def test_bf16_matches_torch_cpu_cast():
+    rng = np.random.default_rng(0)
+    x = np.concatenate([
+        rng.standard_normal(200000).astype(np.float32) * np.float32(10.0) ** rng.integers(-20, 20, 200000).astype(np.float32),
+        np.array([0.0, -0.0, np.inf, -np.inf, 1.0, 1.00390625, 1.0078125, 3.3895314e38, 1e-40, -1e-45], np.float32),
+    ]).astype(np.float32)
+    ours = O.f32_to_bf16_bits(x)
+    theirs = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(ours, theirs)
+
+
+def test_bf16_midpoints_round_to_even():
+    # halfway between consecutive bf16 values c and c+1 (positive normals): the result must be the even code
+    codes = np.arange(0x0080, 0x7F7F, dtype=np.uint32)
+    mid = ((codes << 16) | 0x8000).astype(np.uint32).view(np.float32)
+    got = O.f32_to_bf16_bits(mid).astype(np.uint32)
+    want = np.where(codes & 1, codes + 1, codes)
+    assert np.array_equal(got, want)
+    just_above = ((codes << 16) | 0x8001).astype(np.uint32).view(np.float32)
+    assert np.array_equal(O.f32_to_bf16_bits(just_above).astype(np.uint32), codes + 1)
+    just_below = ((codes << 16) | 0x7FFF).astype(np.uint32).view(np.float32)
+    assert np.array_equal(O.f32_to_bf16_bits(just_below).astype(np.uint32), codes)
+
+
+def test_e4m3_table_matches_torch_decode():
+    codes = torch.arange(256, dtype=torch.int32).to(torch.uint8)
+    theirs = codes.view(torch.float8_e4m3fn).to(torch.float32).numpy()
+    ours = O.E4M3_VALUES.astype(np.float32)
+    assert np.array_equal(np.isnan(ours), np.isnan(theirs))
+    ok = ~np.isnan(ours)
+    assert np.array_equal(ours[ok], theirs[ok])
+    assert ours[0x7E] == 448.0 and ours[0x38] == 1.0 and ours[0x01] == 2.0 ** -9
+
+
+def test_e4m3_encode_identity_and_torch_cast_in_range():
+    codes = np.arange(256, dtype=np.uint8)
+    vals = O.e4m3_bits_to_f32(codes)
+    ok = ~np.isnan(vals)
+    back = O.f32_to_e4m3_bits(vals[ok])
+    # -0 and +0 keep their sign bit
+    assert np.array_equal(back, codes[ok])
+    rng = np.random.default_rng(1)
+    x = (rng.standard_normal(300000) * 10.0 ** rng.integers(-4, 3, 300000)).astype(np.float32)
+    x = x[np.abs(x) <= 448.0]
+    theirs = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(O.f32_to_e4m3_bits(x), theirs)
+
+
+def test_e4m3_saturates_and_ties_to_even():
+    x = np.array([449.0, 464.0, 480.0, 1e30, -1000.0, np.inf], np.float32)
+    assert list(O.f32_to_e4m3_bits(x)) == [0x7E, 0x7E, 0x7E, 0x7E, 0xFE, 0x7E]
+    # 17 lies halfway between 16 (0x58) and 18 (0x59): even code wins; 19 between 18 and 20 (0x5A)
+    assert list(O.f32_to_e4m3_bits(np.array([17.0, 19.0], np.float32))) == [0x58, 0x5A]
+    assert O.f32_to_e4m3_bits(np.array([np.nan], np.float32))[0] & 0x7F == 0x7F
+
+
+# ----------------------------------------------------------------------------- the 2:4 pick
+def _bruteforce_pick(mags):
+    """Independent characterisation: among the 6 index pairs, the one with the largest kept magnitude
+    sum; among equals, the lexicographically smallest pair."""
+    best = None
+    for pair in itertools.combinations(range(4), 2):
+        s = mags[pair[0]] + mags[pair[1]]
+        if best is None or s > best[0]:
+            best = (s, pair)
+    return best[1]
+
+
+def test_pick24_bruteforce_all_small_tuples():
+    vals = [0.0, 1.0, -1.0, 2.0, -2.0, 3.0, -3.0]
+    tuples = np.array(list(itertools.product(vals, repeat=4)), dtype=np.float32)  # 2401 x 4
+    words = O.f32_to_bf16_bits(tuples)
+    i0, i1 = O.pick24(words)
+    seen = set()
+    for row, a, b in zip(tuples, i0[:, 0], i1[:, 0]):
+        want = _bruteforce_pick(np.abs(row))
+        assert (a, b) == want, (row, a, b, want)
+        seen.add(int(a) | (int(b) << 2))
+    assert seen == {0x4, 0x8, 0xC, 0x9, 0xD, 0xE}
+
+
+def test_pick24_tie_rule_examples():
+    w = O.f32_to_bf16_bits(np.array([[0, 0, 5, 0], [0, 0, 0, 0], [2, 2, 2, 2], [1, 2, 2, 2], [-3, 3, 1, 3], [0.0, -0.0, 0, 1]], np.float32))
+    i0, i1 = O.pick24(w)
+    assert [(int(a), int(b)) for a, b in zip(i0[:, 0], i1[:, 0])] == [(0, 2), (0, 1), (0, 1), (1, 2), (0, 1), (0, 3)]
+
+
+def test_sparsify24_invariants_and_encoding():
+    words = synth.random_activation_words(64, 256, 0.3, seed=7)
+    values, meta = O.sparsify24(words)
+    assert values.shape == (64, 128) and meta.shape == (64, 32) and meta.dtype == np.uint8
+    i0, i1 = O.unpack_meta(meta)
+    assert np.all(i0 < i1)
+    dense = O.decompress24(values, meta)
+    # at most 2 non-zeros per group of 4 (Sec. 1, definition of 2:4)
+    assert np.all((dense.reshape(64, 64, 4) != 0).sum(-1) <= 2)
+    # what is kept is a subset of the input, in place
+    m = O.mask_from_meta(meta)
+    assert np.array_equal(dense[m], words[m]) and np.all(dense[~m] == 0)
+    assert np.all(m.reshape(64, 64, 4).sum(-1) == 2)
+    # every dropped magnitude <= every kept magnitude of its group
+    mag = (words & 0x7FFF).astype(np.int64).reshape(64, 64, 4)
+    mg = m.reshape(64, 64, 4)
+    kept_min = np.where(mg, mag, 1 << 20).min(-1)
+    drop_max = np.where(~mg, mag, -1).max(-1)
+    assert np.all(drop_max <= kept_min)
+    # byte layout: low nibble = even group
+    assert meta[3, 5] == (i0[3, 10] | (i1[3, 10] << 2) | (i0[3, 11] << 4) | (i1[3, 11] << 6))
+    # values are stored in index order
+    g = words.reshape(64, 64, 4)
+    assert values[9, 2 * 17] == g[9, 17, i0[9, 17]] and values[9, 2 * 17 + 1] == g[9, 17, i1[9, 17]]
+
+
+def test_sparsify24_lossless_when_already_24():
+    # Fig. 2 caption: if nothing has to be dropped the computation is exact
+    rng = np.random.default_rng(3)
+    h = rng.standard_normal((32, 64)).astype(np.float32) ** 2
+    kill = np.zeros((32, 16, 4), bool)
+    for r in range(32):
+        for g in range(16):
+            kill[r, g, rng.choice(4, size=rng.integers(2, 5), replace=False)] = True
+    h = np.where(kill.reshape(32, 64), 0, h).astype(np.float32)
+    w = O.f32_to_bf16_bits(h)
+    v, m = O.sparsify24(w)
+    assert np.array_equal(O.decompress24(v, m), w)
+
+
+def test_sparsify24_signed_and_negative_zero():
+    w = O.f32_to_bf16_bits(np.array([[-4.0, 3.0, -0.0, 0.0, -1.0, -1.0, 1.0, 0.5]], np.float32))
+    v, m = O.sparsify24(w)
+    assert list(O.bf16_bits_to_f32(v)[0]) == [-4.0, 3.0, -1.0, -1.0]
+    assert m[0, 0] == (0 | (1 << 2)) | ((0 | (1 << 2)) << 4)
+
+
+def test_drop_rate_closed_form():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "drop_rate.txt")) if l.strip() and not l.startswith("#")]
+    for p_s, want_s in rows:
+        p, want = float(p_s), float(want_s)
+        assert abs((4 * p ** 3 * (1 - p) + 2 * p ** 4) / (4 * p) - want) < 1e-6
+        words = synth.random_activation_words(2048, 4096, p, seed=int(p * 1000))
+        v, m = O.sparsify24(words)
+        nnz_in = np.count_nonzero(words)
+        nnz_out = np.count_nonzero(v)
+        got = (nnz_in - nnz_out) / nnz_in
+        assert abs(got - want) < 0.08 * want + 2e-5, (p, got, want)
+    # the paper's "about 1 %" at about 90 % sparsity
+    assert 0.005 < (4 * 0.1 ** 3 * 0.9 + 2 * 0.1 ** 4) / 0.4 < 0.015
+
+
+# ----------------------------------------------------------------------------- GEMM on the compressed operand
+def test_gather_matmul_equals_dense_matmul_on_pruned():
+    words = synth.random_activation_words(48, 128, 0.4, seed=11)
+    v, m = O.sparsify24(words)
+    B = np.random.default_rng(5).standard_normal((128, 24))
+    dense = O.bf16_bits_to_f32(O.decompress24(v, m)).astype(np.float64)
+    y1 = O.gather_matmul24(O.bf16_bits_to_f32(v), m, B)
+    y2 = dense @ B
+    y3 = torch.matmul(torch.from_numpy(dense), torch.from_numpy(B)).numpy()
+    assert np.allclose(y1, y2, rtol=1e-12, atol=1e-12)
+    assert np.allclose(y2, y3, rtol=1e-12, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------- forward
+def _small_inputs(T=16, D=12, F=32, seed=0, sparsity=0.6):
+    return synth.make_inputs(T, D, F, sparsity, seed, with_dy=True)
+
+
+def test_generator_half_sparse_at_zero_bias():
+    # Sec. 1: centred normal pre-activations give about 50 % zeros
+    inp = synth.make_inputs(512, 256, 1024, 0.5, 42)
+    assert np.allclose(inp["b1"], 0.0, atol=1e-7)
+    f = O.ffn_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"])
+    frac = np.mean(f["Hq"] == 0)
+    assert abs(frac - 0.5) < 0.01
+
+
+@pytest.mark.parametrize("target", [0.85, 0.90, 0.95, 0.98, "per_feature"])
+def test_generator_hits_target_sparsity(target):
+    inp = synth.make_inputs(512, 256, 1024, target, 43)
+    f = O.ffn_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"])
+    frac = np.mean(f["Hq"] == 0)
+    want = 1 - (0.02 + 0.15) / 2 if target == "per_feature" else target
+    assert abs(frac - want) < 0.012
+
+
+def test_ffn24_equals_dense_ffn_when_nothing_dropped():
+    inp = _small_inputs(T=24, D=16, F=64, seed=2, sparsity=0.3)
+    b1 = inp["b1"].copy()
+    b1.reshape(-1, 4)[:, [1, 3]] = -1e9   # two of every four features are always off
+    a = O.ffn24_fwd(inp["X"], inp["W1"], b1, inp["W2"])
+    d = O.ffn_fwd(inp["X"], inp["W1"], b1, inp["W2"])
+    assert np.array_equal(a["H24"], d["Hq"])
+    assert np.array_equal(a["Y"], d["Y"])
+    assert np.count_nonzero(d["Hq"]) > 100
+
+
+def test_ffn_fwd_matches_torch_float64_definition():
+    inp = _small_inputs()
+    f = O.ffn_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"], st=O.Exact)
+    X, W1, b1, W2 = (torch.from_numpy(inp[k].astype(np.float64)) for k in ("X", "W1", "b1", "W2"))
+    Y = torch.clamp(X @ W1 + b1, min=0) ** 2 @ W2
+    assert np.allclose(f["Y"], Y.numpy(), rtol=1e-12, atol=1e-12)
+
+
+def test_ffn24_fwd_structure():
+    inp = _small_inputs(T=32, D=24, F=64, sparsity=0.5)
+    f = O.ffn24_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"])
+    # the pick is the standalone sparsify of the rounded activation
+    v, m = O.sparsify24(O.f32_to_bf16_bits(f["Hq"]))
+    assert np.array_equal(v, f["Hc_words"]) and np.array_equal(m, f["meta"])
+    # Y from (values, metadata) == Y from the dense pruned matrix
+    y = O.gather_matmul24(O.bf16_bits_to_f32(f["Hc_words"]), f["meta"], f["W2q"])
+    assert np.allclose(y, f["Y"], rtol=1e-12, atol=1e-12)
+    # bf16 storage: H differs from the float64 definition by at most one bf16 rounding (2^-8 relative) plus fp32 noise
+    h_exact = np.maximum(f["Z"], 0) ** 2
+    assert np.all(np.abs(f["Hq"] - h_exact) <= h_exact * (2.0 ** -8 + 1e-6) + 1e-30)
+    # something was actually dropped in this configuration
+    assert np.count_nonzero(f["Hq"]) > np.count_nonzero(f["H24"])
+
+
+def test_forward_is_per_token():
+    inp = _small_inputs(T=32)
+    perm = np.random.default_rng(9).permutation(32)
+    a = O.ffn24_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"])
+    b = O.ffn24_fwd(inp["X"][perm], inp["W1"], inp["b1"], inp["W2"])
+    assert np.array_equal(a["Y"][perm], b["Y"])
+    assert np.array_equal(a["meta"][perm], b["meta"])
+
+
+# ----------------------------------------------------------------------------- backward
+def _torch_masked_ffn_grads(inp, mask_h, mask_w=None):
+    """Autograd (torch, float64) of Y = ((max(0, X W1 + b1)^2) * M) W2 with M constant -- the textbook
+    gradient the oracle's backward must reproduce when storage rounding is off."""
+    X, W1, b1, W2, dY = (torch.from_numpy(inp[k].astype(np.float64)) for k in ("X", "W1", "b1", "W2", "dY"))
+    X.requires_grad_(True); W1.requires_grad_(True); W2.requires_grad_(True)
+    M = torch.from_numpy(mask_h.astype(np.float64))
+    Y = ((torch.clamp(X @ W1 + b1, min=0) ** 2) * M) @ W2
+    Y.backward(dY)
+    return X.grad.numpy(), W1.grad.numpy(), W2.grad.numpy()
+
+
+def test_dense_backward_matches_torch_autograd():
+    inp = _small_inputs()
+    f = O.ffn_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"], st=O.Exact)
+    g = O.ffn_bwd(f, inp["dY"], st=O.Exact)
+    dX, dW1, dW2 = _torch_masked_ffn_grads(inp, np.ones_like(f["Hq"]))
+    assert np.allclose(g["dX"], dX, rtol=1e-10, atol=1e-12)
+    assert np.allclose(g["dW1"], dW1, rtol=1e-10, atol=1e-12)
+    assert np.allclose(g["dW2"], dW2, rtol=1e-10, atol=1e-12)
+
+
+def test_ffn24_backward_tokenwise_mode_is_exact_gradient_of_masked_forward():
+    inp = _small_inputs(sparsity=0.4)
+    f = O.ffn24_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"], st=O.Exact)
+    g = O.ffn24_bwd(f, inp["dY"], st=O.Exact, wgrad_mask="tokenwise")
+    dX, dW1, dW2 = _torch_masked_ffn_grads(inp, f["Mtok"])
+    assert np.allclose(g["dX"], dX, rtol=1e-10, atol=1e-12)
+    assert np.allclose(g["dW1"], dW1, rtol=1e-10, atol=1e-12)
+    assert np.allclose(g["dW2"], dW2, rtol=1e-10, atol=1e-12)
+    assert not np.allclose(dW2, _torch_masked_ffn_grads(inp, np.ones_like(f["Mtok"]))[2])  # the mask matters here
+
+
+def test_ffn24_backward_finite_differences():
+    inp = _small_inputs(T=8, D=6, F=16, seed=4, sparsity=0.4)
+    f = O.ffn24_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"], st=O.Exact)
+    g = O.ffn24_bwd(f, inp["dY"], st=O.Exact, wgrad_mask="tokenwise")
+    M = f["Mtok"]
+
+    def loss(X, W1, W2):
+        H = np.maximum(X @ W1 + inp["b1"].astype(np.float64), 0) ** 2 * M
+        return float(np.sum((H @ W2) * inp["dY"].astype(np.float64)))
+
+    X0, W10, W20 = (inp[k].astype(np.float64) for k in ("X", "W1", "W2"))
+    eps = 1e-6
+    rng = np.random.default_rng(0)
+    for name, grad, base in (("X", g["dX"], X0), ("W1", g["dW1"], W10), ("W2", g["dW2"], W20)):
+        for _ in range(12):
+            idx = tuple(rng.integers(0, s) for s in base.shape)
+            p = base.copy(); p[idx] += eps
+            m = base.copy(); m[idx] -= eps
+            args_p = {"X": X0, "W1": W10, "W2": W20}; args_p[name] = p
+            args_m = {"X": X0, "W1": W10, "W2": W20}; args_m[name] = m
+            fd = (loss(**args_p) - loss(**args_m)) / (2 * eps)
+            assert abs(fd - grad[idx]) <= 1e-5 * max(1.0, abs(fd)), (name, idx, fd, grad[idx])
+
+
+def test_featurewise_mask_sits_on_top_of_tokenwise():
+    inp = _small_inputs(T=64, D=16, F=64, sparsity=0.4)
+    f = O.ffn24_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"])
+    g = O.ffn24_bwd(f, inp["dY"])
+    M_T, Mtok, H24 = g["M_T"], f["Mtok"], f["H24"]
+    # nothing that the forward dropped reappears (Sec. 2, last paragraph)
+    assert np.all(~(M_T & (H24 != 0)) | Mtok)
+    # 2:4 along tokens for every feature
+    Ht = np.where(M_T, H24, 0).T.reshape(64, 16, 4)
+    assert np.all((Ht != 0).sum(-1) <= 2)
+    # meta_t is the standalone sparsify of the transposed pruned activation
+    v, m = O.sparsify24(O.f32_to_bf16_bits(np.ascontiguousarray(H24.T)))
+    assert np.array_equal(v, g["Hc_t_words"]) and np.array_equal(m, g["meta_t"])
+    # the feature-wise prune really drops something here, and the weight gradients see it
+    assert np.count_nonzero(np.where(M_T, H24, 0)) < np.count_nonzero(H24)
+    e = O.ffn24_bwd(f, inp["dY"], wgrad_mask="tokenwise")
+    assert not np.array_equal(e["dW2"], g["dW2"])
+    assert np.array_equal(e["dX"], g["dX"])
+    # dW2, dW1 are the dense products with the doubly-masked operands, and equal the products from the compressed forms
+    dYq = O.round_bf16(inp["dY"]).astype(np.float64)
+    assert np.allclose(g["dW2"], O.gather_matmul24(O.bf16_bits_to_f32(g["Hc_t_words"]), g["meta_t"], dYq), rtol=1e-12, atol=1e-12)
+    assert np.allclose(g["dW1"].T, O.gather_matmul24(g["dZc_t"], g["meta_t"], f["Xq"]), rtol=1e-12, atol=1e-12)
+    assert np.allclose(g["dX"], O.gather_matmul24(g["dZc"], f["meta"], f["W1q"].T), rtol=1e-12, atol=1e-12)
+
+
+def test_featurewise_equals_tokenwise_when_columns_already_24():
+    inp = _small_inputs(T=32, D=16, F=32, sparsity=0.3)
+    X = inp["X"].copy()
+    X.reshape(8, 4, 16)[:, [0, 2]] = 0.0        # tokens 0 and 2 of every 4 are zero vectors ...
+    b1 = -np.abs(inp["b1"]) - 0.01              # ... and a negative bias keeps their activations at zero
+    f = O.ffn24_fwd(X, inp["W1"], b1, inp["W2"])
+    assert np.count_nonzero(f["H24"]) > 20
+    a = O.ffn24_bwd(f, inp["dY"])
+    b = O.ffn24_bwd(f, inp["dY"], wgrad_mask="tokenwise")
+    assert np.array_equal(a["dW1"], b["dW1"]) and np.array_equal(a["dW2"], b["dW2"])
+
+
+def test_backward_permutation_properties():
+    inp = _small_inputs(T=32, D=12, F=32, sparsity=0.4)
+    blocks = np.random.default_rng(2).permutation(8)
+    perm = (blocks[:, None] * 4 + np.arange(4)[None, :]).reshape(-1)   # permutes whole groups of 4 tokens
+    f0 = O.ffn24_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"])
+    g0 = O.ffn24_bwd(f0, inp["dY"])
+    f1 = O.ffn24_fwd(inp["X"][perm], inp["W1"], inp["b1"], inp["W2"])
+    g1 = O.ffn24_bwd(f1, inp["dY"][perm])
+    assert np.array_equal(g0["dX"][perm], g1["dX"])
+    assert np.allclose(g0["dW1"], g1["dW1"], rtol=1e-12, atol=1e-12)
+    assert np.allclose(g0["dW2"], g1["dW2"], rtol=1e-12, atol=1e-12)
+
+
+def test_backward_rounding_points():
+    inp = _small_inputs(T=16, D=16, F=32, sparsity=0.4)
+    f = O.ffn24_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"])
+    g = O.ffn24_bwd(f, inp["dY"])
+    # dZ is stored in bf16 and is zero off the token-wise mask
+    assert np.array_equal(O.round_bf16(g["dZq"]), g["dZq"])
+    assert np.all(g["dZq"][~f["Mtok"]] == 0)
+    # derivative of max(0,z)^2 is 2 max(0,z): check against the unrounded definition within bf16 precision
+    dH = O.round_bf16(inp["dY"]).astype(np.float64) @ f["W2q"].T
+    want = dH * 2 * np.maximum(f["Z"], 0) * f["Mtok"]
+    assert np.allclose(g["dZq"], want, rtol=2.0 ** -6, atol=1e-6)
+
+
+# ----------------------------------------------------------------------------- fp8 forward
+def test_fp8_forward_reduces_to_bf16_forward_on_exact_inputs():
+    rng = np.random.default_rng(8)
+    X = rng.integers(-1, 2, (16, 4)).astype(np.float32)
+    W1 = rng.integers(-1, 2, (4, 32)).astype(np.float32)
+    W2 = rng.integers(-2, 3, (32, 8)).astype(np.float32)
+    b1 = np.zeros(32, np.float32)
+    a = O.ffn24_fwd_fp8(X, W1, b1, W2, 1.0, 1.0, 1.0, 1.0)
+    b = O.ffn24_fwd(X, W1, b1, W2)
+    assert np.array_equal(a["meta"], b["meta"])
+    assert np.array_equal(a["Y"], b["Y"])
+    # scales are undone: doubling a scale and halving the tensor's stored range leaves Y unchanged here
+    c = O.ffn24_fwd_fp8(X, W1, b1, W2, 0.5, 2.0, 0.25, 4.0)
+    assert np.array_equal(c["Y"], b["Y"])
+
+
+def test_max_rel_err_definition():
+    assert O.max_rel_err([1.0, 2.0, 4.0], [1.0, 2.0, 4.0]) == 0.0
+    assert abs(O.max_rel_err([1.0, 2.5, 4.0], [1.0, 2.0, 4.0]) - 0.125) < 1e-15
