@@ -1,0 +1,132 @@
+/* ffn24 -- Squared-ReLU feed-forward block with 2:4 activation sparsity, for AMD MI355X (gfx950).
+ *
+ * C ABI of libffn24.so.  The method is that of "Accelerating Transformer Inference and Training with 2:4
+ * Activation Sparsity" (Haziza et al.): the hidden activation H = max(0, X W1)^2 of an FFN is mostly zero, so of
+ * every 4 consecutive hidden features of a token only the 2 of largest magnitude are kept, and the second GEMM
+ * (and, in training, three of the four backward GEMMs) run on sparse matrix cores.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller, row-major and contiguous, 16-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue work on that
+ *     stream; they never synchronise, and they allocate nothing (ffn24_ctx_create is the only allocating call).
+ *   - Return value: FFN24_OK (0) or a negative FFN24_ERR_* code; ffn24_strerror() names it.  Bad arguments are
+ *     rejected before anything is launched; nothing aborts or throws across this boundary.
+ *   - Element type: bf16 (FFN24_BF16) with fp32 accumulation.  FFN24_FP8_E4M3 is reserved and currently
+ *     returns FFN24_ERR_DTYPE.
+ *   - Outputs are overwritten, never accumulated into.
+ *
+ * Compressed 2:4 form used everywhere (the paper leaves the encoding open; this one equals the index operand of
+ * the gfx950 sparse matrix instruction, so it is consumed without any shuffling):
+ *   values [rows][cols/2]  the two kept entries of each group of 4, in position order;
+ *   meta   [rows][cols/8]  one nibble per group, i0 | (i1 << 2) with i0 < i1 the kept positions; the even
+ *                          group of a pair sits in the low nibble of the byte.
+ * Pick rule: order the 4 entries by (magnitude descending, position ascending) and keep the first two; the
+ * magnitude is the bf16 word with its sign bit cleared, compared as an integer.  Zeros compete like any value,
+ * so an all-zero group keeps positions {0, 1}.
+ */
+#ifndef FFN24_H
+#define FFN24_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(__GNUC__)
+#define FFN24_API __attribute__((visibility("default")))
+#else
+#define FFN24_API
+#endif
+
+#define FFN24_OK 0
+#define FFN24_ERR_NULL (-1)   /* a required pointer is NULL */
+#define FFN24_ERR_SHAPE (-2)  /* a size violates the divisibility rules stated at the call */
+#define FFN24_ERR_ALIGN (-3)  /* a pointer is not 16-byte aligned */
+#define FFN24_ERR_DTYPE (-4)  /* element type not supported */
+#define FFN24_ERR_STATE (-5)  /* call order: backward without the matching forward, missing context flag */
+#define FFN24_ERR_HIP (-6)    /* the HIP runtime reported an error (allocation, launch) */
+
+typedef enum { FFN24_BF16 = 0, FFN24_FP8_E4M3 = 1 } ffn24_dtype;
+
+/* context flags */
+#define FFN24_TRAINING 1     /* allocate what ffn24_bwd needs (dZ, transposed operands) */
+#define FFN24_DENSE 2        /* allocate what the dense baseline ffn_fwd / ffn_bwd needs (H, dZ as [T][F]) */
+#define FFN24_DEBUG_DUMP_H 4 /* ffn24_fwd also stores the rounded activation before pruning, [T][F] */
+
+typedef struct ffn24_ctx ffn24_ctx; /* opaque; owns only its device workspace */
+
+/* Create a context for token count T, model dimension D, hidden dimension F.
+ * Requires T, D, F to be multiples of 256 (the GEMM tile).  Allocates the device workspace with hipMalloc on the
+ * current device: about 1.13 T F bytes, plus 3.13 T F with FFN24_TRAINING, plus 4 T F with FFN24_DENSE, plus
+ * 2 T F with FFN24_DEBUG_DUMP_H.  *out is untouched on error. */
+FFN24_API int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dtype dtype, int flags);
+
+/* Free the workspace.  The caller must have synchronised every stream that used the context.  NULL is allowed. */
+FFN24_API int ffn24_ctx_destroy(ffn24_ctx* ctx);
+
+/* Standalone 2:4 compression along the columns (paper Sec. 2, first paragraph: keep the 2 largest magnitudes of
+ * each block of 4).   H [rows][cols] -> values [rows][cols/2], meta [rows][cols/8].
+ * cols must be a multiple of 8; rows >= 0 (rows == 0 is a no-op).  Signed inputs are allowed. */
+FFN24_API int sparsify24(const void* H, int64_t rows, int64_t cols, ffn24_dtype dtype, void* values, uint8_t* meta, void* stream);
+
+/* Feature-wise 2:4 on top of the token-wise one (paper Sec. 2, last paragraph, and Fig. 2c): the operand of a
+ * GEMM that reduces over tokens must be 2:4 along tokens.  From the token-wise compressed activation
+ * Hc [T][F/2] + meta [T][F/8] build, for each feature and each 4 consecutive tokens, the top-2 of the already
+ * pruned activation:  Hc_t [F][T/2], meta_t [F][T/8].  If dZc (same shape and metadata as Hc) is given, dZc_t
+ * [F][T/2] receives dZ at the positions picked for H; dZc and dZc_t may both be NULL.
+ * T must be a multiple of 128, F a multiple of 64. */
+FFN24_API int sparsify24_featurewise(const void* Hc, const uint8_t* meta, const void* dZc, int64_t T, int64_t F,
+                           void* Hc_t, uint8_t* meta_t, void* dZc_t, void* stream);
+
+/* C [M][N] = A24 . B on the sparse matrix cores (paper Sec. 1: a 2:4 operand lets the hardware skip half the
+ * multiplications; Fig. 2b).  A24 is given compressed along K: values [M][K/2], meta [M][K/8].
+ * b_layout 0: B is [K][N];  b_layout 1: B is [N][K].  M, N multiples of 256, K a multiple of 64. */
+FFN24_API int spmm24(const void* values, const uint8_t* meta, const void* B, int b_layout, int64_t M, int64_t N, int64_t K,
+           void* C, void* stream);
+
+/* Forward of the 2:4 FFN (paper Sec. 2):  Z = X W1 + b1;  H = bf16(max(0, Z)^2);  H24 = keep-2-of-4 of H along
+ * the hidden features of each token;  Y = H24 W2.
+ *   X [T][D], W1 [D][F], b1 [F] fp32 or NULL (the paper's FFN has no bias; b1 only dials the sparsity of synthetic
+ *   inputs), W2 [F][D], Y [T][D].
+ * Two kernels: dense-MFMA up-projection with the activation and the pruning fused into its epilogue (H is never
+ * written densely), then the sparse-MFMA down-projection.  The context keeps (Hc, meta) and the X, W1, W2
+ * pointers for ffn24_bwd; the caller keeps X, W1, W2 alive and unchanged until then. */
+FFN24_API int ffn24_fwd(ffn24_ctx* ctx, const void* X, const void* W1, const float* b1, const void* W2, void* Y, void* stream);
+
+/* Backward of the last ffn24_fwd on this context, masks held fixed (paper Fig. 4 and Sec. 2, backward paragraphs):
+ *   dZ  = (dY W2^T) * 2 max(0, Z) on the kept positions        dense GEMM, derivative taken as 2 sqrt(H)
+ *   dX  = dZ24 W1^T                                            sparse GEMM (token-wise mask)
+ *   dW2 = (H24 * M_T)^T dY,   dW1 = X^T (dZ24 * M_T)           sparse GEMMs; M_T = feature-wise mask on top
+ *   dY [T][D] -> dX [T][D], dW1 [D][F], dW2 [F][D].
+ * Needs FFN24_TRAINING.  Returns FFN24_ERR_STATE if no ffn24_fwd preceded it. */
+FFN24_API int ffn24_bwd(ffn24_ctx* ctx, const void* dY, void* dX, void* dW1, void* dW2, void* stream);
+
+/* Dense Squared-ReLU FFN on the same GEMM core (paper Sec. 1, "Squared ReLU"): the speed-up baseline.
+ * Y = bf16(max(0, X W1 + b1)^2) W2.  Needs FFN24_DENSE. */
+FFN24_API int ffn_fwd(ffn24_ctx* ctx, const void* X, const void* W1, const float* b1, const void* W2, void* Y, void* stream);
+
+/* Backward of the last ffn_fwd: dZ = (dY W2^T) * 2 sqrt(H); dX = dZ W1^T; dW2 = H^T dY; dW1 = X^T dZ. */
+FFN24_API int ffn_bwd(ffn24_ctx* ctx, const void* dY, void* dX, void* dW1, void* dW2, void* stream);
+
+/* Device pointers into the workspace, for parity checks.  `which`:
+ *   0 Hc [T][F/2]   1 meta [T][F/8]   2 dZc [T][F/2]   3 Hc_t [F][T/2]   4 meta_t [F][T/8]   5 dZc_t [F][T/2]
+ *   6 pre-prune H dump [T][F] (FFN24_DEBUG_DUMP_H)   7 dense H [T][F]   8 dense dZ [T][F]
+ * *ptr is NULL if the context was created without the flag that owns the buffer. */
+FFN24_API int ffn24_get_saved(ffn24_ctx* ctx, int which, const void** ptr, int64_t* nbytes);
+
+/* Per-kernel timing with HIP events recorded on the stream each kernel is launched on.
+ * ffn24_set_profiling(ctx, 1) makes every later call bracket each of its kernels with an event pair;
+ * ffn24_kernel_ms(ctx, k, &ms) waits for kernel k's events of the most recent call and returns its duration.
+ * Kernel ids: 0 up-projection+prune, 1 sparse down-projection, 2 dH+derivative, 3 sparse dX, 4 feature-wise
+ * re-compression, 5 sparse dW2, 6 sparse dW1, 7..12 the six dense-baseline GEMMs in the same order
+ * (up, down, dH, dX, dW2, dW1).  Returns FFN24_ERR_STATE if that kernel has not run with profiling on. */
+FFN24_API int ffn24_set_profiling(ffn24_ctx* ctx, int on);
+FFN24_API int ffn24_kernel_ms(ffn24_ctx* ctx, int kernel, float* ms);
+
+FFN24_API const char* ffn24_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FFN24_H */

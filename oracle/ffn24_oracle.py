@@ -29,6 +29,7 @@ Readings where the paper is silent (each is listed in the design notes of the re
   * metadata: one nibble i0 | (i1 << 2) per group, two groups per byte, even group in the low nibble;
   * a per-feature bias b1 is added before the ReLU (a synthetic sparsity dial; b1 = None is the paper's FFN);
   * one feature-wise mask, ranked on |H24|, is applied to both H24^T and dZ^T;
+  * the backward takes the derivative 2 max(0, z) as 2 sqrt(h) of the stored (rounded) activation;
   * dX uses only the token-wise mask.
 
 Parity pins live in tests/test_oracle_*.py.  Absolute output values for the benchmark shapes have
@@ -341,6 +342,23 @@ def featurewise24(H24, st=Bf16):
     return Hc_t, meta_t, M_T
 
 
+def _drelu2(dH, Hq, st):
+    """dH * d(max(0,z)^2)/dz.  The derivative 2 max(0, z) is written through the stored activation as
+    2 sqrt(h) (on h > 0 the two are the same number; the paper does not say what is kept for backward).
+    With a storage type the product runs in float32, as the kernels do."""
+    if st is Exact:
+        return dH * 2.0 * np.sqrt(np.asarray(Hq, dtype=np.float64))
+    g = np.float32(2) * np.sqrt(np.asarray(Hq, dtype=np.float32))
+    return dH.astype(np.float32) * g
+
+
+def fwd_from_saved(Hc_words, meta, X, W1, W2, st=Bf16):
+    """Rebuild what ffn24_bwd needs from the compressed activation a forward pass saved."""
+    H24 = st.from_words(decompress24(np.asarray(Hc_words, dtype=np.uint16), meta))
+    return {"H24": H24, "meta": np.asarray(meta, dtype=np.uint8), "Mtok": mask_from_meta(meta),
+            "Xq": st.q(X).astype(np.float64), "W1q": st.q(W1).astype(np.float64), "W2q": st.q(W2).astype(np.float64)}
+
+
 def ffn24_bwd(fwd: dict, dY, st=Bf16, wgrad_mask="featurewise"):
     """Backward of ffn24_fwd with the masks held fixed (Fig. 4 caption; Sec. 2, backward paragraphs).
 
@@ -349,16 +367,13 @@ def ffn24_bwd(fwd: dict, dY, st=Bf16, wgrad_mask="featurewise"):
       dX  = dZ W1^T                                  (sparse along features: token-wise mask only)
       dW2 = (H24 * M_T)^T dY,  dW1 = X^T (dZ * M_T)   (sparse along tokens: feature-wise mask on top)
 
-    wgrad_mask="tokenwise" replaces M_T by M_tok in the last line: the exact gradient of the pruned
-    forward, used only to pin the calculus.
+    Needs of `fwd` only H24, meta, Mtok, Xq, W1q, W2q.  wgrad_mask="tokenwise" replaces M_T by M_tok in the
+    last line: the exact gradient of the pruned forward, used only to pin the calculus.
     """
     dYq = st.q(dY).astype(np.float64)
     dH = dYq @ fwd["W2q"].T
     Mtok = fwd["Mtok"]
-    if st is Exact:
-        dZ = dH * 2.0 * fwd["Rq"]
-    else:
-        dZ = dH.astype(np.float32) * (np.float32(2) * fwd["Rq"].astype(np.float32))
+    dZ = _drelu2(dH, fwd["H24"], st)
     dZ = np.where(Mtok, dZ, dZ.dtype.type(0))
     dZq = st.q(dZ)
     dX = dZq.astype(np.float64) @ fwd["W1q"].T
@@ -376,16 +391,13 @@ def ffn24_bwd(fwd: dict, dY, st=Bf16, wgrad_mask="featurewise"):
 
 
 def ffn_bwd(fwd: dict, dY, st=Bf16):
-    """Textbook backward of the dense FFN: dZ = (dY W2^T) * 2 max(0, Z); dX = dZ W1^T; dW2 = H^T dY; dW1 = X^T dZ."""
+    """Textbook backward of the dense FFN: dZ = (dY W2^T) * 2 max(0, Z); dX = dZ W1^T; dW2 = H^T dY; dW1 = X^T dZ.
+    Needs of `fwd` only Hq, Xq, W1q, W2q."""
     dYq = st.q(dY).astype(np.float64)
     dH = dYq @ fwd["W2q"].T
-    if st is Exact:
-        dZ = dH * 2.0 * fwd["Rq"]
-    else:
-        dZ = dH.astype(np.float32) * (np.float32(2) * fwd["Rq"].astype(np.float32))
-    dZq = st.q(dZ)
+    dZq = st.q(_drelu2(dH, fwd["Hq"], st))
     dX = dZq.astype(np.float64) @ fwd["W1q"].T
-    dW2 = fwd["Hq"].astype(np.float64).T @ dYq
+    dW2 = np.asarray(fwd["Hq"], dtype=np.float64).T @ dYq
     dW1 = fwd["Xq"].T @ dZq.astype(np.float64)
     return {"dZq": dZq, "dX": dX, "dW1": dW1, "dW2": dW2}
 

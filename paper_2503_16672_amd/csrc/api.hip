@@ -1,0 +1,225 @@
+// C ABI of libffn24.so: argument checks, the context's workspace, and the kernel sequences.
+#include <hip/hip_runtime.h>
+#include <new>
+#include "../../include/ffn24.h"
+#include "launch.hpp"
+
+using namespace ffn24;
+
+namespace {
+constexpr int NUM_KERNELS = 13;
+enum { K_UP = 0, K_DOWN, K_DH, K_DX, K_FW, K_DW2, K_DW1, KD_UP, KD_DOWN, KD_DH, KD_DX, KD_DW2, KD_DW1 };
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+}  // namespace
+
+struct ffn24_ctx {
+  int64_t T, D, F;
+  int flags;
+  int device;
+  // workspace (device)
+  void* Hc; uint8_t* meta; void* dZc; void* Hc_t; uint8_t* meta_t; void* dZc_t; void* Hdbg; void* Hd; void* dZd;
+  // forward state
+  const void *X, *W1, *W2;
+  int have_fwd24, have_fwd_dense;
+  // profiling
+  int profiling;
+  hipEvent_t ev[NUM_KERNELS][2];
+  int ev_valid[NUM_KERNELS];
+};
+
+namespace {
+
+struct Timed {
+  ffn24_ctx* c; int k; hipStream_t s;
+  Timed(ffn24_ctx* c_, int k_, hipStream_t s_) : c(c_), k(k_), s(s_) {
+    if (c->profiling) (void)hipEventRecord(c->ev[k][0], s);
+  }
+  int done(int rc) {
+    if (c->profiling) { (void)hipEventRecord(c->ev[k][1], s); c->ev_valid[k] = (rc == 0); }
+    return rc;
+  }
+};
+
+int free_all(ffn24_ctx* c) {
+  int bad = 0;
+  void* bufs[] = {c->Hc, c->meta, c->dZc, c->Hc_t, c->meta_t, c->dZc_t, c->Hdbg, c->Hd, c->dZd};
+  for (void* b : bufs) if (b && hipFree(b) != hipSuccess) bad = 1;
+  for (int k = 0; k < NUM_KERNELS; k++) for (int j = 0; j < 2; j++) if (c->ev[k][j]) (void)hipEventDestroy(c->ev[k][j]);
+  return bad;
+}
+
+int check_ptrs(std::initializer_list<const void*> ps) {
+  for (const void* p : ps) if (!p) return FFN24_ERR_NULL;
+  for (const void* p : ps) if (misaligned(p)) return FFN24_ERR_ALIGN;
+  return FFN24_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ffn24_strerror(int code) {
+  switch (code) {
+    case FFN24_OK: return "ok";
+    case FFN24_ERR_NULL: return "a required pointer is NULL";
+    case FFN24_ERR_SHAPE: return "a size violates the divisibility rules of the call";
+    case FFN24_ERR_ALIGN: return "a pointer is not 16-byte aligned";
+    case FFN24_ERR_DTYPE: return "element type not supported";
+    case FFN24_ERR_STATE: return "wrong call order or missing context flag";
+    case FFN24_ERR_HIP: return "HIP runtime error";
+    default: return "unknown ffn24 error code";
+  }
+}
+
+int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dtype dtype, int flags) {
+  if (!out) return FFN24_ERR_NULL;
+  if (dtype != FFN24_BF16) return FFN24_ERR_DTYPE;
+  if (T <= 0 || D <= 0 || F <= 0 || T % 256 || D % 256 || F % 256) return FFN24_ERR_SHAPE;
+  if (T > (1 << 24) || D > (1 << 24) || F > (1 << 24)) return FFN24_ERR_SHAPE;
+  ffn24_ctx* c = new (std::nothrow) ffn24_ctx();
+  if (!c) return FFN24_ERR_HIP;
+  c->T = T; c->D = D; c->F = F; c->flags = flags;
+  if (hipGetDevice(&c->device) != hipSuccess) { delete c; return FFN24_ERR_HIP; }
+  size_t tf = (size_t)T * (size_t)F;
+  bool ok = hipMalloc(&c->Hc, tf) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->meta), tf / 8) == hipSuccess;
+  if (ok && (flags & FFN24_TRAINING))
+    ok = hipMalloc(&c->dZc, tf) == hipSuccess && hipMalloc(&c->Hc_t, tf) == hipSuccess &&
+         hipMalloc(reinterpret_cast<void**>(&c->meta_t), tf / 8) == hipSuccess && hipMalloc(&c->dZc_t, tf) == hipSuccess;
+  if (ok && (flags & FFN24_DENSE)) ok = hipMalloc(&c->Hd, 2 * tf) == hipSuccess && hipMalloc(&c->dZd, 2 * tf) == hipSuccess;
+  if (ok && (flags & FFN24_DEBUG_DUMP_H)) ok = hipMalloc(&c->Hdbg, 2 * tf) == hipSuccess;
+  for (int k = 0; ok && k < NUM_KERNELS; k++)
+    for (int j = 0; ok && j < 2; j++) ok = hipEventCreate(&c->ev[k][j]) == hipSuccess;
+  if (!ok) { (void)hipGetLastError(); free_all(c); delete c; return FFN24_ERR_HIP; }
+  *out = c;
+  return FFN24_OK;
+}
+
+int ffn24_ctx_destroy(ffn24_ctx* c) {
+  if (!c) return FFN24_OK;
+  int bad = free_all(c);
+  delete c;
+  return bad ? FFN24_ERR_HIP : FFN24_OK;
+}
+
+int ffn24_set_profiling(ffn24_ctx* c, int on) {
+  if (!c) return FFN24_ERR_NULL;
+  c->profiling = on != 0;
+  return FFN24_OK;
+}
+
+int ffn24_kernel_ms(ffn24_ctx* c, int k, float* ms) {
+  if (!c || !ms) return FFN24_ERR_NULL;
+  if (k < 0 || k >= NUM_KERNELS) return FFN24_ERR_SHAPE;
+  if (!c->ev_valid[k]) return FFN24_ERR_STATE;
+  if (hipEventSynchronize(c->ev[k][1]) != hipSuccess) return FFN24_ERR_HIP;
+  if (hipEventElapsedTime(ms, c->ev[k][0], c->ev[k][1]) != hipSuccess) return FFN24_ERR_HIP;
+  return FFN24_OK;
+}
+
+int ffn24_get_saved(ffn24_ctx* c, int which, const void** ptr, int64_t* nbytes) {
+  if (!c || !ptr || !nbytes) return FFN24_ERR_NULL;
+  int64_t tf = c->T * c->F;
+  switch (which) {
+    case 0: *ptr = c->Hc; *nbytes = tf; break;
+    case 1: *ptr = c->meta; *nbytes = tf / 8; break;
+    case 2: *ptr = c->dZc; *nbytes = tf; break;
+    case 3: *ptr = c->Hc_t; *nbytes = tf; break;
+    case 4: *ptr = c->meta_t; *nbytes = tf / 8; break;
+    case 5: *ptr = c->dZc_t; *nbytes = tf; break;
+    case 6: *ptr = c->Hdbg; *nbytes = 2 * tf; break;
+    case 7: *ptr = c->Hd; *nbytes = 2 * tf; break;
+    case 8: *ptr = c->dZd; *nbytes = 2 * tf; break;
+    default: return FFN24_ERR_SHAPE;
+  }
+  return FFN24_OK;
+}
+
+int sparsify24(const void* H, int64_t rows, int64_t cols, ffn24_dtype dtype, void* values, uint8_t* meta, void* stream) {
+  if (dtype != FFN24_BF16) return FFN24_ERR_DTYPE;
+  if (rows < 0 || cols < 0 || cols % 8) return FFN24_ERR_SHAPE;
+  if (rows == 0 || cols == 0) return FFN24_OK;
+  if (rows > (INT64_MAX / 2) / cols) return FFN24_ERR_SHAPE;
+  if (!H || !values || !meta) return FFN24_ERR_NULL;
+  if (misaligned(H) || misaligned(values)) return FFN24_ERR_ALIGN;
+  return launch_sparsify24(H, rows, cols, values, meta, static_cast<hipStream_t>(stream)) ? FFN24_ERR_HIP : FFN24_OK;
+}
+
+int sparsify24_featurewise(const void* Hc, const uint8_t* meta, const void* dZc, int64_t T, int64_t F,
+                           void* Hc_t, uint8_t* meta_t, void* dZc_t, void* stream) {
+  if (T <= 0 || F <= 0 || T % 128 || F % 64 || T > (1 << 24) || F > (1 << 24)) return FFN24_ERR_SHAPE;
+  if (!Hc || !meta || !Hc_t || !meta_t) return FFN24_ERR_NULL;
+  if ((dZc == nullptr) != (dZc_t == nullptr)) return FFN24_ERR_NULL;
+  if (misaligned(Hc) || misaligned(meta) || misaligned(Hc_t) || misaligned(meta_t) || misaligned(dZc) || misaligned(dZc_t))
+    return FFN24_ERR_ALIGN;
+  return launch_featurewise24(Hc, meta, dZc, (int)T, (int)F, Hc_t, meta_t, dZc_t, static_cast<hipStream_t>(stream)) ? FFN24_ERR_HIP : FFN24_OK;
+}
+
+int spmm24(const void* values, const uint8_t* meta, const void* B, int b_layout, int64_t M, int64_t N, int64_t K,
+           void* C, void* stream) {
+  if (M <= 0 || N <= 0 || K <= 0 || M % 256 || N % 256 || K % 64 || M > (1 << 24) || N > (1 << 24) || K > (1 << 24)) return FFN24_ERR_SHAPE;
+  if (b_layout != 0 && b_layout != 1) return FFN24_ERR_SHAPE;
+  int rc = check_ptrs({values, meta, B, C});
+  if (rc) return rc;
+  return launch_sp_rowmajor(values, meta, B, b_layout, (int)M, (int)N, (int)K, C, static_cast<hipStream_t>(stream)) ? FFN24_ERR_HIP : FFN24_OK;
+}
+
+int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const void* W2, void* Y, void* stream) {
+  if (!c) return FFN24_ERR_NULL;
+  int rc = check_ptrs({X, W1, W2, Y});
+  if (rc) return rc;
+  if (b1 && misaligned(b1)) return FFN24_ERR_ALIGN;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int T = (int)c->T, D = (int)c->D, F = (int)c->F;
+  c->have_fwd24 = 0;
+  { Timed t(c, K_UP, s);   if (t.done(launch_up_prune24(W1, X, b1, T, D, F, c->Hc, c->meta, c->Hdbg, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_DOWN, s); if (t.done(launch_sp_rowmajor(c->Hc, c->meta, W2, 0, T, D, F, Y, s))) return FFN24_ERR_HIP; }
+  c->X = X; c->W1 = W1; c->W2 = W2; c->have_fwd24 = 1;
+  return FFN24_OK;
+}
+
+int ffn24_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void* stream) {
+  if (!c) return FFN24_ERR_NULL;
+  if (!(c->flags & FFN24_TRAINING) || !c->have_fwd24) return FFN24_ERR_STATE;
+  int rc = check_ptrs({dY, dX, dW1, dW2});
+  if (rc) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int T = (int)c->T, D = (int)c->D, F = (int)c->F;
+  { Timed t(c, K_DH, s);  if (t.done(launch_dh_gather(c->W2, dY, c->Hc, c->meta, T, D, F, c->dZc, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_DX, s);  if (t.done(launch_sp_rowmajor(c->dZc, c->meta, c->W1, 1, T, D, F, dX, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_FW, s);  if (t.done(launch_featurewise24(c->Hc, c->meta, c->dZc, T, F, c->Hc_t, c->meta_t, c->dZc_t, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_DW2, s); if (t.done(launch_sp_rowmajor(c->Hc_t, c->meta_t, dY, 0, F, D, T, dW2, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_DW1, s); if (t.done(launch_sp_nc_colmajor(c->dZc_t, c->meta_t, c->X, F, D, T, dW1, s))) return FFN24_ERR_HIP; }
+  return FFN24_OK;
+}
+
+int ffn_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const void* W2, void* Y, void* stream) {
+  if (!c) return FFN24_ERR_NULL;
+  if (!(c->flags & FFN24_DENSE)) return FFN24_ERR_STATE;
+  int rc = check_ptrs({X, W1, W2, Y});
+  if (rc) return rc;
+  if (b1 && misaligned(b1)) return FFN24_ERR_ALIGN;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int T = (int)c->T, D = (int)c->D, F = (int)c->F;
+  c->have_fwd_dense = 0;
+  { Timed t(c, KD_UP, s);   if (t.done(launch_up_relu2(W1, X, b1, T, D, F, c->Hd, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_DOWN, s); if (t.done(launch_kc_nc_rowmajor(c->Hd, W2, T, D, F, Y, s))) return FFN24_ERR_HIP; }
+  c->X = X; c->W1 = W1; c->W2 = W2; c->have_fwd_dense = 1;
+  return FFN24_OK;
+}
+
+int ffn_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void* stream) {
+  if (!c) return FFN24_ERR_NULL;
+  if (!(c->flags & FFN24_DENSE) || !c->have_fwd_dense) return FFN24_ERR_STATE;
+  int rc = check_ptrs({dY, dX, dW1, dW2});
+  if (rc) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int T = (int)c->T, D = (int)c->D, F = (int)c->F;
+  { Timed t(c, KD_DH, s);  if (t.done(launch_dh_drelu(c->W2, dY, c->Hd, T, D, F, c->dZd, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_DX, s);  if (t.done(launch_kc_kc_rowmajor(c->dZd, c->W1, T, D, F, dX, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_DW2, s); if (t.done(launch_mc_nc_rowmajor(c->Hd, dY, F, D, T, dW2, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_DW1, s); if (t.done(launch_mc_nc_colmajor(c->dZd, c->X, F, D, T, dW1, s))) return FFN24_ERR_HIP; }
+  return FFN24_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,186 @@
+// Epilogues of the GEMM core: what happens to a lane's 4x4x16 accumulators.
+// A lane owns rows m_lane + 16*mi + v (64 consecutive) and columns n_lane + ni (4 consecutive).
+#pragma once
+#include "gemm_core.hpp"
+
+namespace ffn24 {
+
+// C[m][n], n contiguous: 4 consecutive columns per lane and row -> one 8-byte store per row.
+struct EpiRowMajor {
+  struct Args { __bf16* C; int ldc; };
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+#pragma unroll
+    for (int mi = 0; mi < 4; mi++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        u32x2 o;
+        o[0] = pack_bf16x2(acc[mi][0][v], acc[mi][1][v]);
+        o[1] = pack_bf16x2(acc[mi][2][v], acc[mi][3][v]);
+        *reinterpret_cast<u32x2*>(e.C + (size_t)(m_lane + 16 * mi + v) * e.ldc + n_lane) = o;
+      }
+  }
+};
+
+// C stored transposed, out[n][m] with m contiguous: 64 consecutive elements per lane and column.
+struct EpiColMajor {
+  struct Args { __bf16* C; int ldc; };
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+#pragma unroll
+    for (int ni = 0; ni < 4; ni++) {
+      __bf16* row = e.C + (size_t)(n_lane + ni) * e.ldc + m_lane;
+#pragma unroll
+      for (int mi = 0; mi < 4; mi++)
+#pragma unroll
+        for (int q = 0; q < 2; q++) {
+          u32x4 o;
+#pragma unroll
+          for (int d = 0; d < 4; d++) o[d] = pack_bf16x2(acc[mi][ni][8 * q + 2 * d], acc[mi][ni][8 * q + 2 * d + 1]);
+          *reinterpret_cast<u32x4*>(row + 16 * mi + 8 * q) = o;
+        }
+    }
+  }
+};
+
+// Dense FFN up-projection epilogue (Sec. 1, Squared ReLU): rows m are features, columns n are tokens;
+// H[t][f] = bf16( max(0, acc + b1[f])^2 ), stored [T][F].
+struct EpiRelu2 {
+  struct Args { __bf16* H; const float* b1; int F; };
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+#pragma unroll
+    for (int mi = 0; mi < 4; mi++) {
+      float bias[16];
+#pragma unroll
+      for (int v = 0; v < 16; v++) bias[v] = e.b1 ? e.b1[m_lane + 16 * mi + v] : 0.f;
+#pragma unroll
+      for (int ni = 0; ni < 4; ni++) {
+        __bf16* row = e.H + (size_t)(n_lane + ni) * e.F + m_lane + 16 * mi;
+#pragma unroll
+        for (int q = 0; q < 2; q++) {
+          u32x4 o;
+#pragma unroll
+          for (int d = 0; d < 4; d++) {
+            float r0 = fmaxf(acc[mi][ni][8 * q + 2 * d] + bias[8 * q + 2 * d], 0.f);
+            float r1 = fmaxf(acc[mi][ni][8 * q + 2 * d + 1] + bias[8 * q + 2 * d + 1], 0.f);
+            o[d] = pack_bf16x2(r0 * r0, r1 * r1);
+          }
+          *reinterpret_cast<u32x4*>(row + 8 * q) = o;
+        }
+      }
+    }
+  }
+};
+
+// Fused up-projection epilogue of the 2:4 FFN (Sec. 2: activation, then sparsification, in one pass):
+// h = bf16(max(0, acc + b1)^2); of every 4 consecutive features of a token keep the 2 largest
+// (ties -> lower index); write the kept pair and its metadata nibble.  The 4 members of a group are the
+// accumulator registers 4a..4a+3 of one MFMA tile, so the pick needs no cross-lane traffic.
+//   Hc   [T][F/2]  kept values, position order        meta [T][F/8]  nibble i0 | i1<<2, even group low
+//   Hdbg [T][F]    optional: the rounded activation before pruning (parity checks)
+struct EpiPrune24 {
+  struct Args { __bf16* Hc; uint8_t* meta; __bf16* Hdbg; const float* b1; int F; };
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+#pragma unroll
+    for (int ni = 0; ni < 4; ni++) {
+      size_t t = (size_t)(n_lane + ni);
+      uint32_t vals[16];
+      uint32_t nib[2] = {0u, 0u};
+#pragma unroll
+      for (int mi = 0; mi < 4; mi++) {
+        uint32_t hpk[8];
+#pragma unroll
+        for (int d = 0; d < 8; d++) {
+          float b0 = e.b1 ? e.b1[m_lane + 16 * mi + 2 * d] : 0.f;
+          float b1v = e.b1 ? e.b1[m_lane + 16 * mi + 2 * d + 1] : 0.f;
+          float r0 = fmaxf(acc[mi][ni][2 * d] + b0, 0.f);
+          float r1 = fmaxf(acc[mi][ni][2 * d + 1] + b1v, 0.f);
+          hpk[d] = pack_bf16x2(r0 * r0, r1 * r1);
+        }
+        if (e.Hdbg) {
+          __bf16* row = e.Hdbg + t * e.F + m_lane + 16 * mi;
+          *reinterpret_cast<u32x4*>(row) = u32x4{hpk[0], hpk[1], hpk[2], hpk[3]};
+          *reinterpret_cast<u32x4*>(row + 8) = u32x4{hpk[4], hpk[5], hpk[6], hpk[7]};
+        }
+#pragma unroll
+        for (int a = 0; a < 4; a++) {
+          // h >= 0, so the storage word is its own magnitude
+          uint32_t k0 = ((hpk[2 * a] & 0xFFFFu) << 2) | 3u;
+          uint32_t k1 = ((hpk[2 * a] >> 16) << 2) | 2u;
+          uint32_t k2 = ((hpk[2 * a + 1] & 0xFFFFu) << 2) | 1u;
+          uint32_t k3 = ((hpk[2 * a + 1] >> 16) << 2);
+          uint32_t kf, ks;
+          uint32_t n4 = pick24_keys(k0, k1, k2, k3, kf, ks);
+          int gi = 4 * mi + a;
+          vals[gi] = (kf >> 2) | ((ks >> 2) << 16);
+          nib[gi >> 3] |= n4 << (4 * (gi & 7));
+        }
+      }
+      __bf16* hrow = e.Hc + t * (size_t)(e.F / 2) + m_lane / 2;
+#pragma unroll
+      for (int q = 0; q < 4; q++)
+        *reinterpret_cast<u32x4*>(hrow + 8 * q) = u32x4{vals[4 * q], vals[4 * q + 1], vals[4 * q + 2], vals[4 * q + 3]};
+      *reinterpret_cast<u32x2*>(e.meta + t * (size_t)(e.F / 8) + m_lane / 8) = u32x2{nib[0], nib[1]};
+    }
+  }
+};
+
+// Dense backward, pointwise part: rows m are features, columns n are tokens; acc = dH[t][f];
+// dZ[t][f] = bf16( acc * 2 sqrt(H[t][f]) )  (derivative of max(0,z)^2 is 2 max(0,z) = 2 sqrt(h)).
+struct EpiDRelu {
+  struct Args { const __bf16* H; __bf16* dZ; int F; };
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+#pragma unroll
+    for (int ni = 0; ni < 4; ni++)
+#pragma unroll
+      for (int mi = 0; mi < 4; mi++) {
+        size_t o = (size_t)(n_lane + ni) * e.F + m_lane + 16 * mi;
+#pragma unroll
+        for (int q = 0; q < 2; q++) {
+          u32x4 h = *reinterpret_cast<const u32x4*>(e.H + o + 8 * q);
+          u32x4 r;
+#pragma unroll
+          for (int d = 0; d < 4; d++) {
+            float g0 = 2.f * __builtin_amdgcn_sqrtf(bf16_lo_to_f32(h[d]));
+            float g1 = 2.f * __builtin_amdgcn_sqrtf(bf16_hi_to_f32(h[d]));
+            r[d] = pack_bf16x2(acc[mi][ni][8 * q + 2 * d] * g0, acc[mi][ni][8 * q + 2 * d + 1] * g1);
+          }
+          *reinterpret_cast<u32x4*>(e.dZ + o + 8 * q) = r;
+        }
+      }
+  }
+};
+
+// 2:4 backward, pointwise part (Fig. 4 caption; Sec. 2, last paragraph): acc = dH[t][f]; on the positions
+// the forward kept, dZ = dH * 2 sqrt(h); elsewhere dZ = 0 and nothing is stored.  Output is compressed with
+// the forward's metadata: dZc [T][F/2].
+struct EpiDGather {
+  struct Args { const __bf16* Hc; const uint8_t* meta; __bf16* dZc; int F; };
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+#pragma unroll
+    for (int ni = 0; ni < 4; ni++) {
+      size_t t = (size_t)(n_lane + ni);
+      const __bf16* hrow = e.Hc + t * (size_t)(e.F / 2) + m_lane / 2;
+      u32x2 mt = *reinterpret_cast<const u32x2*>(e.meta + t * (size_t)(e.F / 8) + m_lane / 8);
+      __bf16* zrow = e.dZc + t * (size_t)(e.F / 2) + m_lane / 2;
+#pragma unroll
+      for (int mi = 0; mi < 4; mi++) {
+        u32x4 h = *reinterpret_cast<const u32x4*>(hrow + 8 * mi);
+        u32x4 z;
+#pragma unroll
+        for (int a = 0; a < 4; a++) {
+          int gi = 4 * mi + a;
+          uint32_t n4 = (mt[gi >> 3] >> (4 * (gi & 7))) & 15u;
+          uint32_t i0 = n4 & 3u, i1 = n4 >> 2;
+          float x0 = acc[mi][ni][4 * a], x1 = acc[mi][ni][4 * a + 1], x2 = acc[mi][ni][4 * a + 2], x3 = acc[mi][ni][4 * a + 3];
+          float s0 = i0 == 0 ? x0 : (i0 == 1 ? x1 : x2);
+          float s1 = i1 == 3 ? x3 : (i1 == 2 ? x2 : x1);
+          float g0 = 2.f * __builtin_amdgcn_sqrtf(bf16_lo_to_f32(h[a]));
+          float g1 = 2.f * __builtin_amdgcn_sqrtf(bf16_hi_to_f32(h[a]));
+          z[a] = pack_bf16x2(s0 * g0, s1 * g1);
+        }
+        *reinterpret_cast<u32x4*>(zrow + 8 * mi) = z;
+      }
+    }
+  }
+};
+
+}  // namespace ffn24

@@ -1,0 +1,134 @@
+// Streaming (HBM-bound) kernels: the standalone 2:4 compression of an activation matrix, and the
+// feature-wise (along-token) re-compression the weight-gradient GEMMs need.
+#include "gemm_core.hpp"
+#include "launch.hpp"
+
+namespace ffn24 {
+
+// key of a bf16 storage word at position i of its group: ((magnitude << 2) | (3 - i)) << 1 | sign.
+// The sign rides in the lowest bit, below the position, so it never takes part in the ordering.
+__device__ __forceinline__ uint32_t key_of(uint32_t w, uint32_t i) { return ((((w & 0x7FFFu) << 2) | (3u - i)) << 1) | (w >> 15); }
+__device__ __forceinline__ uint32_t word_of(uint32_t key) { return (key >> 3) | ((key & 1u) << 15); }
+
+// pick on keys that carry the sign bit: strip it for the position arithmetic of pick24_keys
+__device__ __forceinline__ uint32_t pick24_words(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3, uint32_t& pair) {
+  uint32_t k0 = key_of(w0, 0), k1 = key_of(w1, 1), k2 = key_of(w2, 2), k3 = key_of(w3, 3);
+  uint32_t a = max(k0, k1), b = min(k0, k1), c = max(k2, k3), d = min(k2, k3);
+  uint32_t top = max(a, c);
+  uint32_t e = max(b, d);
+  uint32_t second = max(min(a, c), min(max(a, c), e));
+  uint32_t ct = (top >> 1) & 3u, cs = (second >> 1) & 3u;
+  bool top_first = ct > cs;
+  uint32_t kf = top_first ? top : second, ks = top_first ? second : top;
+  pair = word_of(kf) | (word_of(ks) << 16);
+  uint32_t cmax = max(ct, cs), cmin = min(ct, cs);
+  return (cmax | (cmin << 2)) ^ 15u;
+}
+
+// Standalone sparsify24 (Sec. 2 of the paper, first paragraph): each thread takes 8 consecutive elements
+// (two groups): one 16-byte load, one 8-byte store of kept values, one metadata byte.  The matrix is
+// processed as a flat array, which is valid because cols % 8 == 0.
+__global__ void __launch_bounds__(256) sparsify24_kernel(const u32x4* __restrict__ in, int64_t n_oct,
+                                                         u32x2* __restrict__ vals, uint8_t* __restrict__ meta) {
+  int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < n_oct; o += stride) {
+    u32x4 v = in[o];
+    uint32_t p0, p1;
+    uint32_t n0 = pick24_words(v[0] & 0xFFFFu, v[0] >> 16, v[1] & 0xFFFFu, v[1] >> 16, p0);
+    uint32_t n1 = pick24_words(v[2] & 0xFFFFu, v[2] >> 16, v[3] & 0xFFFFu, v[3] >> 16, p1);
+    vals[o] = u32x2{p0, p1};
+    meta[o] = (uint8_t)(n0 | (n1 << 4));
+  }
+}
+
+int launch_sparsify24(const void* H, int64_t rows, int64_t cols, void* vals, uint8_t* meta, hipStream_t s) {
+  int64_t n_oct = rows * cols / 8;
+  if (n_oct == 0) return 0;
+  int64_t blocks = (n_oct + 255) / 256;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  hipLaunchKernelGGL(sparsify24_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const u32x4*>(H), n_oct,
+                     static_cast<u32x2*>(vals), meta);
+  return (int)hipGetLastError();
+}
+
+// Feature-wise 2:4 on top of the token-wise mask (Sec. 2, last paragraph; Fig. 2c).
+// Input: token-wise compressed Hc [T][F/2] + meta [T][F/8], and optionally dZc [T][F/2] with the same metadata.
+// Output: for every feature, groups of 4 consecutive tokens of the pruned activation keep their top-2:
+//   Hc_t [F][T/2], meta_t [F][T/8], and dZc_t [F][T/2] = dZ at the positions picked for H.
+// One workgroup handles 128 tokens x 64 features: decompress into LDS, then each work item takes one feature
+// and 8 consecutive tokens (two groups) so that a feature row's outputs are written 128 bytes at a time.
+constexpr int FW_TOK = 128, FW_FEAT = 64, FW_LD = FW_FEAT + 2;
+
+__global__ void __launch_bounds__(256) featurewise24_kernel(const uint16_t* __restrict__ Hc, const uint8_t* __restrict__ meta,
+                                                            const uint16_t* __restrict__ dZc, int T, int F,
+                                                            uint16_t* __restrict__ Hc_t, uint8_t* __restrict__ meta_t,
+                                                            uint16_t* __restrict__ dZc_t) {
+  __shared__ uint16_t sH[FW_TOK * FW_LD];
+  __shared__ uint16_t sZ[FW_TOK * FW_LD];
+  int f0 = blockIdx.x * FW_FEAT, t0 = blockIdx.y * FW_TOK;
+  int tid = threadIdx.x;
+  bool has_z = dZc != nullptr;
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+    int item = tid + 256 * i;
+    int tok = item >> 2, ch = item & 3;
+    size_t row = (size_t)(t0 + tok);
+    u32x4 hv = *reinterpret_cast<const u32x4*>(Hc + row * (F / 2) + f0 / 2 + 8 * ch);
+    u32x4 zv = {0u, 0u, 0u, 0u};
+    if (has_z) zv = *reinterpret_cast<const u32x4*>(dZc + row * (F / 2) + f0 / 2 + 8 * ch);
+    uint32_t m16 = *reinterpret_cast<const uint16_t*>(meta + row * (F / 8) + f0 / 8 + 2 * ch);
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+      uint32_t nib = (m16 >> (4 * g)) & 15u;
+      uint32_t i0 = nib & 3u, i1 = nib >> 2;
+      uint32_t h_lo = hv[g] & 0xFFFFu, h_hi = hv[g] >> 16, z_lo = zv[g] & 0xFFFFu, z_hi = zv[g] >> 16;
+      uint32_t hw[4], zw[4];
+#pragma unroll
+      for (uint32_t j = 0; j < 4; j++) {
+        hw[j] = (i0 == j) ? h_lo : ((i1 == j) ? h_hi : 0u);
+        zw[j] = (i0 == j) ? z_lo : ((i1 == j) ? z_hi : 0u);
+      }
+      int o = tok * FW_LD + 16 * ch + 4 * g;   // even: 4-byte aligned
+      *reinterpret_cast<uint32_t*>(&sH[o]) = hw[0] | (hw[1] << 16);
+      *reinterpret_cast<uint32_t*>(&sH[o + 2]) = hw[2] | (hw[3] << 16);
+      *reinterpret_cast<uint32_t*>(&sZ[o]) = zw[0] | (zw[1] << 16);
+      *reinterpret_cast<uint32_t*>(&sZ[o + 2]) = zw[2] | (zw[3] << 16);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    int item = tid + 256 * i;
+    int oct = item & 15, f = item >> 4;
+    uint32_t h[8], z[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+      h[j] = sH[(8 * oct + j) * FW_LD + f];
+      z[j] = sZ[(8 * oct + j) * FW_LD + f];
+    }
+    uint32_t hp[2], zp[2], nb[2];
+#pragma unroll
+    for (int g = 0; g < 2; g++) {
+      nb[g] = pick24_words(h[4 * g], h[4 * g + 1], h[4 * g + 2], h[4 * g + 3], hp[g]);
+      uint32_t i0 = nb[g] & 3u, i1 = nb[g] >> 2;
+      uint32_t za = i0 == 0 ? z[4 * g] : (i0 == 1 ? z[4 * g + 1] : z[4 * g + 2]);
+      uint32_t zb = i1 == 3 ? z[4 * g + 3] : (i1 == 2 ? z[4 * g + 2] : z[4 * g + 1]);
+      zp[g] = za | (zb << 16);
+    }
+    size_t frow = (size_t)(f0 + f);
+    size_t vo = frow * (T / 2) + (t0 + 8 * oct) / 2;
+    *reinterpret_cast<u32x2*>(Hc_t + vo) = u32x2{hp[0], hp[1]};
+    if (has_z) *reinterpret_cast<u32x2*>(dZc_t + vo) = u32x2{zp[0], zp[1]};
+    meta_t[frow * (T / 8) + t0 / 8 + oct] = (uint8_t)(nb[0] | (nb[1] << 4));
+  }
+}
+
+int launch_featurewise24(const void* Hc, const uint8_t* meta, const void* dZc, int T, int F,
+                         void* Hc_t, uint8_t* meta_t, void* dZc_t, hipStream_t s) {
+  dim3 grid(F / FW_FEAT, T / FW_TOK);
+  hipLaunchKernelGGL(featurewise24_kernel, grid, dim3(256), 0, s, static_cast<const uint16_t*>(Hc), meta,
+                     static_cast<const uint16_t*>(dZc), T, F, static_cast<uint16_t*>(Hc_t), meta_t, static_cast<uint16_t*>(dZc_t));
+  return (int)hipGetLastError();
+}
+
+}  // namespace ffn24

@@ -1,0 +1,28 @@
+// Included by the k_*.hip translation units that instantiate the GEMM kernel.
+#pragma once
+#include "epilogues.hpp"
+#include "launch.hpp"
+
+namespace ffn24 {
+
+template <int AMODE, int BMODE, class Epi>
+static int launch_gemm(const GemmArgs& g, const typename Epi::Args& ea, hipStream_t s) {
+  auto kern = gemm_kernel<AMODE, BMODE, Epi>;
+  constexpr int lds = lds_total_bytes(AMODE);
+  // the opt-in for more than 64 KiB of dynamic LDS is per device; keep one flag per device
+  static bool configured[64] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return (int)e;
+  if (dev < 0 || dev >= 64) return (int)hipErrorInvalidDevice;
+  if (!configured[dev]) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return (int)e;
+    configured[dev] = true;
+  }
+  int nblocks = (g.M / TILE_M) * (g.N / TILE_N);
+  hipLaunchKernelGGL(kern, dim3(nblocks), dim3(GEMM_THREADS), lds, s, g, ea);
+  return (int)hipGetLastError();
+}
+
+}  // namespace ffn24

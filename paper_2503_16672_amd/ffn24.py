@@ -1,0 +1,206 @@
+"""ctypes binding over libffn24.so: the same names as include/ffn24.h, argument marshalling only.
+
+Tensors are torch CUDA tensors (torch is used for device memory and streams, nothing else); every
+call enqueues on torch's current stream.  Loading fails loudly if the library has not been built:
+there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libffn24.so")
+
+FFN24_BF16 = 0
+FFN24_FP8_E4M3 = 1
+FFN24_TRAINING = 1
+FFN24_DENSE = 2
+FFN24_DEBUG_DUMP_H = 4
+
+EXPORTS = (
+    "ffn24_ctx_create", "ffn24_ctx_destroy", "sparsify24", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd",
+    "ffn_fwd", "ffn_bwd", "ffn24_get_saved", "ffn24_set_profiling", "ffn24_kernel_ms", "ffn24_strerror",
+)
+
+KERNEL_NAMES = ("up_prune24", "down_sp", "dh_gather", "dx_sp", "featurewise24", "dw2_sp", "dw1_sp",
+                "dense_up", "dense_down", "dense_dh", "dense_dx", "dense_dw2", "dense_dw1")
+
+_lib = None
+
+
+class Ffn24Error(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: ffn24 error {code}: {strerror(code)}")
+        self.code = code
+
+
+def lib() -> ctypes.CDLL:
+    """Load libffn24.so (once).  Raises if it is missing: build it with `python -m paper_2503_16672_amd.build`."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is not built; run `python -m paper_2503_16672_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        L.ffn24_ctx_create.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ci, ci]
+        L.ffn24_ctx_destroy.argtypes = [vp]
+        L.sparsify24.argtypes = [vp, i64, i64, ci, vp, vp, vp]
+        L.sparsify24_featurewise.argtypes = [vp, vp, vp, i64, i64, vp, vp, vp, vp]
+        L.spmm24.argtypes = [vp, vp, vp, ci, i64, i64, i64, vp, vp]
+        L.ffn24_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+        L.ffn24_bwd.argtypes = [vp, vp, vp, vp, vp, vp]
+        L.ffn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+        L.ffn_bwd.argtypes = [vp, vp, vp, vp, vp, vp]
+        L.ffn24_get_saved.argtypes = [vp, ci, ctypes.POINTER(vp), ctypes.POINTER(i64)]
+        L.ffn24_set_profiling.argtypes = [vp, ci]
+        L.ffn24_kernel_ms.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_float)]
+        L.ffn24_strerror.argtypes = [ci]
+        L.ffn24_strerror.restype = ctypes.c_char_p
+        for name in EXPORTS:
+            if name != "ffn24_strerror":
+                getattr(L, name).restype = ci
+        _lib = L
+    return _lib
+
+
+_hiprt = None
+
+
+def _hip() -> ctypes.CDLL:
+    """The HIP runtime the library is linked against (only used for a device-to-device copy)."""
+    global _hiprt
+    if _hiprt is None:
+        _hiprt = ctypes.CDLL("libamdhip64.so")
+        _hiprt.hipMemcpyAsync.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
+        _hiprt.hipMemcpyAsync.restype = ctypes.c_int
+    return _hiprt
+
+
+def strerror(code: int) -> str:
+    return lib().ffn24_strerror(code).decode()
+
+
+def _check(code: int, what: str) -> None:
+    if code != 0:
+        raise Ffn24Error(code, what)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("ffn24 takes contiguous CUDA tensors")
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def sparsify24(H: torch.Tensor):
+    """H [rows, cols] bf16 -> (values [rows, cols/2] bf16, meta [rows, cols/8] uint8)."""
+    rows, cols = H.shape
+    values = torch.empty((rows, cols // 2), dtype=torch.bfloat16, device=H.device)
+    meta = torch.empty((rows, cols // 8), dtype=torch.uint8, device=H.device)
+    _check(lib().sparsify24(_ptr(H), rows, cols, FFN24_BF16, _ptr(values), _ptr(meta), _stream()), "sparsify24")
+    return values, meta
+
+
+def sparsify24_featurewise(Hc: torch.Tensor, meta: torch.Tensor, dZc: torch.Tensor | None = None):
+    """Token-wise compressed (Hc [T,F/2], meta [T,F/8]) -> (Hc_t [F,T/2], meta_t [F,T/8], dZc_t [F,T/2] or None)."""
+    T, F = Hc.shape[0], Hc.shape[1] * 2
+    Hc_t = torch.empty((F, T // 2), dtype=torch.bfloat16, device=Hc.device)
+    meta_t = torch.empty((F, T // 8), dtype=torch.uint8, device=Hc.device)
+    dZc_t = torch.empty((F, T // 2), dtype=torch.bfloat16, device=Hc.device) if dZc is not None else None
+    _check(lib().sparsify24_featurewise(_ptr(Hc), _ptr(meta), _ptr(dZc), T, F, _ptr(Hc_t), _ptr(meta_t), _ptr(dZc_t), _stream()),
+           "sparsify24_featurewise")
+    return Hc_t, meta_t, dZc_t
+
+
+def spmm24(values: torch.Tensor, meta: torch.Tensor, B: torch.Tensor, b_layout: int = 0) -> torch.Tensor:
+    """C [M,N] = A24 . B with A24 given as (values [M,K/2], meta [M,K/8]); B is [K,N] (layout 0) or [N,K] (layout 1)."""
+    M, K = values.shape[0], values.shape[1] * 2
+    N = B.shape[1] if b_layout == 0 else B.shape[0]
+    C = torch.empty((M, N), dtype=torch.bfloat16, device=values.device)
+    _check(lib().spmm24(_ptr(values), _ptr(meta), _ptr(B), b_layout, M, N, K, _ptr(C), _stream()), "spmm24")
+    return C
+
+
+class Context:
+    """Owns an ffn24_ctx (the device workspace for one (T, D, F) problem)."""
+
+    def __init__(self, T: int, D: int, F: int, flags: int = 0, dtype: int = FFN24_BF16):
+        self.T, self.D, self.F, self.flags = T, D, F, flags
+        h = ctypes.c_void_p()
+        _check(lib().ffn24_ctx_create(ctypes.byref(h), T, D, F, dtype, flags), "ffn24_ctx_create")
+        self._h = h
+
+    def close(self):
+        if self._h:
+            torch.cuda.synchronize()
+            _check(lib().ffn24_ctx_destroy(self._h), "ffn24_ctx_destroy")
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def ffn24_fwd(self, X, W1, b1, W2, Y=None):
+        Y = torch.empty((self.T, self.D), dtype=torch.bfloat16, device=X.device) if Y is None else Y
+        _check(lib().ffn24_fwd(self._h, _ptr(X), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(Y), _stream()), "ffn24_fwd")
+        return Y
+
+    def ffn_fwd(self, X, W1, b1, W2, Y=None):
+        Y = torch.empty((self.T, self.D), dtype=torch.bfloat16, device=X.device) if Y is None else Y
+        _check(lib().ffn_fwd(self._h, _ptr(X), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(Y), _stream()), "ffn_fwd")
+        return Y
+
+    def _bwd(self, fn, name, dY, out):
+        dev = dY.device
+        if out is None:
+            out = (torch.empty((self.T, self.D), dtype=torch.bfloat16, device=dev),
+                   torch.empty((self.D, self.F), dtype=torch.bfloat16, device=dev),
+                   torch.empty((self.F, self.D), dtype=torch.bfloat16, device=dev))
+        dX, dW1, dW2 = out
+        _check(fn(self._h, _ptr(dY), _ptr(dX), _ptr(dW1), _ptr(dW2), _stream()), name)
+        return dX, dW1, dW2
+
+    def ffn24_bwd(self, dY, out=None):
+        return self._bwd(lib().ffn24_bwd, "ffn24_bwd", dY, out)
+
+    def ffn_bwd(self, dY, out=None):
+        return self._bwd(lib().ffn_bwd, "ffn_bwd", dY, out)
+
+    _SAVED = {"Hc": (0, torch.bfloat16, lambda T, F: (T, F // 2)), "meta": (1, torch.uint8, lambda T, F: (T, F // 8)),
+              "dZc": (2, torch.bfloat16, lambda T, F: (T, F // 2)), "Hc_t": (3, torch.bfloat16, lambda T, F: (F, T // 2)),
+              "meta_t": (4, torch.uint8, lambda T, F: (F, T // 8)), "dZc_t": (5, torch.bfloat16, lambda T, F: (F, T // 2)),
+              "H_dump": (6, torch.bfloat16, lambda T, F: (T, F)), "H_dense": (7, torch.bfloat16, lambda T, F: (T, F)),
+              "dZ_dense": (8, torch.bfloat16, lambda T, F: (T, F))}
+
+    def saved(self, name: str) -> torch.Tensor:
+        """Copy of a workspace buffer as a torch tensor (device-to-device copy on the current stream)."""
+        which, dtype, shape_fn = self._SAVED[name]
+        p, n = ctypes.c_void_p(), ctypes.c_int64()
+        _check(lib().ffn24_get_saved(self._h, which, ctypes.byref(p), ctypes.byref(n)), "ffn24_get_saved")
+        if not p.value:
+            raise Ffn24Error(-5, f"buffer {name} not allocated in this context")
+        shape = shape_fn(self.T, self.F)
+        out = torch.empty(shape, dtype=dtype, device="cuda")
+        assert out.numel() * out.element_size() == n.value
+        rc = _hip().hipMemcpyAsync(ctypes.c_void_p(out.data_ptr()), p, ctypes.c_size_t(n.value), 3, ctypes.c_void_p(_stream()))
+        if int(rc) != 0:
+            raise RuntimeError(f"hipMemcpyAsync failed: {rc}")
+        return out
+
+    def set_profiling(self, on: bool):
+        _check(lib().ffn24_set_profiling(self._h, int(on)), "ffn24_set_profiling")
+
+    def kernel_ms(self, kernel: int) -> float:
+        ms = ctypes.c_float()
+        _check(lib().ffn24_kernel_ms(self._h, kernel, ctypes.byref(ms)), "ffn24_kernel_ms")
+        return float(ms.value)

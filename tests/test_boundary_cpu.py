@@ -1,0 +1,68 @@
+"""The C-ABI library loads, exports every symbol the header declares, and rejects bad arguments
+before touching the GPU.  No compute calls: runs without a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2503_16672_amd", "libffn24.so")
+HEADER = os.path.join(ROOT, "include", "ffn24.h")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libffn24.so not built (python -m paper_2503_16672_amd.build)")
+
+
+def _declared():
+    src = open(HEADER).read()
+    return re.findall(r"FFN24_API\s+(?:const\s+)?\w+\*?\s+(\w+)\s*\(", src)
+
+
+def test_header_symbols_are_exported():
+    names = _declared()
+    assert len(names) == 13 and "ffn24_fwd" in names and "sparsify24" in names
+    lib = ctypes.CDLL(LIB)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_binding_lists_the_same_names():
+    from paper_2503_16672_amd import ffn24
+    assert sorted(ffn24.EXPORTS) == sorted(_declared())
+    ffn24.lib()
+
+
+def test_strerror():
+    from paper_2503_16672_amd import ffn24
+    assert ffn24.strerror(0) == "ok"
+    assert "NULL" in ffn24.strerror(-1)
+    assert "unknown" in ffn24.strerror(-99)
+
+
+def test_argument_validation_without_gpu():
+    from paper_2503_16672_amd import ffn24
+    L = ffn24.lib()
+    a16 = 0x1000
+    # sparsify24: cols not a multiple of 8, negative rows, NULL, misaligned, unsupported dtype; rows == 0 is a no-op
+    assert L.sparsify24(a16, 4, 12, 0, a16, a16, None) == -2
+    assert L.sparsify24(a16, -1, 16, 0, a16, a16, None) == -2
+    assert L.sparsify24(None, 4, 16, 0, a16, a16, None) == -1
+    assert L.sparsify24(a16 + 2, 4, 16, 0, a16, a16, None) == -3
+    assert L.sparsify24(a16, 4, 16, 1, a16, a16, None) == -4
+    assert L.sparsify24(None, 0, 16, 0, None, None, None) == 0
+    # spmm24 shape rules
+    assert L.spmm24(a16, a16, a16, 0, 256, 256, 32, a16, None) == -2
+    assert L.spmm24(a16, a16, a16, 0, 100, 256, 64, a16, None) == -2
+    assert L.spmm24(a16, a16, a16, 2, 256, 256, 64, a16, None) == -2
+    assert L.spmm24(None, a16, a16, 0, 256, 256, 64, a16, None) == -1
+    # feature-wise
+    assert L.sparsify24_featurewise(a16, a16, None, 100, 64, a16, a16, None, None) == -2
+    assert L.sparsify24_featurewise(a16, a16, a16, 128, 64, a16, a16, None, None) == -1
+    # context: shape and dtype rules are checked before any allocation
+    h = ctypes.c_void_p()
+    assert L.ffn24_ctx_create(ctypes.byref(h), 100, 512, 2048, 0, 0) == -2
+    assert L.ffn24_ctx_create(ctypes.byref(h), 256, 512, 2048, 1, 0) == -4
+    assert L.ffn24_ctx_create(None, 256, 512, 2048, 0, 0) == -1
+    assert h.value is None
+    assert L.ffn24_fwd(None, a16, a16, None, a16, a16, None) == -1
+    assert L.ffn24_ctx_destroy(None) == 0

@@ -1,0 +1,364 @@
+"""GPU parity: every entry point of libffn24.so against the CPU oracle, through the C ABI.
+
+Bars: bit-exact for kept values' positions, metadata and anything copied unchanged; for floating-point
+outputs max|gpu - oracle| / max|oracle| <= 2e-2 (bf16 storage, fp32 accumulation).
+
+Staging of the mask comparison.  The pick is made on the bf16-rounded activation.  The GPU accumulates X W1 in
+fp32 in another order than the oracle's float64, so a few of the 10^5..10^8 activations round to the neighbouring
+bf16 value and a few picks may differ.  Therefore:
+  (S1) on identical bf16 input the pick is bit-exact (sparsify24, feature-wise, and the fused epilogue's pick
+       re-derived by the oracle from the activation the kernel itself dumped);
+  (S2) outputs downstream are compared with the oracle run on the GPU's own upstream tensors (tolerance);
+  (S3) end to end from the raw inputs: output tolerance, and the fraction of metadata bytes that agree is reported
+       and must be >= 99.5 %.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ffn24_oracle as O
+from paper_2503_16672_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-2
+
+
+@pytest.fixture(scope="module")
+def F24():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2503_16672_amd import ffn24
+    ffn24.lib()
+    return ffn24
+
+
+def dev_bf16_from_words(words: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(words.view(np.int16).copy()).cuda().view(torch.bfloat16)
+
+
+def words_of(t: torch.Tensor) -> np.ndarray:
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def to_dev_bf16(x: np.ndarray) -> torch.Tensor:
+    """Round with the oracle-independent torch cast (RNE) and upload."""
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16).cuda()
+
+
+def f64(t: torch.Tensor) -> np.ndarray:
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+# ----------------------------------------------------------------------------- sparsify24
+@pytest.mark.parametrize("rows,cols,p", [(1, 8, 0.5), (3, 40, 0.5), (257, 1000, 0.1), (256, 2048, 0.1), (1031, 4104, 0.3), (64, 8192, 1.0)])
+def test_sparsify24_bit_exact(F24, rows, cols, p):
+    print(f"sparsify24 rows={rows} cols={cols} p={p}", flush=True)
+    words = synth.random_activation_words(rows, cols, p, seed=rows * 7 + cols)
+    v_ref, m_ref = O.sparsify24(words)
+    v, m = F24.sparsify24(dev_bf16_from_words(words))
+    torch.cuda.synchronize()
+    assert np.array_equal(words_of(v), v_ref)
+    assert np.array_equal(m.cpu().numpy(), m_ref)
+
+
+def test_sparsify24_ties_signs_and_specials(F24):
+    print("sparsify24 ties/signs", flush=True)
+    rng = np.random.default_rng(5)
+    small = rng.integers(-3, 4, size=(512, 256)).astype(np.float32)          # many exact ties, both signs, zeros
+    small[::7] *= -0.0
+    words = O.f32_to_bf16_bits(small)
+    words[5, :8] = np.array([0x7F80, 0xFF80, 0x0001, 0x8001, 0x7F7F, 0x0000, 0x8000, 0x0080], np.uint16)  # inf, denormals, -0
+    v_ref, m_ref = O.sparsify24(words)
+    v, m = F24.sparsify24(dev_bf16_from_words(words))
+    torch.cuda.synchronize()
+    assert np.array_equal(words_of(v), v_ref)
+    assert np.array_equal(m.cpu().numpy(), m_ref)
+
+
+def test_sparsify24_empty(F24):
+    v, m = F24.sparsify24(torch.empty((0, 64), dtype=torch.bfloat16, device="cuda"))
+    assert v.shape == (0, 32) and m.shape == (0, 8)
+
+
+def test_sparsify24_large_sampled(F24):
+    """Full-size activation (16384 x 16384): sampled rows against the oracle, the 2:4 invariant everywhere."""
+    print("sparsify24 16384x16384", flush=True)
+    rows = cols = 16384
+    g = torch.Generator(device="cuda"); g.manual_seed(1)
+    z = torch.randn((rows, cols), generator=g, device="cuda")
+    H = torch.where(torch.rand((rows, cols), generator=g, device="cuda") < 0.1, z * z, torch.zeros((), device="cuda")).to(torch.bfloat16)
+    del z
+    v, m = F24.sparsify24(H)
+    torch.cuda.synchronize()
+    sel = np.random.default_rng(0).choice(rows, 48, replace=False)
+    sel_t = torch.from_numpy(sel).cuda()
+    v_ref, m_ref = O.sparsify24(words_of(H[sel_t]))
+    assert np.array_equal(words_of(v[sel_t]), v_ref)
+    assert np.array_equal(m[sel_t].cpu().numpy(), m_ref)
+    # invariants at full size, on the device: positions strictly increasing in every nibble
+    lo, hi = m & 0xF, m >> 4
+    for nib in (lo, hi):
+        assert bool(((nib & 3) < (nib >> 2)).all())
+
+
+# ----------------------------------------------------------------------------- sparse GEMM
+@pytest.mark.parametrize("M,N,K,layout", [(256, 256, 64, 0), (256, 256, 64, 1), (512, 256, 448, 0), (256, 768, 1024, 1), (1024, 512, 2048, 0)])
+def test_spmm24_matches_gather_matmul(F24, M, N, K, layout):
+    print(f"spmm24 M={M} N={N} K={K} layout={layout}", flush=True)
+    words = synth.random_activation_words(M, K, 0.6, seed=M + N + K)
+    # signs on some entries so that cancellation errors would show
+    words = np.where(np.random.default_rng(1).random(words.shape) < 0.3, words | 0x8000, words).astype(np.uint16)
+    v_w, meta = O.sparsify24(words)
+    rng = np.random.default_rng(K)
+    B = (rng.standard_normal((K, N)) / np.sqrt(K)).astype(np.float32)
+    Bq = O.round_bf16(B)
+    ref = O.gather_matmul24(O.bf16_bits_to_f32(v_w), meta, Bq.astype(np.float64))
+    Bd = to_dev_bf16(Bq if layout == 0 else np.ascontiguousarray(Bq.T))
+    C = F24.spmm24(dev_bf16_from_words(v_w), torch.from_numpy(meta).cuda(), Bd, layout)
+    torch.cuda.synchronize()
+    err = O.max_rel_err(f64(C), ref)
+    print("  max_rel_err", err, flush=True)
+    assert err <= 6e-3   # one bf16 rounding of the output (2^-9) plus fp32 accumulation
+
+
+def test_spmm24_integer_exact(F24):
+    """Small-integer operands: every product and sum is exact, so the result must match exactly --
+    any wrong lane/index pairing in the sparse instruction's operand layout shows as a wrong integer."""
+    print("spmm24 integer exact", flush=True)
+    M, N, K = 256, 256, 256
+    rng = np.random.default_rng(3)
+    A = rng.integers(-3, 4, size=(M, K)).astype(np.float32)
+    v_w, meta = O.sparsify24(O.f32_to_bf16_bits(A))
+    B = rng.integers(-2, 3, size=(K, N)).astype(np.float32)
+    ref = O.gather_matmul24(O.bf16_bits_to_f32(v_w), meta, B.astype(np.float64))
+    assert np.abs(ref).max() < 256
+    for layout in (0, 1):
+        Bd = to_dev_bf16(B if layout == 0 else np.ascontiguousarray(B.T))
+        C = F24.spmm24(dev_bf16_from_words(v_w), torch.from_numpy(meta).cuda(), Bd, layout)
+        torch.cuda.synchronize()
+        assert np.array_equal(f64(C), ref), layout
+
+
+# ----------------------------------------------------------------------------- feature-wise re-compression
+@pytest.mark.parametrize("T,Fh", [(128, 64), (384, 320), (1024, 2048)])
+def test_featurewise_bit_exact(F24, T, Fh):
+    print(f"featurewise T={T} F={Fh}", flush=True)
+    words = synth.random_activation_words(T, Fh, 0.35, seed=T + Fh)
+    Hc_w, meta = O.sparsify24(words)
+    H24_w = O.decompress24(Hc_w, meta)
+    rng = np.random.default_rng(2)
+    dZ_w = O.f32_to_bf16_bits(rng.standard_normal((T, Fh)).astype(np.float32))
+    dZc_w = O.compress_with_meta(dZ_w, meta)
+    dZ24_w = O.decompress24(dZc_w, meta)
+    Hct_ref, mt_ref = O.sparsify24(np.ascontiguousarray(H24_w.T))
+    dZct_ref = O.compress_with_meta(np.ascontiguousarray(dZ24_w.T), mt_ref)
+    Hc_t, meta_t, dZc_t = F24.sparsify24_featurewise(dev_bf16_from_words(Hc_w), torch.from_numpy(meta).cuda(), dev_bf16_from_words(dZc_w))
+    torch.cuda.synchronize()
+    assert np.array_equal(meta_t.cpu().numpy(), mt_ref)
+    assert np.array_equal(words_of(Hc_t), Hct_ref)
+    assert np.array_equal(words_of(dZc_t), dZct_ref)
+    Hc_t2, meta_t2, none = F24.sparsify24_featurewise(dev_bf16_from_words(Hc_w), torch.from_numpy(meta).cuda(), None)
+    torch.cuda.synchronize()
+    assert none is None and np.array_equal(meta_t2.cpu().numpy(), mt_ref) and np.array_equal(words_of(Hc_t2), Hct_ref)
+
+
+# ----------------------------------------------------------------------------- forward
+def _upload(inp):
+    d = {k: to_dev_bf16(inp[k]) for k in ("X", "W1", "W2")}
+    d["b1"] = torch.from_numpy(inp["b1"]).cuda()
+    if "dY" in inp:
+        d["dY"] = to_dev_bf16(inp["dY"])
+    return d
+
+
+def _check_fwd24(F24, inp, ctx, d, Y, full_oracle=True, rows=None):
+    """Staged forward checks.  rows: optional token subset (numpy indices) for the oracle side."""
+    T, Fh = ctx.T, ctx.F
+    rsel = np.arange(T) if rows is None else rows
+    rs_t = torch.from_numpy(rsel).cuda()
+    Hd = ctx.saved("H_dump")[rs_t]
+    Hc = ctx.saved("Hc")[rs_t]
+    meta = ctx.saved("meta")[rs_t]
+    torch.cuda.synchronize()
+    # S1: the epilogue's pick is the oracle's pick on the very activation the kernel rounded
+    v_ref, m_ref = O.sparsify24(words_of(Hd))
+    assert np.array_equal(meta.cpu().numpy(), m_ref)
+    assert np.array_equal(words_of(Hc), v_ref)
+    # S2: down-projection on the GPU's own compressed activation
+    W2q = f64(d["W2"])
+    y_staged = O.gather_matmul24(f64(Hc), meta.cpu().numpy(), W2q)
+    e2 = O.max_rel_err(f64(Y[rs_t]), y_staged)
+    # S3: from the raw inputs
+    ref = O.ffn24_fwd(inp["X"][rsel], inp["W1"], inp["b1"], inp["W2"])
+    eh = O.max_rel_err(f64(Hd), ref["Hq"])
+    e3 = O.max_rel_err(f64(Y[rs_t]), ref["Y"])
+    agree = float(np.mean(meta.cpu().numpy() == ref["meta"]))
+    print(f"  fwd24: H err {eh:.2e}  Y staged err {e2:.2e}  Y end-to-end err {e3:.2e}  meta agreement {agree:.5f}", flush=True)
+    assert eh <= TOL_BF16 and e2 <= TOL_BF16 and e3 <= TOL_BF16
+    assert agree >= 0.995
+    return ref
+
+
+def test_ffn24_fwd_c1(F24):
+    print("ffn24_fwd c1", flush=True)
+    inp = synth.make_workload("c1")
+    d = _upload(inp)
+    ctx = F24.Context(256, 512, 2048, F24.FFN24_DEBUG_DUMP_H)
+    Y = ctx.ffn24_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    torch.cuda.synchronize()
+    ref = _check_fwd24(F24, inp, ctx, d, Y)
+    sparsity = float(np.mean(ref["Hq"] == 0))
+    assert 0.88 < sparsity < 0.92
+    # deterministic: a second run gives the same bits
+    Y2 = ctx.ffn24_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y2)
+    ctx.close()
+
+
+def test_ffn24_fwd_no_bias_and_lossless_case(F24):
+    """b1 = NULL is the paper's FFN.  With two of every four hidden features switched off nothing is dropped
+    and the 2:4 FFN must equal the dense FFN run by the same library (Fig. 2 caption: exact if nothing is dropped)."""
+    print("ffn24_fwd lossless", flush=True)
+    inp = synth.make_inputs(256, 256, 512, 0.5, seed=77)
+    d = _upload(inp)
+    ctx = F24.Context(256, 256, 512, F24.FFN24_DEBUG_DUMP_H | F24.FFN24_DENSE)
+    Y0 = ctx.ffn24_fwd(d["X"], d["W1"], None, d["W2"])
+    torch.cuda.synchronize()
+    ref0 = O.ffn24_fwd(inp["X"], inp["W1"], None, inp["W2"])
+    assert O.max_rel_err(f64(Y0), ref0["Y"]) <= TOL_BF16
+    b1 = inp["b1"].copy()
+    b1.reshape(-1, 4)[:, [0, 3]] = -1e9
+    b1d = torch.from_numpy(b1).cuda()
+    Ya = ctx.ffn24_fwd(d["X"], d["W1"], b1d, d["W2"])
+    Yb = ctx.ffn_fwd(d["X"], d["W1"], b1d, d["W2"])
+    torch.cuda.synchronize()
+    Hdense = ctx.saved("H_dense")
+    H24 = O.decompress24(words_of(ctx.saved("Hc")), ctx.saved("meta").cpu().numpy())
+    assert np.array_equal(H24, words_of(Hdense))
+    assert O.max_rel_err(f64(Ya), f64(Yb)) <= 4e-3   # same operands, different summation order only
+    ctx.close()
+
+
+def test_ffn_fwd_dense_c1(F24):
+    print("ffn_fwd dense c1", flush=True)
+    inp = synth.make_workload("c1")
+    d = _upload(inp)
+    ctx = F24.Context(256, 512, 2048, F24.FFN24_DENSE)
+    Y = ctx.ffn_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    torch.cuda.synchronize()
+    ref = O.ffn_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"])
+    eh = O.max_rel_err(f64(ctx.saved("H_dense")), ref["Hq"])
+    ey = O.max_rel_err(f64(Y), ref["Y"])
+    print(f"  dense: H err {eh:.2e}  Y err {ey:.2e}", flush=True)
+    assert eh <= TOL_BF16 and ey <= TOL_BF16
+    ctx.close()
+
+
+# ----------------------------------------------------------------------------- backward
+def _check_bwd24(F24, inp, ctx, d, grads):
+    dX, dW1, dW2 = grads
+    Hc_w = words_of(ctx.saved("Hc")); meta = ctx.saved("meta").cpu().numpy()
+    dZc = ctx.saved("dZc"); Hc_t = ctx.saved("Hc_t"); meta_t = ctx.saved("meta_t").cpu().numpy(); dZc_t = ctx.saved("dZc_t")
+    torch.cuda.synchronize()
+    # oracle backward run on the GPU's own forward state (S2)
+    fwd = O.fwd_from_saved(Hc_w, meta, inp["X"], inp["W1"], inp["W2"])
+    ref = O.ffn24_bwd(fwd, inp["dY"])
+    e_dz = O.max_rel_err(f64(dZc), ref["dZc"])
+    # S1: feature-wise picks, bit-exact on the GPU's own H24; dZc_t is a pure gather of the GPU's dZc
+    assert np.array_equal(meta_t, ref["meta_t"])
+    assert np.array_equal(words_of(Hc_t), ref["Hc_t_words"])
+    dZ24_gpu = O.decompress24(words_of(dZc), meta)
+    assert np.array_equal(words_of(dZc_t), O.compress_with_meta(np.ascontiguousarray(dZ24_gpu.T), meta_t))
+    # S2: the three sparse GEMMs on the GPU's own operands
+    W1q, Xq, dYq = f64(d["W1"]), f64(d["X"]), f64(d["dY"])
+    e_dx = O.max_rel_err(f64(dX), O.gather_matmul24(f64(dZc), meta, W1q.T))
+    e_dw2 = O.max_rel_err(f64(dW2), O.gather_matmul24(f64(Hc_t), meta_t, dYq))
+    e_dw1 = O.max_rel_err(f64(dW1).T, O.gather_matmul24(f64(dZc_t), meta_t, Xq))
+    # against the oracle's own chain from the same forward state
+    e2_dx = O.max_rel_err(f64(dX), ref["dX"]); e2_dw1 = O.max_rel_err(f64(dW1), ref["dW1"]); e2_dw2 = O.max_rel_err(f64(dW2), ref["dW2"])
+    print(f"  bwd24: dZc {e_dz:.2e} | staged dX {e_dx:.2e} dW2 {e_dw2:.2e} dW1 {e_dw1:.2e} | chain dX {e2_dx:.2e} dW1 {e2_dw1:.2e} dW2 {e2_dw2:.2e}", flush=True)
+    for e in (e_dz, e_dx, e_dw2, e_dw1, e2_dx, e2_dw1, e2_dw2):
+        assert e <= TOL_BF16
+    return ref
+
+
+def test_ffn24_fwd_bwd_c1(F24):
+    print("ffn24 fwd+bwd c1", flush=True)
+    inp = synth.make_workload("c1", with_dy=True)
+    d = _upload(inp)
+    ctx = F24.Context(256, 512, 2048, F24.FFN24_DEBUG_DUMP_H | F24.FFN24_TRAINING)
+    Y = ctx.ffn24_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    grads = ctx.ffn24_bwd(d["dY"])
+    torch.cuda.synchronize()
+    _check_fwd24(F24, inp, ctx, d, Y)
+    _check_bwd24(F24, inp, ctx, d, grads)
+    # S3: end to end from the raw inputs
+    f = O.ffn24_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"])
+    g = O.ffn24_bwd(f, inp["dY"])
+    errs = [O.max_rel_err(f64(a), g[k]) for a, k in zip(grads, ("dX", "dW1", "dW2"))]
+    print("  end-to-end grads err", errs, flush=True)
+    assert max(errs) <= TOL_BF16
+    ctx.close()
+
+
+def test_ffn24_bwd_needs_fwd_and_flag(F24):
+    ctx = F24.Context(256, 256, 256, 0)
+    dY = torch.zeros((256, 256), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(F24.Ffn24Error) as e:
+        ctx.ffn24_bwd(dY)
+    assert e.value.code == -5
+    ctx.close()
+    ctx = F24.Context(256, 256, 256, F24.FFN24_TRAINING)
+    with pytest.raises(F24.Ffn24Error) as e:
+        ctx.ffn24_bwd(dY)
+    assert e.value.code == -5
+    with pytest.raises(F24.Ffn24Error):
+        ctx.ffn_fwd(dY, dY, None, dY)
+    ctx.close()
+
+
+def test_ffn_dense_fwd_bwd_c1(F24):
+    print("dense fwd+bwd c1", flush=True)
+    inp = synth.make_workload("c1", with_dy=True)
+    d = _upload(inp)
+    ctx = F24.Context(256, 512, 2048, F24.FFN24_DENSE)
+    ctx.ffn_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    dX, dW1, dW2 = ctx.ffn_bwd(d["dY"])
+    torch.cuda.synchronize()
+    Hq = ctx.saved("H_dense").float().cpu().numpy()
+    fwd = {"Hq": Hq, "Xq": f64(d["X"]), "W1q": f64(d["W1"]), "W2q": f64(d["W2"])}
+    ref = O.ffn_bwd(fwd, inp["dY"])
+    errs = {"dZ": O.max_rel_err(f64(ctx.saved("dZ_dense")), ref["dZq"]), "dX": O.max_rel_err(f64(dX), ref["dX"]),
+            "dW1": O.max_rel_err(f64(dW1), ref["dW1"]), "dW2": O.max_rel_err(f64(dW2), ref["dW2"])}
+    print("  dense bwd errs", errs, flush=True)
+    assert max(errs.values()) <= TOL_BF16
+    # and from the raw inputs
+    f = O.ffn_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"])
+    g = O.ffn_bwd(f, inp["dY"])
+    assert max(O.max_rel_err(f64(a), g[k]) for a, k in ((dX, "dX"), (dW1, "dW1"), (dW2, "dW2"))) <= TOL_BF16
+    ctx.close()
+
+
+def test_multi_tile_shapes(F24):
+    """Several block tiles in every GEMM dimension and K stages that are not a power of two."""
+    print("multi-tile fwd+bwd T=768 D=768 F=1280", flush=True)
+    T, D, Fh = 768, 768, 1280
+    inp = synth.make_inputs(T, D, Fh, "per_feature", seed=31, with_dy=True)
+    d = _upload(inp)
+    ctx = F24.Context(T, D, Fh, F24.FFN24_DEBUG_DUMP_H | F24.FFN24_TRAINING | F24.FFN24_DENSE)
+    Y = ctx.ffn24_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    grads = ctx.ffn24_bwd(d["dY"])
+    torch.cuda.synchronize()
+    _check_fwd24(F24, inp, ctx, d, Y)
+    _check_bwd24(F24, inp, ctx, d, grads)
+    Yd = ctx.ffn_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    gd = ctx.ffn_bwd(d["dY"])
+    torch.cuda.synchronize()
+    f = O.ffn_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"])
+    g = O.ffn_bwd(f, inp["dY"])
+    errs = [O.max_rel_err(f64(Yd), f["Y"])] + [O.max_rel_err(f64(a), g[k]) for a, k in zip(gd, ("dX", "dW1", "dW2"))]
+    print("  dense errs", errs, flush=True)
+    assert max(errs) <= TOL_BF16
+    ctx.close()
