@@ -1,0 +1,152 @@
+#!/usr/bin/env python3
+"""Benchmark of the 2:4 Squared-ReLU FFN hot path on one MI355X.
+
+A step is one forward + backward of the 2:4 FFN (all kernels of the path) on one batch of seeded synthetic
+inputs that are resident in HBM before the clock starts.  Prints ONE JSON line:
+  value     dense-equivalent TFLOP/s of the step (12 T D F flops per step)
+  roofline  the dominant kernel (largest share of the step) against the published MFMA peak, from HIP events
+            recorded inside the library on the launch stream
+  cpu_baseline  the CPU oracle timed on a bounded token slice of the same workload on this host
+plus the dense-MFMA FFN timed the same way (speed-up) and every kernel's own rate.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_DENSE = 2500.0   # TFLOP/s, MI355X published dense bf16 MFMA peak
+# executed MFMA flops per kernel, in units of T*D*F (dense GEMM = 2, sparse GEMM executes half of its dense equivalent)
+KERNEL_FLOPS = {"up_prune24": 2.0, "down_sp": 1.0, "dh_gather": 2.0, "dx_sp": 1.0, "dw2_sp": 1.0, "dw1_sp": 1.0,
+                "dense_up": 2.0, "dense_down": 2.0, "dense_dh": 2.0, "dense_dx": 2.0, "dense_dw2": 2.0, "dense_dw1": 2.0}
+SPARSE = {"down_sp", "dx_sp", "dw2_sp", "dw1_sp"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c4", help="c1, c2, c3_85..c3_98, c4 (default: forward+backward at the 7B FFN dims)")
+    ap.add_argument("--fwd-only", action="store_true", help="time the forward pass only")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--cpu-tokens", type=int, default=512, help="token slice the CPU oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU by design (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2503_16672_amd import ffn24, synth
+
+    ffn24.lib()  # fails loudly if libffn24.so is not built; there is no fallback path
+    w = synth.WORKLOADS[args.workload]
+    T, D, F = w.T, w.D, w.F
+    inp = synth.make_workload(args.workload, with_dy=True)
+    dev = {k: torch.from_numpy(inp[k]).to(torch.bfloat16).cuda() for k in ("X", "W1", "W2", "dY")}
+    b1 = torch.from_numpy(inp["b1"]).cuda()
+    ctx = ffn24.Context(T, D, F, ffn24.FFN24_TRAINING | ffn24.FFN24_DENSE)
+    Y = torch.empty((T, D), dtype=torch.bfloat16, device="cuda")
+    grads = (torch.empty((T, D), dtype=torch.bfloat16, device="cuda"), torch.empty((D, F), dtype=torch.bfloat16, device="cuda"),
+             torch.empty((F, D), dtype=torch.bfloat16, device="cuda"))
+    bwd = not args.fwd_only
+
+    def step24():
+        ctx.ffn24_fwd(dev["X"], dev["W1"], b1, dev["W2"], Y)
+        if bwd:
+            ctx.ffn24_bwd(dev["dY"], grads)
+
+    def step_dense():
+        ctx.ffn_fwd(dev["X"], dev["W1"], b1, dev["W2"], Y)
+        if bwd:
+            ctx.ffn_bwd(dev["dY"], grads)
+
+    def timed(fn, warmup, steps):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    ctx.set_profiling(True)   # event pairs around every kernel, on the launch stream; no synchronisation added
+    sec24 = timed(step24, args.warmup, args.steps)
+    # per-kernel durations: average over the same number of steps, reading the events after each step
+    k24 = list(range(0, 7 if bwd else 2))
+    kd = list(range(7, 13 if bwd else 9))
+    acc = {k: 0.0 for k in k24 + kd}
+    for _ in range(args.steps):
+        step24()
+        torch.cuda.synchronize()
+        for k in k24:
+            acc[k] += ctx.kernel_ms(k)
+    sec_dense = timed(step_dense, args.warmup, args.steps)
+    for _ in range(args.steps):
+        step_dense()
+        torch.cuda.synchronize()
+        for k in kd:
+            acc[k] += ctx.kernel_ms(k)
+    ctx.set_profiling(False)
+    kernel_ms = {ffn24.KERNEL_NAMES[k]: acc[k] / args.steps for k in acc}
+
+    tdf = float(T) * D * F
+    flops_step = (12.0 if bwd else 4.0) * tdf
+    value = flops_step / sec24 / 1e12
+    kernels = {}
+    for name, ms in kernel_ms.items():
+        if name in KERNEL_FLOPS:
+            tf = KERNEL_FLOPS[name] * tdf / (ms * 1e-3) / 1e12
+            kernels[name] = {"ms": round(ms, 4), "tflops_executed": round(tf, 1), "frac_of_dense_mfma_peak": round(tf / PEAK_BF16_DENSE, 4)}
+            if name in SPARSE:
+                kernels[name]["tflops_dense_equivalent"] = round(2 * tf, 1)
+        else:
+            # feature-wise re-compression: HBM-bound, 4.25 bytes per element of [T, F]
+            gbs = 4.25 * T * F / (ms * 1e-3) / 1e9
+            kernels[name] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / 8000.0, 4)}
+    dom = max((n for n in kernel_ms if n in KERNEL_FLOPS and not n.startswith("dense_")), key=lambda n: kernel_ms[n])
+    achieved = KERNEL_FLOPS[dom] * tdf / (kernel_ms[dom] * 1e-3) / 1e12
+    roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_DENSE, "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_BF16_DENSE, 4), "traffic": None,
+                "note": "executed bf16 MFMA flops of the launch / its HIP-event duration; a sparse kernel executes half its dense-equivalent flops"}
+
+    cpu = None
+    if not args.no_cpu:
+        from oracle import ffn24_oracle as O
+        Ts = min(args.cpu_tokens, T)
+        sl = {k: inp[k][:Ts] if k in ("X", "dY") else inp[k] for k in inp}
+        t0 = time.perf_counter()
+        f = O.ffn24_fwd(sl["X"], sl["W1"], sl["b1"], sl["W2"])
+        if bwd:
+            O.ffn24_bwd(f, sl["dY"])
+        dt = time.perf_counter() - t0
+        cpu = {"value": round((12.0 if bwd else 4.0) * Ts * D * F / dt / 1e12, 5), "unit": "TFLOP/s", "cores": len(os.sched_getaffinity(0)),
+               "kind": "oracle", "sample": f"first {Ts} of {T} tokens of the same workload, float64 numpy, {dt:.1f} s"}
+
+    out = {
+        "metric": "FFN fwd+bwd dense-equiv TFLOP/s" if bwd else "FFN fwd dense-equiv TFLOP/s",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec24 * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: 2:4 Squared-ReLU FFN {'fwd+bwd' if bwd else 'fwd'}, T={T} d_model={D} d_ff={F}, target sparsity {w.sparsity}",
+                   "T": T, "d_model": D, "d_ff": F, "parallelism": "single GPU"},
+        "frac_of_sparse_mfma_peak": round(value / (2 * PEAK_BF16_DENSE), 4),
+        "dense_ffn": {"ms_per_step": round(sec_dense * 1e3, 4), "tflops": round(flops_step / sec_dense / 1e12, 2)},
+        "speedup_vs_dense_ffn": round(sec_dense / sec24, 4),
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+    }
+    ctx.close()
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
