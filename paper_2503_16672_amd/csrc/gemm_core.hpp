@@ -31,6 +31,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <utility>
 
 namespace ffn24 {
 
@@ -94,6 +95,11 @@ struct StageKC {
       off[j] = p * 128 + ((chunk ^ swz8(p)) << 4);
     }
   }
+  static constexpr int NLOAD = 8, NSTORE = 8;
+  template <int J> __device__ __forceinline__ void load1(int kt) {
+    r[J] = *reinterpret_cast<const u32x4*>(g + (size_t)kt * (TILE_K * 2) + J * jstride);
+  }
+  template <int J> __device__ __forceinline__ void store1(char* lds) { *reinterpret_cast<u32x4*>(lds + off[J]) = r[J]; }
   __device__ __forceinline__ void load(int kt) {
     const char* p = g + (size_t)kt * (TILE_K * 2);
 #pragma unroll
@@ -123,23 +129,25 @@ struct StageMC {
       off[j] = p * 128 + ((kb ^ swz8(p)) << 4);
     }
   }
-  __device__ __forceinline__ void load(int kt) {
-    const char* p = g + (size_t)kt * TILE_K * kstride;
+  static constexpr int NLOAD = 8, NSTORE = 8;
+  template <int I> __device__ __forceinline__ void load1(int kt) {
+    r[I] = *reinterpret_cast<const u32x4*>(g + ((size_t)kt * TILE_K + I) * kstride);
+  }
+  // column J of the 8x8 block: dword d = (r[2d] half J, r[2d+1] half J) -- an 8x8 transpose of 16-bit elements
+  template <int J> __device__ __forceinline__ void store1(char* lds) {
+    u32x4 o;
 #pragma unroll
-    for (int i = 0; i < 8; i++) r[i] = *reinterpret_cast<const u32x4*>(p + i * kstride);
+    for (int d = 0; d < 4; d++) {
+      uint32_t lo = r[2 * d][J >> 1], hi = r[2 * d + 1][J >> 1];
+      o[d] = (J & 1) ? ((lo >> 16) | (hi & 0xFFFF0000u)) : ((lo & 0xFFFFu) | (hi << 16));
+    }
+    *reinterpret_cast<u32x4*>(lds + off[J]) = o;
+  }
+  __device__ __forceinline__ void load(int kt) {
+    load1<0>(kt); load1<1>(kt); load1<2>(kt); load1<3>(kt); load1<4>(kt); load1<5>(kt); load1<6>(kt); load1<7>(kt);
   }
   __device__ __forceinline__ void store(char* lds) {
-    // out[j] dword d = (r[2d] half j, r[2d+1] half j): 8x8 transpose of 16-bit elements
-#pragma unroll
-    for (int j = 0; j < 8; j++) {
-      u32x4 o;
-#pragma unroll
-      for (int d = 0; d < 4; d++) {
-        uint32_t lo = r[2 * d][j >> 1], hi = r[2 * d + 1][j >> 1];
-        o[d] = (j & 1) ? ((lo >> 16) | (hi & 0xFFFF0000u)) : ((lo & 0xFFFFu) | (hi << 16));
-      }
-      *reinterpret_cast<u32x4*>(lds + off[j]) = o;
-    }
+    store1<0>(lds); store1<1>(lds); store1<2>(lds); store1<3>(lds); store1<4>(lds); store1<5>(lds); store1<6>(lds); store1<7>(lds);
   }
 };
 
@@ -164,17 +172,17 @@ struct StageSP {
     }
     moff = LDS_COMP + perm_m(tid) * 8;
   }
-  __device__ __forceinline__ void load(int kt) {
-    const char* p = g + (size_t)kt * (TILE_K / 2 * 2);
-#pragma unroll
-    for (int j = 0; j < 4; j++) r[j] = *reinterpret_cast<const u32x4*>(p + j * jstride);
-    m = *reinterpret_cast<const u32x2*>(gm + (size_t)kt * (TILE_K / 8));
+  static constexpr int NLOAD = 5, NSTORE = 5;
+  template <int J> __device__ __forceinline__ void load1(int kt) {
+    if constexpr (J < 4) r[J] = *reinterpret_cast<const u32x4*>(g + (size_t)kt * (TILE_K / 2 * 2) + J * jstride);
+    else m = *reinterpret_cast<const u32x2*>(gm + (size_t)kt * (TILE_K / 8));
   }
-  __device__ __forceinline__ void store(char* lds) {
-#pragma unroll
-    for (int j = 0; j < 4; j++) *reinterpret_cast<u32x4*>(lds + off[j]) = r[j];
-    *reinterpret_cast<u32x2*>(lds + moff) = m;
+  template <int J> __device__ __forceinline__ void store1(char* lds) {
+    if constexpr (J < 4) *reinterpret_cast<u32x4*>(lds + off[J]) = r[J];
+    else *reinterpret_cast<u32x2*>(lds + moff) = m;
   }
+  __device__ __forceinline__ void load(int kt) { load1<0>(kt); load1<1>(kt); load1<2>(kt); load1<3>(kt); load1<4>(kt); }
+  __device__ __forceinline__ void store(char* lds) { store1<0>(lds); store1<1>(lds); store1<2>(lds); store1<3>(lds); store1<4>(lds); }
 };
 
 template <int AMODE> struct AStager;
@@ -207,59 +215,85 @@ struct LaneCtx {
   int fsw;         // swz8 of the lane's row with mi = 0
 };
 
-__device__ __forceinline__ void compute_dense(const char* sA, const char* sB, const LaneCtx& L, f32x16 (&acc)[4][4]) {
-#pragma unroll
-  for (int s = 0; s < 4; s++) {
-    bf16x8 a[4], b[4];
-    int c = 2 * s + L.h;
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-      int sw = L.fsw ^ ((i & 1) << 2);
-      a[i] = *reinterpret_cast<const bf16x8*>(sA + L.a_row_off + i * (32 * 128) + ((c ^ sw) << 4));
-      b[i] = *reinterpret_cast<const bf16x8*>(sB + L.b_row_off + i * (32 * 128) + ((c ^ sw) << 4));
-    }
-#pragma unroll
-    for (int mi = 0; mi < 4; mi++)
-#pragma unroll
-      for (int ni = 0; ni < 4; ni++)
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
-  }
+// compile-time loop: f(std::integral_constant<int, 0>) ... f(std::integral_constant<int, N-1>)
+template <class F, int... Is>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>) { (f(std::integral_constant<int, Is>{}), ...); }
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) { static_for_impl(f, std::make_integer_sequence<int, N>{}); }
+
+// Nothing may be moved across this point by the instruction scheduler.  The main loop is written as a sequence of
+// slots {one matrix op + the memory ops that ride on it}, fenced from each other, so the issue order is the source order.
+#define FFN24_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// MFMA fragments of one K step.  Dense: 16-wide step, 4 A + 4 B fragments of 8 bf16.
+struct FragD {
+  bf16x8 a[4], b[4];
+};
+
+// fragment I of K step s: I < 4 -> a[I], else b[I-4]
+template <int I>
+__device__ __forceinline__ void load_frag_dense1(const char* sA, const char* sB, const LaneCtx& L, int s, FragD& f) {
+  int c = 2 * s + L.h;
+  constexpr int i = I & 3;
+  int sw = L.fsw ^ ((i & 1) << 2);
+  if constexpr (I < 4) f.a[i] = *reinterpret_cast<const bf16x8*>(sA + L.a_row_off + i * (32 * 128) + ((c ^ sw) << 4));
+  else f.b[i] = *reinterpret_cast<const bf16x8*>(sB + L.b_row_off + i * (32 * 128) + ((c ^ sw) << 4));
 }
 
-// Stage K window of 64 = four 16-wide windows w.  Instruction s (0,1) gives lane half q the window 2q+s, so a lane's
-// two instructions use 32 consecutive stored-value bytes and one 32-bit metadata word (ABID = s picks the half).
-// B lane half h then needs, for instruction s, the 8-k chunks 2s+h (registers 0..7) and 4+2s+h (registers 8..15).
-template <int S>
-__device__ __forceinline__ void smfmac_step(const char* sAc, const char* sB, const LaneCtx& L, int arow64, int asw,
-                                            const uint32_t (&idx)[4], f32x16 (&acc)[4][4]) {
+template <int M>
+__device__ __forceinline__ void mfma_dense1(const FragD& f, f32x16 (&acc)[4][4]) {
+  constexpr int mi = M >> 2, ni = M & 3;
+  acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[mi], f.b[ni], acc[mi][ni], 0, 0, 0);
+}
+
+// Sparse: the stage's K window of 64 = four 16-wide windows w.  Instruction S (0,1) gives lane half q the window
+// 2q+S, so a lane's two instructions use 32 consecutive stored-value bytes and one 32-bit metadata word (ABID = S
+// picks the half).  B lane half h then needs, for instruction S, the 8-k chunks 2S+h (registers 0..7) and 4+2S+h
+// (registers 8..15).
+struct FragS {
   bf16x8 a[4];
-  bf16x16 b[4];
-  int w = 2 * L.h + S;
-#pragma unroll
-  for (int i = 0; i < 4; i++) {
-    a[i] = *reinterpret_cast<const bf16x8*>(sAc + arow64 + i * (32 * 64) + ((w ^ asw) << 4));
+  bf16x8 blo[4], bhi[4];
+};
+
+template <int I>
+__device__ __forceinline__ void load_idx_sparse1(const char* sA, const LaneCtx& L, uint32_t (&idx)[4]) {
+  int p = L.wy * 128 + L.rho;
+  idx[I] = *reinterpret_cast<const uint32_t*>(sA + LDS_COMP + (p + 32 * I) * 8 + 4 * L.h);
+}
+
+// fragment I of instruction S: I < 4 -> a[I]; 4..7 -> low half of b[I-4]; 8..11 -> high half of b[I-8]
+template <int S, int I>
+__device__ __forceinline__ void load_frag_sparse1(const char* sAc, const char* sB, const LaneCtx& L, FragS& f) {
+  constexpr int i = I & 3;
+  if constexpr (I < 4) {
+    int p = L.wy * 128 + L.rho;
+    int w = 2 * L.h + S;
+    f.a[i] = *reinterpret_cast<const bf16x8*>(sAc + p * 64 + i * (32 * 64) + ((w ^ swz4(p)) << 4));
+  } else {
     int sw = L.fsw ^ ((i & 1) << 2);
     const char* row = sB + L.b_row_off + i * (32 * 128);
-    bf16x8 lo = *reinterpret_cast<const bf16x8*>(row + (((2 * S + L.h) ^ sw) << 4));
-    bf16x8 hi = *reinterpret_cast<const bf16x8*>(row + (((4 + 2 * S + L.h) ^ sw) << 4));
-    b[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+    if constexpr (I < 8) f.blo[i] = *reinterpret_cast<const bf16x8*>(row + (((2 * S + L.h) ^ sw) << 4));
+    else f.bhi[i] = *reinterpret_cast<const bf16x8*>(row + (((4 + 2 * S + L.h) ^ sw) << 4));
   }
-#pragma unroll
-  for (int mi = 0; mi < 4; mi++)
-#pragma unroll
-    for (int ni = 0; ni < 4; ni++)
-      acc[mi][ni] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a[mi], b[ni], acc[mi][ni], (int)idx[mi], 0, S);
 }
 
-__device__ __forceinline__ void compute_sparse(const char* sA, const char* sB, const LaneCtx& L, f32x16 (&acc)[4][4]) {
-  int p = L.wy * 128 + L.rho;
-  int arow64 = p * 64;
-  int asw = swz4(p);
-  uint32_t idx[4];
-#pragma unroll
-  for (int i = 0; i < 4; i++) idx[i] = *reinterpret_cast<const uint32_t*>(sA + LDS_COMP + (p + 32 * i) * 8 + 4 * L.h);
-  smfmac_step<0>(sA, sB, L, arow64, asw, idx, acc);
-  smfmac_step<1>(sA, sB, L, arow64, asw, idx, acc);
+template <int S, int M>
+__device__ __forceinline__ void mfma_sparse1(const FragS& f, const uint32_t (&idx)[4], f32x16 (&acc)[4][4]) {
+  constexpr int mi = M >> 2, ni = M & 3;
+  bf16x16 b = __builtin_shufflevector(f.blo[ni], f.bhi[ni], 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+  acc[mi][ni] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(f.a[mi], b, acc[mi][ni], (int)idx[mi], 0, S);
+}
+
+// global load / LDS store number J of the stage: A's ops first, then B's
+template <int J, class SA, class SB>
+__device__ __forceinline__ void gload1(SA& sa, SB& sb, int kt) {
+  if constexpr (J < SA::NLOAD) sa.template load1<J>(kt);
+  else if constexpr (J < SA::NLOAD + SB::NLOAD) sb.template load1<J - SA::NLOAD>(kt);
+}
+template <int J, class SA, class SB>
+__device__ __forceinline__ void lstore1(SA& sa, SB& sb, char* ldsA, char* ldsB) {
+  if constexpr (J < SA::NSTORE) sa.template store1<J>(ldsA);
+  else if constexpr (J < SA::NSTORE + SB::NSTORE) sb.template store1<J - SA::NSTORE>(ldsB);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -316,6 +350,12 @@ __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(GemmArgs g, typename
     for (int j = 0; j < 4; j++)
 #pragma unroll
       for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
+  // Pin the accumulators to the accumulation register file: an empty asm with an AGPR constraint gives their
+  // live ranges the AGPR class, so the 256 arch VGPRs stay free for fragments, prefetch and addresses.
+#pragma unroll
+  for (int i = 0; i < 4; i++)
+#pragma unroll
+    for (int j = 0; j < 4; j++) asm volatile("" : "+a"(acc[i][j]));
 
   int nk = g.K / TILE_K;
   sa.load(0);
@@ -323,15 +363,99 @@ __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(GemmArgs g, typename
   sa.store(smem);
   sb.store(smem + A_BYTES);
   __syncthreads();
-  for (int kt = 0; kt < nk; kt++) {
-    char* cur = smem + (kt & 1) * STAGE;
-    char* nxt = smem + ((kt + 1) & 1) * STAGE;
-    bool more = kt + 1 < nk;
-    if (more) { sa.load(kt + 1); sb.load(kt + 1); }
-    if (AMODE == A_SP) compute_sparse(cur, cur + A_BYTES, L, acc);
-    else compute_dense(cur, cur + A_BYTES, L, acc);
-    if (more) { sa.store(nxt); sb.store(nxt + A_BYTES); }
-    __syncthreads();
+
+  // Software pipeline, written slot by slot (one matrix op per slot, fenced).  Per stage: the global loads of the
+  // next stage ride on the first matrix ops; the fragments of K step s+1 are read from LDS under the matrix ops of
+  // step s; under the first half of the last step the next stage is written to the other LDS buffer; then the one
+  // barrier of the stage; under the second half of the last step the first fragments of the next stage are read.
+  constexpr int NL = AStager<AMODE>::NLOAD + BStager<BMODE>::NLOAD;
+  constexpr int NS = AStager<AMODE>::NSTORE + BStager<BMODE>::NSTORE;
+  if constexpr (AMODE == A_SP) {
+    FragS f0, f1;
+    uint32_t idx[4];
+    static_for<4>([&](auto I) { load_idx_sparse1<I>(smem, L, idx); });
+    static_for<12>([&](auto I) { load_frag_sparse1<0, I>(smem, smem + A_BYTES, L, f0); });
+    auto stage = [&](int kt, auto has_next) {
+      constexpr bool more = decltype(has_next)::value;
+      const char* cur = smem + (kt & 1) * STAGE;
+      char* nxt = smem + ((kt + 1) & 1) * STAGE;
+      uint32_t idx_n[4] = {0u, 0u, 0u, 0u};
+      FFN24_FENCE();
+      static_for<16>([&](auto M) {
+        mfma_sparse1<0, M>(f0, idx, acc);
+        if constexpr (more) gload1<M>(sa, sb, kt + 1);
+        if constexpr (M < 12) load_frag_sparse1<1, M>(cur, cur + A_BYTES, L, f1);
+        FFN24_FENCE();
+      });
+      static_for<8>([&](auto M) {
+        mfma_sparse1<1, M>(f1, idx, acc);
+        if constexpr (more) {
+          lstore1<2 * M>(sa, sb, nxt, nxt + A_BYTES);
+          lstore1<2 * M + 1>(sa, sb, nxt, nxt + A_BYTES);
+        }
+        FFN24_FENCE();
+      });
+      if constexpr (more) __syncthreads();
+      FFN24_FENCE();
+      static_for<8>([&](auto M) {
+        mfma_sparse1<1, M + 8>(f1, idx, acc);
+        if constexpr (more) {
+          if constexpr (M < 4) load_idx_sparse1<M>(nxt, L, idx_n);
+          if constexpr (M < 6) {
+            load_frag_sparse1<0, 2 * M>(nxt, nxt + A_BYTES, L, f0);
+            load_frag_sparse1<0, 2 * M + 1>(nxt, nxt + A_BYTES, L, f0);
+          }
+        }
+        FFN24_FENCE();
+      });
+#pragma unroll
+      for (int i = 0; i < 4; i++) idx[i] = idx_n[i];
+    };
+    for (int kt = 0; kt < nk - 1; kt++) stage(kt, std::true_type{});
+    stage(nk - 1, std::false_type{});
+  } else {
+    static_assert(NL == 16 && NS == 16, "dense stages issue one global load per slot of step 0");
+    FragD f0, f1;
+    static_for<8>([&](auto I) { load_frag_dense1<I>(smem, smem + A_BYTES, L, 0, f0); });
+    auto stage = [&](int kt, auto has_next) {
+      constexpr bool more = decltype(has_next)::value;
+      const char* cur = smem + (kt & 1) * STAGE;
+      char* nxt = smem + ((kt + 1) & 1) * STAGE;
+      FFN24_FENCE();
+      static_for<16>([&](auto M) {
+        mfma_dense1<M>(f0, acc);
+        if constexpr (more) gload1<M>(sa, sb, kt + 1);
+        if constexpr (M < 8) load_frag_dense1<M>(cur, cur + A_BYTES, L, 1, f1);
+        FFN24_FENCE();
+      });
+      static_for<16>([&](auto M) {
+        mfma_dense1<M>(f1, acc);
+        if constexpr (M < 8) load_frag_dense1<M>(cur, cur + A_BYTES, L, 2, f0);
+        FFN24_FENCE();
+      });
+      static_for<16>([&](auto M) {
+        mfma_dense1<M>(f0, acc);
+        if constexpr (M < 8) load_frag_dense1<M>(cur, cur + A_BYTES, L, 3, f1);
+        FFN24_FENCE();
+      });
+      static_for<8>([&](auto M) {
+        mfma_dense1<M>(f1, acc);
+        if constexpr (more) {
+          lstore1<2 * M>(sa, sb, nxt, nxt + A_BYTES);
+          lstore1<2 * M + 1>(sa, sb, nxt, nxt + A_BYTES);
+        }
+        FFN24_FENCE();
+      });
+      if constexpr (more) __syncthreads();
+      FFN24_FENCE();
+      static_for<8>([&](auto M) {
+        mfma_dense1<M + 8>(f1, acc);
+        if constexpr (more) load_frag_dense1<M>(nxt, nxt + A_BYTES, L, 0, f0);
+        FFN24_FENCE();
+      });
+    };
+    for (int kt = 0; kt < nk - 1; kt++) stage(kt, std::true_type{});
+    stage(nk - 1, std::false_type{});
   }
   int m_lane = m0 + L.wy * 128 + 64 * L.h;
   int n_lane = n0 + L.wx * 128 + 4 * L.rho;
