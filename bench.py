@@ -52,11 +52,11 @@ def main() -> int:
     inp = synth.make_workload(args.workload, with_dy=True)
     dev = {k: torch.from_numpy(inp[k]).to(torch.bfloat16).cuda() for k in ("X", "W1", "W2", "dY")}
     b1 = torch.from_numpy(inp["b1"]).cuda()
-    ctx = ffn24.Context(T, D, F, ffn24.FFN24_TRAINING | ffn24.FFN24_DENSE)
+    bwd = not args.fwd_only
+    ctx = ffn24.Context(T, D, F, (ffn24.FFN24_TRAINING if bwd else 0) | ffn24.FFN24_DENSE)
     Y = torch.empty((T, D), dtype=torch.bfloat16, device="cuda")
     grads = (torch.empty((T, D), dtype=torch.bfloat16, device="cuda"), torch.empty((D, F), dtype=torch.bfloat16, device="cuda"),
              torch.empty((F, D), dtype=torch.bfloat16, device="cuda"))
-    bwd = not args.fwd_only
 
     def step24():
         ctx.ffn24_fwd(dev["X"], dev["W1"], b1, dev["W2"], Y)
@@ -81,7 +81,7 @@ def main() -> int:
     ctx.set_profiling(True)   # event pairs around every kernel, on the launch stream; no synchronisation added
     sec24 = timed(step24, args.warmup, args.steps)
     # per-kernel durations: average over the same number of steps, reading the events after each step
-    k24 = list(range(0, 7 if bwd else 2))
+    k24 = list(range(0, 7 if bwd else 2)) + ([13, 14] if bwd else [13])
     kd = list(range(7, 13 if bwd else 9))
     acc = {k: 0.0 for k in k24 + kd}
     for _ in range(args.steps):
@@ -109,8 +109,10 @@ def main() -> int:
             if name in SPARSE:
                 kernels[name]["tflops_dense_equivalent"] = round(2 * tf, 1)
         else:
-            # feature-wise re-compression: HBM-bound, 4.25 bytes per element of [T, F]
-            gbs = 4.25 * T * F / (ms * 1e-3) / 1e9
+            # streaming kernels: feature-wise re-compression moves 4.25 bytes per element of [T, F]; a transpose pair
+            # reads and writes 2 x 2 bytes per element of its two matrices
+            nbytes = {"featurewise24": 4.25 * T * F, "transpose_weights": 8.0 * D * F, "transpose_acts": 8.0 * T * D}[name]
+            gbs = nbytes / (ms * 1e-3) / 1e9
             kernels[name] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / 8000.0, 4)}
     dom = max((n for n in kernel_ms if n in KERNEL_FLOPS and not n.startswith("dense_")), key=lambda n: kernel_ms[n])
     achieved = KERNEL_FLOPS[dom] * tdf / (kernel_ms[dom] * 1e-3) / 1e12

@@ -57,9 +57,10 @@ typedef enum { FFN24_BF16 = 0, FFN24_FP8_E4M3 = 1 } ffn24_dtype;
 typedef struct ffn24_ctx ffn24_ctx; /* opaque; owns only its device workspace */
 
 /* Create a context for token count T, model dimension D, hidden dimension F.
- * Requires T, D, F to be multiples of 256 (the GEMM tile).  Allocates the device workspace with hipMalloc on the
- * current device: about 1.13 T F bytes, plus 3.13 T F with FFN24_TRAINING, plus 4 T F with FFN24_DENSE, plus
- * 2 T F with FFN24_DEBUG_DUMP_H.  *out is untouched on error. */
+ * Requires T, D, F to be multiples of 256 (the GEMM tile) and at most 2^20.  Allocates the device workspace with
+ * hipMalloc on the current device: about 1.13 T F + 4 D F bytes; plus 3.13 T F + 4 T D with FFN24_TRAINING; plus
+ * 2 T F with FFN24_DENSE (6 T F more when FFN24_TRAINING is set too); plus 2 T F with FFN24_DEBUG_DUMP_H.
+ * *out is untouched on error. */
 FFN24_API int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dtype dtype, int flags);
 
 /* Free the workspace.  The caller must have synchronised every stream that used the context.  NULL is allowed. */
@@ -81,16 +82,16 @@ FFN24_API int sparsify24_featurewise(const void* Hc, const uint8_t* meta, const 
 
 /* C [M][N] = A24 . B on the sparse matrix cores (paper Sec. 1: a 2:4 operand lets the hardware skip half the
  * multiplications; Fig. 2b).  A24 is given compressed along K: values [M][K/2], meta [M][K/8].
- * b_layout 0: B is [K][N];  b_layout 1: B is [N][K].  M, N multiples of 256, K a multiple of 64. */
-FFN24_API int spmm24(const void* values, const uint8_t* meta, const void* B, int b_layout, int64_t M, int64_t N, int64_t K,
-           void* C, void* stream);
+ * B is given transposed, Bt [N][K] (K contiguous, like A).  M, N multiples of 256, K a multiple of 64. */
+FFN24_API int spmm24(const void* values, const uint8_t* meta, const void* Bt, int64_t M, int64_t N, int64_t K, void* C,
+                     void* stream);
 
 /* Forward of the 2:4 FFN (paper Sec. 2):  Z = X W1 + b1;  H = bf16(max(0, Z)^2);  H24 = keep-2-of-4 of H along
  * the hidden features of each token;  Y = H24 W2.
  *   X [T][D], W1 [D][F], b1 [F] fp32 or NULL (the paper's FFN has no bias; b1 only dials the sparsity of synthetic
  *   inputs), W2 [F][D], Y [T][D].
- * Two kernels: dense-MFMA up-projection with the activation and the pruning fused into its epilogue (H is never
- * written densely), then the sparse-MFMA down-projection.  The context keeps (Hc, meta) and the X, W1, W2
+ * Kernels: two weight transposes (every GEMM operand is consumed K-contiguous), the dense-MFMA up-projection with
+ * the activation and the pruning fused into its epilogue (H is never written densely), the sparse-MFMA down-projection.  The context keeps (Hc, meta) and the X, W1, W2
  * pointers for ffn24_bwd; the caller keeps X, W1, W2 alive and unchanged until then. */
 FFN24_API int ffn24_fwd(ffn24_ctx* ctx, const void* X, const void* W1, const float* b1, const void* W2, void* Y, void* stream);
 
@@ -106,7 +107,8 @@ FFN24_API int ffn24_bwd(ffn24_ctx* ctx, const void* dY, void* dX, void* dW1, voi
  * Y = bf16(max(0, X W1 + b1)^2) W2.  Needs FFN24_DENSE. */
 FFN24_API int ffn_fwd(ffn24_ctx* ctx, const void* X, const void* W1, const float* b1, const void* W2, void* Y, void* stream);
 
-/* Backward of the last ffn_fwd: dZ = (dY W2^T) * 2 sqrt(H); dX = dZ W1^T; dW2 = H^T dY; dW1 = X^T dZ. */
+/* Backward of the last ffn_fwd: dZ = (dY W2^T) * 2 sqrt(H); dX = dZ W1^T; dW2 = H^T dY; dW1 = X^T dZ.
+ * Needs FFN24_DENSE | FFN24_TRAINING. */
 FFN24_API int ffn_bwd(ffn24_ctx* ctx, const void* dY, void* dX, void* dW1, void* dW2, void* stream);
 
 /* Device pointers into the workspace, for parity checks.  `which`:
@@ -120,7 +122,8 @@ FFN24_API int ffn24_get_saved(ffn24_ctx* ctx, int which, const void** ptr, int64
  * ffn24_kernel_ms(ctx, k, &ms) waits for kernel k's events of the most recent call and returns its duration.
  * Kernel ids: 0 up-projection+prune, 1 sparse down-projection, 2 dH+derivative, 3 sparse dX, 4 feature-wise
  * re-compression, 5 sparse dW2, 6 sparse dW1, 7..12 the six dense-baseline GEMMs in the same order
- * (up, down, dH, dX, dW2, dW1).  Returns FFN24_ERR_STATE if that kernel has not run with profiling on. */
+ * (up, down, dH, dX, dW2, dW1), 13 the two weight transposes of a forward (W1, W2 -> K-contiguous), 14 the two
+ * activation transposes of a backward (dY, X).  Returns FFN24_ERR_STATE if that kernel has not run with profiling on. */
 FFN24_API int ffn24_set_profiling(ffn24_ctx* ctx, int on);
 FFN24_API int ffn24_kernel_ms(ffn24_ctx* ctx, int kernel, float* ms);
 

@@ -7,8 +7,8 @@
 using namespace ffn24;
 
 namespace {
-constexpr int NUM_KERNELS = 13;
-enum { K_UP = 0, K_DOWN, K_DH, K_DX, K_FW, K_DW2, K_DW1, KD_UP, KD_DOWN, KD_DH, KD_DX, KD_DW2, KD_DW1 };
+constexpr int NUM_KERNELS = 15;
+enum { K_UP = 0, K_DOWN, K_DH, K_DX, K_FW, K_DW2, K_DW1, KD_UP, KD_DOWN, KD_DH, KD_DX, KD_DW2, KD_DW1, K_TR_W, K_TR_ACT };
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 }  // namespace
@@ -19,6 +19,7 @@ struct ffn24_ctx {
   int device;
   // workspace (device)
   void* Hc; uint8_t* meta; void* dZc; void* Hc_t; uint8_t* meta_t; void* dZc_t; void* Hdbg; void* Hd; void* dZd;
+  void* W1t; void* W2t; void* Xt; void* dYt; void* Hd_t; void* dZd_t;   // K-contiguous copies of GEMM operands
   // forward state
   const void *X, *W1, *W2;
   int have_fwd24, have_fwd_dense;
@@ -43,7 +44,8 @@ struct Timed {
 
 int free_all(ffn24_ctx* c) {
   int bad = 0;
-  void* bufs[] = {c->Hc, c->meta, c->dZc, c->Hc_t, c->meta_t, c->dZc_t, c->Hdbg, c->Hd, c->dZd};
+  void* bufs[] = {c->Hc, c->meta, c->dZc, c->Hc_t, c->meta_t, c->dZc_t, c->Hdbg, c->Hd, c->dZd,
+                  c->W1t, c->W2t, c->Xt, c->dYt, c->Hd_t, c->dZd_t};
   for (void* b : bufs) if (b && hipFree(b) != hipSuccess) bad = 1;
   for (int k = 0; k < NUM_KERNELS; k++) for (int j = 0; j < 2; j++) if (c->ev[k][j]) (void)hipEventDestroy(c->ev[k][j]);
   return bad;
@@ -76,17 +78,21 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
   if (!out) return FFN24_ERR_NULL;
   if (dtype != FFN24_BF16) return FFN24_ERR_DTYPE;
   if (T <= 0 || D <= 0 || F <= 0 || T % 256 || D % 256 || F % 256) return FFN24_ERR_SHAPE;
-  if (T > (1 << 24) || D > (1 << 24) || F > (1 << 24)) return FFN24_ERR_SHAPE;
+  if (T > (1 << 20) || D > (1 << 20) || F > (1 << 20)) return FFN24_ERR_SHAPE;
   ffn24_ctx* c = new (std::nothrow) ffn24_ctx();
   if (!c) return FFN24_ERR_HIP;
   c->T = T; c->D = D; c->F = F; c->flags = flags;
   if (hipGetDevice(&c->device) != hipSuccess) { delete c; return FFN24_ERR_HIP; }
-  size_t tf = (size_t)T * (size_t)F;
-  bool ok = hipMalloc(&c->Hc, tf) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->meta), tf / 8) == hipSuccess;
+  size_t tf = (size_t)T * (size_t)F, df = (size_t)D * (size_t)F, td = (size_t)T * (size_t)D;
+  bool ok = hipMalloc(&c->Hc, tf) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->meta), tf / 8) == hipSuccess &&
+            hipMalloc(&c->W1t, 2 * df) == hipSuccess && hipMalloc(&c->W2t, 2 * df) == hipSuccess;
   if (ok && (flags & FFN24_TRAINING))
     ok = hipMalloc(&c->dZc, tf) == hipSuccess && hipMalloc(&c->Hc_t, tf) == hipSuccess &&
-         hipMalloc(reinterpret_cast<void**>(&c->meta_t), tf / 8) == hipSuccess && hipMalloc(&c->dZc_t, tf) == hipSuccess;
-  if (ok && (flags & FFN24_DENSE)) ok = hipMalloc(&c->Hd, 2 * tf) == hipSuccess && hipMalloc(&c->dZd, 2 * tf) == hipSuccess;
+         hipMalloc(reinterpret_cast<void**>(&c->meta_t), tf / 8) == hipSuccess && hipMalloc(&c->dZc_t, tf) == hipSuccess &&
+         hipMalloc(&c->Xt, 2 * td) == hipSuccess && hipMalloc(&c->dYt, 2 * td) == hipSuccess;
+  if (ok && (flags & FFN24_DENSE)) ok = hipMalloc(&c->Hd, 2 * tf) == hipSuccess;
+  if (ok && (flags & FFN24_DENSE) && (flags & FFN24_TRAINING))
+    ok = hipMalloc(&c->dZd, 2 * tf) == hipSuccess && hipMalloc(&c->Hd_t, 2 * tf) == hipSuccess && hipMalloc(&c->dZd_t, 2 * tf) == hipSuccess;
   if (ok && (flags & FFN24_DEBUG_DUMP_H)) ok = hipMalloc(&c->Hdbg, 2 * tf) == hipSuccess;
   for (int k = 0; ok && k < NUM_KERNELS; k++)
     for (int j = 0; ok && j < 2; j++) ok = hipEventCreate(&c->ev[k][j]) == hipSuccess;
@@ -147,7 +153,7 @@ int sparsify24(const void* H, int64_t rows, int64_t cols, ffn24_dtype dtype, voi
 
 int sparsify24_featurewise(const void* Hc, const uint8_t* meta, const void* dZc, int64_t T, int64_t F,
                            void* Hc_t, uint8_t* meta_t, void* dZc_t, void* stream) {
-  if (T <= 0 || F <= 0 || T % 128 || F % 64 || T > (1 << 24) || F > (1 << 24)) return FFN24_ERR_SHAPE;
+  if (T <= 0 || F <= 0 || T % 128 || F % 64 || T > (1 << 20) || F > (1 << 20)) return FFN24_ERR_SHAPE;
   if (!Hc || !meta || !Hc_t || !meta_t) return FFN24_ERR_NULL;
   if ((dZc == nullptr) != (dZc_t == nullptr)) return FFN24_ERR_NULL;
   if (misaligned(Hc) || misaligned(meta) || misaligned(Hc_t) || misaligned(meta_t) || misaligned(dZc) || misaligned(dZc_t))
@@ -155,13 +161,11 @@ int sparsify24_featurewise(const void* Hc, const uint8_t* meta, const void* dZc,
   return launch_featurewise24(Hc, meta, dZc, (int)T, (int)F, Hc_t, meta_t, dZc_t, static_cast<hipStream_t>(stream)) ? FFN24_ERR_HIP : FFN24_OK;
 }
 
-int spmm24(const void* values, const uint8_t* meta, const void* B, int b_layout, int64_t M, int64_t N, int64_t K,
-           void* C, void* stream) {
-  if (M <= 0 || N <= 0 || K <= 0 || M % 256 || N % 256 || K % 64 || M > (1 << 24) || N > (1 << 24) || K > (1 << 24)) return FFN24_ERR_SHAPE;
-  if (b_layout != 0 && b_layout != 1) return FFN24_ERR_SHAPE;
-  int rc = check_ptrs({values, meta, B, C});
+int spmm24(const void* values, const uint8_t* meta, const void* Bt, int64_t M, int64_t N, int64_t K, void* C, void* stream) {
+  if (M <= 0 || N <= 0 || K <= 0 || M % 256 || N % 256 || K % 64 || M > (1 << 20) || N > (1 << 20) || K > (1 << 20)) return FFN24_ERR_SHAPE;
+  int rc = check_ptrs({values, meta, Bt, C});
   if (rc) return rc;
-  return launch_sp_rowmajor(values, meta, B, b_layout, (int)M, (int)N, (int)K, C, static_cast<hipStream_t>(stream)) ? FFN24_ERR_HIP : FFN24_OK;
+  return launch_sp_rowmajor(values, meta, Bt, (int)M, (int)N, (int)K, C, static_cast<hipStream_t>(stream)) ? FFN24_ERR_HIP : FFN24_OK;
 }
 
 int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const void* W2, void* Y, void* stream) {
@@ -172,8 +176,11 @@ int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, cons
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   c->have_fwd24 = 0;
-  { Timed t(c, K_UP, s);   if (t.done(launch_up_prune24(W1, X, b1, T, D, F, c->Hc, c->meta, c->Hdbg, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, K_DOWN, s); if (t.done(launch_sp_rowmajor(c->Hc, c->meta, W2, 0, T, D, F, Y, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_TR_W, s);
+    int rc1 = launch_transpose(W1, D, F, c->W1t, s);
+    if (t.done(rc1 ? rc1 : launch_transpose(W2, F, D, c->W2t, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_UP, s);   if (t.done(launch_up_prune24(c->W1t, X, b1, T, D, F, c->Hc, c->meta, c->Hdbg, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_DOWN, s); if (t.done(launch_sp_rowmajor(c->Hc, c->meta, c->W2t, T, D, F, Y, s))) return FFN24_ERR_HIP; }
   c->X = X; c->W1 = W1; c->W2 = W2; c->have_fwd24 = 1;
   return FFN24_OK;
 }
@@ -186,10 +193,13 @@ int ffn24_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   { Timed t(c, K_DH, s);  if (t.done(launch_dh_gather(c->W2, dY, c->Hc, c->meta, T, D, F, c->dZc, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, K_DX, s);  if (t.done(launch_sp_rowmajor(c->dZc, c->meta, c->W1, 1, T, D, F, dX, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_DX, s);  if (t.done(launch_sp_rowmajor(c->dZc, c->meta, c->W1, T, D, F, dX, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_FW, s);  if (t.done(launch_featurewise24(c->Hc, c->meta, c->dZc, T, F, c->Hc_t, c->meta_t, c->dZc_t, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, K_DW2, s); if (t.done(launch_sp_rowmajor(c->Hc_t, c->meta_t, dY, 0, F, D, T, dW2, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, K_DW1, s); if (t.done(launch_sp_nc_colmajor(c->dZc_t, c->meta_t, c->X, F, D, T, dW1, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_TR_ACT, s);
+    int rc1 = launch_transpose(dY, T, D, c->dYt, s);
+    if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_DW2, s); if (t.done(launch_sp_rowmajor(c->Hc_t, c->meta_t, c->dYt, F, D, T, dW2, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_DW1, s); if (t.done(launch_sp_colmajor(c->dZc_t, c->meta_t, c->Xt, F, D, T, dW1, s))) return FFN24_ERR_HIP; }
   return FFN24_OK;
 }
 
@@ -202,23 +212,29 @@ int ffn_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const 
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   c->have_fwd_dense = 0;
-  { Timed t(c, KD_UP, s);   if (t.done(launch_up_relu2(W1, X, b1, T, D, F, c->Hd, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, KD_DOWN, s); if (t.done(launch_kc_nc_rowmajor(c->Hd, W2, T, D, F, Y, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_TR_W, s);
+    int rc1 = launch_transpose(W1, D, F, c->W1t, s);
+    if (t.done(rc1 ? rc1 : launch_transpose(W2, F, D, c->W2t, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_UP, s);   if (t.done(launch_up_relu2(c->W1t, X, b1, T, D, F, c->Hd, c->Hd_t, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_DOWN, s); if (t.done(launch_dense_rowmajor(c->Hd, c->W2t, T, D, F, Y, s))) return FFN24_ERR_HIP; }
   c->X = X; c->W1 = W1; c->W2 = W2; c->have_fwd_dense = 1;
   return FFN24_OK;
 }
 
 int ffn_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void* stream) {
   if (!c) return FFN24_ERR_NULL;
-  if (!(c->flags & FFN24_DENSE) || !c->have_fwd_dense) return FFN24_ERR_STATE;
+  if (!(c->flags & FFN24_DENSE) || !(c->flags & FFN24_TRAINING) || !c->have_fwd_dense) return FFN24_ERR_STATE;
   int rc = check_ptrs({dY, dX, dW1, dW2});
   if (rc) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
-  { Timed t(c, KD_DH, s);  if (t.done(launch_dh_drelu(c->W2, dY, c->Hd, T, D, F, c->dZd, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, KD_DX, s);  if (t.done(launch_kc_kc_rowmajor(c->dZd, c->W1, T, D, F, dX, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, KD_DW2, s); if (t.done(launch_mc_nc_rowmajor(c->Hd, dY, F, D, T, dW2, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, KD_DW1, s); if (t.done(launch_mc_nc_colmajor(c->dZd, c->X, F, D, T, dW1, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_DH, s);  if (t.done(launch_dh_drelu(c->W2, dY, c->Hd, T, D, F, c->dZd, c->dZd_t, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_DX, s);  if (t.done(launch_dense_rowmajor(c->dZd, c->W1, T, D, F, dX, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_TR_ACT, s);
+    int rc1 = launch_transpose(dY, T, D, c->dYt, s);
+    if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_DW2, s); if (t.done(launch_dense_rowmajor(c->Hd_t, c->dYt, F, D, T, dW2, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_DW1, s); if (t.done(launch_dense_colmajor(c->dZd_t, c->Xt, F, D, T, dW1, s))) return FFN24_ERR_HIP; }
   return FFN24_OK;
 }
 

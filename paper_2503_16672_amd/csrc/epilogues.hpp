@@ -42,9 +42,10 @@ struct EpiColMajor {
 };
 
 // Dense FFN up-projection epilogue (Sec. 1, Squared ReLU): rows m are features, columns n are tokens;
-// H[t][f] = bf16( max(0, acc + b1[f])^2 ), stored [T][F].
+// H[t][f] = bf16( max(0, acc + b1[f])^2 ), stored [T][F]; if Ht is given the same values are also stored [F][T]
+// (the operand layout the dense weight-gradient GEMM reduces over).
 struct EpiRelu2 {
-  struct Args { __bf16* H; const float* b1; int F; };
+  struct Args { __bf16* H; __bf16* Ht; const float* b1; int F; int T; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
 #pragma unroll
     for (int mi = 0; mi < 4; mi++) {
@@ -53,17 +54,27 @@ struct EpiRelu2 {
       for (int v = 0; v < 16; v++) bias[v] = e.b1 ? e.b1[m_lane + 16 * mi + v] : 0.f;
 #pragma unroll
       for (int ni = 0; ni < 4; ni++) {
+#pragma unroll
+        for (int v = 0; v < 16; v++) {
+          float r = fmaxf(acc[mi][ni][v] + bias[v], 0.f);
+          acc[mi][ni][v] = r * r;
+        }
         __bf16* row = e.H + (size_t)(n_lane + ni) * e.F + m_lane + 16 * mi;
 #pragma unroll
         for (int q = 0; q < 2; q++) {
           u32x4 o;
 #pragma unroll
-          for (int d = 0; d < 4; d++) {
-            float r0 = fmaxf(acc[mi][ni][8 * q + 2 * d] + bias[8 * q + 2 * d], 0.f);
-            float r1 = fmaxf(acc[mi][ni][8 * q + 2 * d + 1] + bias[8 * q + 2 * d + 1], 0.f);
-            o[d] = pack_bf16x2(r0 * r0, r1 * r1);
-          }
+          for (int d = 0; d < 4; d++) o[d] = pack_bf16x2(acc[mi][ni][8 * q + 2 * d], acc[mi][ni][8 * q + 2 * d + 1]);
           *reinterpret_cast<u32x4*>(row + 8 * q) = o;
+        }
+      }
+      if (e.Ht) {
+#pragma unroll
+        for (int v = 0; v < 16; v++) {
+          u32x2 o;
+          o[0] = pack_bf16x2(acc[mi][0][v], acc[mi][1][v]);
+          o[1] = pack_bf16x2(acc[mi][2][v], acc[mi][3][v]);
+          *reinterpret_cast<u32x2*>(e.Ht + (size_t)(m_lane + 16 * mi + v) * e.T + n_lane) = o;
         }
       }
     }
@@ -125,13 +136,14 @@ struct EpiPrune24 {
 
 // Dense backward, pointwise part: rows m are features, columns n are tokens; acc = dH[t][f];
 // dZ[t][f] = bf16( acc * 2 sqrt(H[t][f]) )  (derivative of max(0,z)^2 is 2 max(0,z) = 2 sqrt(h)).
+// Stored [T][F] and, for the weight-gradient GEMM that reduces over tokens, also [F][T].
 struct EpiDRelu {
-  struct Args { const __bf16* H; __bf16* dZ; int F; };
+  struct Args { const __bf16* H; __bf16* dZ; __bf16* dZt; int F; int T; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
 #pragma unroll
-    for (int ni = 0; ni < 4; ni++)
+    for (int mi = 0; mi < 4; mi++) {
 #pragma unroll
-      for (int mi = 0; mi < 4; mi++) {
+      for (int ni = 0; ni < 4; ni++) {
         size_t o = (size_t)(n_lane + ni) * e.F + m_lane + 16 * mi;
 #pragma unroll
         for (int q = 0; q < 2; q++) {
@@ -141,11 +153,23 @@ struct EpiDRelu {
           for (int d = 0; d < 4; d++) {
             float g0 = 2.f * __builtin_amdgcn_sqrtf(bf16_lo_to_f32(h[d]));
             float g1 = 2.f * __builtin_amdgcn_sqrtf(bf16_hi_to_f32(h[d]));
-            r[d] = pack_bf16x2(acc[mi][ni][8 * q + 2 * d] * g0, acc[mi][ni][8 * q + 2 * d + 1] * g1);
+            acc[mi][ni][8 * q + 2 * d] *= g0;
+            acc[mi][ni][8 * q + 2 * d + 1] *= g1;
+            r[d] = pack_bf16x2(acc[mi][ni][8 * q + 2 * d], acc[mi][ni][8 * q + 2 * d + 1]);
           }
           *reinterpret_cast<u32x4*>(e.dZ + o + 8 * q) = r;
         }
       }
+      if (e.dZt) {
+#pragma unroll
+        for (int v = 0; v < 16; v++) {
+          u32x2 o;
+          o[0] = pack_bf16x2(acc[mi][0][v], acc[mi][1][v]);
+          o[1] = pack_bf16x2(acc[mi][2][v], acc[mi][3][v]);
+          *reinterpret_cast<u32x2*>(e.dZt + (size_t)(m_lane + 16 * mi + v) * e.T + n_lane) = o;
+        }
+      }
+    }
   }
 };
 

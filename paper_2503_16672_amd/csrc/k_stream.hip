@@ -1,5 +1,6 @@
-// Streaming (HBM-bound) kernels: the standalone 2:4 compression of an activation matrix, and the
-// feature-wise (along-token) re-compression the weight-gradient GEMMs need.
+// Streaming (HBM-bound) kernels: the standalone 2:4 compression of an activation matrix, the feature-wise
+// (along-token) re-compression the weight-gradient GEMMs need, and the bf16 matrix transpose that brings a GEMM
+// operand into K-contiguous form.
 #include "gemm_core.hpp"
 #include "launch.hpp"
 
@@ -128,6 +129,42 @@ int launch_featurewise24(const void* Hc, const uint8_t* meta, const void* dZc, i
   dim3 grid(F / FW_FEAT, T / FW_TOK);
   hipLaunchKernelGGL(featurewise24_kernel, grid, dim3(256), 0, s, static_cast<const uint16_t*>(Hc), meta,
                      static_cast<const uint16_t*>(dZc), T, F, static_cast<uint16_t*>(Hc_t), meta_t, static_cast<uint16_t*>(dZc_t));
+  return (int)hipGetLastError();
+}
+
+// out[c][r] = in[r][c] for a bf16 matrix [R][C], R and C multiples of 64.  One workgroup per 64x64 tile: rows are
+// read 128 bytes at a time, scattered into an LDS tile with a 132-byte pitch (conflict-free for this pattern), and
+// written out as 128-byte rows of the transposed matrix.
+constexpr int TR_LD = 66;
+
+__global__ void __launch_bounds__(256) transpose_kernel(const uint16_t* __restrict__ in, int R, int C, uint16_t* __restrict__ out) {
+  __shared__ __attribute__((aligned(16))) uint16_t sT[64 * TR_LD];
+  int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  int tid = threadIdx.x;
+  int ch = tid & 7, rr = tid >> 3;
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+    int r = rr + 32 * i;
+    u32x4 v = *reinterpret_cast<const u32x4*>(in + (size_t)(r0 + r) * C + c0 + 8 * ch);
+#pragma unroll
+    for (int d = 0; d < 4; d++) {
+      sT[(8 * ch + 2 * d) * TR_LD + r] = (uint16_t)(v[d] & 0xFFFFu);
+      sT[(8 * ch + 2 * d + 1) * TR_LD + r] = (uint16_t)(v[d] >> 16);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+    int c = rr + 32 * i;
+    const uint32_t* src = reinterpret_cast<const uint32_t*>(&sT[c * TR_LD + 8 * ch]);
+    u32x4 v = {src[0], src[1], src[2], src[3]};
+    *reinterpret_cast<u32x4*>(out + (size_t)(c0 + c) * R + r0 + 8 * ch) = v;
+  }
+}
+
+int launch_transpose(const void* in, int R, int C, void* out, hipStream_t s) {
+  dim3 grid(C / 64, R / 64);
+  hipLaunchKernelGGL(transpose_kernel, grid, dim3(256), 0, s, static_cast<const uint16_t*>(in), R, C, static_cast<uint16_t*>(out));
   return (int)hipGetLastError();
 }
 

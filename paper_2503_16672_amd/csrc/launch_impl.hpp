@@ -5,10 +5,10 @@
 
 namespace ffn24 {
 
-template <int AMODE, int BMODE, class Epi>
+template <bool SPARSE, class Epi>
 static int launch_gemm(const GemmArgs& g, const typename Epi::Args& ea, hipStream_t s) {
-  auto kern = gemm_kernel<AMODE, BMODE, Epi>;
-  constexpr int lds = lds_total_bytes(AMODE);
+  auto kern = gemm_kernel<SPARSE, Epi>;
+  constexpr int lds = Geo<SPARSE>::LDS_TOTAL;
   // the opt-in for more than 64 KiB of dynamic LDS is per device; keep one flag per device
   static bool configured[64] = {};
   int dev = 0;

@@ -26,7 +26,7 @@ EXPORTS = (
 )
 
 KERNEL_NAMES = ("up_prune24", "down_sp", "dh_gather", "dx_sp", "featurewise24", "dw2_sp", "dw1_sp",
-                "dense_up", "dense_down", "dense_dh", "dense_dx", "dense_dw2", "dense_dw1")
+                "dense_up", "dense_down", "dense_dh", "dense_dx", "dense_dw2", "dense_dw1", "transpose_weights", "transpose_acts")
 
 _lib = None
 
@@ -49,7 +49,7 @@ def lib() -> ctypes.CDLL:
         L.ffn24_ctx_destroy.argtypes = [vp]
         L.sparsify24.argtypes = [vp, i64, i64, ci, vp, vp, vp]
         L.sparsify24_featurewise.argtypes = [vp, vp, vp, i64, i64, vp, vp, vp, vp]
-        L.spmm24.argtypes = [vp, vp, vp, ci, i64, i64, i64, vp, vp]
+        L.spmm24.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp]
         L.ffn24_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp]
         L.ffn24_bwd.argtypes = [vp, vp, vp, vp, vp, vp]
         L.ffn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp]
@@ -120,12 +120,12 @@ def sparsify24_featurewise(Hc: torch.Tensor, meta: torch.Tensor, dZc: torch.Tens
     return Hc_t, meta_t, dZc_t
 
 
-def spmm24(values: torch.Tensor, meta: torch.Tensor, B: torch.Tensor, b_layout: int = 0) -> torch.Tensor:
-    """C [M,N] = A24 . B with A24 given as (values [M,K/2], meta [M,K/8]); B is [K,N] (layout 0) or [N,K] (layout 1)."""
+def spmm24(values: torch.Tensor, meta: torch.Tensor, Bt: torch.Tensor) -> torch.Tensor:
+    """C [M,N] = A24 . B with A24 given as (values [M,K/2], meta [M,K/8]) and B given transposed, Bt [N,K]."""
     M, K = values.shape[0], values.shape[1] * 2
-    N = B.shape[1] if b_layout == 0 else B.shape[0]
+    N = Bt.shape[0]
     C = torch.empty((M, N), dtype=torch.bfloat16, device=values.device)
-    _check(lib().spmm24(_ptr(values), _ptr(meta), _ptr(B), b_layout, M, N, K, _ptr(C), _stream()), "spmm24")
+    _check(lib().spmm24(_ptr(values), _ptr(meta), _ptr(Bt), M, N, K, _ptr(C), _stream()), "spmm24")
     return C
 
 

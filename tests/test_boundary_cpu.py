@@ -51,10 +51,10 @@ def test_argument_validation_without_gpu():
     assert L.sparsify24(a16, 4, 16, 1, a16, a16, None) == -4
     assert L.sparsify24(None, 0, 16, 0, None, None, None) == 0
     # spmm24 shape rules
-    assert L.spmm24(a16, a16, a16, 0, 256, 256, 32, a16, None) == -2
-    assert L.spmm24(a16, a16, a16, 0, 100, 256, 64, a16, None) == -2
-    assert L.spmm24(a16, a16, a16, 2, 256, 256, 64, a16, None) == -2
-    assert L.spmm24(None, a16, a16, 0, 256, 256, 64, a16, None) == -1
+    assert L.spmm24(a16, a16, a16, 256, 256, 32, a16, None) == -2
+    assert L.spmm24(a16, a16, a16, 100, 256, 64, a16, None) == -2
+    assert L.spmm24(a16, a16, a16 + 8, 256, 256, 64, a16, None) == -3
+    assert L.spmm24(None, a16, a16, 256, 256, 64, a16, None) == -1
     # feature-wise
     assert L.sparsify24_featurewise(a16, a16, None, 100, 64, a16, a16, None, None) == -2
     assert L.sparsify24_featurewise(a16, a16, a16, 128, 64, a16, a16, None, None) == -1
