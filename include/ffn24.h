@@ -111,11 +111,15 @@ FFN24_API int ffn_fwd(ffn24_ctx* ctx, const void* X, const void* W1, const float
  * Needs FFN24_DENSE | FFN24_TRAINING. */
 FFN24_API int ffn_bwd(ffn24_ctx* ctx, const void* dY, void* dX, void* dW1, void* dW2, void* stream);
 
-/* Device pointers into the workspace, for parity checks.  `which`:
+/* Copies of the context's saved tensors, for parity checks.  `which`:
  *   0 Hc [T][F/2]   1 meta [T][F/8]   2 dZc [T][F/2]   3 Hc_t [F][T/2]   4 meta_t [F][T/8]   5 dZc_t [F][T/2]
  *   6 pre-prune H dump [T][F] (FFN24_DEBUG_DUMP_H)   7 dense H [T][F]   8 dense dZ [T][F]
- * *ptr is NULL if the context was created without the flag that owns the buffer. */
-FFN24_API int ffn24_get_saved(ffn24_ctx* ctx, int which, const void** ptr, int64_t* nbytes);
+ * ffn24_saved_bytes gives the size of tensor `which`; ffn24_copy_saved enqueues a copy of it into dst (device memory
+ * of exactly that size, 16-byte aligned) in the row-major compressed form described at the top -- inside the context
+ * the compressed tensors are kept in a tiled order that the sparse GEMM streams faster.  Returns FFN24_ERR_STATE if
+ * the context was created without the flag that owns the tensor, FFN24_ERR_SHAPE on a size mismatch. */
+FFN24_API int ffn24_saved_bytes(ffn24_ctx* ctx, int which, int64_t* nbytes);
+FFN24_API int ffn24_copy_saved(ffn24_ctx* ctx, int which, void* dst, int64_t dst_bytes, void* stream);
 
 /* Per-kernel timing with HIP events recorded on the stream each kernel is launched on.
  * ffn24_set_profiling(ctx, 1) makes every later call bracket each of its kernels with an event pair;

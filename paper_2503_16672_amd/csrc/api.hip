@@ -123,22 +123,43 @@ int ffn24_kernel_ms(ffn24_ctx* c, int k, float* ms) {
   return FFN24_OK;
 }
 
-int ffn24_get_saved(ffn24_ctx* c, int which, const void** ptr, int64_t* nbytes) {
-  if (!c || !ptr || !nbytes) return FFN24_ERR_NULL;
+int ffn24_saved_bytes(ffn24_ctx* c, int which, int64_t* nbytes) {
+  if (!c || !nbytes) return FFN24_ERR_NULL;
   int64_t tf = c->T * c->F;
   switch (which) {
-    case 0: *ptr = c->Hc; *nbytes = tf; break;
-    case 1: *ptr = c->meta; *nbytes = tf / 8; break;
-    case 2: *ptr = c->dZc; *nbytes = tf; break;
-    case 3: *ptr = c->Hc_t; *nbytes = tf; break;
-    case 4: *ptr = c->meta_t; *nbytes = tf / 8; break;
-    case 5: *ptr = c->dZc_t; *nbytes = tf; break;
-    case 6: *ptr = c->Hdbg; *nbytes = 2 * tf; break;
-    case 7: *ptr = c->Hd; *nbytes = 2 * tf; break;
-    case 8: *ptr = c->dZd; *nbytes = 2 * tf; break;
+    case 0: case 2: case 3: case 5: *nbytes = tf; break;
+    case 1: case 4: *nbytes = tf / 8; break;
+    case 6: case 7: case 8: *nbytes = 2 * tf; break;
     default: return FFN24_ERR_SHAPE;
   }
   return FFN24_OK;
+}
+
+int ffn24_copy_saved(ffn24_ctx* c, int which, void* dst, int64_t dst_bytes, void* stream) {
+  if (!c || !dst) return FFN24_ERR_NULL;
+  if (misaligned(dst)) return FFN24_ERR_ALIGN;
+  int64_t need = 0;
+  int rc = ffn24_saved_bytes(c, which, &need);
+  if (rc) return rc;
+  if (dst_bytes != need) return FFN24_ERR_SHAPE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int T = (int)c->T, F = (int)c->F;
+  const void* src = nullptr;
+  int rows = 0, K = 0, piece = 0;   // piece != 0: the buffer is in panel form
+  switch (which) {
+    case 0: src = c->Hc; rows = T; K = F; piece = 64; break;
+    case 1: src = c->meta; rows = T; K = F; piece = 8; break;
+    case 2: src = c->dZc; rows = T; K = F; piece = 64; break;
+    case 3: src = c->Hc_t; rows = F; K = T; piece = 64; break;
+    case 4: src = c->meta_t; rows = F; K = T; piece = 8; break;
+    case 5: src = c->dZc_t; rows = F; K = T; piece = 64; break;
+    case 6: src = c->Hdbg; break;
+    case 7: src = c->Hd; break;
+    default: src = c->dZd; break;
+  }
+  if (!src) return FFN24_ERR_STATE;
+  if (piece) return launch_unpanel(src, rows, K, piece, dst, s) ? FFN24_ERR_HIP : FFN24_OK;
+  return hipMemcpyAsync(dst, src, (size_t)need, hipMemcpyDeviceToDevice, s) == hipSuccess ? FFN24_OK : FFN24_ERR_HIP;
 }
 
 int sparsify24(const void* H, int64_t rows, int64_t cols, ffn24_dtype dtype, void* values, uint8_t* meta, void* stream) {
@@ -158,14 +179,14 @@ int sparsify24_featurewise(const void* Hc, const uint8_t* meta, const void* dZc,
   if ((dZc == nullptr) != (dZc_t == nullptr)) return FFN24_ERR_NULL;
   if (misaligned(Hc) || misaligned(meta) || misaligned(Hc_t) || misaligned(meta_t) || misaligned(dZc) || misaligned(dZc_t))
     return FFN24_ERR_ALIGN;
-  return launch_featurewise24(Hc, meta, dZc, (int)T, (int)F, Hc_t, meta_t, dZc_t, static_cast<hipStream_t>(stream)) ? FFN24_ERR_HIP : FFN24_OK;
+  return launch_featurewise24(Hc, meta, dZc, (int)T, (int)F, Hc_t, meta_t, dZc_t, 0, static_cast<hipStream_t>(stream)) ? FFN24_ERR_HIP : FFN24_OK;
 }
 
 int spmm24(const void* values, const uint8_t* meta, const void* Bt, int64_t M, int64_t N, int64_t K, void* C, void* stream) {
   if (M <= 0 || N <= 0 || K <= 0 || M % 256 || N % 256 || K % 64 || M > (1 << 20) || N > (1 << 20) || K > (1 << 20)) return FFN24_ERR_SHAPE;
   int rc = check_ptrs({values, meta, Bt, C});
   if (rc) return rc;
-  return launch_sp_rowmajor(values, meta, Bt, (int)M, (int)N, (int)K, C, static_cast<hipStream_t>(stream)) ? FFN24_ERR_HIP : FFN24_OK;
+  return launch_sp_rowmajor(values, meta, 0, Bt, (int)M, (int)N, (int)K, C, static_cast<hipStream_t>(stream)) ? FFN24_ERR_HIP : FFN24_OK;
 }
 
 int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const void* W2, void* Y, void* stream) {
@@ -180,7 +201,7 @@ int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, cons
     int rc1 = launch_transpose(W1, D, F, c->W1t, s);
     if (t.done(rc1 ? rc1 : launch_transpose(W2, F, D, c->W2t, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_UP, s);   if (t.done(launch_up_prune24(c->W1t, X, b1, T, D, F, c->Hc, c->meta, c->Hdbg, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, K_DOWN, s); if (t.done(launch_sp_rowmajor(c->Hc, c->meta, c->W2t, T, D, F, Y, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_DOWN, s); if (t.done(launch_sp_rowmajor(c->Hc, c->meta, 1, c->W2t, T, D, F, Y, s))) return FFN24_ERR_HIP; }
   c->X = X; c->W1 = W1; c->W2 = W2; c->have_fwd24 = 1;
   return FFN24_OK;
 }
@@ -193,13 +214,13 @@ int ffn24_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   { Timed t(c, K_DH, s);  if (t.done(launch_dh_gather(c->W2, dY, c->Hc, c->meta, T, D, F, c->dZc, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, K_DX, s);  if (t.done(launch_sp_rowmajor(c->dZc, c->meta, c->W1, T, D, F, dX, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, K_FW, s);  if (t.done(launch_featurewise24(c->Hc, c->meta, c->dZc, T, F, c->Hc_t, c->meta_t, c->dZc_t, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_DX, s);  if (t.done(launch_sp_rowmajor(c->dZc, c->meta, 1, c->W1, T, D, F, dX, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_FW, s);  if (t.done(launch_featurewise24(c->Hc, c->meta, c->dZc, T, F, c->Hc_t, c->meta_t, c->dZc_t, 1, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_TR_ACT, s);
     int rc1 = launch_transpose(dY, T, D, c->dYt, s);
     if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, K_DW2, s); if (t.done(launch_sp_rowmajor(c->Hc_t, c->meta_t, c->dYt, F, D, T, dW2, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, K_DW1, s); if (t.done(launch_sp_colmajor(c->dZc_t, c->meta_t, c->Xt, F, D, T, dW1, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_DW2, s); if (t.done(launch_sp_rowmajor(c->Hc_t, c->meta_t, 1, c->dYt, F, D, T, dW2, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_DW1, s); if (t.done(launch_sp_colmajor(c->dZc_t, c->meta_t, 1, c->Xt, F, D, T, dW1, s))) return FFN24_ERR_HIP; }
   return FFN24_OK;
 }
 

@@ -85,8 +85,10 @@ struct EpiRelu2 {
 // h = bf16(max(0, acc + b1)^2); of every 4 consecutive features of a token keep the 2 largest
 // (ties -> lower index); write the kept pair and its metadata nibble.  The 4 members of a group are the
 // accumulator registers 4a..4a+3 of one MFMA tile, so the pick needs no cross-lane traffic.
-//   Hc   [T][F/2]  kept values, position order        meta [T][F/8]  nibble i0 | i1<<2, even group low
-//   Hdbg [T][F]    optional: the rounded activation before pruning (parity checks)
+//   Hc, meta: the compressed activation [T][F/2] + [T][F/8] in panel form (gemm_core.hpp): a lane's 64 features of
+//   one token are exactly one piece, 64 bytes of kept values (position order) + 8 metadata bytes (nibble
+//   i0 | i1<<2, even group low).
+//   Hdbg [T][F]    optional, row-major: the rounded activation before pruning (parity checks)
 struct EpiPrune24 {
   struct Args { __bf16* Hc; uint8_t* meta; __bf16* Hdbg; const float* b1; int F; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
@@ -125,11 +127,12 @@ struct EpiPrune24 {
           nib[gi >> 3] |= n4 << (4 * (gi & 7));
         }
       }
-      __bf16* hrow = e.Hc + t * (size_t)(e.F / 2) + m_lane / 2;
+      size_t piece = a24_piece((int)t, m_lane >> 6, e.F >> 6);
+      __bf16* hrow = e.Hc + piece * 32;
 #pragma unroll
       for (int q = 0; q < 4; q++)
         *reinterpret_cast<u32x4*>(hrow + 8 * q) = u32x4{vals[4 * q], vals[4 * q + 1], vals[4 * q + 2], vals[4 * q + 3]};
-      *reinterpret_cast<u32x2*>(e.meta + t * (size_t)(e.F / 8) + m_lane / 8) = u32x2{nib[0], nib[1]};
+      *reinterpret_cast<u32x2*>(e.meta + piece * 8) = u32x2{nib[0], nib[1]};
     }
   }
 };
@@ -175,16 +178,17 @@ struct EpiDRelu {
 
 // 2:4 backward, pointwise part (Fig. 4 caption; Sec. 2, last paragraph): acc = dH[t][f]; on the positions
 // the forward kept, dZ = dH * 2 sqrt(h); elsewhere dZ = 0 and nothing is stored.  Output is compressed with
-// the forward's metadata: dZc [T][F/2].
+// the forward's metadata: dZc [T][F/2].  Hc, meta and dZc are in panel form: one piece per lane and token.
 struct EpiDGather {
   struct Args { const __bf16* Hc; const uint8_t* meta; __bf16* dZc; int F; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
 #pragma unroll
     for (int ni = 0; ni < 4; ni++) {
       size_t t = (size_t)(n_lane + ni);
-      const __bf16* hrow = e.Hc + t * (size_t)(e.F / 2) + m_lane / 2;
-      u32x2 mt = *reinterpret_cast<const u32x2*>(e.meta + t * (size_t)(e.F / 8) + m_lane / 8);
-      __bf16* zrow = e.dZc + t * (size_t)(e.F / 2) + m_lane / 2;
+      size_t piece = a24_piece((int)t, m_lane >> 6, e.F >> 6);
+      const __bf16* hrow = e.Hc + piece * 32;
+      u32x2 mt = *reinterpret_cast<const u32x2*>(e.meta + piece * 8);
+      __bf16* zrow = e.dZc + piece * 32;
 #pragma unroll
       for (int mi = 0; mi < 4; mi++) {
         u32x4 h = *reinterpret_cast<const u32x4*>(hrow + 8 * mi);

@@ -14,6 +14,13 @@
 // i0 | i1<<2 per group, even group in the low nibble) is exactly the index word the sparse MFMA consumes: a lane's
 // 8 stored values of one instruction take 16 consecutive metadata bits, selected from a 32-bit register by ABID.
 //
+// Panel form of a 2:4 operand.  The compressed operands that the library produces for itself (never the ones a
+// caller hands in) are stored by pieces: piece (r, kp) = the 32 stored values (64 bytes) and the 8 metadata bytes of
+// row r for the dense k range [64 kp, 64 kp + 64), at piece index ((r / 256) * (K / 64) + kp) * 256 + r % 256.
+// The 256 rows x 64 k that a block tile consumes per stage are then one contiguous 16 KiB (+ 2 KiB) run, fetched as
+// full 128-byte lines, instead of 256 pieces of 64 (8) bytes that are a whole matrix row apart.  Measured: the
+// sparse GEMM is bound by its global->LDS stream, and the 8-byte metadata pieces alone cost it 17 %.
+//
 // Data movement.  Global memory goes straight to LDS (global_load_lds_dwordx4: no VGPR staging, no LDS store
 // instructions) into a ring of stage buffers, 2-3 stages ahead of the math, so that L2/HBM latency is covered:
 //   dense : stage = 32 k  (A 16 KiB + B 16 KiB), ring of 4  -> 128 KiB of the CU's 160 KiB LDS
@@ -62,7 +69,13 @@ struct GemmArgs {
   const uint8_t* Ameta;  // sparse only: [M][K/8]
   const void* B;         // [N][K]
   int M, N, K;           // K is the dense reduction length
+  int a_panel;           // sparse only: values and metadata are in panel form (see above) instead of row-major
 };
+
+// piece index of row r, 64-k panel kp, for an operand with `npanels` = K / 64 panels per row
+__host__ __device__ __forceinline__ size_t a24_piece(int r, int kp, int npanels) {
+  return ((size_t)(r >> 8) * npanels + kp) * 256 + (r & 255);
+}
 
 template <bool SPARSE>
 struct Geo {
@@ -119,6 +132,7 @@ struct Dma {
   const char* am;     // metadata
   const char* b;
   uint32_t va[4], vm[2], vb[SPARSE ? 8 : 4];   // per-lane byte offsets from the uniform bases
+  uint32_t a_stage, m_stage;                   // bytes from one stage to the next in the A values / metadata stream
   int wave;
 
   __device__ __forceinline__ void init(const GemmArgs& g, int m0, int n0, int tid) {
@@ -128,11 +142,16 @@ struct Dma {
     a = static_cast<const char*>(g.A) + (size_t)m0 * a_row;
     b = static_cast<const char*>(g.B) + (size_t)n0 * g.K * 2;
     am = SPARSE ? reinterpret_cast<const char*>(g.Ameta) + (size_t)m0 * (g.K / 8) : nullptr;
+    // a block tile's 256 rows occupy the same byte range in both forms; only the order of the pieces inside differs
+    const bool panel = SPARSE && g.a_panel;
+    const uint32_t a_pitch = panel ? 64u : a_row, m_pitch = panel ? 8u : (uint32_t)(g.K / 8);
+    a_stage = panel ? 256u * 64u : 64u;
+    m_stage = panel ? 256u * 8u : 8u;
 #pragma unroll
     for (int j = 0; j < 4; j++) {
       int p = 64 * wave + 16 * j + (lane >> 2);
       int c = (lane & 3) ^ swz4(p);
-      va[j] = (uint32_t)unperm_m(p) * a_row + c * 16;
+      va[j] = (uint32_t)unperm_m(p) * a_pitch + c * 16;
       if constexpr (!SPARSE) vb[j] = (uint32_t)unperm_n(p) * ((uint32_t)g.K * 2u) + c * 16;
     }
     if constexpr (SPARSE) {
@@ -145,7 +164,7 @@ struct Dma {
 #pragma unroll
       for (int j = 0; j < 2; j++) {
         int d = 64 * (2 * wave + j) + lane;
-        vm[j] = (uint32_t)unperm_m(d >> 1) * (uint32_t)(g.K / 8) + 4 * (d & 1);
+        vm[j] = (uint32_t)unperm_m(d >> 1) * m_pitch + 4 * (d & 1);
       }
     }
   }
@@ -154,13 +173,13 @@ struct Dma {
   template <int J>
   __device__ __forceinline__ void issue(int kt, char* buf) const {
     if constexpr (J < 4) {
-      __builtin_amdgcn_global_load_lds((glb_char*)(a + (size_t)kt * 64 + va[J]), (lds_char*)(buf + (4 * wave + J) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_char*)(a + (size_t)kt * a_stage + va[J]), (lds_char*)(buf + (4 * wave + J) * 1024), 16, 0, 0);
     } else if constexpr (!SPARSE) {
       constexpr int j = J - 4;
       __builtin_amdgcn_global_load_lds((glb_char*)(b + (size_t)kt * 64 + vb[j]), (lds_char*)(buf + G::B_OFF + (4 * wave + j) * 1024), 16, 0, 0);
     } else if constexpr (J < 6) {
       constexpr int j = J - 4;
-      __builtin_amdgcn_global_load_lds((glb_char*)(am + (size_t)kt * 8 + vm[j]), (lds_char*)(buf + G::META_OFF + (2 * wave + j) * 256), 4, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_char*)(am + (size_t)kt * m_stage + vm[j]), (lds_char*)(buf + G::META_OFF + (2 * wave + j) * 256), 4, 0, 0);
     } else {
       constexpr int j = J - 6;
       __builtin_amdgcn_global_load_lds((glb_char*)(b + (size_t)kt * 128 + vb[j]), (lds_char*)(buf + G::B_OFF + (8 * wave + j) * 1024), 16, 0, 0);

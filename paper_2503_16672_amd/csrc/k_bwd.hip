@@ -4,13 +4,13 @@
 namespace ffn24 {
 
 int launch_dh_gather(const void* W2, const void* dY, const void* Hc, const uint8_t* meta, int T, int D, int F, void* dZc, hipStream_t s) {
-  GemmArgs g{W2, nullptr, dY, F, T, D};
+  GemmArgs g{W2, nullptr, dY, F, T, D, 0};
   EpiDGather::Args ea{static_cast<const __bf16*>(Hc), meta, static_cast<__bf16*>(dZc), F};
   return launch_gemm<false, EpiDGather>(g, ea, s);
 }
 
-int launch_sp_colmajor(const void* vals, const uint8_t* meta, const void* B, int M, int N, int K, void* Ct, hipStream_t s) {
-  GemmArgs g{vals, meta, B, M, N, K};
+int launch_sp_colmajor(const void* vals, const uint8_t* meta, int a_panel, const void* B, int M, int N, int K, void* Ct, hipStream_t s) {
+  GemmArgs g{vals, meta, B, M, N, K, a_panel};
   EpiColMajor::Args ea{static_cast<__bf16*>(Ct), M};
   return launch_gemm<true, EpiColMajor>(g, ea, s);
 }

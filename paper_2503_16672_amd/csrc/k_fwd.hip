@@ -6,13 +6,13 @@ namespace ffn24 {
 
 int launch_up_prune24(const void* W1t, const void* X, const float* b1, int T, int D, int F,
                       void* Hc, uint8_t* meta, void* Hdbg, hipStream_t s) {
-  GemmArgs g{W1t, nullptr, X, F, T, D};
+  GemmArgs g{W1t, nullptr, X, F, T, D, 0};
   EpiPrune24::Args ea{static_cast<__bf16*>(Hc), meta, static_cast<__bf16*>(Hdbg), b1, F};
   return launch_gemm<false, EpiPrune24>(g, ea, s);
 }
 
-int launch_sp_rowmajor(const void* vals, const uint8_t* meta, const void* B, int M, int N, int K, void* C, hipStream_t s) {
-  GemmArgs g{vals, meta, B, M, N, K};
+int launch_sp_rowmajor(const void* vals, const uint8_t* meta, int a_panel, const void* B, int M, int N, int K, void* C, hipStream_t s) {
+  GemmArgs g{vals, meta, B, M, N, K, a_panel};
   EpiRowMajor::Args ea{static_cast<__bf16*>(C), N};
   return launch_gemm<true, EpiRowMajor>(g, ea, s);
 }

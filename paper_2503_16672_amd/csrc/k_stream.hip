@@ -57,9 +57,12 @@ int launch_sparsify24(const void* H, int64_t rows, int64_t cols, void* vals, uin
 // Output: for every feature, groups of 4 consecutive tokens of the pruned activation keep their top-2:
 //   Hc_t [F][T/2], meta_t [F][T/8], and dZc_t [F][T/2] = dZ at the positions picked for H.
 // One workgroup handles 128 tokens x 64 features: decompress into LDS, then each work item takes one feature
-// and 8 consecutive tokens (two groups) so that a feature row's outputs are written 128 bytes at a time.
+// and 8 consecutive tokens (two groups).  PANEL: inputs and outputs are in the panel form of gemm_core.hpp (the
+// workgroup's input is then one contiguous 8 KiB run per tensor and it writes two contiguous 4 KiB runs); otherwise
+// row-major, where a feature row's outputs are written 128 bytes at a time.
 constexpr int FW_TOK = 128, FW_FEAT = 64, FW_LD = FW_FEAT + 2;
 
+template <bool PANEL>
 __global__ void __launch_bounds__(256) featurewise24_kernel(const uint16_t* __restrict__ Hc, const uint8_t* __restrict__ meta,
                                                             const uint16_t* __restrict__ dZc, int T, int F,
                                                             uint16_t* __restrict__ Hc_t, uint8_t* __restrict__ meta_t,
@@ -73,11 +76,20 @@ __global__ void __launch_bounds__(256) featurewise24_kernel(const uint16_t* __re
   for (int i = 0; i < 2; i++) {
     int item = tid + 256 * i;
     int tok = item >> 2, ch = item & 3;
-    size_t row = (size_t)(t0 + tok);
-    u32x4 hv = *reinterpret_cast<const u32x4*>(Hc + row * (F / 2) + f0 / 2 + 8 * ch);
+    int t = t0 + tok;
+    size_t vo, mo;   // offsets of this item's 8 stored values (in elements) and of its 2 metadata bytes
+    if constexpr (PANEL) {
+      size_t piece = a24_piece(t, f0 >> 6, F >> 6);
+      vo = piece * 32 + 8 * ch;
+      mo = piece * 8 + 2 * ch;
+    } else {
+      vo = (size_t)t * (F / 2) + f0 / 2 + 8 * ch;
+      mo = (size_t)t * (F / 8) + f0 / 8 + 2 * ch;
+    }
+    u32x4 hv = *reinterpret_cast<const u32x4*>(Hc + vo);
     u32x4 zv = {0u, 0u, 0u, 0u};
-    if (has_z) zv = *reinterpret_cast<const u32x4*>(dZc + row * (F / 2) + f0 / 2 + 8 * ch);
-    uint32_t m16 = *reinterpret_cast<const uint16_t*>(meta + row * (F / 8) + f0 / 8 + 2 * ch);
+    if (has_z) zv = *reinterpret_cast<const u32x4*>(dZc + vo);
+    uint32_t m16 = *reinterpret_cast<const uint16_t*>(meta + mo);
 #pragma unroll
     for (int g = 0; g < 4; g++) {
       uint32_t nib = (m16 >> (4 * g)) & 15u;
@@ -100,7 +112,9 @@ __global__ void __launch_bounds__(256) featurewise24_kernel(const uint16_t* __re
 #pragma unroll
   for (int i = 0; i < 4; i++) {
     int item = tid + 256 * i;
-    int oct = item & 15, f = item >> 4;
+    int oct, f;
+    if constexpr (PANEL) { oct = (item & 7) | ((item >> 9) << 3); f = (item >> 3) & 63; }
+    else { oct = item & 15; f = item >> 4; }
     uint32_t h[8], z[8];
 #pragma unroll
     for (int j = 0; j < 8; j++) {
@@ -116,19 +130,55 @@ __global__ void __launch_bounds__(256) featurewise24_kernel(const uint16_t* __re
       uint32_t zb = i1 == 3 ? z[4 * g + 3] : (i1 == 2 ? z[4 * g + 2] : z[4 * g + 1]);
       zp[g] = za | (zb << 16);
     }
-    size_t frow = (size_t)(f0 + f);
-    size_t vo = frow * (T / 2) + (t0 + 8 * oct) / 2;
+    size_t vo, mo;
+    if constexpr (PANEL) {
+      size_t piece = a24_piece(f0 + f, (t0 + 8 * oct) >> 6, T >> 6);
+      vo = piece * 32 + 4 * (oct & 7);
+      mo = piece * 8 + (oct & 7);
+    } else {
+      size_t frow = (size_t)(f0 + f);
+      vo = frow * (T / 2) + (t0 + 8 * oct) / 2;
+      mo = frow * (T / 8) + t0 / 8 + oct;
+    }
     *reinterpret_cast<u32x2*>(Hc_t + vo) = u32x2{hp[0], hp[1]};
     if (has_z) *reinterpret_cast<u32x2*>(dZc_t + vo) = u32x2{zp[0], zp[1]};
-    meta_t[frow * (T / 8) + t0 / 8 + oct] = (uint8_t)(nb[0] | (nb[1] << 4));
+    meta_t[mo] = (uint8_t)(nb[0] | (nb[1] << 4));
   }
 }
 
 int launch_featurewise24(const void* Hc, const uint8_t* meta, const void* dZc, int T, int F,
-                         void* Hc_t, uint8_t* meta_t, void* dZc_t, hipStream_t s) {
+                         void* Hc_t, uint8_t* meta_t, void* dZc_t, int panel, hipStream_t s) {
   dim3 grid(F / FW_FEAT, T / FW_TOK);
-  hipLaunchKernelGGL(featurewise24_kernel, grid, dim3(256), 0, s, static_cast<const uint16_t*>(Hc), meta,
+  auto kern = panel ? featurewise24_kernel<true> : featurewise24_kernel<false>;
+  hipLaunchKernelGGL(kern, grid, dim3(256), 0, s, static_cast<const uint16_t*>(Hc), meta,
                      static_cast<const uint16_t*>(dZc), T, F, static_cast<uint16_t*>(Hc_t), meta_t, static_cast<uint16_t*>(dZc_t));
+  return (int)hipGetLastError();
+}
+
+// Panel form -> row-major.  The operand has `rows` rows and K / 64 pieces of PIECE bytes per row (64: stored values,
+// 8: metadata); each work item moves 8 bytes.
+template <int PIECE>
+__global__ void __launch_bounds__(256) unpanel_kernel(const u32x2* __restrict__ src, int rows, int npanels, u32x2* __restrict__ dst) {
+  constexpr int W = PIECE / 8;                       // 8-byte words per piece
+  size_t n = (size_t)rows * npanels * W;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+    size_t pc = i / W;                               // row-major piece number: r * npanels + kp
+    int w = (int)(i % W);
+    int r = (int)(pc / npanels), kp = (int)(pc % npanels);
+    dst[i] = src[a24_piece(r, kp, npanels) * W + w];
+  }
+}
+
+int launch_unpanel(const void* src, int rows, int K, int piece_bytes, void* dst, hipStream_t s) {
+  int npanels = K / 64;
+  size_t n = (size_t)rows * npanels * (piece_bytes / 8);
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  if (piece_bytes == 64)
+    hipLaunchKernelGGL(unpanel_kernel<64>, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const u32x2*>(src), rows, npanels, static_cast<u32x2*>(dst));
+  else
+    hipLaunchKernelGGL(unpanel_kernel<8>, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const u32x2*>(src), rows, npanels, static_cast<u32x2*>(dst));
   return (int)hipGetLastError();
 }
 

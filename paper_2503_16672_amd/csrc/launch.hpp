@@ -12,10 +12,10 @@ namespace ffn24 {
 int launch_up_prune24(const void* W1t, const void* X, const float* b1, int T, int D, int F,
                       void* Hc, uint8_t* meta, void* Hdbg, hipStream_t s);
 int launch_up_relu2(const void* W1t, const void* X, const float* b1, int T, int D, int F, void* H, void* Ht, hipStream_t s);
-// C[M][N] = A24[M][K] * B[N][K]^T
-int launch_sp_rowmajor(const void* vals, const uint8_t* meta, const void* B, int M, int N, int K, void* C, hipStream_t s);
+// C[M][N] = A24[M][K] * B[N][K]^T; a_panel: (vals, meta) are in panel form instead of row-major
+int launch_sp_rowmajor(const void* vals, const uint8_t* meta, int a_panel, const void* B, int M, int N, int K, void* C, hipStream_t s);
 // out[N][M] = (A24[M][K] * B[N][K]^T)^T
-int launch_sp_colmajor(const void* vals, const uint8_t* meta, const void* B, int M, int N, int K, void* Ct, hipStream_t s);
+int launch_sp_colmajor(const void* vals, const uint8_t* meta, int a_panel, const void* B, int M, int N, int K, void* Ct, hipStream_t s);
 // dH = dY W2^T with rows = hidden features: A = W2 [F][D], B = dY [T][D]; pointwise part fused
 int launch_dh_gather(const void* W2, const void* dY, const void* Hc, const uint8_t* meta, int T, int D, int F, void* dZc, hipStream_t s);
 int launch_dh_drelu(const void* W2, const void* dY, const void* H, int T, int D, int F, void* dZ, void* dZt, hipStream_t s);
@@ -24,8 +24,11 @@ int launch_dense_rowmajor(const void* A, const void* B, int M, int N, int K, voi
 int launch_dense_colmajor(const void* A, const void* B, int M, int N, int K, void* Ct, hipStream_t s);
 // streaming kernels
 int launch_sparsify24(const void* H, int64_t rows, int64_t cols, void* vals, uint8_t* meta, hipStream_t s);
+// panel: inputs and outputs are in panel form (the library's own buffers) instead of row-major
 int launch_featurewise24(const void* Hc, const uint8_t* meta, const void* dZc, int T, int F,
-                         void* Hc_t, uint8_t* meta_t, void* dZc_t, hipStream_t s);
+                         void* Hc_t, uint8_t* meta_t, void* dZc_t, int panel, hipStream_t s);
+// panel form -> row-major copy of a compressed operand: rows x (K/64) pieces of `piece_bytes` (64 values / 8 metadata)
+int launch_unpanel(const void* src, int rows, int K, int piece_bytes, void* dst, hipStream_t s);
 int launch_transpose(const void* in, int R, int C, void* out, hipStream_t s);   // in [R][C] -> out [C][R], R, C % 64 == 0
 
 }  // namespace ffn24

@@ -22,7 +22,7 @@ FFN24_DEBUG_DUMP_H = 4
 
 EXPORTS = (
     "ffn24_ctx_create", "ffn24_ctx_destroy", "sparsify24", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd",
-    "ffn_fwd", "ffn_bwd", "ffn24_get_saved", "ffn24_set_profiling", "ffn24_kernel_ms", "ffn24_strerror",
+    "ffn_fwd", "ffn_bwd", "ffn24_saved_bytes", "ffn24_copy_saved", "ffn24_set_profiling", "ffn24_kernel_ms", "ffn24_strerror",
 )
 
 KERNEL_NAMES = ("up_prune24", "down_sp", "dh_gather", "dx_sp", "featurewise24", "dw2_sp", "dw1_sp",
@@ -54,7 +54,8 @@ def lib() -> ctypes.CDLL:
         L.ffn24_bwd.argtypes = [vp, vp, vp, vp, vp, vp]
         L.ffn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp]
         L.ffn_bwd.argtypes = [vp, vp, vp, vp, vp, vp]
-        L.ffn24_get_saved.argtypes = [vp, ci, ctypes.POINTER(vp), ctypes.POINTER(i64)]
+        L.ffn24_saved_bytes.argtypes = [vp, ci, ctypes.POINTER(i64)]
+        L.ffn24_copy_saved.argtypes = [vp, ci, vp, i64, vp]
         L.ffn24_set_profiling.argtypes = [vp, ci]
         L.ffn24_kernel_ms.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_float)]
         L.ffn24_strerror.argtypes = [ci]
@@ -64,19 +65,6 @@ def lib() -> ctypes.CDLL:
                 getattr(L, name).restype = ci
         _lib = L
     return _lib
-
-
-_hiprt = None
-
-
-def _hip() -> ctypes.CDLL:
-    """The HIP runtime the library is linked against (only used for a device-to-device copy)."""
-    global _hiprt
-    if _hiprt is None:
-        _hiprt = ctypes.CDLL("libamdhip64.so")
-        _hiprt.hipMemcpyAsync.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
-        _hiprt.hipMemcpyAsync.restype = ctypes.c_int
-    return _hiprt
 
 
 def strerror(code: int) -> str:
@@ -183,18 +171,13 @@ class Context:
               "dZ_dense": (8, torch.bfloat16, lambda T, F: (T, F))}
 
     def saved(self, name: str) -> torch.Tensor:
-        """Copy of a workspace buffer as a torch tensor (device-to-device copy on the current stream)."""
+        """Row-major copy of a saved tensor of the context (enqueued on the current stream)."""
         which, dtype, shape_fn = self._SAVED[name]
-        p, n = ctypes.c_void_p(), ctypes.c_int64()
-        _check(lib().ffn24_get_saved(self._h, which, ctypes.byref(p), ctypes.byref(n)), "ffn24_get_saved")
-        if not p.value:
-            raise Ffn24Error(-5, f"buffer {name} not allocated in this context")
-        shape = shape_fn(self.T, self.F)
-        out = torch.empty(shape, dtype=dtype, device="cuda")
+        n = ctypes.c_int64()
+        _check(lib().ffn24_saved_bytes(self._h, which, ctypes.byref(n)), "ffn24_saved_bytes")
+        out = torch.empty(shape_fn(self.T, self.F), dtype=dtype, device="cuda")
         assert out.numel() * out.element_size() == n.value
-        rc = _hip().hipMemcpyAsync(ctypes.c_void_p(out.data_ptr()), p, ctypes.c_size_t(n.value), 3, ctypes.c_void_p(_stream()))
-        if int(rc) != 0:
-            raise RuntimeError(f"hipMemcpyAsync failed: {rc}")
+        _check(lib().ffn24_copy_saved(self._h, which, _ptr(out), n.value, _stream()), f"ffn24_copy_saved({name})")
         return out
 
     def set_profiling(self, on: bool):
