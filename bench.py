@@ -28,6 +28,19 @@ KERNEL_FLOPS = {"up_prune24": 2.0, "down_sp": 1.0, "dh_gather": 2.0, "dx_sp": 1.
 SPARSE = {"down_sp", "dx_sp", "dw2_sp", "dw1_sp"}
 
 
+def measured_traffic(kernel: str, workload: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE, each
+    scaled by what the same counter reads for a 1 GiB copy); None if no summary covers this kernel and workload."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("hbm_bytes_per_launch"):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -36,7 +49,9 @@ def main() -> int:
     ap.add_argument("--workload", default="c4", help="c1, c2, c3_85..c3_98, c4 (default: forward+backward at the 7B FFN dims)")
     ap.add_argument("--fwd-only", action="store_true", help="time the forward pass only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--cpu-tokens", type=int, default=512, help="token slice the CPU oracle is timed on")
+    ap.add_argument("--cpu-tokens", type=int, default=2048, help="token slice the CPU oracle is timed on")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy before the steps (the known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
@@ -78,6 +93,13 @@ def main() -> int:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
+    if args.calib_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     ctx.set_profiling(True)   # event pairs around every kernel, on the launch stream; no synchronisation added
     sec24 = timed(step24, args.warmup, args.steps)
     # per-kernel durations: average over the same number of steps, reading the events after each step
@@ -117,7 +139,7 @@ def main() -> int:
     dom = max((n for n in kernel_ms if n in KERNEL_FLOPS and not n.startswith("dense_")), key=lambda n: kernel_ms[n])
     achieved = KERNEL_FLOPS[dom] * tdf / (kernel_ms[dom] * 1e-3) / 1e12
     roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_DENSE, "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_BF16_DENSE, 4), "traffic": None,
+                "frac": round(achieved / PEAK_BF16_DENSE, 4), "traffic": measured_traffic(dom, w.name),
                 "note": "executed bf16 MFMA flops of the launch / its HIP-event duration; a sparse kernel executes half its dense-equivalent flops"}
 
     cpu = None

@@ -169,6 +169,12 @@ def _upload(inp):
     return d
 
 
+def _mm24(values_f64, meta, B):
+    """(compressed A) . B through the definition: decompress, then a dense float64 product.  Equal to
+    O.gather_matmul24 (pinned in the CPU tests) and fast enough for the full-size cases."""
+    return O.decompress24(np.asarray(values_f64, dtype=np.float64), meta) @ np.asarray(B, dtype=np.float64)
+
+
 def _check_fwd24(F24, inp, ctx, d, Y, full_oracle=True, rows=None):
     """Staged forward checks.  rows: optional token subset (numpy indices) for the oracle side."""
     T, Fh = ctx.T, ctx.F
@@ -184,7 +190,7 @@ def _check_fwd24(F24, inp, ctx, d, Y, full_oracle=True, rows=None):
     assert np.array_equal(words_of(Hc), v_ref)
     # S2: down-projection on the GPU's own compressed activation
     W2q = f64(d["W2"])
-    y_staged = O.gather_matmul24(f64(Hc), meta.cpu().numpy(), W2q)
+    y_staged = (_mm24 if rows is not None else O.gather_matmul24)(f64(Hc), meta.cpu().numpy(), W2q)
     e2 = O.max_rel_err(f64(Y[rs_t]), y_staged)
     # S3: from the raw inputs
     ref = O.ffn24_fwd(inp["X"][rsel], inp["W1"], inp["b1"], inp["W2"])
@@ -358,4 +364,126 @@ def test_multi_tile_shapes(F24):
     errs = [O.max_rel_err(f64(Yd), f["Y"])] + [O.max_rel_err(f64(a), g[k]) for a, k in zip(gd, ("dX", "dW1", "dW2"))]
     print("  dense errs", errs, flush=True)
     assert max(errs) <= TOL_BF16
+    ctx.close()
+
+
+# ----------------------------------------------------------------------------- full size (bench configuration), sampled
+def _groups_to_cols(gsel):
+    """feature groups -> their 4 features each, and their 2 stored slots each."""
+    f4 = (4 * gsel[:, None] + np.arange(4)[None, :]).reshape(-1)
+    f2 = (2 * gsel[:, None] + np.arange(2)[None, :]).reshape(-1)
+    return f4, f2
+
+
+def _meta_of_groups(meta_rows: np.ndarray, gsel: np.ndarray) -> np.ndarray:
+    """meta [rows, G/2] bytes -> a [rows, len(gsel)/2] byte array holding only the chosen groups (len(gsel) even)."""
+    i0, i1 = O.unpack_meta(meta_rows)
+    nib = (i0[:, gsel] | (i1[:, gsel] << 2)).astype(np.uint8)
+    return (nib[:, 0::2] | (nib[:, 1::2] << 4)).astype(np.uint8)
+
+
+@pytest.mark.timeout(900)
+def test_ffn24_full_size_sampled(F24):
+    """c4 (T=16384, D=4096, F=16384, fwd+bwd), the shape and launch configuration bench.py times.
+    Y and dX depend on one token each: a seeded sample of token rows is checked at full D and F.
+    dW1 / dW2 rows depend on one hidden feature (and the token-wise group of 4 it sits in): a seeded sample of
+    feature groups is checked over all T.  Masks: staged as in the small tests (S1 bit-exact on the GPU's own
+    tensors), on the same samples; the 2:4 invariant everywhere."""
+    w = synth.WORKLOADS["c4"]
+    T, D, Fh = w.T, w.D, w.F
+    print(f"full size c4 T={T} D={D} F={Fh}: generating inputs", flush=True)
+    inp = synth.make_workload("c4", with_dy=True)
+    d = _upload(inp)
+    ctx = F24.Context(T, D, Fh, F24.FFN24_DEBUG_DUMP_H | F24.FFN24_TRAINING)
+    print("  running fwd+bwd on the GPU", flush=True)
+    Y = ctx.ffn24_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    dX, dW1, dW2 = ctx.ffn24_bwd(d["dY"])
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(44)
+    rows = np.sort(rng.choice(T, 192, replace=False))
+    rows_t = torch.from_numpy(rows).cuda()
+
+    # ---- token-row sample: forward (S1, S2, S3) and dX
+    print("  token-row sample: forward", flush=True)
+    ref = _check_fwd24(F24, inp, ctx, d, Y, rows=rows)
+    print("  token-row sample: dZ, dX", flush=True)
+    meta_all = ctx.saved("meta")
+    Hc_all = ctx.saved("Hc")
+    dZc_all = ctx.saved("dZc")
+    torch.cuda.synchronize()
+    Hc_r = Hc_all[rows_t]; meta_r = meta_all[rows_t].cpu().numpy(); dZc_r = dZc_all[rows_t]
+    fwd_rows = O.fwd_from_saved(words_of(Hc_r), meta_r, inp["X"][rows], inp["W1"], inp["W2"])
+    dYq = f64(d["dY"][rows_t])
+    dH = dYq @ fwd_rows["W2q"].T
+    dZ = O._drelu2(dH, fwd_rows["H24"], O.Bf16)
+    dZ = np.where(fwd_rows["Mtok"], dZ, np.float32(0))
+    dZq = O.round_bf16(dZ)
+    e_dz = O.max_rel_err(f64(dZc_r), O.compress_with_meta(dZq, meta_r))
+    e_dx_staged = O.max_rel_err(f64(dX[rows_t]), _mm24(f64(dZc_r), meta_r, f64(d["W1"]).T))
+    e_dx_chain = O.max_rel_err(f64(dX[rows_t]), dZq.astype(np.float64) @ fwd_rows["W1q"].T)
+    print(f"  dZc {e_dz:.2e}  dX staged {e_dx_staged:.2e}  dX chain {e_dx_chain:.2e}", flush=True)
+    assert max(e_dz, e_dx_staged, e_dx_chain) <= TOL_BF16
+
+    # ---- 2:4 invariant of both metadata tensors, everywhere, on the device
+    meta_t_all = ctx.saved("meta_t")
+    for m in (meta_all, meta_t_all):
+        for nib in (m & 0xF, m >> 4):
+            assert bool(((nib & 3) < (nib >> 2)).all())
+
+    # ---- feature-group sample: feature-wise picks (bit-exact) and the two weight gradients over all tokens
+    print("  feature-group sample: feature-wise picks, dW2, dW1", flush=True)
+    gsel = np.sort(rng.choice(Fh // 4, 24, replace=False))
+    f4, f2 = _groups_to_cols(gsel)
+    f2_t = torch.from_numpy(f2).cuda(); f4_t = torch.from_numpy(f4).cuda()
+    Hc_g = words_of(Hc_all[:, f2_t]); dZc_g = words_of(dZc_all[:, f2_t])
+    meta_g = _meta_of_groups(meta_all.cpu().numpy(), gsel)
+    H24_g = O.decompress24(Hc_g, meta_g)            # [T, 96] words, the GPU's own pruned activation on these features
+    dZ24_g = O.decompress24(dZc_g, meta_g)
+    Hct_ref, mt_ref = O.sparsify24(np.ascontiguousarray(H24_g.T))
+    dZct_ref = O.compress_with_meta(np.ascontiguousarray(dZ24_g.T), mt_ref)
+    Hc_t = ctx.saved("Hc_t")[f4_t]; dZc_t = ctx.saved("dZc_t")[f4_t]; meta_t = meta_t_all[f4_t].cpu().numpy()
+    torch.cuda.synchronize()
+    assert np.array_equal(meta_t, mt_ref)
+    assert np.array_equal(words_of(Hc_t), Hct_ref)
+    assert np.array_equal(words_of(dZc_t), dZct_ref)
+    dY_all = f64(d["dY"]); X_all = f64(d["X"])
+    dW2_ref = _mm24(O.bf16_bits_to_f32(Hct_ref), mt_ref, dY_all)
+    dW1_ref = _mm24(O.bf16_bits_to_f32(dZct_ref), mt_ref, X_all)
+    e_dw2 = O.max_rel_err(f64(dW2[f4_t]), dW2_ref)
+    e_dw1 = O.max_rel_err(f64(dW1[:, f4_t]).T, dW1_ref)
+    # the same through the masked definition: (H24 * M_T)^T dY
+    M_T = O.mask_from_meta(mt_ref).T
+    dW2_def = np.where(M_T, O.bf16_bits_to_f32(H24_g), np.float32(0)).astype(np.float64).T @ dY_all
+    e_def = O.max_rel_err(dW2_ref, dW2_def)
+    print(f"  dW2 {e_dw2:.2e}  dW1 {e_dw1:.2e}  (compressed vs masked definition {e_def:.1e})", flush=True)
+    assert e_dw2 <= TOL_BF16 and e_dw1 <= TOL_BF16 and e_def <= 1e-12
+    assert ref["Y"].shape == (len(rows), D)
+    ctx.close()
+
+
+@pytest.mark.timeout(900)
+def test_ffn_dense_full_size_sampled(F24):
+    """The dense baseline at the bench shape: sampled token rows of Y and dX, sampled features of dW1 / dW2."""
+    w = synth.WORKLOADS["c4"]
+    T, D, Fh = w.T, w.D, w.F
+    print(f"dense full size c4", flush=True)
+    inp = synth.make_workload("c4", with_dy=True)
+    d = _upload(inp)
+    ctx = F24.Context(T, D, Fh, F24.FFN24_DENSE | F24.FFN24_TRAINING)
+    Y = ctx.ffn_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    dX, dW1, dW2 = ctx.ffn_bwd(d["dY"])
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(45)
+    rows = np.sort(rng.choice(T, 128, replace=False)); rows_t = torch.from_numpy(rows).cuda()
+    f = O.ffn_fwd(inp["X"][rows], inp["W1"], inp["b1"], inp["W2"])
+    g = O.ffn_bwd(f, inp["dY"][rows])
+    Hd = ctx.saved("H_dense"); dZd = ctx.saved("dZ_dense")
+    torch.cuda.synchronize()
+    errs = {"H": O.max_rel_err(f64(Hd[rows_t]), f["Hq"]), "Y": O.max_rel_err(f64(Y[rows_t]), f["Y"]),
+            "dZ": O.max_rel_err(f64(dZd[rows_t]), g["dZq"]), "dX": O.max_rel_err(f64(dX[rows_t]), g["dX"])}
+    fsel = np.sort(rng.choice(Fh, 64, replace=False)); fsel_t = torch.from_numpy(fsel).cuda()
+    errs["dW2"] = O.max_rel_err(f64(dW2[fsel_t]), f64(Hd[:, fsel_t]).T @ f64(d["dY"]))
+    errs["dW1"] = O.max_rel_err(f64(dW1[:, fsel_t]), f64(d["X"]).T @ f64(dZd[:, fsel_t]))
+    print("  dense full-size errs", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    assert max(errs.values()) <= TOL_BF16
     ctx.close()
