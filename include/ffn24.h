@@ -58,7 +58,7 @@ typedef struct ffn24_ctx ffn24_ctx; /* opaque; owns only its device workspace */
 
 /* Create a context for token count T, model dimension D, hidden dimension F.
  * Requires T, D, F to be multiples of 256 (the GEMM tile) and at most 2^20.  Allocates the device workspace with
- * hipMalloc on the current device: about 1.13 T F + 4 D F bytes; plus 3.13 T F + 4 T D with FFN24_TRAINING; plus
+ * hipMalloc on the current device: about 1.13 T F + 4 D F bytes; plus 3.13 T F + 4 T D + 2 D F with FFN24_TRAINING; plus
  * 2 T F with FFN24_DENSE (6 T F more when FFN24_TRAINING is set too); plus 2 T F with FFN24_DEBUG_DUMP_H.
  * *out is untouched on error. */
 FFN24_API int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dtype dtype, int flags);

@@ -20,6 +20,7 @@ struct ffn24_ctx {
   // workspace (device)
   void* Hc; uint8_t* meta; void* dZc; void* Hc_t; uint8_t* meta_t; void* dZc_t; void* Hdbg; void* Hd; void* dZd;
   void* W1t; void* W2t; void* Xt; void* dYt; void* Hd_t; void* dZd_t;   // K-contiguous copies of GEMM operands
+  void* W2p;   // W2 itself in dense panel form (A operand of the dH GEMMs)
   // forward state
   const void *X, *W1, *W2;
   int have_fwd24, have_fwd_dense;
@@ -45,7 +46,7 @@ struct Timed {
 int free_all(ffn24_ctx* c) {
   int bad = 0;
   void* bufs[] = {c->Hc, c->meta, c->dZc, c->Hc_t, c->meta_t, c->dZc_t, c->Hdbg, c->Hd, c->dZd,
-                  c->W1t, c->W2t, c->Xt, c->dYt, c->Hd_t, c->dZd_t};
+                  c->W1t, c->W2t, c->Xt, c->dYt, c->Hd_t, c->dZd_t, c->W2p};
   for (void* b : bufs) if (b && hipFree(b) != hipSuccess) bad = 1;
   for (int k = 0; k < NUM_KERNELS; k++) for (int j = 0; j < 2; j++) if (c->ev[k][j]) (void)hipEventDestroy(c->ev[k][j]);
   return bad;
@@ -89,7 +90,7 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
   if (ok && (flags & FFN24_TRAINING))
     ok = hipMalloc(&c->dZc, tf) == hipSuccess && hipMalloc(&c->Hc_t, tf) == hipSuccess &&
          hipMalloc(reinterpret_cast<void**>(&c->meta_t), tf / 8) == hipSuccess && hipMalloc(&c->dZc_t, tf) == hipSuccess &&
-         hipMalloc(&c->Xt, 2 * td) == hipSuccess && hipMalloc(&c->dYt, 2 * td) == hipSuccess;
+         hipMalloc(&c->Xt, 2 * td) == hipSuccess && hipMalloc(&c->dYt, 2 * td) == hipSuccess && hipMalloc(&c->W2p, 2 * df) == hipSuccess;
   if (ok && (flags & FFN24_DENSE)) ok = hipMalloc(&c->Hd, 2 * tf) == hipSuccess;
   if (ok && (flags & FFN24_DENSE) && (flags & FFN24_TRAINING))
     ok = hipMalloc(&c->dZd, 2 * tf) == hipSuccess && hipMalloc(&c->Hd_t, 2 * tf) == hipSuccess && hipMalloc(&c->dZd_t, 2 * tf) == hipSuccess;
@@ -198,8 +199,8 @@ int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, cons
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   c->have_fwd24 = 0;
   { Timed t(c, K_TR_W, s);
-    int rc1 = launch_transpose(W1, D, F, c->W1t, s);
-    if (t.done(rc1 ? rc1 : launch_transpose(W2, F, D, c->W2t, s))) return FFN24_ERR_HIP; }
+    int rc1 = launch_transpose(W1, D, F, c->W1t, 1, nullptr, s);
+    if (t.done(rc1 ? rc1 : launch_transpose(W2, F, D, c->W2t, 0, c->W2p, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_UP, s);   if (t.done(launch_up_prune24(c->W1t, X, b1, T, D, F, c->Hc, c->meta, c->Hdbg, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_DOWN, s); if (t.done(launch_sp_rowmajor(c->Hc, c->meta, 1, c->W2t, T, D, F, Y, s))) return FFN24_ERR_HIP; }
   c->X = X; c->W1 = W1; c->W2 = W2; c->have_fwd24 = 1;
@@ -213,12 +214,12 @@ int ffn24_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void
   if (rc) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
-  { Timed t(c, K_DH, s);  if (t.done(launch_dh_gather(c->W2, dY, c->Hc, c->meta, T, D, F, c->dZc, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_DH, s);  if (t.done(launch_dh_gather(c->W2p, dY, c->Hc, c->meta, T, D, F, c->dZc, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_DX, s);  if (t.done(launch_sp_rowmajor(c->dZc, c->meta, 1, c->W1, T, D, F, dX, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_FW, s);  if (t.done(launch_featurewise24(c->Hc, c->meta, c->dZc, T, F, c->Hc_t, c->meta_t, c->dZc_t, 1, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_TR_ACT, s);
-    int rc1 = launch_transpose(dY, T, D, c->dYt, s);
-    if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, s))) return FFN24_ERR_HIP; }
+    int rc1 = launch_transpose(dY, T, D, c->dYt, 0, nullptr, s);
+    if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, 0, nullptr, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_DW2, s); if (t.done(launch_sp_rowmajor(c->Hc_t, c->meta_t, 1, c->dYt, F, D, T, dW2, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_DW1, s); if (t.done(launch_sp_colmajor(c->dZc_t, c->meta_t, 1, c->Xt, F, D, T, dW1, s))) return FFN24_ERR_HIP; }
   return FFN24_OK;
@@ -234,8 +235,8 @@ int ffn_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const 
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   c->have_fwd_dense = 0;
   { Timed t(c, K_TR_W, s);
-    int rc1 = launch_transpose(W1, D, F, c->W1t, s);
-    if (t.done(rc1 ? rc1 : launch_transpose(W2, F, D, c->W2t, s))) return FFN24_ERR_HIP; }
+    int rc1 = launch_transpose(W1, D, F, c->W1t, 1, nullptr, s);
+    if (t.done(rc1 ? rc1 : launch_transpose(W2, F, D, c->W2t, 0, c->W2p, s))) return FFN24_ERR_HIP; }
   { Timed t(c, KD_UP, s);   if (t.done(launch_up_relu2(c->W1t, X, b1, T, D, F, c->Hd, c->Hd_t, s))) return FFN24_ERR_HIP; }
   { Timed t(c, KD_DOWN, s); if (t.done(launch_dense_rowmajor(c->Hd, c->W2t, T, D, F, Y, s))) return FFN24_ERR_HIP; }
   c->X = X; c->W1 = W1; c->W2 = W2; c->have_fwd_dense = 1;
@@ -249,11 +250,11 @@ int ffn_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void* 
   if (rc) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
-  { Timed t(c, KD_DH, s);  if (t.done(launch_dh_drelu(c->W2, dY, c->Hd, T, D, F, c->dZd, c->dZd_t, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_DH, s);  if (t.done(launch_dh_drelu(c->W2p, dY, c->Hd, T, D, F, c->dZd, c->dZd_t, s))) return FFN24_ERR_HIP; }
   { Timed t(c, KD_DX, s);  if (t.done(launch_dense_rowmajor(c->dZd, c->W1, T, D, F, dX, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_TR_ACT, s);
-    int rc1 = launch_transpose(dY, T, D, c->dYt, s);
-    if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, s))) return FFN24_ERR_HIP; }
+    int rc1 = launch_transpose(dY, T, D, c->dYt, 0, nullptr, s);
+    if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, 0, nullptr, s))) return FFN24_ERR_HIP; }
   { Timed t(c, KD_DW2, s); if (t.done(launch_dense_rowmajor(c->Hd_t, c->dYt, F, D, T, dW2, s))) return FFN24_ERR_HIP; }
   { Timed t(c, KD_DW1, s); if (t.done(launch_dense_colmajor(c->dZd_t, c->Xt, F, D, T, dW1, s))) return FFN24_ERR_HIP; }
   return FFN24_OK;

@@ -21,6 +21,9 @@
 // full 128-byte lines, instead of 256 pieces of 64 (8) bytes that are a whole matrix row apart.  Measured: the
 // sparse GEMM is bound by its global->LDS stream, and the 8-byte metadata pieces alone cost it 17 %.
 //
+// A dense A operand can be in panel form too: piece (r, kp) = the 32 k (64 bytes) [32 kp, 32 kp + 32) of row r,
+// same piece index with K / 32 panels per row (the weight copies the library makes for itself).
+//
 // Data movement.  Global memory goes straight to LDS (global_load_lds_dwordx4: no VGPR staging, no LDS store
 // instructions) into a ring of stage buffers, 2-3 stages ahead of the math, so that L2/HBM latency is covered:
 //   dense : stage = 32 k  (A 16 KiB + B 16 KiB), ring of 4  -> 128 KiB of the CU's 160 KiB LDS
@@ -69,7 +72,7 @@ struct GemmArgs {
   const uint8_t* Ameta;  // sparse only: [M][K/8]
   const void* B;         // [N][K]
   int M, N, K;           // K is the dense reduction length
-  int a_panel;           // sparse only: values and metadata are in panel form (see above) instead of row-major
+  int a_panel;           // A (and its metadata) is in panel form (see above) instead of row-major
 };
 
 // piece index of row r, 64-k panel kp, for an operand with `npanels` = K / 64 panels per row
@@ -143,7 +146,7 @@ struct Dma {
     b = static_cast<const char*>(g.B) + (size_t)n0 * g.K * 2;
     am = SPARSE ? reinterpret_cast<const char*>(g.Ameta) + (size_t)m0 * (g.K / 8) : nullptr;
     // a block tile's 256 rows occupy the same byte range in both forms; only the order of the pieces inside differs
-    const bool panel = SPARSE && g.a_panel;
+    const bool panel = g.a_panel != 0;
     const uint32_t a_pitch = panel ? 64u : a_row, m_pitch = panel ? 8u : (uint32_t)(g.K / 8);
     a_stage = panel ? 256u * 64u : 64u;
     m_stage = panel ? 256u * 8u : 8u;

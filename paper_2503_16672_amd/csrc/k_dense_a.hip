@@ -4,13 +4,13 @@
 namespace ffn24 {
 
 int launch_up_relu2(const void* W1t, const void* X, const float* b1, int T, int D, int F, void* H, void* Ht, hipStream_t s) {
-  GemmArgs g{W1t, nullptr, X, F, T, D, 0};
+  GemmArgs g{W1t, nullptr, X, F, T, D, 1};
   EpiRelu2::Args ea{static_cast<__bf16*>(H), static_cast<__bf16*>(Ht), b1, F, T};
   return launch_gemm<false, EpiRelu2>(g, ea, s);
 }
 
 int launch_dh_drelu(const void* W2, const void* dY, const void* H, int T, int D, int F, void* dZ, void* dZt, hipStream_t s) {
-  GemmArgs g{W2, nullptr, dY, F, T, D, 0};
+  GemmArgs g{W2, nullptr, dY, F, T, D, 1};
   EpiDRelu::Args ea{static_cast<const __bf16*>(H), static_cast<__bf16*>(dZ), static_cast<__bf16*>(dZt), F, T};
   return launch_gemm<false, EpiDRelu>(g, ea, s);
 }

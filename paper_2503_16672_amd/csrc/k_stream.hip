@@ -185,9 +185,13 @@ int launch_unpanel(const void* src, int rows, int K, int piece_bytes, void* dst,
 // out[c][r] = in[r][c] for a bf16 matrix [R][C], R and C multiples of 64.  One workgroup per 64x64 tile: rows are
 // read 128 bytes at a time, scattered into an LDS tile with a 132-byte pitch (conflict-free for this pattern), and
 // written out as 128-byte rows of the transposed matrix.
+// OUT_PANEL: the transposed matrix is written in the dense panel form of gemm_core.hpp (64-byte pieces of 32 k, K = R).
+// in_panel (optional): a copy of the input itself in panel form (K = C), made in the same pass.
 constexpr int TR_LD = 66;
 
-__global__ void __launch_bounds__(256) transpose_kernel(const uint16_t* __restrict__ in, int R, int C, uint16_t* __restrict__ out) {
+template <bool OUT_PANEL>
+__global__ void __launch_bounds__(256) transpose_kernel(const uint16_t* __restrict__ in, int R, int C, uint16_t* __restrict__ out,
+                                                        uint16_t* __restrict__ in_panel) {
   __shared__ __attribute__((aligned(16))) uint16_t sT[64 * TR_LD];
   int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
   int tid = threadIdx.x;
@@ -196,6 +200,10 @@ __global__ void __launch_bounds__(256) transpose_kernel(const uint16_t* __restri
   for (int i = 0; i < 2; i++) {
     int r = rr + 32 * i;
     u32x4 v = *reinterpret_cast<const u32x4*>(in + (size_t)(r0 + r) * C + c0 + 8 * ch);
+    if (in_panel) {
+      int c = c0 + 8 * ch;
+      *reinterpret_cast<u32x4*>(in_panel + a24_piece(r0 + r, c >> 5, C >> 5) * 32 + (c & 31)) = v;
+    }
 #pragma unroll
     for (int d = 0; d < 4; d++) {
       sT[(8 * ch + 2 * d) * TR_LD + r] = (uint16_t)(v[d] & 0xFFFFu);
@@ -208,13 +216,17 @@ __global__ void __launch_bounds__(256) transpose_kernel(const uint16_t* __restri
     int c = rr + 32 * i;
     const uint32_t* src = reinterpret_cast<const uint32_t*>(&sT[c * TR_LD + 8 * ch]);
     u32x4 v = {src[0], src[1], src[2], src[3]};
-    *reinterpret_cast<u32x4*>(out + (size_t)(c0 + c) * R + r0 + 8 * ch) = v;
+    int r = r0 + 8 * ch;
+    if constexpr (OUT_PANEL) *reinterpret_cast<u32x4*>(out + a24_piece(c0 + c, r >> 5, R >> 5) * 32 + (r & 31)) = v;
+    else *reinterpret_cast<u32x4*>(out + (size_t)(c0 + c) * R + r) = v;
   }
 }
 
-int launch_transpose(const void* in, int R, int C, void* out, hipStream_t s) {
+int launch_transpose(const void* in, int R, int C, void* out, int out_panel, void* in_panel, hipStream_t s) {
   dim3 grid(C / 64, R / 64);
-  hipLaunchKernelGGL(transpose_kernel, grid, dim3(256), 0, s, static_cast<const uint16_t*>(in), R, C, static_cast<uint16_t*>(out));
+  auto kern = out_panel ? transpose_kernel<true> : transpose_kernel<false>;
+  hipLaunchKernelGGL(kern, grid, dim3(256), 0, s, static_cast<const uint16_t*>(in), R, C, static_cast<uint16_t*>(out),
+                     static_cast<uint16_t*>(in_panel));
   return (int)hipGetLastError();
 }
 

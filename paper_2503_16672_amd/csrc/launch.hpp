@@ -8,7 +8,7 @@ namespace ffn24 {
 // All return a hipError_t cast to int (0 = success); shapes must already be validated by the caller:
 // M % 256 == 0, N % 256 == 0, K % 64 == 0, 16-byte aligned pointers.  Every GEMM operand is K-contiguous.
 
-// up-projection with rows = hidden features: A = W1^T [F][D], B = X [T][D]
+// up-projection with rows = hidden features: A = W1^T [F][D] in dense panel form, B = X [T][D]
 int launch_up_prune24(const void* W1t, const void* X, const float* b1, int T, int D, int F,
                       void* Hc, uint8_t* meta, void* Hdbg, hipStream_t s);
 int launch_up_relu2(const void* W1t, const void* X, const float* b1, int T, int D, int F, void* H, void* Ht, hipStream_t s);
@@ -16,7 +16,7 @@ int launch_up_relu2(const void* W1t, const void* X, const float* b1, int T, int 
 int launch_sp_rowmajor(const void* vals, const uint8_t* meta, int a_panel, const void* B, int M, int N, int K, void* C, hipStream_t s);
 // out[N][M] = (A24[M][K] * B[N][K]^T)^T
 int launch_sp_colmajor(const void* vals, const uint8_t* meta, int a_panel, const void* B, int M, int N, int K, void* Ct, hipStream_t s);
-// dH = dY W2^T with rows = hidden features: A = W2 [F][D], B = dY [T][D]; pointwise part fused
+// dH = dY W2^T with rows = hidden features: A = W2 [F][D] in dense panel form, B = dY [T][D]; pointwise part fused
 int launch_dh_gather(const void* W2, const void* dY, const void* Hc, const uint8_t* meta, int T, int D, int F, void* dZc, hipStream_t s);
 int launch_dh_drelu(const void* W2, const void* dY, const void* H, int T, int D, int F, void* dZ, void* dZt, hipStream_t s);
 // dense GEMMs: A [M][K], B [N][K]
@@ -29,6 +29,8 @@ int launch_featurewise24(const void* Hc, const uint8_t* meta, const void* dZc, i
                          void* Hc_t, uint8_t* meta_t, void* dZc_t, int panel, hipStream_t s);
 // panel form -> row-major copy of a compressed operand: rows x (K/64) pieces of `piece_bytes` (64 values / 8 metadata)
 int launch_unpanel(const void* src, int rows, int K, int piece_bytes, void* dst, hipStream_t s);
-int launch_transpose(const void* in, int R, int C, void* out, hipStream_t s);   // in [R][C] -> out [C][R], R, C % 64 == 0
+// in [R][C] -> out [C][R] (R, C % 64 == 0); out_panel: out is written in dense panel form (then C % 256 == 0);
+// in_panel (may be NULL): also a panel-form copy of `in` itself (then R % 256 == 0)
+int launch_transpose(const void* in, int R, int C, void* out, int out_panel, void* in_panel, hipStream_t s);
 
 }  // namespace ffn24
