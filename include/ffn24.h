@@ -11,8 +11,8 @@
  *     stream; they never synchronise, and they allocate nothing (ffn24_ctx_create is the only allocating call).
  *   - Return value: FFN24_OK (0) or a negative FFN24_ERR_* code; ffn24_strerror() names it.  Bad arguments are
  *     rejected before anything is launched; nothing aborts or throws across this boundary.
- *   - Element type: bf16 (FFN24_BF16) with fp32 accumulation.  FFN24_FP8_E4M3 is reserved and currently
- *     returns FFN24_ERR_DTYPE.
+ *   - Element type: bf16 (FFN24_BF16) with fp32 accumulation; or, forward only, fp8 (FFN24_FP8_E4M3, the OCP e4m3
+ *     format, per-tensor fp32 scales, fp32 accumulation, bf16 result; see ffn24_set_scales).
  *   - Outputs are overwritten, never accumulated into.
  *
  * Compressed 2:4 form used everywhere (the paper leaves the encoding open; this one equals the index operand of
@@ -62,6 +62,15 @@ typedef struct ffn24_ctx ffn24_ctx; /* opaque; owns only its device workspace */
  * 2 T F with FFN24_DENSE (6 T F more when FFN24_TRAINING is set too); plus 2 T F with FFN24_DEBUG_DUMP_H.
  * *out is untouched on error. */
 FFN24_API int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dtype dtype, int flags);
+
+/* Scales of an FFN24_FP8_E4M3 context (all 1 after creation), each > 0:  the caller hands in X8 = e4m3(X / sx),
+ * W1_8 = e4m3(W1 / sw1), W2_8 = e4m3(W2 / sw2) as byte tensors of the usual shapes, and the kernels compute
+ *   Z = sx sw1 (X8 W1_8) + b1;  H = bf16(max(0, Z)^2);  keep-2-of-4 on the bf16 words (as in the bf16 path);
+ *   Hc8 = e4m3(kept / sh), saturating at +-448, round to nearest even;  Y = bf16(sh sw2 (Hc8 . W2_8))
+ * (paper Sec. 2: activation, then sparsification, then FP8 quantisation; per-tensor scales instead of the paper's
+ * row-wise ones).  Saved tensors 0 and 1 are then bytes: Hc8 [T][F/2], meta [T][F/8]; tensor 7 is H8 [T][F].
+ * An fp8 context supports ffn24_fwd and ffn_fwd only (no FFN24_TRAINING: FFN24_ERR_DTYPE). */
+FFN24_API int ffn24_set_scales(ffn24_ctx* ctx, float sx, float sw1, float sh, float sw2);
 
 /* Free the workspace.  The caller must have synchronised every stream that used the context.  NULL is allowed. */
 FFN24_API int ffn24_ctx_destroy(ffn24_ctx* ctx);

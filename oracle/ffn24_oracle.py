@@ -407,12 +407,12 @@ def ffn_bwd(fwd: dict, dY, st=Bf16):
 # --------------------------------------------------------------------------------------
 
 
-def ffn24_fwd_fp8(X, W1, b1, W2, sx, sw1, sh, sw2):
-    """Per-tensor-scaled e4m3 variant.  Xq = e4m3(X / sx), W1q = e4m3(W1 / sw1);
-    Z = sx sw1 (Xq W1q) + b1;  the 2:4 pick is made on bf16(H) exactly as in ffn24_fwd;
-    the kept values are then quantised, Hc8 = e4m3(Hc / sh);  Y = sh sw2 (Hc8 . e4m3(W2 / sw2))."""
-    Xq = round_e4m3(np.asarray(X, np.float32) / np.float32(sx)).astype(np.float64)
-    W1q = round_e4m3(np.asarray(W1, np.float32) / np.float32(sw1)).astype(np.float64)
+def ffn24_fwd_fp8_codes(X8, W1_8, b1, W2_8, sx, sw1, sh, sw2):
+    """The fp8 forward on operands that are already e4m3 codes (uint8): X8 [T,D], W1_8 [D,F], W2_8 [F,D].
+    Z = sx sw1 (X8 W1_8) + b1;  the 2:4 pick is made on bf16(H) exactly as in ffn24_fwd;  the kept values are then
+    quantised, Hc8 = e4m3(Hc / sh);  Y = sh sw2 (Hc8 . W2_8)."""
+    Xq = E4M3_VALUES[np.ascontiguousarray(X8, dtype=np.uint8)]
+    W1q = E4M3_VALUES[np.ascontiguousarray(W1_8, dtype=np.uint8)]
     Z = (Xq @ W1q) * (float(sx) * float(sw1))
     if b1 is not None:
         Z = Z + np.asarray(b1, dtype=np.float64)[None, :]
@@ -421,11 +421,35 @@ def ffn24_fwd_fp8(X, W1, b1, W2, sx, sw1, sh, sw2):
     Hc_w, meta = sparsify24(f32_to_bf16_bits(Hq))
     Hc = bf16_bits_to_f32(Hc_w)
     Hc8_bits = f32_to_e4m3_bits(Hc / np.float32(sh))
-    Hc8 = e4m3_bits_to_f32(Hc8_bits)
-    W2q = round_e4m3(np.asarray(W2, np.float32) / np.float32(sw2)).astype(np.float64)
-    H24_8 = decompress24(Hc8, meta).astype(np.float64)
+    Hc8 = E4M3_VALUES[Hc8_bits]
+    W2q = E4M3_VALUES[np.ascontiguousarray(W2_8, dtype=np.uint8)]
+    H24_8 = decompress24(Hc8, meta)
     Y = (H24_8 @ W2q) * (float(sh) * float(sw2))
     return {"Z": Z, "Hq": Hq, "meta": meta, "Hc8_bits": Hc8_bits, "Y": Y}
+
+
+def ffn24_fwd_fp8(X, W1, b1, W2, sx, sw1, sh, sw2):
+    """Per-tensor-scaled e4m3 variant (order of Sec. 2: activation, sparsification, then FP8 quantisation).
+    Xq = e4m3(X / sx), W1q = e4m3(W1 / sw1), W2q = e4m3(W2 / sw2), then ffn24_fwd_fp8_codes."""
+    X8 = f32_to_e4m3_bits(np.asarray(X, np.float32) / np.float32(sx))
+    W1_8 = f32_to_e4m3_bits(np.asarray(W1, np.float32) / np.float32(sw1))
+    W2_8 = f32_to_e4m3_bits(np.asarray(W2, np.float32) / np.float32(sw2))
+    return ffn24_fwd_fp8_codes(X8, W1_8, b1, W2_8, sx, sw1, sh, sw2)
+
+
+def ffn_fwd_fp8(X, W1, b1, W2, sx, sw1, sh, sw2):
+    """Dense counterpart of ffn24_fwd_fp8 (no pruning): every activation is quantised, H8 = e4m3(bf16(H) / sh)."""
+    Xq = round_e4m3(np.asarray(X, np.float32) / np.float32(sx)).astype(np.float64)
+    W1q = round_e4m3(np.asarray(W1, np.float32) / np.float32(sw1)).astype(np.float64)
+    Z = (Xq @ W1q) * (float(sx) * float(sw1))
+    if b1 is not None:
+        Z = Z + np.asarray(b1, dtype=np.float64)[None, :]
+    R, H = _relu2(Z, Bf16)
+    Hq = round_bf16(H)
+    H8_bits = f32_to_e4m3_bits(Hq / np.float32(sh))
+    W2q = round_e4m3(np.asarray(W2, np.float32) / np.float32(sw2)).astype(np.float64)
+    Y = (e4m3_bits_to_f32(H8_bits).astype(np.float64) @ W2q) * (float(sh) * float(sw2))
+    return {"Z": Z, "Hq": Hq, "H8_bits": H8_bits, "Y": Y}
 
 
 # --------------------------------------------------------------------------------------

@@ -17,6 +17,8 @@ struct ffn24_ctx {
   int64_t T, D, F;
   int flags;
   int device;
+  int f8;                      // element type FFN24_FP8_E4M3 (forward only)
+  float sx, sw1, sh, sw2;      // per-tensor scales of the fp8 path
   // workspace (device)
   void* Hc; uint8_t* meta; void* dZc; void* Hc_t; uint8_t* meta_t; void* dZc_t; void* Hdbg; void* Hd; void* dZd;
   void* W1t; void* W2t; void* Xt; void* dYt; void* Hd_t; void* dZd_t;   // K-contiguous copies of GEMM operands
@@ -77,21 +79,25 @@ const char* ffn24_strerror(int code) {
 
 int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dtype dtype, int flags) {
   if (!out) return FFN24_ERR_NULL;
-  if (dtype != FFN24_BF16) return FFN24_ERR_DTYPE;
+  if (dtype != FFN24_BF16 && dtype != FFN24_FP8_E4M3) return FFN24_ERR_DTYPE;
+  const bool f8 = dtype == FFN24_FP8_E4M3;
+  if (f8 && (flags & FFN24_TRAINING)) return FFN24_ERR_DTYPE;   // the fp8 path is forward only
   if (T <= 0 || D <= 0 || F <= 0 || T % 256 || D % 256 || F % 256) return FFN24_ERR_SHAPE;
   if (T > (1 << 20) || D > (1 << 20) || F > (1 << 20)) return FFN24_ERR_SHAPE;
   ffn24_ctx* c = new (std::nothrow) ffn24_ctx();
   if (!c) return FFN24_ERR_HIP;
-  c->T = T; c->D = D; c->F = F; c->flags = flags;
+  c->T = T; c->D = D; c->F = F; c->flags = flags; c->f8 = f8;
+  c->sx = c->sw1 = c->sh = c->sw2 = 1.f;
   if (hipGetDevice(&c->device) != hipSuccess) { delete c; return FFN24_ERR_HIP; }
+  const size_t es = f8 ? 1 : 2;   // bytes per stored element
   size_t tf = (size_t)T * (size_t)F, df = (size_t)D * (size_t)F, td = (size_t)T * (size_t)D;
-  bool ok = hipMalloc(&c->Hc, tf) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->meta), tf / 8) == hipSuccess &&
-            hipMalloc(&c->W1t, 2 * df) == hipSuccess && hipMalloc(&c->W2t, 2 * df) == hipSuccess;
+  bool ok = hipMalloc(&c->Hc, tf * es / 2) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->meta), tf / 8) == hipSuccess &&
+            hipMalloc(&c->W1t, es * df) == hipSuccess && hipMalloc(&c->W2t, es * df) == hipSuccess;
   if (ok && (flags & FFN24_TRAINING))
     ok = hipMalloc(&c->dZc, tf) == hipSuccess && hipMalloc(&c->Hc_t, tf) == hipSuccess &&
          hipMalloc(reinterpret_cast<void**>(&c->meta_t), tf / 8) == hipSuccess && hipMalloc(&c->dZc_t, tf) == hipSuccess &&
          hipMalloc(&c->Xt, 2 * td) == hipSuccess && hipMalloc(&c->dYt, 2 * td) == hipSuccess && hipMalloc(&c->W2p, 2 * df) == hipSuccess;
-  if (ok && (flags & FFN24_DENSE)) ok = hipMalloc(&c->Hd, 2 * tf) == hipSuccess;
+  if (ok && (flags & FFN24_DENSE)) ok = hipMalloc(&c->Hd, es * tf) == hipSuccess;
   if (ok && (flags & FFN24_DENSE) && (flags & FFN24_TRAINING))
     ok = hipMalloc(&c->dZd, 2 * tf) == hipSuccess && hipMalloc(&c->Hd_t, 2 * tf) == hipSuccess && hipMalloc(&c->dZd_t, 2 * tf) == hipSuccess;
   if (ok && (flags & FFN24_DEBUG_DUMP_H)) ok = hipMalloc(&c->Hdbg, 2 * tf) == hipSuccess;
@@ -107,6 +113,14 @@ int ffn24_ctx_destroy(ffn24_ctx* c) {
   int bad = free_all(c);
   delete c;
   return bad ? FFN24_ERR_HIP : FFN24_OK;
+}
+
+int ffn24_set_scales(ffn24_ctx* c, float sx, float sw1, float sh, float sw2) {
+  if (!c) return FFN24_ERR_NULL;
+  if (!c->f8) return FFN24_ERR_DTYPE;
+  if (!(sx > 0.f) || !(sw1 > 0.f) || !(sh > 0.f) || !(sw2 > 0.f)) return FFN24_ERR_SHAPE;
+  c->sx = sx; c->sw1 = sw1; c->sh = sh; c->sw2 = sw2;
+  return FFN24_OK;
 }
 
 int ffn24_set_profiling(ffn24_ctx* c, int on) {
@@ -127,10 +141,12 @@ int ffn24_kernel_ms(ffn24_ctx* c, int k, float* ms) {
 int ffn24_saved_bytes(ffn24_ctx* c, int which, int64_t* nbytes) {
   if (!c || !nbytes) return FFN24_ERR_NULL;
   int64_t tf = c->T * c->F;
+  const int64_t es = c->f8 ? 1 : 2;
   switch (which) {
-    case 0: case 2: case 3: case 5: *nbytes = tf; break;
+    case 0: case 2: case 3: case 5: *nbytes = tf * es / 2; break;
     case 1: case 4: *nbytes = tf / 8; break;
-    case 6: case 7: case 8: *nbytes = 2 * tf; break;
+    case 6: *nbytes = 2 * tf; break;
+    case 7: case 8: *nbytes = es * tf; break;
     default: return FFN24_ERR_SHAPE;
   }
   return FFN24_OK;
@@ -159,7 +175,12 @@ int ffn24_copy_saved(ffn24_ctx* c, int which, void* dst, int64_t dst_bytes, void
     default: src = c->dZd; break;
   }
   if (!src) return FFN24_ERR_STATE;
-  if (piece) return launch_unpanel(src, rows, K, piece, dst, s) ? FFN24_ERR_HIP : FFN24_OK;
+  if (piece) {
+    // a piece covers 64 k (bf16) or 128 k (fp8, whose metadata pieces are twice as long)
+    const int npanels = c->f8 ? K / 128 : K / 64;
+    if (c->f8 && piece == 8) piece = 16;
+    return launch_unpanel(src, rows, npanels, piece, dst, s) ? FFN24_ERR_HIP : FFN24_OK;
+  }
   return hipMemcpyAsync(dst, src, (size_t)need, hipMemcpyDeviceToDevice, s) == hipSuccess ? FFN24_OK : FFN24_ERR_HIP;
 }
 
@@ -198,6 +219,16 @@ int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, cons
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   c->have_fwd24 = 0;
+  if (c->f8) {
+    { Timed t(c, K_TR_W, s);
+      int rc1 = launch_transpose8(W1, D, F, c->W1t, 1, s);
+      if (t.done(rc1 ? rc1 : launch_transpose8(W2, F, D, c->W2t, 0, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_UP, s);
+      if (t.done(launch_up_prune24_f8(c->W1t, X, b1, T, D, F, c->sx * c->sw1, c->sh, c->Hc, c->meta, c->Hdbg, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_DOWN, s);
+      if (t.done(launch_sp_rowmajor_f8(c->Hc, c->meta, 1, c->W2t, T, D, F, c->sh * c->sw2, Y, s))) return FFN24_ERR_HIP; }
+    return FFN24_OK;
+  }
   { Timed t(c, K_TR_W, s);
     int rc1 = launch_transpose(W1, D, F, c->W1t, 1, nullptr, s);
     if (t.done(rc1 ? rc1 : launch_transpose(W2, F, D, c->W2t, 0, c->W2p, s))) return FFN24_ERR_HIP; }
@@ -234,6 +265,16 @@ int ffn_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const 
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   c->have_fwd_dense = 0;
+  if (c->f8) {
+    { Timed t(c, K_TR_W, s);
+      int rc1 = launch_transpose8(W1, D, F, c->W1t, 1, s);
+      if (t.done(rc1 ? rc1 : launch_transpose8(W2, F, D, c->W2t, 0, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, KD_UP, s);
+      if (t.done(launch_up_relu2_f8(c->W1t, X, b1, T, D, F, c->sx * c->sw1, c->sh, c->Hd, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, KD_DOWN, s);
+      if (t.done(launch_dense_rowmajor_f8(c->Hd, c->W2t, T, D, F, c->sh * c->sw2, Y, s))) return FFN24_ERR_HIP; }
+    return FFN24_OK;
+  }
   { Timed t(c, K_TR_W, s);
     int rc1 = launch_transpose(W1, D, F, c->W1t, 1, nullptr, s);
     if (t.done(rc1 ? rc1 : launch_transpose(W2, F, D, c->W2t, 0, c->W2p, s))) return FFN24_ERR_HIP; }

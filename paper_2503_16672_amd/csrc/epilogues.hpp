@@ -211,4 +211,112 @@ struct EpiDGather {
   }
 };
 
+// ------------------------------------------------------------------------------------------------
+// fp8 (e4m3) forward: per-tensor scales; order of Sec. 2: activation, sparsification, then FP8 quantisation
+// ------------------------------------------------------------------------------------------------
+
+// Saturating round-to-nearest-even conversion of two floats to e4m3 (the conversion instruction alone turns values
+// beyond the format's largest finite number, 448, into NaN codes).
+__device__ __forceinline__ uint32_t cvt_e4m3x2(float lo, float hi, uint32_t old, bool high_half) {
+  lo = __builtin_fminf(__builtin_fmaxf(lo, -448.f), 448.f);
+  hi = __builtin_fminf(__builtin_fmaxf(hi, -448.f), 448.f);
+  return high_half ? (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(lo, hi, (int)old, true)
+                   : (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(lo, hi, (int)old, false);
+}
+
+// fp8 up-projection: z = zscale * acc + b1 (zscale = sx * sw1); h = bf16(max(0, z)^2); the keep-2-of-4 pick is made on
+// the bf16 words exactly as in EpiPrune24; the kept values are then quantised, e4m3(h / sh).
+//   Hc8, meta: panel form of the fp8 operand: piece = 64 stored bytes + 16 metadata bytes for 128 features of a token;
+//   a lane's 64 features are one half of a piece.
+struct EpiPrune24F8 {
+  struct Args { uint8_t* Hc8; uint8_t* meta; __bf16* Hdbg; const float* b1; int F; float zscale; float sh; };
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+#pragma unroll
+    for (int ni = 0; ni < 4; ni++) {
+      size_t t = (size_t)(n_lane + ni);
+      uint32_t q8[8];
+      uint32_t nib[2] = {0u, 0u};
+#pragma unroll
+      for (int mi = 0; mi < 4; mi++) {
+        uint32_t hpk[8];
+#pragma unroll
+        for (int d = 0; d < 8; d++) {
+          float b0 = e.b1 ? e.b1[m_lane + 16 * mi + 2 * d] : 0.f;
+          float b1v = e.b1 ? e.b1[m_lane + 16 * mi + 2 * d + 1] : 0.f;
+          float r0 = fmaxf(acc[mi][ni][2 * d] * e.zscale + b0, 0.f);
+          float r1 = fmaxf(acc[mi][ni][2 * d + 1] * e.zscale + b1v, 0.f);
+          hpk[d] = pack_bf16x2(r0 * r0, r1 * r1);
+        }
+        if (e.Hdbg) {
+          __bf16* row = e.Hdbg + t * e.F + m_lane + 16 * mi;
+          *reinterpret_cast<u32x4*>(row) = u32x4{hpk[0], hpk[1], hpk[2], hpk[3]};
+          *reinterpret_cast<u32x4*>(row + 8) = u32x4{hpk[4], hpk[5], hpk[6], hpk[7]};
+        }
+#pragma unroll
+        for (int a = 0; a < 4; a++) {
+          uint32_t k0 = ((hpk[2 * a] & 0xFFFFu) << 2) | 3u;
+          uint32_t k1 = ((hpk[2 * a] >> 16) << 2) | 2u;
+          uint32_t k2 = ((hpk[2 * a + 1] & 0xFFFFu) << 2) | 1u;
+          uint32_t k3 = ((hpk[2 * a + 1] >> 16) << 2);
+          uint32_t kf, ks;
+          uint32_t n4 = pick24_keys(k0, k1, k2, k3, kf, ks);
+          int gi = 4 * mi + a;
+          float v0 = __builtin_bit_cast(float, (kf >> 2) << 16) / e.sh;
+          float v1 = __builtin_bit_cast(float, (ks >> 2) << 16) / e.sh;
+          // group gi's two stored bytes are bytes 2 gi, 2 gi + 1 of the lane's 32
+          q8[gi >> 1] = cvt_e4m3x2(v0, v1, (gi & 1) ? q8[gi >> 1] : 0u, (gi & 1) != 0);
+          nib[gi >> 3] |= n4 << (4 * (gi & 7));
+        }
+      }
+      size_t piece = a24_piece((int)t, m_lane >> 7, e.F >> 7);
+      int half = (m_lane >> 6) & 1;
+      uint8_t* hrow = e.Hc8 + piece * 64 + 32 * half;
+      *reinterpret_cast<u32x4*>(hrow) = u32x4{q8[0], q8[1], q8[2], q8[3]};
+      *reinterpret_cast<u32x4*>(hrow + 16) = u32x4{q8[4], q8[5], q8[6], q8[7]};
+      *reinterpret_cast<u32x2*>(e.meta + piece * 16 + 8 * half) = u32x2{nib[0], nib[1]};
+    }
+  }
+};
+
+// fp8 dense up-projection (baseline): H8[t][f] = e4m3( bf16(max(0, zscale acc + b1)^2) / sh ), stored [T][F] bytes.
+struct EpiRelu2F8 {
+  struct Args { uint8_t* H8; const float* b1; int F; float zscale; float sh; };
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+#pragma unroll
+    for (int ni = 0; ni < 4; ni++) {
+      uint8_t* row = e.H8 + (size_t)(n_lane + ni) * e.F + m_lane;
+#pragma unroll
+      for (int mi = 0; mi < 4; mi++) {
+        uint32_t q[4];
+#pragma unroll
+        for (int d = 0; d < 8; d++) {
+          float b0 = e.b1 ? e.b1[m_lane + 16 * mi + 2 * d] : 0.f;
+          float b1v = e.b1 ? e.b1[m_lane + 16 * mi + 2 * d + 1] : 0.f;
+          float r0 = fmaxf(acc[mi][ni][2 * d] * e.zscale + b0, 0.f);
+          float r1 = fmaxf(acc[mi][ni][2 * d + 1] * e.zscale + b1v, 0.f);
+          uint32_t hp = pack_bf16x2(r0 * r0, r1 * r1);
+          q[d >> 1] = cvt_e4m3x2(bf16_lo_to_f32(hp) / e.sh, bf16_hi_to_f32(hp) / e.sh, (d & 1) ? q[d >> 1] : 0u, (d & 1) != 0);
+        }
+        *reinterpret_cast<u32x4*>(row + 16 * mi) = u32x4{q[0], q[1], q[2], q[3]};
+      }
+    }
+  }
+};
+
+// C[m][n] = bf16(scale * acc), n contiguous (fp8 down-projection: scale = sh * sw2).
+struct EpiRowMajorScaled {
+  struct Args { __bf16* C; int ldc; float scale; };
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+#pragma unroll
+    for (int mi = 0; mi < 4; mi++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        u32x2 o;
+        o[0] = pack_bf16x2(acc[mi][0][v] * e.scale, acc[mi][1][v] * e.scale);
+        o[1] = pack_bf16x2(acc[mi][2][v] * e.scale, acc[mi][3][v] * e.scale);
+        *reinterpret_cast<u32x2*>(e.C + (size_t)(m_lane + 16 * mi + v) * e.ldc + n_lane) = o;
+      }
+  }
+};
+
 }  // namespace ffn24

@@ -80,11 +80,15 @@ __host__ __device__ __forceinline__ size_t a24_piece(int r, int kp, int npanels)
   return ((size_t)(r >> 8) * npanels + kp) * 256 + (r & 255);
 }
 
-template <bool SPARSE>
+// Stage geometry.  Everything is laid out in bytes, and an fp8 kernel has exactly the byte geometry of its bf16
+// counterpart with twice the k per byte: the LDS tiles, swizzles, DMA plan and fragment addresses are shared.
+template <bool SPARSE, bool F8 = false>
 struct Geo {
-  static constexpr int BK = SPARSE ? 64 : 32;            // dense k per stage
-  static constexpr int A_BYTES = 256 * 64;               // 64-byte rows: 32 dense k, or 32 stored values of 64 k
-  static constexpr int META_BYTES = SPARSE ? 256 * 8 : 0;
+  static constexpr int ESIZE = F8 ? 1 : 2;
+  static constexpr int BK = (SPARSE ? 128 : 64) / ESIZE;  // dense k per stage (B rows of 128 / 64 bytes)
+  static constexpr int A_BYTES = 256 * 64;               // 64-byte rows: dense k, or the stored values of twice as many k
+  static constexpr int META_ROW = SPARSE ? (F8 ? 16 : 8) : 0;   // metadata bytes per row and stage (4 bits per group of 4 k)
+  static constexpr int META_BYTES = 256 * META_ROW;
   static constexpr int B_ROW = SPARSE ? 128 : 64;
   static constexpr int B_BYTES = 256 * B_ROW;
   static constexpr int META_OFF = A_BYTES;
@@ -92,7 +96,8 @@ struct Geo {
   static constexpr int STAGE = A_BYTES + META_BYTES + B_BYTES;
   static constexpr int NB = SPARSE ? 3 : 4;              // ring depth
   static constexpr int LDS_TOTAL = NB * STAGE;
-  static constexpr int NDMA = SPARSE ? 4 + 2 + 8 : 4 + 4;  // DMA instructions per wave and stage
+  static constexpr int NM = SPARSE ? (F8 ? 1 : 2) : 0;   // metadata DMA instructions per wave and stage
+  static constexpr int NDMA = SPARSE ? 4 + NM + 8 : 4 + 4;  // DMA instructions per wave and stage
 };
 
 // LDS row -> row of the 256-row block tile (inverse of the permutation described above)
@@ -128,9 +133,9 @@ __device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC
 // ------------------------------------------------------------------------------------------------
 // global -> LDS DMA plan of one wave
 // ------------------------------------------------------------------------------------------------
-template <bool SPARSE>
+template <bool SPARSE, bool F8 = false>
 struct Dma {
-  using G = Geo<SPARSE>;
+  using G = Geo<SPARSE, F8>;
   const char* a;      // block's first A row (uniform)
   const char* am;     // metadata
   const char* b;
@@ -141,38 +146,44 @@ struct Dma {
   __device__ __forceinline__ void init(const GemmArgs& g, int m0, int n0, int tid) {
     int lane = tid & 63;
     wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    uint32_t a_row = SPARSE ? (uint32_t)g.K : (uint32_t)g.K * 2u;   // bytes per A row in memory
+    const uint32_t b_row = (uint32_t)g.K * G::ESIZE;                 // bytes per B row in memory
+    const uint32_t a_row = SPARSE ? b_row / 2 : b_row;               // bytes per A row (stored values only if sparse)
     a = static_cast<const char*>(g.A) + (size_t)m0 * a_row;
-    b = static_cast<const char*>(g.B) + (size_t)n0 * g.K * 2;
+    b = static_cast<const char*>(g.B) + (size_t)n0 * b_row;
     am = SPARSE ? reinterpret_cast<const char*>(g.Ameta) + (size_t)m0 * (g.K / 8) : nullptr;
     // a block tile's 256 rows occupy the same byte range in both forms; only the order of the pieces inside differs
     const bool panel = g.a_panel != 0;
-    const uint32_t a_pitch = panel ? 64u : a_row, m_pitch = panel ? 8u : (uint32_t)(g.K / 8);
+    const uint32_t a_pitch = panel ? 64u : a_row, m_pitch = panel ? (uint32_t)G::META_ROW : (uint32_t)(g.K / 8);
     a_stage = panel ? 256u * 64u : 64u;
-    m_stage = panel ? 256u * 8u : 8u;
+    m_stage = panel ? 256u * G::META_ROW : (uint32_t)G::META_ROW;
 #pragma unroll
     for (int j = 0; j < 4; j++) {
       int p = 64 * wave + 16 * j + (lane >> 2);
       int c = (lane & 3) ^ swz4(p);
       va[j] = (uint32_t)unperm_m(p) * a_pitch + c * 16;
-      if constexpr (!SPARSE) vb[j] = (uint32_t)unperm_n(p) * ((uint32_t)g.K * 2u) + c * 16;
+      if constexpr (!SPARSE) vb[j] = (uint32_t)unperm_n(p) * b_row + c * 16;
     }
     if constexpr (SPARSE) {
 #pragma unroll
       for (int j = 0; j < 8; j++) {
         int p = 64 * wave + 8 * j + (lane >> 3);
         int c = (lane & 7) ^ swz8(p);
-        vb[j] = (uint32_t)unperm_n(p) * ((uint32_t)g.K * 2u) + c * 16;
+        vb[j] = (uint32_t)unperm_n(p) * b_row + c * 16;
       }
+      if constexpr (F8) {
+        vm[0] = (uint32_t)unperm_m(64 * wave + lane) * m_pitch;      // one row's 16 metadata bytes per lane
+        vm[1] = 0;
+      } else {
 #pragma unroll
-      for (int j = 0; j < 2; j++) {
-        int d = 64 * (2 * wave + j) + lane;
-        vm[j] = (uint32_t)unperm_m(d >> 1) * m_pitch + 4 * (d & 1);
+        for (int j = 0; j < 2; j++) {
+          int d = 64 * (2 * wave + j) + lane;
+          vm[j] = (uint32_t)unperm_m(d >> 1) * m_pitch + 4 * (d & 1);
+        }
       }
     }
   }
 
-  // DMA instruction J of the stage whose K offset is kt*BK, into the stage buffer at `buf` (uniform LDS pointer)
+  // DMA instruction J of stage kt into the stage buffer at `buf` (uniform LDS pointer)
   template <int J>
   __device__ __forceinline__ void issue(int kt, char* buf) const {
     if constexpr (J < 4) {
@@ -180,11 +191,14 @@ struct Dma {
     } else if constexpr (!SPARSE) {
       constexpr int j = J - 4;
       __builtin_amdgcn_global_load_lds((glb_char*)(b + (size_t)kt * 64 + vb[j]), (lds_char*)(buf + G::B_OFF + (4 * wave + j) * 1024), 16, 0, 0);
-    } else if constexpr (J < 6) {
+    } else if constexpr (J < 4 + G::NM) {
       constexpr int j = J - 4;
-      __builtin_amdgcn_global_load_lds((glb_char*)(am + (size_t)kt * m_stage + vm[j]), (lds_char*)(buf + G::META_OFF + (2 * wave + j) * 256), 4, 0, 0);
+      if constexpr (F8)
+        __builtin_amdgcn_global_load_lds((glb_char*)(am + (size_t)kt * m_stage + vm[0]), (lds_char*)(buf + G::META_OFF + wave * 1024), 16, 0, 0);
+      else
+        __builtin_amdgcn_global_load_lds((glb_char*)(am + (size_t)kt * m_stage + vm[j]), (lds_char*)(buf + G::META_OFF + (2 * wave + j) * 256), 4, 0, 0);
     } else {
-      constexpr int j = J - 6;
+      constexpr int j = J - 4 - G::NM;
       __builtin_amdgcn_global_load_lds((glb_char*)(b + (size_t)kt * 128 + vb[j]), (lds_char*)(buf + G::B_OFF + (8 * wave + j) * 1024), 16, 0, 0);
     }
   }
@@ -222,6 +236,21 @@ __device__ __forceinline__ void mfma_dense1(const FragD& f, f32x16 (&acc)[4][4])
   constexpr int mi = M >> 2, ni = M & 3;
   acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[mi], f.b[ni], acc[mi][ni], 0, 0, 0);
 }
+// fp8 e4m3, v_mfma_f32_32x32x64_f8f6f4: 32 operand bytes per lane, paired byte by byte between A and B (measured:
+// any assignment of the 64 k to (lane half, byte) works if both operands use the same one).  The two 16-byte
+// fragments of a stage (S = 0 and S = 1 above) are exactly one such operand, so a 64-byte-row stage is one K step.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ i32x8 cat16(const bf16x8& lo, const bf16x8& hi) {
+  i32x4 l = __builtin_bit_cast(i32x4, lo), h = __builtin_bit_cast(i32x4, hi);
+  return __builtin_shufflevector(l, h, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+template <int M>
+__device__ __forceinline__ void mfma_dense_f8(const FragD& f0, const FragD& f1, f32x16 (&acc)[4][4]) {
+  constexpr int mi = M >> 2, ni = M & 3;
+  acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(cat16(f0.a[mi], f1.a[mi]), cat16(f0.b[ni], f1.b[ni]), acc[mi][ni],
+                                                                 0, 0, 0, 0, 0, 0);   // both operands e4m3, unscaled
+}
 
 // Sparse: the stage's K window of 64 = four 16-wide windows w.  Instruction S (0,1) gives lane half q the window
 // 2q+S, so a lane's two instructions use 32 consecutive stored-value bytes and one 32-bit metadata word (ABID = S
@@ -231,28 +260,44 @@ struct FragS {
   bf16x8 a[4];
   bf16x8 blo[4], bhi[4];
 };
-template <int I>
-__device__ __forceinline__ void load_idx_sparse1(const char* buf, const LaneCtx& L, uint32_t (&idx)[4]) {
-  idx[I] = *reinterpret_cast<const uint32_t*>(buf + Geo<true>::META_OFF + (L.wy * 128 + L.rho + 32 * I) * 8 + 4 * L.h);
+// Metadata of a lane for the stage's two instructions: bf16 one 32-bit word (16 bits per instruction, picked by
+// ABID); fp8 (twice the groups per stored byte) two words, one per instruction.
+template <bool F8> struct IdxWords { uint32_t w[F8 ? 2 : 1]; };
+template <bool F8, int I>
+__device__ __forceinline__ void load_idx_sparse1(const char* buf, const LaneCtx& L, IdxWords<F8> (&idx)[4]) {
+  const char* p = buf + Geo<true, F8>::META_OFF + (L.wy * 128 + L.rho + 32 * I) * Geo<true, F8>::META_ROW;
+  if constexpr (F8) {
+    u32x2 v = *reinterpret_cast<const u32x2*>(p + 8 * L.h);
+    idx[I].w[0] = v[0]; idx[I].w[1] = v[1];
+  } else {
+    idx[I].w[0] = *reinterpret_cast<const uint32_t*>(p + 4 * L.h);
+  }
 }
 // fragment I of instruction S: I < 4 -> a[I]; 4..7 -> low half of b[I-4]; 8..11 -> high half of b[I-8]
-template <int S, int I>
+template <bool F8, int S, int I>
 __device__ __forceinline__ void load_frag_sparse1(const char* buf, const LaneCtx& L, FragS& f) {
   constexpr int i = I & 3;
   if constexpr (I < 4) {
     f.a[i] = *reinterpret_cast<const bf16x8*>(buf + L.a_row64 + i * (32 * 64) + (((2 * L.h + S) ^ L.sw4) << 4));
   } else {
     int sw = L.sw8 ^ ((i & 1) << 2);
-    const char* row = buf + Geo<true>::B_OFF + L.b_row128 + i * (32 * 128);
+    const char* row = buf + Geo<true, F8>::B_OFF + L.b_row128 + i * (32 * 128);
     if constexpr (I < 8) f.blo[i] = *reinterpret_cast<const bf16x8*>(row + (((2 * S + L.h) ^ sw) << 4));
     else f.bhi[i] = *reinterpret_cast<const bf16x8*>(row + (((4 + 2 * S + L.h) ^ sw) << 4));
   }
 }
-template <int S, int M>
-__device__ __forceinline__ void mfma_sparse1(const FragS& f, const uint32_t (&idx)[4], f32x16 (&acc)[4][4]) {
+// fp8: v_smfmac_f32_32x32x64_fp8_fp8 has, byte for byte, the operand layout of the bf16 instruction (measured): A 16
+// stored bytes of the lane half's window, B the two 16-byte chunks, and a full 32-bit index word per instruction.
+template <bool F8, int S, int M>
+__device__ __forceinline__ void mfma_sparse1(const FragS& f, const IdxWords<F8> (&idx)[4], f32x16 (&acc)[4][4]) {
   constexpr int mi = M >> 2, ni = M & 3;
-  bf16x16 b = __builtin_shufflevector(f.blo[ni], f.bhi[ni], 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
-  acc[mi][ni] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(f.a[mi], b, acc[mi][ni], (int)idx[mi], 0, S);
+  if constexpr (F8) {
+    acc[mi][ni] = __builtin_amdgcn_smfmac_f32_32x32x64_fp8_fp8(__builtin_bit_cast(i32x4, f.a[mi]), cat16(f.blo[ni], f.bhi[ni]), acc[mi][ni],
+                                                               (int)idx[mi].w[S], 0, 0);
+  } else {
+    bf16x16 b = __builtin_shufflevector(f.blo[ni], f.bhi[ni], 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+    acc[mi][ni] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(f.a[mi], b, acc[mi][ni], (int)idx[mi].w[0], 0, S);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -279,10 +324,10 @@ __device__ __forceinline__ void tile_coords(int ntm, int ntn, int& tm, int& tn) 
 // Epilogue concept:  struct E { struct Args {...}; static __device__ void run(const Args&, acc, m_lane, n_lane); }
 //   m_lane = global row of acc[0][*][0] for this lane (its 64 rows are m_lane + 16*mi + v),
 //   n_lane = global column of acc[*][0][*] (its 4 columns are n_lane + ni).
-template <bool SPARSE, class Epi>
+template <bool SPARSE, class Epi, bool F8 = false>
 __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(GemmArgs g, typename Epi::Args ea) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  using G = Geo<SPARSE>;
+  using G = Geo<SPARSE, F8>;
   constexpr int NB = G::NB, NDMA = G::NDMA;
 
   int tid = threadIdx.x;
@@ -299,7 +344,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(GemmArgs g, typename
   L.sw4 = swz4(L.rho);
   L.sw8 = (L.rho & 7) ^ (L.rho >> 3);
 
-  Dma<SPARSE> dma;
+  Dma<SPARSE, F8> dma;
   dma.init(g, m0, n0, tid);
 
   f32x16 acc[4][4];
@@ -329,16 +374,16 @@ __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(GemmArgs g, typename
   // MODE 2: last stage -- no barrier, no next fragments
   if constexpr (SPARSE) {
     FragS f0, f1;
-    uint32_t idx[4];
-    static_for<4>([&](auto I) { load_idx_sparse1<I>(smem, L, idx); });
-    static_for<12>([&](auto I) { load_frag_sparse1<0, I>(smem, L, f0); });
+    IdxWords<F8> idx[4];
+    static_for<4>([&](auto I) { load_idx_sparse1<F8, I>(smem, L, idx); });
+    static_for<12>([&](auto I) { load_frag_sparse1<F8, 0, I>(smem, L, f0); });
     auto stage = [&](int kt, char* cur, char* nxt, auto mode) {
       constexpr int MODE = decltype(mode)::value;
-      uint32_t idx_n[4] = {0u, 0u, 0u, 0u};
+      IdxWords<F8> idx_n[4] = {};
       FFN24_FENCE();
       static_for<16>([&](auto M) {
-        mfma_sparse1<0, M>(f0, idx, acc);
-        if constexpr (M < 12) load_frag_sparse1<1, M>(cur, L, f1);
+        mfma_sparse1<F8, 0, M>(f0, idx, acc);
+        if constexpr (M < 12) load_frag_sparse1<F8, 1, M>(cur, L, f1);
         FFN24_FENCE();
       });
       if constexpr (MODE != 2) {
@@ -348,11 +393,11 @@ __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(GemmArgs g, typename
       }
       FFN24_FENCE();
       static_for<16>([&](auto M) {
-        mfma_sparse1<1, M>(f1, idx, acc);
+        mfma_sparse1<F8, 1, M>(f1, idx, acc);
         if constexpr (MODE == 0 && M < NDMA) dma.template issue<M>(kt + NB, cur);
         if constexpr (MODE != 2) {
-          if constexpr (M < 4) load_idx_sparse1<M>(nxt, L, idx_n);
-          if constexpr (M < 12) load_frag_sparse1<0, M>(nxt, L, f0);
+          if constexpr (M < 4) load_idx_sparse1<F8, M>(nxt, L, idx_n);
+          if constexpr (M < 12) load_frag_sparse1<F8, 0, M>(nxt, L, f0);
         }
         FFN24_FENCE();
       });
@@ -363,6 +408,49 @@ __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(GemmArgs g, typename
     auto advance = [&](int kt, auto mode) {
       int ns = slot + 1 == NB ? 0 : slot + 1;
       stage(kt, smem + slot * G::STAGE, smem + ns * G::STAGE, mode);
+      slot = ns;
+    };
+    int kt = 0;
+    for (; kt < nk - NB; kt++) advance(kt, std::integral_constant<int, 0>{});
+    for (; kt < nk - 1; kt++) advance(kt, std::integral_constant<int, 1>{});
+    advance(kt, std::integral_constant<int, 2>{});
+  } else if constexpr (F8) {
+    // Dense fp8: a stage is ONE K step of 16 matrix ops (64 cycles each).  The fragments of the whole next stage and
+    // the DMA of the stage that reuses this stage's buffer (its fragments are already in registers) ride on them;
+    // one barrier at the end of the stage.  Two fragment sets alternate.
+    FragD fr[2][2];
+    static_for<8>([&](auto I) { load_frag_dense1<0, I>(smem, L, fr[0][0]); });
+    static_for<8>([&](auto I) { load_frag_dense1<1, I>(smem, L, fr[0][1]); });
+    auto stage = [&](int kt, char* cur, char* nxt, auto par, auto mode) {
+      constexpr int P = decltype(par)::value, MODE = decltype(mode)::value;
+      FFN24_FENCE();
+      static_for<16>([&](auto M) {
+        mfma_dense_f8<M>(fr[P][0], fr[P][1], acc);
+        if constexpr (MODE == 0 && M < NDMA) dma.template issue<M>(kt + NB, cur);
+        if constexpr (MODE != 2) {
+          if constexpr (M < 8) load_frag_dense1<0, M>(nxt, L, fr[P ^ 1][0]);
+          else load_frag_dense1<1, M - 8>(nxt, L, fr[P ^ 1][1]);
+        }
+        FFN24_FENCE();
+      });
+      if constexpr (MODE != 2) {
+        // the next stage reads fragments of stage kt+2 from the first op on: it must have landed, everywhere
+        if constexpr (MODE == 0) wait_vmcnt<(NB - 2) * NDMA>(); else wait_vmcnt<0>();
+        wait_lgkmcnt0();
+        __builtin_amdgcn_s_barrier();
+      }
+      FFN24_FENCE();
+    };
+    // the loop above reads stage 1 during stage 0: the prologue's wait covered stage 0 only
+    if (npro == NB) wait_vmcnt<(NB - 2) * NDMA>(); else wait_vmcnt<0>();
+    wait_lgkmcnt0();
+    __builtin_amdgcn_s_barrier();
+    FFN24_FENCE();
+    int slot = 0;
+    auto advance = [&](int kt, auto mode) {
+      int ns = slot + 1 == NB ? 0 : slot + 1;
+      if (kt & 1) stage(kt, smem + slot * G::STAGE, smem + ns * G::STAGE, std::integral_constant<int, 1>{}, mode);
+      else stage(kt, smem + slot * G::STAGE, smem + ns * G::STAGE, std::integral_constant<int, 0>{}, mode);
       slot = ns;
     };
     int kt = 0;

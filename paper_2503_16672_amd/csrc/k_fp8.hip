@@ -1,0 +1,32 @@
+// fp8 (e4m3) forward kernels: dense-MFMA up-projection with the fused activation + 2:4 + quantisation epilogue, the
+// sparse-MFMA down-projection, and the dense fp8 baseline.
+#include "launch_impl.hpp"
+
+namespace ffn24 {
+
+int launch_up_prune24_f8(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, float zscale, float sh,
+                         void* Hc8, uint8_t* meta, void* Hdbg, hipStream_t s) {
+  GemmArgs g{W1t8, nullptr, X8, F, T, D, 1};
+  EpiPrune24F8::Args ea{static_cast<uint8_t*>(Hc8), meta, static_cast<__bf16*>(Hdbg), b1, F, zscale, sh};
+  return launch_gemm<false, EpiPrune24F8, true>(g, ea, s);
+}
+
+int launch_up_relu2_f8(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, float zscale, float sh, void* H8, hipStream_t s) {
+  GemmArgs g{W1t8, nullptr, X8, F, T, D, 1};
+  EpiRelu2F8::Args ea{static_cast<uint8_t*>(H8), b1, F, zscale, sh};
+  return launch_gemm<false, EpiRelu2F8, true>(g, ea, s);
+}
+
+int launch_sp_rowmajor_f8(const void* vals8, const uint8_t* meta, int a_panel, const void* B8, int M, int N, int K, float scale, void* C, hipStream_t s) {
+  GemmArgs g{vals8, meta, B8, M, N, K, a_panel};
+  EpiRowMajorScaled::Args ea{static_cast<__bf16*>(C), N, scale};
+  return launch_gemm<true, EpiRowMajorScaled, true>(g, ea, s);
+}
+
+int launch_dense_rowmajor_f8(const void* A8, const void* B8, int M, int N, int K, float scale, void* C, hipStream_t s) {
+  GemmArgs g{A8, nullptr, B8, M, N, K, 0};
+  EpiRowMajorScaled::Args ea{static_cast<__bf16*>(C), N, scale};
+  return launch_gemm<false, EpiRowMajorScaled, true>(g, ea, s);
+}
+
+}  // namespace ffn24

@@ -155,8 +155,8 @@ int launch_featurewise24(const void* Hc, const uint8_t* meta, const void* dZc, i
   return (int)hipGetLastError();
 }
 
-// Panel form -> row-major.  The operand has `rows` rows and K / 64 pieces of PIECE bytes per row (64: stored values,
-// 8: metadata); each work item moves 8 bytes.
+// Panel form -> row-major.  The operand has `rows` rows and `npanels` pieces of PIECE bytes per row (64: stored
+// values, 8 / 16: bf16 / fp8 metadata); each work item moves 8 bytes.
 template <int PIECE>
 __global__ void __launch_bounds__(256) unpanel_kernel(const u32x2* __restrict__ src, int rows, int npanels, u32x2* __restrict__ dst) {
   constexpr int W = PIECE / 8;                       // 8-byte words per piece
@@ -170,15 +170,12 @@ __global__ void __launch_bounds__(256) unpanel_kernel(const u32x2* __restrict__ 
   }
 }
 
-int launch_unpanel(const void* src, int rows, int K, int piece_bytes, void* dst, hipStream_t s) {
-  int npanels = K / 64;
+int launch_unpanel(const void* src, int rows, int npanels, int piece_bytes, void* dst, hipStream_t s) {
   size_t n = (size_t)rows * npanels * (piece_bytes / 8);
   size_t blocks = (n + 255) / 256;
   if (blocks > 256 * 32) blocks = 256 * 32;
-  if (piece_bytes == 64)
-    hipLaunchKernelGGL(unpanel_kernel<64>, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const u32x2*>(src), rows, npanels, static_cast<u32x2*>(dst));
-  else
-    hipLaunchKernelGGL(unpanel_kernel<8>, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const u32x2*>(src), rows, npanels, static_cast<u32x2*>(dst));
+  auto kern = piece_bytes == 64 ? unpanel_kernel<64> : (piece_bytes == 16 ? unpanel_kernel<16> : unpanel_kernel<8>);
+  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const u32x2*>(src), rows, npanels, static_cast<u32x2*>(dst));
   return (int)hipGetLastError();
 }
 
@@ -227,6 +224,36 @@ int launch_transpose(const void* in, int R, int C, void* out, int out_panel, voi
   auto kern = out_panel ? transpose_kernel<true> : transpose_kernel<false>;
   hipLaunchKernelGGL(kern, grid, dim3(256), 0, s, static_cast<const uint16_t*>(in), R, C, static_cast<uint16_t*>(out),
                      static_cast<uint16_t*>(in_panel));
+  return (int)hipGetLastError();
+}
+
+// Byte-matrix transpose (fp8 weights): out[c][r] = in[r][c], in [R][C], R and C multiples of 64.  One workgroup per
+// 64 x 64 tile; a work item reads 16 bytes of a row, scatters them into an LDS tile (pitch 68 bytes), then reads 16
+// bytes of a transposed row and writes them out.  OUT_PANEL: dense panel form, 64-byte pieces of 64 k (K = R).
+template <bool OUT_PANEL>
+__global__ void __launch_bounds__(256) transpose8_kernel(const uint8_t* __restrict__ in, int R, int C, uint8_t* __restrict__ out) {
+  __shared__ __attribute__((aligned(16))) uint8_t sT[64 * 68];
+  int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  int tid = threadIdx.x;
+  int ch = tid & 3, rr = tid >> 2;
+  u32x4 v = *reinterpret_cast<const u32x4*>(in + (size_t)(r0 + rr) * C + c0 + 16 * ch);
+#pragma unroll
+  for (int d = 0; d < 4; d++)
+#pragma unroll
+    for (int b = 0; b < 4; b++) sT[(16 * ch + 4 * d + b) * 68 + rr] = (uint8_t)(v[d] >> (8 * b));
+  __syncthreads();
+  int c = rr;   // transposed row
+  const uint32_t* src = reinterpret_cast<const uint32_t*>(&sT[c * 68 + 16 * ch]);
+  u32x4 o = {src[0], src[1], src[2], src[3]};
+  int r = r0 + 16 * ch;
+  if constexpr (OUT_PANEL) *reinterpret_cast<u32x4*>(out + a24_piece(c0 + c, r >> 6, R >> 6) * 64 + (r & 63)) = o;
+  else *reinterpret_cast<u32x4*>(out + (size_t)(c0 + c) * R + r) = o;
+}
+
+int launch_transpose8(const void* in, int R, int C, void* out, int out_panel, hipStream_t s) {
+  dim3 grid(C / 64, R / 64);
+  auto kern = out_panel ? transpose8_kernel<true> : transpose8_kernel<false>;
+  hipLaunchKernelGGL(kern, grid, dim3(256), 0, s, static_cast<const uint8_t*>(in), R, C, static_cast<uint8_t*>(out));
   return (int)hipGetLastError();
 }
 

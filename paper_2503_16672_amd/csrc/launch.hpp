@@ -22,15 +22,24 @@ int launch_dh_drelu(const void* W2, const void* dY, const void* H, int T, int D,
 // dense GEMMs: A [M][K], B [N][K]
 int launch_dense_rowmajor(const void* A, const void* B, int M, int N, int K, void* C, hipStream_t s);
 int launch_dense_colmajor(const void* A, const void* B, int M, int N, int K, void* Ct, hipStream_t s);
+// fp8 e4m3 forward (per-tensor scales).  W1t8 [F][D] in dense panel form (64-byte pieces = 64 k), X8 [T][D];
+// compressed activation in the fp8 panel form (64 stored bytes + 16 metadata bytes per 128 k); bf16 results.
+int launch_up_prune24_f8(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, float zscale, float sh,
+                         void* Hc8, uint8_t* meta, void* Hdbg, hipStream_t s);
+int launch_up_relu2_f8(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, float zscale, float sh, void* H8, hipStream_t s);
+int launch_sp_rowmajor_f8(const void* vals8, const uint8_t* meta, int a_panel, const void* B8, int M, int N, int K, float scale, void* C, hipStream_t s);
+int launch_dense_rowmajor_f8(const void* A8, const void* B8, int M, int N, int K, float scale, void* C, hipStream_t s);
 // streaming kernels
 int launch_sparsify24(const void* H, int64_t rows, int64_t cols, void* vals, uint8_t* meta, hipStream_t s);
 // panel: inputs and outputs are in panel form (the library's own buffers) instead of row-major
 int launch_featurewise24(const void* Hc, const uint8_t* meta, const void* dZc, int T, int F,
                          void* Hc_t, uint8_t* meta_t, void* dZc_t, int panel, hipStream_t s);
-// panel form -> row-major copy of a compressed operand: rows x (K/64) pieces of `piece_bytes` (64 values / 8 metadata)
-int launch_unpanel(const void* src, int rows, int K, int piece_bytes, void* dst, hipStream_t s);
+// panel form -> row-major copy of a compressed operand: rows x npanels pieces of `piece_bytes` (64 values / 8 or 16 metadata)
+int launch_unpanel(const void* src, int rows, int npanels, int piece_bytes, void* dst, hipStream_t s);
 // in [R][C] -> out [C][R] (R, C % 64 == 0); out_panel: out is written in dense panel form (then C % 256 == 0);
 // in_panel (may be NULL): also a panel-form copy of `in` itself (then R % 256 == 0)
 int launch_transpose(const void* in, int R, int C, void* out, int out_panel, void* in_panel, hipStream_t s);
+// the same for 1-byte elements (fp8): in [R][C] -> out [C][R]; out_panel: 64-byte pieces of 64 k
+int launch_transpose8(const void* in, int R, int C, void* out, int out_panel, hipStream_t s);
 
 }  // namespace ffn24

@@ -5,10 +5,10 @@
 
 namespace ffn24 {
 
-template <bool SPARSE, class Epi>
+template <bool SPARSE, class Epi, bool F8 = false>
 static int launch_gemm(const GemmArgs& g, const typename Epi::Args& ea, hipStream_t s) {
-  auto kern = gemm_kernel<SPARSE, Epi>;
-  constexpr int lds = Geo<SPARSE>::LDS_TOTAL;
+  auto kern = gemm_kernel<SPARSE, Epi, F8>;
+  constexpr int lds = Geo<SPARSE, F8>::LDS_TOTAL;
   // the opt-in for more than 64 KiB of dynamic LDS is per device; keep one flag per device
   static bool configured[64] = {};
   int dev = 0;

@@ -21,7 +21,7 @@ FFN24_DENSE = 2
 FFN24_DEBUG_DUMP_H = 4
 
 EXPORTS = (
-    "ffn24_ctx_create", "ffn24_ctx_destroy", "sparsify24", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd",
+    "ffn24_ctx_create", "ffn24_ctx_destroy", "ffn24_set_scales", "sparsify24", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd",
     "ffn_fwd", "ffn_bwd", "ffn24_saved_bytes", "ffn24_copy_saved", "ffn24_set_profiling", "ffn24_kernel_ms", "ffn24_strerror",
 )
 
@@ -47,6 +47,7 @@ def lib() -> ctypes.CDLL:
         vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
         L.ffn24_ctx_create.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ci, ci]
         L.ffn24_ctx_destroy.argtypes = [vp]
+        L.ffn24_set_scales.argtypes = [vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_float]
         L.sparsify24.argtypes = [vp, i64, i64, ci, vp, vp, vp]
         L.sparsify24_featurewise.argtypes = [vp, vp, vp, i64, i64, vp, vp, vp, vp]
         L.spmm24.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp]
@@ -121,7 +122,7 @@ class Context:
     """Owns an ffn24_ctx (the device workspace for one (T, D, F) problem)."""
 
     def __init__(self, T: int, D: int, F: int, flags: int = 0, dtype: int = FFN24_BF16):
-        self.T, self.D, self.F, self.flags = T, D, F, flags
+        self.T, self.D, self.F, self.flags, self.dtype = T, D, F, flags, dtype
         h = ctypes.c_void_p()
         _check(lib().ffn24_ctx_create(ctypes.byref(h), T, D, F, dtype, flags), "ffn24_ctx_create")
         self._h = h
@@ -137,6 +138,10 @@ class Context:
             self.close()
         except Exception:
             pass
+
+    def set_scales(self, sx: float, sw1: float, sh: float, sw2: float):
+        """Per-tensor scales of an fp8 context (see ffn24_set_scales in the header)."""
+        _check(lib().ffn24_set_scales(self._h, sx, sw1, sh, sw2), "ffn24_set_scales")
 
     def ffn24_fwd(self, X, W1, b1, W2, Y=None):
         Y = torch.empty((self.T, self.D), dtype=torch.bfloat16, device=X.device) if Y is None else Y
@@ -173,6 +178,8 @@ class Context:
     def saved(self, name: str) -> torch.Tensor:
         """Row-major copy of a saved tensor of the context (enqueued on the current stream)."""
         which, dtype, shape_fn = self._SAVED[name]
+        if self.dtype == FFN24_FP8_E4M3 and dtype == torch.bfloat16 and name != "H_dump":
+            dtype = torch.uint8      # e4m3 codes
         n = ctypes.c_int64()
         _check(lib().ffn24_saved_bytes(self._h, which, ctypes.byref(n)), "ffn24_saved_bytes")
         out = torch.empty(shape_fn(self.T, self.F), dtype=dtype, device="cuda")

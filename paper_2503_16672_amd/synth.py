@@ -81,3 +81,19 @@ def random_activation_words(rows: int, cols: int, p_nonzero: float, seed: int) -
     keep = rng.random((rows, cols), dtype=np.float32) < np.float32(p_nonzero)
     h = np.where(keep, z * z, np.float32(0)).astype(np.float32)
     return (h.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+
+
+def make_inputs_fp8(T: int, D: int, F: int, sparsity, seed: int, sh: float = 16.0 / 448.0) -> dict:
+    """fp8 workload: the bf16 recipe's tensors quantised per tensor to OCP e4m3 codes (uint8) with fp32 scales
+    s = amax / 448 (so nothing saturates and torch's CPU cast is the plain round-to-nearest-even conversion).
+    The activation scale sh is static and handed in: the default puts the format's largest value, 448, at a
+    squared-ReLU activation of 16 (pre-activation 4 standard deviations above zero); larger activations saturate."""
+    import torch
+    inp = make_inputs(T, D, F, sparsity, seed)
+    out = {"b1": inp["b1"], "sh": float(sh)}
+    for k in ("X", "W1", "W2"):
+        s = float(np.abs(inp[k]).max() / 448.0)
+        out["s" + k.lower()] = s
+        q = torch.from_numpy(inp[k] / np.float32(s)).to(torch.float8_e4m3fn)
+        out[k] = q.view(torch.uint8).numpy()
+    return out

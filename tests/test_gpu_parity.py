@@ -487,3 +487,127 @@ def test_ffn_dense_full_size_sampled(F24):
     print("  dense full-size errs", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
     assert max(errs.values()) <= TOL_BF16
     ctx.close()
+
+
+# ----------------------------------------------------------------------------- fp8 (e4m3) forward
+TOL_FP8 = 6e-2
+
+
+def _fp8_inputs(T, D, Fh, sparsity, seed):
+    inp = synth.make_inputs(T, D, Fh, sparsity, seed)
+    sc = {"sx": float(np.abs(inp["X"]).max() / 448.0), "sw1": float(np.abs(inp["W1"]).max() / 448.0),
+          "sw2": float(np.abs(inp["W2"]).max() / 448.0)}
+    # static activation scale, calibrated on a token slice with the oracle's own forward (a fused epilogue cannot know
+    # the global maximum); deliberately a bit low so that a few values saturate
+    cal = O.ffn24_fwd(inp["X"][:64], inp["W1"], inp["b1"], inp["W2"])
+    sc["sh"] = float(0.8 * np.abs(cal["Hq"]).max() / 448.0)
+    q = {"X": O.f32_to_e4m3_bits(inp["X"] / np.float32(sc["sx"])), "W1": O.f32_to_e4m3_bits(inp["W1"] / np.float32(sc["sw1"])),
+         "W2": O.f32_to_e4m3_bits(inp["W2"] / np.float32(sc["sw2"]))}
+    return inp, sc, q
+
+
+def _check_fp8(F24, T, D, Fh, sparsity, seed, rows=None):
+    inp, sc, q = _fp8_inputs(T, D, Fh, sparsity, seed)
+    d = {k: torch.from_numpy(q[k]).cuda() for k in q}
+    b1 = torch.from_numpy(inp["b1"]).cuda()
+    ctx = F24.Context(T, D, Fh, F24.FFN24_DEBUG_DUMP_H | F24.FFN24_DENSE, dtype=F24.FFN24_FP8_E4M3)
+    ctx.set_scales(sc["sx"], sc["sw1"], sc["sh"], sc["sw2"])
+    Y = ctx.ffn24_fwd(d["X"], d["W1"], b1, d["W2"])
+    torch.cuda.synchronize()
+    rsel = np.arange(T) if rows is None else rows
+    rs_t = torch.from_numpy(rsel).cuda()
+    Hd = ctx.saved("H_dump")[rs_t]; Hc8 = ctx.saved("Hc")[rs_t].cpu().numpy(); meta = ctx.saved("meta")[rs_t].cpu().numpy()
+    torch.cuda.synchronize()
+    # S1: pick and quantisation re-derived by the oracle from the activation the kernel itself rounded
+    v_ref, m_ref = O.sparsify24(words_of(Hd))
+    assert np.array_equal(meta, m_ref)
+    q_ref = O.f32_to_e4m3_bits(O.bf16_bits_to_f32(v_ref) / np.float32(sc["sh"]))
+    assert np.array_equal(Hc8, q_ref)
+    assert (Hc8 == 0x7E).any()                       # the saturating branch is exercised
+    # S2: down-projection on the GPU's own compressed fp8 activation
+    W2q = O.e4m3_bits_to_f32(q["W2"]).astype(np.float64)
+    y_staged = O.decompress24(O.e4m3_bits_to_f32(Hc8).astype(np.float64), meta) @ W2q * (sc["sh"] * sc["sw2"])
+    e2 = O.max_rel_err(f64(Y[rs_t]), y_staged)
+    # S3: from the raw inputs
+    ref = O.ffn24_fwd_fp8(inp["X"][rsel], inp["W1"], inp["b1"], inp["W2"], sc["sx"], sc["sw1"], sc["sh"], sc["sw2"])
+    eh = O.max_rel_err(f64(Hd), ref["Hq"])
+    e3 = O.max_rel_err(f64(Y[rs_t]), ref["Y"])
+    agree = float(np.mean(meta == ref["meta"]))
+    print(f"  fp8 fwd24: H err {eh:.2e}  Y staged {e2:.2e}  Y end-to-end {e3:.2e}  meta agreement {agree:.5f}", flush=True)
+    assert eh <= TOL_FP8 and e2 <= TOL_FP8 and e3 <= TOL_FP8 and agree >= 0.995
+    # dense fp8 baseline
+    Yd = ctx.ffn_fwd(d["X"], d["W1"], b1, d["W2"])
+    torch.cuda.synchronize()
+    refd = O.ffn_fwd_fp8(inp["X"][rsel], inp["W1"], inp["b1"], inp["W2"], sc["sx"], sc["sw1"], sc["sh"], sc["sw2"])
+    H8 = ctx.saved("H_dense")[rs_t].cpu().numpy()
+    yd_staged = O.e4m3_bits_to_f32(H8).astype(np.float64) @ W2q * (sc["sh"] * sc["sw2"])
+    ed2 = O.max_rel_err(f64(Yd[rs_t]), yd_staged)
+    ed3 = O.max_rel_err(f64(Yd[rs_t]), refd["Y"])
+    h8_agree = float(np.mean(H8 == refd["H8_bits"]))
+    print(f"  fp8 dense: Y staged {ed2:.2e}  Y end-to-end {ed3:.2e}  H8 code agreement {h8_agree:.5f}", flush=True)
+    assert ed2 <= TOL_FP8 and ed3 <= TOL_FP8 and h8_agree >= 0.99
+    # determinism
+    Y2 = ctx.ffn24_fwd(d["X"], d["W1"], b1, d["W2"])
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y2)
+    ctx.close()
+
+
+def test_ffn24_fwd_fp8_small(F24):
+    print("fp8 fwd T=256 D=512 F=2048", flush=True)
+    _check_fp8(F24, 256, 512, 2048, 0.90, seed=51)
+
+
+def test_ffn24_fwd_fp8_multi_tile(F24):
+    print("fp8 fwd T=512 D=768 F=1280 (odd stage counts)", flush=True)
+    _check_fp8(F24, 512, 768, 1280, "per_feature", seed=52)
+
+
+def test_fp8_context_rules(F24):
+    with pytest.raises(F24.Ffn24Error) as e:
+        F24.Context(256, 256, 256, F24.FFN24_TRAINING, dtype=F24.FFN24_FP8_E4M3)
+    assert e.value.code == -4
+    ctx = F24.Context(256, 256, 256, 0)
+    with pytest.raises(F24.Ffn24Error) as e:
+        ctx.set_scales(1.0, 1.0, 1.0, 1.0)          # bf16 context has no scales
+    assert e.value.code == -4
+    ctx.close()
+
+
+@pytest.mark.timeout(900)
+def test_ffn24_fwd_fp8_full_size_sampled(F24):
+    """c5 (T=8192, D=8192, F=32768), fp8 forward in the configuration bench.py --workload c5 times: a seeded sample of
+    token rows, staged exactly like the small fp8 test (S1 bit-exact pick and codes, S2, S3)."""
+    w = synth.WORKLOADS["c5"]
+    T, D, Fh = w.T, w.D, w.F
+    print(f"fp8 full size c5 T={T} D={D} F={Fh}: generating inputs", flush=True)
+    inp = synth.make_inputs_fp8(T, D, Fh, w.sparsity, w.seed)
+    d = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2")}
+    b1 = torch.from_numpy(inp["b1"]).cuda()
+    ctx = F24.Context(T, D, Fh, F24.FFN24_DEBUG_DUMP_H, dtype=F24.FFN24_FP8_E4M3)
+    ctx.set_scales(inp["sx"], inp["sw1"], inp["sh"], inp["sw2"])
+    print("  running the forward on the GPU", flush=True)
+    Y = ctx.ffn24_fwd(d["X"], d["W1"], b1, d["W2"])
+    torch.cuda.synchronize()
+    rows = np.sort(np.random.default_rng(46).choice(T, 48, replace=False)); rs_t = torch.from_numpy(rows).cuda()
+    Hd = ctx.saved("H_dump")[rs_t]; Hc8 = ctx.saved("Hc")[rs_t].cpu().numpy(); meta_all = ctx.saved("meta")
+    meta = meta_all[rs_t].cpu().numpy()
+    torch.cuda.synchronize()
+    for nib in (meta_all & 0xF, meta_all >> 4):
+        assert bool(((nib & 3) < (nib >> 2)).all())
+    print("  oracle on the sampled rows", flush=True)
+    v_ref, m_ref = O.sparsify24(words_of(Hd))
+    assert np.array_equal(meta, m_ref)
+    assert np.array_equal(Hc8, O.f32_to_e4m3_bits(O.bf16_bits_to_f32(v_ref) / np.float32(inp["sh"])))
+    ref = O.ffn24_fwd_fp8_codes(inp["X"][rows], inp["W1"], inp["b1"], inp["W2"], inp["sx"], inp["sw1"], inp["sh"], inp["sw2"])
+    W2q = O.E4M3_VALUES[inp["W2"]]
+    y_staged = O.decompress24(O.E4M3_VALUES[Hc8], meta) @ W2q * (inp["sh"] * inp["sw2"])
+    e2 = O.max_rel_err(f64(Y[rs_t]), y_staged)
+    eh = O.max_rel_err(f64(Hd), ref["Hq"])
+    e3 = O.max_rel_err(f64(Y[rs_t]), ref["Y"])
+    agree = float(np.mean(meta == ref["meta"]))
+    sparsity = float(np.mean(ref["Hq"] == 0))
+    print(f"  fp8 c5: H err {eh:.2e}  Y staged {e2:.2e}  Y end-to-end {e3:.2e}  meta agreement {agree:.5f}  sparsity {sparsity:.3f}", flush=True)
+    assert eh <= TOL_FP8 and e2 <= TOL_FP8 and e3 <= TOL_FP8 and agree >= 0.995
+    assert 0.93 < sparsity < 0.97
+    ctx.close()

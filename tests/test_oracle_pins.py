@@ -392,3 +392,44 @@ def test_fp8_forward_reduces_to_bf16_forward_on_exact_inputs():
 def test_max_rel_err_definition():
     assert O.max_rel_err([1.0, 2.0, 4.0], [1.0, 2.0, 4.0]) == 0.0
     assert abs(O.max_rel_err([1.0, 2.5, 4.0], [1.0, 2.0, 4.0]) - 0.125) < 1e-15
+
+
+def test_fp8_sparse_forward_equals_dense_fp8_forward_when_nothing_dropped():
+    """Fig. 2 caption: if no value is dropped the 2:4 result is exact -- also through the fp8 quantisation, because
+    the kept values are quantised exactly like the dense ones."""
+    rng = np.random.default_rng(9)
+    T, D, F = 24, 32, 64
+    X = rng.standard_normal((T, D)).astype(np.float32)
+    W1 = (rng.standard_normal((D, F)) / np.sqrt(D)).astype(np.float32)
+    W2 = (rng.standard_normal((F, D)) / np.sqrt(F)).astype(np.float32)
+    b1 = np.zeros(F, np.float32)
+    b1.reshape(-1, 4)[:, [1, 2]] = -1e9            # two of every four features can never fire
+    sc = dict(sx=np.abs(X).max() / 448, sw1=np.abs(W1).max() / 448, sh=0.05, sw2=np.abs(W2).max() / 448)
+    a = O.ffn24_fwd_fp8(X, W1, b1, W2, **sc)
+    b = O.ffn_fwd_fp8(X, W1, b1, W2, **sc)
+    assert np.array_equal(O.decompress24(a["Hc8_bits"], a["meta"]), b["H8_bits"])
+    np.testing.assert_allclose(a["Y"], b["Y"], rtol=0, atol=1e-12 * np.abs(b["Y"]).max())
+    assert np.count_nonzero(b["H8_bits"]) > 0.2 * T * F / 2
+
+
+def test_fp8_forward_quantisation_steps():
+    """The fp8 forward quantises where the paper says (after the pick) and saturates: a kept value far above
+    448 sh becomes code 0x7E, and the pick itself is the bf16 pick (unchanged by sh)."""
+    X = np.eye(8, dtype=np.float32) * 4.0
+    W1 = np.zeros((8, 8), np.float32); W1[0, :4] = [1.0, 2.0, 3.0, 0.5]
+    W2 = np.eye(8, dtype=np.float32)
+    out = O.ffn24_fwd_fp8(X, W1, None, W2, sx=1.0, sw1=1.0, sh=0.25, sw2=1.0)
+    # token 0: z = [4, 8, 12, 2] -> h = [16, 64, 144, 4]; kept: 64 (pos 1), 144 (pos 2); /0.25 -> 256, 576 -> 256, sat 448
+    assert out["meta"][0, 0] & 0xF == (1 | (2 << 2))
+    assert list(out["Hc8_bits"][0, :2]) == [int(O.f32_to_e4m3_bits(np.float32(256.0))), 0x7E]
+    np.testing.assert_allclose(out["Y"][0, :4], [0.0, 64.0, 112.0, 0.0])
+
+
+def test_fp8_workload_codes_match_the_oracle_quantiser():
+    """The fp8 workload generator quantises with torch's CPU cast; on its in-range inputs that is the oracle's
+    saturating round-to-nearest-even conversion, code for code."""
+    w = synth.make_inputs_fp8(64, 128, 256, 0.9, seed=3)
+    raw = synth.make_inputs(64, 128, 256, 0.9, seed=3)
+    for k in ("X", "W1", "W2"):
+        assert np.array_equal(w[k], O.f32_to_e4m3_bits(raw[k] / np.float32(w["s" + k.lower()])))
+    assert w["sh"] > 0
