@@ -22,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_DENSE = 2500.0   # TFLOP/s, MI355X published dense bf16 MFMA peak
+PEAK_FP8_DENSE = 5000.0    # TFLOP/s, published dense fp8 MFMA peak
 # executed MFMA flops per kernel, in units of T*D*F (dense GEMM = 2, sparse GEMM executes half of its dense equivalent)
 KERNEL_FLOPS = {"up_prune24": 2.0, "down_sp": 1.0, "dh_gather": 2.0, "dx_sp": 1.0, "dw2_sp": 1.0, "dw1_sp": 1.0,
                 "dense_up": 2.0, "dense_down": 2.0, "dense_dh": 2.0, "dense_dx": 2.0, "dense_dw2": 2.0, "dense_dw1": 2.0}
@@ -46,7 +47,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c4", help="c1, c2, c3_85..c3_98, c4 (default: forward+backward at the 7B FFN dims)")
+    ap.add_argument("--workload", default="c4", help="c1, c2, c3_85..c3_98, c4 (default: forward+backward at the 7B FFN dims), c5 (fp8 forward)")
     ap.add_argument("--fwd-only", action="store_true", help="time the forward pass only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-tokens", type=int, default=2048, help="token slice the CPU oracle is timed on")
@@ -64,11 +65,19 @@ def main() -> int:
     ffn24.lib()  # fails loudly if libffn24.so is not built; there is no fallback path
     w = synth.WORKLOADS[args.workload]
     T, D, F = w.T, w.D, w.F
-    inp = synth.make_workload(args.workload, with_dy=True)
-    dev = {k: torch.from_numpy(inp[k]).to(torch.bfloat16).cuda() for k in ("X", "W1", "W2", "dY")}
+    fp8 = args.workload == "c5"
+    bwd = not (args.fwd_only or fp8)
+    if fp8:
+        inp = synth.make_inputs_fp8(T, D, F, w.sparsity, w.seed)
+        dev = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2")}
+        ctx = ffn24.Context(T, D, F, ffn24.FFN24_DENSE, dtype=ffn24.FFN24_FP8_E4M3)
+        ctx.set_scales(inp["sx"], inp["sw1"], inp["sh"], inp["sw2"])
+    else:
+        inp = synth.make_workload(args.workload, with_dy=True)
+        dev = {k: torch.from_numpy(inp[k]).to(torch.bfloat16).cuda() for k in ("X", "W1", "W2", "dY")}
+        ctx = ffn24.Context(T, D, F, (ffn24.FFN24_TRAINING if bwd else 0) | ffn24.FFN24_DENSE)
     b1 = torch.from_numpy(inp["b1"]).cuda()
-    bwd = not args.fwd_only
-    ctx = ffn24.Context(T, D, F, (ffn24.FFN24_TRAINING if bwd else 0) | ffn24.FFN24_DENSE)
+    peak = PEAK_FP8_DENSE if fp8 else PEAK_BF16_DENSE
     Y = torch.empty((T, D), dtype=torch.bfloat16, device="cuda")
     grads = (torch.empty((T, D), dtype=torch.bfloat16, device="cuda"), torch.empty((D, F), dtype=torch.bfloat16, device="cuda"),
              torch.empty((F, D), dtype=torch.bfloat16, device="cuda"))
@@ -127,30 +136,35 @@ def main() -> int:
     for name, ms in kernel_ms.items():
         if name in KERNEL_FLOPS:
             tf = KERNEL_FLOPS[name] * tdf / (ms * 1e-3) / 1e12
-            kernels[name] = {"ms": round(ms, 4), "tflops_executed": round(tf, 1), "frac_of_dense_mfma_peak": round(tf / PEAK_BF16_DENSE, 4)}
+            kernels[name] = {"ms": round(ms, 4), "tflops_executed": round(tf, 1), "frac_of_dense_mfma_peak": round(tf / peak, 4)}
             if name in SPARSE:
                 kernels[name]["tflops_dense_equivalent"] = round(2 * tf, 1)
         else:
             # streaming kernels: feature-wise re-compression moves 4.25 bytes per element of [T, F]; a transpose pair
             # reads and writes 2 x 2 bytes per element of its two matrices
-            nbytes = {"featurewise24": 4.25 * T * F, "transpose_weights": 8.0 * D * F, "transpose_acts": 8.0 * T * D}[name]
+            # (the forward's weight pass also writes a panel-form copy of W2 when the context trains: 10 D F bytes then)
+            es = 1.0 if fp8 else 2.0
+            nbytes = {"featurewise24": 4.25 * T * F, "transpose_weights": (5.0 if bwd else 4.0) * es * D * F, "transpose_acts": 8.0 * T * D}[name]
             gbs = nbytes / (ms * 1e-3) / 1e9
             kernels[name] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / 8000.0, 4)}
     dom = max((n for n in kernel_ms if n in KERNEL_FLOPS and not n.startswith("dense_")), key=lambda n: kernel_ms[n])
     achieved = KERNEL_FLOPS[dom] * tdf / (kernel_ms[dom] * 1e-3) / 1e12
-    roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_DENSE, "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_BF16_DENSE, 4), "traffic": measured_traffic(dom, w.name),
-                "note": "executed bf16 MFMA flops of the launch / its HIP-event duration; a sparse kernel executes half its dense-equivalent flops"}
+    roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 1), "peak": peak, "unit": "TFLOP/s",
+                "frac": round(achieved / peak, 4), "traffic": measured_traffic(dom, w.name),
+                "note": "executed MFMA flops of the launch / its HIP-event duration; a sparse kernel executes half its dense-equivalent flops"}
 
     cpu = None
     if not args.no_cpu:
         from oracle import ffn24_oracle as O
         Ts = min(args.cpu_tokens, T)
-        sl = {k: inp[k][:Ts] if k in ("X", "dY") else inp[k] for k in inp}
         t0 = time.perf_counter()
-        f = O.ffn24_fwd(sl["X"], sl["W1"], sl["b1"], sl["W2"])
-        if bwd:
-            O.ffn24_bwd(f, sl["dY"])
+        if fp8:
+            O.ffn24_fwd_fp8_codes(inp["X"][:Ts], inp["W1"], inp["b1"], inp["W2"], inp["sx"], inp["sw1"], inp["sh"], inp["sw2"])
+        else:
+            sl = {k: inp[k][:Ts] if k in ("X", "dY") else inp[k] for k in inp}
+            f = O.ffn24_fwd(sl["X"], sl["W1"], sl["b1"], sl["W2"])
+            if bwd:
+                O.ffn24_bwd(f, sl["dY"])
         dt = time.perf_counter() - t0
         cpu = {"value": round((12.0 if bwd else 4.0) * Ts * D * F / dt / 1e12, 5), "unit": "TFLOP/s", "cores": len(os.sched_getaffinity(0)),
                "kind": "oracle", "sample": f"first {Ts} of {T} tokens of the same workload, float64 numpy, {dt:.1f} s"}
@@ -159,10 +173,10 @@ def main() -> int:
         "metric": "FFN fwd+bwd dense-equiv TFLOP/s" if bwd else "FFN fwd dense-equiv TFLOP/s",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(sec24 * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "fp8" if fp8 else "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: 2:4 Squared-ReLU FFN {'fwd+bwd' if bwd else 'fwd'}, T={T} d_model={D} d_ff={F}, target sparsity {w.sparsity}",
                    "T": T, "d_model": D, "d_ff": F, "parallelism": "single GPU"},
-        "frac_of_sparse_mfma_peak": round(value / (2 * PEAK_BF16_DENSE), 4),
+        "frac_of_sparse_mfma_peak": round(value / (2 * peak), 4),
         "dense_ffn": {"ms_per_step": round(sec_dense * 1e3, 4), "tflops": round(flops_step / sec_dense / 1e12, 2)},
         "speedup_vs_dense_ffn": round(sec_dense / sec24, 4),
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,

@@ -248,8 +248,14 @@ __device__ __forceinline__ i32x8 cat16(const bf16x8& lo, const bf16x8& hi) {
 template <int M>
 __device__ __forceinline__ void mfma_dense_f8(const FragD& f0, const FragD& f1, f32x16 (&acc)[4][4]) {
   constexpr int mi = M >> 2, ni = M & 3;
-  acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(cat16(f0.a[mi], f1.a[mi]), cat16(f0.b[ni], f1.b[ni]), acc[mi][ni],
-                                                                 0, 0, 0, 0, 0, 0);   // both operands e4m3, unscaled
+  // Written as inline assembly with the accumulator tied in place: through the builtin the compiler gives this
+  // instruction a destination different from its accumulator input, which with all 256 accumulation registers in
+  // use spills accumulators to scratch memory on every op.  Default modifiers = both operands e4m3, unscaled.
+  // No software wait states are needed here: consecutive ops use different accumulators, and the same one is only
+  // touched again 16 ops later.
+  asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, %0"
+               : "+a"(acc[mi][ni])
+               : "v"(cat16(f0.a[mi], f1.a[mi])), "v"(cat16(f0.b[ni], f1.b[ni])));
 }
 
 // Sparse: the stage's K window of 64 = four 16-wide windows w.  Instruction S (0,1) gives lane half q the window
@@ -446,17 +452,22 @@ __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(GemmArgs g, typename
     wait_lgkmcnt0();
     __builtin_amdgcn_s_barrier();
     FFN24_FENCE();
+    // The two fragment sets alternate by stage parity.  The stage count is even (K is a multiple of 128 here), so
+    // the stages are walked in pairs, straight-line: a parity branch inside the loop makes the compiler shuffle the
+    // 256 accumulation registers between its two arms.
     int slot = 0;
-    auto advance = [&](int kt, auto mode) {
+    auto advance = [&](int kt, auto par, auto mode) {
       int ns = slot + 1 == NB ? 0 : slot + 1;
-      if (kt & 1) stage(kt, smem + slot * G::STAGE, smem + ns * G::STAGE, std::integral_constant<int, 1>{}, mode);
-      else stage(kt, smem + slot * G::STAGE, smem + ns * G::STAGE, std::integral_constant<int, 0>{}, mode);
+      stage(kt, smem + slot * G::STAGE, smem + ns * G::STAGE, par, mode);
       slot = ns;
     };
+    using P0 = std::integral_constant<int, 0>; using P1 = std::integral_constant<int, 1>;
+    using M0 = std::integral_constant<int, 0>; using M1 = std::integral_constant<int, 1>; using M2 = std::integral_constant<int, 2>;
     int kt = 0;
-    for (; kt < nk - NB; kt++) advance(kt, std::integral_constant<int, 0>{});
-    for (; kt < nk - 1; kt++) advance(kt, std::integral_constant<int, 1>{});
-    advance(kt, std::integral_constant<int, 2>{});
+    for (; kt < nk - NB; kt += 2) { advance(kt, P0{}, M0{}); advance(kt + 1, P1{}, M0{}); }
+    if (nk >= NB) { advance(kt, P0{}, M1{}); advance(kt + 1, P1{}, M1{}); kt += 2; }
+    advance(kt, P0{}, M1{});
+    advance(kt + 1, P1{}, M2{});
   } else {
     FragD f0, f1;
     static_for<8>([&](auto I) { load_frag_dense1<0, I>(smem, L, f0); });
@@ -493,6 +504,11 @@ __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(GemmArgs g, typename
     advance(kt, std::integral_constant<int, 2>{});
   }
 
+  if constexpr (F8 && !SPARSE) {
+    // the dense fp8 ops are inline assembly, which the compiler's hazard handling does not see: let the last ones
+    // (16 passes each) drain before the epilogue reads the accumulators
+    asm volatile("s_nop 15\n s_nop 15\n s_nop 15\n s_nop 15\n s_nop 15" ::: "memory");
+  }
   int m_lane = m0 + L.wy * 128 + 64 * L.h;
   int n_lane = n0 + L.wx * 128 + 4 * L.rho;
   Epi::run(ea, acc, m_lane, n_lane);
