@@ -175,6 +175,8 @@ int ffn24_copy_saved(ffn24_ctx* c, int which, void* dst, int64_t dst_bytes, void
     default: src = c->dZd; break;
   }
   if (!src) return FFN24_ERR_STATE;
+  if (which >= 7)   // the dense baseline's H and dZ: dense panel form, 64-byte pieces of 32 (fp8: 64) k
+    return launch_unpanel(src, T, c->f8 ? F / 64 : F / 32, 64, dst, s) ? FFN24_ERR_HIP : FFN24_OK;
   if (piece) {
     // a piece covers 64 k (bf16) or 128 k (fp8, whose metadata pieces are twice as long)
     const int npanels = c->f8 ? K / 128 : K / 64;
@@ -272,14 +274,14 @@ int ffn_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const 
     { Timed t(c, KD_UP, s);
       if (t.done(launch_up_relu2_f8(c->W1t, X, b1, T, D, F, c->sx * c->sw1, c->sh, c->Hd, s))) return FFN24_ERR_HIP; }
     { Timed t(c, KD_DOWN, s);
-      if (t.done(launch_dense_rowmajor_f8(c->Hd, c->W2t, T, D, F, c->sh * c->sw2, Y, s))) return FFN24_ERR_HIP; }
+      if (t.done(launch_dense_rowmajor_f8(c->Hd, 1, c->W2t, T, D, F, c->sh * c->sw2, Y, s))) return FFN24_ERR_HIP; }
     return FFN24_OK;
   }
   { Timed t(c, K_TR_W, s);
     int rc1 = launch_transpose(W1, D, F, c->W1t, 1, nullptr, s);
     if (t.done(rc1 ? rc1 : launch_transpose(W2, F, D, c->W2t, 0, c->W2p, s))) return FFN24_ERR_HIP; }
   { Timed t(c, KD_UP, s);   if (t.done(launch_up_relu2(c->W1t, X, b1, T, D, F, c->Hd, c->Hd_t, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, KD_DOWN, s); if (t.done(launch_dense_rowmajor(c->Hd, c->W2t, T, D, F, Y, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_DOWN, s); if (t.done(launch_dense_rowmajor(c->Hd, 1, c->W2t, T, D, F, Y, s))) return FFN24_ERR_HIP; }
   c->X = X; c->W1 = W1; c->W2 = W2; c->have_fwd_dense = 1;
   return FFN24_OK;
 }
@@ -292,12 +294,12 @@ int ffn_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void* 
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   { Timed t(c, KD_DH, s);  if (t.done(launch_dh_drelu(c->W2p, dY, c->Hd, T, D, F, c->dZd, c->dZd_t, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, KD_DX, s);  if (t.done(launch_dense_rowmajor(c->dZd, c->W1, T, D, F, dX, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_DX, s);  if (t.done(launch_dense_rowmajor(c->dZd, 1, c->W1, T, D, F, dX, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_TR_ACT, s);
     int rc1 = launch_transpose(dY, T, D, c->dYt, 0, nullptr, s);
     if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, 0, nullptr, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, KD_DW2, s); if (t.done(launch_dense_rowmajor(c->Hd_t, c->dYt, F, D, T, dW2, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, KD_DW1, s); if (t.done(launch_dense_colmajor(c->dZd_t, c->Xt, F, D, T, dW1, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_DW2, s); if (t.done(launch_dense_rowmajor(c->Hd_t, 1, c->dYt, F, D, T, dW2, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_DW1, s); if (t.done(launch_dense_colmajor(c->dZd_t, 1, c->Xt, F, D, T, dW1, s))) return FFN24_ERR_HIP; }
   return FFN24_OK;
 }
 

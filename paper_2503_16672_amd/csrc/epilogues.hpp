@@ -42,8 +42,9 @@ struct EpiColMajor {
 };
 
 // Dense FFN up-projection epilogue (Sec. 1, Squared ReLU): rows m are features, columns n are tokens;
-// H[t][f] = bf16( max(0, acc + b1[f])^2 ), stored [T][F]; if Ht is given the same values are also stored [F][T]
-// (the operand layout the dense weight-gradient GEMM reduces over).
+// H[t][f] = bf16( max(0, acc + b1[f])^2 ), stored as the [T][F] operand of the down-projection; if Ht is given the
+// same values are also stored as the [F][T] operand of the weight-gradient GEMM that reduces over tokens.  Both in
+// the dense panel form of gemm_core.hpp (64-byte pieces of 32 k), like every A operand the library makes for itself.
 struct EpiRelu2 {
   struct Args { __bf16* H; __bf16* Ht; const float* b1; int F; int T; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
@@ -59,7 +60,8 @@ struct EpiRelu2 {
           float r = fmaxf(acc[mi][ni][v] + bias[v], 0.f);
           acc[mi][ni][v] = r * r;
         }
-        __bf16* row = e.H + (size_t)(n_lane + ni) * e.F + m_lane + 16 * mi;
+        int f = m_lane + 16 * mi;
+        __bf16* row = e.H + a24_piece(n_lane + ni, f >> 5, e.F >> 5) * 32 + (f & 31);
 #pragma unroll
         for (int q = 0; q < 2; q++) {
           u32x4 o;
@@ -74,7 +76,7 @@ struct EpiRelu2 {
           u32x2 o;
           o[0] = pack_bf16x2(acc[mi][0][v], acc[mi][1][v]);
           o[1] = pack_bf16x2(acc[mi][2][v], acc[mi][3][v]);
-          *reinterpret_cast<u32x2*>(e.Ht + (size_t)(m_lane + 16 * mi + v) * e.T + n_lane) = o;
+          *reinterpret_cast<u32x2*>(e.Ht + a24_piece(m_lane + 16 * mi + v, n_lane >> 5, e.T >> 5) * 32 + (n_lane & 31)) = o;
         }
       }
     }
@@ -139,7 +141,8 @@ struct EpiPrune24 {
 
 // Dense backward, pointwise part: rows m are features, columns n are tokens; acc = dH[t][f];
 // dZ[t][f] = bf16( acc * 2 sqrt(H[t][f]) )  (derivative of max(0,z)^2 is 2 max(0,z) = 2 sqrt(h)).
-// Stored [T][F] and, for the weight-gradient GEMM that reduces over tokens, also [F][T].
+// Stored as a [T][F] operand and, for the weight-gradient GEMM that reduces over tokens, also as an [F][T] operand;
+// H, dZ and dZt are all in dense panel form.
 struct EpiDRelu {
   struct Args { const __bf16* H; __bf16* dZ; __bf16* dZt; int F; int T; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
@@ -147,7 +150,8 @@ struct EpiDRelu {
     for (int mi = 0; mi < 4; mi++) {
 #pragma unroll
       for (int ni = 0; ni < 4; ni++) {
-        size_t o = (size_t)(n_lane + ni) * e.F + m_lane + 16 * mi;
+        int f = m_lane + 16 * mi;
+        size_t o = a24_piece(n_lane + ni, f >> 5, e.F >> 5) * 32 + (f & 31);
 #pragma unroll
         for (int q = 0; q < 2; q++) {
           u32x4 h = *reinterpret_cast<const u32x4*>(e.H + o + 8 * q);
@@ -169,7 +173,7 @@ struct EpiDRelu {
           u32x2 o;
           o[0] = pack_bf16x2(acc[mi][0][v], acc[mi][1][v]);
           o[1] = pack_bf16x2(acc[mi][2][v], acc[mi][3][v]);
-          *reinterpret_cast<u32x2*>(e.dZt + (size_t)(m_lane + 16 * mi + v) * e.T + n_lane) = o;
+          *reinterpret_cast<u32x2*>(e.dZt + a24_piece(m_lane + 16 * mi + v, n_lane >> 5, e.T >> 5) * 32 + (n_lane & 31)) = o;
         }
       }
     }
@@ -278,13 +282,14 @@ struct EpiPrune24F8 {
   }
 };
 
-// fp8 dense up-projection (baseline): H8[t][f] = e4m3( bf16(max(0, zscale acc + b1)^2) / sh ), stored [T][F] bytes.
+// fp8 dense up-projection (baseline): H8[t][f] = e4m3( bf16(max(0, zscale acc + b1)^2) / sh ), the [T][F] byte operand
+// of the dense down-projection, in dense panel form (64-byte pieces of 64 k).
 struct EpiRelu2F8 {
   struct Args { uint8_t* H8; const float* b1; int F; float zscale; float sh; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
 #pragma unroll
     for (int ni = 0; ni < 4; ni++) {
-      uint8_t* row = e.H8 + (size_t)(n_lane + ni) * e.F + m_lane;
+      uint8_t* row = e.H8 + a24_piece(n_lane + ni, m_lane >> 6, e.F >> 6) * 64;   // a lane's 64 features: one piece
 #pragma unroll
       for (int mi = 0; mi < 4; mi++) {
         uint32_t q[4];

@@ -23,8 +23,8 @@ int launch_sp_rowmajor_f8(const void* vals8, const uint8_t* meta, int a_panel, c
   return launch_gemm<true, EpiRowMajorScaled, true>(g, ea, s);
 }
 
-int launch_dense_rowmajor_f8(const void* A8, const void* B8, int M, int N, int K, float scale, void* C, hipStream_t s) {
-  GemmArgs g{A8, nullptr, B8, M, N, K, 0};
+int launch_dense_rowmajor_f8(const void* A8, int a_panel, const void* B8, int M, int N, int K, float scale, void* C, hipStream_t s) {
+  GemmArgs g{A8, nullptr, B8, M, N, K, a_panel};
   EpiRowMajorScaled::Args ea{static_cast<__bf16*>(C), N, scale};
   return launch_gemm<false, EpiRowMajorScaled, true>(g, ea, s);
 }

@@ -19,16 +19,16 @@ int launch_sp_colmajor(const void* vals, const uint8_t* meta, int a_panel, const
 // dH = dY W2^T with rows = hidden features: A = W2 [F][D] in dense panel form, B = dY [T][D]; pointwise part fused
 int launch_dh_gather(const void* W2, const void* dY, const void* Hc, const uint8_t* meta, int T, int D, int F, void* dZc, hipStream_t s);
 int launch_dh_drelu(const void* W2, const void* dY, const void* H, int T, int D, int F, void* dZ, void* dZt, hipStream_t s);
-// dense GEMMs: A [M][K], B [N][K]
-int launch_dense_rowmajor(const void* A, const void* B, int M, int N, int K, void* C, hipStream_t s);
-int launch_dense_colmajor(const void* A, const void* B, int M, int N, int K, void* Ct, hipStream_t s);
+// dense GEMMs: A [M][K] (a_panel: in dense panel form), B [N][K]
+int launch_dense_rowmajor(const void* A, int a_panel, const void* B, int M, int N, int K, void* C, hipStream_t s);
+int launch_dense_colmajor(const void* A, int a_panel, const void* B, int M, int N, int K, void* Ct, hipStream_t s);
 // fp8 e4m3 forward (per-tensor scales).  W1t8 [F][D] in dense panel form (64-byte pieces = 64 k), X8 [T][D];
 // compressed activation in the fp8 panel form (64 stored bytes + 16 metadata bytes per 128 k); bf16 results.
 int launch_up_prune24_f8(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, float zscale, float sh,
                          void* Hc8, uint8_t* meta, void* Hdbg, hipStream_t s);
 int launch_up_relu2_f8(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, float zscale, float sh, void* H8, hipStream_t s);
 int launch_sp_rowmajor_f8(const void* vals8, const uint8_t* meta, int a_panel, const void* B8, int M, int N, int K, float scale, void* C, hipStream_t s);
-int launch_dense_rowmajor_f8(const void* A8, const void* B8, int M, int N, int K, float scale, void* C, hipStream_t s);
+int launch_dense_rowmajor_f8(const void* A8, int a_panel, const void* B8, int M, int N, int K, float scale, void* C, hipStream_t s);
 // streaming kernels
 int launch_sparsify24(const void* H, int64_t rows, int64_t cols, void* vals, uint8_t* meta, hipStream_t s);
 // panel: inputs and outputs are in panel form (the library's own buffers) instead of row-major

@@ -89,11 +89,11 @@ def _stream():
     return torch.cuda.current_stream().cuda_stream
 
 
-def sparsify24(H: torch.Tensor):
-    """H [rows, cols] bf16 -> (values [rows, cols/2] bf16, meta [rows, cols/8] uint8)."""
+def sparsify24(H: torch.Tensor, values: torch.Tensor | None = None, meta: torch.Tensor | None = None):
+    """H [rows, cols] bf16 -> (values [rows, cols/2] bf16, meta [rows, cols/8] uint8); outputs may be handed in."""
     rows, cols = H.shape
-    values = torch.empty((rows, cols // 2), dtype=torch.bfloat16, device=H.device)
-    meta = torch.empty((rows, cols // 8), dtype=torch.uint8, device=H.device)
+    values = torch.empty((rows, cols // 2), dtype=torch.bfloat16, device=H.device) if values is None else values
+    meta = torch.empty((rows, cols // 8), dtype=torch.uint8, device=H.device) if meta is None else meta
     _check(lib().sparsify24(_ptr(H), rows, cols, FFN24_BF16, _ptr(values), _ptr(meta), _stream()), "sparsify24")
     return values, meta
 
