@@ -42,12 +42,56 @@ def measured_traffic(kernel: str, workload: str):
     return None
 
 
+def run_c3(args) -> int:
+    """Workload c3: four independent forward FFN layers at the 7B dims, each with its own seed and sparsity
+    (85 / 90 / 95 / 98 % zeros); per-layer time of the 2:4 FFN against the dense MFMA FFN."""
+    import torch
+    from paper_2503_16672_amd import ffn24, synth
+    layers = {}
+    tot24 = totd = 0.0
+    for name in ("c3_85", "c3_90", "c3_95", "c3_98"):
+        w = synth.WORKLOADS[name]
+        T, D, F = w.T, w.D, w.F
+        inp = synth.make_workload(name)
+        dev = {k: torch.from_numpy(inp[k]).to(torch.bfloat16).cuda() for k in ("X", "W1", "W2")}
+        b1 = torch.from_numpy(inp["b1"]).cuda()
+        ctx = ffn24.Context(T, D, F, ffn24.FFN24_DENSE)
+        Y = torch.empty((T, D), dtype=torch.bfloat16, device="cuda")
+
+        def timed(fn):
+            for _ in range(args.warmup):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / args.steps
+        s24 = timed(lambda: ctx.ffn24_fwd(dev["X"], dev["W1"], b1, dev["W2"], Y))
+        sd = timed(lambda: ctx.ffn_fwd(dev["X"], dev["W1"], b1, dev["W2"], Y))
+        fl = 4.0 * T * D * F
+        layers[name] = {"sparsity": w.sparsity, "ms": round(s24 * 1e3, 4), "tflops": round(fl / s24 / 1e12, 1),
+                        "dense_ms": round(sd * 1e3, 4), "speedup_vs_dense_ffn": round(sd / s24, 4)}
+        tot24 += s24; totd += sd
+        ctx.close()
+        del dev, Y
+    w = synth.WORKLOADS["c3_90"]
+    fl = 4 * 4.0 * w.T * w.D * w.F
+    print(json.dumps({"metric": "FFN fwd dense-equiv TFLOP/s", "value": round(fl / tot24 / 1e12, 2), "unit": "TFLOP/s", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(tot24 * 1e3, 4), "higher_is_better": True,
+                      "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": "c3: four 2:4 Squared-ReLU FFN layers, fwd, T=16384 d_model=4096 d_ff=16384, 85/90/95/98 % zeros",
+                                 "parallelism": "single GPU"},
+                      "speedup_vs_dense_ffn": round(totd / tot24, 4), "layers": layers}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c4", help="c1, c2, c3_85..c3_98, c4 (default: forward+backward at the 7B FFN dims), c5 (fp8 forward)")
+    ap.add_argument("--workload", default="c4", help="c1, c2, c3 (four forward layers), c3_85..c3_98, c4 (default: forward+backward at the 7B FFN dims), c5 (fp8 forward)")
     ap.add_argument("--fwd-only", action="store_true", help="time the forward pass only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-tokens", type=int, default=2048, help="token slice the CPU oracle is timed on")
@@ -63,6 +107,8 @@ def main() -> int:
     from paper_2503_16672_amd import ffn24, synth
 
     ffn24.lib()  # fails loudly if libffn24.so is not built; there is no fallback path
+    if args.workload == "c3":
+        return run_c3(args)
     w = synth.WORKLOADS[args.workload]
     T, D, F = w.T, w.D, w.F
     fp8 = args.workload == "c5"
