@@ -359,7 +359,28 @@ def fwd_from_saved(Hc_words, meta, X, W1, W2, st=Bf16):
             "Xq": st.q(X).astype(np.float64), "W1q": st.q(W1).astype(np.float64), "W2q": st.q(W2).astype(np.float64)}
 
 
-def ffn24_bwd(fwd: dict, dY, st=Bf16, wgrad_mask="featurewise"):
+def feature_nnz(Hq) -> np.ndarray:
+    """Column-level statistic of Sec. 2, "Optimization 1": for every hidden feature the number of tokens whose
+    (storage-rounded, not yet pruned) activation is non-zero -- what the first GEMM's epilogue can count for free."""
+    return np.count_nonzero(np.asarray(Hq), axis=0).astype(np.int64)
+
+
+def split_features(nnz, n_dense: int) -> np.ndarray:
+    """Partition of the features for the split weight-gradient GEMMs (Sec. 2, "Optimization 1"): the n_dense
+    least sparse features (largest non-zero count; ties -> lower feature index) are kept dense, the rest is
+    2:4-sparsified along tokens.  Returns a boolean array [F], True = dense feature.  (The paper sorts with an
+    argsort kernel and takes 5 %; the count is a parameter here.)"""
+    nnz = np.asarray(nnz, dtype=np.int64)
+    F = nnz.shape[0]
+    if not 0 <= n_dense <= F:
+        raise ValueError("n_dense out of range")
+    order = np.argsort(-nnz, kind="stable")        # count descending, index ascending among equals
+    dense = np.zeros(F, dtype=bool)
+    dense[order[:n_dense]] = True
+    return dense
+
+
+def ffn24_bwd(fwd: dict, dY, st=Bf16, wgrad_mask="featurewise", dense_features=None):
     """Backward of ffn24_fwd with the masks held fixed (Fig. 4 caption; Sec. 2, backward paragraphs).
 
       dH  = dY W2^T                                  (dense)
@@ -369,6 +390,8 @@ def ffn24_bwd(fwd: dict, dY, st=Bf16, wgrad_mask="featurewise"):
 
     Needs of `fwd` only H24, meta, Mtok, Xq, W1q, W2q.  wgrad_mask="tokenwise" replaces M_T by M_tok in the
     last line: the exact gradient of the pruned forward, used only to pin the calculus.
+    dense_features (bool [F], optional): the split of Sec. 2, "Optimization 1" -- for these features the weight
+    gradients use the token-wise mask only (a dense GEMM over them), for all others the feature-wise mask on top.
     """
     dYq = st.q(dY).astype(np.float64)
     dH = dYq @ fwd["W2q"].T
@@ -379,6 +402,8 @@ def ffn24_bwd(fwd: dict, dY, st=Bf16, wgrad_mask="featurewise"):
     dX = dZq.astype(np.float64) @ fwd["W1q"].T
     Hc_t, meta_t, M_T = featurewise24(fwd["H24"], st)
     Mw = M_T if wgrad_mask == "featurewise" else Mtok
+    if dense_features is not None:
+        Mw = np.where(np.asarray(dense_features, dtype=bool)[None, :], Mtok, Mw)
     H24m = np.where(Mw, fwd["H24"], fwd["H24"].dtype.type(0)).astype(np.float64)
     dZm = np.where(Mw, dZq, dZq.dtype.type(0)).astype(np.float64)
     dW2 = H24m.T @ dYq

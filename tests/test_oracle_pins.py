@@ -433,3 +433,43 @@ def test_fp8_workload_codes_match_the_oracle_quantiser():
     for k in ("X", "W1", "W2"):
         assert np.array_equal(w[k], O.f32_to_e4m3_bits(raw[k] / np.float32(w["s" + k.lower()])))
     assert w["sh"] > 0
+
+
+def test_split_features_against_brute_force():
+    """The n_dense features with the largest non-zero counts, ties to the lower index: checked against a plain
+    python selection on small arrays with many ties."""
+    rng = np.random.default_rng(12)
+    for F, n_dense in [(8, 0), (8, 8), (16, 3), (64, 5), (64, 63)]:
+        nnz = rng.integers(0, 4, size=F)
+        dense = O.split_features(nnz, n_dense)
+        ranked = sorted(range(F), key=lambda j: (-int(nnz[j]), j))
+        expect = np.zeros(F, bool); expect[ranked[:n_dense]] = True
+        assert np.array_equal(dense, expect)
+        assert dense.sum() == n_dense
+        if 0 < n_dense < F:
+            assert nnz[dense].min() >= nnz[~dense].max()
+
+
+def test_feature_nnz_counts_unpruned_activation():
+    Hq = np.array([[0, 1.5, 0, 2], [3, 0, 0, 1], [0.5, 0.25, 0, 4]], np.float32)
+    assert list(O.feature_nnz(Hq)) == [2, 2, 0, 3]
+
+
+def test_split_backward_limits():
+    """Split weight gradients (Sec. 2, Optimization 1): with no dense feature they are the feature-wise-masked ones,
+    with every feature dense they are the exact gradients of the pruned forward (token-wise mask only); in between,
+    each feature's row of dW2 / column of dW1 equals the row / column of the limit it belongs to; dX never changes."""
+    inp = synth.make_inputs(64, 32, 96, 0.6, seed=21, with_dy=True)
+    f = O.ffn24_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"])
+    g_fw = O.ffn24_bwd(f, inp["dY"])
+    g_tw = O.ffn24_bwd(f, inp["dY"], wgrad_mask="tokenwise")
+    none = O.ffn24_bwd(f, inp["dY"], dense_features=np.zeros(96, bool))
+    allf = O.ffn24_bwd(f, inp["dY"], dense_features=np.ones(96, bool))
+    for k in ("dX", "dW1", "dW2"):
+        assert np.array_equal(none[k], g_fw[k]) and np.array_equal(allf[k], g_tw[k])
+    dense = O.split_features(O.feature_nnz(f["Hq"]), 24)
+    assert (g_fw["dW2"] != g_tw["dW2"]).any()          # at 60 % zeros the two limits differ
+    g = O.ffn24_bwd(f, inp["dY"], dense_features=dense)
+    assert np.array_equal(g["dX"], g_fw["dX"])
+    assert np.array_equal(g["dW2"][dense], g_tw["dW2"][dense]) and np.array_equal(g["dW2"][~dense], g_fw["dW2"][~dense])
+    assert np.array_equal(g["dW1"][:, dense], g_tw["dW1"][:, dense]) and np.array_equal(g["dW1"][:, ~dense], g_fw["dW1"][:, ~dense])
