@@ -53,12 +53,14 @@ typedef enum { FFN24_BF16 = 0, FFN24_FP8_E4M3 = 1 } ffn24_dtype;
 #define FFN24_TRAINING 1     /* allocate what ffn24_bwd needs (dZ, transposed operands) */
 #define FFN24_DENSE 2        /* allocate what the dense baseline ffn_fwd / ffn_bwd needs (H, dZ as [T][F]) */
 #define FFN24_DEBUG_DUMP_H 4 /* ffn24_fwd also stores the rounded activation before pruning, [T][F] */
+#define FFN24_SPLIT 8        /* allocate what the split weight-gradient GEMMs need (with FFN24_TRAINING; see ffn24_set_split) */
 
 typedef struct ffn24_ctx ffn24_ctx; /* opaque; owns only its device workspace */
 
 /* Create a context for token count T, model dimension D, hidden dimension F.
  * Requires T, D, F to be multiples of 256 (the GEMM tile) and at most 2^20.  Allocates the device workspace with
- * hipMalloc on the current device: about 1.13 T F + 4 D F bytes; plus 3.13 T F + 4 T D + 2 D F with FFN24_TRAINING; plus
+ * hipMalloc on the current device: about 1.13 T F + 4 D F bytes; plus 3.13 T F + 4 T D + 2 D F with FFN24_TRAINING
+ * (T F + 2 D F more with FFN24_SPLIT); plus
  * 2 T F with FFN24_DENSE (6 T F more when FFN24_TRAINING is set too); plus 2 T F with FFN24_DEBUG_DUMP_H.
  * *out is untouched on error. */
 FFN24_API int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dtype dtype, int flags);
@@ -71,6 +73,17 @@ FFN24_API int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F,
  * row-wise ones).  Saved tensors 0 and 1 are then bytes: Hc8 [T][F/2], meta [T][F/8]; tensor 7 is H8 [T][F].
  * An fp8 context supports ffn24_fwd and ffn_fwd only (no FFN24_TRAINING: FFN24_ERR_DTYPE). */
 FFN24_API int ffn24_set_scales(ffn24_ctx* ctx, float sx, float sw1, float sh, float sw2);
+
+/* Split of the weight-gradient GEMMs (paper Sec. 2, "Optimization 1"): some hidden features are too dense to be
+ * 2:4-sparsified along tokens, so the n_dense least sparse features are kept out of the feature-wise pruning.
+ * With n_dense > 0, ffn24_fwd also counts, per feature, the non-zero activations before pruning (in the up-projection's
+ * epilogue), and ffn24_bwd partitions the features (the n_dense largest counts, ties to the lower index, are "dense"),
+ * computes the rows of dW2 and the columns of dW1 of the dense features with dense GEMMs over the token-wise-pruned
+ * activation, and all others with the sparse GEMMs as before.  n_dense is a multiple of 256, 0 <= n_dense <= F / 4
+ * (0 = no split, the default).  Needs FFN24_SPLIT | FFN24_TRAINING; call it before the forward it shall apply to.
+ * Saved tensors 9 (the counts, [F] uint32) and 10 (feature of each operand row, [F] int32: sparse features first,
+ * then the dense ones, each in ascending order) are valid after the backward. */
+FFN24_API int ffn24_set_split(ffn24_ctx* ctx, int64_t n_dense);
 
 /* Free the workspace.  The caller must have synchronised every stream that used the context.  NULL is allowed. */
 FFN24_API int ffn24_ctx_destroy(ffn24_ctx* ctx);
@@ -123,6 +136,7 @@ FFN24_API int ffn_bwd(ffn24_ctx* ctx, const void* dY, void* dX, void* dW1, void*
 /* Copies of the context's saved tensors, for parity checks.  `which`:
  *   0 Hc [T][F/2]   1 meta [T][F/8]   2 dZc [T][F/2]   3 Hc_t [F][T/2]   4 meta_t [F][T/8]   5 dZc_t [F][T/2]
  *   6 pre-prune H dump [T][F] (FFN24_DEBUG_DUMP_H)   7 dense H [T][F]   8 dense dZ [T][F]
+ *   9 per-feature non-zero counts [F] uint32, 10 feature of each split-operand row [F] int32 (FFN24_SPLIT)
  * ffn24_saved_bytes gives the size of tensor `which`; ffn24_copy_saved enqueues a copy of it into dst (device memory
  * of exactly that size, 16-byte aligned) in the row-major compressed form described at the top -- inside the context
  * the compressed tensors are kept in a tiled order that the sparse GEMM streams faster.  Returns FFN24_ERR_STATE if
@@ -136,7 +150,8 @@ FFN24_API int ffn24_copy_saved(ffn24_ctx* ctx, int which, void* dst, int64_t dst
  * Kernel ids: 0 up-projection+prune, 1 sparse down-projection, 2 dH+derivative, 3 sparse dX, 4 feature-wise
  * re-compression, 5 sparse dW2, 6 sparse dW1, 7..12 the six dense-baseline GEMMs in the same order
  * (up, down, dH, dX, dW2, dW1), 13 the two weight transposes of a forward (W1, W2 -> K-contiguous), 14 the two
- * activation transposes of a backward (dY, X).  Returns FFN24_ERR_STATE if that kernel has not run with profiling on. */
+ * activation transposes of a backward (dY, X), 15 the feature partition of the split, 16 the two dense GEMMs of the
+ * split (with a split, 5 and 6 are its two sparse GEMMs), 17 the transpose that brings dW1 into [D][F] after a split.  Returns FFN24_ERR_STATE if that kernel has not run with profiling on. */
 FFN24_API int ffn24_set_profiling(ffn24_ctx* ctx, int on);
 FFN24_API int ffn24_kernel_ms(ffn24_ctx* ctx, int kernel, float* ms);
 

@@ -7,8 +7,8 @@
 using namespace ffn24;
 
 namespace {
-constexpr int NUM_KERNELS = 15;
-enum { K_UP = 0, K_DOWN, K_DH, K_DX, K_FW, K_DW2, K_DW1, KD_UP, KD_DOWN, KD_DH, KD_DX, KD_DW2, KD_DW1, K_TR_W, K_TR_ACT };
+constexpr int NUM_KERNELS = 18;
+enum { K_UP = 0, K_DOWN, K_DH, K_DX, K_FW, K_DW2, K_DW1, KD_UP, KD_DOWN, KD_DH, KD_DX, KD_DW2, KD_DW1, K_TR_W, K_TR_ACT, K_PART, K_SPLIT_DENSE, K_TR_DW1 };
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 }  // namespace
@@ -23,6 +23,9 @@ struct ffn24_ctx {
   void* Hc; uint8_t* meta; void* dZc; void* Hc_t; uint8_t* meta_t; void* dZc_t; void* Hdbg; void* Hd; void* dZd;
   void* W1t; void* W2t; void* Xt; void* dYt; void* Hd_t; void* dZd_t;   // K-contiguous copies of GEMM operands
   void* W2p;   // W2 itself in dense panel form (A operand of the dH GEMMs)
+  // split weight gradients (FFN24_SPLIT)
+  uint32_t* nnz; int* row_of_feat; int* feat_of_row; void* Hdn_t; void* dZdn_t; void* dW1t;
+  int n_dense;
   // forward state
   const void *X, *W1, *W2;
   int have_fwd24, have_fwd_dense;
@@ -48,7 +51,8 @@ struct Timed {
 int free_all(ffn24_ctx* c) {
   int bad = 0;
   void* bufs[] = {c->Hc, c->meta, c->dZc, c->Hc_t, c->meta_t, c->dZc_t, c->Hdbg, c->Hd, c->dZd,
-                  c->W1t, c->W2t, c->Xt, c->dYt, c->Hd_t, c->dZd_t, c->W2p};
+                  c->W1t, c->W2t, c->Xt, c->dYt, c->Hd_t, c->dZd_t, c->W2p,
+                  c->nnz, c->row_of_feat, c->feat_of_row, c->Hdn_t, c->dZdn_t, c->dW1t};
   for (void* b : bufs) if (b && hipFree(b) != hipSuccess) bad = 1;
   for (int k = 0; k < NUM_KERNELS; k++) for (int j = 0; j < 2; j++) if (c->ev[k][j]) (void)hipEventDestroy(c->ev[k][j]);
   return bad;
@@ -82,6 +86,7 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
   if (dtype != FFN24_BF16 && dtype != FFN24_FP8_E4M3) return FFN24_ERR_DTYPE;
   const bool f8 = dtype == FFN24_FP8_E4M3;
   if (f8 && (flags & FFN24_TRAINING)) return FFN24_ERR_DTYPE;   // the fp8 path is forward only
+  if ((flags & FFN24_SPLIT) && !(flags & FFN24_TRAINING)) return FFN24_ERR_STATE;
   if (T <= 0 || D <= 0 || F <= 0 || T % 256 || D % 256 || F % 256) return FFN24_ERR_SHAPE;
   if (T > (1 << 20) || D > (1 << 20) || F > (1 << 20)) return FFN24_ERR_SHAPE;
   ffn24_ctx* c = new (std::nothrow) ffn24_ctx();
@@ -97,6 +102,12 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
     ok = hipMalloc(&c->dZc, tf) == hipSuccess && hipMalloc(&c->Hc_t, tf) == hipSuccess &&
          hipMalloc(reinterpret_cast<void**>(&c->meta_t), tf / 8) == hipSuccess && hipMalloc(&c->dZc_t, tf) == hipSuccess &&
          hipMalloc(&c->Xt, 2 * td) == hipSuccess && hipMalloc(&c->dYt, 2 * td) == hipSuccess && hipMalloc(&c->W2p, 2 * df) == hipSuccess;
+  if (ok && (flags & FFN24_SPLIT))
+    ok = hipMalloc(reinterpret_cast<void**>(&c->nnz), 4 * (size_t)F) == hipSuccess &&
+         hipMalloc(reinterpret_cast<void**>(&c->row_of_feat), 4 * (size_t)F) == hipSuccess &&
+         hipMalloc(reinterpret_cast<void**>(&c->feat_of_row), 4 * (size_t)F) == hipSuccess &&
+         hipMalloc(&c->Hdn_t, tf / 2) == hipSuccess && hipMalloc(&c->dZdn_t, tf / 2) == hipSuccess &&   // up to F/4 dense rows
+         hipMalloc(&c->dW1t, 2 * df) == hipSuccess;
   if (ok && (flags & FFN24_DENSE)) ok = hipMalloc(&c->Hd, es * tf) == hipSuccess;
   if (ok && (flags & FFN24_DENSE) && (flags & FFN24_TRAINING))
     ok = hipMalloc(&c->dZd, 2 * tf) == hipSuccess && hipMalloc(&c->Hd_t, 2 * tf) == hipSuccess && hipMalloc(&c->dZd_t, 2 * tf) == hipSuccess;
@@ -120,6 +131,15 @@ int ffn24_set_scales(ffn24_ctx* c, float sx, float sw1, float sh, float sw2) {
   if (!c->f8) return FFN24_ERR_DTYPE;
   if (!(sx > 0.f) || !(sw1 > 0.f) || !(sh > 0.f) || !(sw2 > 0.f)) return FFN24_ERR_SHAPE;
   c->sx = sx; c->sw1 = sw1; c->sh = sh; c->sw2 = sw2;
+  return FFN24_OK;
+}
+
+int ffn24_set_split(ffn24_ctx* c, int64_t n_dense) {
+  if (!c) return FFN24_ERR_NULL;
+  if (!(c->flags & FFN24_SPLIT)) return FFN24_ERR_STATE;
+  if (n_dense < 0 || n_dense % 256 || n_dense > c->F / 4) return FFN24_ERR_SHAPE;
+  c->n_dense = (int)n_dense;
+  c->have_fwd24 = 0;   // the statistics of an earlier forward do not belong to this setting
   return FFN24_OK;
 }
 
@@ -147,6 +167,7 @@ int ffn24_saved_bytes(ffn24_ctx* c, int which, int64_t* nbytes) {
     case 1: case 4: *nbytes = tf / 8; break;
     case 6: *nbytes = 2 * tf; break;
     case 7: case 8: *nbytes = es * tf; break;
+    case 9: case 10: *nbytes = 4 * c->F; break;
     default: return FFN24_ERR_SHAPE;
   }
   return FFN24_OK;
@@ -172,9 +193,12 @@ int ffn24_copy_saved(ffn24_ctx* c, int which, void* dst, int64_t dst_bytes, void
     case 5: src = c->dZc_t; rows = F; K = T; piece = 64; break;
     case 6: src = c->Hdbg; break;
     case 7: src = c->Hd; break;
-    default: src = c->dZd; break;
+    case 8: src = c->dZd; break;
+    case 9: src = c->nnz; break;
+    default: src = c->feat_of_row; break;
   }
   if (!src) return FFN24_ERR_STATE;
+  if (which >= 9) return hipMemcpyAsync(dst, src, (size_t)need, hipMemcpyDeviceToDevice, s) == hipSuccess ? FFN24_OK : FFN24_ERR_HIP;
   if (which >= 7)   // the dense baseline's H and dZ: dense panel form, 64-byte pieces of 32 (fp8: 64) k
     return launch_unpanel(src, T, c->f8 ? F / 64 : F / 32, 64, dst, s) ? FFN24_ERR_HIP : FFN24_OK;
   if (piece) {
@@ -234,7 +258,9 @@ int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, cons
   { Timed t(c, K_TR_W, s);
     int rc1 = launch_transpose(W1, D, F, c->W1t, 1, nullptr, s);
     if (t.done(rc1 ? rc1 : launch_transpose(W2, F, D, c->W2t, 0, c->W2p, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, K_UP, s);   if (t.done(launch_up_prune24(c->W1t, X, b1, T, D, F, c->Hc, c->meta, c->Hdbg, s))) return FFN24_ERR_HIP; }
+  uint32_t* nnz = (c->flags & FFN24_SPLIT) && c->n_dense > 0 ? c->nnz : nullptr;
+  if (nnz && hipMemsetAsync(nnz, 0, 4 * (size_t)F, s) != hipSuccess) return FFN24_ERR_HIP;
+  { Timed t(c, K_UP, s);   if (t.done(launch_up_prune24(c->W1t, X, b1, T, D, F, c->Hc, c->meta, c->Hdbg, nnz, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_DOWN, s); if (t.done(launch_sp_rowmajor(c->Hc, c->meta, 1, c->W2t, T, D, F, Y, s))) return FFN24_ERR_HIP; }
   c->X = X; c->W1 = W1; c->W2 = W2; c->have_fwd24 = 1;
   return FFN24_OK;
@@ -249,6 +275,26 @@ int ffn24_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   { Timed t(c, K_DH, s);  if (t.done(launch_dh_gather(c->W2p, dY, c->Hc, c->meta, T, D, F, c->dZc, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_DX, s);  if (t.done(launch_sp_rowmajor(c->dZc, c->meta, 1, c->W1, T, D, F, dX, s))) return FFN24_ERR_HIP; }
+  const bool split = (c->flags & FFN24_SPLIT) && c->n_dense > 0;
+  if (split) {
+    // Sec. 2, "Optimization 1": the n_dense least sparse features are kept out of the feature-wise 2:4; their rows
+    // of both weight gradients come from dense GEMMs, all others from the sparse ones
+    const int nd = c->n_dense, ns = F - nd;
+    { Timed t(c, K_PART, s); if (t.done(launch_split_partition(c->nnz, F, nd, c->row_of_feat, c->feat_of_row, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_FW, s);
+      if (t.done(launch_featurewise24_split(c->Hc, c->meta, c->dZc, T, F, c->row_of_feat, ns, c->Hc_t, c->meta_t, c->dZc_t, c->Hdn_t, c->dZdn_t, s)))
+        return FFN24_ERR_HIP; }
+    { Timed t(c, K_TR_ACT, s);
+      int rc1 = launch_transpose(dY, T, D, c->dYt, 0, nullptr, s);
+      if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, 0, nullptr, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_DW2, s); if (t.done(launch_sp_rowmajor_mapped(c->Hc_t, c->meta_t, c->dYt, ns, D, T, dW2, D, c->feat_of_row, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_DW1, s); if (t.done(launch_sp_rowmajor_mapped(c->dZc_t, c->meta_t, c->Xt, ns, D, T, c->dW1t, D, c->feat_of_row, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_SPLIT_DENSE, s);
+      int rc1 = launch_dense_rowmajor_mapped(c->Hdn_t, c->dYt, nd, D, T, dW2, D, c->feat_of_row + ns, s);
+      if (t.done(rc1 ? rc1 : launch_dense_rowmajor_mapped(c->dZdn_t, c->Xt, nd, D, T, c->dW1t, D, c->feat_of_row + ns, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_TR_DW1, s); if (t.done(launch_transpose(c->dW1t, F, D, dW1, 0, nullptr, s))) return FFN24_ERR_HIP; }
+    return FFN24_OK;
+  }
   { Timed t(c, K_FW, s);  if (t.done(launch_featurewise24(c->Hc, c->meta, c->dZc, T, F, c->Hc_t, c->meta_t, c->dZc_t, 1, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_TR_ACT, s);
     int rc1 = launch_transpose(dY, T, D, c->dYt, 0, nullptr, s);

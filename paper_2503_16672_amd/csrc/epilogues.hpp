@@ -91,9 +91,16 @@ struct EpiRelu2 {
 //   one token are exactly one piece, 64 bytes of kept values (position order) + 8 metadata bytes (nibble
 //   i0 | i1<<2, even group low).
 //   Hdbg [T][F]    optional, row-major: the rounded activation before pruning (parity checks)
+//   nnz  [F] optional: per-feature count of non-zero activations before pruning (Sec. 2, "Optimization 1": the
+//   column-level sparsity the first GEMM's epilogue can compute for free), accumulated with atomics; the caller
+//   zeroes it.  A lane counts its 4 tokens in 8-bit fields (4 features per register), the 32 lanes that hold the
+//   same 64 features add their fields up with a butterfly, and each lane then adds two features' totals.
 struct EpiPrune24 {
-  struct Args { __bf16* Hc; uint8_t* meta; __bf16* Hdbg; const float* b1; int F; };
+  struct Args { __bf16* Hc; uint8_t* meta; __bf16* Hdbg; const float* b1; int F; uint32_t* nnz; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+    uint32_t cnt[16];
+#pragma unroll
+    for (int i = 0; i < 16; i++) cnt[i] = 0u;
 #pragma unroll
     for (int ni = 0; ni < 4; ni++) {
       size_t t = (size_t)(n_lane + ni);
@@ -109,6 +116,11 @@ struct EpiPrune24 {
           float r0 = fmaxf(acc[mi][ni][2 * d] + b0, 0.f);
           float r1 = fmaxf(acc[mi][ni][2 * d + 1] + b1v, 0.f);
           hpk[d] = pack_bf16x2(r0 * r0, r1 * r1);
+          if (e.nnz) {
+            // features 16 mi + 2 d and + 1 of the lane: fields (2 d) % 4 and (2 d + 1) % 4 of register 4 mi + d / 2
+            uint32_t lo = min(hpk[d] & 0xFFFFu, 1u), hi = min(hpk[d] >> 16, 1u);
+            cnt[4 * mi + (d >> 1)] += (lo << (16 * (d & 1))) + (hi << (16 * (d & 1) + 8));
+          }
         }
         if (e.Hdbg) {
           __bf16* row = e.Hdbg + t * e.F + m_lane + 16 * mi;
@@ -136,6 +148,41 @@ struct EpiPrune24 {
         *reinterpret_cast<u32x4*>(hrow + 8 * q) = u32x4{vals[4 * q], vals[4 * q + 1], vals[4 * q + 2], vals[4 * q + 3]};
       *reinterpret_cast<u32x2*>(e.meta + piece * 8) = u32x2{nib[0], nib[1]};
     }
+    if (e.nnz) {
+      // totals over the 32 lanes of this lane half (<= 128 per field); then lane r adds features r and r + 32
+      int lane = threadIdx.x & 63;
+#pragma unroll
+      for (int i = 0; i < 16; i++)
+#pragma unroll
+        for (int sft = 1; sft < 32; sft <<= 1) cnt[i] += (uint32_t)__shfl_xor((int)cnt[i], sft, 64);
+      int r = lane & 31;
+      uint32_t w0 = 0u, w1 = 0u;
+#pragma unroll
+      for (int i = 0; i < 8; i++) {
+        w0 = (r >> 2) == i ? cnt[i] : w0;
+        w1 = (r >> 2) == i ? cnt[8 + i] : w1;
+      }
+      uint32_t c0 = (w0 >> (8 * (r & 3))) & 0xFFu, c1 = (w1 >> (8 * (r & 3))) & 0xFFu;
+      if (c0) atomicAdd(e.nnz + m_lane + r, c0);
+      if (c1) atomicAdd(e.nnz + m_lane + 32 + r, c1);
+    }
+  }
+};
+
+// C[map[m]][n], n contiguous: the rows of the result are scattered through a row map (the split weight-gradient
+// GEMMs work on a permutation of the hidden features and write each row back to its feature).
+struct EpiRowMajorMapped {
+  struct Args { __bf16* C; int ldc; const int* rowmap; };
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+#pragma unroll
+    for (int mi = 0; mi < 4; mi++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        u32x2 o;
+        o[0] = pack_bf16x2(acc[mi][0][v], acc[mi][1][v]);
+        o[1] = pack_bf16x2(acc[mi][2][v], acc[mi][3][v]);
+        *reinterpret_cast<u32x2*>(e.C + (size_t)e.rowmap[m_lane + 16 * mi + v] * e.ldc + n_lane) = o;
+      }
   }
 };
 

@@ -15,4 +15,18 @@ int launch_sp_colmajor(const void* vals, const uint8_t* meta, int a_panel, const
   return launch_gemm<true, EpiColMajor>(g, ea, s);
 }
 
+// split weight gradients: result rows scattered through a row map
+int launch_sp_rowmajor_mapped(const void* vals, const uint8_t* meta, const void* B, int M, int N, int K, void* C, int ldc,
+                              const int* rowmap, hipStream_t s) {
+  GemmArgs g{vals, meta, B, M, N, K, 1};
+  EpiRowMajorMapped::Args ea{static_cast<__bf16*>(C), ldc, rowmap};
+  return launch_gemm<true, EpiRowMajorMapped>(g, ea, s);
+}
+
+int launch_dense_rowmajor_mapped(const void* A, const void* B, int M, int N, int K, void* C, int ldc, const int* rowmap, hipStream_t s) {
+  GemmArgs g{A, nullptr, B, M, N, K, 1};
+  EpiRowMajorMapped::Args ea{static_cast<__bf16*>(C), ldc, rowmap};
+  return launch_gemm<false, EpiRowMajorMapped>(g, ea, s);
+}
+
 }  // namespace ffn24

@@ -5,9 +5,9 @@
 namespace ffn24 {
 
 int launch_up_prune24(const void* W1t, const void* X, const float* b1, int T, int D, int F,
-                      void* Hc, uint8_t* meta, void* Hdbg, hipStream_t s) {
+                      void* Hc, uint8_t* meta, void* Hdbg, uint32_t* nnz, hipStream_t s) {
   GemmArgs g{W1t, nullptr, X, F, T, D, 1};
-  EpiPrune24::Args ea{static_cast<__bf16*>(Hc), meta, static_cast<__bf16*>(Hdbg), b1, F};
+  EpiPrune24::Args ea{static_cast<__bf16*>(Hc), meta, static_cast<__bf16*>(Hdbg), b1, F, nnz};
   return launch_gemm<false, EpiPrune24>(g, ea, s);
 }
 

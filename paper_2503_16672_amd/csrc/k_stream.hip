@@ -62,11 +62,15 @@ int launch_sparsify24(const void* H, int64_t rows, int64_t cols, void* vals, uin
 // row-major, where a feature row's outputs are written 128 bytes at a time.
 constexpr int FW_TOK = 128, FW_FEAT = 64, FW_LD = FW_FEAT + 2;
 
-template <bool PANEL>
+// SPLIT (Sec. 2, "Optimization 1"; panel form only): feature f becomes row row_of_feat[f] of the outputs; rows below
+// n_sparse are 2:4-compressed along tokens as above, the others -- the least sparse features -- are written out
+// uncompressed, as rows [row - n_sparse] of the dense operands Hdn_t, dZdn_t [n_dense][T] (dense panel form).
+template <bool PANEL, bool SPLIT = false>
 __global__ void __launch_bounds__(256) featurewise24_kernel(const uint16_t* __restrict__ Hc, const uint8_t* __restrict__ meta,
                                                             const uint16_t* __restrict__ dZc, int T, int F,
                                                             uint16_t* __restrict__ Hc_t, uint8_t* __restrict__ meta_t,
-                                                            uint16_t* __restrict__ dZc_t) {
+                                                            uint16_t* __restrict__ dZc_t, const int* __restrict__ row_of_feat,
+                                                            int n_sparse, uint16_t* __restrict__ Hdn_t, uint16_t* __restrict__ dZdn_t) {
   __shared__ uint16_t sH[FW_TOK * FW_LD];
   __shared__ uint16_t sZ[FW_TOK * FW_LD];
   int f0 = blockIdx.x * FW_FEAT, t0 = blockIdx.y * FW_TOK;
@@ -121,6 +125,16 @@ __global__ void __launch_bounds__(256) featurewise24_kernel(const uint16_t* __re
       h[j] = sH[(8 * oct + j) * FW_LD + f];
       z[j] = sZ[(8 * oct + j) * FW_LD + f];
     }
+    int orow = f0 + f;
+    if constexpr (SPLIT) {
+      orow = row_of_feat[f0 + f];
+      if (orow >= n_sparse) {   // dense feature: its 8 tokens as they are (already token-wise pruned)
+        size_t o = a24_piece(orow - n_sparse, (t0 + 8 * oct) >> 5, T >> 5) * 32 + ((t0 + 8 * oct) & 31);
+        *reinterpret_cast<u32x4*>(Hdn_t + o) = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+        if (has_z) *reinterpret_cast<u32x4*>(dZdn_t + o) = u32x4{z[0] | (z[1] << 16), z[2] | (z[3] << 16), z[4] | (z[5] << 16), z[6] | (z[7] << 16)};
+        continue;
+      }
+    }
     uint32_t hp[2], zp[2], nb[2];
 #pragma unroll
     for (int g = 0; g < 2; g++) {
@@ -132,7 +146,7 @@ __global__ void __launch_bounds__(256) featurewise24_kernel(const uint16_t* __re
     }
     size_t vo, mo;
     if constexpr (PANEL) {
-      size_t piece = a24_piece(f0 + f, (t0 + 8 * oct) >> 6, T >> 6);
+      size_t piece = a24_piece(orow, (t0 + 8 * oct) >> 6, T >> 6);
       vo = piece * 32 + 4 * (oct & 7);
       mo = piece * 8 + (oct & 7);
     } else {
@@ -151,7 +165,93 @@ int launch_featurewise24(const void* Hc, const uint8_t* meta, const void* dZc, i
   dim3 grid(F / FW_FEAT, T / FW_TOK);
   auto kern = panel ? featurewise24_kernel<true> : featurewise24_kernel<false>;
   hipLaunchKernelGGL(kern, grid, dim3(256), 0, s, static_cast<const uint16_t*>(Hc), meta,
-                     static_cast<const uint16_t*>(dZc), T, F, static_cast<uint16_t*>(Hc_t), meta_t, static_cast<uint16_t*>(dZc_t));
+                     static_cast<const uint16_t*>(dZc), T, F, static_cast<uint16_t*>(Hc_t), meta_t, static_cast<uint16_t*>(dZc_t),
+                     nullptr, 0, nullptr, nullptr);
+  return (int)hipGetLastError();
+}
+
+int launch_featurewise24_split(const void* Hc, const uint8_t* meta, const void* dZc, int T, int F, const int* row_of_feat, int n_sparse,
+                               void* Hc_t, uint8_t* meta_t, void* dZc_t, void* Hdn_t, void* dZdn_t, hipStream_t s) {
+  dim3 grid(F / FW_FEAT, T / FW_TOK);
+  hipLaunchKernelGGL((featurewise24_kernel<true, true>), grid, dim3(256), 0, s, static_cast<const uint16_t*>(Hc), meta,
+                     static_cast<const uint16_t*>(dZc), T, F, static_cast<uint16_t*>(Hc_t), meta_t, static_cast<uint16_t*>(dZc_t),
+                     row_of_feat, n_sparse, static_cast<uint16_t*>(Hdn_t), static_cast<uint16_t*>(dZdn_t));
+  return (int)hipGetLastError();
+}
+
+// Feature partition of the split weight-gradient GEMMs (Sec. 2, "Optimization 1": the paper's "cheap argsort kernel").
+// Only the set matters, so no sort: the threshold count c* = the smallest c with #{nnz > c} <= n_dense is found by
+// bisection; every feature above it is dense, and of those equal to it the first (n_dense - #above) by index.
+// Sparse features become rows 0 .. F - n_dense - 1, dense ones the rows after, both in ascending feature order.
+// One workgroup of 1024; F <= 2^20.
+__global__ void __launch_bounds__(1024) split_partition_kernel(const uint32_t* __restrict__ nnz, int F, int n_dense,
+                                                               int* __restrict__ row_of_feat, int* __restrict__ feat_of_row) {
+  __shared__ int s_red[1024];
+  __shared__ int s_scan_eq[1024], s_scan_d[1024];
+  const int tid = threadIdx.x;
+  const int per = (F + 1023) / 1024;                 // consecutive features per thread
+  const int f_lo = min(tid * per, F), f_hi = min(f_lo + per, F);
+  auto block_sum = [&](int v) {
+    s_red[tid] = v;
+    __syncthreads();
+    for (int st = 512; st > 0; st >>= 1) {
+      if (tid < st) s_red[tid] += s_red[tid + st];
+      __syncthreads();
+    }
+    int r = s_red[0];
+    __syncthreads();
+    return r;
+  };
+  // bisection on the count: invariant #{nnz > hi} <= n_dense, (lo == -1 or #{nnz > lo} > n_dense)
+  long long lo = -1, hi = 0xFFFFFFFFll;
+  while (hi - lo > 1) {
+    long long mid = (lo + hi) >> 1;
+    int c = 0;
+    for (int f = f_lo; f < f_hi; f++) c += (long long)nnz[f] > mid;
+    if (block_sum(c) <= n_dense) hi = mid; else lo = mid;
+  }
+  const uint32_t cstar = (uint32_t)hi;
+  int above = 0, equal = 0;
+  for (int f = f_lo; f < f_hi; f++) { above += nnz[f] > cstar; equal += nnz[f] == cstar; }
+  const int n_above = block_sum(above);
+  const int take_eq = n_dense - n_above;             // how many of the features equal to c* become dense (by index)
+  // exclusive scan of `equal` over threads
+  auto block_excl_scan = [&](int v, int* buf) {
+    buf[tid] = v;
+    __syncthreads();
+    for (int st = 1; st < 1024; st <<= 1) {
+      int add = tid >= st ? buf[tid - st] : 0;
+      __syncthreads();
+      buf[tid] += add;
+      __syncthreads();
+    }
+    return buf[tid] - v;
+  };
+  int eq_before = block_excl_scan(equal, s_scan_eq);
+  int dense_here = 0;
+  {
+    int e = eq_before;
+    for (int f = f_lo; f < f_hi; f++) {
+      bool d = nnz[f] > cstar || (nnz[f] == cstar && e < take_eq);
+      e += nnz[f] == cstar;
+      dense_here += d;
+    }
+  }
+  int d_before = block_excl_scan(dense_here, s_scan_d);
+  const int n_sparse = F - n_dense;
+  int e = eq_before, dpos = d_before;
+  for (int f = f_lo; f < f_hi; f++) {
+    bool d = nnz[f] > cstar || (nnz[f] == cstar && e < take_eq);
+    e += nnz[f] == cstar;
+    int row = d ? n_sparse + dpos : f - dpos;
+    dpos += d;
+    row_of_feat[f] = row;
+    feat_of_row[row] = f;
+  }
+}
+
+int launch_split_partition(const uint32_t* nnz, int F, int n_dense, int* row_of_feat, int* feat_of_row, hipStream_t s) {
+  hipLaunchKernelGGL(split_partition_kernel, dim3(1), dim3(1024), 0, s, nnz, F, n_dense, row_of_feat, feat_of_row);
   return (int)hipGetLastError();
 }
 

@@ -9,8 +9,9 @@ namespace ffn24 {
 // M % 256 == 0, N % 256 == 0, K % 64 == 0, 16-byte aligned pointers.  Every GEMM operand is K-contiguous.
 
 // up-projection with rows = hidden features: A = W1^T [F][D] in dense panel form, B = X [T][D]
+// nnz (may be NULL): [F] per-feature non-zero counts, accumulated with atomics (zeroed by the caller)
 int launch_up_prune24(const void* W1t, const void* X, const float* b1, int T, int D, int F,
-                      void* Hc, uint8_t* meta, void* Hdbg, hipStream_t s);
+                      void* Hc, uint8_t* meta, void* Hdbg, uint32_t* nnz, hipStream_t s);
 int launch_up_relu2(const void* W1t, const void* X, const float* b1, int T, int D, int F, void* H, void* Ht, hipStream_t s);
 // C[M][N] = A24[M][K] * B[N][K]^T; a_panel: (vals, meta) are in panel form instead of row-major
 int launch_sp_rowmajor(const void* vals, const uint8_t* meta, int a_panel, const void* B, int M, int N, int K, void* C, hipStream_t s);
@@ -19,6 +20,17 @@ int launch_sp_colmajor(const void* vals, const uint8_t* meta, int a_panel, const
 // dH = dY W2^T with rows = hidden features: A = W2 [F][D] in dense panel form, B = dY [T][D]; pointwise part fused
 int launch_dh_gather(const void* W2, const void* dY, const void* Hc, const uint8_t* meta, int T, int D, int F, void* dZc, hipStream_t s);
 int launch_dh_drelu(const void* W2, const void* dY, const void* H, int T, int D, int F, void* dZ, void* dZt, hipStream_t s);
+// split weight gradients (A in panel form): row m of the result goes to C[rowmap[m]][*]
+int launch_sp_rowmajor_mapped(const void* vals, const uint8_t* meta, const void* B, int M, int N, int K, void* C, int ldc,
+                              const int* rowmap, hipStream_t s);
+int launch_dense_rowmajor_mapped(const void* A, const void* B, int M, int N, int K, void* C, int ldc, const int* rowmap, hipStream_t s);
+// feature partition for the split (one workgroup): the n_dense features with the largest counts (ties: lower index)
+// become rows [F - n_dense, F) of the split operands, the others rows [0, F - n_dense), both in ascending feature order
+int launch_split_partition(const uint32_t* nnz, int F, int n_dense, int* row_of_feat, int* feat_of_row, hipStream_t s);
+// feature-wise re-compression with the split: sparse features as in launch_featurewise24 (panel form, row = row_of_feat),
+// dense features as plain [n_dense][T] rows of H24 and dZ24 in dense panel form
+int launch_featurewise24_split(const void* Hc, const uint8_t* meta, const void* dZc, int T, int F, const int* row_of_feat, int n_sparse,
+                               void* Hc_t, uint8_t* meta_t, void* dZc_t, void* Hdn_t, void* dZdn_t, hipStream_t s);
 // dense GEMMs: A [M][K] (a_panel: in dense panel form), B [N][K]
 int launch_dense_rowmajor(const void* A, int a_panel, const void* B, int M, int N, int K, void* C, hipStream_t s);
 int launch_dense_colmajor(const void* A, int a_panel, const void* B, int M, int N, int K, void* Ct, hipStream_t s);

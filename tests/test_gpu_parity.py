@@ -641,3 +641,90 @@ def test_ffn24_fwd_full_size_other_configs(F24, name):
         print(f"  zeros {1 - p:.4f}  dropped non-zeros {dropped:.5f}", flush=True)
         assert 0.89 < 1 - p < 0.94 and dropped < 0.03
     ctx.close()
+
+
+# ----------------------------------------------------------------------------- split weight gradients (Optimization 1)
+def _check_split(F24, T, D, Fh, sparsity, seed, n_dense, sample=None):
+    inp = synth.make_inputs(T, D, Fh, sparsity, seed, with_dy=True)
+    d = _upload(inp)
+    ctx = F24.Context(T, D, Fh, F24.FFN24_DEBUG_DUMP_H | F24.FFN24_TRAINING | F24.FFN24_SPLIT)
+    ctx.set_split(n_dense)
+    Y = ctx.ffn24_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    dX, dW1, dW2 = ctx.ffn24_bwd(d["dY"])
+    torch.cuda.synchronize()
+    # statistic and partition: bit-exact against the oracle on the activation the kernel itself rounded
+    nnz = ctx.saved("nnz").cpu().numpy().astype(np.int64)
+    Hd = ctx.saved("H_dump")
+    nnz_ref = torch.count_nonzero(Hd, dim=0).cpu().numpy().astype(np.int64) if sample is not None else O.feature_nnz(f64(Hd))
+    if sample is not None:                      # the library count of torch is only a shortcut for 2.7e8 elements:
+        cols = sample[:8]                       # the oracle's own count on a few columns pins it
+        assert np.array_equal(O.feature_nnz(f64(Hd[:, torch.from_numpy(cols).cuda()])), nnz_ref[cols])
+    assert np.array_equal(nnz, nnz_ref)
+    dense = O.split_features(nnz, n_dense)
+    feat_of_row = ctx.saved("feat_of_row").cpu().numpy()
+    ns = Fh - n_dense
+    assert np.array_equal(feat_of_row[:ns], np.flatnonzero(~dense)) and np.array_equal(feat_of_row[ns:], np.flatnonzero(dense))
+    # gradients: oracle backward on the GPU's own forward state, with the same partition
+    meta = ctx.saved("meta").cpu().numpy(); Hc_w = words_of(ctx.saved("Hc"))
+    if sample is None:
+        fwd = O.fwd_from_saved(Hc_w, meta, inp["X"], inp["W1"], inp["W2"])
+        ref = O.ffn24_bwd(fwd, inp["dY"], dense_features=dense)
+        plain = O.ffn24_bwd(fwd, inp["dY"])
+        errs = {k: O.max_rel_err(f64(a), ref[k]) for a, k in ((dX, "dX"), (dW1, "dW1"), (dW2, "dW2"))}
+        differs = O.max_rel_err(plain["dW2"], ref["dW2"])
+        print(f"  split n_dense={n_dense}: errs {errs}  (split vs unsplit oracle dW2 differ by {differs:.2e})", flush=True)
+        assert max(errs.values()) <= TOL_BF16
+        assert differs > 1e-3      # the case does exercise the split
+    else:
+        # full size: a sample of features from both parts, over all tokens, from the GPU's own Hc / dZc
+        gsel = np.unique(sample // 4)
+        f4, f2 = _groups_to_cols(gsel)
+        f2_t = torch.from_numpy(f2).cuda(); f4_t = torch.from_numpy(f4).cuda()
+        meta_g = _meta_of_groups(meta, gsel)
+        H24_g = O.bf16_bits_to_f32(O.decompress24(Hc_w[:, f2], meta_g)).astype(np.float64)
+        dZ24_g = O.bf16_bits_to_f32(O.decompress24(words_of(ctx.saved("dZc")[:, f2_t]), meta_g)).astype(np.float64)
+        _, _, M_T = O.featurewise24(H24_g.astype(np.float32))
+        Mw = np.where(dense[f4][None, :], True, M_T)
+        dW2_ref = np.where(Mw, H24_g, 0.0).T @ f64(d["dY"])
+        dW1_ref = f64(d["X"]).T @ np.where(Mw, dZ24_g, 0.0)
+        e2 = O.max_rel_err(f64(dW2[f4_t]), dW2_ref); e1 = O.max_rel_err(f64(dW1[:, f4_t]), dW1_ref)
+        print(f"  split n_dense={n_dense} full size: {int(dense[f4].sum())} dense / {len(f4)} sampled features, dW2 {e2:.2e} dW1 {e1:.2e}", flush=True)
+        assert e1 <= TOL_BF16 and e2 <= TOL_BF16 and 0 < dense[f4].sum() < len(f4)
+    ctx.close()
+
+
+@pytest.mark.parametrize("n_dense", [256, 512])
+def test_ffn24_split_small(F24, n_dense):
+    print(f"split weight gradients T=512 D=256 F=2048 n_dense={n_dense}", flush=True)
+    _check_split(F24, 512, 256, 2048, "per_feature", seed=61, n_dense=n_dense)
+
+
+def test_ffn24_split_rules(F24):
+    ctx = F24.Context(256, 256, 1024, F24.FFN24_TRAINING | F24.FFN24_SPLIT)
+    for bad in (100, 512, -256):                     # not a multiple of 256; more than F/4; negative
+        with pytest.raises(F24.Ffn24Error) as e:
+            ctx.set_split(bad)
+        assert e.value.code == -2
+    ctx.set_split(256)
+    with pytest.raises(F24.Ffn24Error) as e:         # a backward needs the forward that counted
+        ctx.ffn24_bwd(torch.zeros((256, 256), dtype=torch.bfloat16, device="cuda"))
+    assert e.value.code == -5
+    ctx.close()
+    ctx = F24.Context(256, 256, 1024, F24.FFN24_TRAINING)
+    with pytest.raises(F24.Ffn24Error) as e:
+        ctx.set_split(256)
+    assert e.value.code == -5
+    ctx.close()
+
+
+@pytest.mark.timeout(900)
+def test_ffn24_split_full_size_sampled(F24):
+    """c4 with 1024 of the 16384 features (6.25 %) kept dense: statistic and partition bit-exact at full size, weight
+    gradients on a sample of features from both parts."""
+    w = synth.WORKLOADS["c4"]
+    print("split full size c4, n_dense=1024", flush=True)
+    rng = np.random.default_rng(48)
+    # with a uniform bias every feature has about the same count, so the partition is decided by sampling noise:
+    # take the sample after the fact from both parts -- here simply many features, the check requires both kinds
+    sample = np.sort(rng.choice(w.F, 400, replace=False))
+    _check_split(F24, w.T, w.D, w.F, "per_feature", w.seed, 1024, sample=sample)
