@@ -86,6 +86,60 @@ def run_c3(args) -> int:
     return 0
 
 
+def run_split_sweep(args) -> int:
+    """Weight-gradient stage (dW2 and dW1, K = tokens) against the number of hidden features kept dense: the split
+    GEMM of the paper's second kernel benchmark (operand 90 % zeros).  Each point times, from HIP events inside the
+    library, everything the split adds or changes: partition, feature-wise kernel, sparse + dense GEMMs, dW1 transpose."""
+    import torch
+    from paper_2503_16672_amd import ffn24, synth
+    w = synth.WORKLOADS[args.workload]
+    T, D, F = w.T, w.D, w.F
+    inp = synth.make_workload(args.workload, with_dy=True)
+    dev = {k: torch.from_numpy(inp[k]).to(torch.bfloat16).cuda() for k in ("X", "W1", "W2", "dY")}
+    b1 = torch.from_numpy(inp["b1"]).cuda()
+    ctx = ffn24.Context(T, D, F, ffn24.FFN24_TRAINING | ffn24.FFN24_DENSE | ffn24.FFN24_SPLIT)
+    Y = torch.empty((T, D), dtype=torch.bfloat16, device="cuda")
+    grads = (torch.empty((T, D), dtype=torch.bfloat16, device="cuda"), torch.empty((D, F), dtype=torch.bfloat16, device="cuda"),
+             torch.empty((F, D), dtype=torch.bfloat16, device="cuda"))
+    ctx.set_profiling(True)
+    flops = 4.0 * T * D * F            # dense-equivalent flops of the two weight-gradient GEMMs
+    points = []
+    for nd in [0, 256, 512, 1024, 2048, 4096]:
+        if nd > F // 4:
+            continue
+        ctx.set_split(nd)
+        ids = [4, 5, 6] + ([15, 16] if nd else [])
+        acc = {k: 0.0 for k in ids}
+        up = 0.0
+        for it in range(args.warmup + args.steps):
+            ctx.ffn24_fwd(dev["X"], dev["W1"], b1, dev["W2"], Y)
+            ctx.ffn24_bwd(dev["dY"], grads)
+            torch.cuda.synchronize()
+            if it >= args.warmup:
+                up += ctx.kernel_ms(0)
+                for k in ids:
+                    acc[k] += ctx.kernel_ms(k)
+        ms = {ffn24.KERNEL_NAMES[k]: round(v / args.steps, 4) for k, v in acc.items()}
+        gemm_ms = sum(v for n, v in ms.items() if n in ("dw2_sp", "dw1_sp"))
+        stage_ms = sum(ms.values())
+        points.append({"n_dense": nd, "dense_fraction": round(nd / F, 4), "gemms_ms": round(gemm_ms, 4), "gemms_tflops": round(flops / gemm_ms / 1e9, 1),
+                       "stage_ms": round(stage_ms, 4), "up_prune24_ms": round(up / args.steps, 4), "kernels": ms})
+    dd = 0.0
+    for it in range(args.warmup + args.steps):
+        ctx.ffn_fwd(dev["X"], dev["W1"], b1, dev["W2"], Y)
+        ctx.ffn_bwd(dev["dY"], grads)
+        torch.cuda.synchronize()
+        if it >= args.warmup:
+            dd += ctx.kernel_ms(11) + ctx.kernel_ms(12)
+    dense_ms = dd / args.steps
+    ctx.close()
+    print(json.dumps({"metric": "split weight-gradient GEMMs, dense-equiv TFLOP/s", "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+                      "warmup": args.warmup, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": f"{w.name}: dW2 + dW1 of the 2:4 FFN, T={T} d_model={D} d_ff={F}, target sparsity {w.sparsity}"},
+                      "fully_dense_gemms": {"ms": round(dense_ms, 4), "tflops": round(flops / dense_ms / 1e9, 1)}, "points": points}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -95,6 +149,9 @@ def main() -> int:
     ap.add_argument("--fwd-only", action="store_true", help="time the forward pass only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-tokens", type=int, default=2048, help="token slice the CPU oracle is timed on")
+    ap.add_argument("--split", type=int, default=0, help="keep this many hidden features (multiple of 256, <= d_ff/4) out of the "
+                    "feature-wise 2:4: split weight-gradient GEMMs (bf16 fwd+bwd workloads)")
+    ap.add_argument("--split-sweep", action="store_true", help="time the weight-gradient stage over a range of split sizes")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy before the steps (the known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -109,6 +166,8 @@ def main() -> int:
     ffn24.lib()  # fails loudly if libffn24.so is not built; there is no fallback path
     if args.workload == "c3":
         return run_c3(args)
+    if args.split_sweep:
+        return run_split_sweep(args)
     w = synth.WORKLOADS[args.workload]
     T, D, F = w.T, w.D, w.F
     fp8 = args.workload == "c5"
@@ -121,7 +180,9 @@ def main() -> int:
     else:
         inp = synth.make_workload(args.workload, with_dy=True)
         dev = {k: torch.from_numpy(inp[k]).to(torch.bfloat16).cuda() for k in ("X", "W1", "W2", "dY")}
-        ctx = ffn24.Context(T, D, F, (ffn24.FFN24_TRAINING if bwd else 0) | ffn24.FFN24_DENSE)
+        ctx = ffn24.Context(T, D, F, (ffn24.FFN24_TRAINING if bwd else 0) | ffn24.FFN24_DENSE | (ffn24.FFN24_SPLIT if args.split and bwd else 0))
+        if args.split and bwd:
+            ctx.set_split(args.split)
     b1 = torch.from_numpy(inp["b1"]).cuda()
     peak = PEAK_FP8_DENSE if fp8 else PEAK_BF16_DENSE
     Y = torch.empty((T, D), dtype=torch.bfloat16, device="cuda")
@@ -158,7 +219,7 @@ def main() -> int:
     ctx.set_profiling(True)   # event pairs around every kernel, on the launch stream; no synchronisation added
     sec24 = timed(step24, args.warmup, args.steps)
     # per-kernel durations: average over the same number of steps, reading the events after each step
-    k24 = list(range(0, 7 if bwd else 2)) + ([13, 14] if bwd else [13])
+    k24 = list(range(0, 7 if bwd else 2)) + ([13, 14] if bwd else [13]) + ([15, 16] if args.split and bwd else [])
     kd = list(range(7, 13 if bwd else 9))
     acc = {k: 0.0 for k in k24 + kd}
     for _ in range(args.steps):
@@ -211,7 +272,11 @@ def main() -> int:
             # reads and writes 2 x 2 bytes per element of its two matrices
             # (the forward's weight pass also writes a panel-form copy of W2 when the context trains: 10 D F bytes then)
             es = 1.0 if fp8 else 2.0
-            nbytes = {"featurewise24": 4.25 * T * F, "transpose_weights": (5.0 if bwd else 4.0) * es * D * F, "transpose_acts": 8.0 * T * D}[name]
+            if name == "split_partition":
+                kernels[name] = {"ms": round(ms, 4)}
+                continue
+            nbytes = {"featurewise24": 4.25 * T * F, "transpose_weights": (5.0 if bwd else 4.0) * es * D * F, "transpose_acts": 8.0 * T * D,
+                      "transpose_dw1": 4.0 * D * F}[name]
             gbs = nbytes / (ms * 1e-3) / 1e9
             kernels[name] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / 8000.0, 4)}
     dom = max((n for n in kernel_ms if n in KERNEL_FLOPS and not n.startswith("dense_")), key=lambda n: kernel_ms[n])
@@ -241,7 +306,8 @@ def main() -> int:
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(sec24 * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "fp8" if fp8 else "bf16", "data": "synthetic",
-        "config": {"workload": f"{w.name}: 2:4 Squared-ReLU FFN {'fwd+bwd' if bwd else 'fwd'}, T={T} d_model={D} d_ff={F}, target sparsity {w.sparsity}",
+        "config": {"workload": f"{w.name}: 2:4 Squared-ReLU FFN {'fwd+bwd' if bwd else 'fwd'}, T={T} d_model={D} d_ff={F}, target sparsity {w.sparsity}"
+                               + (f", {args.split} dense features in the weight gradients" if args.split and bwd else ""),
                    "T": T, "d_model": D, "d_ff": F, "parallelism": "single GPU"},
         "frac_of_sparse_mfma_peak": round(value / (2 * peak), 4),
         "dense_ffn": {"ms_per_step": round(sec_dense * 1e3, 4), "tflops": round(flops_step / sec_dense / 1e12, 2)},

@@ -150,8 +150,8 @@ FFN24_API int ffn24_copy_saved(ffn24_ctx* ctx, int which, void* dst, int64_t dst
  * Kernel ids: 0 up-projection+prune, 1 sparse down-projection, 2 dH+derivative, 3 sparse dX, 4 feature-wise
  * re-compression, 5 sparse dW2, 6 sparse dW1, 7..12 the six dense-baseline GEMMs in the same order
  * (up, down, dH, dX, dW2, dW1), 13 the two weight transposes of a forward (W1, W2 -> K-contiguous), 14 the two
- * activation transposes of a backward (dY, X), 15 the feature partition of the split, 16 the two dense GEMMs of the
- * split (with a split, 5 and 6 are its two sparse GEMMs), 17 the transpose that brings dW1 into [D][F] after a split.  Returns FFN24_ERR_STATE if that kernel has not run with profiling on. */
+ * activation transposes of a backward (dY, X), 15 the feature partition of the split, 16 the transpose that brings
+ * dW1 into [D][F] after a split (with a split, 5 and 6 are the combined sparse + dense launches of dW2 and dW1).  Returns FFN24_ERR_STATE if that kernel has not run with profiling on. */
 FFN24_API int ffn24_set_profiling(ffn24_ctx* ctx, int on);
 FFN24_API int ffn24_kernel_ms(ffn24_ctx* ctx, int kernel, float* ms);
 

@@ -7,8 +7,8 @@
 using namespace ffn24;
 
 namespace {
-constexpr int NUM_KERNELS = 18;
-enum { K_UP = 0, K_DOWN, K_DH, K_DX, K_FW, K_DW2, K_DW1, KD_UP, KD_DOWN, KD_DH, KD_DX, KD_DW2, KD_DW1, K_TR_W, K_TR_ACT, K_PART, K_SPLIT_DENSE, K_TR_DW1 };
+constexpr int NUM_KERNELS = 17;
+enum { K_UP = 0, K_DOWN, K_DH, K_DX, K_FW, K_DW2, K_DW1, KD_UP, KD_DOWN, KD_DH, KD_DX, KD_DW2, KD_DW1, K_TR_W, K_TR_ACT, K_PART, K_TR_DW1 };
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 }  // namespace
@@ -280,18 +280,15 @@ int ffn24_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void
     // Sec. 2, "Optimization 1": the n_dense least sparse features are kept out of the feature-wise 2:4; their rows
     // of both weight gradients come from dense GEMMs, all others from the sparse ones
     const int nd = c->n_dense, ns = F - nd;
-    { Timed t(c, K_PART, s); if (t.done(launch_split_partition(c->nnz, F, nd, c->row_of_feat, c->feat_of_row, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_PART, s); if (t.done(launch_split_partition(c->nnz, F, nd, T, c->row_of_feat, c->feat_of_row, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_FW, s);
       if (t.done(launch_featurewise24_split(c->Hc, c->meta, c->dZc, T, F, c->row_of_feat, ns, c->Hc_t, c->meta_t, c->dZc_t, c->Hdn_t, c->dZdn_t, s)))
         return FFN24_ERR_HIP; }
     { Timed t(c, K_TR_ACT, s);
       int rc1 = launch_transpose(dY, T, D, c->dYt, 0, nullptr, s);
       if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, 0, nullptr, s))) return FFN24_ERR_HIP; }
-    { Timed t(c, K_DW2, s); if (t.done(launch_sp_rowmajor_mapped(c->Hc_t, c->meta_t, c->dYt, ns, D, T, dW2, D, c->feat_of_row, s))) return FFN24_ERR_HIP; }
-    { Timed t(c, K_DW1, s); if (t.done(launch_sp_rowmajor_mapped(c->dZc_t, c->meta_t, c->Xt, ns, D, T, c->dW1t, D, c->feat_of_row, s))) return FFN24_ERR_HIP; }
-    { Timed t(c, K_SPLIT_DENSE, s);
-      int rc1 = launch_dense_rowmajor_mapped(c->Hdn_t, c->dYt, nd, D, T, dW2, D, c->feat_of_row + ns, s);
-      if (t.done(rc1 ? rc1 : launch_dense_rowmajor_mapped(c->dZdn_t, c->Xt, nd, D, T, c->dW1t, D, c->feat_of_row + ns, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_DW2, s); if (t.done(launch_split_wgrad(c->Hc_t, c->meta_t, ns, c->Hdn_t, nd, c->dYt, D, T, dW2, D, c->feat_of_row, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_DW1, s); if (t.done(launch_split_wgrad(c->dZc_t, c->meta_t, ns, c->dZdn_t, nd, c->Xt, D, T, c->dW1t, D, c->feat_of_row, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_TR_DW1, s); if (t.done(launch_transpose(c->dW1t, F, D, dW1, 0, nullptr, s))) return FFN24_ERR_HIP; }
     return FFN24_OK;
   }

@@ -313,9 +313,8 @@ __device__ __forceinline__ void mfma_sparse1(const FragS& f, const IdxWords<F8> 
 // tile id -> (tile_m, tile_n).  Consecutive workgroup ids go round-robin over the 8 XCDs (each with its own L2),
 // so ids are first regrouped so that each XCD works on a contiguous run of tiles, then walked in bands of
 // 8 tile-rows so that a band's A rows and the B columns it sweeps stay L2-resident.
-__device__ __forceinline__ void tile_coords(int ntm, int ntn, int& tm, int& tn) {
+__device__ __forceinline__ void tile_coords(int ntm, int ntn, int pid, int& tm, int& tn) {
   int nb = ntm * ntn;
-  int pid = blockIdx.x;
   if ((nb & 7) == 0) pid = (pid & 7) * (nb >> 3) + (pid >> 3);
   const int GROUP = 8;
   int per_group = GROUP * ntn;
@@ -330,16 +329,16 @@ __device__ __forceinline__ void tile_coords(int ntm, int ntn, int& tm, int& tn) 
 // Epilogue concept:  struct E { struct Args {...}; static __device__ void run(const Args&, acc, m_lane, n_lane); }
 //   m_lane = global row of acc[0][*][0] for this lane (its 64 rows are m_lane + 16*mi + v),
 //   n_lane = global column of acc[*][0][*] (its 4 columns are n_lane + ni).
+// One block tile of one GEMM: tile number `pid` of g (workgroup-uniform), LDS ring at `smem`.
 template <bool SPARSE, class Epi, bool F8 = false>
-__global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(GemmArgs g, typename Epi::Args ea) {
-  extern __shared__ __attribute__((aligned(1024))) char smem[];
+__device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi::Args& ea, char* smem, int pid) {
   using G = Geo<SPARSE, F8>;
   constexpr int NB = G::NB, NDMA = G::NDMA;
 
   int tid = threadIdx.x;
   int lane = tid & 63, wave = tid >> 6;
   int tm, tn;
-  tile_coords(g.M / TILE_M, g.N / TILE_N, tm, tn);
+  tile_coords(g.M / TILE_M, g.N / TILE_N, pid, tm, tn);
   int m0 = tm * TILE_M, n0 = tn * TILE_N;
 
   LaneCtx L;
@@ -512,6 +511,26 @@ __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(GemmArgs g, typename
   int m_lane = m0 + L.wy * 128 + 64 * L.h;
   int n_lane = n0 + L.wx * 128 + 4 * L.rho;
   Epi::run(ea, acc, m_lane, n_lane);
+}
+
+template <bool SPARSE, class Epi, bool F8 = false>
+__global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(GemmArgs g, typename Epi::Args ea) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  gemm_tile<SPARSE, Epi, F8>(g, ea, smem, blockIdx.x);
+}
+
+// Two GEMMs in one launch: the first `nd_tiles` workgroups compute the tiles of a dense GEMM gd, the others those of
+// a sparse GEMM gs (same epilogue type, separate arguments).  The split weight-gradient GEMMs use it (Sec. 2,
+// "Optimization 1": a 2:4 GEMM over most hidden features plus a dense one over the few that are not sparse enough):
+// alone, the small dense GEMM would occupy a fraction of the CUs for as long as a full round of tiles.  The dense
+// tiles, which take longer, come first.
+template <class Epi>
+__global__ void __launch_bounds__(GEMM_THREADS) gemm_pair_kernel(GemmArgs gd, typename Epi::Args ead, int nd_tiles,
+                                                                  GemmArgs gs, typename Epi::Args eas) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int pid = blockIdx.x;
+  if (pid < nd_tiles) gemm_tile<false, Epi>(gd, ead, smem, pid);
+  else gemm_tile<true, Epi>(gs, eas, smem, pid - nd_tiles);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -15,18 +15,15 @@ int launch_sp_colmajor(const void* vals, const uint8_t* meta, int a_panel, const
   return launch_gemm<true, EpiColMajor>(g, ea, s);
 }
 
-// split weight gradients: result rows scattered through a row map
-int launch_sp_rowmajor_mapped(const void* vals, const uint8_t* meta, const void* B, int M, int N, int K, void* C, int ldc,
-                              const int* rowmap, hipStream_t s) {
-  GemmArgs g{vals, meta, B, M, N, K, 1};
-  EpiRowMajorMapped::Args ea{static_cast<__bf16*>(C), ldc, rowmap};
-  return launch_gemm<true, EpiRowMajorMapped>(g, ea, s);
-}
-
-int launch_dense_rowmajor_mapped(const void* A, const void* B, int M, int N, int K, void* C, int ldc, const int* rowmap, hipStream_t s) {
-  GemmArgs g{A, nullptr, B, M, N, K, 1};
-  EpiRowMajorMapped::Args ea{static_cast<__bf16*>(C), ldc, rowmap};
-  return launch_gemm<false, EpiRowMajorMapped>(g, ea, s);
+// split weight gradient: rows [0, ns) of the permuted feature space from the sparse GEMM over (vals, meta), rows
+// [ns, ns + nd) from the dense GEMM over Ad, both against the same B, in one launch; row m goes to C[rowmap[m]][*]
+int launch_split_wgrad(const void* vals, const uint8_t* meta, int ns, const void* Ad, int nd, const void* B, int N, int K,
+                       void* C, int ldc, const int* rowmap, hipStream_t s) {
+  GemmArgs gs{vals, meta, B, ns, N, K, 1};
+  GemmArgs gd{Ad, nullptr, B, nd, N, K, 1};
+  EpiRowMajorMapped::Args eas{static_cast<__bf16*>(C), ldc, rowmap};
+  EpiRowMajorMapped::Args ead{static_cast<__bf16*>(C), ldc, rowmap + ns};
+  return launch_gemm_pair<EpiRowMajorMapped>(gd, ead, gs, eas, s);
 }
 
 }  // namespace ffn24

@@ -181,53 +181,61 @@ int launch_featurewise24_split(const void* Hc, const uint8_t* meta, const void* 
 
 // Feature partition of the split weight-gradient GEMMs (Sec. 2, "Optimization 1": the paper's "cheap argsort kernel").
 // Only the set matters, so no sort: the threshold count c* = the smallest c with #{nnz > c} <= n_dense is found by
-// bisection; every feature above it is dense, and of those equal to it the first (n_dense - #above) by index.
-// Sparse features become rows 0 .. F - n_dense - 1, dense ones the rows after, both in ascending feature order.
-// One workgroup of 1024; F <= 2^20.
-__global__ void __launch_bounds__(1024) split_partition_kernel(const uint32_t* __restrict__ nnz, int F, int n_dense,
+// bisection over the counts (which sit in LDS); every feature above it is dense, and of those equal to it the first
+// (n_dense - #above) by index.  Sparse features become rows 0 .. F - n_dense - 1, dense ones the rows after, both in
+// ascending feature order.  One workgroup of 1024; F <= 2^20 (beyond 32768 features the counts stay in global memory).
+constexpr int PART_LDS_FEATS = 32768;
+
+__global__ void __launch_bounds__(1024) split_partition_kernel(const uint32_t* __restrict__ nnz_g, int F, int n_dense, uint32_t max_count,
                                                                int* __restrict__ row_of_feat, int* __restrict__ feat_of_row) {
-  __shared__ int s_red[1024];
-  __shared__ int s_scan_eq[1024], s_scan_d[1024];
-  const int tid = threadIdx.x;
-  const int per = (F + 1023) / 1024;                 // consecutive features per thread
-  const int f_lo = min(tid * per, F), f_hi = min(f_lo + per, F);
-  auto block_sum = [&](int v) {
-    s_red[tid] = v;
-    __syncthreads();
-    for (int st = 512; st > 0; st >>= 1) {
-      if (tid < st) s_red[tid] += s_red[tid + st];
-      __syncthreads();
+  extern __shared__ uint32_t s_nnz[];                // F counts if they fit
+  __shared__ int s_part[16];
+  __shared__ int s_total;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const bool in_lds = F <= PART_LDS_FEATS;
+  if (in_lds) for (int f = tid; f < F; f += 1024) s_nnz[f] = nnz_g[f];
+  __syncthreads();
+  const uint32_t* nnz = in_lds ? s_nnz : nnz_g;
+  // block-wide sum, and exclusive prefix over threads, of one int per thread (wave shuffles + 16 partials in LDS)
+  auto block_scan = [&](int v, int& total) {
+    int incl = v;
+#pragma unroll
+    for (int st = 1; st < 64; st <<= 1) {
+      int o = __shfl_up(incl, st, 64);
+      if (lane >= st) incl += o;
     }
-    int r = s_red[0];
+    if (lane == 63) s_part[wave] = incl;
     __syncthreads();
-    return r;
+    if (tid == 0) {
+      int run = 0;
+      for (int w = 0; w < 16; w++) { int x = s_part[w]; s_part[w] = run; run += x; }
+      s_total = run;
+    }
+    __syncthreads();
+    int excl = s_part[wave] + incl - v;
+    total = s_total;
+    __syncthreads();
+    return excl;
   };
-  // bisection on the count: invariant #{nnz > hi} <= n_dense, (lo == -1 or #{nnz > lo} > n_dense)
-  long long lo = -1, hi = 0xFFFFFFFFll;
+  // bisection: invariant #{nnz > hi} <= n_dense and (lo == -1 or #{nnz > lo} > n_dense); strided accesses here
+  long long lo = -1, hi = max_count;             // no count exceeds max_count (the number of tokens)
   while (hi - lo > 1) {
     long long mid = (lo + hi) >> 1;
-    int c = 0;
-    for (int f = f_lo; f < f_hi; f++) c += (long long)nnz[f] > mid;
-    if (block_sum(c) <= n_dense) hi = mid; else lo = mid;
+    int c = 0, total;
+    for (int f = tid; f < F; f += 1024) c += (long long)nnz[f] > mid;
+    block_scan(c, total);
+    if (total <= n_dense) hi = mid; else lo = mid;
   }
   const uint32_t cstar = (uint32_t)hi;
+  // consecutive features per thread from here on, so that ranks follow the feature index
+  const int per = (F + 1023) / 1024;
+  const int f_lo = min(tid * per, F), f_hi = min(f_lo + per, F);
   int above = 0, equal = 0;
   for (int f = f_lo; f < f_hi; f++) { above += nnz[f] > cstar; equal += nnz[f] == cstar; }
-  const int n_above = block_sum(above);
+  int n_above, n_equal;
+  block_scan(above, n_above);
   const int take_eq = n_dense - n_above;             // how many of the features equal to c* become dense (by index)
-  // exclusive scan of `equal` over threads
-  auto block_excl_scan = [&](int v, int* buf) {
-    buf[tid] = v;
-    __syncthreads();
-    for (int st = 1; st < 1024; st <<= 1) {
-      int add = tid >= st ? buf[tid - st] : 0;
-      __syncthreads();
-      buf[tid] += add;
-      __syncthreads();
-    }
-    return buf[tid] - v;
-  };
-  int eq_before = block_excl_scan(equal, s_scan_eq);
+  const int eq_before = block_scan(equal, n_equal);
   int dense_here = 0;
   {
     int e = eq_before;
@@ -237,7 +245,8 @@ __global__ void __launch_bounds__(1024) split_partition_kernel(const uint32_t* _
       dense_here += d;
     }
   }
-  int d_before = block_excl_scan(dense_here, s_scan_d);
+  int n_d;
+  const int d_before = block_scan(dense_here, n_d);
   const int n_sparse = F - n_dense;
   int e = eq_before, dpos = d_before;
   for (int f = f_lo; f < f_hi; f++) {
@@ -250,8 +259,19 @@ __global__ void __launch_bounds__(1024) split_partition_kernel(const uint32_t* _
   }
 }
 
-int launch_split_partition(const uint32_t* nnz, int F, int n_dense, int* row_of_feat, int* feat_of_row, hipStream_t s) {
-  hipLaunchKernelGGL(split_partition_kernel, dim3(1), dim3(1024), 0, s, nnz, F, n_dense, row_of_feat, feat_of_row);
+int launch_split_partition(const uint32_t* nnz, int F, int n_dense, int max_count, int* row_of_feat, int* feat_of_row, hipStream_t s) {
+  static bool configured[64] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return (int)e;
+  if (dev < 0 || dev >= 64) return (int)hipErrorInvalidDevice;
+  if (!configured[dev]) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(split_partition_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * PART_LDS_FEATS);
+    if (e != hipSuccess) return (int)e;
+    configured[dev] = true;
+  }
+  size_t lds = F <= PART_LDS_FEATS ? 4 * (size_t)F : 0;
+  hipLaunchKernelGGL(split_partition_kernel, dim3(1), dim3(1024), lds, s, nnz, F, n_dense, (uint32_t)max_count, row_of_feat, feat_of_row);
   return (int)hipGetLastError();
 }
 

@@ -20,13 +20,14 @@ int launch_sp_colmajor(const void* vals, const uint8_t* meta, int a_panel, const
 // dH = dY W2^T with rows = hidden features: A = W2 [F][D] in dense panel form, B = dY [T][D]; pointwise part fused
 int launch_dh_gather(const void* W2, const void* dY, const void* Hc, const uint8_t* meta, int T, int D, int F, void* dZc, hipStream_t s);
 int launch_dh_drelu(const void* W2, const void* dY, const void* H, int T, int D, int F, void* dZ, void* dZt, hipStream_t s);
-// split weight gradients (A in panel form): row m of the result goes to C[rowmap[m]][*]
-int launch_sp_rowmajor_mapped(const void* vals, const uint8_t* meta, const void* B, int M, int N, int K, void* C, int ldc,
-                              const int* rowmap, hipStream_t s);
-int launch_dense_rowmajor_mapped(const void* A, const void* B, int M, int N, int K, void* C, int ldc, const int* rowmap, hipStream_t s);
+// split weight gradient (operands in panel form): rows [0, ns) from the sparse GEMM over (vals, meta) [ns][K], rows
+// [ns, ns + nd) from the dense GEMM over Ad [nd][K], both against B [N][K], one launch; row m goes to C[rowmap[m]][*]
+int launch_split_wgrad(const void* vals, const uint8_t* meta, int ns, const void* Ad, int nd, const void* B, int N, int K,
+                       void* C, int ldc, const int* rowmap, hipStream_t s);
 // feature partition for the split (one workgroup): the n_dense features with the largest counts (ties: lower index)
 // become rows [F - n_dense, F) of the split operands, the others rows [0, F - n_dense), both in ascending feature order
-int launch_split_partition(const uint32_t* nnz, int F, int n_dense, int* row_of_feat, int* feat_of_row, hipStream_t s);
+// (max_count: an upper bound of every count, the number of tokens)
+int launch_split_partition(const uint32_t* nnz, int F, int n_dense, int max_count, int* row_of_feat, int* feat_of_row, hipStream_t s);
 // feature-wise re-compression with the split: sparse features as in launch_featurewise24 (panel form, row = row_of_feat),
 // dense features as plain [n_dense][T] rows of H24 and dZ24 in dense panel form
 int launch_featurewise24_split(const void* Hc, const uint8_t* meta, const void* dZc, int T, int F, const int* row_of_feat, int n_sparse,

@@ -25,4 +25,24 @@ static int launch_gemm(const GemmArgs& g, const typename Epi::Args& ea, hipStrea
   return (int)hipGetLastError();
 }
 
+// dense GEMM gd and sparse GEMM gs in one launch (gemm_pair_kernel)
+template <class Epi>
+static int launch_gemm_pair(const GemmArgs& gd, const typename Epi::Args& ead, const GemmArgs& gs, const typename Epi::Args& eas, hipStream_t s) {
+  auto kern = gemm_pair_kernel<Epi>;
+  constexpr int lds = Geo<true>::LDS_TOTAL > Geo<false>::LDS_TOTAL ? Geo<true>::LDS_TOTAL : Geo<false>::LDS_TOTAL;
+  static bool configured[64] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return (int)e;
+  if (dev < 0 || dev >= 64) return (int)hipErrorInvalidDevice;
+  if (!configured[dev]) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return (int)e;
+    configured[dev] = true;
+  }
+  int nd_tiles = (gd.M / TILE_M) * (gd.N / TILE_N), ns_tiles = (gs.M / TILE_M) * (gs.N / TILE_N);
+  hipLaunchKernelGGL(kern, dim3(nd_tiles + ns_tiles), dim3(GEMM_THREADS), lds, s, gd, ead, nd_tiles, gs, eas);
+  return (int)hipGetLastError();
+}
+
 }  // namespace ffn24
