@@ -151,6 +151,7 @@ def main() -> int:
     ap.add_argument("--cpu-tokens", type=int, default=2048, help="token slice the CPU oracle is timed on")
     ap.add_argument("--split", type=int, default=0, help="keep this many hidden features (multiple of 256, <= d_ff/4) out of the "
                     "feature-wise 2:4: split weight-gradient GEMMs (bf16 fwd+bwd workloads)")
+    ap.add_argument("--rowwise", action="store_true", help="fp8 workload with row-wise instead of per-tensor scales (no dense baseline in this mode)")
     ap.add_argument("--split-sweep", action="store_true", help="time the weight-gradient stage over a range of split sizes")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy before the steps (the known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE)")
@@ -172,7 +173,13 @@ def main() -> int:
     T, D, F = w.T, w.D, w.F
     fp8 = args.workload == "c5"
     bwd = not (args.fwd_only or fp8)
-    if fp8:
+    rowwise = fp8 and args.rowwise
+    if rowwise:
+        inp = synth.make_inputs_fp8_rowwise(T, D, F, w.sparsity, w.seed)
+        dev = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2", "sx", "sw1", "sw2")}
+        ctx = ffn24.Context(T, D, F, ffn24.FFN24_ROWWISE, dtype=ffn24.FFN24_FP8_E4M3)
+        ctx.set_row_scales(dev["sx"], dev["sw1"], dev["sw2"])
+    elif fp8:
         inp = synth.make_inputs_fp8(T, D, F, w.sparsity, w.seed)
         dev = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2")}
         ctx = ffn24.Context(T, D, F, ffn24.FFN24_DENSE, dtype=ffn24.FFN24_FP8_E4M3)
@@ -219,16 +226,16 @@ def main() -> int:
     ctx.set_profiling(True)   # event pairs around every kernel, on the launch stream; no synchronisation added
     sec24 = timed(step24, args.warmup, args.steps)
     # per-kernel durations: average over the same number of steps, reading the events after each step
-    k24 = list(range(0, 7 if bwd else 2)) + ([13, 14] if bwd else [13]) + ([15, 16] if args.split and bwd else [])
-    kd = list(range(7, 13 if bwd else 9))
+    k24 = list(range(0, 7 if bwd else 2)) + ([13, 14] if bwd else [13]) + ([15, 16] if args.split and bwd else []) + ([17] if rowwise else [])
+    kd = [] if rowwise else list(range(7, 13 if bwd else 9))
     acc = {k: 0.0 for k in k24 + kd}
     for _ in range(args.steps):
         step24()
         torch.cuda.synchronize()
         for k in k24:
             acc[k] += ctx.kernel_ms(k)
-    sec_dense = timed(step_dense, args.warmup, args.steps)
-    for _ in range(args.steps):
+    sec_dense = timed(step_dense, args.warmup, args.steps) if not rowwise else float("nan")
+    for _ in range(args.steps if not rowwise else 0):
         step_dense()
         torch.cuda.synchronize()
         for k in kd:
@@ -272,6 +279,10 @@ def main() -> int:
             # reads and writes 2 x 2 bytes per element of its two matrices
             # (the forward's weight pass also writes a panel-form copy of W2 when the context trains: 10 D F bytes then)
             es = 1.0 if fp8 else 2.0
+            if name == "quantise_rows":     # reads the bf16 kept values + metadata, writes codes + metadata (+ one scale per token)
+                gbs = (1.0 + 0.125 + 0.5 + 0.125) * T * F / (ms * 1e-3) / 1e9
+                kernels[name] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / 8000.0, 4)}
+                continue
             if name == "split_partition":
                 kernels[name] = {"ms": round(ms, 4)}
                 continue
@@ -290,7 +301,9 @@ def main() -> int:
         from oracle import ffn24_oracle as O
         Ts = min(args.cpu_tokens, T)
         t0 = time.perf_counter()
-        if fp8:
+        if rowwise:
+            O.ffn24_fwd_fp8_rowwise_codes(inp["X"][:Ts], inp["sx"][:Ts], inp["W1"], inp["sw1"], inp["b1"], inp["W2"], inp["sw2"])
+        elif fp8:
             O.ffn24_fwd_fp8_codes(inp["X"][:Ts], inp["W1"], inp["b1"], inp["W2"], inp["sx"], inp["sw1"], inp["sh"], inp["sw2"])
         else:
             sl = {k: inp[k][:Ts] if k in ("X", "dY") else inp[k] for k in inp}
@@ -307,11 +320,12 @@ def main() -> int:
         "ms_per_step": round(sec24 * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "fp8" if fp8 else "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: 2:4 Squared-ReLU FFN {'fwd+bwd' if bwd else 'fwd'}, T={T} d_model={D} d_ff={F}, target sparsity {w.sparsity}"
-                               + (f", {args.split} dense features in the weight gradients" if args.split and bwd else ""),
+                               + (f", {args.split} dense features in the weight gradients" if args.split and bwd else "")
+                               + (", row-wise fp8 scales" if rowwise else ""),
                    "T": T, "d_model": D, "d_ff": F, "parallelism": "single GPU"},
         "frac_of_sparse_mfma_peak": round(value / (2 * peak), 4),
-        "dense_ffn": {"ms_per_step": round(sec_dense * 1e3, 4), "tflops": round(flops_step / sec_dense / 1e12, 2)},
-        "speedup_vs_dense_ffn": round(sec_dense / sec24, 4),
+        "dense_ffn": None if rowwise else {"ms_per_step": round(sec_dense * 1e3, 4), "tflops": round(flops_step / sec_dense / 1e12, 2)},
+        "speedup_vs_dense_ffn": None if rowwise else round(sec_dense / sec24, 4),
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "sparsify24_standalone": sparsify,
     }
     ctx.close()

@@ -54,6 +54,7 @@ typedef enum { FFN24_BF16 = 0, FFN24_FP8_E4M3 = 1 } ffn24_dtype;
 #define FFN24_DENSE 2        /* allocate what the dense baseline ffn_fwd / ffn_bwd needs (H, dZ as [T][F]) */
 #define FFN24_DEBUG_DUMP_H 4 /* ffn24_fwd also stores the rounded activation before pruning, [T][F] */
 #define FFN24_SPLIT 8        /* allocate what the split weight-gradient GEMMs need (with FFN24_TRAINING; see ffn24_set_split) */
+#define FFN24_ROWWISE 16     /* fp8 context with row-wise instead of per-tensor scales (see ffn24_set_row_scales) */
 
 typedef struct ffn24_ctx ffn24_ctx; /* opaque; owns only its device workspace */
 
@@ -73,6 +74,17 @@ FFN24_API int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F,
  * row-wise ones).  Saved tensors 0 and 1 are then bytes: Hc8 [T][F/2], meta [T][F/8]; tensor 7 is H8 [T][F].
  * An fp8 context supports ffn24_fwd and ffn_fwd only (no FFN24_TRAINING: FFN24_ERR_DTYPE). */
 FFN24_API int ffn24_set_scales(ffn24_ctx* ctx, float sx, float sw1, float sh, float sw2);
+
+/* Row-wise scaling of an fp8 context created with FFN24_ROWWISE (paper Sec. 2: "FP8 rowwise scaling"): the activation
+ * operand of each GEMM has one scale per token, the weight operand one per output channel.  The caller hands in
+ * X8[t][k] = e4m3(X[t][k] / sx[t]), W1_8[k][f] = e4m3(W1[k][f] / sw1[f]), W2_8[f][d] = e4m3(W2[f][d] / sw2[d]) and the
+ * three scale vectors sx [T], sw1 [F], sw2 [D] (fp32, device memory, 16-byte aligned, kept alive by the caller).
+ * ffn24_fwd then computes  Z = sx[t] sw1[f] (X8 W1_8) + b1;  H = bf16(max(0, Z)^2);  keep-2-of-4 on the bf16 words;
+ * sh[t] = (largest activation of token t) / 448, 1 for an all-zero row;  Hc8 = e4m3(kept / sh[t]);
+ * Y = bf16(sh[t] sw2[d] (Hc8 . W2_8)).  Three kernels as in the paper: the up-projection (with activation and
+ * sparsification fused in), a quantisation kernel (the row scale needs the whole row), the 2:4 GEMM.
+ * Saved tensor 11 is sh [T] fp32.  ffn_fwd is not available in this mode (FFN24_ERR_STATE). */
+FFN24_API int ffn24_set_row_scales(ffn24_ctx* ctx, const float* sx, const float* sw1, const float* sw2);
 
 /* Split of the weight-gradient GEMMs (paper Sec. 2, "Optimization 1"): some hidden features are too dense to be
  * 2:4-sparsified along tokens, so the n_dense least sparse features are kept out of the feature-wise pruning.
@@ -137,6 +149,7 @@ FFN24_API int ffn_bwd(ffn24_ctx* ctx, const void* dY, void* dX, void* dW1, void*
  *   0 Hc [T][F/2]   1 meta [T][F/8]   2 dZc [T][F/2]   3 Hc_t [F][T/2]   4 meta_t [F][T/8]   5 dZc_t [F][T/2]
  *   6 pre-prune H dump [T][F] (FFN24_DEBUG_DUMP_H)   7 dense H [T][F]   8 dense dZ [T][F]
  *   9 per-feature non-zero counts [F] uint32, 10 feature of each split-operand row [F] int32 (FFN24_SPLIT)
+ *   11 per-token activation scale sh [T] fp32 (FFN24_ROWWISE)
  * ffn24_saved_bytes gives the size of tensor `which`; ffn24_copy_saved enqueues a copy of it into dst (device memory
  * of exactly that size, 16-byte aligned) in the row-major compressed form described at the top -- inside the context
  * the compressed tensors are kept in a tiled order that the sparse GEMM streams faster.  Returns FFN24_ERR_STATE if
@@ -151,7 +164,8 @@ FFN24_API int ffn24_copy_saved(ffn24_ctx* ctx, int which, void* dst, int64_t dst
  * re-compression, 5 sparse dW2, 6 sparse dW1, 7..12 the six dense-baseline GEMMs in the same order
  * (up, down, dH, dX, dW2, dW1), 13 the two weight transposes of a forward (W1, W2 -> K-contiguous), 14 the two
  * activation transposes of a backward (dY, X), 15 the feature partition of the split, 16 the transpose that brings
- * dW1 into [D][F] after a split (with a split, 5 and 6 are the combined sparse + dense launches of dW2 and dW1).  Returns FFN24_ERR_STATE if that kernel has not run with profiling on. */
+ * dW1 into [D][F] after a split (with a split, 5 and 6 are the combined sparse + dense launches of dW2 and dW1),
+ * 17 the row-wise fp8 quantisation kernel.  Returns FFN24_ERR_STATE if that kernel has not run with profiling on. */
 FFN24_API int ffn24_set_profiling(ffn24_ctx* ctx, int on);
 FFN24_API int ffn24_kernel_ms(ffn24_ctx* ctx, int kernel, float* ms);
 

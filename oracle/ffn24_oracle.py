@@ -462,6 +462,39 @@ def ffn24_fwd_fp8(X, W1, b1, W2, sx, sw1, sh, sw2):
     return ffn24_fwd_fp8_codes(X8, W1_8, b1, W2_8, sx, sw1, sh, sw2)
 
 
+def ffn24_fwd_fp8_rowwise_codes(X8, sx, W1_8, sw1, b1, W2_8, sw2):
+    """fp8 forward with row-wise scaling (the paper's precision recipe, Sec. 2: "FP8 rowwise scaling"): the
+    activation operand of each GEMM carries one scale per token row, the weight operand one per output channel.
+      X8 [T,D] codes, sx [T];  W1_8 [D,F] codes, sw1 [F];  W2_8 [F,D] codes, sw2 [D]
+      Z[t,f] = sx[t] sw1[f] (X8 W1_8)[t,f] + b1[f];  H = bf16(max(0,Z)^2);  2:4 pick on the bf16 words;
+      sh[t] = max_f H24[t,f] / 448 (1 if the row is all zero), computed in float32;  Hc8 = e4m3(Hc / sh[t]);
+      Y[t,d] = sh[t] sw2[d] (Hc8 . W2_8)[t,d]."""
+    Xq = E4M3_VALUES[np.ascontiguousarray(X8, dtype=np.uint8)]
+    W1q = E4M3_VALUES[np.ascontiguousarray(W1_8, dtype=np.uint8)]
+    sx = np.asarray(sx, dtype=np.float32); sw1 = np.asarray(sw1, dtype=np.float32); sw2 = np.asarray(sw2, dtype=np.float32)
+    Z = (Xq @ W1q) * sx.astype(np.float64)[:, None] * sw1.astype(np.float64)[None, :]
+    if b1 is not None:
+        Z = Z + np.asarray(b1, dtype=np.float64)[None, :]
+    R, H = _relu2(Z, Bf16)
+    Hq = round_bf16(H)
+    Hc_w, meta = sparsify24(f32_to_bf16_bits(Hq))
+    Hc = bf16_bits_to_f32(Hc_w)
+    rowmax = Hc.max(axis=1).astype(np.float32)                      # the largest entry of a group is always kept
+    sh = np.where(rowmax > 0, rowmax / np.float32(448.0), np.float32(1.0)).astype(np.float32)
+    Hc8_bits = f32_to_e4m3_bits(Hc / sh[:, None])
+    W2q = E4M3_VALUES[np.ascontiguousarray(W2_8, dtype=np.uint8)]
+    Y = (decompress24(E4M3_VALUES[Hc8_bits], meta) @ W2q) * sh.astype(np.float64)[:, None] * sw2.astype(np.float64)[None, :]
+    return {"Z": Z, "Hq": Hq, "meta": meta, "Hc_words": Hc_w, "rowmax": rowmax, "sh": sh, "Hc8_bits": Hc8_bits, "Y": Y}
+
+
+def quantise_rows_e4m3(x):
+    """Row-wise e4m3 quantisation of a float matrix: s[r] = max|x[r,:]| / 448 (1 for an all-zero row), codes of x / s."""
+    x = np.asarray(x, dtype=np.float32)
+    amax = np.abs(x).max(axis=1).astype(np.float32)
+    s = np.where(amax > 0, amax / np.float32(448.0), np.float32(1.0)).astype(np.float32)
+    return f32_to_e4m3_bits(x / s[:, None]), s
+
+
 def ffn_fwd_fp8(X, W1, b1, W2, sx, sw1, sh, sw2):
     """Dense counterpart of ffn24_fwd_fp8 (no pruning): every activation is quantised, H8 = e4m3(bf16(H) / sh)."""
     Xq = round_e4m3(np.asarray(X, np.float32) / np.float32(sx)).astype(np.float64)

@@ -7,8 +7,8 @@
 using namespace ffn24;
 
 namespace {
-constexpr int NUM_KERNELS = 17;
-enum { K_UP = 0, K_DOWN, K_DH, K_DX, K_FW, K_DW2, K_DW1, KD_UP, KD_DOWN, KD_DH, KD_DX, KD_DW2, KD_DW1, K_TR_W, K_TR_ACT, K_PART, K_TR_DW1 };
+constexpr int NUM_KERNELS = 18;
+enum { K_UP = 0, K_DOWN, K_DH, K_DX, K_FW, K_DW2, K_DW1, KD_UP, KD_DOWN, KD_DH, KD_DX, KD_DW2, KD_DW1, K_TR_W, K_TR_ACT, K_PART, K_TR_DW1, K_QUANT };
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 }  // namespace
@@ -19,6 +19,9 @@ struct ffn24_ctx {
   int device;
   int f8;                      // element type FFN24_FP8_E4M3 (forward only)
   float sx, sw1, sh, sw2;      // per-tensor scales of the fp8 path
+  // row-wise-scaled fp8 forward (FFN24_ROWWISE): caller's scale vectors, and the library's intermediate tensors
+  const float *rsx, *rsw1, *rsw2;
+  void* Hc16; uint8_t* meta16; uint32_t* rowmax; float* rsh;
   // workspace (device)
   void* Hc; uint8_t* meta; void* dZc; void* Hc_t; uint8_t* meta_t; void* dZc_t; void* Hdbg; void* Hd; void* dZd;
   void* W1t; void* W2t; void* Xt; void* dYt; void* Hd_t; void* dZd_t;   // K-contiguous copies of GEMM operands
@@ -52,7 +55,7 @@ int free_all(ffn24_ctx* c) {
   int bad = 0;
   void* bufs[] = {c->Hc, c->meta, c->dZc, c->Hc_t, c->meta_t, c->dZc_t, c->Hdbg, c->Hd, c->dZd,
                   c->W1t, c->W2t, c->Xt, c->dYt, c->Hd_t, c->dZd_t, c->W2p,
-                  c->nnz, c->row_of_feat, c->feat_of_row, c->Hdn_t, c->dZdn_t, c->dW1t};
+                  c->nnz, c->row_of_feat, c->feat_of_row, c->Hdn_t, c->dZdn_t, c->dW1t, c->Hc16, c->meta16, c->rowmax, c->rsh};
   for (void* b : bufs) if (b && hipFree(b) != hipSuccess) bad = 1;
   for (int k = 0; k < NUM_KERNELS; k++) for (int j = 0; j < 2; j++) if (c->ev[k][j]) (void)hipEventDestroy(c->ev[k][j]);
   return bad;
@@ -87,6 +90,7 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
   const bool f8 = dtype == FFN24_FP8_E4M3;
   if (f8 && (flags & FFN24_TRAINING)) return FFN24_ERR_DTYPE;   // the fp8 path is forward only
   if ((flags & FFN24_SPLIT) && !(flags & FFN24_TRAINING)) return FFN24_ERR_STATE;
+  if ((flags & FFN24_ROWWISE) && !f8) return FFN24_ERR_DTYPE;
   if (T <= 0 || D <= 0 || F <= 0 || T % 256 || D % 256 || F % 256) return FFN24_ERR_SHAPE;
   if (T > (1 << 20) || D > (1 << 20) || F > (1 << 20)) return FFN24_ERR_SHAPE;
   ffn24_ctx* c = new (std::nothrow) ffn24_ctx();
@@ -108,6 +112,9 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
          hipMalloc(reinterpret_cast<void**>(&c->feat_of_row), 4 * (size_t)F) == hipSuccess &&
          hipMalloc(&c->Hdn_t, tf / 2) == hipSuccess && hipMalloc(&c->dZdn_t, tf / 2) == hipSuccess &&   // up to F/4 dense rows
          hipMalloc(&c->dW1t, 2 * df) == hipSuccess;
+  if (ok && (flags & FFN24_ROWWISE))
+    ok = hipMalloc(&c->Hc16, tf) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->meta16), tf / 8) == hipSuccess &&
+         hipMalloc(reinterpret_cast<void**>(&c->rowmax), 4 * (size_t)T) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->rsh), 4 * (size_t)T) == hipSuccess;
   if (ok && (flags & FFN24_DENSE)) ok = hipMalloc(&c->Hd, es * tf) == hipSuccess;
   if (ok && (flags & FFN24_DENSE) && (flags & FFN24_TRAINING))
     ok = hipMalloc(&c->dZd, 2 * tf) == hipSuccess && hipMalloc(&c->Hd_t, 2 * tf) == hipSuccess && hipMalloc(&c->dZd_t, 2 * tf) == hipSuccess;
@@ -131,6 +138,15 @@ int ffn24_set_scales(ffn24_ctx* c, float sx, float sw1, float sh, float sw2) {
   if (!c->f8) return FFN24_ERR_DTYPE;
   if (!(sx > 0.f) || !(sw1 > 0.f) || !(sh > 0.f) || !(sw2 > 0.f)) return FFN24_ERR_SHAPE;
   c->sx = sx; c->sw1 = sw1; c->sh = sh; c->sw2 = sw2;
+  return FFN24_OK;
+}
+
+int ffn24_set_row_scales(ffn24_ctx* c, const float* sx, const float* sw1, const float* sw2) {
+  if (!c) return FFN24_ERR_NULL;
+  if (!(c->flags & FFN24_ROWWISE)) return FFN24_ERR_STATE;
+  if (!sx || !sw1 || !sw2) return FFN24_ERR_NULL;
+  if (misaligned(sx) || misaligned(sw1) || misaligned(sw2)) return FFN24_ERR_ALIGN;
+  c->rsx = sx; c->rsw1 = sw1; c->rsw2 = sw2;
   return FFN24_OK;
 }
 
@@ -168,6 +184,7 @@ int ffn24_saved_bytes(ffn24_ctx* c, int which, int64_t* nbytes) {
     case 6: *nbytes = 2 * tf; break;
     case 7: case 8: *nbytes = es * tf; break;
     case 9: case 10: *nbytes = 4 * c->F; break;
+    case 11: *nbytes = 4 * c->T; break;
     default: return FFN24_ERR_SHAPE;
   }
   return FFN24_OK;
@@ -195,7 +212,8 @@ int ffn24_copy_saved(ffn24_ctx* c, int which, void* dst, int64_t dst_bytes, void
     case 7: src = c->Hd; break;
     case 8: src = c->dZd; break;
     case 9: src = c->nnz; break;
-    default: src = c->feat_of_row; break;
+    case 10: src = c->feat_of_row; break;
+    default: src = c->rsh; break;
   }
   if (!src) return FFN24_ERR_STATE;
   if (which >= 9) return hipMemcpyAsync(dst, src, (size_t)need, hipMemcpyDeviceToDevice, s) == hipSuccess ? FFN24_OK : FFN24_ERR_HIP;
@@ -245,6 +263,21 @@ int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, cons
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   c->have_fwd24 = 0;
+  if (c->f8 && (c->flags & FFN24_ROWWISE)) {
+    // row-wise scaling: up-projection (bf16 kept values + row maxima), row-wise quantisation, scaled sparse GEMM
+    if (!c->rsx) return FFN24_ERR_STATE;
+    { Timed t(c, K_TR_W, s);
+      int rc1 = launch_transpose8(W1, D, F, c->W1t, 1, s);
+      if (t.done(rc1 ? rc1 : launch_transpose8(W2, F, D, c->W2t, 0, s))) return FFN24_ERR_HIP; }
+    if (hipMemsetAsync(c->rowmax, 0, 4 * (size_t)T, s) != hipSuccess) return FFN24_ERR_HIP;
+    { Timed t(c, K_UP, s);
+      if (t.done(launch_up_prune24_f8_rowwise(c->W1t, X, b1, T, D, F, c->rsx, c->rsw1, c->Hc16, c->meta16, c->Hdbg, c->rowmax, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_QUANT, s);
+      if (t.done(launch_quantise_rows(c->Hc16, c->meta16, c->rowmax, T, F, c->Hc, c->meta, c->rsh, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_DOWN, s);
+      if (t.done(launch_sp_rowmajor_f8_rowwise(c->Hc, c->meta, c->W2t, T, D, F, c->rsh, c->rsw2, Y, s))) return FFN24_ERR_HIP; }
+    return FFN24_OK;
+  }
   if (c->f8) {
     { Timed t(c, K_TR_W, s);
       int rc1 = launch_transpose8(W1, D, F, c->W1t, 1, s);
@@ -303,7 +336,7 @@ int ffn24_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void
 
 int ffn_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const void* W2, void* Y, void* stream) {
   if (!c) return FFN24_ERR_NULL;
-  if (!(c->flags & FFN24_DENSE)) return FFN24_ERR_STATE;
+  if (!(c->flags & FFN24_DENSE) || (c->flags & FFN24_ROWWISE)) return FFN24_ERR_STATE;
   int rc = check_ptrs({X, W1, W2, Y});
   if (rc) return rc;
   if (b1 && misaligned(b1)) return FFN24_ERR_ALIGN;

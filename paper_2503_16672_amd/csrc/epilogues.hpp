@@ -329,6 +329,83 @@ struct EpiPrune24F8 {
   }
 };
 
+// fp8 up-projection with ROW-WISE scaling (the paper's precision recipe, Sec. 2: "FP8 rowwise scaling"): the
+// activation operand carries one scale per token, the weight one per output channel:
+//   z = sx[t] sw1[f] acc + b1[f];  h = bf16(max(0, z)^2);  keep-2-of-4 as in EpiPrune24.
+// The kept values cannot be quantised here -- their scale is the maximum of the whole token row, which spans many
+// block tiles -- so they are written as bf16 in the bf16 panel form (Hc, meta), and every lane raises rowmax[t] (bf16
+// word of the largest activation, non-negative, so integer order = value order) with one atomic per token.
+// A streaming kernel then quantises with sh[t] = rowmax[t] / 448 (k_stream.hip).
+struct EpiPrune24Rw {
+  struct Args { __bf16* Hc; uint8_t* meta; __bf16* Hdbg; const float* b1; int F; const float* sx; const float* sw1; uint32_t* rowmax; };
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+#pragma unroll
+    for (int ni = 0; ni < 4; ni++) {
+      size_t t = (size_t)(n_lane + ni);
+      const float sxt = e.sx[t];
+      uint32_t vals[16];
+      uint32_t nib[2] = {0u, 0u};
+      uint32_t mx = 0u;
+#pragma unroll
+      for (int mi = 0; mi < 4; mi++) {
+        uint32_t hpk[8];
+#pragma unroll
+        for (int d = 0; d < 8; d++) {
+          int f = m_lane + 16 * mi + 2 * d;
+          float b0 = e.b1 ? e.b1[f] : 0.f;
+          float b1v = e.b1 ? e.b1[f + 1] : 0.f;
+          float r0 = fmaxf(acc[mi][ni][2 * d] * (sxt * e.sw1[f]) + b0, 0.f);
+          float r1 = fmaxf(acc[mi][ni][2 * d + 1] * (sxt * e.sw1[f + 1]) + b1v, 0.f);
+          hpk[d] = pack_bf16x2(r0 * r0, r1 * r1);
+          mx = max(mx, max(hpk[d] & 0xFFFFu, hpk[d] >> 16));
+        }
+        if (e.Hdbg) {
+          __bf16* row = e.Hdbg + t * e.F + m_lane + 16 * mi;
+          *reinterpret_cast<u32x4*>(row) = u32x4{hpk[0], hpk[1], hpk[2], hpk[3]};
+          *reinterpret_cast<u32x4*>(row + 8) = u32x4{hpk[4], hpk[5], hpk[6], hpk[7]};
+        }
+#pragma unroll
+        for (int a = 0; a < 4; a++) {
+          uint32_t k0 = ((hpk[2 * a] & 0xFFFFu) << 2) | 3u;
+          uint32_t k1 = ((hpk[2 * a] >> 16) << 2) | 2u;
+          uint32_t k2 = ((hpk[2 * a + 1] & 0xFFFFu) << 2) | 1u;
+          uint32_t k3 = ((hpk[2 * a + 1] >> 16) << 2);
+          uint32_t kf, ks;
+          uint32_t n4 = pick24_keys(k0, k1, k2, k3, kf, ks);
+          int gi = 4 * mi + a;
+          vals[gi] = (kf >> 2) | ((ks >> 2) << 16);
+          nib[gi >> 3] |= n4 << (4 * (gi & 7));
+        }
+      }
+      size_t piece = a24_piece((int)t, m_lane >> 6, e.F >> 6);
+      __bf16* hrow = e.Hc + piece * 32;
+#pragma unroll
+      for (int q = 0; q < 4; q++)
+        *reinterpret_cast<u32x4*>(hrow + 8 * q) = u32x4{vals[4 * q], vals[4 * q + 1], vals[4 * q + 2], vals[4 * q + 3]};
+      *reinterpret_cast<u32x2*>(e.meta + piece * 8) = u32x2{nib[0], nib[1]};
+      if (mx) atomicMax(e.rowmax + t, mx);
+    }
+  }
+};
+
+// C[m][n] = bf16(acc * rs[m] * cs[n]), n contiguous (row-wise-scaled fp8 down-projection: rs = sh per token, cs = sw2).
+struct EpiRowMajorRowCol {
+  struct Args { __bf16* C; int ldc; const float* rs; const float* cs; };
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+    const f32x4 cs = *reinterpret_cast<const f32x4*>(e.cs + n_lane);
+#pragma unroll
+    for (int mi = 0; mi < 4; mi++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        const float r = e.rs[m_lane + 16 * mi + v];
+        u32x2 o;
+        o[0] = pack_bf16x2(acc[mi][0][v] * r * cs[0], acc[mi][1][v] * r * cs[1]);
+        o[1] = pack_bf16x2(acc[mi][2][v] * r * cs[2], acc[mi][3][v] * r * cs[3]);
+        *reinterpret_cast<u32x2*>(e.C + (size_t)(m_lane + 16 * mi + v) * e.ldc + n_lane) = o;
+      }
+  }
+};
+
 // fp8 dense up-projection (baseline): H8[t][f] = e4m3( bf16(max(0, zscale acc + b1)^2) / sh ), the [T][F] byte operand
 // of the dense down-projection, in dense panel form (64-byte pieces of 64 k).
 struct EpiRelu2F8 {

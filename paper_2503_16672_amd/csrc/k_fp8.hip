@@ -29,4 +29,19 @@ int launch_dense_rowmajor_f8(const void* A8, int a_panel, const void* B8, int M,
   return launch_gemm<false, EpiRowMajorScaled, true>(g, ea, s);
 }
 
+// row-wise-scaled variants (scales per token for the activation operand, per output channel for the weight)
+int launch_up_prune24_f8_rowwise(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, const float* sx, const float* sw1,
+                                 void* Hc16, uint8_t* meta16, void* Hdbg, uint32_t* rowmax, hipStream_t s) {
+  GemmArgs g{W1t8, nullptr, X8, F, T, D, 1};
+  EpiPrune24Rw::Args ea{static_cast<__bf16*>(Hc16), meta16, static_cast<__bf16*>(Hdbg), b1, F, sx, sw1, rowmax};
+  return launch_gemm<false, EpiPrune24Rw, true>(g, ea, s);
+}
+
+int launch_sp_rowmajor_f8_rowwise(const void* vals8, const uint8_t* meta, const void* B8, int M, int N, int K, const float* rs, const float* cs,
+                                  void* C, hipStream_t s) {
+  GemmArgs g{vals8, meta, B8, M, N, K, 1};
+  EpiRowMajorRowCol::Args ea{static_cast<__bf16*>(C), N, rs, cs};
+  return launch_gemm<true, EpiRowMajorRowCol, true>(g, ea, s);
+}
+
 }  // namespace ffn24

@@ -1,7 +1,7 @@
 // Streaming (HBM-bound) kernels: the standalone 2:4 compression of an activation matrix, the feature-wise
 // (along-token) re-compression the weight-gradient GEMMs need, and the bf16 matrix transpose that brings a GEMM
 // operand into K-contiguous form.
-#include "gemm_core.hpp"
+#include "epilogues.hpp"
 #include "launch.hpp"
 
 namespace ffn24 {
@@ -374,6 +374,59 @@ int launch_transpose8(const void* in, int R, int C, void* out, int out_panel, hi
   dim3 grid(C / 64, R / 64);
   auto kern = out_panel ? transpose8_kernel<true> : transpose8_kernel<false>;
   hipLaunchKernelGGL(kern, grid, dim3(256), 0, s, static_cast<const uint8_t*>(in), R, C, static_cast<uint8_t*>(out));
+  return (int)hipGetLastError();
+}
+
+// Row-wise fp8 quantisation of the compressed activation (Sec. 2: "a new kernel that applies the activation, the
+// sparsification, and FP8 quantization" -- here only the last step is left to a kernel of its own, because the scale of
+// a token row, sh[t] = (largest activation of the row) / 448, is known only once the whole row exists).
+// Input: bf16 kept values + metadata in the bf16 panel form (64-byte / 8-byte pieces per 64 features);
+// output: e4m3 codes + metadata in the fp8 panel form (64-byte / 16-byte pieces per 128 features), and sh [T].
+// One work item per (token, 128 features): two input pieces -> one output piece.
+__global__ void __launch_bounds__(256) quantise_rows_kernel(const u32x4* __restrict__ Hc16, const u32x2* __restrict__ meta16,
+                                                            const uint32_t* __restrict__ rowmax, int T, int F,
+                                                            u32x4* __restrict__ Hc8, u32x4* __restrict__ meta8, float* __restrict__ sh) {
+  const int np8 = F >> 7;                                 // output pieces per token
+  size_t n = (size_t)T * np8;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+    // item order = output piece order: ((t / 256) * np8 + j) * 256 + t % 256
+    int tl = (int)(i & 255);
+    size_t blk = i >> 8;
+    int j = (int)(blk % np8), t = (int)(blk / np8) * 256 + tl;
+    float mxv = __builtin_bit_cast(float, rowmax[t] << 16);
+    float s = mxv > 0.f ? mxv / 448.f : 1.f;
+    if (j == 0) sh[t] = s;
+    u32x4 out[4];
+    u32x2 mo[2];
+#pragma unroll
+    for (int hlf = 0; hlf < 2; hlf++) {
+      size_t pin = a24_piece(t, 2 * j + hlf, F >> 6);
+      mo[hlf] = meta16[pin];
+#pragma unroll
+      for (int c = 0; c < 4; c++) {
+        u32x4 v = Hc16[pin * 4 + c];                      // 8 bf16 values -> 8 codes = 2 dwords
+        uint32_t q0 = cvt_e4m3x2(bf16_lo_to_f32(v[0]) / s, bf16_hi_to_f32(v[0]) / s, 0u, false);
+        q0 = cvt_e4m3x2(bf16_lo_to_f32(v[1]) / s, bf16_hi_to_f32(v[1]) / s, q0, true);
+        uint32_t q1 = cvt_e4m3x2(bf16_lo_to_f32(v[2]) / s, bf16_hi_to_f32(v[2]) / s, 0u, false);
+        q1 = cvt_e4m3x2(bf16_lo_to_f32(v[3]) / s, bf16_hi_to_f32(v[3]) / s, q1, true);
+        out[2 * hlf + (c >> 1)][2 * (c & 1)] = q0;
+        out[2 * hlf + (c >> 1)][2 * (c & 1) + 1] = q1;
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < 4; c++) Hc8[i * 4 + c] = out[c];
+    meta8[i] = u32x4{mo[0][0], mo[0][1], mo[1][0], mo[1][1]};
+  }
+}
+
+int launch_quantise_rows(const void* Hc16, const uint8_t* meta16, const uint32_t* rowmax, int T, int F, void* Hc8, uint8_t* meta8, float* sh,
+                         hipStream_t s) {
+  size_t n = (size_t)T * (F >> 7);
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 256 * 64) blocks = 256 * 64;
+  hipLaunchKernelGGL(quantise_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const u32x4*>(Hc16),
+                     reinterpret_cast<const u32x2*>(meta16), rowmax, T, F, static_cast<u32x4*>(Hc8), reinterpret_cast<u32x4*>(meta8), sh);
   return (int)hipGetLastError();
 }
 

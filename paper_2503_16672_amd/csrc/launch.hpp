@@ -42,6 +42,14 @@ int launch_up_prune24_f8(const void* W1t8, const void* X8, const float* b1, int 
 int launch_up_relu2_f8(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, float zscale, float sh, void* H8, hipStream_t s);
 int launch_sp_rowmajor_f8(const void* vals8, const uint8_t* meta, int a_panel, const void* B8, int M, int N, int K, float scale, void* C, hipStream_t s);
 int launch_dense_rowmajor_f8(const void* A8, int a_panel, const void* B8, int M, int N, int K, float scale, void* C, hipStream_t s);
+// row-wise-scaled fp8 forward: sx [T], sw1 [F], sw2 [N]; the up-projection writes bf16 kept values (bf16 panel form)
+// and raises rowmax [T] (bf16 words; zeroed by the caller); quantise_rows turns them into the fp8 panel form with
+// sh[t] = rowmax[t] / 448 (1 for an all-zero row), which it also writes out
+int launch_up_prune24_f8_rowwise(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, const float* sx, const float* sw1,
+                                 void* Hc16, uint8_t* meta16, void* Hdbg, uint32_t* rowmax, hipStream_t s);
+int launch_quantise_rows(const void* Hc16, const uint8_t* meta16, const uint32_t* rowmax, int T, int F, void* Hc8, uint8_t* meta8, float* sh, hipStream_t s);
+int launch_sp_rowmajor_f8_rowwise(const void* vals8, const uint8_t* meta, const void* B8, int M, int N, int K, const float* rs, const float* cs,
+                                  void* C, hipStream_t s);
 // streaming kernels
 int launch_sparsify24(const void* H, int64_t rows, int64_t cols, void* vals, uint8_t* meta, hipStream_t s);
 // panel: inputs and outputs are in panel form (the library's own buffers) instead of row-major

@@ -20,15 +20,16 @@ FFN24_TRAINING = 1
 FFN24_DENSE = 2
 FFN24_DEBUG_DUMP_H = 4
 FFN24_SPLIT = 8
+FFN24_ROWWISE = 16
 
 EXPORTS = (
-    "ffn24_ctx_create", "ffn24_ctx_destroy", "ffn24_set_scales", "ffn24_set_split", "sparsify24", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd",
+    "ffn24_ctx_create", "ffn24_ctx_destroy", "ffn24_set_scales", "ffn24_set_row_scales", "ffn24_set_split", "sparsify24", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd",
     "ffn_fwd", "ffn_bwd", "ffn24_saved_bytes", "ffn24_copy_saved", "ffn24_set_profiling", "ffn24_kernel_ms", "ffn24_strerror",
 )
 
 KERNEL_NAMES = ("up_prune24", "down_sp", "dh_gather", "dx_sp", "featurewise24", "dw2_sp", "dw1_sp",
                 "dense_up", "dense_down", "dense_dh", "dense_dx", "dense_dw2", "dense_dw1", "transpose_weights", "transpose_acts",
-                "split_partition", "transpose_dw1")
+                "split_partition", "transpose_dw1", "quantise_rows")
 
 _lib = None
 
@@ -51,6 +52,7 @@ def lib() -> ctypes.CDLL:
         L.ffn24_ctx_destroy.argtypes = [vp]
         L.ffn24_set_scales.argtypes = [vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_float]
         L.ffn24_set_split.argtypes = [vp, i64]
+        L.ffn24_set_row_scales.argtypes = [vp, vp, vp, vp]
         L.sparsify24.argtypes = [vp, i64, i64, ci, vp, vp, vp]
         L.sparsify24_featurewise.argtypes = [vp, vp, vp, i64, i64, vp, vp, vp, vp]
         L.spmm24.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp]
@@ -146,6 +148,11 @@ class Context:
         """Per-tensor scales of an fp8 context (see ffn24_set_scales in the header)."""
         _check(lib().ffn24_set_scales(self._h, sx, sw1, sh, sw2), "ffn24_set_scales")
 
+    def set_row_scales(self, sx, sw1, sw2):
+        """Row-wise scales of an FFN24_ROWWISE fp8 context: fp32 CUDA tensors [T], [F], [D]; the context keeps them alive."""
+        self._row_scales = (sx, sw1, sw2)
+        _check(lib().ffn24_set_row_scales(self._h, _ptr(sx), _ptr(sw1), _ptr(sw2)), "ffn24_set_row_scales")
+
     def set_split(self, n_dense: int):
         """Keep the n_dense least sparse features out of the feature-wise 2:4 (see ffn24_set_split in the header)."""
         _check(lib().ffn24_set_split(self._h, n_dense), "ffn24_set_split")
@@ -181,7 +188,8 @@ class Context:
               "meta_t": (4, torch.uint8, lambda T, F: (F, T // 8)), "dZc_t": (5, torch.bfloat16, lambda T, F: (F, T // 2)),
               "H_dump": (6, torch.bfloat16, lambda T, F: (T, F)), "H_dense": (7, torch.bfloat16, lambda T, F: (T, F)),
               "dZ_dense": (8, torch.bfloat16, lambda T, F: (T, F)),
-              "nnz": (9, torch.int32, lambda T, F: (F,)), "feat_of_row": (10, torch.int32, lambda T, F: (F,))}
+              "nnz": (9, torch.int32, lambda T, F: (F,)), "feat_of_row": (10, torch.int32, lambda T, F: (F,)),
+              "sh": (11, torch.float32, lambda T, F: (T,))}
 
     def saved(self, name: str) -> torch.Tensor:
         """Row-major copy of a saved tensor of the context (enqueued on the current stream)."""

@@ -97,3 +97,22 @@ def make_inputs_fp8(T: int, D: int, F: int, sparsity, seed: int, sh: float = 16.
         q = torch.from_numpy(inp[k] / np.float32(s)).to(torch.float8_e4m3fn)
         out[k] = q.view(torch.uint8).numpy()
     return out
+
+
+def make_inputs_fp8_rowwise(T: int, D: int, F: int, sparsity, seed: int) -> dict:
+    """fp8 workload with row-wise scales: X quantised per token row, W1 and W2 per output channel (column), each with
+    s = amax / 448 of its row / column (1 where that is zero), by torch's CPU cast.  Returns codes X [T,D], W1 [D,F],
+    W2 [F,D] (uint8), scales sx [T], sw1 [F], sw2 [D] (float32) and b1."""
+    import torch
+    inp = make_inputs(T, D, F, sparsity, seed)
+
+    def quant(x, axis):
+        amax = np.abs(x).max(axis=axis, keepdims=True).astype(np.float32)
+        s = np.where(amax > 0, amax / np.float32(448.0), np.float32(1.0)).astype(np.float32)
+        q = torch.from_numpy(np.ascontiguousarray(x / s)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+        return q, s.reshape(-1)
+    out = {"b1": inp["b1"]}
+    out["X"], out["sx"] = quant(inp["X"], 1)
+    out["W1"], out["sw1"] = quant(inp["W1"], 0)
+    out["W2"], out["sw2"] = quant(inp["W2"], 0)
+    return out

@@ -728,3 +728,69 @@ def test_ffn24_split_full_size_sampled(F24):
     # take the sample after the fact from both parts -- here simply many features, the check requires both kinds
     sample = np.sort(rng.choice(w.F, 400, replace=False))
     _check_split(F24, w.T, w.D, w.F, "per_feature", w.seed, 1024, sample=sample)
+
+
+# ----------------------------------------------------------------------------- fp8 forward with row-wise scaling
+def _check_fp8_rowwise(F24, T, D, Fh, sparsity, seed, rows=None):
+    inp = synth.make_inputs_fp8_rowwise(T, D, Fh, sparsity, seed)
+    d = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2", "sx", "sw1", "sw2")}
+    b1 = torch.from_numpy(inp["b1"]).cuda()
+    ctx = F24.Context(T, D, Fh, F24.FFN24_DEBUG_DUMP_H | F24.FFN24_ROWWISE, dtype=F24.FFN24_FP8_E4M3)
+    ctx.set_row_scales(d["sx"], d["sw1"], d["sw2"])
+    Y = ctx.ffn24_fwd(d["X"], d["W1"], b1, d["W2"])
+    torch.cuda.synchronize()
+    rsel = np.arange(T) if rows is None else rows
+    rs_t = torch.from_numpy(rsel).cuda()
+    Hd = ctx.saved("H_dump")[rs_t]; Hc8 = ctx.saved("Hc")[rs_t].cpu().numpy(); meta = ctx.saved("meta")[rs_t].cpu().numpy()
+    sh = ctx.saved("sh")[rs_t].cpu().numpy()
+    torch.cuda.synchronize()
+    # S1: pick, row scale and codes re-derived by the oracle's steps from the activation the kernel itself rounded
+    v_ref, m_ref = O.sparsify24(words_of(Hd))
+    assert np.array_equal(meta, m_ref)
+    kept = O.bf16_bits_to_f32(v_ref)
+    rowmax = kept.max(axis=1).astype(np.float32)
+    assert np.array_equal(rowmax, f64(Hd).max(axis=1).astype(np.float32))       # the row maximum is always kept
+    sh_ref = np.where(rowmax > 0, rowmax / np.float32(448.0), np.float32(1.0)).astype(np.float32)
+    assert np.array_equal(sh, sh_ref)
+    assert np.array_equal(Hc8, O.f32_to_e4m3_bits(kept / sh_ref[:, None]))
+    assert (Hc8.max(axis=1)[rowmax > 0] == 0x7E).all()                          # every row uses the full code range
+    # S2: down-projection on the GPU's own codes and scales
+    W2q = O.E4M3_VALUES[inp["W2"]]
+    y_staged = O.decompress24(O.E4M3_VALUES[Hc8], meta) @ W2q * sh.astype(np.float64)[:, None] * inp["sw2"].astype(np.float64)[None, :]
+    e2 = O.max_rel_err(f64(Y[rs_t]), y_staged)
+    # S3: from the inputs
+    ref = O.ffn24_fwd_fp8_rowwise_codes(inp["X"][rsel], inp["sx"][rsel], inp["W1"], inp["sw1"], inp["b1"], inp["W2"], inp["sw2"])
+    eh = O.max_rel_err(f64(Hd), ref["Hq"]); e3 = O.max_rel_err(f64(Y[rs_t]), ref["Y"])
+    agree = float(np.mean(meta == ref["meta"]))
+    print(f"  fp8 row-wise: H err {eh:.2e}  Y staged {e2:.2e}  Y end-to-end {e3:.2e}  meta agreement {agree:.5f}", flush=True)
+    assert eh <= TOL_FP8 and e2 <= TOL_FP8 and e3 <= TOL_FP8 and agree >= 0.995
+    with pytest.raises(F24.Ffn24Error):
+        ctx.ffn_fwd(d["X"], d["W1"], b1, d["W2"])
+    ctx.close()
+
+
+def test_ffn24_fwd_fp8_rowwise_small(F24):
+    print("fp8 row-wise fwd T=256 D=512 F=2048", flush=True)
+    _check_fp8_rowwise(F24, 256, 512, 2048, 0.90, seed=71)
+    print("fp8 row-wise fwd T=512 D=768 F=1280", flush=True)
+    _check_fp8_rowwise(F24, 512, 768, 1280, "per_feature", seed=72)
+
+
+@pytest.mark.timeout(900)
+def test_ffn24_fwd_fp8_rowwise_full_size_sampled(F24):
+    w = synth.WORKLOADS["c5"]
+    print(f"fp8 row-wise full size c5 T={w.T} D={w.D} F={w.F}", flush=True)
+    rows = np.sort(np.random.default_rng(49).choice(w.T, 48, replace=False))
+    _check_fp8_rowwise(F24, w.T, w.D, w.F, w.sparsity, w.seed, rows=rows)
+
+
+def test_fp8_rowwise_rules(F24):
+    with pytest.raises(F24.Ffn24Error) as e:
+        F24.Context(256, 256, 256, F24.FFN24_ROWWISE)            # row-wise scaling is an fp8 mode
+    assert e.value.code == -4
+    ctx = F24.Context(256, 256, 256, F24.FFN24_ROWWISE, dtype=F24.FFN24_FP8_E4M3)
+    z8 = torch.zeros((256, 256), dtype=torch.uint8, device="cuda")
+    with pytest.raises(F24.Ffn24Error) as e:                     # forward before the scales are set
+        ctx.ffn24_fwd(z8, z8, None, z8)
+    assert e.value.code == -5
+    ctx.close()

@@ -473,3 +473,31 @@ def test_split_backward_limits():
     assert np.array_equal(g["dX"], g_fw["dX"])
     assert np.array_equal(g["dW2"][dense], g_tw["dW2"][dense]) and np.array_equal(g["dW2"][~dense], g_fw["dW2"][~dense])
     assert np.array_equal(g["dW1"][:, dense], g_tw["dW1"][:, dense]) and np.array_equal(g["dW1"][:, ~dense], g_fw["dW1"][:, ~dense])
+
+
+def test_fp8_rowwise_reduces_to_per_tensor_when_scales_are_uniform():
+    """Row-wise scaling with the same scale in every row / channel, and an activation whose every token row has the same
+    maximum, is the per-tensor forward: same codes, same output."""
+    rng = np.random.default_rng(14)
+    T, D, F = 16, 32, 64
+    X = rng.standard_normal((T, D)).astype(np.float32)
+    W1 = (rng.standard_normal((D, F)) / np.sqrt(D)).astype(np.float32)
+    W2 = (rng.standard_normal((F, D)) / np.sqrt(F)).astype(np.float32)
+    sx, sw1, sw2 = 0.01, 0.002, 0.003
+    X8 = O.f32_to_e4m3_bits(X / np.float32(sx)); W1_8 = O.f32_to_e4m3_bits(W1 / np.float32(sw1)); W2_8 = O.f32_to_e4m3_bits(W2 / np.float32(sw2))
+    rw = O.ffn24_fwd_fp8_rowwise_codes(X8, np.full(T, sx, np.float32), W1_8, np.full(F, sw1, np.float32), None, W2_8, np.full(D, sw2, np.float32))
+    # per-tensor forward run row by row with that row's own activation scale
+    for t in range(T):
+        pt = O.ffn24_fwd_fp8_codes(X8[t:t + 1], W1_8, None, W2_8, sx, sw1, float(rw["sh"][t]), sw2)
+        assert np.array_equal(pt["Hc8_bits"], rw["Hc8_bits"][t:t + 1]) and np.array_equal(pt["meta"], rw["meta"][t:t + 1])
+        np.testing.assert_allclose(pt["Y"], rw["Y"][t:t + 1], rtol=1e-6)   # the scales are float32 on one side only
+    # every row uses the full code range: its largest kept value maps to 448
+    assert (rw["Hc8_bits"].max(axis=1) == 0x7E).all()
+
+
+def test_quantise_rows_e4m3():
+    x = np.array([[1.0, -2.0, 0.5], [0.0, 0.0, 0.0], [448.0, 3.5, -7.0]], np.float32)
+    codes, s = O.quantise_rows_e4m3(x)
+    assert np.allclose(s, [2.0 / 448, 1.0, 1.0])
+    assert codes[0, 1] == 0xFE and codes[1].tolist() == [0, 0, 0] and codes[2, 0] == 0x7E
+    np.testing.assert_allclose(O.e4m3_bits_to_f32(codes) * s[:, None], x, rtol=0.07, atol=1e-6)
