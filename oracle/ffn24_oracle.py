@@ -415,6 +415,28 @@ def ffn24_bwd(fwd: dict, dY, st=Bf16, wgrad_mask="featurewise", dense_features=N
     }
 
 
+def ffn24_fwd_bwd_permuted(X, W1, b1, W2, dY, perm, st=Bf16, wgrad_mask="featurewise", dense_features=None):
+    """Forward + backward with a fixed token permutation around the FFN (Sec. 2, "Optimization 2": permute the tokens
+    before entering the FFN and shuffle them back after).  Position p inside the FFN holds token perm[p]: the FFN runs
+    on X[perm] and dY[perm]; Y and dX are scattered back to token order; the weight gradients are sums over tokens and
+    keep their layout, but their feature-wise 2:4 groups are now made of the tokens the permutation puts side by side."""
+    perm = np.asarray(perm, dtype=np.int64)
+    T = np.asarray(X).shape[0]
+    if sorted(perm.tolist()) != list(range(T)):
+        raise ValueError("perm is not a permutation of the tokens")
+    f = ffn24_fwd(np.asarray(X)[perm], W1, b1, W2, st)
+    g = ffn24_bwd(f, np.asarray(dY)[perm], st, wgrad_mask, dense_features)
+    Y = np.empty_like(f["Y"]); Y[perm] = f["Y"]
+    dX = np.empty_like(g["dX"]); dX[perm] = g["dX"]
+    return {"fwd": f, "bwd": g, "Y": Y, "dX": dX, "dW1": g["dW1"], "dW2": g["dW2"]}
+
+
+def featurewise_drop_fraction(H24, M_T) -> float:
+    """Fraction of the non-zero entries of the token-wise-pruned activation that the feature-wise 2:4 drops."""
+    nz = np.asarray(H24) != 0
+    return float((nz & ~np.asarray(M_T, dtype=bool)).sum() / max(1, nz.sum()))
+
+
 def ffn_bwd(fwd: dict, dY, st=Bf16):
     """Textbook backward of the dense FFN: dZ = (dY W2^T) * 2 max(0, Z); dX = dZ W1^T; dW2 = H^T dY; dW1 = X^T dZ.
     Needs of `fwd` only Hq, Xq, W1q, W2q."""

@@ -52,11 +52,19 @@ def bias_for(F: int, sparsity, rng: np.random.Generator) -> np.ndarray:
     return np.full(F, -ndtri(float(sparsity)), dtype=np.float32)
 
 
-def make_inputs(T: int, D: int, F: int, sparsity, seed: int, with_dy: bool = False) -> dict:
-    """X ~ N(0,1) [T,D]; W1 ~ N(0,1/D) [D,F]; W2 ~ N(0,1/F) [F,D]; b1 [F]; optionally dY ~ N(0,1) [T,D]."""
+def make_inputs(T: int, D: int, F: int, sparsity, seed: int, with_dy: bool = False, token_corr=None) -> dict:
+    """X ~ N(0,1) [T,D]; W1 ~ N(0,1/D) [D,F]; W2 ~ N(0,1/F) [F,D]; b1 [F]; optionally dY ~ N(0,1) [T,D].
+    token_corr = (L, rho): consecutive tokens are correlated in runs of L (what the paper reports of real activations:
+    a feature is often non-zero on a stretch of consecutive tokens): x_t = sqrt(rho) base_{t // L} + sqrt(1 - rho) e_t,
+    still N(0,1) marginally."""
     rng = np.random.Generator(np.random.Philox(seed))
+    X = rng.standard_normal((T, D), dtype=np.float32)
+    if token_corr is not None:
+        L, rho = token_corr
+        base = np.random.Generator(np.random.Philox(seed + 7919)).standard_normal(((T + L - 1) // L, D), dtype=np.float32)
+        X = np.float32(np.sqrt(rho)) * np.repeat(base, L, axis=0)[:T] + np.float32(np.sqrt(1.0 - rho)) * X
     out = {
-        "X": rng.standard_normal((T, D), dtype=np.float32),
+        "X": X,
         "W1": rng.standard_normal((D, F), dtype=np.float32) * np.float32(1.0 / np.sqrt(D)),
         "W2": rng.standard_normal((F, D), dtype=np.float32) * np.float32(1.0 / np.sqrt(F)),
         "b1": bias_for(F, sparsity, rng),
@@ -116,3 +124,8 @@ def make_inputs_fp8_rowwise(T: int, D: int, F: int, sparsity, seed: int) -> dict
     out["W1"], out["sw1"] = quant(inp["W1"], 0)
     out["W2"], out["sw2"] = quant(inp["W2"], 0)
     return out
+
+
+def token_permutation(T: int, seed: int) -> np.ndarray:
+    """A fixed pseudo-random permutation of the tokens (int32 [T]): position p inside the FFN holds token perm[p]."""
+    return np.random.Generator(np.random.Philox(seed)).permutation(T).astype(np.int32)

@@ -501,3 +501,43 @@ def test_quantise_rows_e4m3():
     assert np.allclose(s, [2.0 / 448, 1.0, 1.0])
     assert codes[0, 1] == 0xFE and codes[1].tolist() == [0, 0, 0] and codes[2, 0] == 0x7E
     np.testing.assert_allclose(O.e4m3_bits_to_f32(codes) * s[:, None], x, rtol=0.07, atol=1e-6)
+
+
+def test_token_permutation_is_exact_for_everything_but_the_featurewise_groups():
+    """Sec. 2, Optimization 2.  The forward is per token, so Y and dX come back unchanged; with the token-wise mask
+    only, the weight gradients are plain sums over tokens and do not change either (up to the order of the float64
+    sum); the feature-wise-masked weight gradients do change, because other tokens share a group of 4."""
+    inp = synth.make_inputs(64, 32, 96, 0.6, seed=23, with_dy=True)
+    perm = synth.token_permutation(64, seed=5)
+    f = O.ffn24_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"])
+    g_tw = O.ffn24_bwd(f, inp["dY"], wgrad_mask="tokenwise")
+    g_fw = O.ffn24_bwd(f, inp["dY"])
+    p_tw = O.ffn24_fwd_bwd_permuted(inp["X"], inp["W1"], inp["b1"], inp["W2"], inp["dY"], perm, wgrad_mask="tokenwise")
+    p_fw = O.ffn24_fwd_bwd_permuted(inp["X"], inp["W1"], inp["b1"], inp["W2"], inp["dY"], perm)
+    assert np.array_equal(p_fw["Y"], f["Y"]) and np.array_equal(p_fw["dX"], g_fw["dX"])
+    np.testing.assert_allclose(p_tw["dW1"], g_tw["dW1"], rtol=0, atol=1e-12)
+    np.testing.assert_allclose(p_tw["dW2"], g_tw["dW2"], rtol=0, atol=1e-12)
+    assert np.abs(p_fw["dW2"] - g_fw["dW2"]).max() > 1e-3
+    ident = O.ffn24_fwd_bwd_permuted(inp["X"], inp["W1"], inp["b1"], inp["W2"], inp["dY"], np.arange(64))
+    assert np.array_equal(ident["dW2"], g_fw["dW2"]) and np.array_equal(ident["dW1"], g_fw["dW1"])
+    with pytest.raises(ValueError):
+        O.ffn24_fwd_bwd_permuted(inp["X"], inp["W1"], inp["b1"], inp["W2"], inp["dY"], np.zeros(64, int))
+
+
+def test_token_permutation_undoes_the_damage_of_correlated_tokens():
+    """Why the paper permutes: when a feature is non-zero on a stretch of consecutive tokens, a group of 4 consecutive
+    tokens often holds more than 2 non-zeros and the feature-wise 2:4 drops many of them; a fixed permutation brings
+    the drop rate back to that of independent tokens (closed form for an i.i.d. support of density p)."""
+    T, D, F = 1024, 64, 512
+    inp = synth.make_inputs(T, D, F, 0.9, seed=29, token_corr=(8, 0.95))
+    f = O.ffn24_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"])
+    _, _, M_T = O.featurewise24(f["H24"])
+    drop_corr = O.featurewise_drop_fraction(f["H24"], M_T)
+    perm = synth.token_permutation(T, seed=6)
+    fp = O.ffn24_fwd(inp["X"][perm], inp["W1"], inp["b1"], inp["W2"])
+    _, _, M_Tp = O.featurewise24(fp["H24"])
+    drop_perm = O.featurewise_drop_fraction(fp["H24"], M_Tp)
+    p = float((f["H24"] != 0).mean())
+    iid = (4 * p ** 3 * (1 - p) + 2 * p ** 4) / (4 * p)
+    assert drop_corr > 5 * drop_perm
+    assert abs(drop_perm - iid) < 0.5 * iid
