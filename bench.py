@@ -152,6 +152,7 @@ def main() -> int:
     ap.add_argument("--split", type=int, default=0, help="keep this many hidden features (multiple of 256, <= d_ff/4) out of the "
                     "feature-wise 2:4: split weight-gradient GEMMs (bf16 fwd+bwd workloads)")
     ap.add_argument("--rowwise", action="store_true", help="fp8 workload with row-wise instead of per-tensor scales (no dense baseline in this mode)")
+    ap.add_argument("--permute", action="store_true", help="run the bf16 workload with a fixed token permutation around the FFN")
     ap.add_argument("--split-sweep", action="store_true", help="time the weight-gradient stage over a range of split sizes")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy before the steps (the known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE)")
@@ -187,9 +188,12 @@ def main() -> int:
     else:
         inp = synth.make_workload(args.workload, with_dy=True)
         dev = {k: torch.from_numpy(inp[k]).to(torch.bfloat16).cuda() for k in ("X", "W1", "W2", "dY")}
-        ctx = ffn24.Context(T, D, F, (ffn24.FFN24_TRAINING if bwd else 0) | ffn24.FFN24_DENSE | (ffn24.FFN24_SPLIT if args.split and bwd else 0))
+        ctx = ffn24.Context(T, D, F, (ffn24.FFN24_TRAINING if bwd else 0) | ffn24.FFN24_DENSE | (ffn24.FFN24_SPLIT if args.split and bwd else 0)
+                            | (ffn24.FFN24_PERMUTE if args.permute else 0))
         if args.split and bwd:
             ctx.set_split(args.split)
+        if args.permute:
+            ctx.set_token_permutation(synth.token_permutation(T, w.seed + 1))
     b1 = torch.from_numpy(inp["b1"]).cuda()
     peak = PEAK_FP8_DENSE if fp8 else PEAK_BF16_DENSE
     Y = torch.empty((T, D), dtype=torch.bfloat16, device="cuda")
@@ -321,7 +325,7 @@ def main() -> int:
         "dtype": "fp8" if fp8 else "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: 2:4 Squared-ReLU FFN {'fwd+bwd' if bwd else 'fwd'}, T={T} d_model={D} d_ff={F}, target sparsity {w.sparsity}"
                                + (f", {args.split} dense features in the weight gradients" if args.split and bwd else "")
-                               + (", row-wise fp8 scales" if rowwise else ""),
+                               + (", row-wise fp8 scales" if rowwise else "") + (", fixed token permutation" if args.permute and not fp8 else ""),
                    "T": T, "d_model": D, "d_ff": F, "parallelism": "single GPU"},
         "frac_of_sparse_mfma_peak": round(value / (2 * peak), 4),
         "dense_ffn": None if rowwise else {"ms_per_step": round(sec_dense * 1e3, 4), "tflops": round(flops_step / sec_dense / 1e12, 2)},

@@ -55,6 +55,7 @@ typedef enum { FFN24_BF16 = 0, FFN24_FP8_E4M3 = 1 } ffn24_dtype;
 #define FFN24_DEBUG_DUMP_H 4 /* ffn24_fwd also stores the rounded activation before pruning, [T][F] */
 #define FFN24_SPLIT 8        /* allocate what the split weight-gradient GEMMs need (with FFN24_TRAINING; see ffn24_set_split) */
 #define FFN24_ROWWISE 16     /* fp8 context with row-wise instead of per-tensor scales (see ffn24_set_row_scales) */
+#define FFN24_PERMUTE 32     /* bf16 context that can run with a token permutation (see ffn24_set_token_permutation) */
 
 typedef struct ffn24_ctx ffn24_ctx; /* opaque; owns only its device workspace */
 
@@ -85,6 +86,17 @@ FFN24_API int ffn24_set_scales(ffn24_ctx* ctx, float sx, float sw1, float sh, fl
  * sparsification fused in), a quantisation kernel (the row scale needs the whole row), the 2:4 GEMM.
  * Saved tensor 11 is sh [T] fp32.  ffn_fwd is not available in this mode (FFN24_ERR_STATE). */
 FFN24_API int ffn24_set_row_scales(ffn24_ctx* ctx, const float* sx, const float* sw1, const float* sw2);
+
+/* Fixed token permutation around the FFN (paper Sec. 2, "Optimization 2": features are correlated among consecutive
+ * tokens, so the tokens are permuted before entering the FFN and shuffled back after).  perm_host is a HOST array
+ * [T]: position p inside the FFN holds token perm_host[p].  It is checked here (FFN24_ERR_SHAPE unless it is a
+ * permutation of 0..T-1) and copied to the device synchronously (the call waits for the device); NULL switches the
+ * permutation off.  Afterwards ffn24_fwd / ffn24_bwd still take and return X, Y, dY, dX in token order: the rows of X
+ * and dY are gathered by the operand DMA of the GEMMs that read them and the rows of Y and dX are scattered by the
+ * epilogues of the GEMMs that produce them, so no extra pass over any tensor is made.  Inside, every saved tensor is in
+ * permuted token order, and the feature-wise 2:4 groups of the weight gradients are made of the tokens the permutation
+ * puts side by side.  Needs FFN24_PERMUTE (bf16 contexts; T d_model < 2^31). */
+FFN24_API int ffn24_set_token_permutation(ffn24_ctx* ctx, const int32_t* perm_host);
 
 /* Split of the weight-gradient GEMMs (paper Sec. 2, "Optimization 1"): some hidden features are too dense to be
  * 2:4-sparsified along tokens, so the n_dense least sparse features are kept out of the feature-wise pruning.

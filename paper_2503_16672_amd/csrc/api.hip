@@ -20,6 +20,7 @@ struct ffn24_ctx {
   int f8;                      // element type FFN24_FP8_E4M3 (forward only)
   float sx, sw1, sh, sw2;      // per-tensor scales of the fp8 path
   // row-wise-scaled fp8 forward (FFN24_ROWWISE): caller's scale vectors, and the library's intermediate tensors
+  int* perm; int perm_on;      // token permutation (FFN24_PERMUTE): device copy, and whether one is set
   const float *rsx, *rsw1, *rsw2;
   void* Hc16; uint8_t* meta16; uint32_t* rowmax; float* rsh;
   // workspace (device)
@@ -55,7 +56,7 @@ int free_all(ffn24_ctx* c) {
   int bad = 0;
   void* bufs[] = {c->Hc, c->meta, c->dZc, c->Hc_t, c->meta_t, c->dZc_t, c->Hdbg, c->Hd, c->dZd,
                   c->W1t, c->W2t, c->Xt, c->dYt, c->Hd_t, c->dZd_t, c->W2p,
-                  c->nnz, c->row_of_feat, c->feat_of_row, c->Hdn_t, c->dZdn_t, c->dW1t, c->Hc16, c->meta16, c->rowmax, c->rsh};
+                  c->nnz, c->row_of_feat, c->feat_of_row, c->Hdn_t, c->dZdn_t, c->dW1t, c->Hc16, c->meta16, c->rowmax, c->rsh, c->perm};
   for (void* b : bufs) if (b && hipFree(b) != hipSuccess) bad = 1;
   for (int k = 0; k < NUM_KERNELS; k++) for (int j = 0; j < 2; j++) if (c->ev[k][j]) (void)hipEventDestroy(c->ev[k][j]);
   return bad;
@@ -91,6 +92,9 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
   if (f8 && (flags & FFN24_TRAINING)) return FFN24_ERR_DTYPE;   // the fp8 path is forward only
   if ((flags & FFN24_SPLIT) && !(flags & FFN24_TRAINING)) return FFN24_ERR_STATE;
   if ((flags & FFN24_ROWWISE) && !f8) return FFN24_ERR_DTYPE;
+  if ((flags & FFN24_PERMUTE) && f8) return FFN24_ERR_DTYPE;
+  // the DMA gathers permuted rows with 32-bit byte offsets from the tensor base
+  if ((flags & FFN24_PERMUTE) && (uint64_t)T * (uint64_t)D * 2u >= (1ull << 32)) return FFN24_ERR_SHAPE;
   if (T <= 0 || D <= 0 || F <= 0 || T % 256 || D % 256 || F % 256) return FFN24_ERR_SHAPE;
   if (T > (1 << 20) || D > (1 << 20) || F > (1 << 20)) return FFN24_ERR_SHAPE;
   ffn24_ctx* c = new (std::nothrow) ffn24_ctx();
@@ -112,6 +116,7 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
          hipMalloc(reinterpret_cast<void**>(&c->feat_of_row), 4 * (size_t)F) == hipSuccess &&
          hipMalloc(&c->Hdn_t, tf / 2) == hipSuccess && hipMalloc(&c->dZdn_t, tf / 2) == hipSuccess &&   // up to F/4 dense rows
          hipMalloc(&c->dW1t, 2 * df) == hipSuccess;
+  if (ok && (flags & FFN24_PERMUTE)) ok = hipMalloc(reinterpret_cast<void**>(&c->perm), 4 * (size_t)T) == hipSuccess;
   if (ok && (flags & FFN24_ROWWISE))
     ok = hipMalloc(&c->Hc16, tf) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->meta16), tf / 8) == hipSuccess &&
          hipMalloc(reinterpret_cast<void**>(&c->rowmax), 4 * (size_t)T) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->rsh), 4 * (size_t)T) == hipSuccess;
@@ -147,6 +152,30 @@ int ffn24_set_row_scales(ffn24_ctx* c, const float* sx, const float* sw1, const 
   if (!sx || !sw1 || !sw2) return FFN24_ERR_NULL;
   if (misaligned(sx) || misaligned(sw1) || misaligned(sw2)) return FFN24_ERR_ALIGN;
   c->rsx = sx; c->rsw1 = sw1; c->rsw2 = sw2;
+  return FFN24_OK;
+}
+
+int ffn24_set_token_permutation(ffn24_ctx* c, const int32_t* perm_host) {
+  if (!c) return FFN24_ERR_NULL;
+  if (!(c->flags & FFN24_PERMUTE)) return FFN24_ERR_STATE;
+  c->have_fwd24 = 0;
+  if (!perm_host) { c->perm_on = 0; return FFN24_OK; }
+  // validated on the host: every index in range and used exactly once (the kernels gather and scatter rows with it)
+  const int64_t T = c->T;
+  uint8_t* seen = new (std::nothrow) uint8_t[(size_t)T]();
+  if (!seen) return FFN24_ERR_HIP;
+  bool ok = true;
+  for (int64_t i = 0; i < T && ok; i++) {
+    int32_t v = perm_host[i];
+    ok = v >= 0 && v < T && !seen[v];
+    if (ok) seen[v] = 1;
+  }
+  delete[] seen;
+  if (!ok) return FFN24_ERR_SHAPE;
+  // synchronous copy: a set-up call, and no stream may still be reading the old permutation
+  if (hipDeviceSynchronize() != hipSuccess) return FFN24_ERR_HIP;
+  if (hipMemcpy(c->perm, perm_host, 4 * (size_t)T, hipMemcpyHostToDevice) != hipSuccess) return FFN24_ERR_HIP;
+  c->perm_on = 1;
   return FFN24_OK;
 }
 
@@ -289,12 +318,15 @@ int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, cons
     return FFN24_OK;
   }
   { Timed t(c, K_TR_W, s);
-    int rc1 = launch_transpose(W1, D, F, c->W1t, 1, nullptr, s);
-    if (t.done(rc1 ? rc1 : launch_transpose(W2, F, D, c->W2t, 0, c->W2p, s))) return FFN24_ERR_HIP; }
+    int rc1 = launch_transpose(W1, D, F, c->W1t, 1, nullptr, nullptr, s);
+    if (t.done(rc1 ? rc1 : launch_transpose(W2, F, D, c->W2t, 0, c->W2p, nullptr, s))) return FFN24_ERR_HIP; }
   uint32_t* nnz = (c->flags & FFN24_SPLIT) && c->n_dense > 0 ? c->nnz : nullptr;
   if (nnz && hipMemsetAsync(nnz, 0, 4 * (size_t)F, s) != hipSuccess) return FFN24_ERR_HIP;
-  { Timed t(c, K_UP, s);   if (t.done(launch_up_prune24(c->W1t, X, b1, T, D, F, c->Hc, c->meta, c->Hdbg, nnz, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, K_DOWN, s); if (t.done(launch_sp_rowmajor(c->Hc, c->meta, 1, c->W2t, T, D, F, Y, s))) return FFN24_ERR_HIP; }
+  const int* perm = c->perm_on ? c->perm : nullptr;   // position p inside the FFN holds token perm[p]
+  { Timed t(c, K_UP, s);   if (t.done(launch_up_prune24(c->W1t, X, b1, T, D, F, c->Hc, c->meta, c->Hdbg, nnz, perm, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_DOWN, s);
+    int rc1 = perm ? launch_sp_rowmajor_mapped(c->Hc, c->meta, 1, c->W2t, T, D, F, Y, perm, s) : launch_sp_rowmajor(c->Hc, c->meta, 1, c->W2t, T, D, F, Y, s);
+    if (t.done(rc1)) return FFN24_ERR_HIP; }
   c->X = X; c->W1 = W1; c->W2 = W2; c->have_fwd24 = 1;
   return FFN24_OK;
 }
@@ -306,8 +338,11 @@ int ffn24_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void
   if (rc) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
-  { Timed t(c, K_DH, s);  if (t.done(launch_dh_gather(c->W2p, dY, c->Hc, c->meta, T, D, F, c->dZc, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, K_DX, s);  if (t.done(launch_sp_rowmajor(c->dZc, c->meta, 1, c->W1, T, D, F, dX, s))) return FFN24_ERR_HIP; }
+  const int* perm = c->perm_on ? c->perm : nullptr;   // position p inside the FFN holds token perm[p]
+  { Timed t(c, K_DH, s);  if (t.done(launch_dh_gather(c->W2p, dY, c->Hc, c->meta, T, D, F, c->dZc, perm, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_DX, s);
+    int rc1 = perm ? launch_sp_rowmajor_mapped(c->dZc, c->meta, 1, c->W1, T, D, F, dX, perm, s) : launch_sp_rowmajor(c->dZc, c->meta, 1, c->W1, T, D, F, dX, s);
+    if (t.done(rc1)) return FFN24_ERR_HIP; }
   const bool split = (c->flags & FFN24_SPLIT) && c->n_dense > 0;
   if (split) {
     // Sec. 2, "Optimization 1": the n_dense least sparse features are kept out of the feature-wise 2:4; their rows
@@ -318,17 +353,17 @@ int ffn24_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void
       if (t.done(launch_featurewise24_split(c->Hc, c->meta, c->dZc, T, F, c->row_of_feat, ns, c->Hc_t, c->meta_t, c->dZc_t, c->Hdn_t, c->dZdn_t, s)))
         return FFN24_ERR_HIP; }
     { Timed t(c, K_TR_ACT, s);
-      int rc1 = launch_transpose(dY, T, D, c->dYt, 0, nullptr, s);
-      if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, 0, nullptr, s))) return FFN24_ERR_HIP; }
+      int rc1 = launch_transpose(dY, T, D, c->dYt, 0, nullptr, perm, s);
+      if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, 0, nullptr, perm, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_DW2, s); if (t.done(launch_split_wgrad(c->Hc_t, c->meta_t, ns, c->Hdn_t, nd, c->dYt, D, T, dW2, D, c->feat_of_row, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_DW1, s); if (t.done(launch_split_wgrad(c->dZc_t, c->meta_t, ns, c->dZdn_t, nd, c->Xt, D, T, c->dW1t, D, c->feat_of_row, s))) return FFN24_ERR_HIP; }
-    { Timed t(c, K_TR_DW1, s); if (t.done(launch_transpose(c->dW1t, F, D, dW1, 0, nullptr, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_TR_DW1, s); if (t.done(launch_transpose(c->dW1t, F, D, dW1, 0, nullptr, nullptr, s))) return FFN24_ERR_HIP; }
     return FFN24_OK;
   }
   { Timed t(c, K_FW, s);  if (t.done(launch_featurewise24(c->Hc, c->meta, c->dZc, T, F, c->Hc_t, c->meta_t, c->dZc_t, 1, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_TR_ACT, s);
-    int rc1 = launch_transpose(dY, T, D, c->dYt, 0, nullptr, s);
-    if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, 0, nullptr, s))) return FFN24_ERR_HIP; }
+    int rc1 = launch_transpose(dY, T, D, c->dYt, 0, nullptr, perm, s);
+    if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, 0, nullptr, perm, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_DW2, s); if (t.done(launch_sp_rowmajor(c->Hc_t, c->meta_t, 1, c->dYt, F, D, T, dW2, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_DW1, s); if (t.done(launch_sp_colmajor(c->dZc_t, c->meta_t, 1, c->Xt, F, D, T, dW1, s))) return FFN24_ERR_HIP; }
   return FFN24_OK;
@@ -354,8 +389,8 @@ int ffn_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const 
     return FFN24_OK;
   }
   { Timed t(c, K_TR_W, s);
-    int rc1 = launch_transpose(W1, D, F, c->W1t, 1, nullptr, s);
-    if (t.done(rc1 ? rc1 : launch_transpose(W2, F, D, c->W2t, 0, c->W2p, s))) return FFN24_ERR_HIP; }
+    int rc1 = launch_transpose(W1, D, F, c->W1t, 1, nullptr, nullptr, s);
+    if (t.done(rc1 ? rc1 : launch_transpose(W2, F, D, c->W2t, 0, c->W2p, nullptr, s))) return FFN24_ERR_HIP; }
   { Timed t(c, KD_UP, s);   if (t.done(launch_up_relu2(c->W1t, X, b1, T, D, F, c->Hd, c->Hd_t, s))) return FFN24_ERR_HIP; }
   { Timed t(c, KD_DOWN, s); if (t.done(launch_dense_rowmajor(c->Hd, 1, c->W2t, T, D, F, Y, s))) return FFN24_ERR_HIP; }
   c->X = X; c->W1 = W1; c->W2 = W2; c->have_fwd_dense = 1;
@@ -372,8 +407,8 @@ int ffn_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void* 
   { Timed t(c, KD_DH, s);  if (t.done(launch_dh_drelu(c->W2p, dY, c->Hd, T, D, F, c->dZd, c->dZd_t, s))) return FFN24_ERR_HIP; }
   { Timed t(c, KD_DX, s);  if (t.done(launch_dense_rowmajor(c->dZd, 1, c->W1, T, D, F, dX, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_TR_ACT, s);
-    int rc1 = launch_transpose(dY, T, D, c->dYt, 0, nullptr, s);
-    if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, 0, nullptr, s))) return FFN24_ERR_HIP; }
+    int rc1 = launch_transpose(dY, T, D, c->dYt, 0, nullptr, nullptr, s);
+    if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, 0, nullptr, nullptr, s))) return FFN24_ERR_HIP; }
   { Timed t(c, KD_DW2, s); if (t.done(launch_dense_rowmajor(c->Hd_t, 1, c->dYt, F, D, T, dW2, s))) return FFN24_ERR_HIP; }
   { Timed t(c, KD_DW1, s); if (t.done(launch_dense_colmajor(c->dZd_t, 1, c->Xt, F, D, T, dW1, s))) return FFN24_ERR_HIP; }
   return FFN24_OK;

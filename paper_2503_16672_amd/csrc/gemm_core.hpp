@@ -73,6 +73,7 @@ struct GemmArgs {
   const void* B;         // [N][K]
   int M, N, K;           // K is the dense reduction length
   int a_panel;           // A (and its metadata) is in panel form (see above) instead of row-major
+  const int* b_rowmap;   // optional: row n of B is taken from memory row b_rowmap[n] (token permutation, gathered by the DMA)
 };
 
 // piece index of row r, 64-k panel kp, for an operand with `npanels` = K / 64 panels per row
@@ -149,7 +150,7 @@ struct Dma {
     const uint32_t b_row = (uint32_t)g.K * G::ESIZE;                 // bytes per B row in memory
     const uint32_t a_row = SPARSE ? b_row / 2 : b_row;               // bytes per A row (stored values only if sparse)
     a = static_cast<const char*>(g.A) + (size_t)m0 * a_row;
-    b = static_cast<const char*>(g.B) + (size_t)n0 * b_row;
+    b = static_cast<const char*>(g.B) + (g.b_rowmap ? (size_t)0 : (size_t)n0 * b_row);
     am = SPARSE ? reinterpret_cast<const char*>(g.Ameta) + (size_t)m0 * (g.K / 8) : nullptr;
     // a block tile's 256 rows occupy the same byte range in both forms; only the order of the pieces inside differs
     const bool panel = g.a_panel != 0;
@@ -161,14 +162,14 @@ struct Dma {
       int p = 64 * wave + 16 * j + (lane >> 2);
       int c = (lane & 3) ^ swz4(p);
       va[j] = (uint32_t)unperm_m(p) * a_pitch + c * 16;
-      if constexpr (!SPARSE) vb[j] = (uint32_t)unperm_n(p) * b_row + c * 16;
+      if constexpr (!SPARSE) vb[j] = (g.b_rowmap ? (uint32_t)g.b_rowmap[n0 + unperm_n(p)] : (uint32_t)unperm_n(p)) * b_row + c * 16;
     }
     if constexpr (SPARSE) {
 #pragma unroll
       for (int j = 0; j < 8; j++) {
         int p = 64 * wave + 8 * j + (lane >> 3);
         int c = (lane & 7) ^ swz8(p);
-        vb[j] = (uint32_t)unperm_n(p) * b_row + c * 16;
+        vb[j] = (g.b_rowmap ? (uint32_t)g.b_rowmap[n0 + unperm_n(p)] : (uint32_t)unperm_n(p)) * b_row + c * 16;
       }
       if constexpr (F8) {
         vm[0] = (uint32_t)unperm_m(64 * wave + lane) * m_pitch;      // one row's 16 metadata bytes per lane

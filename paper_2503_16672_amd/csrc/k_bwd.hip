@@ -3,8 +3,9 @@
 
 namespace ffn24 {
 
-int launch_dh_gather(const void* W2, const void* dY, const void* Hc, const uint8_t* meta, int T, int D, int F, void* dZc, hipStream_t s) {
-  GemmArgs g{W2, nullptr, dY, F, T, D, 1};
+int launch_dh_gather(const void* W2, const void* dY, const void* Hc, const uint8_t* meta, int T, int D, int F, void* dZc,
+                     const int* token_map, hipStream_t s) {
+  GemmArgs g{W2, nullptr, dY, F, T, D, 1, token_map};
   EpiDGather::Args ea{static_cast<const __bf16*>(Hc), meta, static_cast<__bf16*>(dZc), F};
   return launch_gemm<false, EpiDGather>(g, ea, s);
 }

@@ -5,8 +5,8 @@
 namespace ffn24 {
 
 int launch_up_prune24(const void* W1t, const void* X, const float* b1, int T, int D, int F,
-                      void* Hc, uint8_t* meta, void* Hdbg, uint32_t* nnz, hipStream_t s) {
-  GemmArgs g{W1t, nullptr, X, F, T, D, 1};
+                      void* Hc, uint8_t* meta, void* Hdbg, uint32_t* nnz, const int* token_map, hipStream_t s) {
+  GemmArgs g{W1t, nullptr, X, F, T, D, 1, token_map};
   EpiPrune24::Args ea{static_cast<__bf16*>(Hc), meta, static_cast<__bf16*>(Hdbg), b1, F, nnz};
   return launch_gemm<false, EpiPrune24>(g, ea, s);
 }
@@ -15,6 +15,13 @@ int launch_sp_rowmajor(const void* vals, const uint8_t* meta, int a_panel, const
   GemmArgs g{vals, meta, B, M, N, K, a_panel};
   EpiRowMajor::Args ea{static_cast<__bf16*>(C), N};
   return launch_gemm<true, EpiRowMajor>(g, ea, s);
+}
+
+int launch_sp_rowmajor_mapped(const void* vals, const uint8_t* meta, int a_panel, const void* B, int M, int N, int K, void* C,
+                              const int* rowmap, hipStream_t s) {
+  GemmArgs g{vals, meta, B, M, N, K, a_panel};
+  EpiRowMajorMapped::Args ea{static_cast<__bf16*>(C), N, rowmap};
+  return launch_gemm<true, EpiRowMajorMapped>(g, ea, s);
 }
 
 }  // namespace ffn24

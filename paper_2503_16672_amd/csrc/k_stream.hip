@@ -304,11 +304,12 @@ int launch_unpanel(const void* src, int rows, int npanels, int piece_bytes, void
 // written out as 128-byte rows of the transposed matrix.
 // OUT_PANEL: the transposed matrix is written in the dense panel form of gemm_core.hpp (64-byte pieces of 32 k, K = R).
 // in_panel (optional): a copy of the input itself in panel form (K = C), made in the same pass.
+// in_rowmap (optional): input row r is read from memory row in_rowmap[r] (token permutation).
 constexpr int TR_LD = 66;
 
 template <bool OUT_PANEL>
 __global__ void __launch_bounds__(256) transpose_kernel(const uint16_t* __restrict__ in, int R, int C, uint16_t* __restrict__ out,
-                                                        uint16_t* __restrict__ in_panel) {
+                                                        uint16_t* __restrict__ in_panel, const int* __restrict__ in_rowmap) {
   __shared__ __attribute__((aligned(16))) uint16_t sT[64 * TR_LD];
   int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
   int tid = threadIdx.x;
@@ -316,7 +317,8 @@ __global__ void __launch_bounds__(256) transpose_kernel(const uint16_t* __restri
 #pragma unroll
   for (int i = 0; i < 2; i++) {
     int r = rr + 32 * i;
-    u32x4 v = *reinterpret_cast<const u32x4*>(in + (size_t)(r0 + r) * C + c0 + 8 * ch);
+    size_t src_row = in_rowmap ? (size_t)in_rowmap[r0 + r] : (size_t)(r0 + r);
+    u32x4 v = *reinterpret_cast<const u32x4*>(in + src_row * C + c0 + 8 * ch);
     if (in_panel) {
       int c = c0 + 8 * ch;
       *reinterpret_cast<u32x4*>(in_panel + a24_piece(r0 + r, c >> 5, C >> 5) * 32 + (c & 31)) = v;
@@ -339,11 +341,11 @@ __global__ void __launch_bounds__(256) transpose_kernel(const uint16_t* __restri
   }
 }
 
-int launch_transpose(const void* in, int R, int C, void* out, int out_panel, void* in_panel, hipStream_t s) {
+int launch_transpose(const void* in, int R, int C, void* out, int out_panel, void* in_panel, const int* in_rowmap, hipStream_t s) {
   dim3 grid(C / 64, R / 64);
   auto kern = out_panel ? transpose_kernel<true> : transpose_kernel<false>;
   hipLaunchKernelGGL(kern, grid, dim3(256), 0, s, static_cast<const uint16_t*>(in), R, C, static_cast<uint16_t*>(out),
-                     static_cast<uint16_t*>(in_panel));
+                     static_cast<uint16_t*>(in_panel), in_rowmap);
   return (int)hipGetLastError();
 }
 

@@ -10,15 +10,20 @@ namespace ffn24 {
 
 // up-projection with rows = hidden features: A = W1^T [F][D] in dense panel form, B = X [T][D]
 // nnz (may be NULL): [F] per-feature non-zero counts, accumulated with atomics (zeroed by the caller)
+// token_map (may be NULL, also below): column n of the GEMM (position n inside the FFN) is token token_map[n] of X / dY
 int launch_up_prune24(const void* W1t, const void* X, const float* b1, int T, int D, int F,
-                      void* Hc, uint8_t* meta, void* Hdbg, uint32_t* nnz, hipStream_t s);
+                      void* Hc, uint8_t* meta, void* Hdbg, uint32_t* nnz, const int* token_map, hipStream_t s);
 int launch_up_relu2(const void* W1t, const void* X, const float* b1, int T, int D, int F, void* H, void* Ht, hipStream_t s);
 // C[M][N] = A24[M][K] * B[N][K]^T; a_panel: (vals, meta) are in panel form instead of row-major
 int launch_sp_rowmajor(const void* vals, const uint8_t* meta, int a_panel, const void* B, int M, int N, int K, void* C, hipStream_t s);
 // out[N][M] = (A24[M][K] * B[N][K]^T)^T
 int launch_sp_colmajor(const void* vals, const uint8_t* meta, int a_panel, const void* B, int M, int N, int K, void* Ct, hipStream_t s);
 // dH = dY W2^T with rows = hidden features: A = W2 [F][D] in dense panel form, B = dY [T][D]; pointwise part fused
-int launch_dh_gather(const void* W2, const void* dY, const void* Hc, const uint8_t* meta, int T, int D, int F, void* dZc, hipStream_t s);
+int launch_dh_gather(const void* W2, const void* dY, const void* Hc, const uint8_t* meta, int T, int D, int F, void* dZc,
+                     const int* token_map, hipStream_t s);
+// C[rowmap[m]][N] = (A24 * B^T)[m][N]: the result rows go back to their tokens
+int launch_sp_rowmajor_mapped(const void* vals, const uint8_t* meta, int a_panel, const void* B, int M, int N, int K, void* C,
+                              const int* rowmap, hipStream_t s);
 int launch_dh_drelu(const void* W2, const void* dY, const void* H, int T, int D, int F, void* dZ, void* dZt, hipStream_t s);
 // split weight gradient (operands in panel form): rows [0, ns) from the sparse GEMM over (vals, meta) [ns][K], rows
 // [ns, ns + nd) from the dense GEMM over Ad [nd][K], both against B [N][K], one launch; row m goes to C[rowmap[m]][*]
@@ -59,7 +64,8 @@ int launch_featurewise24(const void* Hc, const uint8_t* meta, const void* dZc, i
 int launch_unpanel(const void* src, int rows, int npanels, int piece_bytes, void* dst, hipStream_t s);
 // in [R][C] -> out [C][R] (R, C % 64 == 0); out_panel: out is written in dense panel form (then C % 256 == 0);
 // in_panel (may be NULL): also a panel-form copy of `in` itself (then R % 256 == 0)
-int launch_transpose(const void* in, int R, int C, void* out, int out_panel, void* in_panel, hipStream_t s);
+// in_rowmap (may be NULL): row r of the input is taken from memory row in_rowmap[r]
+int launch_transpose(const void* in, int R, int C, void* out, int out_panel, void* in_panel, const int* in_rowmap, hipStream_t s);
 // the same for 1-byte elements (fp8): in [R][C] -> out [C][R]; out_panel: 64-byte pieces of 64 k
 int launch_transpose8(const void* in, int R, int C, void* out, int out_panel, hipStream_t s);
 

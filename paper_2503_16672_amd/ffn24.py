@@ -21,9 +21,10 @@ FFN24_DENSE = 2
 FFN24_DEBUG_DUMP_H = 4
 FFN24_SPLIT = 8
 FFN24_ROWWISE = 16
+FFN24_PERMUTE = 32
 
 EXPORTS = (
-    "ffn24_ctx_create", "ffn24_ctx_destroy", "ffn24_set_scales", "ffn24_set_row_scales", "ffn24_set_split", "sparsify24", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd",
+    "ffn24_ctx_create", "ffn24_ctx_destroy", "ffn24_set_scales", "ffn24_set_row_scales", "ffn24_set_token_permutation", "ffn24_set_split", "sparsify24", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd",
     "ffn_fwd", "ffn_bwd", "ffn24_saved_bytes", "ffn24_copy_saved", "ffn24_set_profiling", "ffn24_kernel_ms", "ffn24_strerror",
 )
 
@@ -52,6 +53,7 @@ def lib() -> ctypes.CDLL:
         L.ffn24_ctx_destroy.argtypes = [vp]
         L.ffn24_set_scales.argtypes = [vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_float]
         L.ffn24_set_split.argtypes = [vp, i64]
+        L.ffn24_set_token_permutation.argtypes = [vp, vp]
         L.ffn24_set_row_scales.argtypes = [vp, vp, vp, vp]
         L.sparsify24.argtypes = [vp, i64, i64, ci, vp, vp, vp]
         L.sparsify24_featurewise.argtypes = [vp, vp, vp, i64, i64, vp, vp, vp, vp]
@@ -152,6 +154,17 @@ class Context:
         """Row-wise scales of an FFN24_ROWWISE fp8 context: fp32 CUDA tensors [T], [F], [D]; the context keeps them alive."""
         self._row_scales = (sx, sw1, sw2)
         _check(lib().ffn24_set_row_scales(self._h, _ptr(sx), _ptr(sw1), _ptr(sw2)), "ffn24_set_row_scales")
+
+    def set_token_permutation(self, perm):
+        """perm: int32 numpy array [T] on the host (position p inside the FFN holds token perm[p]), or None to switch it off."""
+        if perm is None:
+            _check(lib().ffn24_set_token_permutation(self._h, None), "ffn24_set_token_permutation")
+            return
+        import numpy as np
+        perm = np.ascontiguousarray(perm, dtype=np.int32)
+        if perm.shape != (self.T,):
+            raise ValueError("perm must have one entry per token")
+        _check(lib().ffn24_set_token_permutation(self._h, perm.ctypes.data), "ffn24_set_token_permutation")
 
     def set_split(self, n_dense: int):
         """Keep the n_dense least sparse features out of the feature-wise 2:4 (see ffn24_set_split in the header)."""

@@ -794,3 +794,120 @@ def test_fp8_rowwise_rules(F24):
         ctx.ffn24_fwd(z8, z8, None, z8)
     assert e.value.code == -5
     ctx.close()
+
+
+# ----------------------------------------------------------------------------- token permutation (Optimization 2)
+def _gpu_drop_fraction(ctx):
+    """Fraction of the non-zero kept activations that the feature-wise 2:4 dropped, from the context's own tensors."""
+    nz_tok = int(torch.count_nonzero(ctx.saved("Hc").view(torch.int16)))
+    nz_feat = int(torch.count_nonzero(ctx.saved("Hc_t").view(torch.int16)))
+    return 1.0 - nz_feat / max(1, nz_tok)
+
+
+def test_ffn24_token_permutation_small(F24):
+    print("token permutation T=512 D=256 F=1024, correlated tokens", flush=True)
+    T, D, Fh = 512, 256, 1024
+    inp = synth.make_inputs(T, D, Fh, 0.85, seed=81, with_dy=True, token_corr=(8, 0.9))
+    perm = synth.token_permutation(T, seed=9)
+    d = _upload(inp)
+    ctx = F24.Context(T, D, Fh, F24.FFN24_DEBUG_DUMP_H | F24.FFN24_TRAINING | F24.FFN24_PERMUTE)
+    Y0 = ctx.ffn24_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    dX0, dW1_0, dW2_0 = ctx.ffn24_bwd(d["dY"])
+    torch.cuda.synchronize()
+    drop0 = _gpu_drop_fraction(ctx)
+    ctx.set_token_permutation(perm)
+    with pytest.raises(F24.Ffn24Error):                # a backward needs a forward made with the same setting
+        ctx.ffn24_bwd(d["dY"])
+    Y = ctx.ffn24_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    dX, dW1, dW2 = ctx.ffn24_bwd(d["dY"])
+    torch.cuda.synchronize()
+    drop1 = _gpu_drop_fraction(ctx)
+    # per-token results do not depend on where the token sits: bit-identical to the run without permutation
+    assert torch.equal(Y, Y0) and torch.equal(dX, dX0)
+    assert not torch.equal(dW2, dW2_0)
+    # saved tensors are in permuted order: position p holds token perm[p]
+    perm_t = torch.from_numpy(perm.astype(np.int64)).cuda()
+    Hd = ctx.saved("H_dump"); meta = ctx.saved("meta").cpu().numpy()
+    v_ref, m_ref = O.sparsify24(words_of(Hd))
+    assert np.array_equal(meta, m_ref) and np.array_equal(words_of(ctx.saved("Hc")), v_ref)
+    ref = O.ffn24_fwd_bwd_permuted(inp["X"], inp["W1"], inp["b1"], inp["W2"], inp["dY"], perm)
+    assert float(np.mean(meta == ref["fwd"]["meta"])) >= 0.995
+    # backward staged on the GPU's own forward state, in permuted order
+    fwd = O.fwd_from_saved(v_ref, meta, inp["X"][perm], inp["W1"], inp["W2"])
+    g = O.ffn24_bwd(fwd, inp["dY"][perm])
+    assert np.array_equal(ctx.saved("meta_t").cpu().numpy(), g["meta_t"])
+    assert np.array_equal(words_of(ctx.saved("Hc_t")), g["Hc_t_words"])
+    dX_ref = np.empty_like(g["dX"]); dX_ref[perm] = g["dX"]
+    errs = {"Y": O.max_rel_err(f64(Y), ref["Y"]), "dX": O.max_rel_err(f64(dX), dX_ref), "dW1": O.max_rel_err(f64(dW1), g["dW1"]),
+            "dW2": O.max_rel_err(f64(dW2), g["dW2"]), "dW2 end-to-end": O.max_rel_err(f64(dW2), ref["dW2"])}
+    print(f"  errs {errs}; feature-wise drop without / with permutation: {drop0:.4f} / {drop1:.4f}", flush=True)
+    assert max(errs.values()) <= TOL_BF16
+    assert drop0 > 2 * drop1
+    assert abs(drop1 - O.featurewise_drop_fraction(fwd["H24"], g["M_T"])) < 1e-9
+    # switching it off again restores the first run exactly
+    ctx.set_token_permutation(None)
+    ctx.ffn24_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    _, _, dW2_b = ctx.ffn24_bwd(d["dY"])
+    torch.cuda.synchronize()
+    assert torch.equal(dW2_b, dW2_0)
+    ctx.close()
+
+
+def test_token_permutation_rules(F24):
+    ctx = F24.Context(256, 256, 256, F24.FFN24_TRAINING | F24.FFN24_PERMUTE)
+    bad = np.arange(256, dtype=np.int32); bad[3] = 7                      # 7 twice, 3 never
+    with pytest.raises(F24.Ffn24Error) as e:
+        ctx.set_token_permutation(bad)
+    assert e.value.code == -2
+    bad = np.arange(256, dtype=np.int32); bad[0] = 256                     # out of range
+    with pytest.raises(F24.Ffn24Error) as e:
+        ctx.set_token_permutation(bad)
+    assert e.value.code == -2
+    ctx.close()
+    ctx = F24.Context(256, 256, 256, F24.FFN24_TRAINING)
+    with pytest.raises(F24.Ffn24Error) as e:
+        ctx.set_token_permutation(np.arange(256, dtype=np.int32))
+    assert e.value.code == -5
+    ctx.close()
+
+
+@pytest.mark.timeout(900)
+def test_ffn24_token_permutation_full_size(F24):
+    """c4 shape with correlated tokens: outputs bit-identical to the run without permutation, the feature-wise drop
+    rate falls to the i.i.d. level, feature-wise picks bit-exact on sampled feature groups."""
+    w = synth.WORKLOADS["c4"]
+    T, D, Fh = w.T, w.D, w.F
+    print("token permutation full size c4, correlated tokens (runs of 8, rho 0.9)", flush=True)
+    inp = synth.make_inputs(T, D, Fh, w.sparsity, w.seed, with_dy=True, token_corr=(8, 0.9))
+    perm = synth.token_permutation(T, seed=10)
+    d = _upload(inp)
+    ctx = F24.Context(T, D, Fh, F24.FFN24_TRAINING | F24.FFN24_PERMUTE)
+    Y0 = ctx.ffn24_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    dX0, _, _ = ctx.ffn24_bwd(d["dY"])
+    torch.cuda.synchronize()
+    drop0 = _gpu_drop_fraction(ctx)
+    dX0 = dX0.clone()
+    ctx.set_token_permutation(perm)
+    Y = ctx.ffn24_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    dX, dW1, dW2 = ctx.ffn24_bwd(d["dY"])
+    torch.cuda.synchronize()
+    drop1 = _gpu_drop_fraction(ctx)
+    assert torch.equal(Y, Y0) and torch.equal(dX, dX0)
+    p = float(torch.count_nonzero(ctx.saved("Hc").view(torch.int16))) / (T * Fh)
+    iid = (4 * p ** 3 * (1 - p) + 2 * p ** 4) / (4 * p)
+    print(f"  feature-wise drop without / with permutation {drop0:.4f} / {drop1:.4f}  (i.i.d. closed form at density {p:.3f}: {iid:.4f})", flush=True)
+    assert drop0 > 3 * drop1 and abs(drop1 - iid) < 0.3 * iid
+    # sampled feature groups: picks bit-exact, dW2 rows within tolerance, all in permuted token order
+    gsel = np.sort(np.random.default_rng(50).choice(Fh // 4, 16, replace=False))
+    f4, f2 = _groups_to_cols(gsel)
+    f2_t = torch.from_numpy(f2).cuda(); f4_t = torch.from_numpy(f4).cuda()
+    meta_g = _meta_of_groups(ctx.saved("meta").cpu().numpy(), gsel)
+    H24_g = O.decompress24(words_of(ctx.saved("Hc")[:, f2_t]), meta_g)
+    Hct_ref, mt_ref = O.sparsify24(np.ascontiguousarray(H24_g.T))
+    assert np.array_equal(ctx.saved("meta_t")[f4_t].cpu().numpy(), mt_ref)
+    assert np.array_equal(words_of(ctx.saved("Hc_t")[f4_t]), Hct_ref)
+    perm_t = torch.from_numpy(perm.astype(np.int64)).cuda()
+    e2 = O.max_rel_err(f64(dW2[f4_t]), _mm24(O.bf16_bits_to_f32(Hct_ref), mt_ref, f64(d["dY"][perm_t])))
+    print(f"  dW2 on sampled features {e2:.2e}", flush=True)
+    assert e2 <= TOL_BF16
+    ctx.close()
