@@ -95,7 +95,8 @@ struct EpiRelu2 {
 //   column-level sparsity the first GEMM's epilogue can compute for free), accumulated with atomics; the caller
 //   zeroes it.  A lane counts its 4 tokens in 8-bit fields (4 features per register), the 32 lanes that hold the
 //   same 64 features add their fields up with a butterfly, and each lane then adds two features' totals.
-struct EpiPrune24 {
+template <bool STATS>
+struct EpiPrune24T {
   struct Args { __bf16* Hc; uint8_t* meta; __bf16* Hdbg; const float* b1; int F; uint32_t* nnz; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
     uint32_t cnt[16];
@@ -116,7 +117,7 @@ struct EpiPrune24 {
           float r0 = fmaxf(acc[mi][ni][2 * d] + b0, 0.f);
           float r1 = fmaxf(acc[mi][ni][2 * d + 1] + b1v, 0.f);
           hpk[d] = pack_bf16x2(r0 * r0, r1 * r1);
-          if (e.nnz) {
+          if constexpr (STATS) {
             // features 16 mi + 2 d and + 1 of the lane: fields (2 d) % 4 and (2 d + 1) % 4 of register 4 mi + d / 2
             uint32_t lo = min(hpk[d] & 0xFFFFu, 1u), hi = min(hpk[d] >> 16, 1u);
             cnt[4 * mi + (d >> 1)] += (lo << (16 * (d & 1))) + (hi << (16 * (d & 1) + 8));
@@ -148,7 +149,7 @@ struct EpiPrune24 {
         *reinterpret_cast<u32x4*>(hrow + 8 * q) = u32x4{vals[4 * q], vals[4 * q + 1], vals[4 * q + 2], vals[4 * q + 3]};
       *reinterpret_cast<u32x2*>(e.meta + piece * 8) = u32x2{nib[0], nib[1]};
     }
-    if (e.nnz) {
+    if constexpr (STATS) {
       // totals over the 32 lanes of this lane half (<= 128 per field); then lane r adds features r and r + 32
       int lane = threadIdx.x & 63;
 #pragma unroll
@@ -168,6 +169,7 @@ struct EpiPrune24 {
     }
   }
 };
+using EpiPrune24 = EpiPrune24T<false>;   // without the statistic (a compile-time switch: the plain kernel carries no trace of it)
 
 // C[map[m]][n], n contiguous: the rows of the result are scattered through a row map (the split weight-gradient
 // GEMMs work on a permutation of the hidden features and write each row back to its feature).
