@@ -7,8 +7,12 @@
  *
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers owned by the caller, row-major and contiguous, 16-byte aligned.
- *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue work on that
- *     stream; they never synchronise, and they allocate nothing (ffn24_ctx_create is the only allocating call).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue kernels and copies
+ *     on that stream (no memset nodes, so a sequence can be recorded into a HIP graph); they never synchronise and
+ *     allocate no device memory.  The exceptions are the set-up calls: ffn24_ctx_create allocates, and
+ *     ffn24_set_token_permutation waits for the device.
+ *   - A context belongs to the device that was current when it was created; calls that launch work with another
+ *     device current return FFN24_ERR_STATE.  A context is not thread-safe: one thread at a time per context.
  *   - Return value: FFN24_OK (0) or a negative FFN24_ERR_* code; ffn24_strerror() names it.  Bad arguments are
  *     rejected before anything is launched; nothing aborts or throws across this boundary.
  *   - Element type: bf16 (FFN24_BF16) with fp32 accumulation; or, forward only, fp8 (FFN24_FP8_E4M3, the OCP e4m3
@@ -44,7 +48,7 @@ extern "C" {
 #define FFN24_ERR_SHAPE (-2)  /* a size violates the divisibility rules stated at the call */
 #define FFN24_ERR_ALIGN (-3)  /* a pointer is not 16-byte aligned */
 #define FFN24_ERR_DTYPE (-4)  /* element type not supported */
-#define FFN24_ERR_STATE (-5)  /* call order: backward without the matching forward, missing context flag */
+#define FFN24_ERR_STATE (-5)  /* call order: backward without the matching forward, missing context flag, wrong current device */
 #define FFN24_ERR_HIP (-6)    /* the HIP runtime reported an error (allocation, launch) */
 
 typedef enum { FFN24_BF16 = 0, FFN24_FP8_E4M3 = 1 } ffn24_dtype;
@@ -137,8 +141,9 @@ FFN24_API int spmm24(const void* values, const uint8_t* meta, const void* Bt, in
  *   X [T][D], W1 [D][F], b1 [F] fp32 or NULL (the paper's FFN has no bias; b1 only dials the sparsity of synthetic
  *   inputs), W2 [F][D], Y [T][D].
  * Kernels: two weight transposes (every GEMM operand is consumed K-contiguous), the dense-MFMA up-projection with
- * the activation and the pruning fused into its epilogue (H is never written densely), the sparse-MFMA down-projection.  The context keeps (Hc, meta) and the X, W1, W2
- * pointers for ffn24_bwd; the caller keeps X, W1, W2 alive and unchanged until then. */
+ * the activation and the pruning fused into its epilogue (H is never written densely), the sparse-MFMA
+ * down-projection.  The context keeps (Hc, meta), its own copy of W2 and the X and W1 pointers for ffn24_bwd; the
+ * caller keeps X and W1 alive and unchanged until then. */
 FFN24_API int ffn24_fwd(ffn24_ctx* ctx, const void* X, const void* W1, const float* b1, const void* W2, void* Y, void* stream);
 
 /* Backward of the last ffn24_fwd on this context, masks held fixed (paper Fig. 4 and Sec. 2, backward paragraphs):
@@ -146,7 +151,8 @@ FFN24_API int ffn24_fwd(ffn24_ctx* ctx, const void* X, const void* W1, const flo
  *   dX  = dZ24 W1^T                                            sparse GEMM (token-wise mask)
  *   dW2 = (H24 * M_T)^T dY,   dW1 = X^T (dZ24 * M_T)           sparse GEMMs; M_T = feature-wise mask on top
  *   dY [T][D] -> dX [T][D], dW1 [D][F], dW2 [F][D].
- * Needs FFN24_TRAINING.  Returns FFN24_ERR_STATE if no ffn24_fwd preceded it. */
+ * Needs FFN24_TRAINING.  Returns FFN24_ERR_STATE unless the last forward on this context was an ffn24_fwd (ffn24_fwd
+ * and ffn_fwd share the context's weight workspace, so each invalidates what the other saved). */
 FFN24_API int ffn24_bwd(ffn24_ctx* ctx, const void* dY, void* dX, void* dW1, void* dW2, void* stream);
 
 /* Dense Squared-ReLU FFN on the same GEMM core (paper Sec. 1, "Squared ReLU"): the speed-up baseline.
@@ -154,7 +160,7 @@ FFN24_API int ffn24_bwd(ffn24_ctx* ctx, const void* dY, void* dX, void* dW1, voi
 FFN24_API int ffn_fwd(ffn24_ctx* ctx, const void* X, const void* W1, const float* b1, const void* W2, void* Y, void* stream);
 
 /* Backward of the last ffn_fwd: dZ = (dY W2^T) * 2 sqrt(H); dX = dZ W1^T; dW2 = H^T dY; dW1 = X^T dZ.
- * Needs FFN24_DENSE | FFN24_TRAINING. */
+ * Needs FFN24_DENSE | FFN24_TRAINING.  Returns FFN24_ERR_STATE unless the last forward on this context was an ffn_fwd. */
 FFN24_API int ffn_bwd(ffn24_ctx* ctx, const void* dY, void* dX, void* dW1, void* dW2, void* stream);
 
 /* Copies of the context's saved tensors, for parity checks.  `which`:

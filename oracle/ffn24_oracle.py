@@ -21,7 +21,7 @@ Training with 2:4 Activation Sparsity"):
   * the feature-wise picks are made on top of the forward's token-wise mask -- Sec. 2, last paragraph
   * forward order: activation, then sparsification, then FP8 quantisation -- Sec. 2, "We implemented 2 new kernels"
 
-Readings where the paper is silent (each is listed in the design notes of the repository):
+Readings where the paper is silent:
   * ties in magnitude go to the lower index; zeros take part like any value, so a group always
     yields exactly two kept slots with i0 < i1;
   * magnitude = the storage word with its sign bit cleared, compared as an unsigned integer;

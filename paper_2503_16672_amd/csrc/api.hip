@@ -19,8 +19,8 @@ struct ffn24_ctx {
   int device;
   int f8;                      // element type FFN24_FP8_E4M3 (forward only)
   float sx, sw1, sh, sw2;      // per-tensor scales of the fp8 path
-  // row-wise-scaled fp8 forward (FFN24_ROWWISE): caller's scale vectors, and the library's intermediate tensors
   int* perm; int perm_on;      // token permutation (FFN24_PERMUTE): device copy, and whether one is set
+  // row-wise-scaled fp8 forward (FFN24_ROWWISE): caller's scale vectors, and the library's intermediate tensors
   const float *rsx, *rsw1, *rsw2;
   void* Hc16; uint8_t* meta16; uint32_t* rowmax; float* rsh;
   // workspace (device)
@@ -30,8 +30,9 @@ struct ffn24_ctx {
   // split weight gradients (FFN24_SPLIT)
   uint32_t* nnz; int* row_of_feat; int* feat_of_row; void* Hdn_t; void* dZdn_t; void* dW1t;
   int n_dense;
-  // forward state
-  const void *X, *W1, *W2;
+  // forward state the backward calls read: the caller's X and W1 of the last forward, and which path ran it (the
+  // two paths share the weight workspace, so a forward of one invalidates the saved state of the other)
+  const void *X, *W1;
   int have_fwd24, have_fwd_dense;
   // profiling
   int profiling;
@@ -62,6 +63,13 @@ int free_all(ffn24_ctx* c) {
   return bad;
 }
 
+// the context's buffers live on the device that was current at ffn24_ctx_create
+int check_device(const ffn24_ctx* c) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return FFN24_ERR_HIP;
+  return dev == c->device ? FFN24_OK : FFN24_ERR_STATE;
+}
+
 int check_ptrs(std::initializer_list<const void*> ps) {
   for (const void* p : ps) if (!p) return FFN24_ERR_NULL;
   for (const void* p : ps) if (misaligned(p)) return FFN24_ERR_ALIGN;
@@ -79,7 +87,7 @@ const char* ffn24_strerror(int code) {
     case FFN24_ERR_SHAPE: return "a size violates the divisibility rules of the call";
     case FFN24_ERR_ALIGN: return "a pointer is not 16-byte aligned";
     case FFN24_ERR_DTYPE: return "element type not supported";
-    case FFN24_ERR_STATE: return "wrong call order or missing context flag";
+    case FFN24_ERR_STATE: return "wrong call order, missing context flag, or the context belongs to another device";
     case FFN24_ERR_HIP: return "HIP runtime error";
     default: return "unknown ffn24 error code";
   }
@@ -160,6 +168,7 @@ int ffn24_set_token_permutation(ffn24_ctx* c, const int32_t* perm_host) {
   if (!(c->flags & FFN24_PERMUTE)) return FFN24_ERR_STATE;
   c->have_fwd24 = 0;
   if (!perm_host) { c->perm_on = 0; return FFN24_OK; }
+  if (int rc = check_device(c)) return rc;
   // validated on the host: every index in range and used exactly once (the kernels gather and scatter rows with it)
   const int64_t T = c->T;
   uint8_t* seen = new (std::nothrow) uint8_t[(size_t)T]();
@@ -223,7 +232,9 @@ int ffn24_copy_saved(ffn24_ctx* c, int which, void* dst, int64_t dst_bytes, void
   if (!c || !dst) return FFN24_ERR_NULL;
   if (misaligned(dst)) return FFN24_ERR_ALIGN;
   int64_t need = 0;
-  int rc = ffn24_saved_bytes(c, which, &need);
+  int rc = check_device(c);
+  if (rc) return rc;
+  rc = ffn24_saved_bytes(c, which, &need);
   if (rc) return rc;
   if (dst_bytes != need) return FFN24_ERR_SHAPE;
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -286,19 +297,21 @@ int spmm24(const void* values, const uint8_t* meta, const void* Bt, int64_t M, i
 
 int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const void* W2, void* Y, void* stream) {
   if (!c) return FFN24_ERR_NULL;
-  int rc = check_ptrs({X, W1, W2, Y});
+  int rc = check_device(c);
+  if (rc) return rc;
+  rc = check_ptrs({X, W1, W2, Y});
   if (rc) return rc;
   if (b1 && misaligned(b1)) return FFN24_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
-  c->have_fwd24 = 0;
+  c->have_fwd24 = c->have_fwd_dense = 0;
   if (c->f8 && (c->flags & FFN24_ROWWISE)) {
     // row-wise scaling: up-projection (bf16 kept values + row maxima), row-wise quantisation, scaled sparse GEMM
     if (!c->rsx) return FFN24_ERR_STATE;
     { Timed t(c, K_TR_W, s);
       int rc1 = launch_transpose8(W1, D, F, c->W1t, 1, s);
       if (t.done(rc1 ? rc1 : launch_transpose8(W2, F, D, c->W2t, 0, s))) return FFN24_ERR_HIP; }
-    if (hipMemsetAsync(c->rowmax, 0, 4 * (size_t)T, s) != hipSuccess) return FFN24_ERR_HIP;
+    if (launch_zero32(c->rowmax, (size_t)T, s)) return FFN24_ERR_HIP;
     { Timed t(c, K_UP, s);
       if (t.done(launch_up_prune24_f8_rowwise(c->W1t, X, b1, T, D, F, c->rsx, c->rsw1, c->Hc16, c->meta16, c->Hdbg, c->rowmax, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_QUANT, s);
@@ -321,20 +334,22 @@ int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, cons
     int rc1 = launch_transpose(W1, D, F, c->W1t, 1, nullptr, nullptr, s);
     if (t.done(rc1 ? rc1 : launch_transpose(W2, F, D, c->W2t, 0, c->W2p, nullptr, s))) return FFN24_ERR_HIP; }
   uint32_t* nnz = (c->flags & FFN24_SPLIT) && c->n_dense > 0 ? c->nnz : nullptr;
-  if (nnz && hipMemsetAsync(nnz, 0, 4 * (size_t)F, s) != hipSuccess) return FFN24_ERR_HIP;
+  if (nnz && launch_zero32(nnz, (size_t)F, s)) return FFN24_ERR_HIP;
   const int* perm = c->perm_on ? c->perm : nullptr;   // position p inside the FFN holds token perm[p]
   { Timed t(c, K_UP, s);   if (t.done(launch_up_prune24(c->W1t, X, b1, T, D, F, c->Hc, c->meta, c->Hdbg, nnz, perm, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_DOWN, s);
     int rc1 = perm ? launch_sp_rowmajor_mapped(c->Hc, c->meta, 1, c->W2t, T, D, F, Y, perm, s) : launch_sp_rowmajor(c->Hc, c->meta, 1, c->W2t, T, D, F, Y, s);
     if (t.done(rc1)) return FFN24_ERR_HIP; }
-  c->X = X; c->W1 = W1; c->W2 = W2; c->have_fwd24 = 1;
+  c->X = X; c->W1 = W1; c->have_fwd24 = 1;
   return FFN24_OK;
 }
 
 int ffn24_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void* stream) {
   if (!c) return FFN24_ERR_NULL;
   if (!(c->flags & FFN24_TRAINING) || !c->have_fwd24) return FFN24_ERR_STATE;
-  int rc = check_ptrs({dY, dX, dW1, dW2});
+  int rc = check_device(c);
+  if (rc) return rc;
+  rc = check_ptrs({dY, dX, dW1, dW2});
   if (rc) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
@@ -372,12 +387,14 @@ int ffn24_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void
 int ffn_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const void* W2, void* Y, void* stream) {
   if (!c) return FFN24_ERR_NULL;
   if (!(c->flags & FFN24_DENSE) || (c->flags & FFN24_ROWWISE)) return FFN24_ERR_STATE;
-  int rc = check_ptrs({X, W1, W2, Y});
+  int rc = check_device(c);
+  if (rc) return rc;
+  rc = check_ptrs({X, W1, W2, Y});
   if (rc) return rc;
   if (b1 && misaligned(b1)) return FFN24_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
-  c->have_fwd_dense = 0;
+  c->have_fwd24 = c->have_fwd_dense = 0;
   if (c->f8) {
     { Timed t(c, K_TR_W, s);
       int rc1 = launch_transpose8(W1, D, F, c->W1t, 1, s);
@@ -393,14 +410,16 @@ int ffn_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const 
     if (t.done(rc1 ? rc1 : launch_transpose(W2, F, D, c->W2t, 0, c->W2p, nullptr, s))) return FFN24_ERR_HIP; }
   { Timed t(c, KD_UP, s);   if (t.done(launch_up_relu2(c->W1t, X, b1, T, D, F, c->Hd, c->Hd_t, s))) return FFN24_ERR_HIP; }
   { Timed t(c, KD_DOWN, s); if (t.done(launch_dense_rowmajor(c->Hd, 1, c->W2t, T, D, F, Y, s))) return FFN24_ERR_HIP; }
-  c->X = X; c->W1 = W1; c->W2 = W2; c->have_fwd_dense = 1;
+  c->X = X; c->W1 = W1; c->have_fwd_dense = 1;
   return FFN24_OK;
 }
 
 int ffn_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void* stream) {
   if (!c) return FFN24_ERR_NULL;
   if (!(c->flags & FFN24_DENSE) || !(c->flags & FFN24_TRAINING) || !c->have_fwd_dense) return FFN24_ERR_STATE;
-  int rc = check_ptrs({dY, dX, dW1, dW2});
+  int rc = check_device(c);
+  if (rc) return rc;
+  rc = check_ptrs({dY, dX, dW1, dW2});
   if (rc) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;

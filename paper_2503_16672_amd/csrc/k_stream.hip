@@ -260,16 +260,8 @@ __global__ void __launch_bounds__(1024) split_partition_kernel(const uint32_t* _
 }
 
 int launch_split_partition(const uint32_t* nnz, int F, int n_dense, int max_count, int* row_of_feat, int* feat_of_row, hipStream_t s) {
-  static bool configured[64] = {};
-  int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
-  if (e != hipSuccess) return (int)e;
-  if (dev < 0 || dev >= 64) return (int)hipErrorInvalidDevice;
-  if (!configured[dev]) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(split_partition_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * PART_LDS_FEATS);
-    if (e != hipSuccess) return (int)e;
-    configured[dev] = true;
-  }
+  static std::atomic<bool> configured[MAX_DEVICES] = {};
+  if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(split_partition_kernel), 4 * PART_LDS_FEATS, configured)) return rc;
   size_t lds = F <= PART_LDS_FEATS ? 4 * (size_t)F : 0;
   hipLaunchKernelGGL(split_partition_kernel, dim3(1), dim3(1024), lds, s, nnz, F, n_dense, (uint32_t)max_count, row_of_feat, feat_of_row);
   return (int)hipGetLastError();
@@ -288,6 +280,19 @@ __global__ void __launch_bounds__(256) unpanel_kernel(const u32x2* __restrict__ 
     int r = (int)(pc / npanels), kp = (int)(pc % npanels);
     dst[i] = src[a24_piece(r, kp, npanels) * W + w];
   }
+}
+
+// Clears n 32-bit words.  A kernel rather than a memset node, so that a caller may record the sequence into a HIP graph.
+__global__ void __launch_bounds__(256) zero32_kernel(uint32_t* p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = 0u;
+}
+
+int launch_zero32(uint32_t* p, size_t n, hipStream_t s) {
+  if (n == 0) return 0;
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 1024) blocks = 1024;
+  hipLaunchKernelGGL(zero32_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, n);
+  return (int)hipGetLastError();
 }
 
 int launch_unpanel(const void* src, int rows, int npanels, int piece_bytes, void* dst, hipStream_t s) {

@@ -2,8 +2,26 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 
 namespace ffn24 {
+
+// Opts a kernel in to `bytes` of dynamic LDS (more than 64 KiB needs it), once per device; `done` holds one flag per
+// device and belongs to the call site.  Threads that race here all make the same idempotent runtime call; the flag
+// only saves repeating it on later launches.
+constexpr int MAX_DEVICES = 64;
+inline int ensure_dynamic_lds(const void* kern, int bytes, std::atomic<bool> (&done)[MAX_DEVICES]) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return (int)e;
+  if (dev < 0 || dev >= MAX_DEVICES) return (int)hipErrorInvalidDevice;
+  if (!done[dev].load(std::memory_order_acquire)) {
+    e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return (int)e;
+    done[dev].store(true, std::memory_order_release);
+  }
+  return 0;
+}
 
 // All return a hipError_t cast to int (0 = success); shapes must already be validated by the caller:
 // M % 256 == 0, N % 256 == 0, K % 64 == 0, 16-byte aligned pointers.  Every GEMM operand is K-contiguous.
@@ -56,6 +74,8 @@ int launch_quantise_rows(const void* Hc16, const uint8_t* meta16, const uint32_t
 int launch_sp_rowmajor_f8_rowwise(const void* vals8, const uint8_t* meta, const void* B8, int M, int N, int K, const float* rs, const float* cs,
                                   void* C, hipStream_t s);
 // streaming kernels
+// p[0..n) = 0 (a kernel, not a memset node)
+int launch_zero32(uint32_t* p, size_t n, hipStream_t s);
 int launch_sparsify24(const void* H, int64_t rows, int64_t cols, void* vals, uint8_t* meta, hipStream_t s);
 // panel: inputs and outputs are in panel form (the library's own buffers) instead of row-major
 int launch_featurewise24(const void* Hc, const uint8_t* meta, const void* dZc, int T, int F,

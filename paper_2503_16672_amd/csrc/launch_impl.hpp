@@ -9,17 +9,8 @@ template <bool SPARSE, class Epi, bool F8 = false>
 static int launch_gemm(const GemmArgs& g, const typename Epi::Args& ea, hipStream_t s) {
   auto kern = gemm_kernel<SPARSE, Epi, F8>;
   constexpr int lds = Geo<SPARSE, F8>::LDS_TOTAL;
-  // the opt-in for more than 64 KiB of dynamic LDS is per device; keep one flag per device
-  static bool configured[64] = {};
-  int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
-  if (e != hipSuccess) return (int)e;
-  if (dev < 0 || dev >= 64) return (int)hipErrorInvalidDevice;
-  if (!configured[dev]) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return (int)e;
-    configured[dev] = true;
-  }
+  static std::atomic<bool> configured[MAX_DEVICES] = {};
+  if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds, configured)) return rc;
   int nblocks = (g.M / TILE_M) * (g.N / TILE_N);
   hipLaunchKernelGGL(kern, dim3(nblocks), dim3(GEMM_THREADS), lds, s, g, ea);
   return (int)hipGetLastError();
@@ -30,16 +21,8 @@ template <class Epi>
 static int launch_gemm_pair(const GemmArgs& gd, const typename Epi::Args& ead, const GemmArgs& gs, const typename Epi::Args& eas, hipStream_t s) {
   auto kern = gemm_pair_kernel<Epi>;
   constexpr int lds = Geo<true>::LDS_TOTAL > Geo<false>::LDS_TOTAL ? Geo<true>::LDS_TOTAL : Geo<false>::LDS_TOTAL;
-  static bool configured[64] = {};
-  int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
-  if (e != hipSuccess) return (int)e;
-  if (dev < 0 || dev >= 64) return (int)hipErrorInvalidDevice;
-  if (!configured[dev]) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return (int)e;
-    configured[dev] = true;
-  }
+  static std::atomic<bool> configured[MAX_DEVICES] = {};
+  if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds, configured)) return rc;
   int nd_tiles = (gd.M / TILE_M) * (gd.N / TILE_N), ns_tiles = (gs.M / TILE_M) * (gs.N / TILE_N);
   hipLaunchKernelGGL(kern, dim3(nd_tiles + ns_tiles), dim3(GEMM_THREADS), lds, s, gd, ead, nd_tiles, gs, eas);
   return (int)hipGetLastError();

@@ -92,6 +92,21 @@ def _ptr(t):
     return t.data_ptr()
 
 
+def _expect(t, shape, dtypes, name: str):
+    """The C ABI takes bare pointers, so shapes and element types are checked here, before anything is launched."""
+    if t is None:
+        return
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: shape {tuple(t.shape)}, expected {tuple(shape)}")
+    if t.dtype not in dtypes:
+        raise ValueError(f"{name}: dtype {t.dtype}, expected one of {dtypes}")
+
+
+_BF16 = (torch.bfloat16,)
+_BYTE = (torch.uint8, torch.float8_e4m3fn)
+_F32 = (torch.float32,)
+
+
 def _stream():
     return torch.cuda.current_stream().cuda_stream
 
@@ -99,6 +114,9 @@ def _stream():
 def sparsify24(H: torch.Tensor, values: torch.Tensor | None = None, meta: torch.Tensor | None = None):
     """H [rows, cols] bf16 -> (values [rows, cols/2] bf16, meta [rows, cols/8] uint8); outputs may be handed in."""
     rows, cols = H.shape
+    _expect(H, (rows, cols), _BF16, "H")
+    _expect(values, (rows, cols // 2), _BF16, "values")
+    _expect(meta, (rows, cols // 8), (torch.uint8,), "meta")
     values = torch.empty((rows, cols // 2), dtype=torch.bfloat16, device=H.device) if values is None else values
     meta = torch.empty((rows, cols // 8), dtype=torch.uint8, device=H.device) if meta is None else meta
     _check(lib().sparsify24(_ptr(H), rows, cols, FFN24_BF16, _ptr(values), _ptr(meta), _stream()), "sparsify24")
@@ -108,6 +126,9 @@ def sparsify24(H: torch.Tensor, values: torch.Tensor | None = None, meta: torch.
 def sparsify24_featurewise(Hc: torch.Tensor, meta: torch.Tensor, dZc: torch.Tensor | None = None):
     """Token-wise compressed (Hc [T,F/2], meta [T,F/8]) -> (Hc_t [F,T/2], meta_t [F,T/8], dZc_t [F,T/2] or None)."""
     T, F = Hc.shape[0], Hc.shape[1] * 2
+    _expect(Hc, (T, F // 2), _BF16, "Hc")
+    _expect(meta, (T, F // 8), (torch.uint8,), "meta")
+    _expect(dZc, (T, F // 2), _BF16, "dZc")
     Hc_t = torch.empty((F, T // 2), dtype=torch.bfloat16, device=Hc.device)
     meta_t = torch.empty((F, T // 8), dtype=torch.uint8, device=Hc.device)
     dZc_t = torch.empty((F, T // 2), dtype=torch.bfloat16, device=Hc.device) if dZc is not None else None
@@ -120,6 +141,9 @@ def spmm24(values: torch.Tensor, meta: torch.Tensor, Bt: torch.Tensor) -> torch.
     """C [M,N] = A24 . B with A24 given as (values [M,K/2], meta [M,K/8]) and B given transposed, Bt [N,K]."""
     M, K = values.shape[0], values.shape[1] * 2
     N = Bt.shape[0]
+    _expect(values, (M, K // 2), _BF16, "values")
+    _expect(meta, (M, K // 8), (torch.uint8,), "meta")
+    _expect(Bt, (N, K), _BF16, "Bt")
     C = torch.empty((M, N), dtype=torch.bfloat16, device=values.device)
     _check(lib().spmm24(_ptr(values), _ptr(meta), _ptr(Bt), M, N, K, _ptr(C), _stream()), "spmm24")
     return C
@@ -152,6 +176,9 @@ class Context:
 
     def set_row_scales(self, sx, sw1, sw2):
         """Row-wise scales of an FFN24_ROWWISE fp8 context: fp32 CUDA tensors [T], [F], [D]; the context keeps them alive."""
+        _expect(sx, (self.T,), _F32, "sx")
+        _expect(sw1, (self.F,), _F32, "sw1")
+        _expect(sw2, (self.D,), _F32, "sw2")
         self._row_scales = (sx, sw1, sw2)
         _check(lib().ffn24_set_row_scales(self._h, _ptr(sx), _ptr(sw1), _ptr(sw2)), "ffn24_set_row_scales")
 
@@ -170,13 +197,23 @@ class Context:
         """Keep the n_dense least sparse features out of the feature-wise 2:4 (see ffn24_set_split in the header)."""
         _check(lib().ffn24_set_split(self._h, n_dense), "ffn24_set_split")
 
+    def _check_fwd_args(self, X, W1, b1, W2, Y):
+        el = _BYTE if self.dtype == FFN24_FP8_E4M3 else _BF16
+        _expect(X, (self.T, self.D), el, "X")
+        _expect(W1, (self.D, self.F), el, "W1")
+        _expect(W2, (self.F, self.D), el, "W2")
+        _expect(b1, (self.F,), _F32, "b1")
+        _expect(Y, (self.T, self.D), _BF16, "Y")
+
     def ffn24_fwd(self, X, W1, b1, W2, Y=None):
         Y = torch.empty((self.T, self.D), dtype=torch.bfloat16, device=X.device) if Y is None else Y
+        self._check_fwd_args(X, W1, b1, W2, Y)
         _check(lib().ffn24_fwd(self._h, _ptr(X), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(Y), _stream()), "ffn24_fwd")
         return Y
 
     def ffn_fwd(self, X, W1, b1, W2, Y=None):
         Y = torch.empty((self.T, self.D), dtype=torch.bfloat16, device=X.device) if Y is None else Y
+        self._check_fwd_args(X, W1, b1, W2, Y)
         _check(lib().ffn_fwd(self._h, _ptr(X), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(Y), _stream()), "ffn_fwd")
         return Y
 
@@ -187,6 +224,10 @@ class Context:
                    torch.empty((self.D, self.F), dtype=torch.bfloat16, device=dev),
                    torch.empty((self.F, self.D), dtype=torch.bfloat16, device=dev))
         dX, dW1, dW2 = out
+        _expect(dY, (self.T, self.D), _BF16, "dY")
+        _expect(dX, (self.T, self.D), _BF16, "dX")
+        _expect(dW1, (self.D, self.F), _BF16, "dW1")
+        _expect(dW2, (self.F, self.D), _BF16, "dW2")
         _check(fn(self._h, _ptr(dY), _ptr(dX), _ptr(dW1), _ptr(dW2), _stream()), name)
         return dX, dW1, dW2
 

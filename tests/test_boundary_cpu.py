@@ -68,3 +68,18 @@ def test_argument_validation_without_gpu():
     assert h.value is None
     assert L.ffn24_fwd(None, a16, a16, None, a16, a16, None) == -1
     assert L.ffn24_ctx_destroy(None) == 0
+
+
+def test_binding_checks_shapes_and_dtypes_before_the_call():
+    """The binding rejects tensors whose shape or element type does not match the call (the C ABI sees only pointers)."""
+    import torch
+    from paper_2503_16672_amd import ffn24
+    ok = torch.zeros((4, 16), dtype=torch.bfloat16)
+    ffn24._expect(ok, (4, 16), ffn24._BF16, "H")
+    ffn24._expect(None, (4, 16), ffn24._BF16, "optional")
+    with pytest.raises(ValueError, match="shape"):
+        ffn24._expect(ok, (4, 8), ffn24._BF16, "H")
+    with pytest.raises(ValueError, match="dtype"):
+        ffn24._expect(ok.float(), (4, 16), ffn24._BF16, "H")
+    with pytest.raises(ValueError, match="CUDA"):
+        ffn24.sparsify24(ok)                       # right shape and type, but host memory

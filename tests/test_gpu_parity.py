@@ -344,6 +344,35 @@ def test_ffn_dense_fwd_bwd_c1(F24):
     ctx.close()
 
 
+def test_forward_of_one_path_invalidates_the_other(F24):
+    """ffn24_fwd and ffn_fwd share the context's weight workspace: after a forward of one path the backward of the
+    other is refused, and the matching backward still gives the oracle's gradients."""
+    print("2:4 / dense forwards on one context", flush=True)
+    inpA = synth.make_inputs(256, 256, 1024, sparsity=0.9, seed=11, with_dy=True)
+    inpB = synth.make_inputs(256, 256, 1024, sparsity=0.8, seed=12, with_dy=True)
+    dA, dB = _upload(inpA), _upload(inpB)
+    ctx = F24.Context(256, 256, 1024, F24.FFN24_TRAINING | F24.FFN24_DENSE)
+    ctx.ffn24_fwd(dA["X"], dA["W1"], dA["b1"], dA["W2"])
+    ctx.ffn_fwd(dB["X"], dB["W1"], dB["b1"], dB["W2"])
+    with pytest.raises(F24.Ffn24Error) as e:
+        ctx.ffn24_bwd(dA["dY"])
+    assert e.value.code == -5
+    gd = ctx.ffn_bwd(dB["dY"])
+    ctx.ffn24_fwd(dA["X"], dA["W1"], dA["b1"], dA["W2"])
+    with pytest.raises(F24.Ffn24Error) as e:
+        ctx.ffn_bwd(dB["dY"])
+    assert e.value.code == -5
+    g24 = ctx.ffn24_bwd(dA["dY"])
+    torch.cuda.synchronize()
+    rA = O.ffn24_bwd(O.ffn24_fwd(inpA["X"], inpA["W1"], inpA["b1"], inpA["W2"]), inpA["dY"])
+    rB = O.ffn_bwd(O.ffn_fwd(inpB["X"], inpB["W1"], inpB["b1"], inpB["W2"]), inpB["dY"])
+    e24 = [O.max_rel_err(f64(a), rA[k]) for a, k in zip(g24, ("dX", "dW1", "dW2"))]
+    ed = [O.max_rel_err(f64(a), rB[k]) for a, k in zip(gd, ("dX", "dW1", "dW2"))]
+    print("  2:4 grads err", e24, " dense grads err", ed, flush=True)
+    assert max(e24) <= TOL_BF16 and max(ed) <= TOL_BF16
+    ctx.close()
+
+
 def test_multi_tile_shapes(F24):
     """Several block tiles in every GEMM dimension and K stages that are not a power of two."""
     print("multi-tile fwd+bwd T=768 D=768 F=1280", flush=True)
