@@ -437,6 +437,35 @@ def featurewise_drop_fraction(H24, M_T) -> float:
     return float((nz & ~np.asarray(M_T, dtype=bool)).sum() / max(1, nz.sum()))
 
 
+def sparsity_counts(Hq, H24=None, M_T=None, dense_features=None) -> dict:
+    """The counts behind the paper's sparsity figures (Sec. 1, the sparsity-level figure; Sec. 2, first paragraph: the share
+    of non-zero values that 2:4 drops), for one FFN call:
+      elements        T F
+      nonzero         non-zero entries of the stored activation H
+      kept_tokenwise  of those, the entries that survive the token-wise 2:4 (None for a dense forward)
+      kept_featurewise  of those, the entries the weight-gradient GEMMs still see: the feature-wise 2:4 on top, except
+                        on `dense_features` (Sec. 2, "Optimization 1"), which keep the token-wise set (None without M_T)
+    """
+    Hq = np.asarray(Hq)
+    out = {"elements": int(Hq.size), "nonzero": int(np.count_nonzero(Hq)), "kept_tokenwise": None, "kept_featurewise": None}
+    if H24 is not None:
+        H24 = np.asarray(H24)
+        out["kept_tokenwise"] = int(np.count_nonzero(H24))
+        if M_T is not None:
+            Mw = np.asarray(M_T, dtype=bool)
+            if dense_features is not None:
+                Mw = Mw | np.asarray(dense_features, dtype=bool)[None, :]
+            out["kept_featurewise"] = int(np.count_nonzero(np.where(Mw, H24, H24.dtype.type(0))))
+    return out
+
+
+def use_sparse_path(counts: dict, min_sparsity: float) -> bool:
+    """The dense <-> 2:4 switch behind the paper's dense warm-up (Sec. 2, last paragraph: training starts dense because
+    the activation is only about half zeros at initialisation, and 2:4 is switched on once it is sparse enough): run
+    the 2:4 path iff the measured share of zeros, 1 - nonzero / elements, has reached min_sparsity."""
+    return (1.0 - counts["nonzero"] / counts["elements"]) >= min_sparsity
+
+
 def ffn_bwd(fwd: dict, dY, st=Bf16):
     """Textbook backward of the dense FFN: dZ = (dY W2^T) * 2 max(0, Z); dX = dZ W1^T; dW2 = H^T dY; dW1 = X^T dZ.
     Needs of `fwd` only Hq, Xq, W1q, W2q."""

@@ -541,3 +541,59 @@ def test_token_permutation_undoes_the_damage_of_correlated_tokens():
     iid = (4 * p ** 3 * (1 - p) + 2 * p ** 4) / (4 * p)
     assert drop_corr > 5 * drop_perm
     assert abs(drop_perm - iid) < 0.5 * iid
+
+
+# ----------------------------------------------------------------------------- sparsity counts and the dense <-> 2:4 switch
+def test_sparsity_counts_worked_example():
+    """An activation small enough to count by hand: 8 tokens x 8 features, the last 4 tokens all zero."""
+    H = np.array([[1, 2, 3, 0,  0, 0, 0, 5],      # group 0 has 3 non-zeros: the 1 is dropped
+                  [0, 0, 0, 0,  1, 1, 1, 1],      # group 1 has 4: two are dropped
+                  [4, 0, 0, 0,  0, 2, 0, 0],
+                  [6, 0, 0, 7,  0, 3, 0, 0]], np.float32)
+    H = np.concatenate([H, np.zeros((4, 8), np.float32)])
+    words = O.f32_to_bf16_bits(H)
+    v, m = O.sparsify24(words)
+    H24 = O.bf16_bits_to_f32(O.decompress24(v, m))
+    _, _, M_T = O.featurewise24(H24)
+    c = O.sparsity_counts(H, H24, M_T)
+    assert c["elements"] == 64 and c["nonzero"] == 13
+    assert c["kept_tokenwise"] == 10                      # 13 - 1 - 2
+    # columns of H24 (first group of 4 tokens of each): col0 = (0,0,4,6), col1 = (2,0,0,0), col2 = (3,0,0,0), col3 = (0,0,0,7),
+    # col4 = (0,1,0,0), col5 = (0,1,2,3) -> the 1 goes, col6 = 0, col7 = (5,0,0,0): one more value dropped
+    assert c["kept_featurewise"] == 9
+    # a dense feature keeps its token-wise set
+    dense = np.zeros(8, bool); dense[5] = True
+    assert O.sparsity_counts(H, H24, M_T, dense)["kept_featurewise"] == 10
+    d = O.sparsity_counts(H)
+    assert d["nonzero"] == 13 and d["kept_tokenwise"] is None and d["kept_featurewise"] is None
+
+
+def test_sparsity_counts_equal_min_two_per_group():
+    """Top-2 by magnitude keeps non-zeros before zeros, so a group keeps min(#non-zeros, 2) of them: an independent
+    count, along the features for the token-wise pass and along the tokens (of the pruned tensor) for the second."""
+    inp = synth.make_inputs(256, 64, 512, 0.8, seed=77)
+    f = O.ffn24_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"])
+    _, _, M_T = O.featurewise24(f["H24"])
+    c = O.sparsity_counts(f["Hq"], f["H24"], M_T)
+    nz = np.asarray(f["Hq"]) != 0
+    tok = np.minimum(nz.reshape(256, 128, 4).sum(-1), 2)
+    assert c["nonzero"] == int(nz.sum()) and c["kept_tokenwise"] == int(tok.sum())
+    nz24 = np.asarray(f["H24"]) != 0
+    feat = np.minimum(nz24.T.reshape(512, 64, 4).sum(-1), 2)
+    assert c["kept_featurewise"] == int(feat.sum())
+    assert c["kept_featurewise"] <= c["kept_tokenwise"] <= c["nonzero"] <= c["elements"]
+    # the dropped share matches the closed form for an i.i.d. support of the measured density
+    p = c["nonzero"] / c["elements"]
+    iid = (4 * p ** 3 * (1 - p) + 2 * p ** 4) / (4 * p)
+    assert abs((1 - c["kept_tokenwise"] / c["nonzero"]) - iid) < 0.15 * iid
+
+
+def test_use_sparse_path_follows_the_warm_up_story():
+    """Sec. 2, last paragraph: about half zeros at initialisation (stay dense), 90 % and more after a short while."""
+    at_init = synth.make_inputs(256, 128, 512, 0.5, seed=3)
+    later = synth.make_inputs(256, 128, 512, 0.92, seed=3)
+    c0 = O.sparsity_counts(O.ffn_fwd(at_init["X"], at_init["W1"], at_init["b1"], at_init["W2"])["Hq"])
+    c1 = O.sparsity_counts(O.ffn_fwd(later["X"], later["W1"], later["b1"], later["W2"])["Hq"])
+    assert not O.use_sparse_path(c0, 0.85) and O.use_sparse_path(c1, 0.85)
+    assert O.use_sparse_path({"elements": 100, "nonzero": 10}, 0.9)          # exactly at the threshold counts as reached
+    assert not O.use_sparse_path({"elements": 100, "nonzero": 11}, 0.9)
