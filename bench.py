@@ -153,6 +153,7 @@ def main() -> int:
                     "feature-wise 2:4: split weight-gradient GEMMs (bf16 fwd+bwd workloads)")
     ap.add_argument("--rowwise", action="store_true", help="fp8 workload with row-wise instead of per-tensor scales (no dense baseline in this mode)")
     ap.add_argument("--permute", action="store_true", help="run the bf16 workload with a fixed token permutation around the FFN")
+    ap.add_argument("--telemetry", action="store_true", help="bf16 workloads: count sparsity and 2:4 drops while running (reported under \"telemetry\")")
     ap.add_argument("--split-sweep", action="store_true", help="time the weight-gradient stage over a range of split sizes")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy before the steps (the known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE)")
@@ -189,7 +190,7 @@ def main() -> int:
         inp = synth.make_workload(args.workload, with_dy=True)
         dev = {k: torch.from_numpy(inp[k]).to(torch.bfloat16).cuda() for k in ("X", "W1", "W2", "dY")}
         ctx = ffn24.Context(T, D, F, (ffn24.FFN24_TRAINING if bwd else 0) | ffn24.FFN24_DENSE | (ffn24.FFN24_SPLIT if args.split and bwd else 0)
-                            | (ffn24.FFN24_PERMUTE if args.permute else 0))
+                            | (ffn24.FFN24_PERMUTE if args.permute else 0) | (ffn24.FFN24_TELEMETRY if args.telemetry else 0))
         if args.split and bwd:
             ctx.set_split(args.split)
         if args.permute:
@@ -245,6 +246,13 @@ def main() -> int:
         for k in kd:
             acc[k] += ctx.kernel_ms(k)
     ctx.set_profiling(False)
+    telemetry = None
+    if args.telemetry and not fp8:
+        step24()
+        t = ctx.telemetry()
+        telemetry = {"zeros": round(1 - t["nonzero"] / t["elements"], 5), "dropped_tokenwise": round(1 - t["kept_tokenwise"] / t["nonzero"], 6),
+                     "dropped_featurewise_on_top": round(1 - t["kept_featurewise"] / t["kept_tokenwise"], 6) if t["kept_featurewise"] else None,
+                     "use_sparse_at_0.85": ctx.policy_use_sparse(0.85), "counts": t}
     kernel_ms = {ffn24.KERNEL_NAMES[k]: acc[k] / args.steps for k in acc}
 
     # standalone 2:4 compression of a dense [T, F] activation with the workload's sparsity (HBM-bound streaming kernel;
@@ -332,6 +340,8 @@ def main() -> int:
         "speedup_vs_dense_ffn": None if rowwise else round(sec_dense / sec24, 4),
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "sparsify24_standalone": sparsify,
     }
+    if telemetry:
+        out["telemetry"] = telemetry
     ctx.close()
     print(json.dumps(out))
     return 0

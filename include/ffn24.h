@@ -50,6 +50,7 @@ extern "C" {
 #define FFN24_ERR_DTYPE (-4)  /* element type not supported */
 #define FFN24_ERR_STATE (-5)  /* call order: backward without the matching forward, missing context flag, wrong current device */
 #define FFN24_ERR_HIP (-6)    /* the HIP runtime reported an error (allocation, launch) */
+#define FFN24_ERR_NOTREADY (-7) /* ffn24_get_telemetry without waiting: no snapshot has completed yet */
 
 typedef enum { FFN24_BF16 = 0, FFN24_FP8_E4M3 = 1 } ffn24_dtype;
 
@@ -60,6 +61,7 @@ typedef enum { FFN24_BF16 = 0, FFN24_FP8_E4M3 = 1 } ffn24_dtype;
 #define FFN24_SPLIT 8        /* allocate what the split weight-gradient GEMMs need (with FFN24_TRAINING; see ffn24_set_split) */
 #define FFN24_ROWWISE 16     /* fp8 context with row-wise instead of per-tensor scales (see ffn24_set_row_scales) */
 #define FFN24_PERMUTE 32     /* bf16 context that can run with a token permutation (see ffn24_set_token_permutation) */
+#define FFN24_TELEMETRY 64   /* bf16 context whose forwards and backwards count sparsity and drops (see ffn24_get_telemetry) */
 
 typedef struct ffn24_ctx ffn24_ctx; /* opaque; owns only its device workspace */
 
@@ -162,6 +164,26 @@ FFN24_API int ffn_fwd(ffn24_ctx* ctx, const void* X, const void* W1, const float
 /* Backward of the last ffn_fwd: dZ = (dY W2^T) * 2 sqrt(H); dX = dZ W1^T; dW2 = H^T dY; dW1 = X^T dZ.
  * Needs FFN24_DENSE | FFN24_TRAINING.  Returns FFN24_ERR_STATE unless the last forward on this context was an ffn_fwd. */
 FFN24_API int ffn_bwd(ffn24_ctx* ctx, const void* dY, void* dX, void* dW1, void* dW2, void* stream);
+
+/* Sparsity telemetry of a context created with FFN24_TELEMETRY (bf16 only; paper Sec. 1: the sparsity level of the
+ * activation over training, Sec. 2: the share of non-zero values that 2:4 drops).  The up-projection epilogues of
+ * ffn24_fwd and ffn_fwd and the feature-wise re-compression of ffn24_bwd count while they work; each of these three
+ * calls ends by enqueuing a snapshot (a 40-byte copy to pinned host memory plus an event record, so such calls
+ * cannot be recorded into a HIP graph).  counts[0..4]:
+ *   0  T F                                                 1  non-zero stored activations before pruning
+ *   2  of those, kept by the token-wise 2:4                 3  of those, still seen by the weight-gradient GEMMs
+ *   4  1 if the snapshot comes from the 2:4 path, 0 from ffn_fwd (then 2 and 3 are 0)
+ * Entry 3 is 0 in the snapshot of a forward and filled in by the backward's.  With FFN24_SPLIT the dense features
+ * count in full in entry 3.  wait != 0: blocks until the newest snapshot has landed.  wait == 0: never blocks; returns
+ * the newest snapshot that has landed, or FFN24_ERR_NOTREADY if none has. */
+FFN24_API int ffn24_get_telemetry(ffn24_ctx* ctx, int64_t* counts, int wait);
+
+/* The dense <-> 2:4 switch behind the paper's dense warm-up (Sec. 2, last paragraph: the activation is only about
+ * half zeros at initialisation and reaches 90 % and more after a short while).  *use_sparse = 1 iff the newest landed
+ * snapshot shows a share of zeros, 1 - counts[1] / counts[0], of at least min_sparsity (0..1); 0 while nothing has
+ * been measured.  Never blocks: the decision for a step rests on an earlier step's measurement.  The caller then
+ * runs ffn24_fwd / ffn24_bwd or ffn_fwd / ffn_bwd (a context with FFN24_DENSE | FFN24_TRAINING has both). */
+FFN24_API int ffn24_policy_use_sparse(ffn24_ctx* ctx, double min_sparsity, int* use_sparse);
 
 /* Copies of the context's saved tensors, for parity checks.  `which`:
  *   0 Hc [T][F/2]   1 meta [T][F/8]   2 dZc [T][F/2]   3 Hc_t [F][T/2]   4 meta_t [F][T/8]   5 dZc_t [F][T/2]

@@ -30,6 +30,12 @@ struct ffn24_ctx {
   // split weight gradients (FFN24_SPLIT)
   uint32_t* nnz; int* row_of_feat; int* feat_of_row; void* Hdn_t; void* dZdn_t; void* dW1t;
   int n_dense;
+  // telemetry (FFN24_TELEMETRY): device slots the kernels add to, their sums, and two pinned host snapshots that the
+  // forward and the backward fill in turn (an event each tells when a snapshot has landed)
+  unsigned long long* tele; long long* tele_sum; long long* tele_host;
+  hipEvent_t tele_ev[2];
+  int tele_seq;                 // snapshots enqueued so far
+  long long tele_last[5]; int tele_have;   // the newest snapshot that was seen complete
   // forward state the backward calls read: the caller's X and W1 of the last forward, and which path ran it (the
   // two paths share the weight workspace, so a forward of one invalidates the saved state of the other)
   const void *X, *W1;
@@ -59,6 +65,10 @@ int free_all(ffn24_ctx* c) {
                   c->W1t, c->W2t, c->Xt, c->dYt, c->Hd_t, c->dZd_t, c->W2p,
                   c->nnz, c->row_of_feat, c->feat_of_row, c->Hdn_t, c->dZdn_t, c->dW1t, c->Hc16, c->meta16, c->rowmax, c->rsh, c->perm};
   for (void* b : bufs) if (b && hipFree(b) != hipSuccess) bad = 1;
+  if (c->tele && hipFree(c->tele) != hipSuccess) bad = 1;
+  if (c->tele_sum && hipFree(c->tele_sum) != hipSuccess) bad = 1;
+  if (c->tele_host && hipHostFree(c->tele_host) != hipSuccess) bad = 1;
+  for (int j = 0; j < 2; j++) if (c->tele_ev[j]) (void)hipEventDestroy(c->tele_ev[j]);
   for (int k = 0; k < NUM_KERNELS; k++) for (int j = 0; j < 2; j++) if (c->ev[k][j]) (void)hipEventDestroy(c->ev[k][j]);
   return bad;
 }
@@ -68,6 +78,16 @@ int check_device(const ffn24_ctx* c) {
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess) return FFN24_ERR_HIP;
   return dev == c->device ? FFN24_OK : FFN24_ERR_STATE;
+}
+
+// Telemetry snapshot: sum the slots, copy the five numbers to the next pinned host slot, mark it with an event.
+int tele_snapshot(ffn24_ctx* c, long long path, hipStream_t s) {
+  if (launch_tele_sum(c->tele, (long long)c->T * (long long)c->F, path, c->tele_sum, s)) return FFN24_ERR_HIP;
+  const int slot = c->tele_seq & 1;
+  if (hipMemcpyAsync(c->tele_host + 5 * slot, c->tele_sum, 8 * 5, hipMemcpyDeviceToHost, s) != hipSuccess) return FFN24_ERR_HIP;
+  if (hipEventRecord(c->tele_ev[slot], s) != hipSuccess) return FFN24_ERR_HIP;
+  c->tele_seq++;
+  return FFN24_OK;
 }
 
 int check_ptrs(std::initializer_list<const void*> ps) {
@@ -89,6 +109,7 @@ const char* ffn24_strerror(int code) {
     case FFN24_ERR_DTYPE: return "element type not supported";
     case FFN24_ERR_STATE: return "wrong call order, missing context flag, or the context belongs to another device";
     case FFN24_ERR_HIP: return "HIP runtime error";
+    case FFN24_ERR_NOTREADY: return "no telemetry snapshot has completed yet";
     default: return "unknown ffn24 error code";
   }
 }
@@ -101,6 +122,7 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
   if ((flags & FFN24_SPLIT) && !(flags & FFN24_TRAINING)) return FFN24_ERR_STATE;
   if ((flags & FFN24_ROWWISE) && !f8) return FFN24_ERR_DTYPE;
   if ((flags & FFN24_PERMUTE) && f8) return FFN24_ERR_DTYPE;
+  if ((flags & FFN24_TELEMETRY) && f8) return FFN24_ERR_DTYPE;
   // the DMA gathers permuted rows with 32-bit byte offsets from the tensor base
   if ((flags & FFN24_PERMUTE) && (uint64_t)T * (uint64_t)D * 2u >= (1ull << 32)) return FFN24_ERR_SHAPE;
   if (T <= 0 || D <= 0 || F <= 0 || T % 256 || D % 256 || F % 256) return FFN24_ERR_SHAPE;
@@ -118,6 +140,12 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
     ok = hipMalloc(&c->dZc, tf) == hipSuccess && hipMalloc(&c->Hc_t, tf) == hipSuccess &&
          hipMalloc(reinterpret_cast<void**>(&c->meta_t), tf / 8) == hipSuccess && hipMalloc(&c->dZc_t, tf) == hipSuccess &&
          hipMalloc(&c->Xt, 2 * td) == hipSuccess && hipMalloc(&c->dYt, 2 * td) == hipSuccess && hipMalloc(&c->W2p, 2 * df) == hipSuccess;
+  if (ok && (flags & FFN24_TELEMETRY)) {
+    ok = hipMalloc(reinterpret_cast<void**>(&c->tele), 8 * TELE_WORDS) == hipSuccess &&
+         hipMalloc(reinterpret_cast<void**>(&c->tele_sum), 8 * 5) == hipSuccess &&
+         hipHostMalloc(reinterpret_cast<void**>(&c->tele_host), 8 * 5 * 2, hipHostMallocDefault) == hipSuccess;
+    for (int j = 0; ok && j < 2; j++) ok = hipEventCreateWithFlags(&c->tele_ev[j], hipEventDisableTiming) == hipSuccess;
+  }
   if (ok && (flags & FFN24_SPLIT))
     ok = hipMalloc(reinterpret_cast<void**>(&c->nnz), 4 * (size_t)F) == hipSuccess &&
          hipMalloc(reinterpret_cast<void**>(&c->row_of_feat), 4 * (size_t)F) == hipSuccess &&
@@ -194,6 +222,37 @@ int ffn24_set_split(ffn24_ctx* c, int64_t n_dense) {
   if (n_dense < 0 || n_dense % 256 || n_dense > c->F / 4) return FFN24_ERR_SHAPE;
   c->n_dense = (int)n_dense;
   c->have_fwd24 = 0;   // the statistics of an earlier forward do not belong to this setting
+  return FFN24_OK;
+}
+
+int ffn24_get_telemetry(ffn24_ctx* c, int64_t* counts, int wait) {
+  if (!c || !counts) return FFN24_ERR_NULL;
+  if (!(c->flags & FFN24_TELEMETRY)) return FFN24_ERR_STATE;
+  // newest snapshot first, then the one before it (its host slot is not written again before a further call enqueues)
+  for (int back = 1; back <= 2 && back <= c->tele_seq; back++) {
+    const int slot = (c->tele_seq - back) & 1;
+    hipError_t e = (wait && back == 1) ? hipEventSynchronize(c->tele_ev[slot]) : hipEventQuery(c->tele_ev[slot]);
+    if (e == hipSuccess) {
+      for (int i = 0; i < 5; i++) c->tele_last[i] = c->tele_host[5 * slot + i];
+      c->tele_have = 1;
+      break;
+    }
+    if (e != hipErrorNotReady) { (void)hipGetLastError(); return FFN24_ERR_HIP; }
+  }
+  (void)hipGetLastError();   // a pending event leaves hipErrorNotReady behind
+  if (!c->tele_have) return FFN24_ERR_NOTREADY;
+  for (int i = 0; i < 5; i++) counts[i] = (int64_t)c->tele_last[i];
+  return FFN24_OK;
+}
+
+int ffn24_policy_use_sparse(ffn24_ctx* c, double min_sparsity, int* use_sparse) {
+  if (!c || !use_sparse) return FFN24_ERR_NULL;
+  if (!(min_sparsity >= 0.0 && min_sparsity <= 1.0)) return FFN24_ERR_SHAPE;
+  int64_t n[5];
+  int rc = ffn24_get_telemetry(c, n, 0);
+  if (rc == FFN24_ERR_NOTREADY) { *use_sparse = 0; return FFN24_OK; }   // nothing measured yet: stay dense
+  if (rc) return rc;
+  *use_sparse = (1.0 - (double)n[1] / (double)n[0]) >= min_sparsity;
   return FFN24_OK;
 }
 
@@ -285,7 +344,7 @@ int sparsify24_featurewise(const void* Hc, const uint8_t* meta, const void* dZc,
   if ((dZc == nullptr) != (dZc_t == nullptr)) return FFN24_ERR_NULL;
   if (misaligned(Hc) || misaligned(meta) || misaligned(Hc_t) || misaligned(meta_t) || misaligned(dZc) || misaligned(dZc_t))
     return FFN24_ERR_ALIGN;
-  return launch_featurewise24(Hc, meta, dZc, (int)T, (int)F, Hc_t, meta_t, dZc_t, 0, static_cast<hipStream_t>(stream)) ? FFN24_ERR_HIP : FFN24_OK;
+  return launch_featurewise24(Hc, meta, dZc, (int)T, (int)F, Hc_t, meta_t, dZc_t, 0, nullptr, static_cast<hipStream_t>(stream)) ? FFN24_ERR_HIP : FFN24_OK;
 }
 
 int spmm24(const void* values, const uint8_t* meta, const void* Bt, int64_t M, int64_t N, int64_t K, void* C, void* stream) {
@@ -335,11 +394,13 @@ int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, cons
     if (t.done(rc1 ? rc1 : launch_transpose(W2, F, D, c->W2t, 0, c->W2p, nullptr, s))) return FFN24_ERR_HIP; }
   uint32_t* nnz = (c->flags & FFN24_SPLIT) && c->n_dense > 0 ? c->nnz : nullptr;
   if (nnz && launch_zero32(nnz, (size_t)F, s)) return FFN24_ERR_HIP;
+  if (c->tele && launch_zero32(reinterpret_cast<uint32_t*>(c->tele), 2 * TELE_WORDS, s)) return FFN24_ERR_HIP;
   const int* perm = c->perm_on ? c->perm : nullptr;   // position p inside the FFN holds token perm[p]
-  { Timed t(c, K_UP, s);   if (t.done(launch_up_prune24(c->W1t, X, b1, T, D, F, c->Hc, c->meta, c->Hdbg, nnz, perm, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_UP, s);   if (t.done(launch_up_prune24(c->W1t, X, b1, T, D, F, c->Hc, c->meta, c->Hdbg, nnz, c->tele, perm, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_DOWN, s);
     int rc1 = perm ? launch_sp_rowmajor_mapped(c->Hc, c->meta, 1, c->W2t, T, D, F, Y, perm, s) : launch_sp_rowmajor(c->Hc, c->meta, 1, c->W2t, T, D, F, Y, s);
     if (t.done(rc1)) return FFN24_ERR_HIP; }
+  if (c->tele && (rc = tele_snapshot(c, 1, s))) return rc;
   c->X = X; c->W1 = W1; c->have_fwd24 = 1;
   return FFN24_OK;
 }
@@ -354,6 +415,8 @@ int ffn24_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   const int* perm = c->perm_on ? c->perm : nullptr;   // position p inside the FFN holds token perm[p]
+  // the forward's two counts stay; the feature-wise one belongs to this backward
+  if (c->tele && launch_zero32(reinterpret_cast<uint32_t*>(c->tele + tele_index(TELE_KEPT_FEAT, 0)), 2 * TELE_SLOTS * TELE_STRIDE, s)) return FFN24_ERR_HIP;
   { Timed t(c, K_DH, s);  if (t.done(launch_dh_gather(c->W2p, dY, c->Hc, c->meta, T, D, F, c->dZc, perm, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_DX, s);
     int rc1 = perm ? launch_sp_rowmajor_mapped(c->dZc, c->meta, 1, c->W1, T, D, F, dX, perm, s) : launch_sp_rowmajor(c->dZc, c->meta, 1, c->W1, T, D, F, dX, s);
@@ -365,8 +428,9 @@ int ffn24_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void
     const int nd = c->n_dense, ns = F - nd;
     { Timed t(c, K_PART, s); if (t.done(launch_split_partition(c->nnz, F, nd, T, c->row_of_feat, c->feat_of_row, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_FW, s);
-      if (t.done(launch_featurewise24_split(c->Hc, c->meta, c->dZc, T, F, c->row_of_feat, ns, c->Hc_t, c->meta_t, c->dZc_t, c->Hdn_t, c->dZdn_t, s)))
+      if (t.done(launch_featurewise24_split(c->Hc, c->meta, c->dZc, T, F, c->row_of_feat, ns, c->Hc_t, c->meta_t, c->dZc_t, c->Hdn_t, c->dZdn_t, c->tele, s)))
         return FFN24_ERR_HIP; }
+    if (c->tele && (rc = tele_snapshot(c, 1, s))) return rc;
     { Timed t(c, K_TR_ACT, s);
       int rc1 = launch_transpose(dY, T, D, c->dYt, 0, nullptr, perm, s);
       if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, 0, nullptr, perm, s))) return FFN24_ERR_HIP; }
@@ -375,7 +439,8 @@ int ffn24_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void
     { Timed t(c, K_TR_DW1, s); if (t.done(launch_transpose(c->dW1t, F, D, dW1, 0, nullptr, nullptr, s))) return FFN24_ERR_HIP; }
     return FFN24_OK;
   }
-  { Timed t(c, K_FW, s);  if (t.done(launch_featurewise24(c->Hc, c->meta, c->dZc, T, F, c->Hc_t, c->meta_t, c->dZc_t, 1, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_FW, s);  if (t.done(launch_featurewise24(c->Hc, c->meta, c->dZc, T, F, c->Hc_t, c->meta_t, c->dZc_t, 1, c->tele, s))) return FFN24_ERR_HIP; }
+  if (c->tele && (rc = tele_snapshot(c, 1, s))) return rc;
   { Timed t(c, K_TR_ACT, s);
     int rc1 = launch_transpose(dY, T, D, c->dYt, 0, nullptr, perm, s);
     if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, 0, nullptr, perm, s))) return FFN24_ERR_HIP; }
@@ -408,8 +473,10 @@ int ffn_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const 
   { Timed t(c, K_TR_W, s);
     int rc1 = launch_transpose(W1, D, F, c->W1t, 1, nullptr, nullptr, s);
     if (t.done(rc1 ? rc1 : launch_transpose(W2, F, D, c->W2t, 0, c->W2p, nullptr, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, KD_UP, s);   if (t.done(launch_up_relu2(c->W1t, X, b1, T, D, F, c->Hd, c->Hd_t, s))) return FFN24_ERR_HIP; }
+  if (c->tele && launch_zero32(reinterpret_cast<uint32_t*>(c->tele), 2 * TELE_WORDS, s)) return FFN24_ERR_HIP;
+  { Timed t(c, KD_UP, s);   if (t.done(launch_up_relu2(c->W1t, X, b1, T, D, F, c->Hd, c->Hd_t, c->tele, s))) return FFN24_ERR_HIP; }
   { Timed t(c, KD_DOWN, s); if (t.done(launch_dense_rowmajor(c->Hd, 1, c->W2t, T, D, F, Y, s))) return FFN24_ERR_HIP; }
+  if (c->tele && (rc = tele_snapshot(c, 0, s))) return rc;
   c->X = X; c->W1 = W1; c->have_fwd_dense = 1;
   return FFN24_OK;
 }

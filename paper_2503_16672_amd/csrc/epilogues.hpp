@@ -2,8 +2,20 @@
 // A lane owns rows m_lane + 16*mi + v (64 consecutive) and columns n_lane + ni (4 consecutive).
 #pragma once
 #include "gemm_core.hpp"
+#include "launch.hpp"
 
 namespace ffn24 {
+
+// Sums two 16-bit fields over the wave (each field's total must stay below 65536) and has lane 0 add them to slot
+// `slot` of quantities ka and kb.
+__device__ __forceinline__ void tele_add2(unsigned long long* tele, uint32_t packed, int ka, int kb, int slot) {
+#pragma unroll
+  for (int sft = 1; sft < 64; sft <<= 1) packed += (uint32_t)__shfl_xor((int)packed, sft, 64);
+  if ((threadIdx.x & 63) == 0) {
+    atomicAdd(tele + tele_index(ka, slot), (unsigned long long)(packed & 0xFFFFu));
+    if (kb >= 0) atomicAdd(tele + tele_index(kb, slot), (unsigned long long)(packed >> 16));
+  }
+}
 
 // C[m][n], n contiguous: 4 consecutive columns per lane and row -> one 8-byte store per row.
 struct EpiRowMajor {
@@ -45,9 +57,13 @@ struct EpiColMajor {
 // H[t][f] = bf16( max(0, acc + b1[f])^2 ), stored as the [T][F] operand of the down-projection; if Ht is given the
 // same values are also stored as the [F][T] operand of the weight-gradient GEMM that reduces over tokens.  Both in
 // the dense panel form of gemm_core.hpp (64-byte pieces of 32 k), like every A operand the library makes for itself.
-struct EpiRelu2 {
-  struct Args { __bf16* H; __bf16* Ht; const float* b1; int F; int T; };
+// STATS: also counts the non-zero stored activations of the launch into tele (may be NULL), the sparsity level the
+// dense path reports while 2:4 is still switched off (Sec. 2, last paragraph: the dense warm-up).
+template <bool STATS>
+struct EpiRelu2T {
+  struct Args { __bf16* H; __bf16* Ht; const float* b1; int F; int T; unsigned long long* tele; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+    uint32_t nonzero = 0u;   // of this lane's 256 activations
 #pragma unroll
     for (int mi = 0; mi < 4; mi++) {
       float bias[16];
@@ -66,7 +82,10 @@ struct EpiRelu2 {
         for (int q = 0; q < 2; q++) {
           u32x4 o;
 #pragma unroll
-          for (int d = 0; d < 4; d++) o[d] = pack_bf16x2(acc[mi][ni][8 * q + 2 * d], acc[mi][ni][8 * q + 2 * d + 1]);
+          for (int d = 0; d < 4; d++) {
+            o[d] = pack_bf16x2(acc[mi][ni][8 * q + 2 * d], acc[mi][ni][8 * q + 2 * d + 1]);
+            if constexpr (STATS) nonzero += min(o[d] & 0xFFFFu, 1u) + min(o[d] >> 16, 1u);
+          }
           *reinterpret_cast<u32x4*>(row + 8 * q) = o;
         }
       }
@@ -80,8 +99,12 @@ struct EpiRelu2 {
         }
       }
     }
+    if constexpr (STATS) {
+      if (e.tele) tele_add2(e.tele, nonzero, TELE_NONZERO, -1, blockIdx.x + (threadIdx.x >> 6));
+    }
   }
 };
+using EpiRelu2 = EpiRelu2T<false>;
 
 // Fused up-projection epilogue of the 2:4 FFN (Sec. 2: activation, then sparsification, in one pass):
 // h = bf16(max(0, acc + b1)^2); of every 4 consecutive features of a token keep the 2 largest
@@ -95,11 +118,14 @@ struct EpiRelu2 {
 //   column-level sparsity the first GEMM's epilogue can compute for free), accumulated with atomics; the caller
 //   zeroes it.  A lane counts its 4 tokens in 8-bit fields (4 features per register), the 32 lanes that hold the
 //   same 64 features add their fields up with a butterfly, and each lane then adds two features' totals.
+//   tele optional (STATS only): the launch's totals of non-zero activations before pruning and of non-zero kept values
+//   (Sec. 2, first paragraph: the share of non-zeros that 2:4 drops), one pair of atomics per wave.
 template <bool STATS>
 struct EpiPrune24T {
-  struct Args { __bf16* Hc; uint8_t* meta; __bf16* Hdbg; const float* b1; int F; uint32_t* nnz; };
+  struct Args { __bf16* Hc; uint8_t* meta; __bf16* Hdbg; const float* b1; int F; uint32_t* nnz; unsigned long long* tele; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
     uint32_t cnt[16];
+    uint32_t kept = 0u;   // non-zero values among the lane's 128 stored ones
 #pragma unroll
     for (int i = 0; i < 16; i++) cnt[i] = 0u;
 #pragma unroll
@@ -140,6 +166,7 @@ struct EpiPrune24T {
           int gi = 4 * mi + a;
           vals[gi] = (kf >> 2) | ((ks >> 2) << 16);
           nib[gi >> 3] |= n4 << (4 * (gi & 7));
+          if constexpr (STATS) kept += min(kf >> 2, 1u) + min(ks >> 2, 1u);
         }
       }
       size_t piece = a24_piece((int)t, m_lane >> 6, e.F >> 6);
@@ -150,6 +177,15 @@ struct EpiPrune24T {
       *reinterpret_cast<u32x2*>(e.meta + piece * 8) = u32x2{nib[0], nib[1]};
     }
     if constexpr (STATS) {
+      if (e.tele) {
+        // the lane's own non-zero count is the sum of its fields (at most 4 each); with the kept count, over the wave
+        uint32_t tot = 0u;
+#pragma unroll
+        for (int i = 0; i < 16; i++) tot += (cnt[i] & 0xFFu) + ((cnt[i] >> 8) & 0xFFu) + ((cnt[i] >> 16) & 0xFFu) + (cnt[i] >> 24);
+        tele_add2(e.tele, tot | (kept << 16), TELE_NONZERO, TELE_KEPT_TOK, blockIdx.x + (threadIdx.x >> 6));
+      }
+    }
+    if constexpr (STATS) if (e.nnz) {
       // totals over the 32 lanes of this lane half (<= 128 per field); then lane r adds features r and r + 32
       int lane = threadIdx.x & 63;
 #pragma unroll

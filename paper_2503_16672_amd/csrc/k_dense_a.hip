@@ -3,9 +3,13 @@
 
 namespace ffn24 {
 
-int launch_up_relu2(const void* W1t, const void* X, const float* b1, int T, int D, int F, void* H, void* Ht, hipStream_t s) {
+int launch_up_relu2(const void* W1t, const void* X, const float* b1, int T, int D, int F, void* H, void* Ht, unsigned long long* tele, hipStream_t s) {
   GemmArgs g{W1t, nullptr, X, F, T, D, 1};
-  EpiRelu2::Args ea{static_cast<__bf16*>(H), static_cast<__bf16*>(Ht), b1, F, T};
+  if (tele) {
+    EpiRelu2T<true>::Args eas{static_cast<__bf16*>(H), static_cast<__bf16*>(Ht), b1, F, T, tele};
+    return launch_gemm<false, EpiRelu2T<true>>(g, eas, s);
+  }
+  EpiRelu2::Args ea{static_cast<__bf16*>(H), static_cast<__bf16*>(Ht), b1, F, T, nullptr};
   return launch_gemm<false, EpiRelu2>(g, ea, s);
 }
 

@@ -5,11 +5,11 @@
 namespace ffn24 {
 
 int launch_up_prune24(const void* W1t, const void* X, const float* b1, int T, int D, int F,
-                      void* Hc, uint8_t* meta, void* Hdbg, uint32_t* nnz, const int* token_map, hipStream_t s) {
+                      void* Hc, uint8_t* meta, void* Hdbg, uint32_t* nnz, unsigned long long* tele, const int* token_map, hipStream_t s) {
   GemmArgs g{W1t, nullptr, X, F, T, D, 1, token_map};
-  EpiPrune24::Args ea{static_cast<__bf16*>(Hc), meta, static_cast<__bf16*>(Hdbg), b1, F, nnz};
-  if (nnz) {
-    EpiPrune24T<true>::Args eas{static_cast<__bf16*>(Hc), meta, static_cast<__bf16*>(Hdbg), b1, F, nnz};
+  EpiPrune24::Args ea{static_cast<__bf16*>(Hc), meta, static_cast<__bf16*>(Hdbg), b1, F, nullptr, nullptr};
+  if (nnz || tele) {
+    EpiPrune24T<true>::Args eas{static_cast<__bf16*>(Hc), meta, static_cast<__bf16*>(Hdbg), b1, F, nnz, tele};
     return launch_gemm<false, EpiPrune24T<true>>(g, eas, s);
   }
   return launch_gemm<false, EpiPrune24>(g, ea, s);

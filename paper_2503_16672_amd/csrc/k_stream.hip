@@ -70,7 +70,8 @@ __global__ void __launch_bounds__(256) featurewise24_kernel(const uint16_t* __re
                                                             const uint16_t* __restrict__ dZc, int T, int F,
                                                             uint16_t* __restrict__ Hc_t, uint8_t* __restrict__ meta_t,
                                                             uint16_t* __restrict__ dZc_t, const int* __restrict__ row_of_feat,
-                                                            int n_sparse, uint16_t* __restrict__ Hdn_t, uint16_t* __restrict__ dZdn_t) {
+                                                            int n_sparse, uint16_t* __restrict__ Hdn_t, uint16_t* __restrict__ dZdn_t,
+                                                            unsigned long long* __restrict__ tele) {
   __shared__ uint16_t sH[FW_TOK * FW_LD];
   __shared__ uint16_t sZ[FW_TOK * FW_LD];
   int f0 = blockIdx.x * FW_FEAT, t0 = blockIdx.y * FW_TOK;
@@ -113,6 +114,7 @@ __global__ void __launch_bounds__(256) featurewise24_kernel(const uint16_t* __re
     }
   }
   __syncthreads();
+  uint32_t kept = 0u;   // non-zero activations this work item writes out (at most 32)
 #pragma unroll
   for (int i = 0; i < 4; i++) {
     int item = tid + 256 * i;
@@ -132,6 +134,8 @@ __global__ void __launch_bounds__(256) featurewise24_kernel(const uint16_t* __re
         size_t o = a24_piece(orow - n_sparse, (t0 + 8 * oct) >> 5, T >> 5) * 32 + ((t0 + 8 * oct) & 31);
         *reinterpret_cast<u32x4*>(Hdn_t + o) = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
         if (has_z) *reinterpret_cast<u32x4*>(dZdn_t + o) = u32x4{z[0] | (z[1] << 16), z[2] | (z[3] << 16), z[4] | (z[5] << 16), z[6] | (z[7] << 16)};
+#pragma unroll
+        for (int j = 0; j < 8; j++) kept += min(h[j], 1u);
         continue;
       }
     }
@@ -157,25 +161,55 @@ __global__ void __launch_bounds__(256) featurewise24_kernel(const uint16_t* __re
     *reinterpret_cast<u32x2*>(Hc_t + vo) = u32x2{hp[0], hp[1]};
     if (has_z) *reinterpret_cast<u32x2*>(dZc_t + vo) = u32x2{zp[0], zp[1]};
     meta_t[mo] = (uint8_t)(nb[0] | (nb[1] << 4));
+    kept += min(hp[0] & 0xFFFFu, 1u) + min(hp[0] >> 16, 1u) + min(hp[1] & 0xFFFFu, 1u) + min(hp[1] >> 16, 1u);
+  }
+  // what the weight-gradient GEMMs still see of the activation (Sec. 2: the second, feature-wise drop): one atomic
+  // per workgroup (tele is a kernel argument, so the barrier is reached by all or none)
+  if (tele) {
+    __shared__ uint32_t s_kept[4];
+#pragma unroll
+    for (int sft = 1; sft < 64; sft <<= 1) kept += (uint32_t)__shfl_xor((int)kept, sft, 64);
+    if ((tid & 63) == 0) s_kept[tid >> 6] = kept;
+    __syncthreads();
+    if (tid == 0)
+      atomicAdd(tele + tele_index(TELE_KEPT_FEAT, blockIdx.x + 5 * blockIdx.y),
+                (unsigned long long)(s_kept[0] + s_kept[1] + s_kept[2] + s_kept[3]));
   }
 }
 
+// out[0] = elements, out[1 + k] = the sum of the slots of quantity k, out[4] = path: what a telemetry snapshot holds
+__global__ void __launch_bounds__(64) tele_sum_kernel(const unsigned long long* __restrict__ tele, long long elements, long long path,
+                                                      long long* __restrict__ out) {
+  int k = threadIdx.x;
+  if (k < TELE_KINDS) {
+    unsigned long long sum = 0;
+    for (int i = 0; i < TELE_SLOTS; i++) sum += tele[tele_index(k, i)];
+    out[1 + k] = (long long)sum;
+  }
+  if (k == TELE_KINDS) { out[0] = elements; out[1 + TELE_KINDS] = path; }
+}
+
+int launch_tele_sum(const unsigned long long* tele, long long elements, long long path, long long* out, hipStream_t s) {
+  hipLaunchKernelGGL(tele_sum_kernel, dim3(1), dim3(64), 0, s, tele, elements, path, out);
+  return (int)hipGetLastError();
+}
+
 int launch_featurewise24(const void* Hc, const uint8_t* meta, const void* dZc, int T, int F,
-                         void* Hc_t, uint8_t* meta_t, void* dZc_t, int panel, hipStream_t s) {
+                         void* Hc_t, uint8_t* meta_t, void* dZc_t, int panel, unsigned long long* tele, hipStream_t s) {
   dim3 grid(F / FW_FEAT, T / FW_TOK);
   auto kern = panel ? featurewise24_kernel<true> : featurewise24_kernel<false>;
   hipLaunchKernelGGL(kern, grid, dim3(256), 0, s, static_cast<const uint16_t*>(Hc), meta,
                      static_cast<const uint16_t*>(dZc), T, F, static_cast<uint16_t*>(Hc_t), meta_t, static_cast<uint16_t*>(dZc_t),
-                     nullptr, 0, nullptr, nullptr);
+                     nullptr, 0, nullptr, nullptr, tele);
   return (int)hipGetLastError();
 }
 
 int launch_featurewise24_split(const void* Hc, const uint8_t* meta, const void* dZc, int T, int F, const int* row_of_feat, int n_sparse,
-                               void* Hc_t, uint8_t* meta_t, void* dZc_t, void* Hdn_t, void* dZdn_t, hipStream_t s) {
+                               void* Hc_t, uint8_t* meta_t, void* dZc_t, void* Hdn_t, void* dZdn_t, unsigned long long* tele, hipStream_t s) {
   dim3 grid(F / FW_FEAT, T / FW_TOK);
   hipLaunchKernelGGL((featurewise24_kernel<true, true>), grid, dim3(256), 0, s, static_cast<const uint16_t*>(Hc), meta,
                      static_cast<const uint16_t*>(dZc), T, F, static_cast<uint16_t*>(Hc_t), meta_t, static_cast<uint16_t*>(dZc_t),
-                     row_of_feat, n_sparse, static_cast<uint16_t*>(Hdn_t), static_cast<uint16_t*>(dZdn_t));
+                     row_of_feat, n_sparse, static_cast<uint16_t*>(Hdn_t), static_cast<uint16_t*>(dZdn_t), tele);
   return (int)hipGetLastError();
 }
 

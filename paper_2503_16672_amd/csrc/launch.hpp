@@ -23,15 +23,25 @@ inline int ensure_dynamic_lds(const void* kern, int bytes, std::atomic<bool> (&d
   return 0;
 }
 
+// Telemetry counters (the sparsity level of the activation and what 2:4 keeps of it): TELE_SLOTS 64-bit slots per
+// quantity, each in a 128-byte line of its own and summed when read, so that the atomics of a launch spread over many
+// lines instead of queueing on one.  Slot s of quantity k is word tele_index(k, s).
+constexpr int TELE_SLOTS = 64, TELE_STRIDE = 16;
+enum { TELE_NONZERO = 0, TELE_KEPT_TOK = 1, TELE_KEPT_FEAT = 2, TELE_KINDS = 3 };
+constexpr int TELE_WORDS = TELE_KINDS * TELE_SLOTS * TELE_STRIDE;   // 64-bit words in the buffer
+__host__ __device__ constexpr int tele_index(int kind, int slot) { return (kind * TELE_SLOTS + (slot & (TELE_SLOTS - 1))) * TELE_STRIDE; }
+
 // All return a hipError_t cast to int (0 = success); shapes must already be validated by the caller:
 // M % 256 == 0, N % 256 == 0, K % 64 == 0, 16-byte aligned pointers.  Every GEMM operand is K-contiguous.
 
 // up-projection with rows = hidden features: A = W1^T [F][D] in dense panel form, B = X [T][D]
 // nnz (may be NULL): [F] per-feature non-zero counts, accumulated with atomics (zeroed by the caller)
 // token_map (may be NULL, also below): column n of the GEMM (position n inside the FFN) is token token_map[n] of X / dY
+// tele (may be NULL, also below): the telemetry slots (TELE_KINDS x TELE_SLOTS 64-bit counters, epilogues.hpp) the
+// launch adds its counts to
 int launch_up_prune24(const void* W1t, const void* X, const float* b1, int T, int D, int F,
-                      void* Hc, uint8_t* meta, void* Hdbg, uint32_t* nnz, const int* token_map, hipStream_t s);
-int launch_up_relu2(const void* W1t, const void* X, const float* b1, int T, int D, int F, void* H, void* Ht, hipStream_t s);
+                      void* Hc, uint8_t* meta, void* Hdbg, uint32_t* nnz, unsigned long long* tele, const int* token_map, hipStream_t s);
+int launch_up_relu2(const void* W1t, const void* X, const float* b1, int T, int D, int F, void* H, void* Ht, unsigned long long* tele, hipStream_t s);
 // C[M][N] = A24[M][K] * B[N][K]^T; a_panel: (vals, meta) are in panel form instead of row-major
 int launch_sp_rowmajor(const void* vals, const uint8_t* meta, int a_panel, const void* B, int M, int N, int K, void* C, hipStream_t s);
 // out[N][M] = (A24[M][K] * B[N][K]^T)^T
@@ -54,7 +64,7 @@ int launch_split_partition(const uint32_t* nnz, int F, int n_dense, int max_coun
 // feature-wise re-compression with the split: sparse features as in launch_featurewise24 (panel form, row = row_of_feat),
 // dense features as plain [n_dense][T] rows of H24 and dZ24 in dense panel form
 int launch_featurewise24_split(const void* Hc, const uint8_t* meta, const void* dZc, int T, int F, const int* row_of_feat, int n_sparse,
-                               void* Hc_t, uint8_t* meta_t, void* dZc_t, void* Hdn_t, void* dZdn_t, hipStream_t s);
+                               void* Hc_t, uint8_t* meta_t, void* dZc_t, void* Hdn_t, void* dZdn_t, unsigned long long* tele, hipStream_t s);
 // dense GEMMs: A [M][K] (a_panel: in dense panel form), B [N][K]
 int launch_dense_rowmajor(const void* A, int a_panel, const void* B, int M, int N, int K, void* C, hipStream_t s);
 int launch_dense_colmajor(const void* A, int a_panel, const void* B, int M, int N, int K, void* Ct, hipStream_t s);
@@ -79,7 +89,9 @@ int launch_zero32(uint32_t* p, size_t n, hipStream_t s);
 int launch_sparsify24(const void* H, int64_t rows, int64_t cols, void* vals, uint8_t* meta, hipStream_t s);
 // panel: inputs and outputs are in panel form (the library's own buffers) instead of row-major
 int launch_featurewise24(const void* Hc, const uint8_t* meta, const void* dZc, int T, int F,
-                         void* Hc_t, uint8_t* meta_t, void* dZc_t, int panel, hipStream_t s);
+                         void* Hc_t, uint8_t* meta_t, void* dZc_t, int panel, unsigned long long* tele, hipStream_t s);
+// out[0] = elements, out[1..3] = the sums of the telemetry slots (non-zero, kept token-wise, kept feature-wise), out[4] = path
+int launch_tele_sum(const unsigned long long* tele, long long elements, long long path, long long* out, hipStream_t s);
 // panel form -> row-major copy of a compressed operand: rows x npanels pieces of `piece_bytes` (64 values / 8 or 16 metadata)
 int launch_unpanel(const void* src, int rows, int npanels, int piece_bytes, void* dst, hipStream_t s);
 // in [R][C] -> out [C][R] (R, C % 64 == 0); out_panel: out is written in dense panel form (then C % 256 == 0);

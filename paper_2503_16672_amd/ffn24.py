@@ -22,10 +22,11 @@ FFN24_DEBUG_DUMP_H = 4
 FFN24_SPLIT = 8
 FFN24_ROWWISE = 16
 FFN24_PERMUTE = 32
+FFN24_TELEMETRY = 64
 
 EXPORTS = (
     "ffn24_ctx_create", "ffn24_ctx_destroy", "ffn24_set_scales", "ffn24_set_row_scales", "ffn24_set_token_permutation", "ffn24_set_split", "sparsify24", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd",
-    "ffn_fwd", "ffn_bwd", "ffn24_saved_bytes", "ffn24_copy_saved", "ffn24_set_profiling", "ffn24_kernel_ms", "ffn24_strerror",
+    "ffn_fwd", "ffn_bwd", "ffn24_get_telemetry", "ffn24_policy_use_sparse", "ffn24_saved_bytes", "ffn24_copy_saved", "ffn24_set_profiling", "ffn24_kernel_ms", "ffn24_strerror",
 )
 
 KERNEL_NAMES = ("up_prune24", "down_sp", "dh_gather", "dx_sp", "featurewise24", "dw2_sp", "dw1_sp",
@@ -62,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.ffn24_bwd.argtypes = [vp, vp, vp, vp, vp, vp]
         L.ffn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp]
         L.ffn_bwd.argtypes = [vp, vp, vp, vp, vp, vp]
+        L.ffn24_get_telemetry.argtypes = [vp, ctypes.POINTER(i64), ci]
+        L.ffn24_policy_use_sparse.argtypes = [vp, ctypes.c_double, ctypes.POINTER(ci)]
         L.ffn24_saved_bytes.argtypes = [vp, ci, ctypes.POINTER(i64)]
         L.ffn24_copy_saved.argtypes = [vp, ci, vp, i64, vp]
         L.ffn24_set_profiling.argtypes = [vp, ci]
@@ -256,6 +259,20 @@ class Context:
         assert out.numel() * out.element_size() == n.value
         _check(lib().ffn24_copy_saved(self._h, which, _ptr(out), n.value, _stream()), f"ffn24_copy_saved({name})")
         return out
+
+    def telemetry(self, wait: bool = True) -> dict:
+        """The newest sparsity snapshot of an FFN24_TELEMETRY context (see ffn24_get_telemetry in the header)."""
+        n = (ctypes.c_int64 * 5)()
+        _check(lib().ffn24_get_telemetry(self._h, n, int(wait)), "ffn24_get_telemetry")
+        sparse = bool(n[4])
+        return {"elements": n[0], "nonzero": n[1], "kept_tokenwise": n[2] if sparse else None,
+                "kept_featurewise": n[3] if sparse and n[3] else None, "path": "2:4" if sparse else "dense"}
+
+    def policy_use_sparse(self, min_sparsity: float) -> bool:
+        """Whether the newest landed snapshot is sparse enough for the 2:4 path (see ffn24_policy_use_sparse)."""
+        use = ctypes.c_int()
+        _check(lib().ffn24_policy_use_sparse(self._h, min_sparsity, ctypes.byref(use)), "ffn24_policy_use_sparse")
+        return bool(use.value)
 
     def set_profiling(self, on: bool):
         _check(lib().ffn24_set_profiling(self._h, int(on)), "ffn24_set_profiling")

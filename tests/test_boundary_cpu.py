@@ -20,7 +20,7 @@ def _declared():
 
 def test_header_symbols_are_exported():
     names = _declared()
-    assert len(names) == 18 and "ffn24_fwd" in names and "sparsify24" in names
+    assert len(names) == 20 and "ffn24_fwd" in names and "sparsify24" in names
     lib = ctypes.CDLL(LIB)
     for n in names:
         assert hasattr(lib, n), n
@@ -68,6 +68,11 @@ def test_argument_validation_without_gpu():
     assert h.value is None
     assert L.ffn24_fwd(None, a16, a16, None, a16, a16, None) == -1
     assert L.ffn24_ctx_destroy(None) == 0
+    assert L.ffn24_ctx_create(ctypes.byref(h), 256, 512, 2048, 1, 64) == -4  # telemetry is a bf16 feature
+    n5 = (ctypes.c_int64 * 5)()
+    assert L.ffn24_get_telemetry(None, n5, 0) == -1
+    use = ctypes.c_int()
+    assert L.ffn24_policy_use_sparse(None, 0.9, ctypes.byref(use)) == -1
 
 
 def test_binding_checks_shapes_and_dtypes_before_the_call():

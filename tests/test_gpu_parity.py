@@ -940,3 +940,133 @@ def test_ffn24_token_permutation_full_size(F24):
     print(f"  dW2 on sampled features {e2:.2e}", flush=True)
     assert e2 <= TOL_BF16
     ctx.close()
+
+
+# ----------------------------------------------------------------------------- sparsity telemetry and the dense <-> 2:4 switch
+def _counts_from_saved(F24, ctx, dense=None):
+    """The oracle's counts on the GPU's own stored tensors (small sizes: everything goes through the oracle)."""
+    Hq = f64(ctx.saved("H_dump"))
+    H24 = O.bf16_bits_to_f32(O.decompress24(words_of(ctx.saved("Hc")), ctx.saved("meta").cpu().numpy()))
+    _, _, M_T = O.featurewise24(H24)
+    return O.sparsity_counts(Hq, H24, M_T, dense)
+
+
+def test_telemetry_counts_small(F24):
+    print("telemetry T=512 D=256 F=1024", flush=True)
+    T, D, Fh = 512, 256, 1024
+    inp = synth.make_inputs(T, D, Fh, 0.8, seed=91, with_dy=True)
+    d = _upload(inp)
+    ctx = F24.Context(T, D, Fh, F24.FFN24_TRAINING | F24.FFN24_DENSE | F24.FFN24_TELEMETRY | F24.FFN24_DEBUG_DUMP_H)
+    assert ctx.policy_use_sparse(0.0) is False          # nothing measured yet: dense
+    with pytest.raises(F24.Ffn24Error) as e:
+        ctx.telemetry(wait=False)
+    assert e.value.code == -7
+    ctx.ffn24_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    t_fwd = ctx.telemetry()
+    ctx.ffn24_bwd(d["dY"])
+    t_bwd = ctx.telemetry()
+    torch.cuda.synchronize()
+    ref = _counts_from_saved(F24, ctx)
+    print("  gpu fwd", t_fwd, "\n  gpu bwd", t_bwd, "\n  oracle on the gpu's tensors", ref, flush=True)
+    assert t_fwd["path"] == "2:4" and t_fwd["kept_featurewise"] is None
+    for t in (t_fwd, t_bwd):
+        assert (t["elements"], t["nonzero"], t["kept_tokenwise"]) == (ref["elements"], ref["nonzero"], ref["kept_tokenwise"])
+    assert t_bwd["kept_featurewise"] == ref["kept_featurewise"]
+    # end to end against the oracle's own forward: a few activations round the other way, so nearly equal
+    f = O.ffn24_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"])
+    _, _, M_T = O.featurewise24(f["H24"])
+    e2e = O.sparsity_counts(f["Hq"], f["H24"], M_T)
+    for k in ("nonzero", "kept_tokenwise", "kept_featurewise"):
+        assert abs(t_bwd[k] - e2e[k]) <= 2e-3 * e2e[k], (k, t_bwd[k], e2e[k])
+    # the switch takes the oracle's decision on the same counts, on both sides of the measured level
+    level = 1.0 - ref["nonzero"] / ref["elements"]
+    for thr in (level - 0.05, level + 0.05, 0.0, 1.0):
+        assert ctx.policy_use_sparse(thr) == O.use_sparse_path(ref, thr)
+    # the dense path measures the same level
+    ctx.ffn_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    t_dense = ctx.telemetry()
+    assert t_dense["path"] == "dense" and t_dense["kept_tokenwise"] is None
+    assert t_dense["nonzero"] == int(torch.count_nonzero(ctx.saved("H_dense")))
+    assert t_dense["nonzero"] == O.sparsity_counts(f64(ctx.saved("H_dense")))["nonzero"]
+    ctx.close()
+
+
+def test_telemetry_with_split_and_permutation(F24):
+    print("telemetry with dense features and a token permutation", flush=True)
+    T, D, Fh = 512, 256, 2048
+    inp = synth.make_inputs(T, D, Fh, "per_feature", seed=92, with_dy=True, token_corr=(8, 0.95))
+    d = _upload(inp)
+    flags = F24.FFN24_TRAINING | F24.FFN24_TELEMETRY | F24.FFN24_DEBUG_DUMP_H | F24.FFN24_SPLIT | F24.FFN24_PERMUTE
+    ctx = F24.Context(T, D, Fh, flags)
+    ctx.set_split(256)
+    ctx.ffn24_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    ctx.ffn24_bwd(d["dY"])
+    t0 = ctx.telemetry()
+    dense = O.split_features(ctx.saved("nnz").cpu().numpy().astype(np.int64), 256)
+    ref0 = _counts_from_saved(F24, ctx, dense)
+    assert (t0["nonzero"], t0["kept_tokenwise"], t0["kept_featurewise"]) == (ref0["nonzero"], ref0["kept_tokenwise"], ref0["kept_featurewise"])
+    # with the permutation the same activations sit in other token groups: the first two counts stay, fewer are dropped
+    ctx.set_token_permutation(synth.token_permutation(T, seed=5))
+    ctx.ffn24_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    ctx.ffn24_bwd(d["dY"])
+    t1 = ctx.telemetry()
+    ref1 = _counts_from_saved(F24, ctx, dense)
+    assert (t1["nonzero"], t1["kept_tokenwise"], t1["kept_featurewise"]) == (ref1["nonzero"], ref1["kept_tokenwise"], ref1["kept_featurewise"])
+    assert (t1["nonzero"], t1["kept_tokenwise"]) == (t0["nonzero"], t0["kept_tokenwise"])
+    drop0 = 1 - t0["kept_featurewise"] / t0["kept_tokenwise"]; drop1 = 1 - t1["kept_featurewise"] / t1["kept_tokenwise"]
+    print(f"  feature-wise drop {drop0:.4f} -> {drop1:.4f} with the permutation", flush=True)
+    assert drop1 < 0.5 * drop0
+    ctx.close()
+
+
+def test_telemetry_rules_and_warm_up(F24):
+    ctx = F24.Context(256, 256, 1024, F24.FFN24_DENSE)
+    with pytest.raises(F24.Ffn24Error) as e:
+        ctx.telemetry()
+    assert e.value.code == -5
+    ctx.close()
+    with pytest.raises(F24.Ffn24Error) as e:
+        F24.Context(256, 256, 1024, F24.FFN24_TELEMETRY, dtype=F24.FFN24_FP8_E4M3)
+    assert e.value.code == -4
+    ctx = F24.Context(256, 256, 1024, F24.FFN24_DENSE | F24.FFN24_TELEMETRY)
+    for bad in (-0.1, 1.5, float("nan")):
+        with pytest.raises(F24.Ffn24Error) as e:
+            ctx.policy_use_sparse(bad)
+        assert e.value.code == -2
+    # the warm-up: about half zeros at initialisation -> dense; sparse enough later -> 2:4 (Sec. 2, last paragraph)
+    used = []
+    for sparsity in (0.5, 0.7, 0.92, 0.95):
+        d = _upload(synth.make_inputs(256, 256, 1024, sparsity, seed=17))
+        use = ctx.policy_use_sparse(0.85)
+        used.append(use)
+        (ctx.ffn24_fwd if use else ctx.ffn_fwd)(d["X"], d["W1"], d["b1"], d["W2"])
+        torch.cuda.synchronize()                     # so that the next decision sees this step's measurement
+    print("  2:4 path used per step:", used, flush=True)
+    assert used == [False, False, False, True]       # each step decides on the step before it
+    ctx.close()
+
+
+@pytest.mark.timeout(900)
+def test_telemetry_full_size(F24):
+    """c4: the counts against counts of the stored tensors themselves (torch's count on the device, pinned to the oracle's
+    count on a slice), and the cost of counting."""
+    w = synth.WORKLOADS["c4"]
+    print("telemetry c4", flush=True)
+    inp = synth.make_workload("c4", with_dy=True)
+    d = _upload(inp)
+    ctx = F24.Context(w.T, w.D, w.F, F24.FFN24_TRAINING | F24.FFN24_TELEMETRY | F24.FFN24_DEBUG_DUMP_H)
+    ctx.ffn24_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    ctx.ffn24_bwd(d["dY"])
+    t = ctx.telemetry()
+    Hd, Hc, Hc_t = ctx.saved("H_dump"), ctx.saved("Hc"), ctx.saved("Hc_t")
+    assert int(torch.count_nonzero(Hd[:64])) == O.sparsity_counts(f64(Hd[:64]))["nonzero"]
+    assert t["elements"] == w.T * w.F
+    assert t["nonzero"] == int(torch.count_nonzero(Hd))
+    assert t["kept_tokenwise"] == int(torch.count_nonzero(Hc))
+    assert t["kept_featurewise"] == int(torch.count_nonzero(Hc_t))
+    zeros = 1 - t["nonzero"] / t["elements"]; d_tok = 1 - t["kept_tokenwise"] / t["nonzero"]; d_feat = 1 - t["kept_featurewise"] / t["kept_tokenwise"]
+    print(f"  zeros {zeros:.4f}  dropped token-wise {d_tok:.5f}  feature-wise on top {d_feat:.5f}", flush=True)
+    p = 1 - zeros
+    iid = (4 * p ** 3 * (1 - p) + 2 * p ** 4) / (4 * p)
+    assert abs(zeros - 0.9) < 0.01 and abs(d_tok - iid) < 0.1 * iid and abs(d_feat - iid) < 0.25 * iid
+    ctx.close()
