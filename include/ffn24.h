@@ -138,10 +138,17 @@ FFN24_API int sparsify24_featurewise(const void* Hc, const uint8_t* meta, const 
 FFN24_API int spmm24(const void* values, const uint8_t* meta, const void* Bt, int64_t M, int64_t N, int64_t K, void* C,
                      void* stream);
 
+/* Weights that stay the same over many calls (inference; the micro-batches of one optimizer step): runs the weight
+ * pass of the forward calls once -- W1 [D][F] and W2 [F][D] are re-arranged into the context's workspace -- after
+ * which ffn24_fwd and ffn_fwd accept W1 == NULL and W2 == NULL, meaning "the prepared weights", and skip that pass.
+ * A forward call that is given weights runs the pass itself and drops the prepared state.  The caller keeps W1 alive
+ * and unchanged while it is prepared (ffn24_bwd and ffn_bwd read it). */
+FFN24_API int ffn24_prepare_weights(ffn24_ctx* ctx, const void* W1, const void* W2, void* stream);
+
 /* Forward of the 2:4 FFN (paper Sec. 2):  Z = X W1 + b1;  H = bf16(max(0, Z)^2);  H24 = keep-2-of-4 of H along
  * the hidden features of each token;  Y = H24 W2.
  *   X [T][D], W1 [D][F], b1 [F] fp32 or NULL (the paper's FFN has no bias; b1 only dials the sparsity of synthetic
- *   inputs), W2 [F][D], Y [T][D].
+ *   inputs), W2 [F][D], Y [T][D].  W1 and W2 both NULL: the weights of ffn24_prepare_weights (FFN24_ERR_STATE if none).
  * Kernels: two weight transposes (every GEMM operand is consumed K-contiguous), the dense-MFMA up-projection with
  * the activation and the pruning fused into its epilogue (H is never written densely), the sparse-MFMA
  * down-projection.  The context keeps (Hc, meta), its own copy of W2 and the X and W1 pointers for ffn24_bwd; the

@@ -40,6 +40,7 @@ struct ffn24_ctx {
   // two paths share the weight workspace, so a forward of one invalidates the saved state of the other)
   const void *X, *W1;
   int have_fwd24, have_fwd_dense;
+  const void* prep_W1;          // ffn24_prepare_weights: the caller's W1 whose re-arranged copies the workspace holds (NULL: none)
   // profiling
   int profiling;
   hipEvent_t ev[NUM_KERNELS][2];
@@ -88,6 +89,36 @@ int tele_snapshot(ffn24_ctx* c, long long path, hipStream_t s) {
   if (hipEventRecord(c->tele_ev[slot], s) != hipSuccess) return FFN24_ERR_HIP;
   c->tele_seq++;
   return FFN24_OK;
+}
+
+// The weight pass: W1 -> W1^T in dense panel form (A operand of the up-projection), W2 -> W2^T (B operand of the
+// down-projection) and, when the context trains, W2 itself in panel form (A operand of the dH GEMM).
+int weight_pass(ffn24_ctx* c, const void* W1, const void* W2, hipStream_t s) {
+  int D = (int)c->D, F = (int)c->F;
+  Timed t(c, K_TR_W, s);
+  int rc1;
+  if (c->f8) {
+    rc1 = launch_transpose8(W1, D, F, c->W1t, 1, s);
+    if (!rc1) rc1 = launch_transpose8(W2, F, D, c->W2t, 0, s);
+  } else {
+    rc1 = launch_transpose(W1, D, F, c->W1t, 1, nullptr, nullptr, s);
+    if (!rc1) rc1 = launch_transpose(W2, F, D, c->W2t, 0, c->W2p, nullptr, s);
+  }
+  return t.done(rc1) ? FFN24_ERR_HIP : FFN24_OK;
+}
+
+// Weights of a forward call: both given (run the weight pass; prepared copies are gone after it), or both NULL (use
+// the copies ffn24_prepare_weights left).  On success *W1 is the caller's row-major W1 either way.
+int resolve_weights(ffn24_ctx* c, const void** W1, const void* W2, hipStream_t s) {
+  if (!*W1 && !W2) {
+    if (!c->prep_W1) return FFN24_ERR_STATE;
+    *W1 = c->prep_W1;
+    return FFN24_OK;
+  }
+  if (!*W1 || !W2) return FFN24_ERR_NULL;
+  if (misaligned(*W1) || misaligned(W2)) return FFN24_ERR_ALIGN;
+  c->prep_W1 = nullptr;
+  return weight_pass(c, *W1, W2, s);
 }
 
 int check_ptrs(std::initializer_list<const void*> ps) {
@@ -225,6 +256,19 @@ int ffn24_set_split(ffn24_ctx* c, int64_t n_dense) {
   return FFN24_OK;
 }
 
+int ffn24_prepare_weights(ffn24_ctx* c, const void* W1, const void* W2, void* stream) {
+  if (!c) return FFN24_ERR_NULL;
+  int rc = check_device(c);
+  if (rc) return rc;
+  rc = check_ptrs({W1, W2});
+  if (rc) return rc;
+  c->prep_W1 = nullptr;
+  c->have_fwd24 = c->have_fwd_dense = 0;
+  if ((rc = weight_pass(c, W1, W2, static_cast<hipStream_t>(stream)))) return rc;
+  c->prep_W1 = W1;
+  return FFN24_OK;
+}
+
 int ffn24_get_telemetry(ffn24_ctx* c, int64_t* counts, int wait) {
   if (!c || !counts) return FFN24_ERR_NULL;
   if (!(c->flags & FFN24_TELEMETRY)) return FFN24_ERR_STATE;
@@ -358,18 +402,16 @@ int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, cons
   if (!c) return FFN24_ERR_NULL;
   int rc = check_device(c);
   if (rc) return rc;
-  rc = check_ptrs({X, W1, W2, Y});
+  rc = check_ptrs({X, Y});
   if (rc) return rc;
   if (b1 && misaligned(b1)) return FFN24_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   c->have_fwd24 = c->have_fwd_dense = 0;
+  if (c->f8 && (c->flags & FFN24_ROWWISE) && !c->rsx) return FFN24_ERR_STATE;
+  if ((rc = resolve_weights(c, &W1, W2, s))) return rc;
   if (c->f8 && (c->flags & FFN24_ROWWISE)) {
     // row-wise scaling: up-projection (bf16 kept values + row maxima), row-wise quantisation, scaled sparse GEMM
-    if (!c->rsx) return FFN24_ERR_STATE;
-    { Timed t(c, K_TR_W, s);
-      int rc1 = launch_transpose8(W1, D, F, c->W1t, 1, s);
-      if (t.done(rc1 ? rc1 : launch_transpose8(W2, F, D, c->W2t, 0, s))) return FFN24_ERR_HIP; }
     if (launch_zero32(c->rowmax, (size_t)T, s)) return FFN24_ERR_HIP;
     { Timed t(c, K_UP, s);
       if (t.done(launch_up_prune24_f8_rowwise(c->W1t, X, b1, T, D, F, c->rsx, c->rsw1, c->Hc16, c->meta16, c->Hdbg, c->rowmax, s))) return FFN24_ERR_HIP; }
@@ -380,18 +422,12 @@ int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, cons
     return FFN24_OK;
   }
   if (c->f8) {
-    { Timed t(c, K_TR_W, s);
-      int rc1 = launch_transpose8(W1, D, F, c->W1t, 1, s);
-      if (t.done(rc1 ? rc1 : launch_transpose8(W2, F, D, c->W2t, 0, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_UP, s);
       if (t.done(launch_up_prune24_f8(c->W1t, X, b1, T, D, F, c->sx * c->sw1, c->sh, c->Hc, c->meta, c->Hdbg, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_DOWN, s);
       if (t.done(launch_sp_rowmajor_f8(c->Hc, c->meta, 1, c->W2t, T, D, F, c->sh * c->sw2, Y, s))) return FFN24_ERR_HIP; }
     return FFN24_OK;
   }
-  { Timed t(c, K_TR_W, s);
-    int rc1 = launch_transpose(W1, D, F, c->W1t, 1, nullptr, nullptr, s);
-    if (t.done(rc1 ? rc1 : launch_transpose(W2, F, D, c->W2t, 0, c->W2p, nullptr, s))) return FFN24_ERR_HIP; }
   uint32_t* nnz = (c->flags & FFN24_SPLIT) && c->n_dense > 0 ? c->nnz : nullptr;
   if (nnz && launch_zero32(nnz, (size_t)F, s)) return FFN24_ERR_HIP;
   if (c->tele && launch_zero32(reinterpret_cast<uint32_t*>(c->tele), 2 * TELE_WORDS, s)) return FFN24_ERR_HIP;
@@ -454,25 +490,20 @@ int ffn_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const 
   if (!(c->flags & FFN24_DENSE) || (c->flags & FFN24_ROWWISE)) return FFN24_ERR_STATE;
   int rc = check_device(c);
   if (rc) return rc;
-  rc = check_ptrs({X, W1, W2, Y});
+  rc = check_ptrs({X, Y});
   if (rc) return rc;
   if (b1 && misaligned(b1)) return FFN24_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   c->have_fwd24 = c->have_fwd_dense = 0;
+  if ((rc = resolve_weights(c, &W1, W2, s))) return rc;
   if (c->f8) {
-    { Timed t(c, K_TR_W, s);
-      int rc1 = launch_transpose8(W1, D, F, c->W1t, 1, s);
-      if (t.done(rc1 ? rc1 : launch_transpose8(W2, F, D, c->W2t, 0, s))) return FFN24_ERR_HIP; }
     { Timed t(c, KD_UP, s);
       if (t.done(launch_up_relu2_f8(c->W1t, X, b1, T, D, F, c->sx * c->sw1, c->sh, c->Hd, s))) return FFN24_ERR_HIP; }
     { Timed t(c, KD_DOWN, s);
       if (t.done(launch_dense_rowmajor_f8(c->Hd, 1, c->W2t, T, D, F, c->sh * c->sw2, Y, s))) return FFN24_ERR_HIP; }
     return FFN24_OK;
   }
-  { Timed t(c, K_TR_W, s);
-    int rc1 = launch_transpose(W1, D, F, c->W1t, 1, nullptr, nullptr, s);
-    if (t.done(rc1 ? rc1 : launch_transpose(W2, F, D, c->W2t, 0, c->W2p, nullptr, s))) return FFN24_ERR_HIP; }
   if (c->tele && launch_zero32(reinterpret_cast<uint32_t*>(c->tele), 2 * TELE_WORDS, s)) return FFN24_ERR_HIP;
   { Timed t(c, KD_UP, s);   if (t.done(launch_up_relu2(c->W1t, X, b1, T, D, F, c->Hd, c->Hd_t, c->tele, s))) return FFN24_ERR_HIP; }
   { Timed t(c, KD_DOWN, s); if (t.done(launch_dense_rowmajor(c->Hd, 1, c->W2t, T, D, F, Y, s))) return FFN24_ERR_HIP; }

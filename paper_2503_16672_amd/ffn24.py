@@ -26,7 +26,7 @@ FFN24_TELEMETRY = 64
 
 EXPORTS = (
     "ffn24_ctx_create", "ffn24_ctx_destroy", "ffn24_set_scales", "ffn24_set_row_scales", "ffn24_set_token_permutation", "ffn24_set_split", "sparsify24", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd",
-    "ffn_fwd", "ffn_bwd", "ffn24_get_telemetry", "ffn24_policy_use_sparse", "ffn24_saved_bytes", "ffn24_copy_saved", "ffn24_set_profiling", "ffn24_kernel_ms", "ffn24_strerror",
+    "ffn_fwd", "ffn_bwd", "ffn24_prepare_weights", "ffn24_get_telemetry", "ffn24_policy_use_sparse", "ffn24_saved_bytes", "ffn24_copy_saved", "ffn24_set_profiling", "ffn24_kernel_ms", "ffn24_strerror",
 )
 
 KERNEL_NAMES = ("up_prune24", "down_sp", "dh_gather", "dx_sp", "featurewise24", "dw2_sp", "dw1_sp",
@@ -63,6 +63,7 @@ def lib() -> ctypes.CDLL:
         L.ffn24_bwd.argtypes = [vp, vp, vp, vp, vp, vp]
         L.ffn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp]
         L.ffn_bwd.argtypes = [vp, vp, vp, vp, vp, vp]
+        L.ffn24_prepare_weights.argtypes = [vp, vp, vp, vp]
         L.ffn24_get_telemetry.argtypes = [vp, ctypes.POINTER(i64), ci]
         L.ffn24_policy_use_sparse.argtypes = [vp, ctypes.c_double, ctypes.POINTER(ci)]
         L.ffn24_saved_bytes.argtypes = [vp, ci, ctypes.POINTER(i64)]
@@ -207,6 +208,14 @@ class Context:
         _expect(W2, (self.F, self.D), el, "W2")
         _expect(b1, (self.F,), _F32, "b1")
         _expect(Y, (self.T, self.D), _BF16, "Y")
+
+    def prepare_weights(self, W1, W2):
+        """Run the weight pass once; afterwards ffn24_fwd / ffn_fwd take W1 = W2 = None (see ffn24_prepare_weights)."""
+        el = _BYTE if self.dtype == FFN24_FP8_E4M3 else _BF16
+        _expect(W1, (self.D, self.F), el, "W1")
+        _expect(W2, (self.F, self.D), el, "W2")
+        self._prepared = (W1, W2)      # keeps them alive
+        _check(lib().ffn24_prepare_weights(self._h, _ptr(W1), _ptr(W2), _stream()), "ffn24_prepare_weights")
 
     def ffn24_fwd(self, X, W1, b1, W2, Y=None):
         Y = torch.empty((self.T, self.D), dtype=torch.bfloat16, device=X.device) if Y is None else Y

@@ -20,7 +20,7 @@ def _declared():
 
 def test_header_symbols_are_exported():
     names = _declared()
-    assert len(names) == 20 and "ffn24_fwd" in names and "sparsify24" in names
+    assert len(names) == 21 and "ffn24_fwd" in names and "sparsify24" in names
     lib = ctypes.CDLL(LIB)
     for n in names:
         assert hasattr(lib, n), n
@@ -69,6 +69,7 @@ def test_argument_validation_without_gpu():
     assert L.ffn24_fwd(None, a16, a16, None, a16, a16, None) == -1
     assert L.ffn24_ctx_destroy(None) == 0
     assert L.ffn24_ctx_create(ctypes.byref(h), 256, 512, 2048, 1, 64) == -4  # telemetry is a bf16 feature
+    assert L.ffn24_prepare_weights(None, a16, a16, None) == -1
     n5 = (ctypes.c_int64 * 5)()
     assert L.ffn24_get_telemetry(None, n5, 0) == -1
     use = ctypes.c_int()

@@ -404,32 +404,30 @@ def _groups_to_cols(gsel):
     return f4, f2
 
 
-def _meta_of_groups(meta_rows: np.ndarray, gsel: np.ndarray) -> np.ndarray:
-    """meta [rows, G/2] bytes -> a [rows, len(gsel)/2] byte array holding only the chosen groups (len(gsel) even)."""
-    i0, i1 = O.unpack_meta(meta_rows)
-    nib = (i0[:, gsel] | (i1[:, gsel] << 2)).astype(np.uint8)
+def _meta_of_groups(meta_rows, gsel: np.ndarray) -> np.ndarray:
+    """meta [rows, G/2] bytes (numpy, or a torch tensor on the device) -> a [rows, len(gsel)/2] byte array holding only
+    the chosen groups (len(gsel) even), in the order given.  Only the bytes that hold a chosen group are touched."""
+    gsel = np.asarray(gsel)
+    if isinstance(meta_rows, torch.Tensor):
+        by = meta_rows[:, torch.from_numpy(gsel // 2).to(meta_rows.device)].cpu().numpy()
+    else:
+        by = meta_rows[:, gsel // 2]
+    nib = ((by >> (4 * (gsel & 1)).astype(np.uint8)[None, :]) & np.uint8(15)).astype(np.uint8)
     return (nib[:, 0::2] | (nib[:, 1::2] << 4)).astype(np.uint8)
 
 
-@pytest.mark.timeout(900)
-def test_ffn24_full_size_sampled(F24):
-    """c4 (T=16384, D=4096, F=16384, fwd+bwd), the shape and launch configuration bench.py times.
-    Y and dX depend on one token each: a seeded sample of token rows is checked at full D and F.
-    dW1 / dW2 rows depend on one hidden feature (and the token-wise group of 4 it sits in): a seeded sample of
-    feature groups is checked over all T.  Masks: staged as in the small tests (S1 bit-exact on the GPU's own
-    tensors), on the same samples; the 2:4 invariant everywhere."""
-    w = synth.WORKLOADS["c4"]
-    T, D, Fh = w.T, w.D, w.F
-    print(f"full size c4 T={T} D={D} F={Fh}: generating inputs", flush=True)
-    inp = synth.make_workload("c4", with_dy=True)
+def _fwd_bwd_sampled(F24, inp, T, D, Fh, rows, gsel):
+    """Forward + backward at a size the oracle cannot run whole.
+    Y and dX depend on one token each: the token rows `rows` are checked at full D and F.
+    dW1 / dW2 rows depend on one hidden feature (and the token-wise group of 4 it sits in): the feature groups `gsel`
+    are checked over all T.  Masks: staged as in the small tests (S1 bit-exact on the GPU's own tensors), on the same
+    samples; the 2:4 invariant everywhere."""
     d = _upload(inp)
     ctx = F24.Context(T, D, Fh, F24.FFN24_DEBUG_DUMP_H | F24.FFN24_TRAINING)
     print("  running fwd+bwd on the GPU", flush=True)
     Y = ctx.ffn24_fwd(d["X"], d["W1"], d["b1"], d["W2"])
     dX, dW1, dW2 = ctx.ffn24_bwd(d["dY"])
     torch.cuda.synchronize()
-    rng = np.random.default_rng(44)
-    rows = np.sort(rng.choice(T, 192, replace=False))
     rows_t = torch.from_numpy(rows).cuda()
 
     # ---- token-row sample: forward (S1, S2, S3) and dX
@@ -461,11 +459,10 @@ def test_ffn24_full_size_sampled(F24):
 
     # ---- feature-group sample: feature-wise picks (bit-exact) and the two weight gradients over all tokens
     print("  feature-group sample: feature-wise picks, dW2, dW1", flush=True)
-    gsel = np.sort(rng.choice(Fh // 4, 24, replace=False))
     f4, f2 = _groups_to_cols(gsel)
     f2_t = torch.from_numpy(f2).cuda(); f4_t = torch.from_numpy(f4).cuda()
     Hc_g = words_of(Hc_all[:, f2_t]); dZc_g = words_of(dZc_all[:, f2_t])
-    meta_g = _meta_of_groups(meta_all.cpu().numpy(), gsel)
+    meta_g = _meta_of_groups(meta_all, gsel)
     H24_g = O.decompress24(Hc_g, meta_g)            # [T, 96] words, the GPU's own pruned activation on these features
     dZ24_g = O.decompress24(dZc_g, meta_g)
     Hct_ref, mt_ref = O.sparsify24(np.ascontiguousarray(H24_g.T))
@@ -488,6 +485,33 @@ def test_ffn24_full_size_sampled(F24):
     assert e_dw2 <= TOL_BF16 and e_dw1 <= TOL_BF16 and e_def <= 1e-12
     assert ref["Y"].shape == (len(rows), D)
     ctx.close()
+
+
+@pytest.mark.timeout(900)
+def test_ffn24_full_size_sampled(F24):
+    """c4 (T=16384, D=4096, F=16384, fwd+bwd), the shape and launch configuration bench.py times."""
+    w = synth.WORKLOADS["c4"]
+    print(f"full size c4 T={w.T} D={w.D} F={w.F}: generating inputs", flush=True)
+    inp = synth.make_workload("c4", with_dy=True)
+    rng = np.random.default_rng(44)
+    rows = np.sort(rng.choice(w.T, 192, replace=False))
+    gsel = np.sort(rng.choice(w.F // 4, 24, replace=False))
+    _fwd_bwd_sampled(F24, inp, w.T, w.D, w.F, rows, gsel)
+
+
+@pytest.mark.timeout(900)
+def test_ffn24_offsets_beyond_4_gib(F24):
+    """A long, wide activation (T = 131072 tokens, F = 32768): every [T, F] tensor of the context is 4 GiB and more, so
+    byte offsets no longer fit 32 bits.  The samples include the last tokens and the last feature groups, whose
+    addresses lie beyond that limit; D is small to keep the GEMMs at the bench's size."""
+    T, D, Fh = 131072, 256, 32768
+    print(f"offsets beyond 4 GiB: T={T} D={D} F={Fh}: generating inputs", flush=True)
+    inp = synth.make_inputs(T, D, Fh, 0.9, seed=57, with_dy=True)
+    rng = np.random.default_rng(45)
+    rows = np.unique(np.concatenate([rng.choice(T, 40, replace=False), np.arange(T - 12, T), [0, 65535, 65536, 65537]]))
+    gsel = np.unique(np.concatenate([rng.choice(Fh // 4, 12, replace=False), np.arange(Fh // 4 - 4, Fh // 4), [0, 1]]))
+    gsel = gsel[: len(gsel) // 2 * 2]
+    _fwd_bwd_sampled(F24, inp, T, D, Fh, rows, gsel)
 
 
 @pytest.mark.timeout(900)
@@ -1069,4 +1093,49 @@ def test_telemetry_full_size(F24):
     p = 1 - zeros
     iid = (4 * p ** 3 * (1 - p) + 2 * p ** 4) / (4 * p)
     assert abs(zeros - 0.9) < 0.01 and abs(d_tok - iid) < 0.1 * iid and abs(d_feat - iid) < 0.25 * iid
+    ctx.close()
+
+
+# ----------------------------------------------------------------------------- prepared weights
+def test_prepared_weights_give_identical_results(F24):
+    """Preparing the weights once and passing None afterwards is the same computation without the weight pass: outputs
+    and gradients are bit-identical, on both paths; a call that is given weights drops the prepared state."""
+    print("prepared weights", flush=True)
+    T, D, Fh = 512, 256, 1024
+    inp = synth.make_inputs(T, D, Fh, 0.9, seed=101, with_dy=True)
+    d = _upload(inp)
+    ctx = F24.Context(T, D, Fh, F24.FFN24_TRAINING | F24.FFN24_DENSE)
+    with pytest.raises(F24.Ffn24Error) as e:                 # nothing prepared yet
+        ctx.ffn24_fwd(d["X"], None, d["b1"], None)
+    assert e.value.code == -5
+    with pytest.raises(F24.Ffn24Error) as e:                 # one weight without the other
+        ctx.ffn24_fwd(d["X"], d["W1"], d["b1"], None)
+    assert e.value.code == -1
+    Y0 = ctx.ffn24_fwd(d["X"], d["W1"], d["b1"], d["W2"]); g0 = ctx.ffn24_bwd(d["dY"])
+    Yd0 = ctx.ffn_fwd(d["X"], d["W1"], d["b1"], d["W2"]); gd0 = ctx.ffn_bwd(d["dY"])
+    with pytest.raises(F24.Ffn24Error) as e:                 # those calls were given weights: still nothing prepared
+        ctx.ffn_fwd(d["X"], None, d["b1"], None)
+    assert e.value.code == -5
+    ctx.prepare_weights(d["W1"], d["W2"])
+    for _ in range(2):                                       # the prepared state survives the calls that use it
+        Y1 = ctx.ffn24_fwd(d["X"], None, d["b1"], None); g1 = ctx.ffn24_bwd(d["dY"])
+        Yd1 = ctx.ffn_fwd(d["X"], None, d["b1"], None); gd1 = ctx.ffn_bwd(d["dY"])
+        torch.cuda.synchronize()
+        assert torch.equal(Y0, Y1) and all(torch.equal(a, b) for a, b in zip(g0, g1))
+        assert torch.equal(Yd0, Yd1) and all(torch.equal(a, b) for a, b in zip(gd0, gd1))
+    # and the result is the oracle's
+    f = O.ffn24_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"])
+    assert O.max_rel_err(f64(Y1), f["Y"]) <= TOL_BF16
+    ctx.close()
+    # fp8: the same for the byte weights
+    inp8 = synth.make_inputs_fp8(256, 256, 1024, 0.9, seed=102)
+    d8 = {k: torch.from_numpy(inp8[k]).cuda() for k in ("X", "W1", "W2")}
+    b18 = torch.from_numpy(inp8["b1"]).cuda()
+    ctx = F24.Context(256, 256, 1024, F24.FFN24_DENSE, dtype=F24.FFN24_FP8_E4M3)
+    ctx.set_scales(inp8["sx"], inp8["sw1"], inp8["sh"], inp8["sw2"])
+    Ya = ctx.ffn24_fwd(d8["X"], d8["W1"], b18, d8["W2"])
+    ctx.prepare_weights(d8["W1"], d8["W2"])
+    Yb = ctx.ffn24_fwd(d8["X"], None, b18, None)
+    torch.cuda.synchronize()
+    assert torch.equal(Ya, Yb)
     ctx.close()
