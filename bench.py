@@ -297,7 +297,7 @@ def main() -> int:
         else:
             # streaming kernels: feature-wise re-compression moves 4.25 bytes per element of [T, F]; a transpose pair
             # reads and writes 2 x 2 bytes per element of its two matrices
-            # (the forward's weight pass also writes a panel-form copy of W2 when the context trains: 10 D F bytes then)
+            # (the weight pass also writes panel-form copies of W1 and W2 when the context trains: 12 D F bytes then)
             es = 1.0 if fp8 else 2.0
             if name == "quantise_rows":     # reads the bf16 kept values + metadata, writes codes + metadata (+ one scale per token)
                 gbs = (1.0 + 0.125 + 0.5 + 0.125) * T * F / (ms * 1e-3) / 1e9
@@ -306,7 +306,7 @@ def main() -> int:
             if name == "split_partition":
                 kernels[name] = {"ms": round(ms, 4)}
                 continue
-            nbytes = {"featurewise24": 4.25 * T * F, "transpose_weights": (5.0 if bwd else 4.0) * es * D * F, "transpose_acts": 8.0 * T * D,
+            nbytes = {"featurewise24": 4.25 * T * F, "transpose_weights": (6.0 if bwd else 4.0) * es * D * F, "transpose_acts": 8.0 * T * D,
                       "transpose_dw1": 4.0 * D * F}[name]
             gbs = nbytes / (ms * 1e-3) / 1e9
             kernels[name] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / 8000.0, 4)}

@@ -67,7 +67,7 @@ typedef struct ffn24_ctx ffn24_ctx; /* opaque; owns only its device workspace */
 
 /* Create a context for token count T, model dimension D, hidden dimension F.
  * Requires T, D, F to be multiples of 256 (the GEMM tile) and at most 2^20.  Allocates the device workspace with
- * hipMalloc on the current device: about 1.13 T F + 4 D F bytes; plus 3.13 T F + 4 T D + 2 D F with FFN24_TRAINING
+ * hipMalloc on the current device: about 1.13 T F + 4 D F bytes; plus 3.13 T F + 4 T D + 4 D F with FFN24_TRAINING
  * (T F + 2 D F more with FFN24_SPLIT); plus
  * 2 T F with FFN24_DENSE (6 T F more when FFN24_TRAINING is set too); plus 2 T F with FFN24_DEBUG_DUMP_H.
  * *out is untouched on error. */
@@ -141,8 +141,8 @@ FFN24_API int spmm24(const void* values, const uint8_t* meta, const void* Bt, in
 /* Weights that stay the same over many calls (inference; the micro-batches of one optimizer step): runs the weight
  * pass of the forward calls once -- W1 [D][F] and W2 [F][D] are re-arranged into the context's workspace -- after
  * which ffn24_fwd and ffn_fwd accept W1 == NULL and W2 == NULL, meaning "the prepared weights", and skip that pass.
- * A forward call that is given weights runs the pass itself and drops the prepared state.  The caller keeps W1 alive
- * and unchanged while it is prepared (ffn24_bwd and ffn_bwd read it). */
+ * A forward call that is given weights runs the pass itself and drops the prepared state.  The context holds its own
+ * copies: W1 and W2 need not outlive the call's work on the stream. */
 FFN24_API int ffn24_prepare_weights(ffn24_ctx* ctx, const void* W1, const void* W2, void* stream);
 
 /* Forward of the 2:4 FFN (paper Sec. 2):  Z = X W1 + b1;  H = bf16(max(0, Z)^2);  H24 = keep-2-of-4 of H along
@@ -151,8 +151,8 @@ FFN24_API int ffn24_prepare_weights(ffn24_ctx* ctx, const void* W1, const void* 
  *   inputs), W2 [F][D], Y [T][D].  W1 and W2 both NULL: the weights of ffn24_prepare_weights (FFN24_ERR_STATE if none).
  * Kernels: two weight transposes (every GEMM operand is consumed K-contiguous), the dense-MFMA up-projection with
  * the activation and the pruning fused into its epilogue (H is never written densely), the sparse-MFMA
- * down-projection.  The context keeps (Hc, meta), its own copy of W2 and the X and W1 pointers for ffn24_bwd; the
- * caller keeps X and W1 alive and unchanged until then. */
+ * down-projection.  The context keeps (Hc, meta), its own re-arranged copies of W1 and W2 and the X pointer for
+ * ffn24_bwd; the caller keeps X alive and unchanged until then. */
 FFN24_API int ffn24_fwd(ffn24_ctx* ctx, const void* X, const void* W1, const float* b1, const void* W2, void* Y, void* stream);
 
 /* Backward of the last ffn24_fwd on this context, masks held fixed (paper Fig. 4 and Sec. 2, backward paragraphs):

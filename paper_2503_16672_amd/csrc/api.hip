@@ -27,6 +27,7 @@ struct ffn24_ctx {
   void* Hc; uint8_t* meta; void* dZc; void* Hc_t; uint8_t* meta_t; void* dZc_t; void* Hdbg; void* Hd; void* dZd;
   void* W1t; void* W2t; void* Xt; void* dYt; void* Hd_t; void* dZd_t;   // K-contiguous copies of GEMM operands
   void* W2p;   // W2 itself in dense panel form (A operand of the dH GEMMs)
+  void* W1p;   // W1 itself in B panel form (B operand of the dX GEMMs)
   // split weight gradients (FFN24_SPLIT)
   uint32_t* nnz; int* row_of_feat; int* feat_of_row; void* Hdn_t; void* dZdn_t; void* dW1t;
   int n_dense;
@@ -36,11 +37,11 @@ struct ffn24_ctx {
   hipEvent_t tele_ev[2];
   int tele_seq;                 // snapshots enqueued so far
   long long tele_last[5]; int tele_have;   // the newest snapshot that was seen complete
-  // forward state the backward calls read: the caller's X and W1 of the last forward, and which path ran it (the
-  // two paths share the weight workspace, so a forward of one invalidates the saved state of the other)
-  const void *X, *W1;
+  // forward state the backward calls read: the caller's X of the last forward, and which path ran it (the two paths
+  // share the weight workspace, so a forward of one invalidates the saved state of the other)
+  const void* X;
   int have_fwd24, have_fwd_dense;
-  const void* prep_W1;          // ffn24_prepare_weights: the caller's W1 whose re-arranged copies the workspace holds (NULL: none)
+  int prepared;                 // ffn24_prepare_weights: the workspace holds the re-arranged weights of that call
   // profiling
   int profiling;
   hipEvent_t ev[NUM_KERNELS][2];
@@ -63,7 +64,7 @@ struct Timed {
 int free_all(ffn24_ctx* c) {
   int bad = 0;
   void* bufs[] = {c->Hc, c->meta, c->dZc, c->Hc_t, c->meta_t, c->dZc_t, c->Hdbg, c->Hd, c->dZd,
-                  c->W1t, c->W2t, c->Xt, c->dYt, c->Hd_t, c->dZd_t, c->W2p,
+                  c->W1t, c->W2t, c->Xt, c->dYt, c->Hd_t, c->dZd_t, c->W2p, c->W1p,
                   c->nnz, c->row_of_feat, c->feat_of_row, c->Hdn_t, c->dZdn_t, c->dW1t, c->Hc16, c->meta16, c->rowmax, c->rsh, c->perm};
   for (void* b : bufs) if (b && hipFree(b) != hipSuccess) bad = 1;
   if (c->tele && hipFree(c->tele) != hipSuccess) bad = 1;
@@ -91,34 +92,31 @@ int tele_snapshot(ffn24_ctx* c, long long path, hipStream_t s) {
   return FFN24_OK;
 }
 
-// The weight pass: W1 -> W1^T in dense panel form (A operand of the up-projection), W2 -> W2^T (B operand of the
-// down-projection) and, when the context trains, W2 itself in panel form (A operand of the dH GEMM).
+// The weight pass: W1 -> W1^T in dense panel form (A operand of the up-projection), W2 -> W2^T in B panel form (B
+// operand of the down-projection) and, when the context trains, W2 itself in panel form (A operand of the dH GEMM)
+// and W1 itself in B panel form (B operand of the dX GEMM).
 int weight_pass(ffn24_ctx* c, const void* W1, const void* W2, hipStream_t s) {
   int D = (int)c->D, F = (int)c->F;
   Timed t(c, K_TR_W, s);
   int rc1;
   if (c->f8) {
     rc1 = launch_transpose8(W1, D, F, c->W1t, 1, s);
-    if (!rc1) rc1 = launch_transpose8(W2, F, D, c->W2t, 0, s);
+    if (!rc1) rc1 = launch_transpose8(W2, F, D, c->W2t, 2, s);
   } else {
-    rc1 = launch_transpose(W1, D, F, c->W1t, 1, nullptr, nullptr, s);
-    if (!rc1) rc1 = launch_transpose(W2, F, D, c->W2t, 0, c->W2p, nullptr, s);
+    rc1 = launch_transpose(W1, D, F, c->W1t, 1, c->W1p, 1, nullptr, s);
+    if (!rc1) rc1 = launch_transpose(W2, F, D, c->W2t, 2, c->W2p, 0, nullptr, s);
   }
   return t.done(rc1) ? FFN24_ERR_HIP : FFN24_OK;
 }
 
 // Weights of a forward call: both given (run the weight pass; prepared copies are gone after it), or both NULL (use
-// the copies ffn24_prepare_weights left).  On success *W1 is the caller's row-major W1 either way.
-int resolve_weights(ffn24_ctx* c, const void** W1, const void* W2, hipStream_t s) {
-  if (!*W1 && !W2) {
-    if (!c->prep_W1) return FFN24_ERR_STATE;
-    *W1 = c->prep_W1;
-    return FFN24_OK;
-  }
-  if (!*W1 || !W2) return FFN24_ERR_NULL;
-  if (misaligned(*W1) || misaligned(W2)) return FFN24_ERR_ALIGN;
-  c->prep_W1 = nullptr;
-  return weight_pass(c, *W1, W2, s);
+// the copies ffn24_prepare_weights left).
+int resolve_weights(ffn24_ctx* c, const void* W1, const void* W2, hipStream_t s) {
+  if (!W1 && !W2) return c->prepared ? FFN24_OK : FFN24_ERR_STATE;
+  if (!W1 || !W2) return FFN24_ERR_NULL;
+  if (misaligned(W1) || misaligned(W2)) return FFN24_ERR_ALIGN;
+  c->prepared = 0;
+  return weight_pass(c, W1, W2, s);
 }
 
 int check_ptrs(std::initializer_list<const void*> ps) {
@@ -170,7 +168,7 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
   if (ok && (flags & FFN24_TRAINING))
     ok = hipMalloc(&c->dZc, tf) == hipSuccess && hipMalloc(&c->Hc_t, tf) == hipSuccess &&
          hipMalloc(reinterpret_cast<void**>(&c->meta_t), tf / 8) == hipSuccess && hipMalloc(&c->dZc_t, tf) == hipSuccess &&
-         hipMalloc(&c->Xt, 2 * td) == hipSuccess && hipMalloc(&c->dYt, 2 * td) == hipSuccess && hipMalloc(&c->W2p, 2 * df) == hipSuccess;
+         hipMalloc(&c->Xt, 2 * td) == hipSuccess && hipMalloc(&c->dYt, 2 * td) == hipSuccess && hipMalloc(&c->W2p, 2 * df) == hipSuccess && hipMalloc(&c->W1p, 2 * df) == hipSuccess;
   if (ok && (flags & FFN24_TELEMETRY)) {
     ok = hipMalloc(reinterpret_cast<void**>(&c->tele), 8 * TELE_WORDS) == hipSuccess &&
          hipMalloc(reinterpret_cast<void**>(&c->tele_sum), 8 * 5) == hipSuccess &&
@@ -262,10 +260,10 @@ int ffn24_prepare_weights(ffn24_ctx* c, const void* W1, const void* W2, void* st
   if (rc) return rc;
   rc = check_ptrs({W1, W2});
   if (rc) return rc;
-  c->prep_W1 = nullptr;
+  c->prepared = 0;
   c->have_fwd24 = c->have_fwd_dense = 0;
   if ((rc = weight_pass(c, W1, W2, static_cast<hipStream_t>(stream)))) return rc;
-  c->prep_W1 = W1;
+  c->prepared = 1;
   return FFN24_OK;
 }
 
@@ -395,7 +393,7 @@ int spmm24(const void* values, const uint8_t* meta, const void* Bt, int64_t M, i
   if (M <= 0 || N <= 0 || K <= 0 || M % 256 || N % 256 || K % 64 || M > (1 << 20) || N > (1 << 20) || K > (1 << 20)) return FFN24_ERR_SHAPE;
   int rc = check_ptrs({values, meta, Bt, C});
   if (rc) return rc;
-  return launch_sp_rowmajor(values, meta, 0, Bt, (int)M, (int)N, (int)K, C, static_cast<hipStream_t>(stream)) ? FFN24_ERR_HIP : FFN24_OK;
+  return launch_sp_rowmajor(values, meta, 0, Bt, 0, (int)M, (int)N, (int)K, C, static_cast<hipStream_t>(stream)) ? FFN24_ERR_HIP : FFN24_OK;
 }
 
 int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const void* W2, void* Y, void* stream) {
@@ -409,7 +407,7 @@ int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, cons
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   c->have_fwd24 = c->have_fwd_dense = 0;
   if (c->f8 && (c->flags & FFN24_ROWWISE) && !c->rsx) return FFN24_ERR_STATE;
-  if ((rc = resolve_weights(c, &W1, W2, s))) return rc;
+  if ((rc = resolve_weights(c, W1, W2, s))) return rc;
   if (c->f8 && (c->flags & FFN24_ROWWISE)) {
     // row-wise scaling: up-projection (bf16 kept values + row maxima), row-wise quantisation, scaled sparse GEMM
     if (launch_zero32(c->rowmax, (size_t)T, s)) return FFN24_ERR_HIP;
@@ -425,7 +423,7 @@ int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, cons
     { Timed t(c, K_UP, s);
       if (t.done(launch_up_prune24_f8(c->W1t, X, b1, T, D, F, c->sx * c->sw1, c->sh, c->Hc, c->meta, c->Hdbg, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_DOWN, s);
-      if (t.done(launch_sp_rowmajor_f8(c->Hc, c->meta, 1, c->W2t, T, D, F, c->sh * c->sw2, Y, s))) return FFN24_ERR_HIP; }
+      if (t.done(launch_sp_rowmajor_f8(c->Hc, c->meta, 1, c->W2t, 1, T, D, F, c->sh * c->sw2, Y, s))) return FFN24_ERR_HIP; }
     return FFN24_OK;
   }
   uint32_t* nnz = (c->flags & FFN24_SPLIT) && c->n_dense > 0 ? c->nnz : nullptr;
@@ -434,10 +432,10 @@ int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, cons
   const int* perm = c->perm_on ? c->perm : nullptr;   // position p inside the FFN holds token perm[p]
   { Timed t(c, K_UP, s);   if (t.done(launch_up_prune24(c->W1t, X, b1, T, D, F, c->Hc, c->meta, c->Hdbg, nnz, c->tele, perm, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_DOWN, s);
-    int rc1 = perm ? launch_sp_rowmajor_mapped(c->Hc, c->meta, 1, c->W2t, T, D, F, Y, perm, s) : launch_sp_rowmajor(c->Hc, c->meta, 1, c->W2t, T, D, F, Y, s);
+    int rc1 = perm ? launch_sp_rowmajor_mapped(c->Hc, c->meta, 1, c->W2t, 1, T, D, F, Y, perm, s) : launch_sp_rowmajor(c->Hc, c->meta, 1, c->W2t, 1, T, D, F, Y, s);
     if (t.done(rc1)) return FFN24_ERR_HIP; }
   if (c->tele && (rc = tele_snapshot(c, 1, s))) return rc;
-  c->X = X; c->W1 = W1; c->have_fwd24 = 1;
+  c->X = X; c->have_fwd24 = 1;
   return FFN24_OK;
 }
 
@@ -455,7 +453,7 @@ int ffn24_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void
   if (c->tele && launch_zero32(reinterpret_cast<uint32_t*>(c->tele + tele_index(TELE_KEPT_FEAT, 0)), 2 * TELE_SLOTS * TELE_STRIDE, s)) return FFN24_ERR_HIP;
   { Timed t(c, K_DH, s);  if (t.done(launch_dh_gather(c->W2p, dY, c->Hc, c->meta, T, D, F, c->dZc, perm, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_DX, s);
-    int rc1 = perm ? launch_sp_rowmajor_mapped(c->dZc, c->meta, 1, c->W1, T, D, F, dX, perm, s) : launch_sp_rowmajor(c->dZc, c->meta, 1, c->W1, T, D, F, dX, s);
+    int rc1 = perm ? launch_sp_rowmajor_mapped(c->dZc, c->meta, 1, c->W1p, 1, T, D, F, dX, perm, s) : launch_sp_rowmajor(c->dZc, c->meta, 1, c->W1p, 1, T, D, F, dX, s);
     if (t.done(rc1)) return FFN24_ERR_HIP; }
   const bool split = (c->flags & FFN24_SPLIT) && c->n_dense > 0;
   if (split) {
@@ -468,20 +466,20 @@ int ffn24_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void
         return FFN24_ERR_HIP; }
     if (c->tele && (rc = tele_snapshot(c, 1, s))) return rc;
     { Timed t(c, K_TR_ACT, s);
-      int rc1 = launch_transpose(dY, T, D, c->dYt, 0, nullptr, perm, s);
-      if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, 0, nullptr, perm, s))) return FFN24_ERR_HIP; }
+      int rc1 = launch_transpose(dY, T, D, c->dYt, 2, nullptr, 0, perm, s);
+      if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, 2, nullptr, 0, perm, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_DW2, s); if (t.done(launch_split_wgrad(c->Hc_t, c->meta_t, ns, c->Hdn_t, nd, c->dYt, D, T, dW2, D, c->feat_of_row, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_DW1, s); if (t.done(launch_split_wgrad(c->dZc_t, c->meta_t, ns, c->dZdn_t, nd, c->Xt, D, T, c->dW1t, D, c->feat_of_row, s))) return FFN24_ERR_HIP; }
-    { Timed t(c, K_TR_DW1, s); if (t.done(launch_transpose(c->dW1t, F, D, dW1, 0, nullptr, nullptr, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_TR_DW1, s); if (t.done(launch_transpose(c->dW1t, F, D, dW1, 0, nullptr, 0, nullptr, s))) return FFN24_ERR_HIP; }
     return FFN24_OK;
   }
   { Timed t(c, K_FW, s);  if (t.done(launch_featurewise24(c->Hc, c->meta, c->dZc, T, F, c->Hc_t, c->meta_t, c->dZc_t, 1, c->tele, s))) return FFN24_ERR_HIP; }
   if (c->tele && (rc = tele_snapshot(c, 1, s))) return rc;
   { Timed t(c, K_TR_ACT, s);
-    int rc1 = launch_transpose(dY, T, D, c->dYt, 0, nullptr, perm, s);
-    if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, 0, nullptr, perm, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, K_DW2, s); if (t.done(launch_sp_rowmajor(c->Hc_t, c->meta_t, 1, c->dYt, F, D, T, dW2, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, K_DW1, s); if (t.done(launch_sp_colmajor(c->dZc_t, c->meta_t, 1, c->Xt, F, D, T, dW1, s))) return FFN24_ERR_HIP; }
+    int rc1 = launch_transpose(dY, T, D, c->dYt, 2, nullptr, 0, perm, s);
+    if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, 2, nullptr, 0, perm, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_DW2, s); if (t.done(launch_sp_rowmajor(c->Hc_t, c->meta_t, 1, c->dYt, 1, F, D, T, dW2, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_DW1, s); if (t.done(launch_sp_colmajor(c->dZc_t, c->meta_t, 1, c->Xt, 1, F, D, T, dW1, s))) return FFN24_ERR_HIP; }
   return FFN24_OK;
 }
 
@@ -496,19 +494,19 @@ int ffn_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const 
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   c->have_fwd24 = c->have_fwd_dense = 0;
-  if ((rc = resolve_weights(c, &W1, W2, s))) return rc;
+  if ((rc = resolve_weights(c, W1, W2, s))) return rc;
   if (c->f8) {
     { Timed t(c, KD_UP, s);
       if (t.done(launch_up_relu2_f8(c->W1t, X, b1, T, D, F, c->sx * c->sw1, c->sh, c->Hd, s))) return FFN24_ERR_HIP; }
     { Timed t(c, KD_DOWN, s);
-      if (t.done(launch_dense_rowmajor_f8(c->Hd, 1, c->W2t, T, D, F, c->sh * c->sw2, Y, s))) return FFN24_ERR_HIP; }
+      if (t.done(launch_dense_rowmajor_f8(c->Hd, 1, c->W2t, 1, T, D, F, c->sh * c->sw2, Y, s))) return FFN24_ERR_HIP; }
     return FFN24_OK;
   }
   if (c->tele && launch_zero32(reinterpret_cast<uint32_t*>(c->tele), 2 * TELE_WORDS, s)) return FFN24_ERR_HIP;
   { Timed t(c, KD_UP, s);   if (t.done(launch_up_relu2(c->W1t, X, b1, T, D, F, c->Hd, c->Hd_t, c->tele, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, KD_DOWN, s); if (t.done(launch_dense_rowmajor(c->Hd, 1, c->W2t, T, D, F, Y, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_DOWN, s); if (t.done(launch_dense_rowmajor(c->Hd, 1, c->W2t, 1, T, D, F, Y, s))) return FFN24_ERR_HIP; }
   if (c->tele && (rc = tele_snapshot(c, 0, s))) return rc;
-  c->X = X; c->W1 = W1; c->have_fwd_dense = 1;
+  c->X = X; c->have_fwd_dense = 1;
   return FFN24_OK;
 }
 
@@ -522,12 +520,12 @@ int ffn_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void* 
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   { Timed t(c, KD_DH, s);  if (t.done(launch_dh_drelu(c->W2p, dY, c->Hd, T, D, F, c->dZd, c->dZd_t, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, KD_DX, s);  if (t.done(launch_dense_rowmajor(c->dZd, 1, c->W1, T, D, F, dX, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_DX, s);  if (t.done(launch_dense_rowmajor(c->dZd, 1, c->W1p, 1, T, D, F, dX, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_TR_ACT, s);
-    int rc1 = launch_transpose(dY, T, D, c->dYt, 0, nullptr, nullptr, s);
-    if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, 0, nullptr, nullptr, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, KD_DW2, s); if (t.done(launch_dense_rowmajor(c->Hd_t, 1, c->dYt, F, D, T, dW2, s))) return FFN24_ERR_HIP; }
-  { Timed t(c, KD_DW1, s); if (t.done(launch_dense_colmajor(c->dZd_t, 1, c->Xt, F, D, T, dW1, s))) return FFN24_ERR_HIP; }
+    int rc1 = launch_transpose(dY, T, D, c->dYt, 2, nullptr, 0, nullptr, s);
+    if (t.done(rc1 ? rc1 : launch_transpose(c->X, T, D, c->Xt, 2, nullptr, 0, nullptr, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_DW2, s); if (t.done(launch_dense_rowmajor(c->Hd_t, 1, c->dYt, 1, F, D, T, dW2, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_DW1, s); if (t.done(launch_dense_colmajor(c->dZd_t, 1, c->Xt, 1, F, D, T, dW1, s))) return FFN24_ERR_HIP; }
   return FFN24_OK;
 }
 

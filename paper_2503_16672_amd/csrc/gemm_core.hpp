@@ -74,7 +74,15 @@ struct GemmArgs {
   int M, N, K;           // K is the dense reduction length
   int a_panel;           // A (and its metadata) is in panel form (see above) instead of row-major
   const int* b_rowmap;   // optional: row n of B is taken from memory row b_rowmap[n] (token permutation, gathered by the DMA)
+  int b_panel;           // B is in the B panel form (below) instead of row-major; not together with b_rowmap
 };
+
+// B panel form: the dense panel form (64-byte pieces, a24_piece) whose rows are, inside every block of 256, stored in the
+// order the block tile keeps them in LDS: position q of a block holds row unperm_n(q), i.e. row n sits at b_panel_pos(n).
+// A stage of a block tile's B operand is then one (sparse: two) contiguous 16 KiB run(s), and every DMA instruction
+// reads whole 128-byte lines.  Used for every B operand the library makes itself (re-arranged weights, transposed
+// activations); a caller's row-major B (spmm24; X and dY) is read as it is.
+__host__ __device__ __forceinline__ int b_panel_pos(int n) { return (n & ~255) | ((n & 3) << 5) | ((n >> 2) & 31) | (n & 128); }
 
 // piece index of row r, 64-k panel kp, for an operand with `npanels` = K / 64 panels per row
 __host__ __device__ __forceinline__ size_t a24_piece(int r, int kp, int npanels) {
@@ -141,7 +149,7 @@ struct Dma {
   const char* am;     // metadata
   const char* b;
   uint32_t va[4], vm[2], vb[SPARSE ? 8 : 4];   // per-lane byte offsets from the uniform bases
-  uint32_t a_stage, m_stage;                   // bytes from one stage to the next in the A values / metadata stream
+  uint32_t a_stage, m_stage, b_stage;          // bytes from one stage to the next in the A values / metadata / B stream
   int wave;
 
   __device__ __forceinline__ void init(const GemmArgs& g, int m0, int n0, int tid) {
@@ -157,19 +165,26 @@ struct Dma {
     const uint32_t a_pitch = panel ? 64u : a_row, m_pitch = panel ? (uint32_t)G::META_ROW : (uint32_t)(g.K / 8);
     a_stage = panel ? 256u * 64u : 64u;
     m_stage = panel ? 256u * G::META_ROW : (uint32_t)G::META_ROW;
+    const bool bp = g.b_panel != 0;
+    b_stage = bp ? 256u * (uint32_t)G::B_ROW : (uint32_t)G::B_ROW;
 #pragma unroll
     for (int j = 0; j < 4; j++) {
       int p = 64 * wave + 16 * j + (lane >> 2);
       int c = (lane & 3) ^ swz4(p);
       va[j] = (uint32_t)unperm_m(p) * a_pitch + c * 16;
-      if constexpr (!SPARSE) vb[j] = (g.b_rowmap ? (uint32_t)g.b_rowmap[n0 + unperm_n(p)] : (uint32_t)unperm_n(p)) * b_row + c * 16;
+      if constexpr (!SPARSE) {
+        if (bp) vb[j] = (uint32_t)p * 64u + c * 16;     // LDS row p is piece p of the block's 16 KiB run
+        else vb[j] = (g.b_rowmap ? (uint32_t)g.b_rowmap[n0 + unperm_n(p)] : (uint32_t)unperm_n(p)) * b_row + c * 16;
+      }
     }
     if constexpr (SPARSE) {
 #pragma unroll
       for (int j = 0; j < 8; j++) {
         int p = 64 * wave + 8 * j + (lane >> 3);
         int c = (lane & 7) ^ swz8(p);
-        vb[j] = (g.b_rowmap ? (uint32_t)g.b_rowmap[n0 + unperm_n(p)] : (uint32_t)unperm_n(p)) * b_row + c * 16;
+        // panel: the row's 128 bytes are two 64-byte pieces in consecutive 16 KiB runs
+        if (bp) vb[j] = (uint32_t)(c >> 2) * (256u * 64u) + (uint32_t)p * 64u + (c & 3) * 16;
+        else vb[j] = (g.b_rowmap ? (uint32_t)g.b_rowmap[n0 + unperm_n(p)] : (uint32_t)unperm_n(p)) * b_row + c * 16;
       }
       if constexpr (F8) {
         vm[0] = (uint32_t)unperm_m(64 * wave + lane) * m_pitch;      // one row's 16 metadata bytes per lane
@@ -191,7 +206,7 @@ struct Dma {
       __builtin_amdgcn_global_load_lds((glb_char*)(a + (size_t)kt * a_stage + va[J]), (lds_char*)(buf + (4 * wave + J) * 1024), 16, 0, 0);
     } else if constexpr (!SPARSE) {
       constexpr int j = J - 4;
-      __builtin_amdgcn_global_load_lds((glb_char*)(b + (size_t)kt * 64 + vb[j]), (lds_char*)(buf + G::B_OFF + (4 * wave + j) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_char*)(b + (size_t)kt * b_stage + vb[j]), (lds_char*)(buf + G::B_OFF + (4 * wave + j) * 1024), 16, 0, 0);
     } else if constexpr (J < 4 + G::NM) {
       constexpr int j = J - 4;
       if constexpr (F8)
@@ -200,7 +215,7 @@ struct Dma {
         __builtin_amdgcn_global_load_lds((glb_char*)(am + (size_t)kt * m_stage + vm[j]), (lds_char*)(buf + G::META_OFF + (2 * wave + j) * 256), 4, 0, 0);
     } else {
       constexpr int j = J - 4 - G::NM;
-      __builtin_amdgcn_global_load_lds((glb_char*)(b + (size_t)kt * 128 + vb[j]), (lds_char*)(buf + G::B_OFF + (8 * wave + j) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_char*)(b + (size_t)kt * b_stage + vb[j]), (lds_char*)(buf + G::B_OFF + (8 * wave + j) * 1024), 16, 0, 0);
     }
   }
   __device__ __forceinline__ void issue_all(int kt, char* buf) const {

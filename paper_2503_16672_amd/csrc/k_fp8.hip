@@ -17,14 +17,14 @@ int launch_up_relu2_f8(const void* W1t8, const void* X8, const float* b1, int T,
   return launch_gemm<false, EpiRelu2F8, true>(g, ea, s);
 }
 
-int launch_sp_rowmajor_f8(const void* vals8, const uint8_t* meta, int a_panel, const void* B8, int M, int N, int K, float scale, void* C, hipStream_t s) {
-  GemmArgs g{vals8, meta, B8, M, N, K, a_panel};
+int launch_sp_rowmajor_f8(const void* vals8, const uint8_t* meta, int a_panel, const void* B8, int b_panel, int M, int N, int K, float scale, void* C, hipStream_t s) {
+  GemmArgs g{vals8, meta, B8, M, N, K, a_panel, nullptr, b_panel};
   EpiRowMajorScaled::Args ea{static_cast<__bf16*>(C), N, scale};
   return launch_gemm<true, EpiRowMajorScaled, true>(g, ea, s);
 }
 
-int launch_dense_rowmajor_f8(const void* A8, int a_panel, const void* B8, int M, int N, int K, float scale, void* C, hipStream_t s) {
-  GemmArgs g{A8, nullptr, B8, M, N, K, a_panel};
+int launch_dense_rowmajor_f8(const void* A8, int a_panel, const void* B8, int b_panel, int M, int N, int K, float scale, void* C, hipStream_t s) {
+  GemmArgs g{A8, nullptr, B8, M, N, K, a_panel, nullptr, b_panel};
   EpiRowMajorScaled::Args ea{static_cast<__bf16*>(C), N, scale};
   return launch_gemm<false, EpiRowMajorScaled, true>(g, ea, s);
 }
@@ -39,7 +39,7 @@ int launch_up_prune24_f8_rowwise(const void* W1t8, const void* X8, const float* 
 
 int launch_sp_rowmajor_f8_rowwise(const void* vals8, const uint8_t* meta, const void* B8, int M, int N, int K, const float* rs, const float* cs,
                                   void* C, hipStream_t s) {
-  GemmArgs g{vals8, meta, B8, M, N, K, 1};
+  GemmArgs g{vals8, meta, B8, M, N, K, 1, nullptr, 1};
   EpiRowMajorRowCol::Args ea{static_cast<__bf16*>(C), N, rs, cs};
   return launch_gemm<true, EpiRowMajorRowCol, true>(g, ea, s);
 }

@@ -15,15 +15,15 @@ int launch_up_prune24(const void* W1t, const void* X, const float* b1, int T, in
   return launch_gemm<false, EpiPrune24>(g, ea, s);
 }
 
-int launch_sp_rowmajor(const void* vals, const uint8_t* meta, int a_panel, const void* B, int M, int N, int K, void* C, hipStream_t s) {
-  GemmArgs g{vals, meta, B, M, N, K, a_panel};
+int launch_sp_rowmajor(const void* vals, const uint8_t* meta, int a_panel, const void* B, int b_panel, int M, int N, int K, void* C, hipStream_t s) {
+  GemmArgs g{vals, meta, B, M, N, K, a_panel, nullptr, b_panel};
   EpiRowMajor::Args ea{static_cast<__bf16*>(C), N};
   return launch_gemm<true, EpiRowMajor>(g, ea, s);
 }
 
-int launch_sp_rowmajor_mapped(const void* vals, const uint8_t* meta, int a_panel, const void* B, int M, int N, int K, void* C,
+int launch_sp_rowmajor_mapped(const void* vals, const uint8_t* meta, int a_panel, const void* B, int b_panel, int M, int N, int K, void* C,
                               const int* rowmap, hipStream_t s) {
-  GemmArgs g{vals, meta, B, M, N, K, a_panel};
+  GemmArgs g{vals, meta, B, M, N, K, a_panel, nullptr, b_panel};
   EpiRowMajorMapped::Args ea{static_cast<__bf16*>(C), N, rowmap};
   return launch_gemm<true, EpiRowMajorMapped>(g, ea, s);
 }

@@ -341,14 +341,15 @@ int launch_unpanel(const void* src, int rows, int npanels, int piece_bytes, void
 // out[c][r] = in[r][c] for a bf16 matrix [R][C], R and C multiples of 64.  One workgroup per 64x64 tile: rows are
 // read 128 bytes at a time, scattered into an LDS tile with a 132-byte pitch (conflict-free for this pattern), and
 // written out as 128-byte rows of the transposed matrix.
-// OUT_PANEL: the transposed matrix is written in the dense panel form of gemm_core.hpp (64-byte pieces of 32 k, K = R).
-// in_panel (optional): a copy of the input itself in panel form (K = C), made in the same pass.
+// OUT_FORM: 0 row-major; 1 the dense panel form of gemm_core.hpp (64-byte pieces of 32 k, K = R), as A operands take it;
+// 2 the B panel form (the same with the rows of every block of 256 in LDS order).
+// in_panel (optional): a copy of the input itself in panel form (K = C), made in the same pass; in_panel_b: in the B form.
 // in_rowmap (optional): input row r is read from memory row in_rowmap[r] (token permutation).
 constexpr int TR_LD = 66;
 
-template <bool OUT_PANEL>
+template <int OUT_FORM>
 __global__ void __launch_bounds__(256) transpose_kernel(const uint16_t* __restrict__ in, int R, int C, uint16_t* __restrict__ out,
-                                                        uint16_t* __restrict__ in_panel, const int* __restrict__ in_rowmap) {
+                                                        uint16_t* __restrict__ in_panel, int in_panel_b, const int* __restrict__ in_rowmap) {
   __shared__ __attribute__((aligned(16))) uint16_t sT[64 * TR_LD];
   int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
   int tid = threadIdx.x;
@@ -360,7 +361,8 @@ __global__ void __launch_bounds__(256) transpose_kernel(const uint16_t* __restri
     u32x4 v = *reinterpret_cast<const u32x4*>(in + src_row * C + c0 + 8 * ch);
     if (in_panel) {
       int c = c0 + 8 * ch;
-      *reinterpret_cast<u32x4*>(in_panel + a24_piece(r0 + r, c >> 5, C >> 5) * 32 + (c & 31)) = v;
+      int prow = in_panel_b ? b_panel_pos(r0 + r) : r0 + r;
+      *reinterpret_cast<u32x4*>(in_panel + a24_piece(prow, c >> 5, C >> 5) * 32 + (c & 31)) = v;
     }
 #pragma unroll
     for (int d = 0; d < 4; d++) {
@@ -375,23 +377,25 @@ __global__ void __launch_bounds__(256) transpose_kernel(const uint16_t* __restri
     const uint32_t* src = reinterpret_cast<const uint32_t*>(&sT[c * TR_LD + 8 * ch]);
     u32x4 v = {src[0], src[1], src[2], src[3]};
     int r = r0 + 8 * ch;
-    if constexpr (OUT_PANEL) *reinterpret_cast<u32x4*>(out + a24_piece(c0 + c, r >> 5, R >> 5) * 32 + (r & 31)) = v;
+    if constexpr (OUT_FORM == 1) *reinterpret_cast<u32x4*>(out + a24_piece(c0 + c, r >> 5, R >> 5) * 32 + (r & 31)) = v;
+    else if constexpr (OUT_FORM == 2) *reinterpret_cast<u32x4*>(out + a24_piece(b_panel_pos(c0 + c), r >> 5, R >> 5) * 32 + (r & 31)) = v;
     else *reinterpret_cast<u32x4*>(out + (size_t)(c0 + c) * R + r) = v;
   }
 }
 
-int launch_transpose(const void* in, int R, int C, void* out, int out_panel, void* in_panel, const int* in_rowmap, hipStream_t s) {
+int launch_transpose(const void* in, int R, int C, void* out, int out_form, void* in_panel, int in_panel_b, const int* in_rowmap, hipStream_t s) {
   dim3 grid(C / 64, R / 64);
-  auto kern = out_panel ? transpose_kernel<true> : transpose_kernel<false>;
+  auto kern = out_form == 2 ? transpose_kernel<2> : (out_form == 1 ? transpose_kernel<1> : transpose_kernel<0>);
   hipLaunchKernelGGL(kern, grid, dim3(256), 0, s, static_cast<const uint16_t*>(in), R, C, static_cast<uint16_t*>(out),
-                     static_cast<uint16_t*>(in_panel), in_rowmap);
+                     static_cast<uint16_t*>(in_panel), in_panel_b, in_rowmap);
   return (int)hipGetLastError();
 }
 
 // Byte-matrix transpose (fp8 weights): out[c][r] = in[r][c], in [R][C], R and C multiples of 64.  One workgroup per
 // 64 x 64 tile; a work item reads 16 bytes of a row, scatters them into an LDS tile (pitch 68 bytes), then reads 16
-// bytes of a transposed row and writes them out.  OUT_PANEL: dense panel form, 64-byte pieces of 64 k (K = R).
-template <bool OUT_PANEL>
+// bytes of a transposed row and writes them out.  OUT_FORM: 0 row-major, 1 dense panel form (64-byte pieces of 64 k,
+// K = R), 2 the B panel form.
+template <int OUT_FORM>
 __global__ void __launch_bounds__(256) transpose8_kernel(const uint8_t* __restrict__ in, int R, int C, uint8_t* __restrict__ out) {
   __shared__ __attribute__((aligned(16))) uint8_t sT[64 * 68];
   int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
@@ -407,13 +411,14 @@ __global__ void __launch_bounds__(256) transpose8_kernel(const uint8_t* __restri
   const uint32_t* src = reinterpret_cast<const uint32_t*>(&sT[c * 68 + 16 * ch]);
   u32x4 o = {src[0], src[1], src[2], src[3]};
   int r = r0 + 16 * ch;
-  if constexpr (OUT_PANEL) *reinterpret_cast<u32x4*>(out + a24_piece(c0 + c, r >> 6, R >> 6) * 64 + (r & 63)) = o;
+  if constexpr (OUT_FORM == 1) *reinterpret_cast<u32x4*>(out + a24_piece(c0 + c, r >> 6, R >> 6) * 64 + (r & 63)) = o;
+  else if constexpr (OUT_FORM == 2) *reinterpret_cast<u32x4*>(out + a24_piece(b_panel_pos(c0 + c), r >> 6, R >> 6) * 64 + (r & 63)) = o;
   else *reinterpret_cast<u32x4*>(out + (size_t)(c0 + c) * R + r) = o;
 }
 
-int launch_transpose8(const void* in, int R, int C, void* out, int out_panel, hipStream_t s) {
+int launch_transpose8(const void* in, int R, int C, void* out, int out_form, hipStream_t s) {
   dim3 grid(C / 64, R / 64);
-  auto kern = out_panel ? transpose8_kernel<true> : transpose8_kernel<false>;
+  auto kern = out_form == 2 ? transpose8_kernel<2> : (out_form == 1 ? transpose8_kernel<1> : transpose8_kernel<0>);
   hipLaunchKernelGGL(kern, grid, dim3(256), 0, s, static_cast<const uint8_t*>(in), R, C, static_cast<uint8_t*>(out));
   return (int)hipGetLastError();
 }

@@ -42,19 +42,20 @@ __host__ __device__ constexpr int tele_index(int kind, int slot) { return (kind 
 int launch_up_prune24(const void* W1t, const void* X, const float* b1, int T, int D, int F,
                       void* Hc, uint8_t* meta, void* Hdbg, uint32_t* nnz, unsigned long long* tele, const int* token_map, hipStream_t s);
 int launch_up_relu2(const void* W1t, const void* X, const float* b1, int T, int D, int F, void* H, void* Ht, unsigned long long* tele, hipStream_t s);
-// C[M][N] = A24[M][K] * B[N][K]^T; a_panel: (vals, meta) are in panel form instead of row-major
-int launch_sp_rowmajor(const void* vals, const uint8_t* meta, int a_panel, const void* B, int M, int N, int K, void* C, hipStream_t s);
+// C[M][N] = A24[M][K] * B[N][K]^T; a_panel: (vals, meta) are in panel form instead of row-major;
+// b_panel (also below): B is in the B panel form of gemm_core.hpp instead of row-major
+int launch_sp_rowmajor(const void* vals, const uint8_t* meta, int a_panel, const void* B, int b_panel, int M, int N, int K, void* C, hipStream_t s);
 // out[N][M] = (A24[M][K] * B[N][K]^T)^T
-int launch_sp_colmajor(const void* vals, const uint8_t* meta, int a_panel, const void* B, int M, int N, int K, void* Ct, hipStream_t s);
+int launch_sp_colmajor(const void* vals, const uint8_t* meta, int a_panel, const void* B, int b_panel, int M, int N, int K, void* Ct, hipStream_t s);
 // dH = dY W2^T with rows = hidden features: A = W2 [F][D] in dense panel form, B = dY [T][D]; pointwise part fused
 int launch_dh_gather(const void* W2, const void* dY, const void* Hc, const uint8_t* meta, int T, int D, int F, void* dZc,
                      const int* token_map, hipStream_t s);
 // C[rowmap[m]][N] = (A24 * B^T)[m][N]: the result rows go back to their tokens
-int launch_sp_rowmajor_mapped(const void* vals, const uint8_t* meta, int a_panel, const void* B, int M, int N, int K, void* C,
+int launch_sp_rowmajor_mapped(const void* vals, const uint8_t* meta, int a_panel, const void* B, int b_panel, int M, int N, int K, void* C,
                               const int* rowmap, hipStream_t s);
 int launch_dh_drelu(const void* W2, const void* dY, const void* H, int T, int D, int F, void* dZ, void* dZt, hipStream_t s);
 // split weight gradient (operands in panel form): rows [0, ns) from the sparse GEMM over (vals, meta) [ns][K], rows
-// [ns, ns + nd) from the dense GEMM over Ad [nd][K], both against B [N][K], one launch; row m goes to C[rowmap[m]][*]
+// [ns, ns + nd) from the dense GEMM over Ad [nd][K], both against B [N][K] (B panel form), one launch; row m goes to C[rowmap[m]][*]
 int launch_split_wgrad(const void* vals, const uint8_t* meta, int ns, const void* Ad, int nd, const void* B, int N, int K,
                        void* C, int ldc, const int* rowmap, hipStream_t s);
 // feature partition for the split (one workgroup): the n_dense features with the largest counts (ties: lower index)
@@ -66,15 +67,15 @@ int launch_split_partition(const uint32_t* nnz, int F, int n_dense, int max_coun
 int launch_featurewise24_split(const void* Hc, const uint8_t* meta, const void* dZc, int T, int F, const int* row_of_feat, int n_sparse,
                                void* Hc_t, uint8_t* meta_t, void* dZc_t, void* Hdn_t, void* dZdn_t, unsigned long long* tele, hipStream_t s);
 // dense GEMMs: A [M][K] (a_panel: in dense panel form), B [N][K]
-int launch_dense_rowmajor(const void* A, int a_panel, const void* B, int M, int N, int K, void* C, hipStream_t s);
-int launch_dense_colmajor(const void* A, int a_panel, const void* B, int M, int N, int K, void* Ct, hipStream_t s);
+int launch_dense_rowmajor(const void* A, int a_panel, const void* B, int b_panel, int M, int N, int K, void* C, hipStream_t s);
+int launch_dense_colmajor(const void* A, int a_panel, const void* B, int b_panel, int M, int N, int K, void* Ct, hipStream_t s);
 // fp8 e4m3 forward (per-tensor scales).  W1t8 [F][D] in dense panel form (64-byte pieces = 64 k), X8 [T][D];
 // compressed activation in the fp8 panel form (64 stored bytes + 16 metadata bytes per 128 k); bf16 results.
 int launch_up_prune24_f8(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, float zscale, float sh,
                          void* Hc8, uint8_t* meta, void* Hdbg, hipStream_t s);
 int launch_up_relu2_f8(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, float zscale, float sh, void* H8, hipStream_t s);
-int launch_sp_rowmajor_f8(const void* vals8, const uint8_t* meta, int a_panel, const void* B8, int M, int N, int K, float scale, void* C, hipStream_t s);
-int launch_dense_rowmajor_f8(const void* A8, int a_panel, const void* B8, int M, int N, int K, float scale, void* C, hipStream_t s);
+int launch_sp_rowmajor_f8(const void* vals8, const uint8_t* meta, int a_panel, const void* B8, int b_panel, int M, int N, int K, float scale, void* C, hipStream_t s);
+int launch_dense_rowmajor_f8(const void* A8, int a_panel, const void* B8, int b_panel, int M, int N, int K, float scale, void* C, hipStream_t s);
 // row-wise-scaled fp8 forward: sx [T], sw1 [F], sw2 [N]; the up-projection writes bf16 kept values (bf16 panel form)
 // and raises rowmax [T] (bf16 words; zeroed by the caller); quantise_rows turns them into the fp8 panel form with
 // sh[t] = rowmax[t] / 448 (1 for an all-zero row), which it also writes out
@@ -94,11 +95,12 @@ int launch_featurewise24(const void* Hc, const uint8_t* meta, const void* dZc, i
 int launch_tele_sum(const unsigned long long* tele, long long elements, long long path, long long* out, hipStream_t s);
 // panel form -> row-major copy of a compressed operand: rows x npanels pieces of `piece_bytes` (64 values / 8 or 16 metadata)
 int launch_unpanel(const void* src, int rows, int npanels, int piece_bytes, void* dst, hipStream_t s);
-// in [R][C] -> out [C][R] (R, C % 64 == 0); out_panel: out is written in dense panel form (then C % 256 == 0);
-// in_panel (may be NULL): also a panel-form copy of `in` itself (then R % 256 == 0)
+// in [R][C] -> out [C][R] (R, C % 64 == 0); out_form: 0 row-major, 1 dense panel form (A operands), 2 B panel form
+// (gemm_core.hpp; both then need C % 256 == 0);
+// in_panel (may be NULL): also a panel-form copy of `in` itself (then R % 256 == 0), in the B form if in_panel_b
 // in_rowmap (may be NULL): row r of the input is taken from memory row in_rowmap[r]
-int launch_transpose(const void* in, int R, int C, void* out, int out_panel, void* in_panel, const int* in_rowmap, hipStream_t s);
-// the same for 1-byte elements (fp8): in [R][C] -> out [C][R]; out_panel: 64-byte pieces of 64 k
-int launch_transpose8(const void* in, int R, int C, void* out, int out_panel, hipStream_t s);
+int launch_transpose(const void* in, int R, int C, void* out, int out_form, void* in_panel, int in_panel_b, const int* in_rowmap, hipStream_t s);
+// the same for 1-byte elements (fp8): in [R][C] -> out [C][R]; panel forms: 64-byte pieces of 64 k
+int launch_transpose8(const void* in, int R, int C, void* out, int out_form, hipStream_t s);
 
 }  // namespace ffn24
