@@ -17,6 +17,21 @@ __device__ __forceinline__ void tele_add2(unsigned long long* tele, uint32_t pac
   }
 }
 
+// A per-feature fp32 vector (bias, weight scale) over the lane's 64 features m_lane .. m_lane + 63, loaded once with
+// 16-byte loads and shared by the lane's 4 tokens; `fill` everywhere if the vector is absent.
+struct LaneVec64 {
+  f32x4 v[16];
+  __device__ __forceinline__ void load(const float* p, int m_lane, float fill) {
+#pragma unroll
+    for (int i = 0; i < 16; i++) v[i] = f32x4{fill, fill, fill, fill};
+    if (p) {
+#pragma unroll
+      for (int i = 0; i < 16; i++) v[i] = *reinterpret_cast<const f32x4*>(p + m_lane + 4 * i);
+    }
+  }
+  __device__ __forceinline__ float at(int i) const { return v[i >> 2][i & 3]; }   // feature m_lane + i
+};
+
 // C[m][n], n contiguous: 4 consecutive columns per lane and row -> one 8-byte store per row.
 struct EpiRowMajor {
   struct Args { __bf16* C; int ldc; };
@@ -64,16 +79,15 @@ struct EpiRelu2T {
   struct Args { __bf16* H; __bf16* Ht; const float* b1; int F; int T; unsigned long long* tele; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
     uint32_t nonzero = 0u;   // of this lane's 256 activations
+    LaneVec64 lb;
+    lb.load(e.b1, m_lane, 0.f);
 #pragma unroll
     for (int mi = 0; mi < 4; mi++) {
-      float bias[16];
-#pragma unroll
-      for (int v = 0; v < 16; v++) bias[v] = e.b1 ? e.b1[m_lane + 16 * mi + v] : 0.f;
 #pragma unroll
       for (int ni = 0; ni < 4; ni++) {
 #pragma unroll
         for (int v = 0; v < 16; v++) {
-          float r = fmaxf(acc[mi][ni][v] + bias[v], 0.f);
+          float r = fmaxf(acc[mi][ni][v] + lb.at(16 * mi + v), 0.f);
           acc[mi][ni][v] = r * r;
         }
         int f = m_lane + 16 * mi;
@@ -128,6 +142,8 @@ struct EpiPrune24T {
     uint32_t kept = 0u;   // non-zero values among the lane's 128 stored ones
 #pragma unroll
     for (int i = 0; i < 16; i++) cnt[i] = 0u;
+    LaneVec64 lb;
+    lb.load(e.b1, m_lane, 0.f);
 #pragma unroll
     for (int ni = 0; ni < 4; ni++) {
       size_t t = (size_t)(n_lane + ni);
@@ -138,8 +154,7 @@ struct EpiPrune24T {
         uint32_t hpk[8];
 #pragma unroll
         for (int d = 0; d < 8; d++) {
-          float b0 = e.b1 ? e.b1[m_lane + 16 * mi + 2 * d] : 0.f;
-          float b1v = e.b1 ? e.b1[m_lane + 16 * mi + 2 * d + 1] : 0.f;
+          float b0 = lb.at(16 * mi + 2 * d), b1v = lb.at(16 * mi + 2 * d + 1);
           float r0 = fmaxf(acc[mi][ni][2 * d] + b0, 0.f);
           float r1 = fmaxf(acc[mi][ni][2 * d + 1] + b1v, 0.f);
           hpk[d] = pack_bf16x2(r0 * r0, r1 * r1);
@@ -157,16 +172,12 @@ struct EpiPrune24T {
 #pragma unroll
         for (int a = 0; a < 4; a++) {
           // h >= 0, so the storage word is its own magnitude
-          uint32_t k0 = ((hpk[2 * a] & 0xFFFFu) << 2) | 3u;
-          uint32_t k1 = ((hpk[2 * a] >> 16) << 2) | 2u;
-          uint32_t k2 = ((hpk[2 * a + 1] & 0xFFFFu) << 2) | 1u;
-          uint32_t k3 = ((hpk[2 * a + 1] >> 16) << 2);
-          uint32_t kf, ks;
-          uint32_t n4 = pick24_keys(k0, k1, k2, k3, kf, ks);
+          uint32_t pair;
+          uint32_t n4 = pick24_packed(hpk[2 * a], hpk[2 * a + 1], pair);
           int gi = 4 * mi + a;
-          vals[gi] = (kf >> 2) | ((ks >> 2) << 16);
+          vals[gi] = pair;
           nib[gi >> 3] |= n4 << (4 * (gi & 7));
-          if constexpr (STATS) kept += min(kf >> 2, 1u) + min(ks >> 2, 1u);
+          if constexpr (STATS) kept += min(pair & 0xFFFFu, 1u) + min(pair >> 16, 1u);
         }
       }
       size_t piece = a24_piece((int)t, m_lane >> 6, e.F >> 6);
@@ -320,6 +331,8 @@ __device__ __forceinline__ uint32_t cvt_e4m3x2(float lo, float hi, uint32_t old,
 struct EpiPrune24F8 {
   struct Args { uint8_t* Hc8; uint8_t* meta; __bf16* Hdbg; const float* b1; int F; float zscale; float sh; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+    LaneVec64 lb;
+    lb.load(e.b1, m_lane, 0.f);
 #pragma unroll
     for (int ni = 0; ni < 4; ni++) {
       size_t t = (size_t)(n_lane + ni);
@@ -330,8 +343,7 @@ struct EpiPrune24F8 {
         uint32_t hpk[8];
 #pragma unroll
         for (int d = 0; d < 8; d++) {
-          float b0 = e.b1 ? e.b1[m_lane + 16 * mi + 2 * d] : 0.f;
-          float b1v = e.b1 ? e.b1[m_lane + 16 * mi + 2 * d + 1] : 0.f;
+          float b0 = lb.at(16 * mi + 2 * d), b1v = lb.at(16 * mi + 2 * d + 1);
           float r0 = fmaxf(acc[mi][ni][2 * d] * e.zscale + b0, 0.f);
           float r1 = fmaxf(acc[mi][ni][2 * d + 1] * e.zscale + b1v, 0.f);
           hpk[d] = pack_bf16x2(r0 * r0, r1 * r1);
@@ -343,15 +355,11 @@ struct EpiPrune24F8 {
         }
 #pragma unroll
         for (int a = 0; a < 4; a++) {
-          uint32_t k0 = ((hpk[2 * a] & 0xFFFFu) << 2) | 3u;
-          uint32_t k1 = ((hpk[2 * a] >> 16) << 2) | 2u;
-          uint32_t k2 = ((hpk[2 * a + 1] & 0xFFFFu) << 2) | 1u;
-          uint32_t k3 = ((hpk[2 * a + 1] >> 16) << 2);
-          uint32_t kf, ks;
-          uint32_t n4 = pick24_keys(k0, k1, k2, k3, kf, ks);
+          uint32_t pair;
+          uint32_t n4 = pick24_packed(hpk[2 * a], hpk[2 * a + 1], pair);
           int gi = 4 * mi + a;
-          float v0 = __builtin_bit_cast(float, (kf >> 2) << 16) / e.sh;
-          float v1 = __builtin_bit_cast(float, (ks >> 2) << 16) / e.sh;
+          float v0 = bf16_lo_to_f32(pair) / e.sh;
+          float v1 = bf16_hi_to_f32(pair) / e.sh;
           // group gi's two stored bytes are bytes 2 gi, 2 gi + 1 of the lane's 32
           q8[gi >> 1] = cvt_e4m3x2(v0, v1, (gi & 1) ? q8[gi >> 1] : 0u, (gi & 1) != 0);
           nib[gi >> 3] |= n4 << (4 * (gi & 7));
@@ -377,6 +385,9 @@ struct EpiPrune24F8 {
 struct EpiPrune24Rw {
   struct Args { __bf16* Hc; uint8_t* meta; __bf16* Hdbg; const float* b1; int F; const float* sx; const float* sw1; uint32_t* rowmax; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+    LaneVec64 lb, lw;
+    lb.load(e.b1, m_lane, 0.f);
+    lw.load(e.sw1, m_lane, 1.f);
 #pragma unroll
     for (int ni = 0; ni < 4; ni++) {
       size_t t = (size_t)(n_lane + ni);
@@ -389,11 +400,9 @@ struct EpiPrune24Rw {
         uint32_t hpk[8];
 #pragma unroll
         for (int d = 0; d < 8; d++) {
-          int f = m_lane + 16 * mi + 2 * d;
-          float b0 = e.b1 ? e.b1[f] : 0.f;
-          float b1v = e.b1 ? e.b1[f + 1] : 0.f;
-          float r0 = fmaxf(acc[mi][ni][2 * d] * (sxt * e.sw1[f]) + b0, 0.f);
-          float r1 = fmaxf(acc[mi][ni][2 * d + 1] * (sxt * e.sw1[f + 1]) + b1v, 0.f);
+          float b0 = lb.at(16 * mi + 2 * d), b1v = lb.at(16 * mi + 2 * d + 1);
+          float r0 = fmaxf(acc[mi][ni][2 * d] * (sxt * lw.at(16 * mi + 2 * d)) + b0, 0.f);
+          float r1 = fmaxf(acc[mi][ni][2 * d + 1] * (sxt * lw.at(16 * mi + 2 * d + 1)) + b1v, 0.f);
           hpk[d] = pack_bf16x2(r0 * r0, r1 * r1);
           mx = max(mx, max(hpk[d] & 0xFFFFu, hpk[d] >> 16));
         }
@@ -404,14 +413,10 @@ struct EpiPrune24Rw {
         }
 #pragma unroll
         for (int a = 0; a < 4; a++) {
-          uint32_t k0 = ((hpk[2 * a] & 0xFFFFu) << 2) | 3u;
-          uint32_t k1 = ((hpk[2 * a] >> 16) << 2) | 2u;
-          uint32_t k2 = ((hpk[2 * a + 1] & 0xFFFFu) << 2) | 1u;
-          uint32_t k3 = ((hpk[2 * a + 1] >> 16) << 2);
-          uint32_t kf, ks;
-          uint32_t n4 = pick24_keys(k0, k1, k2, k3, kf, ks);
+          uint32_t pair;
+          uint32_t n4 = pick24_packed(hpk[2 * a], hpk[2 * a + 1], pair);
           int gi = 4 * mi + a;
-          vals[gi] = (kf >> 2) | ((ks >> 2) << 16);
+          vals[gi] = pair;
           nib[gi >> 3] |= n4 << (4 * (gi & 7));
         }
       }
@@ -449,6 +454,8 @@ struct EpiRowMajorRowCol {
 struct EpiRelu2F8 {
   struct Args { uint8_t* H8; const float* b1; int F; float zscale; float sh; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+    LaneVec64 lb;
+    lb.load(e.b1, m_lane, 0.f);
 #pragma unroll
     for (int ni = 0; ni < 4; ni++) {
       uint8_t* row = e.H8 + a24_piece(n_lane + ni, m_lane >> 6, e.F >> 6) * 64;   // a lane's 64 features: one piece
@@ -457,8 +464,7 @@ struct EpiRelu2F8 {
         uint32_t q[4];
 #pragma unroll
         for (int d = 0; d < 8; d++) {
-          float b0 = e.b1 ? e.b1[m_lane + 16 * mi + 2 * d] : 0.f;
-          float b1v = e.b1 ? e.b1[m_lane + 16 * mi + 2 * d + 1] : 0.f;
+          float b0 = lb.at(16 * mi + 2 * d), b1v = lb.at(16 * mi + 2 * d + 1);
           float r0 = fmaxf(acc[mi][ni][2 * d] * e.zscale + b0, 0.f);
           float r1 = fmaxf(acc[mi][ni][2 * d + 1] * e.zscale + b1v, 0.f);
           uint32_t hp = pack_bf16x2(r0 * r0, r1 * r1);

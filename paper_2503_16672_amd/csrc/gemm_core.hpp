@@ -523,6 +523,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi:
     // the dense fp8 ops are inline assembly, which the compiler's hazard handling does not see: let the last ones
     // (16 passes each) drain before the epilogue reads the accumulators
     asm volatile("s_nop 15\n s_nop 15\n s_nop 15\n s_nop 15\n s_nop 15" ::: "memory");
+    // and tie the accumulators to a point after the wait (volatile statements keep their order), so that no read of
+    // them can be scheduled above it
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+      for (int j = 0; j < 4; j++) asm volatile("" : "+a"(acc[i][j]));
   }
   int m_lane = m0 + L.wy * 128 + 64 * L.h;
   int n_lane = n0 + L.wx * 128 + 4 * L.rho;
@@ -576,6 +582,23 @@ __device__ __forceinline__ uint32_t pick24_keys(uint32_t k0, uint32_t k1, uint32
   bool top_first = ct > cs;                                    // larger complement = lower index
   key_first = top_first ? top : second;
   key_second = top_first ? second : top;
+  uint32_t cmax = max(ct, cs), cmin = min(ct, cs);
+  return (cmax | (cmin << 2)) ^ 15u;
+}
+
+// The same pick for a group of non-negative values that arrive packed, lo = h0 | h1 << 16 and hi = h2 | h3 << 16 (the
+// activation epilogues): with the value in the upper half, key_i = h_i << 16 | (3 - i) takes one instruction each, and
+// the kept pair, in position order, is one byte permute of the two winning keys.
+__device__ __forceinline__ uint32_t pick24_packed(uint32_t lo, uint32_t hi, uint32_t& pair) {
+  uint32_t k0 = (lo << 16) | 3u, k1 = (lo & 0xFFFF0000u) | 2u, k2 = (hi << 16) | 1u, k3 = hi & 0xFFFF0000u;
+  uint32_t a = max(k0, k1), b = min(k0, k1), c = max(k2, k3), d = min(k2, k3);
+  uint32_t top = max(a, c);
+  uint32_t e = max(b, d);
+  uint32_t second = max(min(a, c), min(max(a, c), e));
+  uint32_t ct = top & 3u, cs = second & 3u;
+  bool top_first = ct > cs;
+  uint32_t kf = top_first ? top : second, ks = top_first ? second : top;
+  pair = __builtin_amdgcn_perm(ks, kf, 0x07060302u);           // kf's upper half below ks's upper half
   uint32_t cmax = max(ct, cs), cmin = min(ct, cs);
   return (cmax | (cmin << 2)) ^ 15u;
 }
