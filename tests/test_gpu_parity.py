@@ -1139,3 +1139,62 @@ def test_prepared_weights_give_identical_results(F24):
     torch.cuda.synchronize()
     assert torch.equal(Ya, Yb)
     ctx.close()
+
+
+# ----------------------------------------------------------------------------- HIP graph capture
+def test_fwd_bwd_replayed_from_a_hip_graph(F24):
+    """The forward and backward calls only enqueue kernels (no memset nodes, no synchronisation, no allocation), so a
+    training step can be recorded into a HIP graph.  Every replay must reproduce the eager step bit for bit, also with
+    other work and synchronisations between the replays and with new contents in the input buffers."""
+    print("HIP graph: capture fwd+bwd (split + permutation on), replay 4 times", flush=True)
+    T, D, Fh = 512, 256, 2048
+    flags = F24.FFN24_TRAINING | F24.FFN24_SPLIT | F24.FFN24_PERMUTE
+    ctx = F24.Context(T, D, Fh, flags)
+    ctx.set_split(256)                                   # the per-feature counters are cleared inside the step
+    ctx.set_token_permutation(synth.token_permutation(T, seed=8))
+    inps = [synth.make_inputs(T, D, Fh, "per_feature", seed=200 + i, with_dy=True) for i in range(2)]
+    devs = [_upload(i) for i in inps]
+    # static buffers the graph reads and writes
+    X, W1, W2, dY = (torch.empty_like(devs[0][k]) for k in ("X", "W1", "W2", "dY"))
+    b1 = torch.empty_like(devs[0]["b1"])
+    Y = torch.empty((T, D), dtype=torch.bfloat16, device="cuda")
+    grads = (torch.empty((T, D), dtype=torch.bfloat16, device="cuda"), torch.empty((D, Fh), dtype=torch.bfloat16, device="cuda"),
+             torch.empty((Fh, D), dtype=torch.bfloat16, device="cuda"))
+
+    def load(d):
+        X.copy_(d["X"]); W1.copy_(d["W1"]); W2.copy_(d["W2"]); dY.copy_(d["dY"]); b1.copy_(d["b1"])
+
+    def step():
+        ctx.ffn24_fwd(X, W1, b1, W2, Y)
+        ctx.ffn24_bwd(dY, grads)
+
+    # eager results for both input sets (this also does the one-time kernel set-up outside the capture)
+    eager = []
+    for d in devs:
+        load(d); step(); torch.cuda.synchronize()
+        eager.append([Y.clone()] + [g.clone() for g in grads])
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        load(devs[0])
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for rep, which in enumerate((0, 1, 1, 0)):
+        load(devs[which])
+        for t in [Y, *grads]:
+            t.fill_(float("nan"))                        # a replay that skipped work would leave these behind
+        graph.replay()
+        torch.cuda.synchronize()
+        junk = torch.randn(1 << 20, device="cuda").sum().item()      # the program's own eager work between replays
+        got = [Y, *grads]
+        for name, a, b in zip(("Y", "dX", "dW1", "dW2"), got, eager[which]):
+            assert torch.equal(a, b), f"replay {rep} (inputs {which}): {name} differs from the eager step"
+    # and the eager step is the oracle's
+    f = O.ffn24_fwd(inps[0]["X"][synth.token_permutation(T, seed=8)], inps[0]["W1"], inps[0]["b1"], inps[0]["W2"])
+    Yo = np.empty_like(f["Y"]); Yo[synth.token_permutation(T, seed=8)] = f["Y"]
+    assert O.max_rel_err(f64(eager[0][0]), Yo) <= TOL_BF16
+    del graph
+    ctx.close()
