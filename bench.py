@@ -32,10 +32,10 @@ SPARSE = {"down_sp", "dx_sp", "dw2_sp", "dw1_sp"}
 def measured_traffic(kernel: str, workload: str):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE, each
     scaled by what the same counter reads for a 1 GiB copy); None if no summary covers this kernel and workload."""
-    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_hbm_traffic.txt")
+    path = os.path.join(ROOT, "profiles", f"ffn24_{workload}_hbm_traffic.txt")
     try:
         for line in open(path):
-            if line.startswith("hbm_bytes_per_launch"):
+            if line.startswith(f"hbm_bytes_per_launch {kernel} ="):
                 return float(line.split("=")[1])
     except OSError:
         pass
