@@ -19,7 +19,7 @@ Training with 2:4 Activation Sparsity"):
     A^T.B when A is 2:4 along the tokens of a feature ("feature-wise") -- Fig. 2 caption
   * backward graph: 6 GEMMs, those touching y2 or dy1 are the sparse ones -- Fig. 4 caption
   * the feature-wise picks are made on top of the forward's token-wise mask -- Sec. 2, last paragraph
-  * forward order: activation, then sparsification, then FP8 quantisation -- Sec. 2, "We implemented 2 new kernels"
+  * forward order: activation, then sparsification, then FP8 quantisation -- Sec. 2, the paragraph on the two new kernels
 
 Readings where the paper is silent:
   * ties in magnitude go to the lower index; zeros take part like any value, so a group always
@@ -123,7 +123,7 @@ def round_e4m3(x) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------------------
-# 2:4 pruning (Sec. 2: "keep the 2 highest magnitude scalars and drop the others")
+# 2:4 pruning (Sec. 2, first paragraph: of each group of 4 the two entries of largest magnitude stay)
 # --------------------------------------------------------------------------------------
 
 _MAG_MASK = {2: 0x7FFF, 1: 0x7F}

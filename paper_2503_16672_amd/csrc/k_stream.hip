@@ -213,7 +213,7 @@ int launch_featurewise24_split(const void* Hc, const uint8_t* meta, const void* 
   return (int)hipGetLastError();
 }
 
-// Feature partition of the split weight-gradient GEMMs (Sec. 2, "Optimization 1": the paper's "cheap argsort kernel").
+// Feature partition of the split weight-gradient GEMMs (Sec. 2, "Optimization 1", where the paper sorts the features by their statistic).
 // Only the set matters, so no sort: the threshold count c* = the smallest c with #{nnz > c} <= n_dense is found by
 // bisection over the counts (which sit in LDS); every feature above it is dense, and of those equal to it the first
 // (n_dense - #above) by index.  Sparse features become rows 0 .. F - n_dense - 1, dense ones the rows after, both in
@@ -423,9 +423,9 @@ int launch_transpose8(const void* in, int R, int C, void* out, int out_form, hip
   return (int)hipGetLastError();
 }
 
-// Row-wise fp8 quantisation of the compressed activation (Sec. 2: "a new kernel that applies the activation, the
-// sparsification, and FP8 quantization" -- here only the last step is left to a kernel of its own, because the scale of
-// a token row, sh[t] = (largest activation of the row) / 448, is known only once the whole row exists).
+// Row-wise fp8 quantisation of the compressed activation (Sec. 2 describes one kernel for activation, sparsification
+// and FP8 quantisation; here only the last step is left to a kernel of its own, because the scale of a token row,
+// sh[t] = (largest activation of the row) / 448, is known only once the whole row exists).
 // Input: bf16 kept values + metadata in the bf16 panel form (64-byte / 8-byte pieces per 64 features);
 // output: e4m3 codes + metadata in the fp8 panel form (64-byte / 16-byte pieces per 128 features), and sh [T].
 // One work item per (token, 128 features): two input pieces -> one output piece.
