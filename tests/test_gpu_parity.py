@@ -396,6 +396,29 @@ def test_multi_tile_shapes(F24):
     ctx.close()
 
 
+@pytest.mark.parametrize("T,D,Fh", [(256, 256, 256), (256, 512, 256), (512, 256, 768)])
+def test_smallest_shapes(F24, T, D, Fh):
+    """One block tile in some or all GEMM dimensions and the shortest K loops the entry points accept (K = 256: as many
+    stages as the DMA ring has slots, or barely more)."""
+    print(f"smallest shapes fwd+bwd T={T} D={D} F={Fh}", flush=True)
+    inp = synth.make_inputs(T, D, Fh, 0.75, seed=T + D + Fh, with_dy=True)
+    d = _upload(inp)
+    ctx = F24.Context(T, D, Fh, F24.FFN24_DEBUG_DUMP_H | F24.FFN24_TRAINING | F24.FFN24_DENSE)
+    Y = ctx.ffn24_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    grads = ctx.ffn24_bwd(d["dY"])
+    torch.cuda.synchronize()
+    _check_fwd24(F24, inp, ctx, d, Y)
+    _check_bwd24(F24, inp, ctx, d, grads)
+    Yd = ctx.ffn_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    gd = ctx.ffn_bwd(d["dY"])
+    torch.cuda.synchronize()
+    f = O.ffn_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"])
+    g = O.ffn_bwd(f, inp["dY"])
+    errs = [O.max_rel_err(f64(Yd), f["Y"])] + [O.max_rel_err(f64(a), g[k]) for a, k in zip(gd, ("dX", "dW1", "dW2"))]
+    assert max(errs) <= TOL_BF16
+    ctx.close()
+
+
 # ----------------------------------------------------------------------------- full size (bench configuration), sampled
 def _groups_to_cols(gsel):
     """feature groups -> their 4 features each, and their 2 stored slots each."""
