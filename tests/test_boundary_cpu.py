@@ -89,3 +89,11 @@ def test_binding_checks_shapes_and_dtypes_before_the_call():
         ffn24._expect(ok.float(), (4, 16), ffn24._BF16, "H")
     with pytest.raises(ValueError, match="CUDA"):
         ffn24.sparsify24(ok)                       # right shape and type, but host memory
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build is single-GPU: bench.py --gpus N with N > 1 exits with a message instead of launching anything."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "single-GPU" in r.stderr and r.stdout.strip() == ""
