@@ -66,7 +66,12 @@ typedef enum { FFN24_BF16 = 0, FFN24_FP8_E4M3 = 1 } ffn24_dtype;
 typedef struct ffn24_ctx ffn24_ctx; /* opaque; owns only its device workspace */
 
 /* Create a context for token count T, model dimension D, hidden dimension F.
- * Requires T, D, F to be multiples of 256 (the GEMM tile) and at most 2^20.  Allocates the device workspace with
+ * Requires T, D, F to be multiples of 256 (the GEMM tile) and at most 2^20.  Other token counts are the caller's to
+ * pad: give X and dY zero rows up to the next multiple of 256.  A zero row of dY gives a zero row of dZ and a zero
+ * row of X multiplies it, so the padding adds nothing to dW1 and dW2; Y and dX are computed per token, the padding's
+ * rows of them are ignored; and if the real token count is a multiple of 4 no padded token shares a feature-wise
+ * 2:4 group with a real one (without a bias -- the paper's FFN -- a padded token's activation is zero anyway).
+ * Allocates the device workspace with
  * hipMalloc on the current device: about 1.13 T F + 4 D F bytes; plus 3.13 T F + 4 T D + 4 D F with FFN24_TRAINING
  * (T F + 2 D F more with FFN24_SPLIT); plus
  * 2 T F with FFN24_DENSE (6 T F more when FFN24_TRAINING is set too); plus 2 T F with FFN24_DEBUG_DUMP_H.

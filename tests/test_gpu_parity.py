@@ -419,6 +419,32 @@ def test_smallest_shapes(F24, T, D, Fh):
     ctx.close()
 
 
+def test_zero_padded_tokens(F24):
+    """Token counts that are not a multiple of the tile are padded by the caller with zero rows of X and dY: everything
+    the real tokens produce is what the oracle computes from the real tokens alone, also with a bias that makes the
+    padded tokens' activations non-zero."""
+    T_real, T, D, Fh = 200, 256, 256, 512
+    print(f"zero padding {T_real} -> {T} tokens", flush=True)
+    inp = synth.make_inputs(T_real, D, Fh, 0.8, seed=63, with_dy=True)
+    inp["b1"] = inp["b1"].copy()
+    inp["b1"][::5] = 0.5                                    # every fifth feature is non-zero on a padded token
+    pad = lambda a: np.concatenate([a, np.zeros((T - T_real, a.shape[1]), a.dtype)])
+    d = _upload({**inp, "X": pad(inp["X"]), "dY": pad(inp["dY"])})
+    ctx = F24.Context(T, D, Fh, F24.FFN24_TRAINING)
+    Y = ctx.ffn24_fwd(d["X"], d["W1"], d["b1"], d["W2"])
+    dX, dW1, dW2 = ctx.ffn24_bwd(d["dY"])
+    torch.cuda.synchronize()
+    assert bool((ctx.saved("Hc")[T_real:] != 0).any())      # the case does have non-zero padded activations
+    f = O.ffn24_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"])
+    g = O.ffn24_bwd(f, inp["dY"])
+    errs = {"Y": O.max_rel_err(f64(Y[:T_real]), f["Y"]), "dX": O.max_rel_err(f64(dX[:T_real]), g["dX"]),
+            "dW1": O.max_rel_err(f64(dW1), g["dW1"]), "dW2": O.max_rel_err(f64(dW2), g["dW2"])}
+    print("  errs", errs, flush=True)
+    assert max(errs.values()) <= TOL_BF16
+    assert not bool(dX[T_real:].any())                      # zero dY rows give zero dX rows
+    ctx.close()
+
+
 # ----------------------------------------------------------------------------- full size (bench configuration), sampled
 def _groups_to_cols(gsel):
     """feature groups -> their 4 features each, and their 2 stored slots each."""
