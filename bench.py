@@ -149,7 +149,7 @@ def main() -> int:
     ap.add_argument("--workload", default="c4", help="c1, c2, c3 (four forward layers), c3_85..c3_98, c4 (default: forward+backward at the 7B FFN dims), c5 (fp8 forward)")
     ap.add_argument("--fwd-only", action="store_true", help="time the forward pass only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--cpu-tokens", type=int, default=2048, help="token slice the CPU oracle is timed on")
+    ap.add_argument("--cpu-tokens", type=int, default=4096, help="token slice the CPU oracle is timed on (about 15 s of CPU work at the default workload)")
     ap.add_argument("--split", type=int, default=0, help="keep this many hidden features (multiple of 256, <= d_ff/4) out of the "
                     "feature-wise 2:4: split weight-gradient GEMMs (bf16 fwd+bwd workloads)")
     ap.add_argument("--rowwise", action="store_true", help="fp8 workload with row-wise instead of per-tensor scales (no dense baseline in this mode)")
