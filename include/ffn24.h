@@ -214,7 +214,7 @@ FFN24_API int ffn24_copy_saved(ffn24_ctx* ctx, int which, void* dst, int64_t dst
  * ffn24_kernel_ms(ctx, k, &ms) waits for kernel k's events of the most recent call and returns its duration.
  * Kernel ids: 0 up-projection+prune, 1 sparse down-projection, 2 dH+derivative, 3 sparse dX, 4 feature-wise
  * re-compression, 5 sparse dW2, 6 sparse dW1, 7..12 the six dense-baseline GEMMs in the same order
- * (up, down, dH, dX, dW2, dW1), 13 the two weight transposes of a forward (W1, W2 -> K-contiguous), 14 the two
+ * (up, down, dH, dX, dW2, dW1), 13 the weight pass of a forward or of ffn24_prepare_weights (W1, W2 re-arranged), 14 the two
  * activation transposes of a backward (dY, X), 15 the feature partition of the split, 16 the transpose that brings
  * dW1 into [D][F] after a split (with a split, 5 and 6 are the combined sparse + dense launches of dW2 and dW1),
  * 17 the row-wise fp8 quantisation kernel.  Returns FFN24_ERR_STATE if that kernel has not run with profiling on. */
