@@ -367,10 +367,86 @@ def test_backward_rounding_points():
     # dZ is stored in bf16 and is zero off the token-wise mask
     assert np.array_equal(O.round_bf16(g["dZq"]), g["dZq"])
     assert np.all(g["dZq"][~f["Mtok"]] == 0)
-    # derivative of max(0,z)^2 is 2 max(0,z): check against the unrounded definition within bf16 precision
-    dH = O.round_bf16(inp["dY"]).astype(np.float64) @ f["W2q"].T
+    # derivative of max(0,z)^2 is 2 max(0,z) (Fig. 4 caption), from the forward's own Z: the stored dZ is the one
+    # storage rounding of the definition, written out here with torch's cast instead of the oracle's
+    dH = torch.from_numpy(inp["dY"]).to(torch.bfloat16).double().numpy() @ f["W2q"].T
     want = dH * 2 * np.maximum(f["Z"], 0) * f["Mtok"]
-    assert np.allclose(g["dZq"], want, rtol=2.0 ** -6, atol=1e-6)
+    want_q = torch.from_numpy(want.astype(np.float32)).to(torch.bfloat16).float().numpy()
+    assert np.array_equal(g["dZq"], want_q)
+    assert np.count_nonzero(want_q) > 20
+    # the dense backward takes the same derivative at every position
+    fd = O.ffn_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"])
+    gd = O.ffn_bwd(fd, inp["dY"])
+    want_d = torch.from_numpy((dH * 2 * np.maximum(fd["Z"], 0)).astype(np.float32)).to(torch.bfloat16).float().numpy()
+    assert np.array_equal(gd["dZq"], want_d)
+
+
+def test_relu2_derivative_closed_form_and_sign():
+    z = np.array([-3.0, -0.0, 0.0, 0.5, 2.0, 7.25])
+    assert np.array_equal(O.relu2_derivative(z), np.array([0.0, 0.0, 0.0, 1.0, 4.0, 14.5]))
+    # central finite difference of max(0, z)^2 away from the kink
+    zz = np.linspace(-4, 4, 41) + 0.0123
+    act = lambda v: np.maximum(v, 0.0) ** 2
+    fd = (act(zz + 1e-6) - act(zz - 1e-6)) / 2e-6
+    assert np.allclose(O.relu2_derivative(zz), fd, rtol=1e-6, atol=1e-6)
+
+
+def test_stored_activation_derivative_stays_within_storage_rounding_of_the_definition():
+    """2 sqrt(bf16(max(0,z)^2)) against the definition 2 max(0,z): the activation's storage rounding is at most 2^-9
+    relative (bf16 keeps 8 significant bits), and the square root halves a relative error."""
+    rng = np.random.default_rng(21)
+    z = np.concatenate([rng.standard_normal(20000) * 3, np.geomspace(1e-3, 1e3, 5000), -np.geomspace(1e-3, 1e3, 100)])
+    r32 = np.maximum(z.astype(np.float32), np.float32(0))
+    hq = torch.from_numpy(r32 * r32).to(torch.bfloat16).float().numpy()
+    got = O.relu2_derivative_from_stored_activation(hq)
+    want = O.relu2_derivative(z.astype(np.float32))
+    assert np.all(got[z <= 0] == 0)
+    rel = np.abs(got - want)[z > 0] / want[z > 0]
+    assert rel.max() <= 2.0 ** -9
+    assert rel.max() >= 2.0 ** -12         # and it is not the definition: the rounding of h does show
+
+
+def test_staged_state_round_trips_the_forward_and_bounds_the_backward():
+    """staged_state_from_saved on what a forward saved (compressed words + metadata) gives back that forward's pruned
+    activation, mask and operands exactly; the backward run from it differs from the backward of the forward itself only
+    by the stored-activation derivative, i.e. by storage rounding."""
+    inp = _small_inputs(T=64, D=32, F=128, sparsity=0.5, seed=9)
+    f = O.ffn24_fwd(inp["X"], inp["W1"], inp["b1"], inp["W2"])
+    s = O.staged_state_from_saved(f["Hc_words"], f["meta"], inp["X"], inp["W1"], inp["W2"])
+    assert np.array_equal(s["H24"], f["H24"]) and s["H24"].dtype == f["H24"].dtype
+    assert np.array_equal(s["Mtok"], f["Mtok"]) and np.array_equal(s["meta"], f["meta"])
+    for k in ("Xq", "W1q", "W2q"):
+        assert np.array_equal(s[k], f[k])
+    # independent decode of the compressed form: scatter the kept pairs by hand
+    H = np.zeros((64, 128), np.float32)
+    vals = O.bf16_bits_to_f32(f["Hc_words"]).reshape(64, 32, 2)
+    for t in range(64):
+        for g in range(32):
+            nib = (f["meta"][t, g // 2] >> (4 * (g & 1))) & 15
+            H[t, 4 * g + (nib & 3)] = vals[t, g, 0]
+            H[t, 4 * g + (nib >> 2)] = vals[t, g, 1]
+    assert np.array_equal(H, s["H24"])
+    # its derivative is the definition up to the activation's storage rounding, on the kept positions
+    kept = f["Mtok"] & (f["H24"] > 0)
+    rel = np.abs(s["dAct"] - f["dAct"])[kept] / f["dAct"][kept]
+    assert rel.max() <= 2.0 ** -9
+    a, b = O.ffn24_bwd(f, inp["dY"]), O.ffn24_bwd(s, inp["dY"])
+    assert np.array_equal(a["meta_t"], b["meta_t"]) and np.array_equal(a["Hc_t_words"], b["Hc_t_words"])
+    assert np.array_equal(a["dW2"], b["dW2"])                 # dW2 does not see the derivative at all
+    for k in ("dX", "dW1"):
+        assert 0 < O.max_rel_err(b[k], a[k]) <= 2.0 ** -7     # derivative 2^-10 + one bf16 rounding of dZ that may flip
+    assert O.fro_rel_err(b["dZq"], a["dZq"]) <= 2.0 ** -8
+
+
+def test_error_measures():
+    ref = np.array([[100.0, 0.0], [0.01, 0.02], [0.0, 0.0]])
+    y = ref.copy(); y[1] = [0.02, 0.02]                       # a small row wrong by half its own size
+    assert O.max_rel_err(y, ref) == pytest.approx(1e-4)       # the per-tensor maximum hides it
+    assert O.row_rel_err(y, ref) == pytest.approx(0.01 / np.hypot(0.01, 0.02))
+    assert O.fro_rel_err(y, ref) == pytest.approx(0.01 / np.sqrt(100.0 ** 2 + 0.01 ** 2 + 0.02 ** 2))
+    y2 = ref.copy(); y2[2] = [0.0, 3.0]                       # a row whose reference is zero counts by its own norm
+    assert O.row_rel_err(y2, ref) == 3.0
+    assert O.row_rel_err(ref, ref) == 0.0 and O.fro_rel_err(ref, ref) == 0.0
 
 
 # ----------------------------------------------------------------------------- fp8 forward
