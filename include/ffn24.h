@@ -51,6 +51,7 @@ extern "C" {
 #define FFN24_ERR_STATE (-5)  /* call order: backward without the matching forward, missing context flag, wrong current device */
 #define FFN24_ERR_HIP (-6)    /* the HIP runtime reported an error (allocation, launch) */
 #define FFN24_ERR_NOTREADY (-7) /* ffn24_get_telemetry without waiting: no snapshot has completed yet */
+#define FFN24_ERR_SCRATCH (-8)  /* ffn24_fwd_static: the intermediate tensors exceed FFN24_STATIC_SCRATCH_BYTES */
 
 typedef enum { FFN24_BF16 = 0, FFN24_FP8_E4M3 = 1 } ffn24_dtype;
 
@@ -159,6 +160,24 @@ FFN24_API int ffn24_prepare_weights(ffn24_ctx* ctx, const void* W1, const void* 
  * down-projection.  The context keeps (Hc, meta), its own re-arranged copies of W1 and W2 and the X pointer for
  * ffn24_bwd; the caller keeps X alive and unchanged until then. */
 FFN24_API int ffn24_fwd(ffn24_ctx* ctx, const void* X, const void* W1, const float* b1, const void* W2, void* Y, void* stream);
+
+/* ffn24_fwd for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the same forward (bf16, same kernels, bit-identical Y) without a context.  The
+ * intermediate tensors -- the compressed activation and the two re-arranged weights, T F + T F / 8 + 4 D F bytes, which
+ * ffn24_ctx_create would allocate -- live in a static device array of FFN24_STATIC_SCRATCH_BYTES inside the library, of
+ * which every GPU that loads the library holds one copy until the process ends.  The call allocates and frees nothing
+ * and calls no allocating routine; it only enqueues four kernels on `stream`.
+ *   X [T][D], W1 [D][F], b1 [F] fp32 or NULL, W2 [F][D], Y [T][D]: device pointers, bf16, caller-owned as everywhere.
+ *   T, D, F multiples of 256.  FFN24_ERR_SCRATCH if ffn24_static_scratch_needed(T, D, F) exceeds the buffer (use a
+ *   context then); the other error codes as for ffn24_fwd.
+ * All calls on one GPU share that GPU's buffer: two calls whose work overlaps in time on one GPU (different streams,
+ * or different threads) race on it.  Calls on one stream are ordered and safe.  Nothing in the buffer has to start at
+ * zero -- each call writes every byte it later reads -- so it is never cleared.  Inference only: nothing is kept for
+ * a backward pass. */
+#define FFN24_STATIC_SCRATCH_BYTES (64u << 20)
+FFN24_API int64_t ffn24_static_scratch_needed(int64_t T, int64_t D, int64_t F);   /* bytes, or -1 for sizes out of range */
+FFN24_API int ffn24_fwd_static(const void* X, const void* W1, const float* b1, const void* W2, void* Y, int64_t T, int64_t D, int64_t F,
+                               void* stream);
 
 /* Backward of the last ffn24_fwd on this context, masks held fixed (paper Fig. 4 and Sec. 2, backward paragraphs):
  *   dZ  = (dY W2^T) * 2 max(0, Z) on the kept positions        dense GEMM, derivative taken as 2 sqrt(H)

@@ -11,6 +11,28 @@ constexpr int NUM_KERNELS = 18;
 enum { K_UP = 0, K_DOWN, K_DH, K_DX, K_FW, K_DW2, K_DW1, KD_UP, KD_DOWN, KD_DH, KD_DX, KD_DW2, KD_DW1, K_TR_W, K_TR_ACT, K_PART, K_TR_DW1, K_QUANT };
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// Intermediate tensors of ffn24_fwd_static.  One copy per GPU that loads this library, held until the process ends.
+// In host code this name is only a handle for hipGetSymbolAddress: the address kernels and copies use is the one that
+// call returns for the current device (scratch_base below), never the name itself.
+static __device__ __align__(256) unsigned char scratch[FFN24_STATIC_SCRATCH_BYTES];
+unsigned char* scratch_dev[MAX_DEVICES];
+std::atomic<bool> scratch_known[MAX_DEVICES];
+
+// Device address of this GPU's copy of `scratch`, looked up once per device with that device current.
+int scratch_base(unsigned char** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return FFN24_ERR_HIP;
+  if (dev < 0 || dev >= MAX_DEVICES) return FFN24_ERR_HIP;
+  if (!scratch_known[dev].load(std::memory_order_acquire)) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return FFN24_ERR_HIP; }
+    scratch_dev[dev] = static_cast<unsigned char*>(p);   // threads that race here store the same address
+    scratch_known[dev].store(true, std::memory_order_release);
+  }
+  *out = scratch_dev[dev];
+  return FFN24_OK;
+}
 }  // namespace
 
 struct ffn24_ctx {
@@ -139,6 +161,7 @@ const char* ffn24_strerror(int code) {
     case FFN24_ERR_STATE: return "wrong call order, missing context flag, or the context belongs to another device";
     case FFN24_ERR_HIP: return "HIP runtime error";
     case FFN24_ERR_NOTREADY: return "no telemetry snapshot has completed yet";
+    case FFN24_ERR_SCRATCH: return "the call's intermediate tensors do not fit the library's static scratch buffer";
     default: return "unknown ffn24 error code";
   }
 }
@@ -436,6 +459,37 @@ int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, cons
     if (t.done(rc1)) return FFN24_ERR_HIP; }
   if (c->tele && (rc = tele_snapshot(c, 1, s))) return rc;
   c->X = X; c->have_fwd24 = 1;
+  return FFN24_OK;
+}
+
+int64_t ffn24_static_scratch_needed(int64_t T, int64_t D, int64_t F) {
+  if (T <= 0 || D <= 0 || F <= 0 || T > (1 << 20) || D > (1 << 20) || F > (1 << 20)) return -1;
+  // compressed activation (kept values + metadata) and the two re-arranged weights; every part a multiple of 256 bytes
+  return T * F + T * F / 8 + 2 * (2 * D * F);
+}
+
+int ffn24_fwd_static(const void* X, const void* W1, const float* b1, const void* W2, void* Y, int64_t T, int64_t D, int64_t F, void* stream) {
+  if (T <= 0 || D <= 0 || F <= 0 || T % 256 || D % 256 || F % 256 || T > (1 << 20) || D > (1 << 20) || F > (1 << 20)) return FFN24_ERR_SHAPE;
+  if (ffn24_static_scratch_needed(T, D, F) > (int64_t)FFN24_STATIC_SCRATCH_BYTES) return FFN24_ERR_SCRATCH;
+  int rc = check_ptrs({X, W1, W2, Y});
+  if (rc) return rc;
+  if (b1 && misaligned(b1)) return FFN24_ERR_ALIGN;
+  unsigned char* base = nullptr;
+  if ((rc = scratch_base(&base))) return rc;
+  // carve-up of the scratch buffer: Hc [T][F/2] bf16 | meta [T][F/8] | W1^T [F][D] bf16 | W2^T [D][F] bf16 (panel forms).
+  // Every byte a kernel below reads from it has been written by an earlier kernel of this same call, so nothing has to
+  // start at zero and what a previous call left behind is never seen.
+  const size_t tf = (size_t)T * (size_t)F, df = (size_t)D * (size_t)F;
+  unsigned char* Hc = base;
+  uint8_t* meta = base + tf;
+  unsigned char* W1t = base + tf + tf / 8;
+  unsigned char* W2t = W1t + 2 * df;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int Ti = (int)T, Di = (int)D, Fi = (int)F;
+  if (launch_transpose(W1, Di, Fi, W1t, 1, nullptr, 0, nullptr, s)) return FFN24_ERR_HIP;
+  if (launch_transpose(W2, Fi, Di, W2t, 2, nullptr, 0, nullptr, s)) return FFN24_ERR_HIP;
+  if (launch_up_prune24(W1t, X, b1, Ti, Di, Fi, Hc, meta, nullptr, nullptr, nullptr, nullptr, s)) return FFN24_ERR_HIP;
+  if (launch_sp_rowmajor(Hc, meta, 1, W2t, 1, Ti, Di, Fi, Y, s)) return FFN24_ERR_HIP;
   return FFN24_OK;
 }
 

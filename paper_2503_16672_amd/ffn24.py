@@ -27,6 +27,7 @@ FFN24_TELEMETRY = 64
 EXPORTS = (
     "ffn24_ctx_create", "ffn24_ctx_destroy", "ffn24_set_scales", "ffn24_set_row_scales", "ffn24_set_token_permutation", "ffn24_set_split", "sparsify24", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd",
     "ffn_fwd", "ffn_bwd", "ffn24_prepare_weights", "ffn24_get_telemetry", "ffn24_policy_use_sparse", "ffn24_saved_bytes", "ffn24_copy_saved", "ffn24_set_profiling", "ffn24_kernel_ms", "ffn24_strerror",
+    "ffn24_static_scratch_needed", "ffn24_fwd_static",
 )
 
 KERNEL_NAMES = ("up_prune24", "down_sp", "dh_gather", "dx_sp", "featurewise24", "dw2_sp", "dw1_sp",
@@ -72,9 +73,12 @@ def lib() -> ctypes.CDLL:
         L.ffn24_kernel_ms.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_float)]
         L.ffn24_strerror.argtypes = [ci]
         L.ffn24_strerror.restype = ctypes.c_char_p
+        L.ffn24_static_scratch_needed.argtypes = [i64, i64, i64]
+        L.ffn24_fwd_static.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp]
         for name in EXPORTS:
             if name != "ffn24_strerror":
                 getattr(L, name).restype = ci
+        L.ffn24_static_scratch_needed.restype = i64
         _lib = L
     return _lib
 
@@ -151,6 +155,26 @@ def spmm24(values: torch.Tensor, meta: torch.Tensor, Bt: torch.Tensor) -> torch.
     C = torch.empty((M, N), dtype=torch.bfloat16, device=values.device)
     _check(lib().spmm24(_ptr(values), _ptr(meta), _ptr(Bt), M, N, K, _ptr(C), _stream()), "spmm24")
     return C
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def static_scratch_needed(T: int, D: int, F: int) -> int:
+    return int(lib().ffn24_static_scratch_needed(T, D, F))
+
+
+def ffn24_fwd_static(X, W1, b1, W2, Y):
+    """The context-free forward that allocates nothing (see ffn24_fwd_static in the header); Y is handed in."""
+    T, D = X.shape
+    F = W1.shape[1]
+    _expect(X, (T, D), _BF16, "X")
+    _expect(W1, (D, F), _BF16, "W1")
+    _expect(W2, (F, D), _BF16, "W2")
+    _expect(b1, (F,), _F32, "b1")
+    _expect(Y, (T, D), _BF16, "Y")
+    _check(lib().ffn24_fwd_static(_ptr(X), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(Y), T, D, F, _stream()), "ffn24_fwd_static")
+    return Y
 
 
 class Context:

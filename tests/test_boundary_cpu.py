@@ -20,7 +20,7 @@ def _declared():
 
 def test_header_symbols_are_exported():
     names = _declared()
-    assert len(names) == 21 and "ffn24_fwd" in names and "sparsify24" in names
+    assert len(names) == 23 and "ffn24_fwd" in names and "sparsify24" in names
     lib = ctypes.CDLL(LIB)
     for n in names:
         assert hasattr(lib, n), n
@@ -97,3 +97,18 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode == 2 and "single-GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_static_forward_argument_validation_without_gpu():
+    """ffn24_fwd_static checks sizes against the static scratch buffer, and pointers, before it touches the GPU."""
+    from paper_2503_16672_amd import ffn24
+    L = ffn24.lib()
+    a16 = 0x1000
+    assert ffn24.static_scratch_needed(256, 256, 256) == 256 * 256 + 256 * 256 // 8 + 4 * 256 * 256
+    assert ffn24.static_scratch_needed(1024, 1024, 4096) == 1024 * 4096 * 9 // 8 + 4 * 1024 * 4096
+    assert ffn24.static_scratch_needed(0, 256, 256) == -1
+    assert L.ffn24_fwd_static(a16, a16, None, a16, a16, 300, 256, 256, None) == -2
+    assert L.ffn24_fwd_static(a16, a16, None, a16, a16, 16384, 4096, 16384, None) == -8
+    assert L.ffn24_fwd_static(a16, None, None, a16, a16, 256, 256, 256, None) == -1
+    assert L.ffn24_fwd_static(a16, a16, 0x1004, a16, a16, 256, 256, 256, None) == -3
+
