@@ -23,10 +23,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_DENSE = 2500.0   # TFLOP/s, MI355X published dense bf16 MFMA peak
 PEAK_FP8_DENSE = 5000.0    # TFLOP/s, published dense fp8 MFMA peak
-# What this chip's matrix pipes sustain with operands already in registers (no memory traffic at all), measured once
-# with a probe kernel: the clocks settle at 1.5-1.9 GHz under matrix load, the published peaks assume 2.4 GHz.
-# TFLOP/s executed (a sparse op executes half of its dense equivalent): dense bf16, sparse bf16, dense fp8, sparse fp8.
-REGISTER_RESIDENT = {("bf16", False): 1580.0, ("bf16", True): 1815.0, ("fp8", False): 4350.0, ("fp8", True): 3780.0}
+NOMINAL_MHZ = 2400.0       # the clock the published peaks assume; under matrix load the chip runs well below it
 # executed MFMA flops per kernel, in units of T*D*F (dense GEMM = 2, sparse GEMM executes half of its dense equivalent)
 KERNEL_FLOPS = {"up_prune24": 2.0, "down_sp": 1.0, "dh_gather": 2.0, "dx_sp": 1.0, "dw2_sp": 1.0, "dw1_sp": 1.0,
                 "dense_up": 2.0, "dense_down": 2.0, "dense_dh": 2.0, "dense_dx": 2.0, "dense_dw2": 2.0, "dense_dw1": 2.0}
@@ -46,48 +43,118 @@ def measured_traffic(kernel: str, workload: str):
     return None
 
 
+def _time_steps(torch, fn, warmup, steps):
+    """Mean wall-clock seconds per call over `steps` calls bracketed by device synchronisation, then -- in a second pass of
+    the same length -- every call timed on its own with events on the launch stream (median, min)."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    mean = (time.perf_counter() - t0) / steps
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    ev[0].record()
+    for i in range(steps):
+        fn()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    each = sorted(ev[i].elapsed_time(ev[i + 1]) * 1e-3 for i in range(steps))
+    return mean, each[len(each) // 2], each[0]
+
+
 def run_c3(args) -> int:
-    """Workload c3: four independent forward FFN layers at the 7B dims, each with its own seed and sparsity
-    (85 / 90 / 95 / 98 % zeros); per-layer time of the 2:4 FFN against the dense MFMA FFN."""
+    """Workload c3: four independent forward FFN layers at the 7B dims, each with its own seed, weights, buffers and
+    sparsity (85 / 90 / 95 / 98 % zeros).  A step is one pass over the four layers in turn, so that between two calls of
+    a layer the other three (0.8 GB of operands and intermediates each) have gone through the 256 MB last-level cache:
+    no layer finds its operands cached, and no explicit cache flush is used.  Per-layer times come from events around
+    each layer's call inside those same steps."""
     import torch
     from paper_2503_16672_amd import ffn24, synth
-    layers = {}
-    tot24 = totd = 0.0
-    for name in ("c3_85", "c3_90", "c3_95", "c3_98"):
+    names = ("c3_85", "c3_90", "c3_95", "c3_98")
+    L = []
+    for name in names:
         w = synth.WORKLOADS[name]
-        T, D, F = w.T, w.D, w.F
         inp = synth.make_workload(name)
         dev = {k: torch.from_numpy(inp[k]).to(torch.bfloat16).cuda() for k in ("X", "W1", "W2")}
-        b1 = torch.from_numpy(inp["b1"]).cuda()
-        ctx = ffn24.Context(T, D, F, ffn24.FFN24_DENSE)
+        dev["b1"] = torch.from_numpy(inp["b1"]).cuda()
+        ctx = ffn24.Context(w.T, w.D, w.F, ffn24.FFN24_DENSE)
         ctx.prepare_weights(dev["W1"], dev["W2"])      # inference: the weight pass runs once, outside the timed region
-        Y = torch.empty((T, D), dtype=torch.bfloat16, device="cuda")
+        dev["Y"] = torch.empty((w.T, w.D), dtype=torch.bfloat16, device="cuda")
+        L.append((name, w, dev, ctx))
+        del inp
+    w = L[0][1]
+    T, D, F = w.T, w.D, w.F
 
-        def timed(fn):
-            for _ in range(args.warmup):
-                fn()
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(args.steps):
-                fn()
-            torch.cuda.synchronize()
-            return (time.perf_counter() - t0) / args.steps
-        s24 = timed(lambda: ctx.ffn24_fwd(dev["X"], None, b1, None, Y))
-        sd = timed(lambda: ctx.ffn_fwd(dev["X"], None, b1, None, Y))
-        fl = 4.0 * T * D * F
-        layers[name] = {"sparsity": w.sparsity, "ms": round(s24 * 1e3, 4), "tflops": round(fl / s24 / 1e12, 1),
-                        "dense_ms": round(sd * 1e3, 4), "speedup_vs_dense_ffn": round(sd / s24, 4)}
-        tot24 += s24; totd += sd
+    def run(dense: bool):
+        per = {name: [] for name in names}
+        evs = []
+
+        def step(record):
+            for name, _, dev, ctx in L:
+                if record:
+                    e0 = torch.cuda.Event(enable_timing=True); e0.record()
+                (ctx.ffn_fwd if dense else ctx.ffn24_fwd)(dev["X"], None, dev["b1"], None, dev["Y"])
+                if record:
+                    e1 = torch.cuda.Event(enable_timing=True); e1.record()
+                    evs.append((name, e0, e1))
+        for _ in range(args.warmup):
+            step(False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step(False)
+        torch.cuda.synchronize()
+        mean = (time.perf_counter() - t0) / args.steps
+        for _ in range(args.steps):
+            step(True)
+        torch.cuda.synchronize()
+        for name, e0, e1 in evs:
+            per[name].append(e0.elapsed_time(e1))
+        return mean, {k: sorted(v) for k, v in per.items()}
+    s24, per24 = run(False)
+    sd, perd = run(True)
+    fl = 4.0 * T * D * F
+    layers = {}
+    for name, wl, _, ctx in L:
+        a, b = per24[name], perd[name]
+        layers[name] = {"sparsity": wl.sparsity, "ms_median": round(a[len(a) // 2], 4), "ms_min": round(a[0], 4),
+                        "tflops": round(fl / (a[len(a) // 2] * 1e-3) / 1e12, 1), "dense_ms_median": round(b[len(b) // 2], 4),
+                        "speedup_vs_dense_ffn": round(b[len(b) // 2] / a[len(a) // 2], 4)}
         ctx.close()
-        del dev, Y
-    w = synth.WORKLOADS["c3_90"]
-    fl = 4 * 4.0 * w.T * w.D * w.F
-    print(json.dumps({"metric": "FFN fwd dense-equiv TFLOP/s", "value": round(fl / tot24 / 1e12, 2), "unit": "TFLOP/s", "n_gpus": 1,
-                      "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(tot24 * 1e3, 4), "higher_is_better": True,
+    print(json.dumps({"metric": "FFN fwd dense-equiv TFLOP/s", "value": round(4 * fl / s24 / 1e12, 2), "unit": "TFLOP/s", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(s24 * 1e3, 4), "higher_is_better": True,
                       "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-                      "config": {"workload": "c3: four 2:4 Squared-ReLU FFN layers, fwd, T=16384 d_model=4096 d_ff=16384, 85/90/95/98 % zeros, weights prepared once",
+                      "config": {"workload": "c3: four 2:4 Squared-ReLU FFN layers, fwd, T=16384 d_model=4096 d_ff=16384, 85/90/95/98 % zeros, "
+                                             "weights prepared once, layers cycled (separate buffers, no cache flush)",
                                  "parallelism": "single GPU"},
-                      "speedup_vs_dense_ffn": round(totd / tot24, 4), "layers": layers}))
+                      "dense_ffn": {"ms_per_step": round(sd * 1e3, 4)}, "speedup_vs_dense_ffn": round(sd / s24, 4), "layers": layers}))
+    return 0
+
+
+def run_probe(args) -> int:
+    """What the machine delivers, measured with the library's own probe kernels: register-resident matrix-op rates, the
+    GEMM core with ingredients of its main loop removed (at the workload's sparse-GEMM and up-projection shapes), and a
+    plain streaming copy."""
+    from paper_2503_16672_amd import ffn24, synth
+    w = synth.WORKLOADS[args.workload if args.workload in synth.WORKLOADS else "c4"]
+    T, D, F = w.T, w.D, w.F
+    out = {"probe": "machine rates", "workload_shapes": {"T": T, "d_model": D, "d_ff": F}, "mfma_register_resident": {}, "gemm_decomposition": {}}
+    for kind, name in enumerate(ffn24.MFMA_KINDS):
+        r = ffn24.probe_mfma_rate(kind)
+        out["mfma_register_resident"][name] = {k: round(v, 2) for k, v in r.items()}
+    for label, sparse, (M, N, K) in (("sparse_down T x d_model over d_ff", True, (T, D, F)), ("dense_down T x d_model over d_ff", False, (T, D, F)),
+                                     ("dense_up d_ff x T over d_model", False, (F, T, D))):
+        rows = {}
+        for vname, v in ffn24.GEMM_PROBE_VARIANTS.items():
+            r = ffn24.probe_gemm(sparse, v, M, N, K)
+            rows[vname] = {"ms": round(r["ms"], 4), "mhz": round(r["mhz"]), "tflops_dense_equivalent": round(2.0 * M * N * K / (r["ms"] * 1e-3) / 1e12, 1)}
+        out["gemm_decomposition"][label] = rows
+    nbytes = 1 << 30
+    ms = ffn24.probe_copy(nbytes)
+    out["copy_1GiB"] = {"ms": round(ms, 4), "GBps_read_plus_write": round(2 * nbytes / (ms * 1e-3) / 1e9, 1)}
+    print(json.dumps(out))
     return 0
 
 
@@ -148,8 +215,10 @@ def run_split_sweep(args) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--probe", action="store_true", help="print the machine rates the probe kernels measure (matrix-op issue rate, GEMM "
+                    "main-loop decomposition, copy rate) instead of running the workload")
     ap.add_argument("--workload", default="c4", help="c1, c2, c3 (four forward layers), c3_85..c3_98, c4 (default: forward+backward at the 7B FFN dims), c5 (fp8 forward)")
     ap.add_argument("--fwd-only", action="store_true", help="time the forward pass only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -172,6 +241,8 @@ def main() -> int:
     from paper_2503_16672_amd import ffn24, synth
 
     ffn24.lib()  # fails loudly if libffn24.so is not built; there is no fallback path
+    if args.probe:
+        return run_probe(args)
     if args.workload == "c3":
         return run_c3(args)
     if args.split_sweep:
@@ -223,40 +294,33 @@ def main() -> int:
         if bwd:
             ctx.ffn_bwd(dev["dY"], grads)
 
-    def timed(fn, warmup, steps):
-        for _ in range(warmup):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / steps
-
     if args.calib_copy:
-        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        ffn24.probe_copy(1 << 30, 1)
 
-    ctx.set_profiling(True)   # event pairs around every kernel, on the launch stream; no synchronisation added
-    sec24 = timed(step24, args.warmup, args.steps)
-    # per-kernel durations: average over the same number of steps, reading the events after each step
+    # what the matrix pipes of THIS chip sustain right now with operands in registers (no memory traffic): the live
+    # denominator beside the published peak
+    reg = {}
+    for kind in ((2, 3) if fp8 else (0, 1)):
+        reg[kind & 1] = ffn24.probe_mfma_rate(kind, 8000)
+
+    # timed region: profiling off, nothing but the steps
+    sec24, med24, min24 = _time_steps(torch, step24, args.warmup, args.steps)
+    sec_dense, med_dense, min_dense = (_time_steps(torch, step_dense, args.warmup, args.steps) if not rowwise else (float("nan"),) * 3)
+    # separate pass: event pairs around every kernel (on the launch stream) and a clock sample in every GEMM kernel
+    ctx.set_profiling(True)
     k24 = list(range(0, 7 if bwd else 2)) + ([13, 14] if bwd else []) + ([15, 16] if args.split and bwd else []) + ([17] if rowwise else [])
     kd = [] if rowwise else list(range(7, 13 if bwd else 9))
-    acc = {k: 0.0 for k in k24 + kd}
-    for _ in range(args.steps):
-        step24()
-        torch.cuda.synchronize()
-        for k in k24:
-            acc[k] += ctx.kernel_ms(k)
-    sec_dense = timed(step_dense, args.warmup, args.steps) if not rowwise else float("nan")
-    for _ in range(args.steps if not rowwise else 0):
-        step_dense()
-        torch.cuda.synchronize()
-        for k in kd:
-            acc[k] += ctx.kernel_ms(k)
+    acc = {k: [] for k in k24 + kd}
+    mhz = {k: [] for k in k24 + kd}
+    for fn, ids in ((step24, k24), (step_dense, kd)):
+        for _ in range(min(args.steps, 20) if ids else 0):
+            fn()
+            torch.cuda.synchronize()
+            for k in ids:
+                acc[k].append(ctx.kernel_ms(k))
+                m = ctx.kernel_mhz(k)
+                if m:
+                    mhz[k].append(m)
     ctx.set_profiling(False)
     telemetry = None
     if args.telemetry and not fp8:
@@ -265,7 +329,8 @@ def main() -> int:
         telemetry = {"zeros": round(1 - t["nonzero"] / t["elements"], 5), "dropped_tokenwise": round(1 - t["kept_tokenwise"] / t["nonzero"], 6),
                      "dropped_featurewise_on_top": round(1 - t["kept_featurewise"] / t["kept_tokenwise"], 6) if t["kept_featurewise"] else None,
                      "use_sparse_at_0.85": ctx.policy_use_sparse(0.85), "counts": t}
-    kernel_ms = {ffn24.KERNEL_NAMES[k]: acc[k] / args.steps for k in acc}
+    kernel_ms = {ffn24.KERNEL_NAMES[k]: sum(v) / len(v) for k, v in acc.items()}
+    kernel_mhz = {ffn24.KERNEL_NAMES[k]: sum(v) / len(v) for k, v in mhz.items() if v}
 
     # standalone 2:4 compression of a dense [T, F] activation with the workload's sparsity (HBM-bound streaming kernel;
     # launched on torch's current stream, so torch events bracket it)
@@ -295,8 +360,13 @@ def main() -> int:
     for name, ms in kernel_ms.items():
         if name in KERNEL_FLOPS:
             tf = KERNEL_FLOPS[name] * tdf / (ms * 1e-3) / 1e12
+            sp = name in SPARSE
+            rr = reg[1 if sp else 0]["tflops_dense_equivalent"] / (2.0 if sp else 1.0)      # executed flops of the register-resident loop
             kernels[name] = {"ms": round(ms, 4), "tflops_executed": round(tf, 1), "frac_of_dense_mfma_peak": round(tf / peak, 4),
-                             "frac_of_register_resident_rate": round(tf / REGISTER_RESIDENT[("fp8" if fp8 else "bf16", name in SPARSE)], 4)}
+                             "frac_of_register_resident_rate": round(tf / rr, 4)}
+            if name in kernel_mhz:
+                kernels[name]["sclk_mhz"] = round(kernel_mhz[name])
+                kernels[name]["frac_of_peak_at_that_clock"] = round(tf / (peak * kernel_mhz[name] / NOMINAL_MHZ), 4)
             if name in SPARSE:
                 kernels[name]["tflops_dense_equivalent"] = round(2 * tf, 1)
         else:
@@ -317,9 +387,18 @@ def main() -> int:
             kernels[name] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / 8000.0, 4)}
     dom = max((n for n in kernel_ms if n in KERNEL_FLOPS and not n.startswith("dense_")), key=lambda n: kernel_ms[n])
     achieved = KERNEL_FLOPS[dom] * tdf / (kernel_ms[dom] * 1e-3) / 1e12
+    traffic = measured_traffic(dom, w.name)
+    es = 1.0 if fp8 else 2.0
+    # algorithmic HBM bytes of a launch of the dominant kernel (an up-projection or dH GEMM): both operands once, the
+    # compressed activation (values + metadata) written, and for the dH GEMM the saved activation read as well
+    alg = es * (D * F + T * D) + (es / 2 + 0.125) * T * F + ((1.0 + 0.125) * T * F if dom == "dh_gather" else 0.0)
     roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 1), "peak": peak, "unit": "TFLOP/s",
-                "frac": round(achieved / peak, 4), "traffic": measured_traffic(dom, w.name),
-                "note": "executed MFMA flops of the launch / its HIP-event duration; a sparse kernel executes half its dense-equivalent flops"}
+                "frac": round(achieved / peak, 4), "traffic": traffic,
+                "algorithmic_bytes": alg, "traffic_over_algorithmic": round(traffic / alg, 2) if traffic else None,
+                "sclk_mhz": round(kernel_mhz[dom]) if dom in kernel_mhz else None,
+                "frac_of_peak_at_that_clock": round(achieved / (peak * kernel_mhz[dom] / NOMINAL_MHZ), 4) if dom in kernel_mhz else None,
+                "note": "executed MFMA flops of the launch / its HIP-event duration (a sparse kernel executes half its dense-equivalent flops); "
+                        "peak is the published one at 2.4 GHz, sclk_mhz the clock the kernel really ran at"}
 
     cpu = None
     if not args.no_cpu:
@@ -342,7 +421,8 @@ def main() -> int:
     out = {
         "metric": "FFN fwd+bwd dense-equiv TFLOP/s" if bwd else "FFN fwd dense-equiv TFLOP/s",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(sec24 * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(sec24 * 1e3, 4), "ms_per_step_median": round(med24 * 1e3, 4), "ms_per_step_min": round(min24 * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "fp8" if fp8 else "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: 2:4 Squared-ReLU FFN {'fwd+bwd' if bwd else 'fwd'}, T={T} d_model={D} d_ff={F}, target sparsity {w.sparsity}"
                                + (f", {args.split} dense features in the weight gradients" if args.split and bwd else "")
@@ -350,7 +430,9 @@ def main() -> int:
                                + (", weights prepared once" if prepared else ""),
                    "T": T, "d_model": D, "d_ff": F, "parallelism": "single GPU"},
         "frac_of_sparse_mfma_peak": round(value / (2 * peak), 4),
-        "dense_ffn": None if rowwise else {"ms_per_step": round(sec_dense * 1e3, 4), "tflops": round(flops_step / sec_dense / 1e12, 2)},
+        "dense_ffn": None if rowwise else {"ms_per_step": round(sec_dense * 1e3, 4), "ms_per_step_median": round(med_dense * 1e3, 4),
+                                           "ms_per_step_min": round(min_dense * 1e3, 4), "tflops": round(flops_step / sec_dense / 1e12, 2)},
+        "register_resident_mfma": {("sparse" if k else "dense"): {a: round(b, 2) for a, b in v.items()} for k, v in reg.items()},
         "speedup_vs_dense_ffn": None if rowwise else round(sec_dense / sec24, 4),
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "sparsify24_standalone": sparsify,
     }

@@ -239,6 +239,27 @@ FFN24_API int ffn24_copy_saved(ffn24_ctx* ctx, int which, void* dst, int64_t dst
  * 17 the row-wise fp8 quantisation kernel.  Returns FFN24_ERR_STATE if that kernel has not run with profiling on. */
 FFN24_API int ffn24_set_profiling(ffn24_ctx* ctx, int on);
 FFN24_API int ffn24_kernel_ms(ffn24_ctx* ctx, int kernel, float* ms);
+/* The shader clock (MHz) GEMM kernel `kernel` of the most recent profiled call really ran at: the first 64 workgroups
+ * each sample the shader-clock counter against the constant 100 MHz counter over their lifetime.  Under matrix load the
+ * chip settles far below its nominal 2.4 GHz, which every fraction of the published peak has to be read against.
+ * FFN24_ERR_STATE for the streaming kernels (they take no sample) or if the kernel has not run with profiling on. */
+FFN24_API int ffn24_kernel_mhz(ffn24_ctx* ctx, int kernel, float* mhz);
+
+/* Measurement probes (no paper passage: they measure the machine, for the benchmark's report).  Each allocates its own
+ * device buffers, runs on the default stream and waits for its own work; not for serving code.
+ *   ffn24_probe_mfma_rate: a register-resident loop of matrix instructions with no memory traffic, one wave per SIMD on
+ *     every CU, pseudo-random operands.  kind 0 dense bf16 32x32x16, 1 sparse bf16 32x32x32, 2 dense fp8 32x32x64,
+ *     3 sparse fp8 32x32x64; iters x 16 ops per wave.  Returns shader-clock cycles per op and wave, the clock (MHz) the
+ *     loop ran at, and the chip-wide rate in dense-equivalent TFLOP/s (a sparse op counts its dense equivalent).
+ *   ffn24_probe_gemm: the library's GEMM core (dense bf16 if sparse == 0, else 2:4 bf16; plain row-major epilogue) on
+ *     pseudo-random operands, M, N multiples of 256, K a multiple of 128 and >= 512, with ingredients of its main loop
+ *     taken out: variant 0 all of it, 1 no global->LDS DMA, 6 DMA only (no matrix ops, no LDS fragment reads),
+ *     5 matrix ops only, 8 every K stage re-reads the first 8 stages (all L2 hits), 14 = 8 + 6.  Returns the median
+ *     kernel duration over `reps` launches and the clock it ran at.  Variants other than 0 compute nothing meaningful.
+ *   ffn24_probe_copy: a plain device-to-device copy kernel of `bytes` bytes (a multiple of 4096): median duration. */
+FFN24_API int ffn24_probe_mfma_rate(int kind, int iters, double* cycles_per_op, double* mhz, double* tflops_dense_equivalent);
+FFN24_API int ffn24_probe_gemm(int sparse, int variant, int64_t M, int64_t N, int64_t K, int reps, double* ms_median, double* mhz);
+FFN24_API int ffn24_probe_copy(int64_t bytes, int reps, double* ms_median);
 
 FFN24_API const char* ffn24_strerror(int code);
 

@@ -68,6 +68,7 @@ struct ffn24_ctx {
   int profiling;
   hipEvent_t ev[NUM_KERNELS][2];
   int ev_valid[NUM_KERNELS];
+  unsigned long long* clk;      // clock samples of the GEMM kernels, CLK_SLOTS pairs per kernel id (gemm_core.hpp)
 };
 
 namespace {
@@ -75,10 +76,10 @@ namespace {
 struct Timed {
   ffn24_ctx* c; int k; hipStream_t s;
   Timed(ffn24_ctx* c_, int k_, hipStream_t s_) : c(c_), k(k_), s(s_) {
-    if (c->profiling) (void)hipEventRecord(c->ev[k][0], s);
+    if (c->profiling) { (void)hipEventRecord(c->ev[k][0], s); tl_gemm_clk = c->clk + (size_t)k * 2 * CLK_SLOTS; }
   }
   int done(int rc) {
-    if (c->profiling) { (void)hipEventRecord(c->ev[k][1], s); c->ev_valid[k] = (rc == 0); }
+    if (c->profiling) { (void)hipEventRecord(c->ev[k][1], s); c->ev_valid[k] = (rc == 0); tl_gemm_clk = nullptr; }
     return rc;
   }
 };
@@ -89,6 +90,7 @@ int free_all(ffn24_ctx* c) {
                   c->W1t, c->W2t, c->Xt, c->dYt, c->Hd_t, c->dZd_t, c->W2p, c->W1p,
                   c->nnz, c->row_of_feat, c->feat_of_row, c->Hdn_t, c->dZdn_t, c->dW1t, c->Hc16, c->meta16, c->rowmax, c->rsh, c->perm};
   for (void* b : bufs) if (b && hipFree(b) != hipSuccess) bad = 1;
+  if (c->clk && hipFree(c->clk) != hipSuccess) bad = 1;
   if (c->tele && hipFree(c->tele) != hipSuccess) bad = 1;
   if (c->tele_sum && hipFree(c->tele_sum) != hipSuccess) bad = 1;
   if (c->tele_host && hipHostFree(c->tele_host) != hipSuccess) bad = 1;
@@ -214,6 +216,8 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
   if (ok && (flags & FFN24_DEBUG_DUMP_H)) ok = hipMalloc(&c->Hdbg, 2 * tf) == hipSuccess;
   for (int k = 0; ok && k < NUM_KERNELS; k++)
     for (int j = 0; ok && j < 2; j++) ok = hipEventCreate(&c->ev[k][j]) == hipSuccess;
+  if (ok) ok = hipMalloc(reinterpret_cast<void**>(&c->clk), (size_t)NUM_KERNELS * 2 * CLK_SLOTS * 8) == hipSuccess &&
+               hipMemset(c->clk, 0, (size_t)NUM_KERNELS * 2 * CLK_SLOTS * 8) == hipSuccess;
   if (!ok) { (void)hipGetLastError(); free_all(c); delete c; return FFN24_ERR_HIP; }
   *out = c;
   return FFN24_OK;
@@ -334,6 +338,40 @@ int ffn24_kernel_ms(ffn24_ctx* c, int k, float* ms) {
   if (hipEventSynchronize(c->ev[k][1]) != hipSuccess) return FFN24_ERR_HIP;
   if (hipEventElapsedTime(ms, c->ev[k][0], c->ev[k][1]) != hipSuccess) return FFN24_ERR_HIP;
   return FFN24_OK;
+}
+
+int ffn24_kernel_mhz(ffn24_ctx* c, int k, float* mhz) {
+  if (!c || !mhz) return FFN24_ERR_NULL;
+  if (k < 0 || k >= NUM_KERNELS) return FFN24_ERR_SHAPE;
+  if (!c->ev_valid[k]) return FFN24_ERR_STATE;
+  if (hipEventSynchronize(c->ev[k][1]) != hipSuccess) return FFN24_ERR_HIP;
+  unsigned long long h[2 * CLK_SLOTS];
+  if (hipMemcpy(h, c->clk + (size_t)k * 2 * CLK_SLOTS, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return FFN24_ERR_HIP;
+  double t = 0, r = 0;
+  for (int i = 0; i < CLK_SLOTS; i++) { t += (double)h[2 * i]; r += (double)h[2 * i + 1]; }
+  if (r <= 0) return FFN24_ERR_STATE;   // not a GEMM kernel: nothing samples the clock there
+  *mhz = (float)(100.0 * t / r);
+  return FFN24_OK;
+}
+
+int ffn24_probe_mfma_rate(int kind, int iters, double* cycles_per_op, double* mhz, double* tflops_dense_equivalent) {
+  if (!cycles_per_op || !mhz || !tflops_dense_equivalent) return FFN24_ERR_NULL;
+  if (kind < 0 || kind > 3 || iters < 1 || iters > (1 << 22)) return FFN24_ERR_SHAPE;
+  return probe_mfma_rate(kind, iters, cycles_per_op, mhz, tflops_dense_equivalent) ? FFN24_ERR_HIP : FFN24_OK;
+}
+
+int ffn24_probe_gemm(int sparse, int variant, int64_t M, int64_t N, int64_t K, int reps, double* ms_median, double* mhz) {
+  if (!ms_median || !mhz) return FFN24_ERR_NULL;
+  if (M <= 0 || N <= 0 || K < 512 || M % 256 || N % 256 || K % 128 || M > (1 << 16) || N > (1 << 16) || K > (1 << 16) || reps < 1 || reps > 1000)
+    return FFN24_ERR_SHAPE;
+  int rc = probe_gemm(sparse != 0, variant, (int)M, (int)N, (int)K, reps, ms_median, mhz);
+  return rc == 2 ? FFN24_ERR_SHAPE : (rc ? FFN24_ERR_HIP : FFN24_OK);
+}
+
+int ffn24_probe_copy(int64_t bytes, int reps, double* ms_median) {
+  if (!ms_median) return FFN24_ERR_NULL;
+  if (bytes < 4096 || bytes % 4096 || bytes > ((int64_t)16 << 30) || reps < 1 || reps > 1000) return FFN24_ERR_SHAPE;
+  return probe_copy((size_t)bytes, reps, ms_median) ? FFN24_ERR_HIP : FFN24_OK;
 }
 
 int ffn24_saved_bytes(ffn24_ctx* c, int which, int64_t* nbytes) {

@@ -52,6 +52,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <utility>
+#include "launch.hpp"
 
 namespace ffn24 {
 
@@ -75,7 +76,16 @@ struct GemmArgs {
   int a_panel;           // A (and its metadata) is in panel form (see above) instead of row-major
   const int* b_rowmap;   // optional: row n of B is taken from memory row b_rowmap[n] (token permutation, gathered by the DMA)
   int b_panel;           // B is in the B panel form (below) instead of row-major; not together with b_rowmap
+  unsigned long long* clk;   // optional (profiling): workgroup i < CLK_SLOTS stores its own {shader-clock ticks, 100 MHz ticks} at 2 i
 };
+
+// Measurement variants of the GEMM core (bit mask; 0 = the product).  They exist so that what bounds the main loop can be
+// measured with this very code -- the same DMA plan, LDS image, fragment reads and schedule -- with one ingredient taken
+// out; they compute nothing useful.  Only the probe entry points of the library instantiate them.
+constexpr int PROBE_NO_DMA = 1;      // no global->LDS DMA is issued (the matrix ops run on whatever the LDS holds)
+constexpr int PROBE_NO_MFMA = 2;     // no matrix ops
+constexpr int PROBE_NO_FRAG = 4;     // no LDS fragment reads
+constexpr int PROBE_K_WRAP = 8;      // the K stages walk round the first 8 stages of the operands: every line is an L2 hit
 
 // B panel form: the dense panel form (64-byte pieces, a24_piece) whose rows are, inside every block of 256, stored in the
 // order the block tile keeps them in LDS: position q of a block holds row unperm_n(q), i.e. row n sits at b_panel_pos(n).
@@ -142,7 +152,7 @@ __device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC
 // ------------------------------------------------------------------------------------------------
 // global -> LDS DMA plan of one wave
 // ------------------------------------------------------------------------------------------------
-template <bool SPARSE, bool F8 = false>
+template <bool SPARSE, bool F8 = false, int PROBE = 0>
 struct Dma {
   using G = Geo<SPARSE, F8>;
   const char* a;      // block's first A row (uniform)
@@ -202,6 +212,8 @@ struct Dma {
   // DMA instruction J of stage kt into the stage buffer at `buf` (uniform LDS pointer)
   template <int J>
   __device__ __forceinline__ void issue(int kt, char* buf) const {
+    if constexpr ((PROBE & PROBE_NO_DMA) != 0) return;
+    if constexpr ((PROBE & PROBE_K_WRAP) != 0) kt &= 7;
     if constexpr (J < 4) {
       __builtin_amdgcn_global_load_lds((glb_char*)(a + (size_t)kt * a_stage + va[J]), (lds_char*)(buf + (4 * wave + J) * 1024), 16, 0, 0);
     } else if constexpr (!SPARSE) {
@@ -240,15 +252,17 @@ struct LaneCtx {
 struct FragD {
   bf16x8 a[4], b[4];
 };
-template <int S, int I>
+template <int S, int I, int PROBE = 0>
 __device__ __forceinline__ void load_frag_dense1(const char* buf, const LaneCtx& L, FragD& f) {
+  if constexpr ((PROBE & PROBE_NO_FRAG) != 0) return;
   constexpr int i = I & 3;
   int c = ((2 * S + L.h) ^ L.sw4) << 4;
   if constexpr (I < 4) f.a[i] = *reinterpret_cast<const bf16x8*>(buf + L.a_row64 + i * (32 * 64) + c);
   else f.b[i] = *reinterpret_cast<const bf16x8*>(buf + Geo<false>::B_OFF + L.b_row64 + i * (32 * 64) + c);
 }
-template <int M>
+template <int M, int PROBE = 0>
 __device__ __forceinline__ void mfma_dense1(const FragD& f, f32x16 (&acc)[4][4]) {
+  if constexpr ((PROBE & PROBE_NO_MFMA) != 0) return;
   constexpr int mi = M >> 2, ni = M & 3;
   acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[mi], f.b[ni], acc[mi][ni], 0, 0, 0);
 }
@@ -261,8 +275,9 @@ __device__ __forceinline__ i32x8 cat16(const bf16x8& lo, const bf16x8& hi) {
   i32x4 l = __builtin_bit_cast(i32x4, lo), h = __builtin_bit_cast(i32x4, hi);
   return __builtin_shufflevector(l, h, 0, 1, 2, 3, 4, 5, 6, 7);
 }
-template <int M>
+template <int M, int PROBE = 0>
 __device__ __forceinline__ void mfma_dense_f8(const FragD& f0, const FragD& f1, f32x16 (&acc)[4][4]) {
+  if constexpr ((PROBE & PROBE_NO_MFMA) != 0) return;
   constexpr int mi = M >> 2, ni = M & 3;
   // Written as inline assembly with the accumulator tied in place: through the builtin the compiler gives this
   // instruction a destination different from its accumulator input, which with all 256 accumulation registers in
@@ -296,8 +311,9 @@ __device__ __forceinline__ void load_idx_sparse1(const char* buf, const LaneCtx&
   }
 }
 // fragment I of instruction S: I < 4 -> a[I]; 4..7 -> low half of b[I-4]; 8..11 -> high half of b[I-8]
-template <bool F8, int S, int I>
+template <bool F8, int S, int I, int PROBE = 0>
 __device__ __forceinline__ void load_frag_sparse1(const char* buf, const LaneCtx& L, FragS& f) {
+  if constexpr ((PROBE & PROBE_NO_FRAG) != 0) return;
   constexpr int i = I & 3;
   if constexpr (I < 4) {
     f.a[i] = *reinterpret_cast<const bf16x8*>(buf + L.a_row64 + i * (32 * 64) + (((2 * L.h + S) ^ L.sw4) << 4));
@@ -310,8 +326,9 @@ __device__ __forceinline__ void load_frag_sparse1(const char* buf, const LaneCtx
 }
 // fp8: v_smfmac_f32_32x32x64_fp8_fp8 has, byte for byte, the operand layout of the bf16 instruction (measured): A 16
 // stored bytes of the lane half's window, B the two 16-byte chunks, and a full 32-bit index word per instruction.
-template <bool F8, int S, int M>
+template <bool F8, int S, int M, int PROBE = 0>
 __device__ __forceinline__ void mfma_sparse1(const FragS& f, const IdxWords<F8> (&idx)[4], f32x16 (&acc)[4][4]) {
+  if constexpr ((PROBE & PROBE_NO_MFMA) != 0) return;
   constexpr int mi = M >> 2, ni = M & 3;
   if constexpr (F8) {
     acc[mi][ni] = __builtin_amdgcn_smfmac_f32_32x32x64_fp8_fp8(__builtin_bit_cast(i32x4, f.a[mi]), cat16(f.blo[ni], f.bhi[ni]), acc[mi][ni],
@@ -360,7 +377,7 @@ __device__ __forceinline__ void tile_coords(int ntm, int ntn, int pid, int& tm, 
 //   m_lane = global row of acc[0][*][0] for this lane (its 64 rows are m_lane + 16*mi + v),
 //   n_lane = global column of acc[*][0][*] (its 4 columns are n_lane + ni).
 // One block tile of one GEMM: tile number `pid` of g (workgroup-uniform), LDS ring at `smem`.
-template <bool SPARSE, class Epi, bool F8 = false>
+template <bool SPARSE, class Epi, bool F8 = false, int PROBE = 0>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi::Args& ea, char* smem, int pid) {
   using G = Geo<SPARSE, F8>;
   constexpr int NB = G::NB, NDMA = G::NDMA;
@@ -379,7 +396,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi:
   L.sw4 = swz4(L.rho);
   L.sw8 = (L.rho & 7) ^ (L.rho >> 3);
 
-  Dma<SPARSE, F8> dma;
+  Dma<SPARSE, F8, PROBE> dma;
   dma.init(g, m0, n0, tid);
 
   f32x16 acc[4][4];
@@ -411,14 +428,14 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi:
     FragS f0, f1;
     IdxWords<F8> idx[4];
     static_for<4>([&](auto I) { load_idx_sparse1<F8, I>(smem, L, idx); });
-    static_for<12>([&](auto I) { load_frag_sparse1<F8, 0, I>(smem, L, f0); });
+    static_for<12>([&](auto I) { load_frag_sparse1<F8, 0, I, PROBE>(smem, L, f0); });
     auto stage = [&](int kt, char* cur, char* nxt, auto mode) {
       constexpr int MODE = decltype(mode)::value;
       IdxWords<F8> idx_n[4] = {};
       FFN24_FENCE();
       static_for<16>([&](auto M) {
-        mfma_sparse1<F8, 0, M>(f0, idx, acc);
-        if constexpr (M < 12) load_frag_sparse1<F8, 1, M>(cur, L, f1);
+        mfma_sparse1<F8, 0, M, PROBE>(f0, idx, acc);
+        if constexpr (M < 12) load_frag_sparse1<F8, 1, M, PROBE>(cur, L, f1);
         FFN24_FENCE();
       });
       if constexpr (MODE != 2) {
@@ -428,11 +445,11 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi:
       }
       FFN24_FENCE();
       static_for<16>([&](auto M) {
-        mfma_sparse1<F8, 1, M>(f1, idx, acc);
+        mfma_sparse1<F8, 1, M, PROBE>(f1, idx, acc);
         if constexpr (MODE == 0 && M < NDMA) dma.template issue<M>(kt + NB, cur);
         if constexpr (MODE != 2) {
           if constexpr (M < 4) load_idx_sparse1<F8, M>(nxt, L, idx_n);
-          if constexpr (M < 12) load_frag_sparse1<F8, 0, M>(nxt, L, f0);
+          if constexpr (M < 12) load_frag_sparse1<F8, 0, M, PROBE>(nxt, L, f0);
         }
         FFN24_FENCE();
       });
@@ -454,17 +471,17 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi:
     // the DMA of the stage that reuses this stage's buffer (its fragments are already in registers) ride on them;
     // one barrier at the end of the stage.  Two fragment sets alternate.
     FragD fr[2][2];
-    static_for<8>([&](auto I) { load_frag_dense1<0, I>(smem, L, fr[0][0]); });
-    static_for<8>([&](auto I) { load_frag_dense1<1, I>(smem, L, fr[0][1]); });
+    static_for<8>([&](auto I) { load_frag_dense1<0, I, PROBE>(smem, L, fr[0][0]); });
+    static_for<8>([&](auto I) { load_frag_dense1<1, I, PROBE>(smem, L, fr[0][1]); });
     auto stage = [&](int kt, char* cur, char* nxt, auto par, auto mode) {
       constexpr int P = decltype(par)::value, MODE = decltype(mode)::value;
       FFN24_FENCE();
       static_for<16>([&](auto M) {
-        mfma_dense_f8<M>(fr[P][0], fr[P][1], acc);
+        mfma_dense_f8<M, PROBE>(fr[P][0], fr[P][1], acc);
         if constexpr (MODE == 0 && M < NDMA) dma.template issue<M>(kt + NB, cur);
         if constexpr (MODE != 2) {
-          if constexpr (M < 8) load_frag_dense1<0, M>(nxt, L, fr[P ^ 1][0]);
-          else load_frag_dense1<1, M - 8>(nxt, L, fr[P ^ 1][1]);
+          if constexpr (M < 8) load_frag_dense1<0, M, PROBE>(nxt, L, fr[P ^ 1][0]);
+          else load_frag_dense1<1, M - 8, PROBE>(nxt, L, fr[P ^ 1][1]);
         }
         FFN24_FENCE();
       });
@@ -499,13 +516,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi:
     advance(kt + 1, P1{}, M2{});
   } else {
     FragD f0, f1;
-    static_for<8>([&](auto I) { load_frag_dense1<0, I>(smem, L, f0); });
+    static_for<8>([&](auto I) { load_frag_dense1<0, I, PROBE>(smem, L, f0); });
     auto stage = [&](int kt, char* cur, char* nxt, auto mode) {
       constexpr int MODE = decltype(mode)::value;
       FFN24_FENCE();
       static_for<16>([&](auto M) {
-        mfma_dense1<M>(f0, acc);
-        if constexpr (M < 8) load_frag_dense1<1, M>(cur, L, f1);
+        mfma_dense1<M, PROBE>(f0, acc);
+        if constexpr (M < 8) load_frag_dense1<1, M, PROBE>(cur, L, f1);
         FFN24_FENCE();
       });
       if constexpr (MODE != 2) {
@@ -515,9 +532,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi:
       }
       FFN24_FENCE();
       static_for<16>([&](auto M) {
-        mfma_dense1<M>(f1, acc);
+        mfma_dense1<M, PROBE>(f1, acc);
         if constexpr (MODE == 0 && M < NDMA) dma.template issue<M>(kt + NB, cur);
-        if constexpr (MODE != 2 && M < 8) load_frag_dense1<0, M>(nxt, L, f0);
+        if constexpr (MODE != 2 && M < 8) load_frag_dense1<0, M, PROBE>(nxt, L, f0);
         FFN24_FENCE();
       });
     };
@@ -549,10 +566,29 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi:
   Epi::run(ea, acc, m_lane, n_lane);
 }
 
-template <bool SPARSE, class Epi, bool F8 = false>
+// Clock sample of a workgroup (profiling only): ticks of the shader clock and of the constant 100 MHz clock between its
+// first and last instruction; their ratio is the clock the kernel really ran at (it drops well below the nominal 2.4 GHz
+// under matrix load).
+struct ClkSample {
+  unsigned long long t0, r0;
+  __device__ __forceinline__ void begin(const GemmArgs& g) {
+    if (g.clk) { t0 = __builtin_amdgcn_s_memtime(); r0 = __builtin_amdgcn_s_memrealtime(); }
+  }
+  __device__ __forceinline__ void end(const GemmArgs& g) {
+    if (g.clk && blockIdx.x < CLK_SLOTS) {
+      unsigned long long t1 = __builtin_amdgcn_s_memtime(), r1 = __builtin_amdgcn_s_memrealtime();
+      if (threadIdx.x == 0) { g.clk[2 * blockIdx.x] = t1 - t0; g.clk[2 * blockIdx.x + 1] = r1 - r0; }
+    }
+  }
+};
+
+template <bool SPARSE, class Epi, bool F8 = false, int PROBE = 0>
 __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(GemmArgs g, typename Epi::Args ea) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  gemm_tile<SPARSE, Epi, F8>(g, ea, smem, blockIdx.x);
+  ClkSample cs;
+  cs.begin(g);
+  gemm_tile<SPARSE, Epi, F8, PROBE>(g, ea, smem, blockIdx.x);
+  cs.end(g);
 }
 
 // Two GEMMs in one launch: the first `nd_tiles` workgroups compute the tiles of a dense GEMM gd, the others those of
@@ -565,8 +601,11 @@ __global__ void __launch_bounds__(GEMM_THREADS) gemm_pair_kernel(GemmArgs gd, ty
                                                                   GemmArgs gs, typename Epi::Args eas) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int pid = blockIdx.x;
+  ClkSample cs;
+  cs.begin(gs);
   if (pid < nd_tiles) gemm_tile<false, Epi>(gd, ead, smem, pid);
   else gemm_tile<true, Epi>(gs, eas, smem, pid - nd_tiles);
+  cs.end(gs);
 }
 
 // ------------------------------------------------------------------------------------------------

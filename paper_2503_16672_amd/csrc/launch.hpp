@@ -23,6 +23,11 @@ inline int ensure_dynamic_lds(const void* kern, int bytes, std::atomic<bool> (&d
   return 0;
 }
 
+// Where the GEMM launches of the calling thread store their clock samples (gemm_core.hpp, GemmArgs::clk): set by the
+// C-ABI layer around a launch when the context profiles, NULL otherwise.
+inline thread_local unsigned long long* tl_gemm_clk = nullptr;
+constexpr int CLK_SLOTS = 64;   // workgroups of a launch that store a clock sample (a pair of 64-bit counts each)
+
 // Telemetry counters (the sparsity level of the activation and what 2:4 keeps of it): TELE_SLOTS 64-bit slots per
 // quantity, each in a 128-byte line of its own and summed when read, so that the atomics of a launch spread over many
 // lines instead of queueing on one.  Slot s of quantity k is word tele_index(k, s).
@@ -102,5 +107,19 @@ int launch_unpanel(const void* src, int rows, int npanels, int piece_bytes, void
 int launch_transpose(const void* in, int R, int C, void* out, int out_form, void* in_panel, int in_panel_b, const int* in_rowmap, hipStream_t s);
 // the same for 1-byte elements (fp8): in [R][C] -> out [C][R]; panel forms: 64-byte pieces of 64 k
 int launch_transpose8(const void* in, int R, int C, void* out, int out_form, hipStream_t s);
+
+// ------------------------------------------------------------------------------------------------
+// measurement probes (k_probe.hip); they allocate their own buffers and wait for their own work
+// ------------------------------------------------------------------------------------------------
+// Register-resident matrix-op loop, one wave per SIMD on every CU, random operands: cycles per op and wave (shader-clock
+// ticks), the clock it ran at, and the chip-wide rate.  kind: 0 dense bf16 32x32x16, 1 sparse bf16 32x32x32,
+// 2 dense fp8 32x32x64, 3 sparse fp8 32x32x64.
+int probe_mfma_rate(int kind, int iters, double* cycles_per_op, double* mhz, double* tflops_dense_equivalent);
+// The GEMM core on pseudo-random panel-form operands with ingredients taken out (`variant` = mask of PROBE_* in
+// gemm_core.hpp; supported: 0, NO_DMA, NO_MFMA | NO_FRAG, NO_DMA | NO_FRAG, K_WRAP, K_WRAP | NO_MFMA | NO_FRAG):
+// median kernel duration over `reps` launches and the clock it ran at.
+int probe_gemm(int sparse, int variant, int M, int N, int K, int reps, double* ms_median, double* mhz);
+// Plain device-to-device copy kernel of `bytes` bytes (16 per work item): GB/s read + written.
+int probe_copy(size_t bytes, int reps, double* ms_median);
 
 }  // namespace ffn24

@@ -5,9 +5,11 @@
 
 namespace ffn24 {
 
-template <bool SPARSE, class Epi, bool F8 = false>
-static int launch_gemm(const GemmArgs& g, const typename Epi::Args& ea, hipStream_t s) {
-  auto kern = gemm_kernel<SPARSE, Epi, F8>;
+template <bool SPARSE, class Epi, bool F8 = false, int PROBE = 0>
+static int launch_gemm(const GemmArgs& g_in, const typename Epi::Args& ea, hipStream_t s) {
+  GemmArgs g = g_in;
+  g.clk = tl_gemm_clk;
+  auto kern = gemm_kernel<SPARSE, Epi, F8, PROBE>;
   constexpr int lds = Geo<SPARSE, F8>::LDS_TOTAL;
   static std::atomic<bool> configured[MAX_DEVICES] = {};
   if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds, configured)) return rc;
@@ -18,7 +20,9 @@ static int launch_gemm(const GemmArgs& g, const typename Epi::Args& ea, hipStrea
 
 // dense GEMM gd and sparse GEMM gs in one launch (gemm_pair_kernel)
 template <class Epi>
-static int launch_gemm_pair(const GemmArgs& gd, const typename Epi::Args& ead, const GemmArgs& gs, const typename Epi::Args& eas, hipStream_t s) {
+static int launch_gemm_pair(const GemmArgs& gd, const typename Epi::Args& ead, const GemmArgs& gs_in, const typename Epi::Args& eas, hipStream_t s) {
+  GemmArgs gs = gs_in;
+  gs.clk = tl_gemm_clk;
   auto kern = gemm_pair_kernel<Epi>;
   constexpr int lds = Geo<true>::LDS_TOTAL > Geo<false>::LDS_TOTAL ? Geo<true>::LDS_TOTAL : Geo<false>::LDS_TOTAL;
   static std::atomic<bool> configured[MAX_DEVICES] = {};

@@ -27,7 +27,7 @@ FFN24_TELEMETRY = 64
 EXPORTS = (
     "ffn24_ctx_create", "ffn24_ctx_destroy", "ffn24_set_scales", "ffn24_set_row_scales", "ffn24_set_token_permutation", "ffn24_set_split", "sparsify24", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd",
     "ffn_fwd", "ffn_bwd", "ffn24_prepare_weights", "ffn24_get_telemetry", "ffn24_policy_use_sparse", "ffn24_saved_bytes", "ffn24_copy_saved", "ffn24_set_profiling", "ffn24_kernel_ms", "ffn24_strerror",
-    "ffn24_static_scratch_needed", "ffn24_fwd_static",
+    "ffn24_static_scratch_needed", "ffn24_fwd_static", "ffn24_kernel_mhz", "ffn24_probe_mfma_rate", "ffn24_probe_gemm", "ffn24_probe_copy",
 )
 
 KERNEL_NAMES = ("up_prune24", "down_sp", "dh_gather", "dx_sp", "featurewise24", "dw2_sp", "dw1_sp",
@@ -73,6 +73,11 @@ def lib() -> ctypes.CDLL:
         L.ffn24_kernel_ms.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_float)]
         L.ffn24_strerror.argtypes = [ci]
         L.ffn24_strerror.restype = ctypes.c_char_p
+        dp = ctypes.POINTER(ctypes.c_double)
+        L.ffn24_kernel_mhz.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_float)]
+        L.ffn24_probe_mfma_rate.argtypes = [ci, ci, dp, dp, dp]
+        L.ffn24_probe_gemm.argtypes = [ci, ci, i64, i64, i64, ci, dp, dp]
+        L.ffn24_probe_copy.argtypes = [i64, ci, dp]
         L.ffn24_static_scratch_needed.argtypes = [i64, i64, i64]
         L.ffn24_fwd_static.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp]
         for name in EXPORTS:
@@ -155,6 +160,31 @@ def spmm24(values: torch.Tensor, meta: torch.Tensor, Bt: torch.Tensor) -> torch.
     C = torch.empty((M, N), dtype=torch.bfloat16, device=values.device)
     _check(lib().spmm24(_ptr(values), _ptr(meta), _ptr(Bt), M, N, K, _ptr(C), _stream()), "spmm24")
     return C
+
+
+MFMA_KINDS = ("dense bf16 32x32x16", "sparse bf16 32x32x32", "dense fp8 32x32x64", "sparse fp8 32x32x64")
+GEMM_PROBE_VARIANTS = {"all": 0, "no_dma": 1, "dma_only": 6, "mfma_only": 5, "all_l2_hits": 8, "dma_only_l2_hits": 14}
+
+
+def probe_mfma_rate(kind: int, iters: int = 20000) -> dict:
+    """Register-resident matrix-op loop (see ffn24_probe_mfma_rate in the header)."""
+    c, m, t = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    _check(lib().ffn24_probe_mfma_rate(kind, iters, ctypes.byref(c), ctypes.byref(m), ctypes.byref(t)), "ffn24_probe_mfma_rate")
+    return {"cycles_per_op": c.value, "mhz": m.value, "tflops_dense_equivalent": t.value}
+
+
+def probe_gemm(sparse: bool, variant: int, M: int, N: int, K: int, reps: int = 20) -> dict:
+    """The GEMM core with ingredients of its main loop taken out (see ffn24_probe_gemm in the header)."""
+    ms, m = ctypes.c_double(), ctypes.c_double()
+    _check(lib().ffn24_probe_gemm(int(sparse), variant, M, N, K, reps, ctypes.byref(ms), ctypes.byref(m)), "ffn24_probe_gemm")
+    return {"ms": ms.value, "mhz": m.value}
+
+
+def probe_copy(nbytes: int, reps: int = 20) -> float:
+    """Median milliseconds of a plain device copy kernel of nbytes bytes (see ffn24_probe_copy in the header)."""
+    ms = ctypes.c_double()
+    _check(lib().ffn24_probe_copy(nbytes, reps, ctypes.byref(ms)), "ffn24_probe_copy")
+    return ms.value
 
 
 STATIC_SCRATCH_BYTES = 64 << 20
@@ -309,6 +339,15 @@ class Context:
 
     def set_profiling(self, on: bool):
         _check(lib().ffn24_set_profiling(self._h, int(on)), "ffn24_set_profiling")
+
+    def kernel_mhz(self, kernel: int) -> float | None:
+        """Shader clock (MHz) a GEMM kernel of the last profiled call ran at; None for kernels that take no sample."""
+        mhz = ctypes.c_float()
+        rc = lib().ffn24_kernel_mhz(self._h, kernel, ctypes.byref(mhz))
+        if rc == -5:
+            return None
+        _check(rc, "ffn24_kernel_mhz")
+        return float(mhz.value)
 
     def kernel_ms(self, kernel: int) -> float:
         ms = ctypes.c_float()
