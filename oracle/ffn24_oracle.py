@@ -530,6 +530,50 @@ def ffn24_fwd_fp8(X, W1, b1, W2, sx, sw1, sh, sw2):
     return ffn24_fwd_fp8_codes(X8, W1_8, b1, W2_8, sx, sw1, sh, sw2)
 
 
+def ffn24_bwd_fp8_codes(fwd, X8, W1_8, W2_8, dY8, sx, sw1, sh, sw2, sdy, sdz, wgrad_mask="featurewise", quantise_dz=True, dAct=None):
+    """Backward of ffn24_fwd_fp8_codes with every GEMM operand in e4m3 (abstract: FP8 "in both the forwards and backwards
+    pass"; Sec. 2, the paragraph on the fused backward pointwise kernel: it includes the FP8 scaling).  Per-tensor scales.
+      dY8 [T,D] codes with scale sdy;  fwd = the result of ffn24_fwd_fp8_codes on the same X8, W1_8, W2_8 and scales.
+      dH  = sdy sw2 (dY8 . W2_8^T)
+      dZ  = dH * 2 max(0, Z) on the positions the token-wise mask kept (Fig. 4 caption), Z = the forward's own
+      dZ8 = e4m3(dZ / sdz), saturating, stored compressed with the forward's metadata
+      dX  = sdz sw1 (dZ8 . W1_8^T)                                       (token-wise mask only)
+      feature-wise picks on top of the token-wise mask (Sec. 2, last paragraph), ranked on the stored activation's
+      codes H24_8 (the e4m3 words with the sign cleared, as integers; ties -> lower token), one mask for H and dZ
+      dW2 = sh sdy ((H24_8 * M_T)^T . dY8);   dW1 = sx sdz (X8^T . (dZ8 * M_T))
+    Switches for pinning only: wgrad_mask="tokenwise" uses M_tok in the last line; quantise_dz=False keeps dZ / sdz
+    unrounded.  dAct (optional) replaces 2 max(0, Z) for checks that start from a context's saved tensors."""
+    Xv = E4M3_VALUES[np.ascontiguousarray(X8, dtype=np.uint8)]
+    W1v = E4M3_VALUES[np.ascontiguousarray(W1_8, dtype=np.uint8)]
+    W2v = E4M3_VALUES[np.ascontiguousarray(W2_8, dtype=np.uint8)]
+    dYv = E4M3_VALUES[np.ascontiguousarray(dY8, dtype=np.uint8)]
+    meta = np.asarray(fwd["meta"], dtype=np.uint8)
+    Mtok = mask_from_meta(meta)
+    dH = (dYv @ W2v.T) * (float(sdy) * float(sw2))
+    dA = relu2_derivative(fwd["Z"]) if dAct is None else np.asarray(dAct, dtype=np.float64)
+    dZ = np.where(Mtok, dH * dA, 0.0)
+    if quantise_dz:
+        dZ8_bits = f32_to_e4m3_bits((dZ / float(sdz)).astype(np.float32))
+        dZ8v = E4M3_VALUES[dZ8_bits]
+    else:
+        dZ8_bits = None
+        dZ8v = dZ / float(sdz)
+    dX = (dZ8v @ W1v.T) * (float(sdz) * float(sw1))
+    H24_bits = decompress24(np.asarray(fwd["Hc8_bits"], dtype=np.uint8), meta)
+    Hc8_t, meta_t = sparsify24(np.ascontiguousarray(H24_bits.T))
+    M_T = mask_from_meta(meta_t).T
+    Mw = M_T if wgrad_mask == "featurewise" else Mtok
+    H24v = E4M3_VALUES[H24_bits]
+    dW2 = (np.where(Mw, H24v, 0.0).T @ dYv) * (float(sh) * float(sdy))
+    dW1 = (Xv.T @ np.where(Mw, dZ8v, 0.0)) * (float(sx) * float(sdz))
+    out = {"dH": dH, "dZ": dZ, "dX": dX, "dW1": dW1, "dW2": dW2, "Hc8_t_bits": Hc8_t, "meta_t": meta_t, "M_T": M_T, "Mtok": Mtok}
+    if quantise_dz:
+        out["dZ8_bits"] = dZ8_bits
+        out["dZc8_bits"] = compress_with_meta(dZ8_bits, meta)
+        out["dZc8_t_bits"] = compress_with_meta(np.ascontiguousarray(dZ8_bits.T), meta_t)
+    return out
+
+
 def ffn24_fwd_fp8_rowwise_codes(X8, sx, W1_8, sw1, b1, W2_8, sw2):
     """fp8 forward with row-wise scaling (the paper's precision recipe, Sec. 2: "FP8 rowwise scaling"): the
     activation operand of each GEMM carries one scale per token row, the weight operand one per output channel.

@@ -501,6 +501,98 @@ def test_fp8_forward_quantisation_steps():
     np.testing.assert_allclose(out["Y"][0, :4], [0.0, 64.0, 112.0, 0.0])
 
 
+def _fp8_bwd_case(T=24, D=16, F=32, seed=12, sparsity=0.5):
+    inp = _small_inputs(T=T, D=D, F=F, seed=seed, sparsity=sparsity)
+    sc = {k: float(np.abs(inp[n]).max() / 448.0) for k, n in (("sx", "X"), ("sw1", "W1"), ("sw2", "W2"), ("sdy", "dY"))}
+    q = lambda x, s: torch.from_numpy((x / np.float32(s)).astype(np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    X8, W1_8, W2_8, dY8 = q(inp["X"], sc["sx"]), q(inp["W1"], sc["sw1"]), q(inp["W2"], sc["sw2"]), q(inp["dY"], sc["sdy"])
+    sh = 8.0 / 448.0
+    f = O.ffn24_fwd_fp8_codes(X8, W1_8, inp["b1"], W2_8, sc["sx"], sc["sw1"], sh, sc["sw2"])
+    return inp, sc, sh, (X8, W1_8, W2_8, dY8), f
+
+
+def _dec8(b):
+    return torch.from_numpy(np.ascontiguousarray(b)).view(torch.float8_e4m3fn).to(torch.float64)
+
+
+def test_fp8_backward_is_the_masked_straight_through_gradient():
+    """With dZ left unrounded and the token-wise mask in the weight gradients, the fp8 backward is the textbook gradient
+    at the dequantised operands: dX and dW1 of L = <((max(0, Z)^2) * M) W2, dY> with M constant (the quantiser of the
+    stored activation is passed straight through), dW2 of L = <H24_8 W2, dY> with the stored activation constant.
+    torch autograd in float64, torch's own e4m3 decode."""
+    inp, sc, sh, (X8, W1_8, W2_8, dY8), f = _fp8_bwd_case()
+    sdz = 0.37
+    g = O.ffn24_bwd_fp8_codes(f, X8, W1_8, W2_8, dY8, sc["sx"], sc["sw1"], sh, sc["sw2"], sc["sdy"], sdz, wgrad_mask="tokenwise", quantise_dz=False)
+    X = (_dec8(X8) * sc["sx"]).requires_grad_(True); W1 = (_dec8(W1_8) * sc["sw1"]).requires_grad_(True)
+    W2 = _dec8(W2_8) * sc["sw2"]; dY = _dec8(dY8) * sc["sdy"]
+    M = torch.from_numpy(O.mask_from_meta(f["meta"]).astype(np.float64))
+    Y = ((torch.clamp(X @ W1 + torch.from_numpy(inp["b1"].astype(np.float64)), min=0) ** 2) * M) @ W2
+    Y.backward(dY)
+    assert np.allclose(g["dX"], X.grad.numpy(), rtol=1e-9, atol=1e-12)
+    assert np.allclose(g["dW1"], W1.grad.numpy(), rtol=1e-9, atol=1e-12)
+    H24 = torch.from_numpy(O.decompress24(O.E4M3_VALUES[f["Hc8_bits"]], f["meta"])) * sh
+    W2g = W2.clone().requires_grad_(True)
+    (H24 @ W2g).backward(dY)
+    assert np.allclose(g["dW2"], W2g.grad.numpy(), rtol=1e-9, atol=1e-12)
+    assert np.count_nonzero(g["dX"]) > 100 and np.count_nonzero(g["dW2"]) > 50
+
+
+def test_fp8_backward_quantises_dz_once_with_saturation_and_keeps_the_forward_metadata():
+    inp, sc, sh, (X8, W1_8, W2_8, dY8), f = _fp8_bwd_case()
+    exact = O.ffn24_bwd_fp8_codes(f, X8, W1_8, W2_8, dY8, sc["sx"], sc["sw1"], sh, sc["sw2"], sc["sdy"], 1.0, quantise_dz=False)
+    amax = float(np.abs(exact["dZ"]).max())
+    for sdz in (amax / 448.0, amax / 2000.0):                    # the second one saturates the largest entries
+        g = O.ffn24_bwd_fp8_codes(f, X8, W1_8, W2_8, dY8, sc["sx"], sc["sw1"], sh, sc["sw2"], sc["sdy"], sdz)
+        want = torch.from_numpy(np.clip(exact["dZ"] / sdz, -448, 448).astype(np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+        assert np.array_equal(g["dZ8_bits"], want)                # torch's cast (which has no saturation of its own: clipped first)
+        assert np.all(g["dZ8_bits"][~g["Mtok"]] & 0x7F == 0)      # nothing off the token-wise mask
+        assert np.array_equal(g["dZc8_bits"], O.compress_with_meta(g["dZ8_bits"], f["meta"]))
+    assert (np.abs(exact["dZ"]) / (amax / 2000.0) > 448).any()
+    # dX is the plain product of the decoded codes
+    g = O.ffn24_bwd_fp8_codes(f, X8, W1_8, W2_8, dY8, sc["sx"], sc["sw1"], sh, sc["sw2"], sc["sdy"], amax / 448.0)
+    dX = (_dec8(g["dZ8_bits"]) @ _dec8(W1_8).T).numpy() * (amax / 448.0) * sc["sw1"]
+    assert np.allclose(g["dX"], dX, rtol=1e-12, atol=1e-15)
+    # and it stays within the format's rounding of the unrounded backward: e4m3 keeps 4 significant bits
+    assert O.max_rel_err(g["dX"], exact["dX"]) <= 2.0 ** -4 and O.fro_rel_err(g["dX"], exact["dX"]) <= 2.0 ** -4
+
+
+def test_fp8_backward_featurewise_mask_on_the_stored_codes():
+    inp, sc, sh, (X8, W1_8, W2_8, dY8), f = _fp8_bwd_case(T=64, D=16, F=64, sparsity=0.4)
+    sdz = 0.01
+    g = O.ffn24_bwd_fp8_codes(f, X8, W1_8, W2_8, dY8, sc["sx"], sc["sw1"], sh, sc["sw2"], sc["sdy"], sdz)
+    e = O.ffn24_bwd_fp8_codes(f, X8, W1_8, W2_8, dY8, sc["sx"], sc["sw1"], sh, sc["sw2"], sc["sdy"], sdz, wgrad_mask="tokenwise")
+    H24 = O.decompress24(f["Hc8_bits"], f["meta"])                # codes
+    M_T = g["M_T"]
+    assert np.all(~(M_T & (H24 != 0)) | g["Mtok"])                # nothing the forward dropped reappears
+    kept = np.where(M_T, H24, 0).T.reshape(64, 16, 4)
+    assert np.all((kept != 0).sum(-1) <= 2)                       # 2:4 along tokens
+    # brute force of the picks on the codes: per feature and 4 tokens, the two largest codes, ties to the lower token
+    for fcol in range(0, 64, 7):
+        for r in range(16):
+            grp = H24[4 * r:4 * r + 4, fcol].astype(int) & 0x7F
+            order = sorted(range(4), key=lambda i: (-grp[i], i))[:2]
+            assert sorted(np.nonzero(M_T[4 * r:4 * r + 4, fcol])[0].tolist()) == sorted(order)
+    assert np.count_nonzero(np.where(M_T, H24, 0)) < np.count_nonzero(H24)      # the second prune drops something here
+    assert np.array_equal(e["dX"], g["dX"]) and not np.array_equal(e["dW2"], g["dW2"])
+    # the weight gradients are the products of the doubly masked decoded operands, by torch
+    Hm = torch.from_numpy(np.where(M_T, H24, 0).astype(np.uint8)).view(torch.float8_e4m3fn).to(torch.float64)
+    Zm = torch.from_numpy(np.where(M_T, g["dZ8_bits"], 0).astype(np.uint8)).view(torch.float8_e4m3fn).to(torch.float64)
+    assert np.allclose(g["dW2"], (Hm.T @ _dec8(dY8)).numpy() * sh * sc["sdy"], rtol=1e-12, atol=1e-15)
+    assert np.allclose(g["dW1"], (_dec8(X8).T @ Zm).numpy() * sc["sx"] * sdz, rtol=1e-12, atol=1e-15)
+    assert np.array_equal(g["dZc8_t_bits"], O.compress_with_meta(np.ascontiguousarray(g["dZ8_bits"].T), g["meta_t"]))
+
+
+def test_fp8_backward_scales_by_powers_of_two_exactly():
+    """Doubling sdy with the same dY codes doubles the incoming gradient; if sdz doubles too, dZ / sdz and with it every
+    code is unchanged, and all three gradients double exactly."""
+    inp, sc, sh, (X8, W1_8, W2_8, dY8), f = _fp8_bwd_case()
+    a = O.ffn24_bwd_fp8_codes(f, X8, W1_8, W2_8, dY8, sc["sx"], sc["sw1"], sh, sc["sw2"], sc["sdy"], 0.02)
+    b = O.ffn24_bwd_fp8_codes(f, X8, W1_8, W2_8, dY8, sc["sx"], sc["sw1"], sh, sc["sw2"], 2 * sc["sdy"], 0.04)
+    assert np.array_equal(a["dZ8_bits"], b["dZ8_bits"])
+    for k in ("dX", "dW1", "dW2"):
+        assert np.array_equal(2 * a[k], b[k])
+
+
 def test_fp8_workload_codes_match_the_oracle_quantiser():
     """The fp8 workload generator quantises with torch's CPU cast; on its in-range inputs that is the oracle's
     saturating round-to-nearest-even conversion, code for code."""
