@@ -15,8 +15,8 @@
  *     device current return FFN24_ERR_STATE.  A context is not thread-safe: one thread at a time per context.
  *   - Return value: FFN24_OK (0) or a negative FFN24_ERR_* code; ffn24_strerror() names it.  Bad arguments are
  *     rejected before anything is launched; nothing aborts or throws across this boundary.
- *   - Element type: bf16 (FFN24_BF16) with fp32 accumulation; or, forward only, fp8 (FFN24_FP8_E4M3, the OCP e4m3
- *     format, per-tensor fp32 scales, fp32 accumulation, bf16 result; see ffn24_set_scales).
+ *   - Element type: bf16 (FFN24_BF16) with fp32 accumulation; or fp8 (FFN24_FP8_E4M3, the OCP e4m3 format, per-tensor
+ *     fp32 scales, fp32 accumulation, bf16 results; see ffn24_set_scales and ffn24_set_bwd_scales).
  *   - Outputs are overwritten, never accumulated into.
  *
  * Compressed 2:4 form used everywhere (the paper leaves the encoding open; this one equals the index operand of
@@ -85,8 +85,21 @@ FFN24_API int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F,
  *   Hc8 = e4m3(kept / sh), saturating at +-448, round to nearest even;  Y = bf16(sh sw2 (Hc8 . W2_8))
  * (paper Sec. 2: activation, then sparsification, then FP8 quantisation; per-tensor scales instead of the paper's
  * row-wise ones).  Saved tensors 0 and 1 are then bytes: Hc8 [T][F/2], meta [T][F/8]; tensor 7 is H8 [T][F].
- * An fp8 context supports ffn24_fwd and ffn_fwd only (no FFN24_TRAINING: FFN24_ERR_DTYPE). */
+ * ffn_fwd is the dense fp8 baseline of the forward.  With FFN24_TRAINING (and none of FFN24_ROWWISE, FFN24_DENSE,
+ * FFN24_SPLIT: FFN24_ERR_DTYPE otherwise) the context also supports ffn24_bwd in fp8, see ffn24_set_bwd_scales. */
 FFN24_API int ffn24_set_scales(ffn24_ctx* ctx, float sx, float sw1, float sh, float sw2);
+
+/* fp8 backward of an FFN24_FP8_E4M3 | FFN24_TRAINING context (paper abstract: FP8 in both the forwards and the
+ * backwards pass; Sec. 2, the paragraph on the fused backward pointwise kernel: it includes the FP8 scaling).  Both
+ * scales > 0 (1 after creation).  ffn24_bwd then takes dY8 = e4m3(dY / sdy) as bytes [T][D] and computes, with every
+ * GEMM operand in e4m3 and fp32 accumulation,
+ *   dH = sdy sw2 (dY8 . W2_8^T);  dZ = dH * 2 max(0, Z) on the kept positions, the derivative taken as 2 sqrt(h) of the
+ *   bf16 kept activation the forward saved;  dZ8 = e4m3(dZ / sdz), saturating, compressed with the forward's metadata;
+ *   dX = bf16(sdz sw1 (dZ8 . W1_8^T));  feature-wise 2:4 on top, ranked on the stored e4m3 codes of the activation;
+ *   dW2 = bf16(sh sdy ((H24_8 * M_T)^T . dY8));  dW1 = bf16(sx sdz (X8^T . (dZ8 * M_T))).
+ * dX [T][D], dW1 [D][F], dW2 [F][D] are bf16.  Saved tensors 2, 3, 5 are then e4m3 bytes; tensor 12 is the bf16 kept
+ * activation [T][F/2]. */
+FFN24_API int ffn24_set_bwd_scales(ffn24_ctx* ctx, float sdy, float sdz);
 
 /* Row-wise scaling of an fp8 context created with FFN24_ROWWISE (paper Sec. 2: "FP8 rowwise scaling"): the activation
  * operand of each GEMM has one scale per token, the weight operand one per output channel.  The caller hands in
@@ -221,6 +234,7 @@ FFN24_API int ffn24_policy_use_sparse(ffn24_ctx* ctx, double min_sparsity, int* 
  *   6 pre-prune H dump [T][F] (FFN24_DEBUG_DUMP_H)   7 dense H [T][F]   8 dense dZ [T][F]
  *   9 per-feature non-zero counts [F] uint32, 10 feature of each split-operand row [F] int32 (FFN24_SPLIT)
  *   11 per-token activation scale sh [T] fp32 (FFN24_ROWWISE)
+ *   12 kept activation before quantisation [T][F/2] bf16 (fp8 contexts with FFN24_TRAINING or FFN24_ROWWISE)
  * ffn24_saved_bytes gives the size of tensor `which`; ffn24_copy_saved enqueues a copy of it into dst (device memory
  * of exactly that size, 16-byte aligned) in the row-major compressed form described at the top -- inside the context
  * the compressed tensors are kept in a tiled order that the sparse GEMM streams faster.  Returns FFN24_ERR_STATE if

@@ -41,6 +41,7 @@ struct ffn24_ctx {
   int device;
   int f8;                      // element type FFN24_FP8_E4M3 (forward only)
   float sx, sw1, sh, sw2;      // per-tensor scales of the fp8 path
+  float sdy, sdz;              // fp8 backward: scale of the incoming gradient dY8 and of the stored dZ8
   int* perm; int perm_on;      // token permutation (FFN24_PERMUTE): device copy, and whether one is set
   // row-wise-scaled fp8 forward (FFN24_ROWWISE): caller's scale vectors, and the library's intermediate tensors
   const float *rsx, *rsw1, *rsw2;
@@ -124,8 +125,8 @@ int weight_pass(ffn24_ctx* c, const void* W1, const void* W2, hipStream_t s) {
   Timed t(c, K_TR_W, s);
   int rc1;
   if (c->f8) {
-    rc1 = launch_transpose8(W1, D, F, c->W1t, 1, s);
-    if (!rc1) rc1 = launch_transpose8(W2, F, D, c->W2t, 2, s);
+    rc1 = launch_transpose8(W1, D, F, c->W1t, 1, c->W1p, 1, s);
+    if (!rc1) rc1 = launch_transpose8(W2, F, D, c->W2t, 2, c->W2p, 0, s);
   } else {
     rc1 = launch_transpose(W1, D, F, c->W1t, 1, c->W1p, 1, nullptr, s);
     if (!rc1) rc1 = launch_transpose(W2, F, D, c->W2t, 2, c->W2p, 0, nullptr, s);
@@ -172,7 +173,7 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
   if (!out) return FFN24_ERR_NULL;
   if (dtype != FFN24_BF16 && dtype != FFN24_FP8_E4M3) return FFN24_ERR_DTYPE;
   const bool f8 = dtype == FFN24_FP8_E4M3;
-  if (f8 && (flags & FFN24_TRAINING)) return FFN24_ERR_DTYPE;   // the fp8 path is forward only
+  if (f8 && (flags & FFN24_TRAINING) && (flags & (FFN24_ROWWISE | FFN24_DENSE | FFN24_SPLIT))) return FFN24_ERR_DTYPE;   // fp8 training: per-tensor 2:4 path only
   if ((flags & FFN24_SPLIT) && !(flags & FFN24_TRAINING)) return FFN24_ERR_STATE;
   if ((flags & FFN24_ROWWISE) && !f8) return FFN24_ERR_DTYPE;
   if ((flags & FFN24_PERMUTE) && f8) return FFN24_ERR_DTYPE;
@@ -184,16 +185,19 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
   ffn24_ctx* c = new (std::nothrow) ffn24_ctx();
   if (!c) return FFN24_ERR_HIP;
   c->T = T; c->D = D; c->F = F; c->flags = flags; c->f8 = f8;
-  c->sx = c->sw1 = c->sh = c->sw2 = 1.f;
+  c->sx = c->sw1 = c->sh = c->sw2 = c->sdy = c->sdz = 1.f;
   if (hipGetDevice(&c->device) != hipSuccess) { delete c; return FFN24_ERR_HIP; }
   const size_t es = f8 ? 1 : 2;   // bytes per stored element
   size_t tf = (size_t)T * (size_t)F, df = (size_t)D * (size_t)F, td = (size_t)T * (size_t)D;
   bool ok = hipMalloc(&c->Hc, tf * es / 2) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->meta), tf / 8) == hipSuccess &&
             hipMalloc(&c->W1t, es * df) == hipSuccess && hipMalloc(&c->W2t, es * df) == hipSuccess;
   if (ok && (flags & FFN24_TRAINING))
-    ok = hipMalloc(&c->dZc, tf) == hipSuccess && hipMalloc(&c->Hc_t, tf) == hipSuccess &&
-         hipMalloc(reinterpret_cast<void**>(&c->meta_t), tf / 8) == hipSuccess && hipMalloc(&c->dZc_t, tf) == hipSuccess &&
-         hipMalloc(&c->Xt, 2 * td) == hipSuccess && hipMalloc(&c->dYt, 2 * td) == hipSuccess && hipMalloc(&c->W2p, 2 * df) == hipSuccess && hipMalloc(&c->W1p, 2 * df) == hipSuccess;
+    ok = hipMalloc(&c->dZc, tf * es / 2) == hipSuccess && hipMalloc(&c->Hc_t, tf * es / 2) == hipSuccess &&
+         hipMalloc(reinterpret_cast<void**>(&c->meta_t), tf / 8) == hipSuccess && hipMalloc(&c->dZc_t, tf * es / 2) == hipSuccess &&
+         hipMalloc(&c->Xt, es * td) == hipSuccess && hipMalloc(&c->dYt, es * td) == hipSuccess && hipMalloc(&c->W2p, es * df) == hipSuccess && hipMalloc(&c->W1p, es * df) == hipSuccess;
+  // an fp8 training context also keeps the kept activations before quantisation (bf16) for the backward's derivative
+  if (ok && f8 && (flags & FFN24_TRAINING))
+    ok = hipMalloc(&c->Hc16, tf) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->meta16), tf / 8) == hipSuccess;
   if (ok && (flags & FFN24_TELEMETRY)) {
     ok = hipMalloc(reinterpret_cast<void**>(&c->tele), 8 * TELE_WORDS) == hipSuccess &&
          hipMalloc(reinterpret_cast<void**>(&c->tele_sum), 8 * 5) == hipSuccess &&
@@ -235,6 +239,15 @@ int ffn24_set_scales(ffn24_ctx* c, float sx, float sw1, float sh, float sw2) {
   if (!c->f8) return FFN24_ERR_DTYPE;
   if (!(sx > 0.f) || !(sw1 > 0.f) || !(sh > 0.f) || !(sw2 > 0.f)) return FFN24_ERR_SHAPE;
   c->sx = sx; c->sw1 = sw1; c->sh = sh; c->sw2 = sw2;
+  return FFN24_OK;
+}
+
+int ffn24_set_bwd_scales(ffn24_ctx* c, float sdy, float sdz) {
+  if (!c) return FFN24_ERR_NULL;
+  if (!c->f8) return FFN24_ERR_DTYPE;
+  if (!(c->flags & FFN24_TRAINING)) return FFN24_ERR_STATE;
+  if (!(sdy > 0.f) || !(sdz > 0.f)) return FFN24_ERR_SHAPE;
+  c->sdy = sdy; c->sdz = sdz;
   return FFN24_OK;
 }
 
@@ -385,6 +398,7 @@ int ffn24_saved_bytes(ffn24_ctx* c, int which, int64_t* nbytes) {
     case 7: case 8: *nbytes = es * tf; break;
     case 9: case 10: *nbytes = 4 * c->F; break;
     case 11: *nbytes = 4 * c->T; break;
+    case 12: *nbytes = tf; break;
     default: return FFN24_ERR_SHAPE;
   }
   return FFN24_OK;
@@ -415,9 +429,12 @@ int ffn24_copy_saved(ffn24_ctx* c, int which, void* dst, int64_t dst_bytes, void
     case 8: src = c->dZd; break;
     case 9: src = c->nnz; break;
     case 10: src = c->feat_of_row; break;
-    default: src = c->rsh; break;
+    case 11: src = c->rsh; break;
+    default: src = c->Hc16; break;
   }
   if (!src) return FFN24_ERR_STATE;
+  if (which == 12)   // bf16 kept values of an fp8 context: bf16 panel form (64-byte pieces of 64 k)
+    return launch_unpanel(src, T, F / 64, 64, dst, s) ? FFN24_ERR_HIP : FFN24_OK;
   if (which >= 9) return hipMemcpyAsync(dst, src, (size_t)need, hipMemcpyDeviceToDevice, s) == hipSuccess ? FFN24_OK : FFN24_ERR_HIP;
   if (which >= 7)   // the dense baseline's H and dZ: dense panel form, 64-byte pieces of 32 (fp8: 64) k
     return launch_unpanel(src, T, c->f8 ? F / 64 : F / 32, 64, dst, s) ? FFN24_ERR_HIP : FFN24_OK;
@@ -481,10 +498,13 @@ int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, cons
     return FFN24_OK;
   }
   if (c->f8) {
+    const bool train = (c->flags & FFN24_TRAINING) != 0;
     { Timed t(c, K_UP, s);
-      if (t.done(launch_up_prune24_f8(c->W1t, X, b1, T, D, F, c->sx * c->sw1, c->sh, c->Hc, c->meta, c->Hdbg, s))) return FFN24_ERR_HIP; }
+      if (t.done(launch_up_prune24_f8(c->W1t, X, b1, T, D, F, c->sx * c->sw1, c->sh, c->Hc, c->meta, c->Hdbg, train ? c->Hc16 : nullptr,
+                                      train ? c->meta16 : nullptr, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_DOWN, s);
       if (t.done(launch_sp_rowmajor_f8(c->Hc, c->meta, 1, c->W2t, 1, T, D, F, c->sh * c->sw2, Y, s))) return FFN24_ERR_HIP; }
+    if (train) { c->X = X; c->have_fwd24 = 1; }
     return FFN24_OK;
   }
   uint32_t* nnz = (c->flags & FFN24_SPLIT) && c->n_dense > 0 ? c->nnz : nullptr;
@@ -540,6 +560,23 @@ int ffn24_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void
   if (rc) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
+  if (c->f8) {
+    // fp8 backward (per-tensor scales): every GEMM operand is e4m3, the gradients come out in bf16
+    { Timed t(c, K_DH, s);
+      if (t.done(launch_dh_gather_f8(c->W2p, dY, c->Hc16, c->meta16, T, D, F, c->sdy * c->sw2, c->sdz, c->dZc, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_DX, s);
+      if (t.done(launch_sp_rowmajor_f8(c->dZc, c->meta, 1, c->W1p, 1, T, D, F, c->sdz * c->sw1, dX, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_FW, s);
+      if (t.done(launch_featurewise24_f8(c->Hc, c->meta, c->dZc, T, F, c->Hc_t, c->meta_t, c->dZc_t, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_TR_ACT, s);
+      int rc1 = launch_transpose8(dY, T, D, c->dYt, 2, nullptr, 0, s);
+      if (t.done(rc1 ? rc1 : launch_transpose8(c->X, T, D, c->Xt, 2, nullptr, 0, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_DW2, s);
+      if (t.done(launch_sp_rowmajor_f8(c->Hc_t, c->meta_t, 1, c->dYt, 1, F, D, T, c->sh * c->sdy, dW2, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_DW1, s);
+      if (t.done(launch_sp_colmajor_f8(c->dZc_t, c->meta_t, 1, c->Xt, 1, F, D, T, c->sdz * c->sx, dW1, s))) return FFN24_ERR_HIP; }
+    return FFN24_OK;
+  }
   const int* perm = c->perm_on ? c->perm : nullptr;   // position p inside the FFN holds token perm[p]
   // the forward's two counts stay; the feature-wise one belongs to this backward
   if (c->tele && launch_zero32(reinterpret_cast<uint32_t*>(c->tele + tele_index(TELE_KEPT_FEAT, 0)), 2 * TELE_SLOTS * TELE_STRIDE, s)) return FFN24_ERR_HIP;

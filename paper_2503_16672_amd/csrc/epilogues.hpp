@@ -328,8 +328,11 @@ __device__ __forceinline__ uint32_t cvt_e4m3x2(float lo, float hi, uint32_t old,
 // the bf16 words exactly as in EpiPrune24; the kept values are then quantised, e4m3(h / sh).
 //   Hc8, meta: panel form of the fp8 operand: piece = 64 stored bytes + 16 metadata bytes for 128 features of a token;
 //   a lane's 64 features are one half of a piece.
+//   Hc16, meta16 (optional, a training context): the kept values before quantisation, bf16, with their metadata, in the
+//   bf16 panel form -- what the backward takes the activation's derivative from (the e4m3 code of h keeps 4
+//   significant bits, too few for 2 sqrt(h)).
 struct EpiPrune24F8 {
-  struct Args { uint8_t* Hc8; uint8_t* meta; __bf16* Hdbg; const float* b1; int F; float zscale; float sh; };
+  struct Args { uint8_t* Hc8; uint8_t* meta; __bf16* Hdbg; const float* b1; int F; float zscale; float sh; __bf16* Hc16; uint8_t* meta16; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
     LaneVec64 lb;
     lb.load(e.b1, m_lane, 0.f);
@@ -338,6 +341,7 @@ struct EpiPrune24F8 {
       size_t t = (size_t)(n_lane + ni);
       uint32_t q8[8];
       uint32_t nib[2] = {0u, 0u};
+      size_t piece16 = a24_piece((int)t, m_lane >> 6, e.F >> 6);
 #pragma unroll
       for (int mi = 0; mi < 4; mi++) {
         uint32_t hpk[8];
@@ -353,10 +357,12 @@ struct EpiPrune24F8 {
           *reinterpret_cast<u32x4*>(row) = u32x4{hpk[0], hpk[1], hpk[2], hpk[3]};
           *reinterpret_cast<u32x4*>(row + 8) = u32x4{hpk[4], hpk[5], hpk[6], hpk[7]};
         }
+        uint32_t pairs[4];
 #pragma unroll
         for (int a = 0; a < 4; a++) {
           uint32_t pair;
           uint32_t n4 = pick24_packed(hpk[2 * a], hpk[2 * a + 1], pair);
+          pairs[a] = pair;
           int gi = 4 * mi + a;
           float v0 = bf16_lo_to_f32(pair) / e.sh;
           float v1 = bf16_hi_to_f32(pair) / e.sh;
@@ -364,6 +370,7 @@ struct EpiPrune24F8 {
           q8[gi >> 1] = cvt_e4m3x2(v0, v1, (gi & 1) ? q8[gi >> 1] : 0u, (gi & 1) != 0);
           nib[gi >> 3] |= n4 << (4 * (gi & 7));
         }
+        if (e.Hc16) *reinterpret_cast<u32x4*>(e.Hc16 + piece16 * 32 + 8 * mi) = u32x4{pairs[0], pairs[1], pairs[2], pairs[3]};
       }
       size_t piece = a24_piece((int)t, m_lane >> 7, e.F >> 7);
       int half = (m_lane >> 6) & 1;
@@ -371,6 +378,67 @@ struct EpiPrune24F8 {
       *reinterpret_cast<u32x4*>(hrow) = u32x4{q8[0], q8[1], q8[2], q8[3]};
       *reinterpret_cast<u32x4*>(hrow + 16) = u32x4{q8[4], q8[5], q8[6], q8[7]};
       *reinterpret_cast<u32x2*>(e.meta + piece * 16 + 8 * half) = u32x2{nib[0], nib[1]};
+      if (e.Hc16) *reinterpret_cast<u32x2*>(e.meta16 + piece16 * 8) = u32x2{nib[0], nib[1]};
+    }
+  }
+};
+
+// fp8 backward, pointwise part (the abstract's FP8 backward pass; Sec. 2's fused backward pointwise step with its FP8
+// scaling): acc = (W2_8 . dY8) for a lane's 64 features x 4 tokens; dH = scale * acc (scale = sdy * sw2); on the
+// positions the forward kept dZ = dH * 2 sqrt(h) with h the bf16 kept value the forward saved (Hc16, meta16: bf16 panel
+// form); the result is quantised, e4m3(dZ / sdz) (saturating), and stored compressed with the forward's metadata in
+// the fp8 panel form (the operand of the sparse dX GEMM).
+struct EpiDGatherF8 {
+  struct Args { const __bf16* Hc16; const uint8_t* meta16; uint8_t* dZc8; int F; float scale; float sdz; };
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+#pragma unroll
+    for (int ni = 0; ni < 4; ni++) {
+      size_t t = (size_t)(n_lane + ni);
+      size_t piece16 = a24_piece((int)t, m_lane >> 6, e.F >> 6);
+      const __bf16* hrow = e.Hc16 + piece16 * 32;
+      u32x2 mt = *reinterpret_cast<const u32x2*>(e.meta16 + piece16 * 8);
+      uint32_t q8[8];
+#pragma unroll
+      for (int mi = 0; mi < 4; mi++) {
+        u32x4 h = *reinterpret_cast<const u32x4*>(hrow + 8 * mi);
+#pragma unroll
+        for (int a = 0; a < 4; a++) {
+          int gi = 4 * mi + a;
+          uint32_t n4 = (mt[gi >> 3] >> (4 * (gi & 7))) & 15u;
+          uint32_t i0 = n4 & 3u, i1 = n4 >> 2;
+          float x0 = acc[mi][ni][4 * a], x1 = acc[mi][ni][4 * a + 1], x2 = acc[mi][ni][4 * a + 2], x3 = acc[mi][ni][4 * a + 3];
+          float s0 = i0 == 0 ? x0 : (i0 == 1 ? x1 : x2);
+          float s1 = i1 == 3 ? x3 : (i1 == 2 ? x2 : x1);
+          float g0 = 2.f * __builtin_amdgcn_sqrtf(bf16_lo_to_f32(h[a]));
+          float g1 = 2.f * __builtin_amdgcn_sqrtf(bf16_hi_to_f32(h[a]));
+          float v0 = (s0 * e.scale * g0) / e.sdz, v1 = (s1 * e.scale * g1) / e.sdz;
+          q8[gi >> 1] = cvt_e4m3x2(v0, v1, (gi & 1) ? q8[gi >> 1] : 0u, (gi & 1) != 0);
+        }
+      }
+      size_t piece = a24_piece((int)t, m_lane >> 7, e.F >> 7);
+      uint8_t* zrow = e.dZc8 + piece * 64 + 32 * ((m_lane >> 6) & 1);
+      *reinterpret_cast<u32x4*>(zrow) = u32x4{q8[0], q8[1], q8[2], q8[3]};
+      *reinterpret_cast<u32x4*>(zrow + 16) = u32x4{q8[4], q8[5], q8[6], q8[7]};
+    }
+  }
+};
+
+// out[n][m] = bf16(scale * acc), m contiguous: the transposing store of EpiColMajor with a scale (fp8 dW1).
+struct EpiColMajorScaled {
+  struct Args { __bf16* C; int ldc; float scale; };
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+#pragma unroll
+    for (int ni = 0; ni < 4; ni++) {
+      __bf16* row = e.C + (size_t)(n_lane + ni) * e.ldc + m_lane;
+#pragma unroll
+      for (int mi = 0; mi < 4; mi++)
+#pragma unroll
+        for (int q = 0; q < 2; q++) {
+          u32x4 o;
+#pragma unroll
+          for (int d = 0; d < 4; d++) o[d] = pack_bf16x2(acc[mi][ni][8 * q + 2 * d] * e.scale, acc[mi][ni][8 * q + 2 * d + 1] * e.scale);
+          *reinterpret_cast<u32x4*>(row + 16 * mi + 8 * q) = o;
+        }
     }
   }
 };

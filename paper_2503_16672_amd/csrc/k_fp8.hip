@@ -5,9 +5,9 @@
 namespace ffn24 {
 
 int launch_up_prune24_f8(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, float zscale, float sh,
-                         void* Hc8, uint8_t* meta, void* Hdbg, hipStream_t s) {
+                         void* Hc8, uint8_t* meta, void* Hdbg, void* Hc16, uint8_t* meta16, hipStream_t s) {
   GemmArgs g{W1t8, nullptr, X8, F, T, D, 1};
-  EpiPrune24F8::Args ea{static_cast<uint8_t*>(Hc8), meta, static_cast<__bf16*>(Hdbg), b1, F, zscale, sh};
+  EpiPrune24F8::Args ea{static_cast<uint8_t*>(Hc8), meta, static_cast<__bf16*>(Hdbg), b1, F, zscale, sh, static_cast<__bf16*>(Hc16), meta16};
   return launch_gemm<false, EpiPrune24F8, true>(g, ea, s);
 }
 
@@ -27,6 +27,22 @@ int launch_dense_rowmajor_f8(const void* A8, int a_panel, const void* B8, int b_
   GemmArgs g{A8, nullptr, B8, M, N, K, a_panel, nullptr, b_panel};
   EpiRowMajorScaled::Args ea{static_cast<__bf16*>(C), N, scale};
   return launch_gemm<false, EpiRowMajorScaled, true>(g, ea, s);
+}
+
+// fp8 backward: dH GEMM (A = W2 itself [F][D] in dense panel form, B = dY8 [T][D]) with the pointwise part fused, and the
+// sparse GEMM with the transposing store (dW1)
+int launch_dh_gather_f8(const void* W2p8, const void* dY8, const void* Hc16, const uint8_t* meta16, int T, int D, int F, float scale, float sdz,
+                        void* dZc8, hipStream_t s) {
+  GemmArgs g{W2p8, nullptr, dY8, F, T, D, 1};
+  EpiDGatherF8::Args ea{static_cast<const __bf16*>(Hc16), meta16, static_cast<uint8_t*>(dZc8), F, scale, sdz};
+  return launch_gemm<false, EpiDGatherF8, true>(g, ea, s);
+}
+
+int launch_sp_colmajor_f8(const void* vals8, const uint8_t* meta, int a_panel, const void* B8, int b_panel, int M, int N, int K, float scale, void* Ct,
+                          hipStream_t s) {
+  GemmArgs g{vals8, meta, B8, M, N, K, a_panel, nullptr, b_panel};
+  EpiColMajorScaled::Args ea{static_cast<__bf16*>(Ct), M, scale};
+  return launch_gemm<true, EpiColMajorScaled, true>(g, ea, s);
 }
 
 // row-wise-scaled variants (scales per token for the activation operand, per output channel for the weight)

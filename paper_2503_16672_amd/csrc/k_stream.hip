@@ -395,13 +395,20 @@ int launch_transpose(const void* in, int R, int C, void* out, int out_form, void
 // 64 x 64 tile; a work item reads 16 bytes of a row, scatters them into an LDS tile (pitch 68 bytes), then reads 16
 // bytes of a transposed row and writes them out.  OUT_FORM: 0 row-major, 1 dense panel form (64-byte pieces of 64 k,
 // K = R), 2 the B panel form.
+// in_panel (optional): a copy of the input itself in panel form (K = C, 64-byte pieces), made in the same pass; in the
+// B form if in_panel_b.
 template <int OUT_FORM>
-__global__ void __launch_bounds__(256) transpose8_kernel(const uint8_t* __restrict__ in, int R, int C, uint8_t* __restrict__ out) {
+__global__ void __launch_bounds__(256) transpose8_kernel(const uint8_t* __restrict__ in, int R, int C, uint8_t* __restrict__ out,
+                                                         uint8_t* __restrict__ in_panel, int in_panel_b) {
   __shared__ __attribute__((aligned(16))) uint8_t sT[64 * 68];
   int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
   int tid = threadIdx.x;
   int ch = tid & 3, rr = tid >> 2;
   u32x4 v = *reinterpret_cast<const u32x4*>(in + (size_t)(r0 + rr) * C + c0 + 16 * ch);
+  if (in_panel) {
+    int prow = in_panel_b ? b_panel_pos(r0 + rr) : r0 + rr;
+    *reinterpret_cast<u32x4*>(in_panel + a24_piece(prow, c0 >> 6, C >> 6) * 64 + 16 * ch) = v;
+  }
 #pragma unroll
   for (int d = 0; d < 4; d++)
 #pragma unroll
@@ -416,10 +423,96 @@ __global__ void __launch_bounds__(256) transpose8_kernel(const uint8_t* __restri
   else *reinterpret_cast<u32x4*>(out + (size_t)(c0 + c) * R + r) = o;
 }
 
-int launch_transpose8(const void* in, int R, int C, void* out, int out_form, hipStream_t s) {
+int launch_transpose8(const void* in, int R, int C, void* out, int out_form, void* in_panel, int in_panel_b, hipStream_t s) {
   dim3 grid(C / 64, R / 64);
   auto kern = out_form == 2 ? transpose8_kernel<2> : (out_form == 1 ? transpose8_kernel<1> : transpose8_kernel<0>);
-  hipLaunchKernelGGL(kern, grid, dim3(256), 0, s, static_cast<const uint8_t*>(in), R, C, static_cast<uint8_t*>(out));
+  hipLaunchKernelGGL(kern, grid, dim3(256), 0, s, static_cast<const uint8_t*>(in), R, C, static_cast<uint8_t*>(out),
+                     static_cast<uint8_t*>(in_panel), in_panel_b);
+  return (int)hipGetLastError();
+}
+
+// Feature-wise 2:4 on top of the token-wise mask for the fp8 operands (Sec. 2, last paragraph; the FP8 side of the fused
+// backward pointwise step).  Everything is in the fp8 panel form: input pieces = 128 hidden features of one token (64
+// stored e4m3 bytes + 16 metadata bytes), output pieces = 128 tokens of one feature.  The picks are made on the stored
+// codes of the activation (sign bit cleared, as integers; ties -> lower token); dZ is gathered at the same positions.
+// One workgroup handles 128 tokens x 128 features: it reads 128 consecutive input pieces of each tensor (8 KiB + 2 KiB
+// runs), spreads them out in LDS, and every work item then takes one feature and 16 consecutive tokens (four groups):
+// 8 stored bytes and 2 metadata bytes of an output piece.
+constexpr int FW8_TOK = 128, FW8_FEAT = 128, FW8_LD = FW8_FEAT + 4;
+
+__device__ __forceinline__ uint32_t pick24_codes(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3, uint32_t& i0, uint32_t& i1) {
+  // keys ((magnitude << 2) | (3 - i)): distinct, ordered by (magnitude, then lower index first)
+  uint32_t k0 = ((w0 & 0x7Fu) << 2) | 3u, k1 = ((w1 & 0x7Fu) << 2) | 2u, k2 = ((w2 & 0x7Fu) << 2) | 1u, k3 = (w3 & 0x7Fu) << 2;
+  uint32_t kf, ks;
+  uint32_t nib = pick24_keys(k0, k1, k2, k3, kf, ks);
+  i0 = nib & 3u; i1 = nib >> 2;
+  return nib;
+}
+
+__global__ void __launch_bounds__(256) featurewise24_f8_kernel(const uint8_t* __restrict__ Hc8, const uint8_t* __restrict__ meta,
+                                                               const uint8_t* __restrict__ dZc8, int T, int F,
+                                                               uint8_t* __restrict__ Hc8_t, uint8_t* __restrict__ meta_t,
+                                                               uint8_t* __restrict__ dZc8_t) {
+  __shared__ __attribute__((aligned(16))) uint8_t sH[FW8_TOK * FW8_LD];
+  __shared__ __attribute__((aligned(16))) uint8_t sZ[FW8_TOK * FW8_LD];
+  const int f0 = blockIdx.x * FW8_FEAT, t0 = blockIdx.y * FW8_TOK;
+  const int tid = threadIdx.x;
+  const bool has_z = dZc8 != nullptr;
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+    int item = tid + 256 * i;
+    int tok = item >> 2, ch = item & 3;              // 16 stored bytes = 8 groups = 32 features
+    size_t piece = a24_piece(t0 + tok, f0 >> 7, F >> 7);
+    u32x4 hv = *reinterpret_cast<const u32x4*>(Hc8 + piece * 64 + 16 * ch);
+    u32x4 zv = {0u, 0u, 0u, 0u};
+    if (has_z) zv = *reinterpret_cast<const u32x4*>(dZc8 + piece * 64 + 16 * ch);
+    uint32_t m32 = *reinterpret_cast<const uint32_t*>(meta + piece * 16 + 4 * ch);
+#pragma unroll
+    for (int g = 0; g < 8; g++) {
+      uint32_t nib = (m32 >> (4 * g)) & 15u;
+      uint32_t i0 = nib & 3u, i1 = nib >> 2;
+      uint32_t hb = (hv[g >> 1] >> (16 * (g & 1))) & 0xFFFFu, zb = (zv[g >> 1] >> (16 * (g & 1))) & 0xFFFFu;
+      // the group's four bytes as one word: kept byte 0 at position i0, kept byte 1 at position i1
+      uint32_t hw = ((hb & 0xFFu) << (8 * i0)) | ((hb >> 8) << (8 * i1));
+      uint32_t zw = ((zb & 0xFFu) << (8 * i0)) | ((zb >> 8) << (8 * i1));
+      int o = tok * FW8_LD + 32 * ch + 4 * g;         // a multiple of 4
+      *reinterpret_cast<uint32_t*>(&sH[o]) = hw;
+      *reinterpret_cast<uint32_t*>(&sZ[o]) = zw;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    int item = tid + 256 * i;
+    int c = item & 7, f = item >> 3;                   // 16 tokens 16 c .. 16 c + 15 of feature f0 + f
+    uint32_t hq[2] = {0u, 0u}, zq[2] = {0u, 0u}, mq = 0u;
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+      uint32_t h[4], z[4];
+#pragma unroll
+      for (int j = 0; j < 4; j++) {
+        h[j] = sH[(16 * c + 4 * g + j) * FW8_LD + f];
+        z[j] = sZ[(16 * c + 4 * g + j) * FW8_LD + f];
+      }
+      uint32_t i0, i1;
+      uint32_t nib = pick24_codes(h[0], h[1], h[2], h[3], i0, i1);
+      uint32_t ha = i0 == 0 ? h[0] : (i0 == 1 ? h[1] : h[2]), hb = i1 == 3 ? h[3] : (i1 == 2 ? h[2] : h[1]);
+      uint32_t za = i0 == 0 ? z[0] : (i0 == 1 ? z[1] : z[2]), zb = i1 == 3 ? z[3] : (i1 == 2 ? z[2] : z[1]);
+      hq[g >> 1] |= (ha | (hb << 8)) << (16 * (g & 1));
+      zq[g >> 1] |= (za | (zb << 8)) << (16 * (g & 1));
+      mq |= nib << (4 * g);
+    }
+    size_t piece = a24_piece(f0 + f, t0 >> 7, T >> 7);
+    *reinterpret_cast<u32x2*>(Hc8_t + piece * 64 + 8 * c) = u32x2{hq[0], hq[1]};
+    if (has_z) *reinterpret_cast<u32x2*>(dZc8_t + piece * 64 + 8 * c) = u32x2{zq[0], zq[1]};
+    *reinterpret_cast<uint16_t*>(meta_t + piece * 16 + 2 * c) = (uint16_t)mq;
+  }
+}
+
+int launch_featurewise24_f8(const void* Hc8, const uint8_t* meta, const void* dZc8, int T, int F, void* Hc8_t, uint8_t* meta_t, void* dZc8_t, hipStream_t s) {
+  dim3 grid(F / FW8_FEAT, T / FW8_TOK);
+  hipLaunchKernelGGL(featurewise24_f8_kernel, grid, dim3(256), 0, s, static_cast<const uint8_t*>(Hc8), meta, static_cast<const uint8_t*>(dZc8),
+                     T, F, static_cast<uint8_t*>(Hc8_t), meta_t, static_cast<uint8_t*>(dZc8_t));
   return (int)hipGetLastError();
 }
 

@@ -76,8 +76,18 @@ int launch_dense_rowmajor(const void* A, int a_panel, const void* B, int b_panel
 int launch_dense_colmajor(const void* A, int a_panel, const void* B, int b_panel, int M, int N, int K, void* Ct, hipStream_t s);
 // fp8 e4m3 forward (per-tensor scales).  W1t8 [F][D] in dense panel form (64-byte pieces = 64 k), X8 [T][D];
 // compressed activation in the fp8 panel form (64 stored bytes + 16 metadata bytes per 128 k); bf16 results.
+// Hc16, meta16 (may be NULL): also the kept values before quantisation (bf16) and their metadata, in the bf16 panel form
 int launch_up_prune24_f8(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, float zscale, float sh,
-                         void* Hc8, uint8_t* meta, void* Hdbg, hipStream_t s);
+                         void* Hc8, uint8_t* meta, void* Hdbg, void* Hc16, uint8_t* meta16, hipStream_t s);
+// fp8 backward.  dH GEMM with rows = hidden features: A = W2 itself [F][D] e4m3 in dense panel form, B = dY8 [T][D];
+// dZc8 = e4m3(scale * acc * 2 sqrt(h) / sdz) on the kept positions (fp8 panel form), h from (Hc16, meta16)
+int launch_dh_gather_f8(const void* W2p8, const void* dY8, const void* Hc16, const uint8_t* meta16, int T, int D, int F, float scale, float sdz,
+                        void* dZc8, hipStream_t s);
+// out[N][M] = bf16(scale * (A24 . B^T))^T, e4m3 operands
+int launch_sp_colmajor_f8(const void* vals8, const uint8_t* meta, int a_panel, const void* B8, int b_panel, int M, int N, int K, float scale, void* Ct,
+                          hipStream_t s);
+// feature-wise re-compression of the fp8 operands (all in the fp8 panel form): T, F multiples of 128
+int launch_featurewise24_f8(const void* Hc8, const uint8_t* meta, const void* dZc8, int T, int F, void* Hc8_t, uint8_t* meta_t, void* dZc8_t, hipStream_t s);
 int launch_up_relu2_f8(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, float zscale, float sh, void* H8, hipStream_t s);
 int launch_sp_rowmajor_f8(const void* vals8, const uint8_t* meta, int a_panel, const void* B8, int b_panel, int M, int N, int K, float scale, void* C, hipStream_t s);
 int launch_dense_rowmajor_f8(const void* A8, int a_panel, const void* B8, int b_panel, int M, int N, int K, float scale, void* C, hipStream_t s);
@@ -106,7 +116,8 @@ int launch_unpanel(const void* src, int rows, int npanels, int piece_bytes, void
 // in_rowmap (may be NULL): row r of the input is taken from memory row in_rowmap[r]
 int launch_transpose(const void* in, int R, int C, void* out, int out_form, void* in_panel, int in_panel_b, const int* in_rowmap, hipStream_t s);
 // the same for 1-byte elements (fp8): in [R][C] -> out [C][R]; panel forms: 64-byte pieces of 64 k
-int launch_transpose8(const void* in, int R, int C, void* out, int out_form, hipStream_t s);
+// in_panel (may be NULL): also a panel-form copy of `in` itself (R % 256 == 0, C % 64 == 0), in the B form if in_panel_b
+int launch_transpose8(const void* in, int R, int C, void* out, int out_form, void* in_panel, int in_panel_b, hipStream_t s);
 
 // ------------------------------------------------------------------------------------------------
 // measurement probes (k_probe.hip); they allocate their own buffers and wait for their own work

@@ -25,7 +25,7 @@ FFN24_PERMUTE = 32
 FFN24_TELEMETRY = 64
 
 EXPORTS = (
-    "ffn24_ctx_create", "ffn24_ctx_destroy", "ffn24_set_scales", "ffn24_set_row_scales", "ffn24_set_token_permutation", "ffn24_set_split", "sparsify24", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd",
+    "ffn24_ctx_create", "ffn24_ctx_destroy", "ffn24_set_scales", "ffn24_set_bwd_scales", "ffn24_set_row_scales", "ffn24_set_token_permutation", "ffn24_set_split", "sparsify24", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd",
     "ffn_fwd", "ffn_bwd", "ffn24_prepare_weights", "ffn24_get_telemetry", "ffn24_policy_use_sparse", "ffn24_saved_bytes", "ffn24_copy_saved", "ffn24_set_profiling", "ffn24_kernel_ms", "ffn24_strerror",
     "ffn24_static_scratch_needed", "ffn24_fwd_static", "ffn24_kernel_mhz", "ffn24_probe_mfma_rate", "ffn24_probe_gemm", "ffn24_probe_copy",
 )
@@ -54,6 +54,7 @@ def lib() -> ctypes.CDLL:
         L.ffn24_ctx_create.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ci, ci]
         L.ffn24_ctx_destroy.argtypes = [vp]
         L.ffn24_set_scales.argtypes = [vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_float]
+        L.ffn24_set_bwd_scales.argtypes = [vp, ctypes.c_float, ctypes.c_float]
         L.ffn24_set_split.argtypes = [vp, i64]
         L.ffn24_set_token_permutation.argtypes = [vp, vp]
         L.ffn24_set_row_scales.argtypes = [vp, vp, vp, vp]
@@ -232,6 +233,10 @@ class Context:
         """Per-tensor scales of an fp8 context (see ffn24_set_scales in the header)."""
         _check(lib().ffn24_set_scales(self._h, sx, sw1, sh, sw2), "ffn24_set_scales")
 
+    def set_bwd_scales(self, sdy: float, sdz: float):
+        """Scales of the incoming gradient and of the stored dZ of an fp8 training context (see ffn24_set_bwd_scales)."""
+        _check(lib().ffn24_set_bwd_scales(self._h, sdy, sdz), "ffn24_set_bwd_scales")
+
     def set_row_scales(self, sx, sw1, sw2):
         """Row-wise scales of an FFN24_ROWWISE fp8 context: fp32 CUDA tensors [T], [F], [D]; the context keeps them alive."""
         _expect(sx, (self.T,), _F32, "sx")
@@ -290,7 +295,7 @@ class Context:
                    torch.empty((self.D, self.F), dtype=torch.bfloat16, device=dev),
                    torch.empty((self.F, self.D), dtype=torch.bfloat16, device=dev))
         dX, dW1, dW2 = out
-        _expect(dY, (self.T, self.D), _BF16, "dY")
+        _expect(dY, (self.T, self.D), _BYTE if self.dtype == FFN24_FP8_E4M3 else _BF16, "dY")
         _expect(dX, (self.T, self.D), _BF16, "dX")
         _expect(dW1, (self.D, self.F), _BF16, "dW1")
         _expect(dW2, (self.F, self.D), _BF16, "dW2")
@@ -309,12 +314,12 @@ class Context:
               "H_dump": (6, torch.bfloat16, lambda T, F: (T, F)), "H_dense": (7, torch.bfloat16, lambda T, F: (T, F)),
               "dZ_dense": (8, torch.bfloat16, lambda T, F: (T, F)),
               "nnz": (9, torch.int32, lambda T, F: (F,)), "feat_of_row": (10, torch.int32, lambda T, F: (F,)),
-              "sh": (11, torch.float32, lambda T, F: (T,))}
+              "sh": (11, torch.float32, lambda T, F: (T,)), "Hc16": (12, torch.bfloat16, lambda T, F: (T, F // 2))}
 
     def saved(self, name: str) -> torch.Tensor:
         """Row-major copy of a saved tensor of the context (enqueued on the current stream)."""
         which, dtype, shape_fn = self._SAVED[name]
-        if self.dtype == FFN24_FP8_E4M3 and dtype == torch.bfloat16 and name != "H_dump":
+        if self.dtype == FFN24_FP8_E4M3 and dtype == torch.bfloat16 and name not in ("H_dump", "Hc16"):
             dtype = torch.uint8      # e4m3 codes
         n = ctypes.c_int64()
         _check(lib().ffn24_saved_bytes(self._h, which, ctypes.byref(n)), "ffn24_saved_bytes")

@@ -698,10 +698,126 @@ def test_ffn24_fwd_fp8_multi_tile(F24):
     _check_fp8(F24, 512, 768, 1280, "per_feature", seed=52)
 
 
+def _fp8_bwd_case(F24, T, D, Fh, sparsity, seed, rows=None, gsel=None):
+    """fp8 forward + backward (per-tensor scales) against the oracle, staged like the bf16 backward:
+    (S1) feature-wise picks and the dZ gather bit-exact on the GPU's own stored codes; (S2) every stage against the
+    oracle run on the GPU's own upstream tensors (derivative from the saved bf16 activation through the named
+    stored-activation helper); (S3) from the raw inputs by the definition 2 max(0, Z) -- at 6e-2.
+    rows / gsel: token rows and hidden-feature groups to check when the oracle cannot run the whole size."""
+    big = T * Fh > (1 << 24)
+    if big:   # quantised by torch's CPU cast (pinned to the oracle's quantiser by the CPU tests); static activation scale
+        w8 = synth.make_inputs_fp8(T, D, Fh, sparsity, seed)
+        inp = {"b1": w8["b1"]}
+        sc = {k: w8[k] for k in ("sx", "sw1", "sw2", "sh")}
+        q = {k: w8[k] for k in ("X", "W1", "W2")}
+    else:
+        inp, sc, q = _fp8_inputs(T, D, Fh, sparsity, seed)
+    rng = np.random.default_rng(seed)
+    dY = rng.standard_normal((T, D)).astype(np.float32)
+    sc["sdy"] = float(np.abs(dY).max() / 448.0)
+    q["dY"] = torch.from_numpy(dY / np.float32(sc["sdy"])).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    # static dZ scale from the oracle's own backward on a token slice; a bit low so that a few values saturate
+    cal_f = O.ffn24_fwd_fp8_codes(q["X"][:64], q["W1"], inp["b1"], q["W2"], sc["sx"], sc["sw1"], sc["sh"], sc["sw2"])
+    cal = O.ffn24_bwd_fp8_codes(cal_f, q["X"][:64], q["W1"], q["W2"], q["dY"][:64], sc["sx"], sc["sw1"], sc["sh"], sc["sw2"], sc["sdy"], 1.0, quantise_dz=False)
+    sc["sdz"] = float(0.8 * np.abs(cal["dZ"]).max() / 448.0)
+    d = {k: torch.from_numpy(q[k]).cuda() for k in q}
+    b1 = torch.from_numpy(inp["b1"]).cuda()
+    ctx = F24.Context(T, D, Fh, F24.FFN24_TRAINING, dtype=F24.FFN24_FP8_E4M3)
+    ctx.set_scales(sc["sx"], sc["sw1"], sc["sh"], sc["sw2"])
+    ctx.set_bwd_scales(sc["sdy"], sc["sdz"])
+    Y = ctx.ffn24_fwd(d["X"], d["W1"], b1, d["W2"])
+    dX, dW1, dW2 = ctx.ffn24_bwd(d["dY"])
+    torch.cuda.synchronize()
+    rsel = np.arange(T) if rows is None else rows
+    rs_t = torch.from_numpy(rsel).cuda()
+    Hc8_all, meta_all, dZc8_all, Hc16_all = ctx.saved("Hc"), ctx.saved("meta"), ctx.saved("dZc"), ctx.saved("Hc16")
+    torch.cuda.synchronize()
+    Hc8 = Hc8_all[rs_t].cpu().numpy(); meta = meta_all[rs_t].cpu().numpy(); dZc8 = dZc8_all[rs_t].cpu().numpy(); Hc16_w = words_of(Hc16_all[rs_t])
+    scales = (sc["sx"], sc["sw1"], sc["sh"], sc["sw2"], sc["sdy"], sc["sdz"])
+    # the saved bf16 activation quantises to the saved codes (what the forward's epilogue did)
+    assert np.array_equal(O.f32_to_e4m3_bits(O.bf16_bits_to_f32(Hc16_w) / np.float32(sc["sh"])), Hc8)
+    # ---- S2 on the sampled token rows: dZ codes and dX from the GPU's own forward state
+    st = {"Z": None, "meta": meta, "Hc8_bits": Hc8}
+    H24_16 = O.bf16_bits_to_f32(O.decompress24(Hc16_w, meta))
+    g_st = O.ffn24_bwd_fp8_codes(st, q["X"][rsel], q["W1"], q["W2"], q["dY"][rsel], *scales, dAct=O.relu2_derivative_from_stored_activation(H24_16))
+    dz_gpu = O.e4m3_bits_to_f32(dZc8).astype(np.float64); dz_ref = O.e4m3_bits_to_f32(g_st["dZc8_bits"]).astype(np.float64)
+    # dZ codes: the GPU forms dZ / sdz in fp32, the oracle in float64, so a value on a rounding boundary may land on the
+    # neighbouring code (one step at the top binade is 7 % of the largest value, which a per-tensor maximum would read
+    # as an error): every code within one step of the oracle's, nearly all equal, and the tensor close as a whole
+    as_int = lambda c: np.where(c & 0x80, -(c & 0x7F).astype(np.int32), (c & 0x7F).astype(np.int32))
+    code_step = int(np.abs(as_int(dZc8) - as_int(g_st["dZc8_bits"])).max())
+    e_dz = O.fro_rel_err(dz_gpu, dz_ref); code_agree = float(np.mean(dZc8 == g_st["dZc8_bits"]))
+    assert code_step <= 1
+    W1v = O.e4m3_bits_to_f32(q["W1"]).astype(np.float64)
+    dx_staged = O.decompress24(dz_gpu, meta) @ W1v.T * (sc["sdz"] * sc["sw1"])
+    e_dx = O.max_rel_err(f64(dX[rs_t]), dx_staged); r_dx = O.row_rel_err(f64(dX[rs_t]), dx_staged)
+    assert (np.abs(dz_gpu) == 448).any()                     # the saturating branch of the dZ quantiser is exercised
+    # ---- S3 on the same rows, from the raw inputs by the definition
+    f_raw = O.ffn24_fwd_fp8_codes(q["X"][rsel], q["W1"], inp["b1"], q["W2"], sc["sx"], sc["sw1"], sc["sh"], sc["sw2"])
+    g_raw = O.ffn24_bwd_fp8_codes(f_raw, q["X"][rsel], q["W1"], q["W2"], q["dY"][rsel], *scales)
+    e_y = O.max_rel_err(f64(Y[rs_t]), f_raw["Y"]); e_dx_raw = O.max_rel_err(f64(dX[rs_t]), g_raw["dX"])
+    print(f"  fp8 bwd rows: dZ (Frobenius) {e_dz:.2e} (codes equal {code_agree:.4f}, largest distance {code_step} step)  dX staged {e_dx:.2e} (row {r_dx:.2e})  from raw inputs: Y {e_y:.2e} dX {e_dx_raw:.2e}", flush=True)
+    assert max(e_dz, e_dx, r_dx, e_y, e_dx_raw) <= TOL_FP8 and code_agree >= 0.98
+    # ---- feature groups over all tokens: feature-wise picks (S1), dW2 / dW1 (S2), and from the raw inputs (S3)
+    G = Fh // 4
+    gs = np.arange(G) if gsel is None else gsel
+    f4, f2 = _groups_to_cols(gs)
+    f4_t, f2_t = torch.from_numpy(f4).cuda(), torch.from_numpy(f2).cuda()
+    Hc8_g = Hc8_all[:, f2_t].cpu().numpy(); dZc8_g = dZc8_all[:, f2_t].cpu().numpy(); meta_g = _meta_of_groups(meta_all, gs)
+    H24_g = O.decompress24(Hc8_g, meta_g); dZ24_g = O.decompress24(dZc8_g, meta_g)          # codes [T, 4 |gs|]
+    Hct_ref, mt_ref = O.sparsify24(np.ascontiguousarray(H24_g.T))
+    dZct_ref = O.compress_with_meta(np.ascontiguousarray(dZ24_g.T), mt_ref)
+    Hc8_t = ctx.saved("Hc_t")[f4_t].cpu().numpy(); dZc8_t = ctx.saved("dZc_t")[f4_t].cpu().numpy(); meta_t = ctx.saved("meta_t")[f4_t].cpu().numpy()
+    torch.cuda.synchronize()
+    assert np.array_equal(meta_t, mt_ref) and np.array_equal(Hc8_t, Hct_ref) and np.array_equal(dZc8_t, dZct_ref)
+    dYv = O.e4m3_bits_to_f32(q["dY"]).astype(np.float64); Xv = O.e4m3_bits_to_f32(q["X"]).astype(np.float64)
+    dW2_st = _mm24(O.e4m3_bits_to_f32(Hct_ref), mt_ref, dYv) * (sc["sh"] * sc["sdy"])
+    dW1_st = _mm24(O.e4m3_bits_to_f32(dZct_ref), mt_ref, Xv) * (sc["sdz"] * sc["sx"])
+    e_dw2 = O.max_rel_err(f64(dW2[f4_t]), dW2_st); e_dw1 = O.max_rel_err(f64(dW1[:, f4_t]).T, dW1_st)
+    f_g = O.ffn24_fwd_fp8_codes(q["X"], q["W1"][:, f4], inp["b1"][f4], q["W2"][f4], sc["sx"], sc["sw1"], sc["sh"], sc["sw2"])
+    g_g = O.ffn24_bwd_fp8_codes(f_g, q["X"], q["W1"][:, f4], q["W2"][f4], q["dY"], *scales)
+    e_dw2_raw = O.max_rel_err(f64(dW2[f4_t]), g_g["dW2"]); e_dw1_raw = O.max_rel_err(f64(dW1[:, f4_t]), g_g["dW1"])
+    r_dw2_raw = O.row_rel_err(f64(dW2[f4_t]), g_g["dW2"])
+    print(f"  fp8 bwd features: dW2 staged {e_dw2:.2e} dW1 staged {e_dw1:.2e}  from raw inputs: dW2 {e_dw2_raw:.2e} (row {r_dw2_raw:.2e}) dW1 {e_dw1_raw:.2e}", flush=True)
+    assert max(e_dw2, e_dw1, e_dw2_raw, e_dw1_raw, r_dw2_raw) <= TOL_FP8
+    # 2:4 invariant of the feature-wise metadata everywhere
+    mt_all = ctx.saved("meta_t")
+    for nib in (mt_all & 0xF, mt_all >> 4):
+        assert bool(((nib & 3) < (nib >> 2)).all())
+    ctx.close()
+
+
+def test_ffn24_bwd_fp8_small(F24):
+    print("fp8 fwd+bwd T=256 D=512 F=2048", flush=True)
+    _fp8_bwd_case(F24, 256, 512, 2048, 0.90, seed=61)
+
+
+def test_ffn24_bwd_fp8_multi_tile(F24):
+    print("fp8 fwd+bwd T=768 D=512 F=1280 (several tiles, ragged stage counts)", flush=True)
+    _fp8_bwd_case(F24, 768, 512, 1280, "per_feature", seed=62)
+
+
+@pytest.mark.timeout(900)
+def test_ffn24_bwd_fp8_full_size_sampled(F24):
+    """c5 dims (T=8192, D=8192, F=32768), fp8 forward + backward: sampled token rows and hidden-feature groups."""
+    w = synth.WORKLOADS["c5"]
+    print(f"fp8 fwd+bwd full size c5 T={w.T} D={w.D} F={w.F}", flush=True)
+    rng = np.random.default_rng(46)
+    rows = np.sort(rng.choice(w.T, 96, replace=False))
+    gsel = np.sort(rng.choice(w.F // 4, 16, replace=False))
+    _fp8_bwd_case(F24, w.T, w.D, w.F, w.sparsity, seed=w.seed, rows=rows, gsel=gsel)
+
+
 def test_fp8_context_rules(F24):
+    for extra in (F24.FFN24_DENSE, F24.FFN24_ROWWISE):      # fp8 training is the per-tensor 2:4 path only
+        with pytest.raises(F24.Ffn24Error) as e:
+            F24.Context(256, 256, 256, F24.FFN24_TRAINING | extra, dtype=F24.FFN24_FP8_E4M3)
+        assert e.value.code == -4
+    ctx = F24.Context(256, 256, 256, 0, dtype=F24.FFN24_FP8_E4M3)
     with pytest.raises(F24.Ffn24Error) as e:
-        F24.Context(256, 256, 256, F24.FFN24_TRAINING, dtype=F24.FFN24_FP8_E4M3)
-    assert e.value.code == -4
+        ctx.set_bwd_scales(1.0, 1.0)                         # not a training context
+    assert e.value.code == -5
+    ctx.close()
     ctx = F24.Context(256, 256, 256, 0)
     with pytest.raises(F24.Ffn24Error) as e:
         ctx.set_scales(1.0, 1.0, 1.0, 1.0)          # bf16 context has no scales
