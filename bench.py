@@ -221,11 +221,12 @@ def main() -> int:
                     "main-loop decomposition, copy rate) instead of running the workload")
     ap.add_argument("--workload", default="c4", help="c1, c2, c3 (four forward layers), c3_85..c3_98, c4 (default: forward+backward at the 7B FFN dims), c5 (fp8 forward)")
     ap.add_argument("--fwd-only", action="store_true", help="time the forward pass only")
+    ap.add_argument("--fp8-bwd", action="store_true", help="workload c5: time forward + backward in fp8 (per-tensor scales; no dense fp8 baseline in this mode)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-tokens", type=int, default=4096, help="token slice the CPU oracle is timed on (about 15 s of CPU work at the default workload)")
     ap.add_argument("--split", type=int, default=0, help="keep this many hidden features (multiple of 256, <= d_ff/4) out of the "
                     "feature-wise 2:4: split weight-gradient GEMMs (bf16 fwd+bwd workloads)")
-    ap.add_argument("--rowwise", action="store_true", help="fp8 workload with row-wise instead of per-tensor scales (no dense baseline in this mode)")
+    ap.add_argument("--rowwise", action="store_true", help="fp8 workload with row-wise instead of per-tensor scales (2:4 FFN and dense baseline alike)")
     ap.add_argument("--permute", action="store_true", help="run the bf16 workload with a fixed token permutation around the FFN")
     ap.add_argument("--telemetry", action="store_true", help="bf16 workloads: count sparsity and 2:4 drops while running (reported under \"telemetry\")")
     ap.add_argument("--split-sweep", action="store_true", help="time the weight-gradient stage over a range of split sizes")
@@ -250,18 +251,27 @@ def main() -> int:
     w = synth.WORKLOADS[args.workload]
     T, D, F = w.T, w.D, w.F
     fp8 = args.workload == "c5"
-    bwd = not (args.fwd_only or fp8)
-    rowwise = fp8 and args.rowwise
+    bwd = not args.fwd_only and (not fp8 or args.fp8_bwd)
+    rowwise = fp8 and args.rowwise and not bwd
+    no_dense = fp8 and bwd
     if rowwise:
         inp = synth.make_inputs_fp8_rowwise(T, D, F, w.sparsity, w.seed)
         dev = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2", "sx", "sw1", "sw2")}
-        ctx = ffn24.Context(T, D, F, ffn24.FFN24_ROWWISE, dtype=ffn24.FFN24_FP8_E4M3)
+        ctx = ffn24.Context(T, D, F, ffn24.FFN24_ROWWISE | ffn24.FFN24_DENSE, dtype=ffn24.FFN24_FP8_E4M3)
         ctx.set_row_scales(dev["sx"], dev["sw1"], dev["sw2"])
     elif fp8:
         inp = synth.make_inputs_fp8(T, D, F, w.sparsity, w.seed)
-        dev = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2")}
-        ctx = ffn24.Context(T, D, F, ffn24.FFN24_DENSE, dtype=ffn24.FFN24_FP8_E4M3)
+        if bwd:   # incoming gradient ~ N(0, 1) quantised per tensor; static dZ scale with the same headroom as the activation's
+            dY = np.random.Generator(np.random.Philox(w.seed + 7)).standard_normal((T, D), dtype=np.float32)
+            inp["sdy"] = float(np.abs(dY).max() / 448.0)
+            inp["dY"] = torch.from_numpy(dY / np.float32(inp["sdy"])).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+            inp["sdz"] = 8.0 * 4.0 / 448.0      # |dH| up to about 4, derivative 2 max(0, z) up to about 8
+            del dY
+        dev = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2") + (("dY",) if bwd else ())}
+        ctx = ffn24.Context(T, D, F, ffn24.FFN24_TRAINING if bwd else ffn24.FFN24_DENSE, dtype=ffn24.FFN24_FP8_E4M3)
         ctx.set_scales(inp["sx"], inp["sw1"], inp["sh"], inp["sw2"])
+        if bwd:
+            ctx.set_bwd_scales(inp["sdy"], inp["sdz"])
     else:
         inp = synth.make_workload(args.workload, with_dy=True)
         dev = {k: torch.from_numpy(inp[k]).to(torch.bfloat16).cuda() for k in ("X", "W1", "W2", "dY")}
@@ -305,11 +315,13 @@ def main() -> int:
 
     # timed region: profiling off, nothing but the steps
     sec24, med24, min24 = _time_steps(torch, step24, args.warmup, args.steps)
-    sec_dense, med_dense, min_dense = (_time_steps(torch, step_dense, args.warmup, args.steps) if not rowwise else (float("nan"),) * 3)
+    sec_dense, med_dense, min_dense = (_time_steps(torch, step_dense, args.warmup, args.steps) if not no_dense else (float("nan"),) * 3)
     # separate pass: event pairs around every kernel (on the launch stream) and a clock sample in every GEMM kernel
     ctx.set_profiling(True)
     k24 = list(range(0, 7 if bwd else 2)) + ([13, 14] if bwd else []) + ([15, 16] if args.split and bwd else []) + ([17] if rowwise else [])
-    kd = [] if rowwise else list(range(7, 13 if bwd else 9))
+    kd = [] if no_dense else list(range(7, 13 if bwd else 9))      # (the dense row-wise quantisation kernel shares id 17 with the 2:4 one)
+    if fp8 and bwd:
+        k24 = [0, 1, 2, 3, 4, 5, 6, 13, 14]
     acc = {k: [] for k in k24 + kd}
     mhz = {k: [] for k in k24 + kd}
     for fn, ids in ((step24, k24), (step_dense, kd)):
@@ -381,8 +393,8 @@ def main() -> int:
             if name == "split_partition":
                 kernels[name] = {"ms": round(ms, 4)}
                 continue
-            nbytes = {"featurewise24": 4.25 * T * F, "transpose_weights": (6.0 if bwd else 4.0) * es * D * F, "transpose_acts": 8.0 * T * D,
-                      "transpose_dw1": 4.0 * D * F}[name]
+            nbytes = {"featurewise24": (2.0 * es + 0.25) * T * F, "transpose_weights": (6.0 if bwd else 4.0) * es * D * F,
+                      "transpose_acts": 4.0 * es * T * D, "transpose_dw1": 4.0 * D * F}[name]
             gbs = nbytes / (ms * 1e-3) / 1e9
             kernels[name] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / 8000.0, 4)}
     dom = max((n for n in kernel_ms if n in KERNEL_FLOPS and not n.startswith("dense_")), key=lambda n: kernel_ms[n])
@@ -408,7 +420,9 @@ def main() -> int:
         if rowwise:
             O.ffn24_fwd_fp8_rowwise_codes(inp["X"][:Ts], inp["sx"][:Ts], inp["W1"], inp["sw1"], inp["b1"], inp["W2"], inp["sw2"])
         elif fp8:
-            O.ffn24_fwd_fp8_codes(inp["X"][:Ts], inp["W1"], inp["b1"], inp["W2"], inp["sx"], inp["sw1"], inp["sh"], inp["sw2"])
+            f8 = O.ffn24_fwd_fp8_codes(inp["X"][:Ts], inp["W1"], inp["b1"], inp["W2"], inp["sx"], inp["sw1"], inp["sh"], inp["sw2"])
+            if bwd:
+                O.ffn24_bwd_fp8_codes(f8, inp["X"][:Ts], inp["W1"], inp["W2"], inp["dY"][:Ts], inp["sx"], inp["sw1"], inp["sh"], inp["sw2"], inp["sdy"], inp["sdz"])
         else:
             sl = {k: inp[k][:Ts] if k in ("X", "dY") else inp[k] for k in inp}
             f = O.ffn24_fwd(sl["X"], sl["W1"], sl["b1"], sl["W2"])
@@ -430,10 +444,10 @@ def main() -> int:
                                + (", weights prepared once" if prepared else ""),
                    "T": T, "d_model": D, "d_ff": F, "parallelism": "single GPU"},
         "frac_of_sparse_mfma_peak": round(value / (2 * peak), 4),
-        "dense_ffn": None if rowwise else {"ms_per_step": round(sec_dense * 1e3, 4), "ms_per_step_median": round(med_dense * 1e3, 4),
+        "dense_ffn": None if no_dense else {"ms_per_step": round(sec_dense * 1e3, 4), "ms_per_step_median": round(med_dense * 1e3, 4),
                                            "ms_per_step_min": round(min_dense * 1e3, 4), "tflops": round(flops_step / sec_dense / 1e12, 2)},
         "register_resident_mfma": {("sparse" if k else "dense"): {a: round(b, 2) for a, b in v.items()} for k, v in reg.items()},
-        "speedup_vs_dense_ffn": None if rowwise else round(sec_dense / sec24, 4),
+        "speedup_vs_dense_ffn": None if no_dense else round(sec_dense / sec24, 4),
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "sparsify24_standalone": sparsify,
     }
     if telemetry:

@@ -109,7 +109,10 @@ FFN24_API int ffn24_set_bwd_scales(ffn24_ctx* ctx, float sdy, float sdz);
  * sh[t] = (largest activation of token t) / 448, 1 for an all-zero row;  Hc8 = e4m3(kept / sh[t]);
  * Y = bf16(sh[t] sw2[d] (Hc8 . W2_8)).  Three kernels as in the paper: the up-projection (with activation and
  * sparsification fused in), a quantisation kernel (the row scale needs the whole row), the 2:4 GEMM.
- * Saved tensor 11 is sh [T] fp32.  ffn_fwd is not available in this mode (FFN24_ERR_STATE). */
+ * Saved tensor 11 is sh [T] fp32.  With FFN24_DENSE the context also runs ffn_fwd with the same scales: the dense
+ * baseline of the paper's forward benchmark, whose FP8 GEMMs use row-wise scaling on both sides -- up-projection,
+ * row-wise quantisation of every activation with sh[t] = (largest activation of token t) / 448, dense GEMM; saved tensor
+ * 7 is then H8 [T][F] and tensor 11 the sh of that forward. */
 FFN24_API int ffn24_set_row_scales(ffn24_ctx* ctx, const float* sx, const float* sw1, const float* sw2);
 
 /* Fixed token permutation around the FFN (paper Sec. 2, "Optimization 2": features are correlated among consecutive
@@ -139,8 +142,16 @@ FFN24_API int ffn24_ctx_destroy(ffn24_ctx* ctx);
 
 /* Standalone 2:4 compression along the columns (paper Sec. 2, first paragraph: keep the 2 largest magnitudes of
  * each block of 4).   H [rows][cols] -> values [rows][cols/2], meta [rows][cols/8].
- * cols must be a multiple of 8; rows >= 0 (rows == 0 is a no-op).  Signed inputs are allowed. */
+ * dtype is the element type of H and of values: FFN24_BF16 (cols a multiple of 8), or FFN24_FP8_E4M3 (bytes; the pick is
+ * made on the codes with the sign bit cleared, as integers; cols a multiple of 16, meta 16-byte aligned too).
+ * rows >= 0 (rows == 0 is a no-op).  Signed inputs are allowed. */
 FFN24_API int sparsify24(const void* H, int64_t rows, int64_t cols, ffn24_dtype dtype, void* values, uint8_t* meta, void* stream);
+
+/* Sparsification and FP8 quantisation in one pass (paper Sec. 2, the second of the forward's kernels: activation, then
+ * sparsification, then FP8 quantisation; the activation is already applied to H here).  H [rows][cols] bf16; the pick
+ * is made on the bf16 words as in sparsify24; values8 [rows][cols/2] receives e4m3(kept / scale), saturating at +-448,
+ * round to nearest even; meta [rows][cols/8].  scale > 0; cols a multiple of 8.  Moves 2.625 bytes per element. */
+FFN24_API int sparsify24_quantise(const void* H, int64_t rows, int64_t cols, float scale, void* values8, uint8_t* meta, void* stream);
 
 /* Feature-wise 2:4 on top of the token-wise one (paper Sec. 2, last paragraph, and Fig. 2c): the operand of a
  * GEMM that reduces over tokens must be 2:4 along tokens.  From the token-wise compressed activation

@@ -599,6 +599,26 @@ def ffn24_fwd_fp8_rowwise_codes(X8, sx, W1_8, sw1, b1, W2_8, sw2):
     return {"Z": Z, "Hq": Hq, "meta": meta, "Hc_words": Hc_w, "rowmax": rowmax, "sh": sh, "Hc8_bits": Hc8_bits, "Y": Y}
 
 
+def ffn_fwd_fp8_rowwise_codes(X8, sx, W1_8, sw1, b1, W2_8, sw2):
+    """Dense counterpart of ffn24_fwd_fp8_rowwise_codes (no pruning): the baseline of the paper's forward benchmark, whose
+    FP8 GEMMs use row-wise scaling on both sides (caption of the forward-speed-up figure).  Every activation is stored:
+    sh[t] = max_f H[t,f] / 448 (1 for an all-zero row);  H8 = e4m3(bf16(H) / sh[t]);  Y = sh[t] sw2[d] (H8 . W2_8)."""
+    Xq = E4M3_VALUES[np.ascontiguousarray(X8, dtype=np.uint8)]
+    W1q = E4M3_VALUES[np.ascontiguousarray(W1_8, dtype=np.uint8)]
+    sx = np.asarray(sx, dtype=np.float32); sw1 = np.asarray(sw1, dtype=np.float32); sw2 = np.asarray(sw2, dtype=np.float32)
+    Z = (Xq @ W1q) * sx.astype(np.float64)[:, None] * sw1.astype(np.float64)[None, :]
+    if b1 is not None:
+        Z = Z + np.asarray(b1, dtype=np.float64)[None, :]
+    R, H = _relu2(Z, Bf16)
+    Hq = round_bf16(H)
+    rowmax = Hq.max(axis=1).astype(np.float32)
+    sh = np.where(rowmax > 0, rowmax / np.float32(448.0), np.float32(1.0)).astype(np.float32)
+    H8_bits = f32_to_e4m3_bits(Hq / sh[:, None])
+    W2q = E4M3_VALUES[np.ascontiguousarray(W2_8, dtype=np.uint8)]
+    Y = (E4M3_VALUES[H8_bits] @ W2q) * sh.astype(np.float64)[:, None] * sw2.astype(np.float64)[None, :]
+    return {"Z": Z, "Hq": Hq, "sh": sh, "H8_bits": H8_bits, "Y": Y}
+
+
 def quantise_rows_e4m3(x):
     """Row-wise e4m3 quantisation of a float matrix: s[r] = max|x[r,:]| / 448 (1 for an all-zero row), codes of x / s."""
     x = np.asarray(x, dtype=np.float32)

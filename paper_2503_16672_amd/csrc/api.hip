@@ -7,7 +7,7 @@
 using namespace ffn24;
 
 namespace {
-constexpr int NUM_KERNELS = 18;
+constexpr int NUM_KERNELS = 18;   // K_QUANT is shared by the 2:4 and the dense row-wise quantisation kernels
 enum { K_UP = 0, K_DOWN, K_DH, K_DX, K_FW, K_DW2, K_DW1, KD_UP, KD_DOWN, KD_DH, KD_DX, KD_DW2, KD_DW1, K_TR_W, K_TR_ACT, K_PART, K_TR_DW1, K_QUANT };
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
@@ -46,6 +46,7 @@ struct ffn24_ctx {
   // row-wise-scaled fp8 forward (FFN24_ROWWISE): caller's scale vectors, and the library's intermediate tensors
   const float *rsx, *rsw1, *rsw2;
   void* Hc16; uint8_t* meta16; uint32_t* rowmax; float* rsh;
+  void* Hd16;                  // dense row-wise baseline: every activation as bf16 before quantisation
   // workspace (device)
   void* Hc; uint8_t* meta; void* dZc; void* Hc_t; uint8_t* meta_t; void* dZc_t; void* Hdbg; void* Hd; void* dZd;
   void* W1t; void* W2t; void* Xt; void* dYt; void* Hd_t; void* dZd_t;   // K-contiguous copies of GEMM operands
@@ -89,7 +90,7 @@ int free_all(ffn24_ctx* c) {
   int bad = 0;
   void* bufs[] = {c->Hc, c->meta, c->dZc, c->Hc_t, c->meta_t, c->dZc_t, c->Hdbg, c->Hd, c->dZd,
                   c->W1t, c->W2t, c->Xt, c->dYt, c->Hd_t, c->dZd_t, c->W2p, c->W1p,
-                  c->nnz, c->row_of_feat, c->feat_of_row, c->Hdn_t, c->dZdn_t, c->dW1t, c->Hc16, c->meta16, c->rowmax, c->rsh, c->perm};
+                  c->nnz, c->row_of_feat, c->feat_of_row, c->Hdn_t, c->dZdn_t, c->dW1t, c->Hc16, c->meta16, c->rowmax, c->rsh, c->perm, c->Hd16};
   for (void* b : bufs) if (b && hipFree(b) != hipSuccess) bad = 1;
   if (c->clk && hipFree(c->clk) != hipSuccess) bad = 1;
   if (c->tele && hipFree(c->tele) != hipSuccess) bad = 1;
@@ -215,6 +216,7 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
     ok = hipMalloc(&c->Hc16, tf) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->meta16), tf / 8) == hipSuccess &&
          hipMalloc(reinterpret_cast<void**>(&c->rowmax), 4 * (size_t)T) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->rsh), 4 * (size_t)T) == hipSuccess;
   if (ok && (flags & FFN24_DENSE)) ok = hipMalloc(&c->Hd, es * tf) == hipSuccess;
+  if (ok && (flags & FFN24_DENSE) && (flags & FFN24_ROWWISE)) ok = hipMalloc(&c->Hd16, 2 * tf) == hipSuccess;
   if (ok && (flags & FFN24_DENSE) && (flags & FFN24_TRAINING))
     ok = hipMalloc(&c->dZd, 2 * tf) == hipSuccess && hipMalloc(&c->Hd_t, 2 * tf) == hipSuccess && hipMalloc(&c->dZd_t, 2 * tf) == hipSuccess;
   if (ok && (flags & FFN24_DEBUG_DUMP_H)) ok = hipMalloc(&c->Hdbg, 2 * tf) == hipSuccess;
@@ -448,13 +450,26 @@ int ffn24_copy_saved(ffn24_ctx* c, int which, void* dst, int64_t dst_bytes, void
 }
 
 int sparsify24(const void* H, int64_t rows, int64_t cols, ffn24_dtype dtype, void* values, uint8_t* meta, void* stream) {
-  if (dtype != FFN24_BF16) return FFN24_ERR_DTYPE;
-  if (rows < 0 || cols < 0 || cols % 8) return FFN24_ERR_SHAPE;
+  if (dtype != FFN24_BF16 && dtype != FFN24_FP8_E4M3) return FFN24_ERR_DTYPE;
+  const bool f8 = dtype == FFN24_FP8_E4M3;
+  if (rows < 0 || cols < 0 || cols % (f8 ? 16 : 8)) return FFN24_ERR_SHAPE;
   if (rows == 0 || cols == 0) return FFN24_OK;
   if (rows > (INT64_MAX / 2) / cols) return FFN24_ERR_SHAPE;
   if (!H || !values || !meta) return FFN24_ERR_NULL;
-  if (misaligned(H) || misaligned(values)) return FFN24_ERR_ALIGN;
-  return launch_sparsify24(H, rows, cols, values, meta, static_cast<hipStream_t>(stream)) ? FFN24_ERR_HIP : FFN24_OK;
+  if (misaligned(H) || misaligned(values) || (f8 && misaligned(meta))) return FFN24_ERR_ALIGN;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (f8) return launch_sparsify24_bytes(H, rows, cols, values, meta, s) ? FFN24_ERR_HIP : FFN24_OK;
+  return launch_sparsify24(H, rows, cols, values, meta, s) ? FFN24_ERR_HIP : FFN24_OK;
+}
+
+int sparsify24_quantise(const void* H, int64_t rows, int64_t cols, float scale, void* values8, uint8_t* meta, void* stream) {
+  if (rows < 0 || cols < 0 || cols % 8) return FFN24_ERR_SHAPE;
+  if (!(scale > 0.f)) return FFN24_ERR_SHAPE;
+  if (rows == 0 || cols == 0) return FFN24_OK;
+  if (rows > (INT64_MAX / 2) / cols) return FFN24_ERR_SHAPE;
+  if (!H || !values8 || !meta) return FFN24_ERR_NULL;
+  if (misaligned(H) || misaligned(values8)) return FFN24_ERR_ALIGN;
+  return launch_sparsify24_quant(H, rows, cols, scale, values8, meta, static_cast<hipStream_t>(stream)) ? FFN24_ERR_HIP : FFN24_OK;
 }
 
 int sparsify24_featurewise(const void* Hc, const uint8_t* meta, const void* dZc, int64_t T, int64_t F,
@@ -614,7 +629,7 @@ int ffn24_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void
 
 int ffn_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const void* W2, void* Y, void* stream) {
   if (!c) return FFN24_ERR_NULL;
-  if (!(c->flags & FFN24_DENSE) || (c->flags & FFN24_ROWWISE)) return FFN24_ERR_STATE;
+  if (!(c->flags & FFN24_DENSE)) return FFN24_ERR_STATE;
   int rc = check_device(c);
   if (rc) return rc;
   rc = check_ptrs({X, Y});
@@ -623,7 +638,19 @@ int ffn_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const 
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   c->have_fwd24 = c->have_fwd_dense = 0;
+  if (c->f8 && (c->flags & FFN24_ROWWISE) && !c->rsx) return FFN24_ERR_STATE;
   if ((rc = resolve_weights(c, W1, W2, s))) return rc;
+  if (c->f8 && (c->flags & FFN24_ROWWISE)) {
+    // dense baseline with row-wise scales: up-projection (bf16 activations + row maxima), row-wise quantisation, dense GEMM
+    if (launch_zero32(c->rowmax, (size_t)T, s)) return FFN24_ERR_HIP;
+    { Timed t(c, KD_UP, s);
+      if (t.done(launch_up_relu2_f8_rowwise(c->W1t, X, b1, T, D, F, c->rsx, c->rsw1, c->Hd16, c->rowmax, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_QUANT, s);
+      if (t.done(launch_quantise_rows_dense(c->Hd16, c->rowmax, T, F, c->Hd, c->rsh, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, KD_DOWN, s);
+      if (t.done(launch_dense_rowmajor_f8_rowwise(c->Hd, c->W2t, T, D, F, c->rsh, c->rsw2, Y, s))) return FFN24_ERR_HIP; }
+    return FFN24_OK;
+  }
   if (c->f8) {
     { Timed t(c, KD_UP, s);
       if (t.done(launch_up_relu2_f8(c->W1t, X, b1, T, D, F, c->sx * c->sw1, c->sh, c->Hd, s))) return FFN24_ERR_HIP; }

@@ -499,6 +499,44 @@ struct EpiPrune24Rw {
   }
 };
 
+// Dense fp8 up-projection with ROW-WISE scaling (the baseline the paper's forward benchmark compares with: all FP8 GEMMs of
+// both sides use row-wise scales): z = sx[t] sw1[f] acc + b1[f];  h = bf16(max(0, z)^2), every one of them stored, as the
+// bf16 [T][F] operand in dense panel form (64-byte pieces of 32 k); rowmax[t] is raised to the row's largest word.  A
+// streaming kernel then quantises each row with sh[t] = rowmax[t] / 448.
+struct EpiRelu2Rw {
+  struct Args { __bf16* H16; const float* b1; int F; const float* sx; const float* sw1; uint32_t* rowmax; };
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+    LaneVec64 lb, lw;
+    lb.load(e.b1, m_lane, 0.f);
+    lw.load(e.sw1, m_lane, 1.f);
+#pragma unroll
+    for (int ni = 0; ni < 4; ni++) {
+      const int t = n_lane + ni;
+      const float sxt = e.sx[t];
+      uint32_t mx = 0u;
+#pragma unroll
+      for (int mi = 0; mi < 4; mi++) {
+        int f = m_lane + 16 * mi;
+        __bf16* row = e.H16 + a24_piece(t, f >> 5, e.F >> 5) * 32 + (f & 31);
+#pragma unroll
+        for (int q = 0; q < 2; q++) {
+          u32x4 o;
+#pragma unroll
+          for (int d = 0; d < 4; d++) {
+            int i = 16 * mi + 8 * q + 2 * d;
+            float r0 = fmaxf(acc[mi][ni][8 * q + 2 * d] * (sxt * lw.at(i)) + lb.at(i), 0.f);
+            float r1 = fmaxf(acc[mi][ni][8 * q + 2 * d + 1] * (sxt * lw.at(i + 1)) + lb.at(i + 1), 0.f);
+            o[d] = pack_bf16x2(r0 * r0, r1 * r1);
+            mx = max(mx, max(o[d] & 0xFFFFu, o[d] >> 16));
+          }
+          *reinterpret_cast<u32x4*>(row + 8 * q) = o;
+        }
+      }
+      if (mx) atomicMax(e.rowmax + t, mx);
+    }
+  }
+};
+
 // C[m][n] = bf16(acc * rs[m] * cs[n]), n contiguous (row-wise-scaled fp8 down-projection: rs = sh per token, cs = sw2).
 struct EpiRowMajorRowCol {
   struct Args { __bf16* C; int ldc; const float* rs; const float* cs; };

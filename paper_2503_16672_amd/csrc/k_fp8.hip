@@ -53,6 +53,19 @@ int launch_up_prune24_f8_rowwise(const void* W1t8, const void* X8, const float* 
   return launch_gemm<false, EpiPrune24Rw, true>(g, ea, s);
 }
 
+int launch_up_relu2_f8_rowwise(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, const float* sx, const float* sw1,
+                               void* H16, uint32_t* rowmax, hipStream_t s) {
+  GemmArgs g{W1t8, nullptr, X8, F, T, D, 1};
+  EpiRelu2Rw::Args ea{static_cast<__bf16*>(H16), b1, F, sx, sw1, rowmax};
+  return launch_gemm<false, EpiRelu2Rw, true>(g, ea, s);
+}
+
+int launch_dense_rowmajor_f8_rowwise(const void* A8, const void* B8, int M, int N, int K, const float* rs, const float* cs, void* C, hipStream_t s) {
+  GemmArgs g{A8, nullptr, B8, M, N, K, 1, nullptr, 1};
+  EpiRowMajorRowCol::Args ea{static_cast<__bf16*>(C), N, rs, cs};
+  return launch_gemm<false, EpiRowMajorRowCol, true>(g, ea, s);
+}
+
 int launch_sp_rowmajor_f8_rowwise(const void* vals8, const uint8_t* meta, const void* B8, int M, int N, int K, const float* rs, const float* cs,
                                   void* C, hipStream_t s) {
   GemmArgs g{vals8, meta, B8, M, N, K, 1, nullptr, 1};

@@ -42,6 +42,69 @@ __global__ void __launch_bounds__(256) sparsify24_kernel(const u32x4* __restrict
   }
 }
 
+// Standalone activation-side kernel of Sec. 2 (sparsification and FP8 quantisation in one pass): the pick is made on the
+// bf16 words exactly as above, the two kept values of each group are then quantised, e4m3(kept / scale), saturating.
+// Per work item 8 elements: one 16-byte load, 4 code bytes, one metadata byte (2.625 bytes per element in all).
+__global__ void __launch_bounds__(256) sparsify24_quant_kernel(const u32x4* __restrict__ in, int64_t n_oct, float scale,
+                                                               uint32_t* __restrict__ vals8, uint8_t* __restrict__ meta) {
+  int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < n_oct; o += stride) {
+    u32x4 v = in[o];
+    uint32_t p0, p1;
+    uint32_t n0 = pick24_words(v[0] & 0xFFFFu, v[0] >> 16, v[1] & 0xFFFFu, v[1] >> 16, p0);
+    uint32_t n1 = pick24_words(v[2] & 0xFFFFu, v[2] >> 16, v[3] & 0xFFFFu, v[3] >> 16, p1);
+    uint32_t q = cvt_e4m3x2(bf16_lo_to_f32(p0) / scale, bf16_hi_to_f32(p0) / scale, 0u, false);
+    q = cvt_e4m3x2(bf16_lo_to_f32(p1) / scale, bf16_hi_to_f32(p1) / scale, q, true);
+    vals8[o] = q;
+    meta[o] = (uint8_t)(n0 | (n1 << 4));
+  }
+}
+
+// 2:4 compression of a tensor that already is e4m3: the pick on the code bytes (sign cleared, as integers; ties -> lower
+// index).  A work item takes 16 bytes (four groups) and writes 8 code bytes and 2 metadata bytes.
+__global__ void __launch_bounds__(256) sparsify24_bytes_kernel(const u32x4* __restrict__ in, int64_t n16,
+                                                               u32x2* __restrict__ vals8, uint16_t* __restrict__ meta) {
+  int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < n16; o += stride) {
+    u32x4 v = in[o];
+    uint32_t out[2] = {0u, 0u}, m = 0u;
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+      uint32_t w = v[g];
+      uint32_t b0 = w & 0xFFu, b1 = (w >> 8) & 0xFFu, b2 = (w >> 16) & 0xFFu, b3 = w >> 24;
+      uint32_t k0 = ((b0 & 0x7Fu) << 2) | 3u, k1 = ((b1 & 0x7Fu) << 2) | 2u, k2 = ((b2 & 0x7Fu) << 2) | 1u, k3 = (b3 & 0x7Fu) << 2;
+      uint32_t kf, ks;
+      uint32_t nib = pick24_keys(k0, k1, k2, k3, kf, ks);
+      uint32_t i0 = nib & 3u, i1 = nib >> 2;
+      uint32_t a = (w >> (8 * i0)) & 0xFFu, b = (w >> (8 * i1)) & 0xFFu;
+      out[g >> 1] |= (a | (b << 8)) << (16 * (g & 1));
+      m |= nib << (4 * g);
+    }
+    vals8[o] = u32x2{out[0], out[1]};
+    meta[o] = (uint16_t)m;
+  }
+}
+
+int launch_sparsify24_quant(const void* H, int64_t rows, int64_t cols, float scale, void* vals8, uint8_t* meta, hipStream_t s) {
+  int64_t n_oct = rows * cols / 8;
+  if (n_oct == 0) return 0;
+  int64_t blocks = (n_oct + 255) / 256;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  hipLaunchKernelGGL(sparsify24_quant_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const u32x4*>(H), n_oct, scale,
+                     static_cast<uint32_t*>(vals8), meta);
+  return (int)hipGetLastError();
+}
+
+int launch_sparsify24_bytes(const void* H8, int64_t rows, int64_t cols, void* vals8, uint8_t* meta, hipStream_t s) {
+  int64_t n16 = rows * cols / 16;
+  if (n16 == 0) return 0;
+  int64_t blocks = (n16 + 255) / 256;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  hipLaunchKernelGGL(sparsify24_bytes_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const u32x4*>(H8), n16,
+                     static_cast<u32x2*>(vals8), reinterpret_cast<uint16_t*>(meta));
+  return (int)hipGetLastError();
+}
+
 int launch_sparsify24(const void* H, int64_t rows, int64_t cols, void* vals, uint8_t* meta, hipStream_t s) {
   int64_t n_oct = rows * cols / 8;
   if (n_oct == 0) return 0;
@@ -557,6 +620,49 @@ __global__ void __launch_bounds__(256) quantise_rows_kernel(const u32x4* __restr
     for (int c = 0; c < 4; c++) Hc8[i * 4 + c] = out[c];
     meta8[i] = u32x4{mo[0][0], mo[0][1], mo[1][0], mo[1][1]};
   }
+}
+
+// The same for the dense baseline: bf16 [T][F] in dense panel form (64-byte pieces of 32 features) -> e4m3 [T][F] in the
+// dense fp8 panel form (64-byte pieces of 64 features).  One work item per (token, 64 features).
+__global__ void __launch_bounds__(256) quantise_rows_dense_kernel(const u32x4* __restrict__ H16, const uint32_t* __restrict__ rowmax,
+                                                                  int T, int F, u32x4* __restrict__ H8, float* __restrict__ sh) {
+  const int np8 = F >> 6;                                 // output pieces per token
+  size_t n = (size_t)T * np8;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+    int tl = (int)(i & 255);
+    size_t blk = i >> 8;
+    int j = (int)(blk % np8), t = (int)(blk / np8) * 256 + tl;
+    float mxv = __builtin_bit_cast(float, rowmax[t] << 16);
+    float s = mxv > 0.f ? mxv / 448.f : 1.f;
+    if (j == 0) sh[t] = s;
+#pragma unroll
+    for (int hlf = 0; hlf < 2; hlf++) {
+      size_t pin = a24_piece(t, 2 * j + hlf, F >> 5);
+#pragma unroll
+      for (int c = 0; c < 2; c++) {                       // 16 bf16 values -> 16 codes
+        u32x4 v0 = H16[pin * 4 + 2 * c], v1 = H16[pin * 4 + 2 * c + 1];
+        u32x4 o;
+#pragma unroll
+        for (int d = 0; d < 2; d++) {
+          uint32_t q = cvt_e4m3x2(bf16_lo_to_f32(v0[2 * d]) / s, bf16_hi_to_f32(v0[2 * d]) / s, 0u, false);
+          o[d] = cvt_e4m3x2(bf16_lo_to_f32(v0[2 * d + 1]) / s, bf16_hi_to_f32(v0[2 * d + 1]) / s, q, true);
+          q = cvt_e4m3x2(bf16_lo_to_f32(v1[2 * d]) / s, bf16_hi_to_f32(v1[2 * d]) / s, 0u, false);
+          o[2 + d] = cvt_e4m3x2(bf16_lo_to_f32(v1[2 * d + 1]) / s, bf16_hi_to_f32(v1[2 * d + 1]) / s, q, true);
+        }
+        H8[i * 4 + 2 * hlf + c] = o;
+      }
+    }
+  }
+}
+
+int launch_quantise_rows_dense(const void* H16, const uint32_t* rowmax, int T, int F, void* H8, float* sh, hipStream_t s) {
+  size_t n = (size_t)T * (F >> 6);
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 256 * 64) blocks = 256 * 64;
+  hipLaunchKernelGGL(quantise_rows_dense_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const u32x4*>(H16), rowmax, T, F,
+                     static_cast<u32x4*>(H8), sh);
+  return (int)hipGetLastError();
 }
 
 int launch_quantise_rows(const void* Hc16, const uint8_t* meta16, const uint32_t* rowmax, int T, int F, void* Hc8, uint8_t* meta8, float* sh,

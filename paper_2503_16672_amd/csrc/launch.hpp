@@ -96,6 +96,12 @@ int launch_dense_rowmajor_f8(const void* A8, int a_panel, const void* B8, int b_
 // sh[t] = rowmax[t] / 448 (1 for an all-zero row), which it also writes out
 int launch_up_prune24_f8_rowwise(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, const float* sx, const float* sw1,
                                  void* Hc16, uint8_t* meta16, void* Hdbg, uint32_t* rowmax, hipStream_t s);
+// the dense row-wise-scaled baseline: up-projection writing every activation as bf16 (dense panel form) and raising rowmax;
+// quantise_rows_dense turns them into e4m3 (dense fp8 panel form) with sh[t] = rowmax[t] / 448; dense GEMM with sh[t] sw2[n]
+int launch_up_relu2_f8_rowwise(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, const float* sx, const float* sw1,
+                               void* H16, uint32_t* rowmax, hipStream_t s);
+int launch_quantise_rows_dense(const void* H16, const uint32_t* rowmax, int T, int F, void* H8, float* sh, hipStream_t s);
+int launch_dense_rowmajor_f8_rowwise(const void* A8, const void* B8, int M, int N, int K, const float* rs, const float* cs, void* C, hipStream_t s);
 int launch_quantise_rows(const void* Hc16, const uint8_t* meta16, const uint32_t* rowmax, int T, int F, void* Hc8, uint8_t* meta8, float* sh, hipStream_t s);
 int launch_sp_rowmajor_f8_rowwise(const void* vals8, const uint8_t* meta, const void* B8, int M, int N, int K, const float* rs, const float* cs,
                                   void* C, hipStream_t s);
@@ -103,6 +109,10 @@ int launch_sp_rowmajor_f8_rowwise(const void* vals8, const uint8_t* meta, const 
 // p[0..n) = 0 (a kernel, not a memset node)
 int launch_zero32(uint32_t* p, size_t n, hipStream_t s);
 int launch_sparsify24(const void* H, int64_t rows, int64_t cols, void* vals, uint8_t* meta, hipStream_t s);
+// bf16 in, pick on the bf16 words, kept values quantised to e4m3(kept / scale); cols % 8 == 0
+int launch_sparsify24_quant(const void* H, int64_t rows, int64_t cols, float scale, void* vals8, uint8_t* meta, hipStream_t s);
+// e4m3 in and out, pick on the code bytes; cols % 16 == 0
+int launch_sparsify24_bytes(const void* H8, int64_t rows, int64_t cols, void* vals8, uint8_t* meta, hipStream_t s);
 // panel: inputs and outputs are in panel form (the library's own buffers) instead of row-major
 int launch_featurewise24(const void* Hc, const uint8_t* meta, const void* dZc, int T, int F,
                          void* Hc_t, uint8_t* meta_t, void* dZc_t, int panel, unsigned long long* tele, hipStream_t s);

@@ -25,7 +25,7 @@ FFN24_PERMUTE = 32
 FFN24_TELEMETRY = 64
 
 EXPORTS = (
-    "ffn24_ctx_create", "ffn24_ctx_destroy", "ffn24_set_scales", "ffn24_set_bwd_scales", "ffn24_set_row_scales", "ffn24_set_token_permutation", "ffn24_set_split", "sparsify24", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd",
+    "ffn24_ctx_create", "ffn24_ctx_destroy", "ffn24_set_scales", "ffn24_set_bwd_scales", "ffn24_set_row_scales", "ffn24_set_token_permutation", "ffn24_set_split", "sparsify24", "sparsify24_quantise", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd",
     "ffn_fwd", "ffn_bwd", "ffn24_prepare_weights", "ffn24_get_telemetry", "ffn24_policy_use_sparse", "ffn24_saved_bytes", "ffn24_copy_saved", "ffn24_set_profiling", "ffn24_kernel_ms", "ffn24_strerror",
     "ffn24_static_scratch_needed", "ffn24_fwd_static", "ffn24_kernel_mhz", "ffn24_probe_mfma_rate", "ffn24_probe_gemm", "ffn24_probe_copy",
 )
@@ -59,6 +59,7 @@ def lib() -> ctypes.CDLL:
         L.ffn24_set_token_permutation.argtypes = [vp, vp]
         L.ffn24_set_row_scales.argtypes = [vp, vp, vp, vp]
         L.sparsify24.argtypes = [vp, i64, i64, ci, vp, vp, vp]
+        L.sparsify24_quantise.argtypes = [vp, i64, i64, ctypes.c_float, vp, vp, vp]
         L.sparsify24_featurewise.argtypes = [vp, vp, vp, i64, i64, vp, vp, vp, vp]
         L.spmm24.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp]
         L.ffn24_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp]
@@ -126,15 +127,30 @@ def _stream():
 
 
 def sparsify24(H: torch.Tensor, values: torch.Tensor | None = None, meta: torch.Tensor | None = None):
-    """H [rows, cols] bf16 -> (values [rows, cols/2] bf16, meta [rows, cols/8] uint8); outputs may be handed in."""
+    """H [rows, cols] bf16 (or e4m3 bytes) -> (values [rows, cols/2] of the same type, meta [rows, cols/8] uint8);
+    outputs may be handed in."""
+    rows, cols = H.shape
+    f8 = H.dtype in _BYTE
+    el = _BYTE if f8 else _BF16
+    _expect(H, (rows, cols), el, "H")
+    _expect(values, (rows, cols // 2), el, "values")
+    _expect(meta, (rows, cols // 8), (torch.uint8,), "meta")
+    values = torch.empty((rows, cols // 2), dtype=H.dtype, device=H.device) if values is None else values
+    meta = torch.empty((rows, cols // 8), dtype=torch.uint8, device=H.device) if meta is None else meta
+    _check(lib().sparsify24(_ptr(H), rows, cols, FFN24_FP8_E4M3 if f8 else FFN24_BF16, _ptr(values), _ptr(meta), _stream()), "sparsify24")
+    return values, meta
+
+
+def sparsify24_quantise(H: torch.Tensor, scale: float, values8: torch.Tensor | None = None, meta: torch.Tensor | None = None):
+    """H [rows, cols] bf16 -> (e4m3 codes of the kept values / scale [rows, cols/2] uint8, meta [rows, cols/8] uint8)."""
     rows, cols = H.shape
     _expect(H, (rows, cols), _BF16, "H")
-    _expect(values, (rows, cols // 2), _BF16, "values")
+    _expect(values8, (rows, cols // 2), _BYTE, "values8")
     _expect(meta, (rows, cols // 8), (torch.uint8,), "meta")
-    values = torch.empty((rows, cols // 2), dtype=torch.bfloat16, device=H.device) if values is None else values
+    values8 = torch.empty((rows, cols // 2), dtype=torch.uint8, device=H.device) if values8 is None else values8
     meta = torch.empty((rows, cols // 8), dtype=torch.uint8, device=H.device) if meta is None else meta
-    _check(lib().sparsify24(_ptr(H), rows, cols, FFN24_BF16, _ptr(values), _ptr(meta), _stream()), "sparsify24")
-    return values, meta
+    _check(lib().sparsify24_quantise(_ptr(H), rows, cols, scale, _ptr(values8), _ptr(meta), _stream()), "sparsify24_quantise")
+    return values8, meta
 
 
 def sparsify24_featurewise(Hc: torch.Tensor, meta: torch.Tensor, dZc: torch.Tensor | None = None):

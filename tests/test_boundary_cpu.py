@@ -20,7 +20,7 @@ def _declared():
 
 def test_header_symbols_are_exported():
     names = _declared()
-    assert len(names) == 28 and "ffn24_fwd" in names and "sparsify24" in names
+    assert len(names) == 29 and "ffn24_fwd" in names and "sparsify24" in names
     lib = ctypes.CDLL(LIB)
     for n in names:
         assert hasattr(lib, n), n
@@ -48,7 +48,11 @@ def test_argument_validation_without_gpu():
     assert L.sparsify24(a16, -1, 16, 0, a16, a16, None) == -2
     assert L.sparsify24(None, 4, 16, 0, a16, a16, None) == -1
     assert L.sparsify24(a16 + 2, 4, 16, 0, a16, a16, None) == -3
-    assert L.sparsify24(a16, 4, 16, 1, a16, a16, None) == -4
+    assert L.sparsify24(a16, 4, 16, 2, a16, a16, None) == -4
+    assert L.sparsify24(a16, 4, 24, 1, a16, a16, None) == -2          # e4m3 input: cols a multiple of 16
+    assert L.sparsify24_quantise(a16, 4, 16, ctypes.c_float(0.0), a16, a16, None) == -2
+    assert L.sparsify24_quantise(a16, 4, 12, ctypes.c_float(1.0), a16, a16, None) == -2
+    assert L.sparsify24_quantise(None, 4, 16, ctypes.c_float(1.0), a16, a16, None) == -1
     assert L.sparsify24(None, 0, 16, 0, None, None, None) == 0
     # spmm24 shape rules
     assert L.spmm24(a16, a16, a16, 256, 256, 32, a16, None) == -2

@@ -82,6 +82,38 @@ def test_sparsify24_ties_signs_and_specials(F24):
     assert np.array_equal(m.cpu().numpy(), m_ref)
 
 
+@pytest.mark.parametrize("rows,cols,p", [(1, 8, 0.5), (257, 1000, 0.1), (1031, 4104, 0.3), (64, 8192, 1.0)])
+def test_sparsify24_quantise_bit_exact(F24, rows, cols, p):
+    """Sparsification + FP8 quantisation in one pass: the oracle's pick on the bf16 words, then its e4m3 quantiser on the
+    kept values / scale (the same fp32 division on both sides), bit for bit; the scale lets the largest values saturate."""
+    print(f"sparsify24_quantise rows={rows} cols={cols} p={p}", flush=True)
+    words = synth.random_activation_words(rows, cols, p, seed=rows * 5 + cols)
+    words = np.where(np.random.default_rng(rows).random(words.shape) < 0.2, words | 0x8000, words).astype(np.uint16)   # some signs
+    scale = float(0.5 * O.bf16_bits_to_f32(words & 0x7FFF).max() / 448.0) or 1.0
+    v_ref, m_ref = O.sparsify24(words)
+    q_ref = O.f32_to_e4m3_bits(O.bf16_bits_to_f32(v_ref) / np.float32(scale))
+    q, m = F24.sparsify24_quantise(dev_bf16_from_words(words), scale)
+    torch.cuda.synchronize()
+    assert np.array_equal(m.cpu().numpy(), m_ref)
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    if rows * cols > 64:
+        assert ((q_ref & 0x7F) == 0x7E).any()
+
+
+@pytest.mark.parametrize("rows,cols", [(1, 16), (3, 48), (300, 1008), (128, 4096)])
+def test_sparsify24_on_e4m3_bytes_bit_exact(F24, rows, cols):
+    """2:4 compression of a tensor that already is e4m3: the oracle's pick on the codes (many exact ties, both signs)."""
+    print(f"sparsify24 fp8 rows={rows} cols={cols}", flush=True)
+    rng = np.random.default_rng(rows + cols)
+    codes = rng.integers(0, 256, size=(rows, cols)).astype(np.uint8)
+    codes[(codes & 0x7F) == 0x7F] = 0                                   # no NaN codes
+    codes = np.where(rng.random(codes.shape) < 0.5, np.uint8(0), codes)   # and many zeros
+    v_ref, m_ref = O.sparsify24(codes)
+    v, m = F24.sparsify24(torch.from_numpy(codes).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(v.cpu().numpy(), v_ref) and np.array_equal(m.cpu().numpy(), m_ref)
+
+
 def test_sparsify24_empty(F24):
     v, m = F24.sparsify24(torch.empty((0, 64), dtype=torch.bfloat16, device="cuda"))
     assert v.shape == (0, 32) and m.shape == (0, 8)
@@ -986,7 +1018,7 @@ def _check_fp8_rowwise(F24, T, D, Fh, sparsity, seed, rows=None):
     inp = synth.make_inputs_fp8_rowwise(T, D, Fh, sparsity, seed)
     d = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2", "sx", "sw1", "sw2")}
     b1 = torch.from_numpy(inp["b1"]).cuda()
-    ctx = F24.Context(T, D, Fh, F24.FFN24_DEBUG_DUMP_H | F24.FFN24_ROWWISE, dtype=F24.FFN24_FP8_E4M3)
+    ctx = F24.Context(T, D, Fh, F24.FFN24_DEBUG_DUMP_H | F24.FFN24_ROWWISE | F24.FFN24_DENSE, dtype=F24.FFN24_FP8_E4M3)
     ctx.set_row_scales(d["sx"], d["sw1"], d["sw2"])
     Y = ctx.ffn24_fwd(d["X"], d["W1"], b1, d["W2"])
     torch.cuda.synchronize()
@@ -1015,8 +1047,20 @@ def _check_fp8_rowwise(F24, T, D, Fh, sparsity, seed, rows=None):
     agree = float(np.mean(meta == ref["meta"]))
     print(f"  fp8 row-wise: H err {eh:.2e}  Y staged {e2:.2e}  Y end-to-end {e3:.2e}  meta agreement {agree:.5f}", flush=True)
     assert eh <= TOL_FP8 and e2 <= TOL_FP8 and e3 <= TOL_FP8 and agree >= 0.995
-    with pytest.raises(F24.Ffn24Error):
-        ctx.ffn_fwd(d["X"], d["W1"], b1, d["W2"])
+    # the dense baseline with the same row-wise scales: the row scale is the row maximum of the very same activation, so
+    # it equals the 2:4 run's; codes against the oracle from the inputs; Y staged on the GPU's own codes, and end to end
+    Yd = ctx.ffn_fwd(d["X"], d["W1"], b1, d["W2"])
+    torch.cuda.synchronize()
+    H8 = ctx.saved("H_dense")[rs_t].cpu().numpy(); shd = ctx.saved("sh")[rs_t].cpu().numpy()
+    torch.cuda.synchronize()
+    assert np.array_equal(shd, sh)
+    assert np.array_equal(H8, O.f32_to_e4m3_bits(f64(Hd).astype(np.float32) / shd[:, None]))      # bit-exact from the dumped activation
+    refd = O.ffn_fwd_fp8_rowwise_codes(inp["X"][rsel], inp["sx"][rsel], inp["W1"], inp["sw1"], inp["b1"], inp["W2"], inp["sw2"])
+    yd_staged = O.E4M3_VALUES[H8] @ W2q * shd.astype(np.float64)[:, None] * inp["sw2"].astype(np.float64)[None, :]
+    ed2 = O.max_rel_err(f64(Yd[rs_t]), yd_staged); ed3 = O.max_rel_err(f64(Yd[rs_t]), refd["Y"])
+    h8_agree = float(np.mean(H8 == refd["H8_bits"]))
+    print(f"  fp8 row-wise dense: Y staged {ed2:.2e}  Y end-to-end {ed3:.2e}  H8 code agreement {h8_agree:.5f}", flush=True)
+    assert ed2 <= TOL_FP8 and ed3 <= TOL_FP8 and h8_agree >= 0.99
     ctx.close()
 
 

@@ -663,6 +663,32 @@ def test_fp8_rowwise_reduces_to_per_tensor_when_scales_are_uniform():
     assert (rw["Hc8_bits"].max(axis=1) == 0x7E).all()
 
 
+def test_dense_fp8_rowwise_forward_reductions():
+    """(1) Row by row with uniform weight scales, the dense row-wise forward is the dense per-tensor forward run with
+    that row's scales.  (2) Fig. 2 caption: with two of every four hidden features switched off nothing is dropped, and
+    the 2:4 row-wise forward equals the dense one exactly (same row maxima, same codes, same products)."""
+    rng = np.random.default_rng(17)
+    T, D, F = 8, 16, 32
+    X = rng.standard_normal((T, D)).astype(np.float32); W1 = (rng.standard_normal((D, F)) / 4).astype(np.float32)
+    W2 = (rng.standard_normal((F, D)) / 6).astype(np.float32)
+    sx = (np.abs(X).max(axis=1) / 448).astype(np.float32); sw1, sw2 = np.float32(np.abs(W1).max() / 448), np.float32(np.abs(W2).max() / 448)
+    X8 = O.f32_to_e4m3_bits(X / sx[:, None]); W1_8 = O.f32_to_e4m3_bits(W1 / sw1); W2_8 = O.f32_to_e4m3_bits(W2 / sw2)
+    rw = O.ffn_fwd_fp8_rowwise_codes(X8, sx, W1_8, np.full(F, sw1, np.float32), None, W2_8, np.full(D, sw2, np.float32))
+    assert np.count_nonzero(rw["H8_bits"]) > 50 and len(set(rw["sh"].tolist())) == T
+    for t in range(T):
+        xt = (O.e4m3_bits_to_f32(X8[t:t + 1]) * sx[t]).astype(np.float32)        # re-quantises to the same codes
+        pt = O.ffn_fwd_fp8(xt, O.e4m3_bits_to_f32(W1_8) * sw1, None, O.e4m3_bits_to_f32(W2_8) * sw2, float(sx[t]), float(sw1), float(rw["sh"][t]), float(sw2))
+        assert np.array_equal(pt["H8_bits"][0], rw["H8_bits"][t])
+        np.testing.assert_allclose(pt["Y"][0], rw["Y"][t], rtol=1e-12, atol=1e-15)
+        assert (rw["H8_bits"][t] == 0x7E).any()                                   # the row's largest entry sits at 448
+    b1 = np.zeros(F, np.float32); b1.reshape(-1, 4)[:, [1, 2]] = -1e9
+    s1 = np.full(F, sw1, np.float32); s2 = np.full(D, sw2, np.float32)
+    a = O.ffn24_fwd_fp8_rowwise_codes(X8, sx, W1_8, s1, b1, W2_8, s2)
+    b = O.ffn_fwd_fp8_rowwise_codes(X8, sx, W1_8, s1, b1, W2_8, s2)
+    assert np.array_equal(a["sh"], b["sh"]) and np.array_equal(O.decompress24(a["Hc8_bits"], a["meta"]), b["H8_bits"])
+    assert np.array_equal(a["Y"], b["Y"]) and np.count_nonzero(b["H8_bits"]) > 20
+
+
 def test_quantise_rows_e4m3():
     x = np.array([[1.0, -2.0, 0.5], [0.0, 0.0, 0.0], [448.0, 3.5, -7.0]], np.float32)
     codes, s = O.quantise_rows_e4m3(x)
