@@ -574,6 +574,42 @@ def ffn24_bwd_fp8_codes(fwd, X8, W1_8, W2_8, dY8, sx, sw1, sh, sw2, sdy, sdz, wg
     return out
 
 
+def ffn_fwd_fp8_codes(X8, W1_8, b1, W2_8, sx, sw1, sh, sw2):
+    """ffn_fwd_fp8 on operands that are already e4m3 codes; also returns Z for the backward."""
+    Xq = E4M3_VALUES[np.ascontiguousarray(X8, dtype=np.uint8)]
+    W1q = E4M3_VALUES[np.ascontiguousarray(W1_8, dtype=np.uint8)]
+    Z = (Xq @ W1q) * (float(sx) * float(sw1))
+    if b1 is not None:
+        Z = Z + np.asarray(b1, dtype=np.float64)[None, :]
+    R, H = _relu2(Z, Bf16)
+    Hq = round_bf16(H)
+    H8_bits = f32_to_e4m3_bits(Hq / np.float32(sh))
+    W2q = E4M3_VALUES[np.ascontiguousarray(W2_8, dtype=np.uint8)]
+    Y = (E4M3_VALUES[H8_bits] @ W2q) * (float(sh) * float(sw2))
+    return {"Z": Z, "Hq": Hq, "H8_bits": H8_bits, "Y": Y}
+
+
+def ffn_bwd_fp8_codes(fwd, X8, W1_8, W2_8, dY8, sx, sw1, sh, sw2, sdy, sdz, quantise_dz=True, dAct=None):
+    """Dense counterpart of ffn24_bwd_fp8_codes (no masks): the textbook backward of the dense FFN with every GEMM operand
+    in e4m3.  dH = sdy sw2 (dY8 . W2_8^T);  dZ8 = e4m3(dH * 2 max(0, Z) / sdz);  dX = sdz sw1 (dZ8 . W1_8^T);
+    dW2 = sh sdy (H8^T . dY8);  dW1 = sx sdz (X8^T . dZ8).  fwd = the result of ffn_fwd_fp8_codes."""
+    Xv = E4M3_VALUES[np.ascontiguousarray(X8, dtype=np.uint8)]
+    W1v = E4M3_VALUES[np.ascontiguousarray(W1_8, dtype=np.uint8)]
+    W2v = E4M3_VALUES[np.ascontiguousarray(W2_8, dtype=np.uint8)]
+    dYv = E4M3_VALUES[np.ascontiguousarray(dY8, dtype=np.uint8)]
+    dH = (dYv @ W2v.T) * (float(sdy) * float(sw2))
+    dZ = dH * (relu2_derivative(fwd["Z"]) if dAct is None else np.asarray(dAct, dtype=np.float64))
+    if quantise_dz:
+        dZ8_bits = f32_to_e4m3_bits((dZ / float(sdz)).astype(np.float32))
+        dZ8v = E4M3_VALUES[dZ8_bits]
+    else:
+        dZ8_bits, dZ8v = None, dZ / float(sdz)
+    dX = (dZ8v @ W1v.T) * (float(sdz) * float(sw1))
+    dW2 = (E4M3_VALUES[np.asarray(fwd["H8_bits"], dtype=np.uint8)].T @ dYv) * (float(sh) * float(sdy))
+    dW1 = (Xv.T @ dZ8v) * (float(sx) * float(sdz))
+    return {"dH": dH, "dZ": dZ, "dZ8_bits": dZ8_bits, "dX": dX, "dW1": dW1, "dW2": dW2}
+
+
 def ffn24_fwd_fp8_rowwise_codes(X8, sx, W1_8, sw1, b1, W2_8, sw2):
     """fp8 forward with row-wise scaling (the paper's precision recipe, Sec. 2: "FP8 rowwise scaling"): the
     activation operand of each GEMM carries one scale per token row, the weight operand one per output channel.

@@ -205,6 +205,7 @@ int probe_gemm(int sparse, int variant, int M, int N, int K, int reps, double* m
   switch (variant) {
     FFN24_PROBE_CASE(0)
     FFN24_PROBE_CASE(PROBE_NO_DMA)
+    FFN24_PROBE_CASE(PROBE_NO_FRAG)
     FFN24_PROBE_CASE(MF)
     FFN24_PROBE_CASE(DF)
     FFN24_PROBE_CASE(PROBE_K_WRAP)

@@ -137,7 +137,7 @@ int launch_transpose8(const void* in, int R, int C, void* out, int out_form, voi
 // 2 dense fp8 32x32x64, 3 sparse fp8 32x32x64.
 int probe_mfma_rate(int kind, int iters, double* cycles_per_op, double* mhz, double* tflops_dense_equivalent);
 // The GEMM core on pseudo-random panel-form operands with ingredients taken out (`variant` = mask of PROBE_* in
-// gemm_core.hpp; supported: 0, NO_DMA, NO_MFMA | NO_FRAG, NO_DMA | NO_FRAG, K_WRAP, K_WRAP | NO_MFMA | NO_FRAG):
+// gemm_core.hpp; supported: 0, NO_DMA, NO_FRAG, NO_MFMA | NO_FRAG, NO_DMA | NO_FRAG, K_WRAP, K_WRAP | NO_MFMA | NO_FRAG):
 // median kernel duration over `reps` launches and the clock it ran at.
 int probe_gemm(int sparse, int variant, int M, int N, int K, int reps, double* ms_median, double* mhz);
 // Plain device-to-device copy kernel of `bytes` bytes (16 per work item): GB/s read + written.

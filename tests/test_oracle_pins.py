@@ -582,6 +582,37 @@ def test_fp8_backward_featurewise_mask_on_the_stored_codes():
     assert np.array_equal(g["dZc8_t_bits"], O.compress_with_meta(np.ascontiguousarray(g["dZ8_bits"].T), g["meta_t"]))
 
 
+def test_dense_fp8_backward_against_autograd_and_the_sparse_one():
+    """(1) With dZ unrounded the dense fp8 backward is torch autograd of the dequantised dense forward (dX, dW1 straight
+    through the activation's quantiser; dW2 with the stored activation constant).  (2) With two of every four features
+    switched off and tokens 1, 3 of every 4 zeroed (so neither 2:4 prune drops anything) it equals the 2:4 fp8 backward."""
+    inp, sc, sh, (X8, W1_8, W2_8, dY8), _ = _fp8_bwd_case()
+    f = O.ffn_fwd_fp8_codes(X8, W1_8, inp["b1"], W2_8, sc["sx"], sc["sw1"], sh, sc["sw2"])
+    g = O.ffn_bwd_fp8_codes(f, X8, W1_8, W2_8, dY8, sc["sx"], sc["sw1"], sh, sc["sw2"], sc["sdy"], 0.3, quantise_dz=False)
+    X = (_dec8(X8) * sc["sx"]).requires_grad_(True); W1 = (_dec8(W1_8) * sc["sw1"]).requires_grad_(True)
+    W2 = _dec8(W2_8) * sc["sw2"]; dY = _dec8(dY8) * sc["sdy"]
+    ((torch.clamp(X @ W1 + torch.from_numpy(inp["b1"].astype(np.float64)), min=0) ** 2) @ W2).backward(dY)
+    assert np.allclose(g["dX"], X.grad.numpy(), rtol=1e-9, atol=1e-12) and np.allclose(g["dW1"], W1.grad.numpy(), rtol=1e-9, atol=1e-12)
+    W2g = W2.clone().requires_grad_(True)
+    ((_dec8(f["H8_bits"]) * sh) @ W2g).backward(dY)
+    assert np.allclose(g["dW2"], W2g.grad.numpy(), rtol=1e-9, atol=1e-12)
+    # the forward of the codes equals the float-input dense forward on the dequantised tensors
+    ff = O.ffn_fwd_fp8((_dec8(X8) * sc["sx"]).detach().numpy().astype(np.float32), (_dec8(W1_8) * sc["sw1"]).detach().numpy().astype(np.float32), inp["b1"],
+                       (_dec8(W2_8) * sc["sw2"]).numpy().astype(np.float32), sc["sx"], sc["sw1"], sh, sc["sw2"])
+    assert np.array_equal(ff["H8_bits"], f["H8_bits"])
+    # lossless case
+    b1 = inp["b1"].copy(); b1.reshape(-1, 4)[:, [0, 3]] = -1e9
+    b1 = np.minimum(b1, -1e-3)                                    # zero tokens then give zero activations
+    X8z = X8.copy(); X8z.reshape(-1, 4, X8.shape[1])[:, [1, 3]] = 0
+    fd = O.ffn_fwd_fp8_codes(X8z, W1_8, b1, W2_8, sc["sx"], sc["sw1"], sh, sc["sw2"])
+    fs = O.ffn24_fwd_fp8_codes(X8z, W1_8, b1, W2_8, sc["sx"], sc["sw1"], sh, sc["sw2"])
+    args = (X8z, W1_8, W2_8, dY8, sc["sx"], sc["sw1"], sh, sc["sw2"], sc["sdy"], 0.05)
+    gd, gs = O.ffn_bwd_fp8_codes(fd, *args), O.ffn24_bwd_fp8_codes(fs, *args)
+    assert np.count_nonzero(fd["H8_bits"]) > 10
+    for k in ("dX", "dW1", "dW2"):
+        assert np.array_equal(gd[k], gs[k])
+
+
 def test_fp8_backward_scales_by_powers_of_two_exactly():
     """Doubling sdy with the same dY codes doubles the incoming gradient; if sdz doubles too, dZ / sdz and with it every
     code is unchanged, and all three gradients double exactly."""
