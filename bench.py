@@ -221,7 +221,7 @@ def main() -> int:
                     "main-loop decomposition, copy rate) instead of running the workload")
     ap.add_argument("--workload", default="c4", help="c1, c2, c3 (four forward layers), c3_85..c3_98, c4 (default: forward+backward at the 7B FFN dims), c5 (fp8 forward)")
     ap.add_argument("--fwd-only", action="store_true", help="time the forward pass only")
-    ap.add_argument("--fp8-bwd", action="store_true", help="workload c5: time forward + backward in fp8 (per-tensor scales; no dense fp8 baseline in this mode)")
+    ap.add_argument("--fp8-bwd", action="store_true", help="workload c5: time forward + backward in fp8 (per-tensor scales), 2:4 FFN and dense fp8 baseline")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-tokens", type=int, default=4096, help="token slice the CPU oracle is timed on (about 15 s of CPU work at the default workload)")
     ap.add_argument("--split", type=int, default=0, help="keep this many hidden features (multiple of 256, <= d_ff/4) out of the "
@@ -253,7 +253,7 @@ def main() -> int:
     fp8 = args.workload == "c5"
     bwd = not args.fwd_only and (not fp8 or args.fp8_bwd)
     rowwise = fp8 and args.rowwise and not bwd
-    no_dense = fp8 and bwd
+    no_dense = False
     if rowwise:
         inp = synth.make_inputs_fp8_rowwise(T, D, F, w.sparsity, w.seed)
         dev = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2", "sx", "sw1", "sw2")}
@@ -268,7 +268,7 @@ def main() -> int:
             inp["sdz"] = 8.0 * 4.0 / 448.0      # |dH| up to about 4, derivative 2 max(0, z) up to about 8
             del dY
         dev = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2") + (("dY",) if bwd else ())}
-        ctx = ffn24.Context(T, D, F, ffn24.FFN24_TRAINING if bwd else ffn24.FFN24_DENSE, dtype=ffn24.FFN24_FP8_E4M3)
+        ctx = ffn24.Context(T, D, F, (ffn24.FFN24_TRAINING if bwd else 0) | ffn24.FFN24_DENSE, dtype=ffn24.FFN24_FP8_E4M3)
         ctx.set_scales(inp["sx"], inp["sw1"], inp["sh"], inp["sw2"])
         if bwd:
             ctx.set_bwd_scales(inp["sdy"], inp["sdz"])
@@ -320,8 +320,6 @@ def main() -> int:
     ctx.set_profiling(True)
     k24 = list(range(0, 7 if bwd else 2)) + ([13, 14] if bwd else []) + ([15, 16] if args.split and bwd else []) + ([17] if rowwise else [])
     kd = [] if no_dense else list(range(7, 13 if bwd else 9))      # (the dense row-wise quantisation kernel shares id 17 with the 2:4 one)
-    if fp8 and bwd:
-        k24 = [0, 1, 2, 3, 4, 5, 6, 13, 14]
     acc = {k: [] for k in k24 + kd}
     mhz = {k: [] for k in k24 + kd}
     for fn, ids in ((step24, k24), (step_dense, kd)):

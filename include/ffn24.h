@@ -85,8 +85,9 @@ FFN24_API int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F,
  *   Hc8 = e4m3(kept / sh), saturating at +-448, round to nearest even;  Y = bf16(sh sw2 (Hc8 . W2_8))
  * (paper Sec. 2: activation, then sparsification, then FP8 quantisation; per-tensor scales instead of the paper's
  * row-wise ones).  Saved tensors 0 and 1 are then bytes: Hc8 [T][F/2], meta [T][F/8]; tensor 7 is H8 [T][F].
- * ffn_fwd is the dense fp8 baseline of the forward.  With FFN24_TRAINING (and none of FFN24_ROWWISE, FFN24_DENSE,
- * FFN24_SPLIT: FFN24_ERR_DTYPE otherwise) the context also supports ffn24_bwd in fp8, see ffn24_set_bwd_scales. */
+ * ffn_fwd is the dense fp8 baseline of the forward.  With FFN24_TRAINING (and neither FFN24_ROWWISE nor FFN24_SPLIT:
+ * FFN24_ERR_DTYPE otherwise) the context also supports ffn24_bwd -- and, with FFN24_DENSE, ffn_bwd -- in fp8, see
+ * ffn24_set_bwd_scales. */
 FFN24_API int ffn24_set_scales(ffn24_ctx* ctx, float sx, float sw1, float sh, float sw2);
 
 /* fp8 backward of an FFN24_FP8_E4M3 | FFN24_TRAINING context (paper abstract: FP8 in both the forwards and the
@@ -98,7 +99,8 @@ FFN24_API int ffn24_set_scales(ffn24_ctx* ctx, float sx, float sw1, float sh, fl
  *   dX = bf16(sdz sw1 (dZ8 . W1_8^T));  feature-wise 2:4 on top, ranked on the stored e4m3 codes of the activation;
  *   dW2 = bf16(sh sdy ((H24_8 * M_T)^T . dY8));  dW1 = bf16(sx sdz (X8^T . (dZ8 * M_T))).
  * dX [T][D], dW1 [D][F], dW2 [F][D] are bf16.  Saved tensors 2, 3, 5 are then e4m3 bytes; tensor 12 is the bf16 kept
- * activation [T][F/2]. */
+ * activation [T][F/2].  ffn_bwd on such a context (FFN24_DENSE too) is the dense fp8 baseline: the same with no masks,
+ * dZ8 = e4m3(dH * 2 sqrt(h) / sdz) at every position (saved tensor 8, bytes), h the bf16 activation its forward saved. */
 FFN24_API int ffn24_set_bwd_scales(ffn24_ctx* ctx, float sdy, float sdz);
 
 /* Row-wise scaling of an fp8 context created with FFN24_ROWWISE (paper Sec. 2: "FP8 rowwise scaling"): the activation

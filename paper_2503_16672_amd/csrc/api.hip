@@ -174,7 +174,7 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
   if (!out) return FFN24_ERR_NULL;
   if (dtype != FFN24_BF16 && dtype != FFN24_FP8_E4M3) return FFN24_ERR_DTYPE;
   const bool f8 = dtype == FFN24_FP8_E4M3;
-  if (f8 && (flags & FFN24_TRAINING) && (flags & (FFN24_ROWWISE | FFN24_DENSE | FFN24_SPLIT))) return FFN24_ERR_DTYPE;   // fp8 training: per-tensor 2:4 path only
+  if (f8 && (flags & FFN24_TRAINING) && (flags & (FFN24_ROWWISE | FFN24_SPLIT))) return FFN24_ERR_DTYPE;   // fp8 training: per-tensor scales, no split
   if ((flags & FFN24_SPLIT) && !(flags & FFN24_TRAINING)) return FFN24_ERR_STATE;
   if ((flags & FFN24_ROWWISE) && !f8) return FFN24_ERR_DTYPE;
   if ((flags & FFN24_PERMUTE) && f8) return FFN24_ERR_DTYPE;
@@ -218,7 +218,8 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
   if (ok && (flags & FFN24_DENSE)) ok = hipMalloc(&c->Hd, es * tf) == hipSuccess;
   if (ok && (flags & FFN24_DENSE) && (flags & FFN24_ROWWISE)) ok = hipMalloc(&c->Hd16, 2 * tf) == hipSuccess;
   if (ok && (flags & FFN24_DENSE) && (flags & FFN24_TRAINING))
-    ok = hipMalloc(&c->dZd, 2 * tf) == hipSuccess && hipMalloc(&c->Hd_t, 2 * tf) == hipSuccess && hipMalloc(&c->dZd_t, 2 * tf) == hipSuccess;
+    ok = hipMalloc(&c->dZd, es * tf) == hipSuccess && hipMalloc(&c->Hd_t, es * tf) == hipSuccess && hipMalloc(&c->dZd_t, es * tf) == hipSuccess;
+  if (ok && f8 && (flags & FFN24_DENSE) && (flags & FFN24_TRAINING) && !c->Hd16) ok = hipMalloc(&c->Hd16, 2 * tf) == hipSuccess;
   if (ok && (flags & FFN24_DEBUG_DUMP_H)) ok = hipMalloc(&c->Hdbg, 2 * tf) == hipSuccess;
   for (int k = 0; ok && k < NUM_KERNELS; k++)
     for (int j = 0; ok && j < 2; j++) ok = hipEventCreate(&c->ev[k][j]) == hipSuccess;
@@ -652,10 +653,13 @@ int ffn_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const 
     return FFN24_OK;
   }
   if (c->f8) {
+    const bool train = (c->flags & FFN24_TRAINING) != 0;
     { Timed t(c, KD_UP, s);
-      if (t.done(launch_up_relu2_f8(c->W1t, X, b1, T, D, F, c->sx * c->sw1, c->sh, c->Hd, s))) return FFN24_ERR_HIP; }
+      if (t.done(launch_up_relu2_f8(c->W1t, X, b1, T, D, F, c->sx * c->sw1, c->sh, c->Hd, train ? c->Hd16 : nullptr, train ? c->Hd_t : nullptr, s)))
+        return FFN24_ERR_HIP; }
     { Timed t(c, KD_DOWN, s);
       if (t.done(launch_dense_rowmajor_f8(c->Hd, 1, c->W2t, 1, T, D, F, c->sh * c->sw2, Y, s))) return FFN24_ERR_HIP; }
+    if (train) { c->X = X; c->have_fwd_dense = 1; }
     return FFN24_OK;
   }
   if (c->tele && launch_zero32(reinterpret_cast<uint32_t*>(c->tele), 2 * TELE_WORDS, s)) return FFN24_ERR_HIP;
@@ -675,6 +679,20 @@ int ffn_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void* 
   if (rc) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
+  if (c->f8) {
+    { Timed t(c, KD_DH, s);
+      if (t.done(launch_dh_drelu_f8(c->W2p, dY, c->Hd16, T, D, F, c->sdy * c->sw2, c->sdz, c->dZd, c->dZd_t, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, KD_DX, s);
+      if (t.done(launch_dense_rowmajor_f8(c->dZd, 1, c->W1p, 1, T, D, F, c->sdz * c->sw1, dX, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_TR_ACT, s);
+      int rc1 = launch_transpose8(dY, T, D, c->dYt, 2, nullptr, 0, s);
+      if (t.done(rc1 ? rc1 : launch_transpose8(c->X, T, D, c->Xt, 2, nullptr, 0, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, KD_DW2, s);
+      if (t.done(launch_dense_rowmajor_f8(c->Hd_t, 1, c->dYt, 1, F, D, T, c->sh * c->sdy, dW2, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, KD_DW1, s);
+      if (t.done(launch_dense_colmajor_f8(c->dZd_t, 1, c->Xt, 1, F, D, T, c->sdz * c->sx, dW1, s))) return FFN24_ERR_HIP; }
+    return FFN24_OK;
+  }
   { Timed t(c, KD_DH, s);  if (t.done(launch_dh_drelu(c->W2p, dY, c->Hd, T, D, F, c->dZd, c->dZd_t, s))) return FFN24_ERR_HIP; }
   { Timed t(c, KD_DX, s);  if (t.done(launch_dense_rowmajor(c->dZd, 1, c->W1p, 1, T, D, F, dX, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_TR_ACT, s);

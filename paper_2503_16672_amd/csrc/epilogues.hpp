@@ -557,28 +557,94 @@ struct EpiRowMajorRowCol {
 
 // fp8 dense up-projection (baseline): H8[t][f] = e4m3( bf16(max(0, zscale acc + b1)^2) / sh ), the [T][F] byte operand
 // of the dense down-projection, in dense panel form (64-byte pieces of 64 k).
+// H16, H8t (optional, a training context): the activation before quantisation as bf16 [T][F] (dense bf16 panel form; the
+// backward takes the derivative from it) and the codes once more as the [F][T] operand of the weight-gradient GEMM that
+// reduces over tokens (dense fp8 panel form).
 struct EpiRelu2F8 {
-  struct Args { uint8_t* H8; const float* b1; int F; float zscale; float sh; };
+  struct Args { uint8_t* H8; const float* b1; int F; float zscale; float sh; __bf16* H16; uint8_t* H8t; int T; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
     LaneVec64 lb;
     lb.load(e.b1, m_lane, 0.f);
+    uint32_t qs[4][16];   // the lane's codes: [token][4 features per word]
 #pragma unroll
     for (int ni = 0; ni < 4; ni++) {
       uint8_t* row = e.H8 + a24_piece(n_lane + ni, m_lane >> 6, e.F >> 6) * 64;   // a lane's 64 features: one piece
 #pragma unroll
       for (int mi = 0; mi < 4; mi++) {
-        uint32_t q[4];
+        uint32_t q[4], hp[8];
 #pragma unroll
         for (int d = 0; d < 8; d++) {
           float b0 = lb.at(16 * mi + 2 * d), b1v = lb.at(16 * mi + 2 * d + 1);
           float r0 = fmaxf(acc[mi][ni][2 * d] * e.zscale + b0, 0.f);
           float r1 = fmaxf(acc[mi][ni][2 * d + 1] * e.zscale + b1v, 0.f);
-          uint32_t hp = pack_bf16x2(r0 * r0, r1 * r1);
-          q[d >> 1] = cvt_e4m3x2(bf16_lo_to_f32(hp) / e.sh, bf16_hi_to_f32(hp) / e.sh, (d & 1) ? q[d >> 1] : 0u, (d & 1) != 0);
+          hp[d] = pack_bf16x2(r0 * r0, r1 * r1);
+          q[d >> 1] = cvt_e4m3x2(bf16_lo_to_f32(hp[d]) / e.sh, bf16_hi_to_f32(hp[d]) / e.sh, (d & 1) ? q[d >> 1] : 0u, (d & 1) != 0);
         }
         *reinterpret_cast<u32x4*>(row + 16 * mi) = u32x4{q[0], q[1], q[2], q[3]};
+        if (e.H16) {
+          int f = m_lane + 16 * mi;
+          __bf16* r16 = e.H16 + a24_piece(n_lane + ni, f >> 5, e.F >> 5) * 32 + (f & 31);
+          *reinterpret_cast<u32x4*>(r16) = u32x4{hp[0], hp[1], hp[2], hp[3]};
+          *reinterpret_cast<u32x4*>(r16 + 8) = u32x4{hp[4], hp[5], hp[6], hp[7]};
+        }
+#pragma unroll
+        for (int d = 0; d < 4; d++) qs[ni][4 * mi + d] = q[d];
       }
     }
+    if (e.H8t) {
+      // feature m_lane + 4 w + b: its codes of the lane's 4 consecutive tokens -> one 4-byte store
+#pragma unroll
+      for (int w = 0; w < 16; w++)
+#pragma unroll
+        for (int b = 0; b < 4; b++) {
+          uint32_t o = ((qs[0][w] >> (8 * b)) & 0xFFu) | (((qs[1][w] >> (8 * b)) & 0xFFu) << 8) | (((qs[2][w] >> (8 * b)) & 0xFFu) << 16) |
+                       (((qs[3][w] >> (8 * b)) & 0xFFu) << 24);
+          *reinterpret_cast<uint32_t*>(e.H8t + a24_piece(m_lane + 4 * w + b, n_lane >> 6, e.T >> 6) * 64 + (n_lane & 63)) = o;
+        }
+    }
+  }
+};
+
+// Dense fp8 backward, pointwise part: acc = (W2_8 . dY8) for a lane's 64 features x 4 tokens; dZ = scale * acc * 2 sqrt(h) with h
+// the bf16 activation the dense forward saved (H16, dense bf16 panel form); stored as e4m3(dZ / sdz) twice: the [T][F]
+// operand of the dX GEMM and the [F][T] operand of the dW1 GEMM (dense fp8 panel forms).
+struct EpiDReluF8 {
+  struct Args { const __bf16* H16; uint8_t* dZ8; uint8_t* dZ8t; int F; int T; float scale; float sdz; };
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+    uint32_t qs[4][16];
+#pragma unroll
+    for (int ni = 0; ni < 4; ni++) {
+      uint8_t* row = e.dZ8 + a24_piece(n_lane + ni, m_lane >> 6, e.F >> 6) * 64;
+#pragma unroll
+      for (int mi = 0; mi < 4; mi++) {
+        int f = m_lane + 16 * mi;
+        const __bf16* r16 = e.H16 + a24_piece(n_lane + ni, f >> 5, e.F >> 5) * 32 + (f & 31);
+        uint32_t q[4];
+#pragma unroll
+        for (int hq = 0; hq < 2; hq++) {
+          u32x4 h = *reinterpret_cast<const u32x4*>(r16 + 8 * hq);
+#pragma unroll
+          for (int d = 0; d < 4; d++) {
+            float g0 = 2.f * __builtin_amdgcn_sqrtf(bf16_lo_to_f32(h[d]));
+            float g1 = 2.f * __builtin_amdgcn_sqrtf(bf16_hi_to_f32(h[d]));
+            float v0 = (acc[mi][ni][8 * hq + 2 * d] * e.scale * g0) / e.sdz, v1 = (acc[mi][ni][8 * hq + 2 * d + 1] * e.scale * g1) / e.sdz;
+            int dd = 4 * hq + d;
+            q[dd >> 1] = cvt_e4m3x2(v0, v1, (dd & 1) ? q[dd >> 1] : 0u, (dd & 1) != 0);
+          }
+        }
+        *reinterpret_cast<u32x4*>(row + 16 * mi) = u32x4{q[0], q[1], q[2], q[3]};
+#pragma unroll
+        for (int d = 0; d < 4; d++) qs[ni][4 * mi + d] = q[d];
+      }
+    }
+#pragma unroll
+    for (int w = 0; w < 16; w++)
+#pragma unroll
+      for (int b = 0; b < 4; b++) {
+        uint32_t o = ((qs[0][w] >> (8 * b)) & 0xFFu) | (((qs[1][w] >> (8 * b)) & 0xFFu) << 8) | (((qs[2][w] >> (8 * b)) & 0xFFu) << 16) |
+                     (((qs[3][w] >> (8 * b)) & 0xFFu) << 24);
+        *reinterpret_cast<uint32_t*>(e.dZ8t + a24_piece(m_lane + 4 * w + b, n_lane >> 6, e.T >> 6) * 64 + (n_lane & 63)) = o;
+      }
   }
 };
 

@@ -11,9 +11,10 @@ int launch_up_prune24_f8(const void* W1t8, const void* X8, const float* b1, int 
   return launch_gemm<false, EpiPrune24F8, true>(g, ea, s);
 }
 
-int launch_up_relu2_f8(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, float zscale, float sh, void* H8, hipStream_t s) {
+int launch_up_relu2_f8(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, float zscale, float sh, void* H8, void* H16, void* H8t,
+                       hipStream_t s) {
   GemmArgs g{W1t8, nullptr, X8, F, T, D, 1};
-  EpiRelu2F8::Args ea{static_cast<uint8_t*>(H8), b1, F, zscale, sh};
+  EpiRelu2F8::Args ea{static_cast<uint8_t*>(H8), b1, F, zscale, sh, static_cast<__bf16*>(H16), static_cast<uint8_t*>(H8t), T};
   return launch_gemm<false, EpiRelu2F8, true>(g, ea, s);
 }
 
@@ -43,6 +44,19 @@ int launch_sp_colmajor_f8(const void* vals8, const uint8_t* meta, int a_panel, c
   GemmArgs g{vals8, meta, B8, M, N, K, a_panel, nullptr, b_panel};
   EpiColMajorScaled::Args ea{static_cast<__bf16*>(Ct), M, scale};
   return launch_gemm<true, EpiColMajorScaled, true>(g, ea, s);
+}
+
+int launch_dh_drelu_f8(const void* W2p8, const void* dY8, const void* H16, int T, int D, int F, float scale, float sdz, void* dZ8, void* dZ8t,
+                       hipStream_t s) {
+  GemmArgs g{W2p8, nullptr, dY8, F, T, D, 1};
+  EpiDReluF8::Args ea{static_cast<const __bf16*>(H16), static_cast<uint8_t*>(dZ8), static_cast<uint8_t*>(dZ8t), F, T, scale, sdz};
+  return launch_gemm<false, EpiDReluF8, true>(g, ea, s);
+}
+
+int launch_dense_colmajor_f8(const void* A8, int a_panel, const void* B8, int b_panel, int M, int N, int K, float scale, void* Ct, hipStream_t s) {
+  GemmArgs g{A8, nullptr, B8, M, N, K, a_panel, nullptr, b_panel};
+  EpiColMajorScaled::Args ea{static_cast<__bf16*>(Ct), M, scale};
+  return launch_gemm<false, EpiColMajorScaled, true>(g, ea, s);
 }
 
 // row-wise-scaled variants (scales per token for the activation operand, per output channel for the weight)

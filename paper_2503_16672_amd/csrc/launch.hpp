@@ -88,7 +88,13 @@ int launch_sp_colmajor_f8(const void* vals8, const uint8_t* meta, int a_panel, c
                           hipStream_t s);
 // feature-wise re-compression of the fp8 operands (all in the fp8 panel form): T, F multiples of 128
 int launch_featurewise24_f8(const void* Hc8, const uint8_t* meta, const void* dZc8, int T, int F, void* Hc8_t, uint8_t* meta_t, void* dZc8_t, hipStream_t s);
-int launch_up_relu2_f8(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, float zscale, float sh, void* H8, hipStream_t s);
+// H16, H8t (may be NULL): also the activation as bf16 [T][F] (dense bf16 panel form) and the codes transposed, [F][T] (dense fp8 panel form)
+int launch_up_relu2_f8(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, float zscale, float sh, void* H8, void* H16, void* H8t,
+                       hipStream_t s);
+// dense fp8 backward: dH GEMM with dZ8 = e4m3(scale * acc * 2 sqrt(h) / sdz) stored as [T][F] and [F][T]; transposing dense GEMM
+int launch_dh_drelu_f8(const void* W2p8, const void* dY8, const void* H16, int T, int D, int F, float scale, float sdz, void* dZ8, void* dZ8t,
+                       hipStream_t s);
+int launch_dense_colmajor_f8(const void* A8, int a_panel, const void* B8, int b_panel, int M, int N, int K, float scale, void* Ct, hipStream_t s);
 int launch_sp_rowmajor_f8(const void* vals8, const uint8_t* meta, int a_panel, const void* B8, int b_panel, int M, int N, int K, float scale, void* C, hipStream_t s);
 int launch_dense_rowmajor_f8(const void* A8, int a_panel, const void* B8, int b_panel, int M, int N, int K, float scale, void* C, hipStream_t s);
 // row-wise-scaled fp8 forward: sx [T], sw1 [F], sw2 [N]; the up-projection writes bf16 kept values (bf16 panel form)

@@ -65,7 +65,7 @@ def test_argument_validation_without_gpu():
     # context: shape and dtype rules are checked before any allocation
     h = ctypes.c_void_p()
     assert L.ffn24_ctx_create(ctypes.byref(h), 100, 512, 2048, 0, 0) == -2
-    assert L.ffn24_ctx_create(ctypes.byref(h), 256, 512, 2048, 1, 1 | 2) == -4   # fp8 training: the 2:4 path only, no dense baseline
+    assert L.ffn24_ctx_create(ctypes.byref(h), 256, 512, 2048, 1, 1 | 8) == -4   # fp8 training: no split
     assert L.ffn24_ctx_create(ctypes.byref(h), 256, 512, 2048, 1, 1 | 16) == -4  # ... and per-tensor scales only
     assert L.ffn24_ctx_create(ctypes.byref(h), 256, 512, 2048, 2, 0) == -4
     assert L.ffn24_set_scales(None, 1.0, 1.0, 1.0, 1.0) == -1

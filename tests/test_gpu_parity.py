@@ -819,6 +819,77 @@ def _fp8_bwd_case(F24, T, D, Fh, sparsity, seed, rows=None, gsel=None):
     ctx.close()
 
 
+def _fp8_dense_bwd_case(F24, T, D, Fh, sparsity, seed, rows=None, fsel=None):
+    """The dense fp8 baseline, forward + backward: every GEMM on the GPU's own stored codes (staged), and everything from
+    the raw inputs against the oracle's dense fp8 forward / backward (derivative by the definition)."""
+    big = T * Fh > (1 << 24)
+    if big:
+        w8 = synth.make_inputs_fp8(T, D, Fh, sparsity, seed)
+        inp = {"b1": w8["b1"]}; sc = {k: w8[k] for k in ("sx", "sw1", "sw2", "sh")}; q = {k: w8[k] for k in ("X", "W1", "W2")}
+    else:
+        inp, sc, q = _fp8_inputs(T, D, Fh, sparsity, seed)
+    dY = np.random.default_rng(seed).standard_normal((T, D)).astype(np.float32)
+    sc["sdy"] = float(np.abs(dY).max() / 448.0)
+    q["dY"] = torch.from_numpy(dY / np.float32(sc["sdy"])).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    cal_f = O.ffn_fwd_fp8_codes(q["X"][:64], q["W1"], inp["b1"], q["W2"], sc["sx"], sc["sw1"], sc["sh"], sc["sw2"])
+    cal = O.ffn_bwd_fp8_codes(cal_f, q["X"][:64], q["W1"], q["W2"], q["dY"][:64], sc["sx"], sc["sw1"], sc["sh"], sc["sw2"], sc["sdy"], 1.0, quantise_dz=False)
+    sc["sdz"] = float(0.8 * np.abs(cal["dZ"]).max() / 448.0)
+    d = {k: torch.from_numpy(q[k]).cuda() for k in q}
+    b1 = torch.from_numpy(inp["b1"]).cuda()
+    ctx = F24.Context(T, D, Fh, F24.FFN24_TRAINING | F24.FFN24_DENSE, dtype=F24.FFN24_FP8_E4M3)
+    ctx.set_scales(sc["sx"], sc["sw1"], sc["sh"], sc["sw2"])
+    ctx.set_bwd_scales(sc["sdy"], sc["sdz"])
+    Y = ctx.ffn_fwd(d["X"], d["W1"], b1, d["W2"])
+    dX, dW1, dW2 = ctx.ffn_bwd(d["dY"])
+    torch.cuda.synchronize()
+    rsel = np.arange(T) if rows is None else rows
+    fs = np.arange(Fh) if fsel is None else fsel
+    rs_t, fs_t = torch.from_numpy(rsel).cuda(), torch.from_numpy(fs).cuda()
+    H8_all, dZ8_all = ctx.saved("H_dense"), ctx.saved("dZ_dense")
+    torch.cuda.synchronize()
+    scales = (sc["sx"], sc["sw1"], sc["sh"], sc["sw2"], sc["sdy"], sc["sdz"])
+    dec = lambda b: O.e4m3_bits_to_f32(b).astype(np.float64)
+    # token rows: Y, dZ codes, dX
+    H8 = H8_all[rs_t].cpu().numpy(); dZ8 = dZ8_all[rs_t].cpu().numpy()
+    f_raw = O.ffn_fwd_fp8_codes(q["X"][rsel], q["W1"], inp["b1"], q["W2"], sc["sx"], sc["sw1"], sc["sh"], sc["sw2"])
+    g_raw = O.ffn_bwd_fp8_codes(f_raw, q["X"][rsel], q["W1"], q["W2"], q["dY"][rsel], *scales)
+    e_y = O.max_rel_err(f64(Y[rs_t]), f_raw["Y"])
+    h_agree = float(np.mean(H8 == f_raw["H8_bits"])); z_agree = float(np.mean(dZ8 == g_raw["dZ8_bits"]))
+    e_dz = O.fro_rel_err(dec(dZ8), dec(g_raw["dZ8_bits"]))
+    dx_st = dec(dZ8) @ dec(q["W1"]).T * (sc["sdz"] * sc["sw1"])
+    e_dx_st = O.max_rel_err(f64(dX[rs_t]), dx_st); e_dx = O.max_rel_err(f64(dX[rs_t]), g_raw["dX"]); r_dx = O.row_rel_err(f64(dX[rs_t]), g_raw["dX"])
+    print(f"  fp8 dense bwd rows: Y {e_y:.2e}  H8 codes equal {h_agree:.4f}  dZ8 codes equal {z_agree:.4f} (Frobenius {e_dz:.2e})  "
+          f"dX staged {e_dx_st:.2e}  dX from raw inputs {e_dx:.2e} (row {r_dx:.2e})", flush=True)
+    assert max(e_y, e_dz, e_dx_st, e_dx, r_dx) <= TOL_FP8 and h_agree >= 0.99 and z_agree >= 0.97
+    assert (np.abs(dec(dZ8)) == 448).any()
+    # hidden features over all tokens: dW2, dW1
+    H8_f = H8_all[:, fs_t].cpu().numpy(); dZ8_f = dZ8_all[:, fs_t].cpu().numpy()
+    dYv, Xv = dec(q["dY"]), dec(q["X"])
+    dW2_st = dec(H8_f).T @ dYv * (sc["sh"] * sc["sdy"]); dW1_st = Xv.T @ dec(dZ8_f) * (sc["sx"] * sc["sdz"])
+    f_f = O.ffn_fwd_fp8_codes(q["X"], q["W1"][:, fs], inp["b1"][fs], q["W2"][fs], sc["sx"], sc["sw1"], sc["sh"], sc["sw2"])
+    g_f = O.ffn_bwd_fp8_codes(f_f, q["X"], q["W1"][:, fs], q["W2"][fs], q["dY"], *scales)
+    errs = {"dW2 staged": O.max_rel_err(f64(dW2[fs_t]), dW2_st), "dW1 staged": O.max_rel_err(f64(dW1[:, fs_t]), dW1_st),
+            "dW2": O.max_rel_err(f64(dW2[fs_t]), g_f["dW2"]), "dW1": O.max_rel_err(f64(dW1[:, fs_t]), g_f["dW1"]),
+            "dW2 row": O.row_rel_err(f64(dW2[fs_t]), g_f["dW2"])}
+    print("  fp8 dense bwd features:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    assert max(errs.values()) <= TOL_FP8
+    ctx.close()
+
+
+def test_ffn_dense_bwd_fp8_small(F24):
+    print("fp8 dense fwd+bwd T=512 D=512 F=1280", flush=True)
+    _fp8_dense_bwd_case(F24, 512, 512, 1280, 0.85, seed=64)
+
+
+@pytest.mark.timeout(900)
+def test_ffn_dense_bwd_fp8_full_size_sampled(F24):
+    w = synth.WORKLOADS["c5"]
+    print(f"fp8 dense fwd+bwd full size c5 T={w.T} D={w.D} F={w.F}", flush=True)
+    rng = np.random.default_rng(47)
+    _fp8_dense_bwd_case(F24, w.T, w.D, w.F, w.sparsity, seed=w.seed, rows=np.sort(rng.choice(w.T, 64, replace=False)),
+                        fsel=np.sort(rng.choice(w.F, 48, replace=False)))
+
+
 def test_ffn24_bwd_fp8_small(F24):
     print("fp8 fwd+bwd T=256 D=512 F=2048", flush=True)
     _fp8_bwd_case(F24, 256, 512, 2048, 0.90, seed=61)
@@ -841,7 +912,7 @@ def test_ffn24_bwd_fp8_full_size_sampled(F24):
 
 
 def test_fp8_context_rules(F24):
-    for extra in (F24.FFN24_DENSE, F24.FFN24_ROWWISE):      # fp8 training is the per-tensor 2:4 path only
+    for extra in (F24.FFN24_SPLIT, F24.FFN24_ROWWISE):      # fp8 training: per-tensor scales, no split
         with pytest.raises(F24.Ffn24Error) as e:
             F24.Context(256, 256, 256, F24.FFN24_TRAINING | extra, dtype=F24.FFN24_FP8_E4M3)
         assert e.value.code == -4
