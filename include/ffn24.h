@@ -199,7 +199,8 @@ FFN24_API int ffn24_fwd(ffn24_ctx* ctx, const void* X, const void* W1, const flo
  * All calls on one GPU share that GPU's buffer: two calls whose work overlaps in time on one GPU (different streams,
  * or different threads) race on it.  Calls on one stream are ordered and safe.  Nothing in the buffer has to start at
  * zero -- each call writes every byte it later reads -- so it is never cleared.  Inference only: nothing is kept for
- * a backward pass. */
+ * a backward pass.  The first call on a device looks up the buffer's address and sets kernel attributes: make one call
+ * before recording calls into a graph. */
 #define FFN24_STATIC_SCRATCH_BYTES (64u << 20)
 FFN24_API int64_t ffn24_static_scratch_needed(int64_t T, int64_t D, int64_t F);   /* bytes, or -1 for sizes out of range */
 FFN24_API int ffn24_fwd_static(const void* X, const void* W1, const float* b1, const void* W2, void* Y, int64_t T, int64_t D, int64_t F,
