@@ -151,6 +151,11 @@ def run_probe(args) -> int:
             r = ffn24.probe_gemm(sparse, v, M, N, K)
             rows[vname] = {"ms": round(r["ms"], 4), "mhz": round(r["mhz"]), "tflops_dense_equivalent": round(2.0 * M * N * K / (r["ms"] * 1e-3) / 1e12, 1)}
         out["gemm_decomposition"][label] = rows
+    # the same loop under other tile walks (rocprofv3 --pmc FETCH_SIZE on this command gives each walk's L2 fills: the
+    # kernels differ in their last template argument)
+    out["tile_walks"] = {}
+    for label, sparse, (M, N, K) in (("sparse_down", True, (T, D, F)), ("dense_up", False, (F, T, D))):
+        out["tile_walks"][label] = {wname: round(ffn24.probe_gemm(sparse, v, M, N, K)["ms"], 4) for wname, v in ffn24.GEMM_PROBE_WALKS.items()}
     nbytes = 1 << 30
     ms = ffn24.probe_copy(nbytes)
     out["copy_1GiB"] = {"ms": round(ms, 4), "GBps_read_plus_write": round(2 * nbytes / (ms * 1e-3) / 1e9, 1)}

@@ -86,6 +86,11 @@ constexpr int PROBE_NO_DMA = 1;      // no global->LDS DMA is issued (the matrix
 constexpr int PROBE_NO_MFMA = 2;     // no matrix ops
 constexpr int PROBE_NO_FRAG = 4;     // no LDS fragment reads
 constexpr int PROBE_K_WRAP = 8;      // the K stages walk round the first 8 stages of the operands: every line is an L2 hit
+// other tile walks (the product's is a 4 x 2 grid of 8 x 4 patches), to measure what the walk does to time and to L2 fills:
+constexpr int PROBE_WALK_BANDS = 16;   // bands of 8 tile-rows, each XCD a contiguous run of tiles (the fallback walk, always)
+constexpr int PROBE_WALK_8x1 = 32;     // the 8 patches of a round side by side along M
+constexpr int PROBE_PATCH_4x8 = 64;    // per-XCD patches of 4 x 8 tiles
+constexpr int PROBE_PATCH_16x2 = 128;  // per-XCD patches of 16 x 2 tiles
 
 // B panel form: the dense panel form (64-byte pieces, a24_piece) whose rows are, inside every block of 256, stored in the
 // order the block tile keeps them in LDS: position q of a block holds row unperm_n(q), i.e. row n sits at b_panel_pos(n).
@@ -351,9 +356,12 @@ __device__ __forceinline__ void mfma_sparse1(const FragS& f, const IdxWords<F8> 
 // the others find in the memory-side cache.  Measured against one 8 x 4 patch per XCD with all XCDs side by side
 // along M (every round then streams the whole A operand): 3.5 % on the sparse GEMMs, nothing on the dense ones.
 // Shapes that the grid does not divide fall back to bands of 8 tile-rows, each XCD a contiguous run of tiles.
+template <int PROBE = 0>
 __device__ __forceinline__ void tile_coords(int ntm, int ntn, int pid, int& tm, int& tn) {
-  constexpr int GX = 4, GY = 2, PM = 8, PN = 4;   // XCD grid, patch shape; GX * GY = 8 XCDs, PM * PN = 32 CUs
-  if (ntm % (PM * GX) == 0 && ntn % (PN * GY) == 0) {
+  // XCD grid, patch shape; GX * GY = 8 XCDs, PM * PN = 32 CUs
+  constexpr int GX = (PROBE & PROBE_WALK_8x1) ? 8 : 4, GY = 8 / GX;
+  constexpr int PM = (PROBE & PROBE_PATCH_4x8) ? 4 : ((PROBE & PROBE_PATCH_16x2) ? 16 : 8), PN = 32 / PM;
+  if (!(PROBE & PROBE_WALK_BANDS) && ntm % (PM * GX) == 0 && ntn % (PN * GY) == 0) {
     const int xcd = pid & 7, idx = pid >> 3;
     const int round = idx >> 5, j = idx & 31;
     const int rounds_n = ntn / (PN * GY);
@@ -385,7 +393,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi:
   int tid = threadIdx.x;
   int lane = tid & 63, wave = tid >> 6;
   int tm, tn;
-  tile_coords(g.M / TILE_M, g.N / TILE_N, pid, tm, tn);
+  tile_coords<PROBE>(g.M / TILE_M, g.N / TILE_N, pid, tm, tn);
   int m0 = tm * TILE_M, n0 = tn * TILE_N;
 
   LaneCtx L;

@@ -210,6 +210,10 @@ int probe_gemm(int sparse, int variant, int M, int N, int K, int reps, double* m
     FFN24_PROBE_CASE(DF)
     FFN24_PROBE_CASE(PROBE_K_WRAP)
     FFN24_PROBE_CASE(WMF)
+    FFN24_PROBE_CASE(PROBE_WALK_BANDS)
+    FFN24_PROBE_CASE(PROBE_WALK_8x1)
+    FFN24_PROBE_CASE(PROBE_PATCH_4x8)
+    FFN24_PROBE_CASE(PROBE_PATCH_16x2)
     default: return 2;
   }
 #undef FFN24_PROBE_CASE

@@ -204,6 +204,8 @@ def probe_copy(nbytes: int, reps: int = 20) -> float:
     return ms.value
 
 
+GEMM_PROBE_WALKS = {"grid 4x2 of 8x4 patches (product)": 0, "bands of 8 tile-rows per XCD": 16, "8 patches side by side along M": 32,
+                    "4x8 patches": 64, "16x2 patches": 128}
 STATIC_SCRATCH_BYTES = 64 << 20
 
 
