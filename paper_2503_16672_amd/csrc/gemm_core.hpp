@@ -91,6 +91,7 @@ constexpr int PROBE_WALK_BANDS = 16;   // bands of 8 tile-rows, each XCD a conti
 constexpr int PROBE_WALK_8x1 = 32;     // the 8 patches of a round side by side along M
 constexpr int PROBE_PATCH_4x8 = 64;    // per-XCD patches of 4 x 8 tiles
 constexpr int PROBE_PATCH_16x2 = 128;  // per-XCD patches of 16 x 2 tiles
+constexpr int PROBE_UNPACED = 256;     // a stage's DMA instructions on consecutive matrix-op slots of its second K step
 
 // B panel form: the dense panel form (64-byte pieces, a24_piece) whose rows are, inside every block of 256, stored in the
 // order the block tile keeps them in LDS: position q of a block holds row unperm_n(q), i.e. row n sits at b_panel_pos(n).
@@ -385,6 +386,28 @@ __device__ __forceinline__ void tile_coords(int ntm, int ntn, int pid, int& tm, 
 //   m_lane = global row of acc[0][*][0] for this lane (its 64 rows are m_lane + 16*mi + v),
 //   n_lane = global column of acc[*][0][*] (its 4 columns are n_lane + ni).
 // One block tile of one GEMM: tile number `pid` of g (workgroup-uniform), LDS ring at `smem`.
+// Pacing of the DMA issue.  The four waves run in step, one per SIMD, and share one address unit that takes about
+// 14 cycles per 16-byte-a-lane DMA instruction; a matrix-op slot is 32 cycles.  When every wave hands over a DMA
+// instruction on every slot, the unit is oversubscribed (4 x 14 > 32), the waves stall in the issue and their matrix
+// pipes idle: measured per K step, the step that carries 14 DMA instructions on consecutive slots takes 1200 cycles
+// instead of 512.  So the instructions ride on every other slot only.  Dense (8 a stage): the even slots of the second
+// K step.  Sparse (13 or 14 a stage): the first half on the even slots of the second K step, the rest on the even slots of
+// the NEXT stage's first K step, still into the buffer that the stage before freed -- one stage buffer is therefore
+// half filled across a stage boundary, which costs nothing because the ring keeps NB - 2 whole stages in flight anyway.
+// dma_on_step1 / dma_on_step0: which DMA instruction rides on slot M of that K step (-1: none).
+template <int NDMA, bool SPREAD, bool PACED>
+constexpr int dma_on_step1(int M) {
+  constexpr int H1 = SPREAD ? NDMA / 2 : NDMA;
+  if (!PACED || 2 * H1 > 16) return M < H1 ? M : -1;
+  return (M % 2 == 0 && M / 2 < H1) ? M / 2 : -1;
+}
+template <int NDMA, bool SPREAD, bool PACED>
+constexpr int dma_on_step0(int M) {
+  constexpr int H1 = SPREAD ? NDMA / 2 : NDMA;
+  if (!SPREAD) return -1;
+  return (M % 2 == 0 && M / 2 < NDMA - H1) ? H1 + M / 2 : -1;
+}
+
 template <bool SPARSE, class Epi, bool F8 = false, int PROBE = 0>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi::Args& ea, char* smem, int pid) {
   using G = Geo<SPARSE, F8>;
@@ -437,16 +460,23 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi:
     IdxWords<F8> idx[4];
     static_for<4>([&](auto I) { load_idx_sparse1<F8, I>(smem, L, idx); });
     static_for<12>([&](auto I) { load_frag_sparse1<F8, 0, I, PROBE>(smem, L, f0); });
-    auto stage = [&](int kt, char* cur, char* nxt, auto mode) {
+    // sparse: spread the DMA of a stage over two K steps (see dma_on_step1) when there is a steady state at all
+    constexpr bool PACED = (PROBE & PROBE_UNPACED) == 0;
+    auto stage = [&](int kt, char* cur, char* nxt, char* prv, auto mode, auto spread) {
       constexpr int MODE = decltype(mode)::value;
+      constexpr bool SPREAD0 = decltype(spread)::value != 0;   // this stage's first K step carries the rest of stage kt-1+NB
       IdxWords<F8> idx_n[4] = {};
       FFN24_FENCE();
       static_for<16>([&](auto M) {
         mfma_sparse1<F8, 0, M, PROBE>(f0, idx, acc);
+        constexpr int J0 = dma_on_step0<NDMA, PACED, PACED>(M);
+        if constexpr (SPREAD0 && J0 >= 0) dma.template issue<(J0 >= 0 ? J0 : 0)>(kt - 1 + NB, prv);
         if constexpr (M < 12) load_frag_sparse1<F8, 1, M, PROBE>(cur, L, f1);
         FFN24_FENCE();
       });
       if constexpr (MODE != 2) {
+        // stage kt+1 must have landed; behind it in issue order are the NB - 2 stages kt+2 .. kt+NB-1, all of them whole
+        // (the rest of stage kt-1+NB went out just above)
         if constexpr (MODE == 0) wait_vmcnt<(NB - 2) * NDMA>(); else wait_vmcnt<0>();
         wait_lgkmcnt0();
         __builtin_amdgcn_s_barrier();
@@ -454,7 +484,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi:
       FFN24_FENCE();
       static_for<16>([&](auto M) {
         mfma_sparse1<F8, 1, M, PROBE>(f1, idx, acc);
-        if constexpr (MODE == 0 && M < NDMA) dma.template issue<M>(kt + NB, cur);
+        constexpr int J1 = dma_on_step1<NDMA, PACED, PACED>(M);
+        if constexpr (MODE == 0 && J1 >= 0) dma.template issue<(J1 >= 0 ? J1 : 0)>(kt + NB, cur);
         if constexpr (MODE != 2) {
           if constexpr (M < 4) load_idx_sparse1<F8, M>(nxt, L, idx_n);
           if constexpr (M < 12) load_frag_sparse1<F8, 0, M, PROBE>(nxt, L, f0);
@@ -465,15 +496,24 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi:
       for (int i = 0; i < 4; i++) idx[i] = idx_n[i];
     };
     int slot = 0;
-    auto advance = [&](int kt, auto mode) {
+    auto advance = [&](int kt, auto mode, auto spread) {
       int ns = slot + 1 == NB ? 0 : slot + 1;
-      stage(kt, smem + slot * G::STAGE, smem + ns * G::STAGE, mode);
+      int ps = slot == 0 ? NB - 1 : slot - 1;
+      stage(kt, smem + slot * G::STAGE, smem + ns * G::STAGE, smem + ps * G::STAGE, mode, spread);
       slot = ns;
     };
+    using I0 = std::integral_constant<int, 0>; using I1 = std::integral_constant<int, 1>; using I2 = std::integral_constant<int, 2>;
+    using SP = std::integral_constant<int, PACED ? 1 : 0>;
     int kt = 0;
-    for (; kt < nk - NB; kt++) advance(kt, std::integral_constant<int, 0>{});
-    for (; kt < nk - 1; kt++) advance(kt, std::integral_constant<int, 1>{});
-    advance(kt, std::integral_constant<int, 2>{});
+    if (nk > NB) {
+      // stage 0 issues the first half of stage NB; stages 1 .. nk-NB each issue the rest of what the stage before began,
+      // and all but the last of them the first half of their own
+      advance(kt, I0{}, I0{}); kt++;
+      for (; kt < nk - NB; kt++) advance(kt, I0{}, SP{});
+      if constexpr (PACED) { advance(kt, I1{}, I1{}); kt++; }
+    }
+    for (; kt < nk - 1; kt++) advance(kt, I1{}, I0{});
+    advance(kt, I2{}, I0{});
   } else if constexpr (F8) {
     // Dense fp8: a stage is ONE K step of 16 matrix ops (64 cycles each).  The fragments of the whole next stage and
     // the DMA of the stage that reuses this stage's buffer (its fragments are already in registers) ride on them;
@@ -541,7 +581,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi:
       FFN24_FENCE();
       static_for<16>([&](auto M) {
         mfma_dense1<M, PROBE>(f1, acc);
-        if constexpr (MODE == 0 && M < NDMA) dma.template issue<M>(kt + NB, cur);
+        constexpr int J1 = dma_on_step1<NDMA, false, (PROBE & PROBE_UNPACED) == 0>(M);
+        if constexpr (MODE == 0 && J1 >= 0) dma.template issue<(J1 >= 0 ? J1 : 0)>(kt + NB, cur);
         if constexpr (MODE != 2 && M < 8) load_frag_dense1<0, M, PROBE>(nxt, L, f0);
         FFN24_FENCE();
       });
