@@ -220,21 +220,35 @@ struct Dma {
   __device__ __forceinline__ void issue(int kt, char* buf) const {
     if constexpr ((PROBE & PROBE_NO_DMA) != 0) return;
     if constexpr ((PROBE & PROBE_K_WRAP) != 0) kt &= 7;
+    // The stage's uniform base goes through an opaque scalar register pair, so that the compiler keeps it apart from the
+    // lane's 32-bit offset and picks the instruction's scalar-base + 32-bit-offset form: no 64-bit vector add per
+    // instruction, one address register per instruction instead of two.
     if constexpr (J < 4) {
-      __builtin_amdgcn_global_load_lds((glb_char*)(a + (size_t)kt * a_stage + va[J]), (lds_char*)(buf + (4 * wave + J) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_char*)(sbase(a, kt, a_stage) + voff(va[J])), (lds_char*)(buf + (4 * wave + J) * 1024), 16, 0, 0);
     } else if constexpr (!SPARSE) {
       constexpr int j = J - 4;
-      __builtin_amdgcn_global_load_lds((glb_char*)(b + (size_t)kt * b_stage + vb[j]), (lds_char*)(buf + G::B_OFF + (4 * wave + j) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_char*)(sbase(b, kt, b_stage) + voff(vb[j])), (lds_char*)(buf + G::B_OFF + (4 * wave + j) * 1024), 16, 0, 0);
     } else if constexpr (J < 4 + G::NM) {
       constexpr int j = J - 4;
       if constexpr (F8)
-        __builtin_amdgcn_global_load_lds((glb_char*)(am + (size_t)kt * m_stage + vm[0]), (lds_char*)(buf + G::META_OFF + wave * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((glb_char*)(sbase(am, kt, m_stage) + voff(vm[0])), (lds_char*)(buf + G::META_OFF + wave * 1024), 16, 0, 0);
       else
-        __builtin_amdgcn_global_load_lds((glb_char*)(am + (size_t)kt * m_stage + vm[j]), (lds_char*)(buf + G::META_OFF + (2 * wave + j) * 256), 4, 0, 0);
+        __builtin_amdgcn_global_load_lds((glb_char*)(sbase(am, kt, m_stage) + voff(vm[j])), (lds_char*)(buf + G::META_OFF + (2 * wave + j) * 256), 4, 0, 0);
     } else {
       constexpr int j = J - 4 - G::NM;
-      __builtin_amdgcn_global_load_lds((glb_char*)(b + (size_t)kt * b_stage + vb[j]), (lds_char*)(buf + G::B_OFF + (8 * wave + j) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_char*)(sbase(b, kt, b_stage) + voff(vb[j])), (lds_char*)(buf + G::B_OFF + (8 * wave + j) * 1024), 16, 0, 0);
     }
+  }
+  static __device__ __forceinline__ const char* sbase(const char* base, int kt, uint32_t stage) {
+    const char* p = base + (size_t)kt * stage;
+    asm volatile("" : "+s"(p));
+    return p;
+  }
+  // (the offset is made opaque at the point of use too: hoisted out of the loop, its zero-extension would be out of the
+  // instruction selector's sight and the 64-bit form would come back)
+  static __device__ __forceinline__ uint32_t voff(uint32_t o) {
+    asm volatile("" : "+v"(o));
+    return o;
   }
   __device__ __forceinline__ void issue_all(int kt, char* buf) const {
     static_for<G::NDMA>([&](auto J) { issue<J>(kt, buf); });
