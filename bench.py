@@ -148,9 +148,21 @@ def run_probe(args) -> int:
                                      ("dense_up d_ff x T over d_model", False, (F, T, D))):
         rows = {}
         for vname, v in ffn24.GEMM_PROBE_VARIANTS.items():
+            if v == 512 and not sparse:
+                continue   # a sparse-loop variant
             r = ffn24.probe_gemm(sparse, v, M, N, K)
             rows[vname] = {"ms": round(r["ms"], 4), "mhz": round(r["mhz"]), "tflops_dense_equivalent": round(2.0 * M * N * K / (r["ms"] * 1e-3) / 1e12, 1)}
         out["gemm_decomposition"][label] = rows
+        # global->LDS fill of a CU: what one 1024-cycle stage of the loop needs (sparse: 16 KiB stored values + 2 KiB metadata +
+        # 32 KiB of B for 64 k; dense: 16 + 16 KiB for 32 k) against what the stream alone delivers when every line hits the L2
+        stage_bytes, stage_k = (51200, 64) if sparse else (32768, 32)
+        per_cu = (M // 256) * (N // 256) / 256.0 * (K // stage_k) * stage_bytes
+        alone = rows["dma_only_l2_hits"]
+        out.setdefault("lds_fill_bytes_per_clk_per_cu", {})[label] = {
+            "needed_at_full_matrix_rate": round(stage_bytes / 1024.0, 1),
+            "stream_alone_all_l2_hits": round(per_cu / (alone["ms"] * 1e-3 * alone["mhz"] * 1e6), 1),
+            "stream_alone_all_l2_hits_GBps_per_cu": round(per_cu / (alone["ms"] * 1e-3) / 1e9, 1),
+            "product_loop": round(per_cu / (rows["all"]["ms"] * 1e-3 * rows["all"]["mhz"] * 1e6), 1)}
     # the same loop under other tile walks (rocprofv3 --pmc FETCH_SIZE on this command gives each walk's L2 fills: the
     # kernels differ in their last template argument)
     out["tile_walks"] = {}

@@ -92,6 +92,8 @@ constexpr int PROBE_WALK_8x1 = 32;     // the 8 patches of a round side by side 
 constexpr int PROBE_PATCH_4x8 = 64;    // per-XCD patches of 4 x 8 tiles
 constexpr int PROBE_PATCH_16x2 = 128;  // per-XCD patches of 16 x 2 tiles
 constexpr int PROBE_UNPACED = 256;     // a stage's DMA instructions on consecutive matrix-op slots of its second K step
+constexpr int PROBE_FILL_LESS = 512;   // sparse: the last 3 of a wave's 14 DMA instructions of every stage are left out -- 38 KiB a stage
+                                       // instead of 50, about the bytes per matrix op of a 384 x 256 tile (what a taller tile could gain)
 
 // B panel form: the dense panel form (64-byte pieces, a24_piece) whose rows are, inside every block of 256, stored in the
 // order the block tile keeps them in LDS: position q of a block holds row unperm_n(q), i.e. row n sits at b_panel_pos(n).
@@ -249,9 +251,6 @@ struct Dma {
   static __device__ __forceinline__ uint32_t voff(uint32_t o) {
     asm volatile("" : "+v"(o));
     return o;
-  }
-  __device__ __forceinline__ void issue_all(int kt, char* buf) const {
-    static_for<G::NDMA>([&](auto J) { issue<J>(kt, buf); });
   }
 };
 
@@ -425,7 +424,7 @@ constexpr int dma_on_step0(int M) {
 template <bool SPARSE, class Epi, bool F8 = false, int PROBE = 0>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi::Args& ea, char* smem, int pid) {
   using G = Geo<SPARSE, F8>;
-  constexpr int NB = G::NB, NDMA = G::NDMA;
+  constexpr int NB = G::NB, NDMA = G::NDMA - ((SPARSE && (PROBE & PROBE_FILL_LESS)) ? 3 : 0);
 
   int tid = threadIdx.x;
   int lane = tid & 63, wave = tid >> 6;
@@ -461,7 +460,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi:
   const int nk = g.K / G::BK;
   // prologue: stages 0 .. min(NB, nk)-1 into their ring slots; wait for stage 0 only
   const int npro = nk < NB ? nk : NB;
-  for (int s = 0; s < npro; s++) dma.issue_all(s, smem + s * G::STAGE);
+  for (int s = 0; s < npro; s++) static_for<NDMA>([&](auto J) { dma.template issue<J>(s, smem + s * G::STAGE); });
   if (npro == NB) wait_vmcnt<(NB - 1) * NDMA>(); else wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
   FFN24_FENCE();

@@ -215,6 +215,7 @@ int probe_gemm(int sparse, int variant, int M, int N, int K, int reps, double* m
     FFN24_PROBE_CASE(PROBE_PATCH_4x8)
     FFN24_PROBE_CASE(PROBE_PATCH_16x2)
     FFN24_PROBE_CASE(PROBE_UNPACED)
+    FFN24_PROBE_CASE(PROBE_FILL_LESS)
     default: return 2;
   }
 #undef FFN24_PROBE_CASE
