@@ -286,7 +286,8 @@ FFN24_API int ffn24_kernel_mhz(ffn24_ctx* ctx, int kernel, float* mhz);
  *     another tile walk: 16 bands of 8 tile-rows per XCD, 32 the 8 per-XCD patches of a round side by side along M,
  *     64 patches of 4 x 8 tiles, 128 patches of 16 x 2 tiles (the product: a 4 x 2 grid of 8 x 4 patches); or, 256, with a
  *     stage's DMA instructions on consecutive matrix-op slots (the product issues them on every other slot); or, 512 (sparse only),
- *     with a quarter of every stage's operand bytes not fetched.  Returns the median
+ *     with a quarter of every stage's operand bytes not fetched; or, 1024, as 256 persistent workgroups that walk the tiles and ask
+ *     for a tile's first stages before the epilogue of the tile before.  Returns the median
  *     kernel duration over `reps` launches and the clock it ran at.  Variants other than 0 compute nothing meaningful.
  *   ffn24_probe_copy: a plain device-to-device copy kernel of `bytes` bytes (a multiple of 4096): median duration. */
 FFN24_API int ffn24_probe_mfma_rate(int kind, int iters, double* cycles_per_op, double* mhz, double* tflops_dense_equivalent);

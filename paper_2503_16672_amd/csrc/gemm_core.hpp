@@ -92,6 +92,8 @@ constexpr int PROBE_WALK_8x1 = 32;     // the 8 patches of a round side by side 
 constexpr int PROBE_PATCH_4x8 = 64;    // per-XCD patches of 4 x 8 tiles
 constexpr int PROBE_PATCH_16x2 = 128;  // per-XCD patches of 16 x 2 tiles
 constexpr int PROBE_UNPACED = 256;     // a stage's DMA instructions on consecutive matrix-op slots of its second K step
+constexpr int PROBE_PERSIST = 1024;    // one workgroup per CU walks the tiles id, id + grid, ...; the next tile's first stages are asked for
+                                       // before the epilogue of the present one
 constexpr int PROBE_FILL_LESS = 512;   // sparse: the last 3 of a wave's 14 DMA instructions of every stage are left out -- 38 KiB a stage
                                        // instead of 50, about the bytes per matrix op of a 384 x 256 tile (what a taller tile could gain)
 
@@ -422,9 +424,10 @@ constexpr int dma_on_step0(int M) {
 }
 
 template <bool SPARSE, class Epi, bool F8 = false, int PROBE = 0>
-__device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi::Args& ea, char* smem, int pid) {
+__device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi::Args& ea, char* smem, int pid, int pid_end = 0, int pid_step = 0) {
   using G = Geo<SPARSE, F8>;
   constexpr int NB = G::NB, NDMA = G::NDMA - ((SPARSE && (PROBE & PROBE_FILL_LESS)) ? 3 : 0);
+  constexpr bool PERSIST = (PROBE & PROBE_PERSIST) != 0;
 
   int tid = threadIdx.x;
   int lane = tid & 63, wave = tid >> 6;
@@ -443,6 +446,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi:
   Dma<SPARSE, F8, PROBE> dma;
   dma.init(g, m0, n0, tid);
 
+  const int nk = g.K / G::BK;
+  // prologue: stages 0 .. min(NB, nk)-1 into their ring slots; wait for stage 0 only
+  const int npro = nk < NB ? nk : NB;
+  for (int s = 0; s < npro; s++) static_for<NDMA>([&](auto J) { dma.template issue<J>(s, smem + s * G::STAGE); });
+  bool first = true;
+
+  for (;;) {   // one pass per tile (PERSIST: several tiles per workgroup)
   f32x16 acc[4][4];
 #pragma unroll
   for (int i = 0; i < 4; i++)
@@ -457,11 +467,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi:
 #pragma unroll
     for (int j = 0; j < 4; j++) asm volatile("" : "+a"(acc[i][j]));
 
-  const int nk = g.K / G::BK;
-  // prologue: stages 0 .. min(NB, nk)-1 into their ring slots; wait for stage 0 only
-  const int npro = nk < NB ? nk : NB;
-  for (int s = 0; s < npro; s++) static_for<NDMA>([&](auto J) { dma.template issue<J>(s, smem + s * G::STAGE); });
-  if (npro == NB) wait_vmcnt<(NB - 1) * NDMA>(); else wait_vmcnt<0>();
+  // a later tile's prologue went out before the previous epilogue, whose stores count in the same counter and complete in no
+  // fixed order with the loads: wait for all of it
+  if (first && npro == NB) wait_vmcnt<(NB - 1) * NDMA>(); else wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
   FFN24_FENCE();
 
@@ -625,7 +633,26 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi:
   }
   int m_lane = m0 + L.wy * 128 + 64 * L.h;
   int n_lane = n0 + L.wx * 128 + 4 * L.rho;
-  Epi::run(ea, acc, m_lane, n_lane);
+  if constexpr (PERSIST) {
+    pid += pid_step;
+    const bool more = pid < pid_end;
+    if (more) {
+      // every wave has read its last fragments: the ring is free for the next tile's first stages, which then land while
+      // the epilogue runs
+      __builtin_amdgcn_s_barrier();
+      tile_coords<PROBE>(g.M / TILE_M, g.N / TILE_N, pid, tm, tn);
+      m0 = tm * TILE_M; n0 = tn * TILE_N;
+      dma.init(g, m0, n0, tid);
+      for (int s = 0; s < npro; s++) static_for<NDMA>([&](auto J) { dma.template issue<J>(s, smem + s * G::STAGE); });
+    }
+    Epi::run(ea, acc, m_lane, n_lane);
+    if (!more) break;
+    first = false;
+  } else {
+    Epi::run(ea, acc, m_lane, n_lane);
+    break;
+  }
+  }   // tiles
 }
 
 // Clock sample of a workgroup (profiling only): ticks of the shader clock and of the constant 100 MHz clock between its
@@ -649,7 +676,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(GemmArgs g, typename
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   ClkSample cs;
   cs.begin(g);
-  gemm_tile<SPARSE, Epi, F8, PROBE>(g, ea, smem, blockIdx.x);
+  gemm_tile<SPARSE, Epi, F8, PROBE>(g, ea, smem, blockIdx.x, (g.M / TILE_M) * (g.N / TILE_N), gridDim.x);
   cs.end(g);
 }
 

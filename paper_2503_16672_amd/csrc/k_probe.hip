@@ -216,6 +216,7 @@ int probe_gemm(int sparse, int variant, int M, int N, int K, int reps, double* m
     FFN24_PROBE_CASE(PROBE_PATCH_16x2)
     FFN24_PROBE_CASE(PROBE_UNPACED)
     FFN24_PROBE_CASE(PROBE_FILL_LESS)
+    FFN24_PROBE_CASE(PROBE_PERSIST)
     default: return 2;
   }
 #undef FFN24_PROBE_CASE

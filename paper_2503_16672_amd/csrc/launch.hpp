@@ -26,7 +26,8 @@ inline int ensure_dynamic_lds(const void* kern, int bytes, std::atomic<bool> (&d
 // Where the GEMM launches of the calling thread store their clock samples (gemm_core.hpp, GemmArgs::clk): set by the
 // C-ABI layer around a launch when the context profiles, NULL otherwise.
 inline thread_local unsigned long long* tl_gemm_clk = nullptr;
-constexpr int CLK_SLOTS = 64;   // workgroups of a launch that store a clock sample (a pair of 64-bit counts each)
+constexpr int CLK_SLOTS = 64;
+constexpr int PERSIST_WORKGROUPS = 256;   // one per CU of the chip (gfx950: 256 CUs; a 256 x 256 tile's registers and LDS fill a CU)   // workgroups of a launch that store a clock sample (a pair of 64-bit counts each)
 
 // Telemetry counters (the sparsity level of the activation and what 2:4 keeps of it): TELE_SLOTS 64-bit slots per
 // quantity, each in a 128-byte line of its own and summed when read, so that the atomics of a launch spread over many

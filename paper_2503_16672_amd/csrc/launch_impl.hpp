@@ -14,6 +14,7 @@ static int launch_gemm(const GemmArgs& g_in, const typename Epi::Args& ea, hipSt
   static std::atomic<bool> configured[MAX_DEVICES] = {};
   if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds, configured)) return rc;
   int nblocks = (g.M / TILE_M) * (g.N / TILE_N);
+  if constexpr ((PROBE & PROBE_PERSIST) != 0) nblocks = nblocks < PERSIST_WORKGROUPS ? nblocks : PERSIST_WORKGROUPS;
   hipLaunchKernelGGL(kern, dim3(nblocks), dim3(GEMM_THREADS), lds, s, g, ea);
   return (int)hipGetLastError();
 }

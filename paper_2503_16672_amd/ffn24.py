@@ -181,7 +181,8 @@ def spmm24(values: torch.Tensor, meta: torch.Tensor, Bt: torch.Tensor) -> torch.
 
 MFMA_KINDS = ("dense bf16 32x32x16", "sparse bf16 32x32x32", "dense fp8 32x32x64", "sparse fp8 32x32x64")
 GEMM_PROBE_VARIANTS = {"all": 0, "no_dma": 1, "no_fragment_reads": 4, "dma_only": 6, "mfma_only": 5, "all_l2_hits": 8, "dma_only_l2_hits": 14,
-                       "all_dma_issue_unpaced": 256, "all_quarter_less_fill": 512}
+                       "all_dma_issue_unpaced": 256, "all_quarter_less_fill": 512,
+                       "all_persistent_workgroups": 1024}
 
 
 def probe_mfma_rate(kind: int, iters: int = 20000) -> dict:
