@@ -104,9 +104,11 @@ __global__ void __launch_bounds__(256) probe_fill_kernel(uint32_t* p, size_t n, 
   }
 }
 
+// The fastest plain copy found on this chip: one 16-byte piece per work item, as many workgroups as that takes, loads and
+// stores with the non-temporal hint (6.0-6.5 TB/s read + written; a grid-stride loop over 8192 workgroups: 4.5-4.7).
 __global__ void __launch_bounds__(256) probe_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n) {
-  size_t st = (size_t)gridDim.x * blockDim.x;
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += st) dst[i] = src[i];
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
 double median_of(std::vector<float>& v) {
@@ -229,7 +231,7 @@ int probe_copy(size_t bytes, int reps, double* ms_median) {
   const size_t n = bytes / 16;
   std::vector<hipEvent_t> ev(reps + 1);
   for (auto& e : ev) if (hipEventCreate(&e) != hipSuccess) return 1;
-  auto launch = [&]() { hipLaunchKernelGGL(probe_copy_kernel, dim3(256 * 32), dim3(256), 0, nullptr, static_cast<const u32x4*>(src.p), static_cast<u32x4*>(dst.p), n); };
+  auto launch = [&]() { hipLaunchKernelGGL(probe_copy_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, nullptr, static_cast<const u32x4*>(src.p), static_cast<u32x4*>(dst.p), n); };
   launch();
   (void)hipEventRecord(ev[0], nullptr);
   for (int i = 0; i < reps; i++) { launch(); (void)hipEventRecord(ev[i + 1], nullptr); }

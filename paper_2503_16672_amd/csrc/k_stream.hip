@@ -6,6 +6,11 @@
 
 namespace ffn24 {
 
+// Streaming accesses: every byte these kernels touch is read or written once, so loads and stores carry the non-temporal
+// hint (measured on a plain copy: 6.0-6.5 TB/s with it, 5.6-6.1 without).
+template <class T> __device__ __forceinline__ T ld_stream(const T* p) { return __builtin_nontemporal_load(p); }
+template <class T> __device__ __forceinline__ void st_stream(T* p, T v) { __builtin_nontemporal_store(v, p); }
+
 // key of a bf16 storage word at position i of its group: ((magnitude << 2) | (3 - i)) << 1 | sign.
 // The sign rides in the lowest bit, below the position, so it never takes part in the ordering.
 __device__ __forceinline__ uint32_t key_of(uint32_t w, uint32_t i) { return ((((w & 0x7FFFu) << 2) | (3u - i)) << 1) | (w >> 15); }
@@ -33,12 +38,12 @@ __global__ void __launch_bounds__(256) sparsify24_kernel(const u32x4* __restrict
                                                          u32x2* __restrict__ vals, uint8_t* __restrict__ meta) {
   int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < n_oct; o += stride) {
-    u32x4 v = in[o];
+    u32x4 v = ld_stream(in + o);
     uint32_t p0, p1;
     uint32_t n0 = pick24_words(v[0] & 0xFFFFu, v[0] >> 16, v[1] & 0xFFFFu, v[1] >> 16, p0);
     uint32_t n1 = pick24_words(v[2] & 0xFFFFu, v[2] >> 16, v[3] & 0xFFFFu, v[3] >> 16, p1);
-    vals[o] = u32x2{p0, p1};
-    meta[o] = (uint8_t)(n0 | (n1 << 4));
+    st_stream(vals + o, u32x2{p0, p1});
+    st_stream(meta + o, (uint8_t)(n0 | (n1 << 4)));
   }
 }
 
@@ -49,14 +54,14 @@ __global__ void __launch_bounds__(256) sparsify24_quant_kernel(const u32x4* __re
                                                                uint32_t* __restrict__ vals8, uint8_t* __restrict__ meta) {
   int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < n_oct; o += stride) {
-    u32x4 v = in[o];
+    u32x4 v = ld_stream(in + o);
     uint32_t p0, p1;
     uint32_t n0 = pick24_words(v[0] & 0xFFFFu, v[0] >> 16, v[1] & 0xFFFFu, v[1] >> 16, p0);
     uint32_t n1 = pick24_words(v[2] & 0xFFFFu, v[2] >> 16, v[3] & 0xFFFFu, v[3] >> 16, p1);
     uint32_t q = cvt_e4m3x2(bf16_lo_to_f32(p0) / scale, bf16_hi_to_f32(p0) / scale, 0u, false);
     q = cvt_e4m3x2(bf16_lo_to_f32(p1) / scale, bf16_hi_to_f32(p1) / scale, q, true);
-    vals8[o] = q;
-    meta[o] = (uint8_t)(n0 | (n1 << 4));
+    st_stream(vals8 + o, q);
+    st_stream(meta + o, (uint8_t)(n0 | (n1 << 4)));
   }
 }
 
@@ -66,7 +71,7 @@ __global__ void __launch_bounds__(256) sparsify24_bytes_kernel(const u32x4* __re
                                                                u32x2* __restrict__ vals8, uint16_t* __restrict__ meta) {
   int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < n16; o += stride) {
-    u32x4 v = in[o];
+    u32x4 v = ld_stream(in + o);
     uint32_t out[2] = {0u, 0u}, m = 0u;
 #pragma unroll
     for (int g = 0; g < 4; g++) {
@@ -80,8 +85,8 @@ __global__ void __launch_bounds__(256) sparsify24_bytes_kernel(const u32x4* __re
       out[g >> 1] |= (a | (b << 8)) << (16 * (g & 1));
       m |= nib << (4 * g);
     }
-    vals8[o] = u32x2{out[0], out[1]};
-    meta[o] = (uint16_t)m;
+    st_stream(vals8 + o, u32x2{out[0], out[1]});
+    st_stream(meta + o, (uint16_t)m);
   }
 }
 
@@ -89,7 +94,7 @@ int launch_sparsify24_quant(const void* H, int64_t rows, int64_t cols, float sca
   int64_t n_oct = rows * cols / 8;
   if (n_oct == 0) return 0;
   int64_t blocks = (n_oct + 255) / 256;
-  if (blocks > 256 * 32) blocks = 256 * 32;
+  if (blocks > 0x7FFFFFFF) blocks = 0x7FFFFFFF;   // one work item per thread: the fastest shape for a streaming kernel here
   hipLaunchKernelGGL(sparsify24_quant_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const u32x4*>(H), n_oct, scale,
                      static_cast<uint32_t*>(vals8), meta);
   return (int)hipGetLastError();
@@ -99,7 +104,7 @@ int launch_sparsify24_bytes(const void* H8, int64_t rows, int64_t cols, void* va
   int64_t n16 = rows * cols / 16;
   if (n16 == 0) return 0;
   int64_t blocks = (n16 + 255) / 256;
-  if (blocks > 256 * 32) blocks = 256 * 32;
+  if (blocks > 0x7FFFFFFF) blocks = 0x7FFFFFFF;   // one work item per thread: the fastest shape for a streaming kernel here
   hipLaunchKernelGGL(sparsify24_bytes_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const u32x4*>(H8), n16,
                      static_cast<u32x2*>(vals8), reinterpret_cast<uint16_t*>(meta));
   return (int)hipGetLastError();
@@ -109,7 +114,7 @@ int launch_sparsify24(const void* H, int64_t rows, int64_t cols, void* vals, uin
   int64_t n_oct = rows * cols / 8;
   if (n_oct == 0) return 0;
   int64_t blocks = (n_oct + 255) / 256;
-  if (blocks > 256 * 32) blocks = 256 * 32;
+  if (blocks > 0x7FFFFFFF) blocks = 0x7FFFFFFF;   // one work item per thread: the fastest shape for a streaming kernel here
   hipLaunchKernelGGL(sparsify24_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const u32x4*>(H), n_oct,
                      static_cast<u32x2*>(vals), meta);
   return (int)hipGetLastError();
@@ -119,11 +124,12 @@ int launch_sparsify24(const void* H, int64_t rows, int64_t cols, void* vals, uin
 // Input: token-wise compressed Hc [T][F/2] + meta [T][F/8], and optionally dZc [T][F/2] with the same metadata.
 // Output: for every feature, groups of 4 consecutive tokens of the pruned activation keep their top-2:
 //   Hc_t [F][T/2], meta_t [F][T/8], and dZc_t [F][T/2] = dZ at the positions picked for H.
-// One workgroup handles 128 tokens x 64 features: decompress into LDS, then each work item takes one feature
+// One workgroup handles 64 tokens x 64 features: decompress into LDS, then each work item takes one feature
 // and 8 consecutive tokens (two groups).  PANEL: inputs and outputs are in the panel form of gemm_core.hpp (the
-// workgroup's input is then one contiguous 8 KiB run per tensor and it writes two contiguous 4 KiB runs); otherwise
-// row-major, where a feature row's outputs are written 128 bytes at a time.
-constexpr int FW_TOK = 128, FW_FEAT = 64, FW_LD = FW_FEAT + 2;
+// workgroup's input is then one contiguous 4 KiB run per tensor and it writes one contiguous 4 KiB run; 128-token tiles, with
+// twice the LDS per workgroup and half the workgroups per CU, ran at 5.0 instead of 5.9 TB/s); otherwise
+// row-major, where a feature row's outputs are written 64 bytes at a time.
+constexpr int FW_TOK = 64, FW_FEAT = 64, FW_LD = FW_FEAT + 2;
 
 // SPLIT (Sec. 2, "Optimization 1"; panel form only): feature f becomes row row_of_feat[f] of the outputs; rows below
 // n_sparse are 2:4-compressed along tokens as above, the others -- the least sparse features -- are written out
@@ -141,7 +147,7 @@ __global__ void __launch_bounds__(256) featurewise24_kernel(const uint16_t* __re
   int tid = threadIdx.x;
   bool has_z = dZc != nullptr;
 #pragma unroll
-  for (int i = 0; i < 2; i++) {
+  for (int i = 0; i < FW_TOK / 64; i++) {
     int item = tid + 256 * i;
     int tok = item >> 2, ch = item & 3;
     int t = t0 + tok;
@@ -154,10 +160,10 @@ __global__ void __launch_bounds__(256) featurewise24_kernel(const uint16_t* __re
       vo = (size_t)t * (F / 2) + f0 / 2 + 8 * ch;
       mo = (size_t)t * (F / 8) + f0 / 8 + 2 * ch;
     }
-    u32x4 hv = *reinterpret_cast<const u32x4*>(Hc + vo);
+    u32x4 hv = ld_stream(reinterpret_cast<const u32x4*>(Hc + vo));
     u32x4 zv = {0u, 0u, 0u, 0u};
-    if (has_z) zv = *reinterpret_cast<const u32x4*>(dZc + vo);
-    uint32_t m16 = *reinterpret_cast<const uint16_t*>(meta + mo);
+    if (has_z) zv = ld_stream(reinterpret_cast<const u32x4*>(dZc + vo));
+    uint32_t m16 = ld_stream(reinterpret_cast<const uint16_t*>(meta + mo));
 #pragma unroll
     for (int g = 0; g < 4; g++) {
       uint32_t nib = (m16 >> (4 * g)) & 15u;
@@ -179,11 +185,11 @@ __global__ void __launch_bounds__(256) featurewise24_kernel(const uint16_t* __re
   __syncthreads();
   uint32_t kept = 0u;   // non-zero activations this work item writes out (at most 32)
 #pragma unroll
-  for (int i = 0; i < 4; i++) {
+  for (int i = 0; i < FW_TOK / 32; i++) {
     int item = tid + 256 * i;
     int oct, f;
     if constexpr (PANEL) { oct = (item & 7) | ((item >> 9) << 3); f = (item >> 3) & 63; }
-    else { oct = item & 15; f = item >> 4; }
+    else { oct = item % (FW_TOK / 8); f = item / (FW_TOK / 8); }
     uint32_t h[8], z[8];
 #pragma unroll
     for (int j = 0; j < 8; j++) {
@@ -221,9 +227,9 @@ __global__ void __launch_bounds__(256) featurewise24_kernel(const uint16_t* __re
       vo = frow * (T / 2) + (t0 + 8 * oct) / 2;
       mo = frow * (T / 8) + t0 / 8 + oct;
     }
-    *reinterpret_cast<u32x2*>(Hc_t + vo) = u32x2{hp[0], hp[1]};
-    if (has_z) *reinterpret_cast<u32x2*>(dZc_t + vo) = u32x2{zp[0], zp[1]};
-    meta_t[mo] = (uint8_t)(nb[0] | (nb[1] << 4));
+    st_stream(reinterpret_cast<u32x2*>(Hc_t + vo), u32x2{hp[0], hp[1]});
+    if (has_z) st_stream(reinterpret_cast<u32x2*>(dZc_t + vo), u32x2{zp[0], zp[1]});
+    st_stream(meta_t + mo, (uint8_t)(nb[0] | (nb[1] << 4)));
     kept += min(hp[0] & 0xFFFFu, 1u) + min(hp[0] >> 16, 1u) + min(hp[1] & 0xFFFFu, 1u) + min(hp[1] >> 16, 1u);
   }
   // what the weight-gradient GEMMs still see of the activation (Sec. 2: the second, feature-wise drop): one atomic
@@ -395,37 +401,38 @@ int launch_zero32(uint32_t* p, size_t n, hipStream_t s) {
 int launch_unpanel(const void* src, int rows, int npanels, int piece_bytes, void* dst, hipStream_t s) {
   size_t n = (size_t)rows * npanels * (piece_bytes / 8);
   size_t blocks = (n + 255) / 256;
-  if (blocks > 256 * 32) blocks = 256 * 32;
+  if (blocks > 0x7FFFFFFF) blocks = 0x7FFFFFFF;   // one work item per thread: the fastest shape for a streaming kernel here
   auto kern = piece_bytes == 64 ? unpanel_kernel<64> : (piece_bytes == 16 ? unpanel_kernel<16> : unpanel_kernel<8>);
   hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const u32x2*>(src), rows, npanels, static_cast<u32x2*>(dst));
   return (int)hipGetLastError();
 }
 
-// out[c][r] = in[r][c] for a bf16 matrix [R][C], R and C multiples of 64.  One workgroup per 64x64 tile: rows are
+// out[c][r] = in[r][c] for a bf16 matrix [R][C], R and C multiples of 64.  One workgroup per 64 x TR_COLS tile: rows are
 // read 128 bytes at a time, scattered into an LDS tile with a 132-byte pitch (conflict-free for this pattern), and
 // written out as 128-byte rows of the transposed matrix.
 // OUT_FORM: 0 row-major; 1 the dense panel form of gemm_core.hpp (64-byte pieces of 32 k, K = R), as A operands take it;
 // 2 the B panel form (the same with the rows of every block of 256 in LDS order).
 // in_panel (optional): a copy of the input itself in panel form (K = C), made in the same pass; in_panel_b: in the B form.
 // in_rowmap (optional): input row r is read from memory row in_rowmap[r] (token permutation).
-constexpr int TR_LD = 66;
+constexpr int TR_LD = 66, TR_COLS = 64;   // a tile is 64 rows x TR_COLS columns (128 columns, 256-byte row segments in, measured 2-5 % slower)
 
 template <int OUT_FORM>
 __global__ void __launch_bounds__(256) transpose_kernel(const uint16_t* __restrict__ in, int R, int C, uint16_t* __restrict__ out,
                                                         uint16_t* __restrict__ in_panel, int in_panel_b, const int* __restrict__ in_rowmap) {
-  __shared__ __attribute__((aligned(16))) uint16_t sT[64 * TR_LD];
-  int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  __shared__ __attribute__((aligned(16))) uint16_t sT[TR_COLS * TR_LD];
+  int r0 = blockIdx.y * 64, c0 = blockIdx.x * TR_COLS;
   int tid = threadIdx.x;
-  int ch = tid & 7, rr = tid >> 3;
+  constexpr int CH = TR_COLS / 8;            // 16-byte chunks per input row segment
+  int ch = tid % CH, rr = tid / CH;
 #pragma unroll
-  for (int i = 0; i < 2; i++) {
-    int r = rr + 32 * i;
+  for (int i = 0; i < 64 * CH / 256; i++) {
+    int r = rr + (256 / CH) * i;
     size_t src_row = in_rowmap ? (size_t)in_rowmap[r0 + r] : (size_t)(r0 + r);
-    u32x4 v = *reinterpret_cast<const u32x4*>(in + src_row * C + c0 + 8 * ch);
+    u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(in + src_row * C + c0 + 8 * ch));
     if (in_panel) {
       int c = c0 + 8 * ch;
       int prow = in_panel_b ? b_panel_pos(r0 + r) : r0 + r;
-      *reinterpret_cast<u32x4*>(in_panel + a24_piece(prow, c >> 5, C >> 5) * 32 + (c & 31)) = v;
+      st_stream(reinterpret_cast<u32x4*>(in_panel + a24_piece(prow, c >> 5, C >> 5) * 32 + (c & 31)), v);
     }
 #pragma unroll
     for (int d = 0; d < 4; d++) {
@@ -434,20 +441,21 @@ __global__ void __launch_bounds__(256) transpose_kernel(const uint16_t* __restri
     }
   }
   __syncthreads();
+  int oc = tid & 7, cc = tid >> 3;           // 16-byte chunk of an output row (8 of the tile's 64 rows), output row
 #pragma unroll
-  for (int i = 0; i < 2; i++) {
-    int c = rr + 32 * i;
-    const uint32_t* src = reinterpret_cast<const uint32_t*>(&sT[c * TR_LD + 8 * ch]);
+  for (int i = 0; i < TR_COLS / 32; i++) {
+    int c = cc + 32 * i;
+    const uint32_t* src = reinterpret_cast<const uint32_t*>(&sT[c * TR_LD + 8 * oc]);
     u32x4 v = {src[0], src[1], src[2], src[3]};
-    int r = r0 + 8 * ch;
-    if constexpr (OUT_FORM == 1) *reinterpret_cast<u32x4*>(out + a24_piece(c0 + c, r >> 5, R >> 5) * 32 + (r & 31)) = v;
-    else if constexpr (OUT_FORM == 2) *reinterpret_cast<u32x4*>(out + a24_piece(b_panel_pos(c0 + c), r >> 5, R >> 5) * 32 + (r & 31)) = v;
-    else *reinterpret_cast<u32x4*>(out + (size_t)(c0 + c) * R + r) = v;
+    int r = r0 + 8 * oc;
+    if constexpr (OUT_FORM == 1) st_stream(reinterpret_cast<u32x4*>(out + a24_piece(c0 + c, r >> 5, R >> 5) * 32 + (r & 31)), v);
+    else if constexpr (OUT_FORM == 2) st_stream(reinterpret_cast<u32x4*>(out + a24_piece(b_panel_pos(c0 + c), r >> 5, R >> 5) * 32 + (r & 31)), v);
+    else st_stream(reinterpret_cast<u32x4*>(out + (size_t)(c0 + c) * R + r), v);
   }
 }
 
 int launch_transpose(const void* in, int R, int C, void* out, int out_form, void* in_panel, int in_panel_b, const int* in_rowmap, hipStream_t s) {
-  dim3 grid(C / 64, R / 64);
+  dim3 grid(C / TR_COLS, R / 64);
   auto kern = out_form == 2 ? transpose_kernel<2> : (out_form == 1 ? transpose_kernel<1> : transpose_kernel<0>);
   hipLaunchKernelGGL(kern, grid, dim3(256), 0, s, static_cast<const uint16_t*>(in), R, C, static_cast<uint16_t*>(out),
                      static_cast<uint16_t*>(in_panel), in_panel_b, in_rowmap);
@@ -526,10 +534,10 @@ __global__ void __launch_bounds__(256) featurewise24_f8_kernel(const uint8_t* __
     int item = tid + 256 * i;
     int tok = item >> 2, ch = item & 3;              // 16 stored bytes = 8 groups = 32 features
     size_t piece = a24_piece(t0 + tok, f0 >> 7, F >> 7);
-    u32x4 hv = *reinterpret_cast<const u32x4*>(Hc8 + piece * 64 + 16 * ch);
+    u32x4 hv = ld_stream(reinterpret_cast<const u32x4*>(Hc8 + piece * 64 + 16 * ch));
     u32x4 zv = {0u, 0u, 0u, 0u};
-    if (has_z) zv = *reinterpret_cast<const u32x4*>(dZc8 + piece * 64 + 16 * ch);
-    uint32_t m32 = *reinterpret_cast<const uint32_t*>(meta + piece * 16 + 4 * ch);
+    if (has_z) zv = ld_stream(reinterpret_cast<const u32x4*>(dZc8 + piece * 64 + 16 * ch));
+    uint32_t m32 = ld_stream(reinterpret_cast<const uint32_t*>(meta + piece * 16 + 4 * ch));
 #pragma unroll
     for (int g = 0; g < 8; g++) {
       uint32_t nib = (m32 >> (4 * g)) & 15u;
@@ -566,9 +574,9 @@ __global__ void __launch_bounds__(256) featurewise24_f8_kernel(const uint8_t* __
       mq |= nib << (4 * g);
     }
     size_t piece = a24_piece(f0 + f, t0 >> 7, T >> 7);
-    *reinterpret_cast<u32x2*>(Hc8_t + piece * 64 + 8 * c) = u32x2{hq[0], hq[1]};
-    if (has_z) *reinterpret_cast<u32x2*>(dZc8_t + piece * 64 + 8 * c) = u32x2{zq[0], zq[1]};
-    *reinterpret_cast<uint16_t*>(meta_t + piece * 16 + 2 * c) = (uint16_t)mq;
+    st_stream(reinterpret_cast<u32x2*>(Hc8_t + piece * 64 + 8 * c), u32x2{hq[0], hq[1]});
+    if (has_z) st_stream(reinterpret_cast<u32x2*>(dZc8_t + piece * 64 + 8 * c), u32x2{zq[0], zq[1]});
+    st_stream(reinterpret_cast<uint16_t*>(meta_t + piece * 16 + 2 * c), (uint16_t)mq);
   }
 }
 
