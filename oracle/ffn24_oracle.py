@@ -655,6 +655,58 @@ def ffn_fwd_fp8_rowwise_codes(X8, sx, W1_8, sw1, b1, W2_8, sw2):
     return {"Z": Z, "Hq": Hq, "sh": sh, "H8_bits": H8_bits, "Y": Y}
 
 
+def ffn24_bwd_fp8_rowwise_codes(fwd, dY8r, sdy_t, W2_8r, sw2_f, W1_8c, sw1_d, dY8c, sdy_d, X8c, sx_d, wgrad_mask="featurewise", quantise_internal=True):
+    """Backward of ffn24_fwd_fp8_rowwise_codes with row-wise scaling in every GEMM (the paper's precision recipe: the caption
+    of the forward-speed-up figure has all FP8 matrix multiplications row-wise scaled; Sec. 2, the paragraph on the fused
+    backward pointwise kernel: it includes the transposition and the FP8 scaling).  Row-wise scaling of a GEMM: each operand
+    carries one scale per index of its non-reduced dimension, so the tensors that enter two GEMMs with different reduced
+    dimensions are quantised twice, by the caller (from its higher-precision copies):
+      dY8r [T,D] codes, sdy_t [T]: dY quantised per token (reduced over d in the dH GEMM)
+      dY8c [T,D] codes, sdy_d [D]: dY quantised per model dimension (reduced over t in the dW2 GEMM)
+      W2_8r [F,D] codes, sw2_f [F]: W2 quantised per hidden feature (dH GEMM);  W1_8c [D,F] codes, sw1_d [D]: W1 per model
+      dimension (dX GEMM);  X8c [T,D] codes, sx_d [D]: X per model dimension (dW1 GEMM)
+    and the tensors the backward makes itself are quantised where they are made, each scale = the largest magnitude / 448 in
+    float32 (1 if all zero), as the forward does for the activation:
+      dH[t,f] = sdy_t[t] sw2_f[f] (dY8r . W2_8r^T)[t,f]
+      dZ      = bf16( dH * 2 max(0, Z) ) on the positions the token-wise mask kept (Fig. 4 caption), 0 elsewhere
+      sdz_t[t] = max_f |dZ[t,f]| / 448;  dZ8r = e4m3(dZ / sdz_t[t]);   dX[t,d] = sdz_t[t] sw1_d[d] (dZ8r . W1_8c^T)[t,d]
+      feature-wise picks on top of the token-wise mask (Sec. 2, last paragraph), ranked on the bf16 activation H24 as in
+      ffn24_bwd (quantisation comes after the pick, as in the forward), one mask M_T for H and dZ
+      sh_f[f] = max_t H24[t,f] / 448;  H8c = e4m3(H24 / sh_f[f]);  sdz_f[f] = max_t |dZ[t,f]| / 448;  dZ8c = e4m3(dZ / sdz_f[f])
+      dW2[f,d] = sh_f[f] sdy_d[d] ((H8c * M_T)^T . dY8c)[f,d];   dW1[d,f] = sx_d[d] sdz_f[f] (X8c^T . (dZ8c * M_T))[d,f]
+    fwd = the result of ffn24_fwd_fp8_rowwise_codes.  Switches for pinning only: wgrad_mask="tokenwise" uses the token-wise
+    mask in the last line; quantise_internal=False leaves dZ and H24 unrounded (neither bf16 nor e4m3) in all three GEMMs."""
+    dec = lambda c: E4M3_VALUES[np.ascontiguousarray(c, dtype=np.uint8)]
+    f64 = lambda v: np.asarray(v, dtype=np.float32).astype(np.float64)
+    meta = np.asarray(fwd["meta"], dtype=np.uint8)
+    Mtok = mask_from_meta(meta)
+    dH = (dec(dY8r) @ dec(W2_8r).T) * f64(sdy_t)[:, None] * f64(sw2_f)[None, :]
+    dZ = np.where(Mtok, dH * relu2_derivative(fwd["Z"]), 0.0)
+    H24 = decompress24(bf16_bits_to_f32(np.asarray(fwd["Hc_words"], dtype=np.uint16)), meta)
+    _, meta_t, M_T = featurewise24(H24)
+    Mw = M_T if wgrad_mask == "featurewise" else Mtok
+    out = {"dH": dH, "Mtok": Mtok, "M_T": M_T, "meta_t": meta_t}
+    if quantise_internal:
+        dZ16 = round_bf16(dZ)
+        dZ8r_bits, sdz_t = quantise_rows_e4m3(dZ16)
+        dZ8c_bits_t, sdz_f = quantise_rows_e4m3(np.ascontiguousarray(dZ16.T))
+        H8c_bits_t, sh_f = quantise_rows_e4m3(np.ascontiguousarray(H24.T))
+        dZr = dec(dZ8r_bits) * sdz_t.astype(np.float64)[:, None]
+        dZc = dec(dZ8c_bits_t).T * sdz_f.astype(np.float64)[None, :]
+        Hc = dec(H8c_bits_t).T * sh_f.astype(np.float64)[None, :]
+        out.update({"dZ16": dZ16, "sdz_t": sdz_t, "sdz_f": sdz_f, "sh_f": sh_f, "dZ8r_bits": dZ8r_bits,
+                    "dZc8r_bits": compress_with_meta(dZ8r_bits, meta),
+                    "Hc8_t_bits": compress_with_meta(H8c_bits_t, meta_t), "dZc8_t_bits": compress_with_meta(dZ8c_bits_t, meta_t)})
+    else:
+        dZr = dZc = dZ
+        Hc = H24.astype(np.float64)
+    out["dZ"] = dZ
+    out["dX"] = (dZr @ dec(W1_8c).T) * f64(sw1_d)[None, :]
+    out["dW2"] = (np.where(Mw, Hc, 0.0).T @ dec(dY8c)) * f64(sdy_d)[None, :]
+    out["dW1"] = (dec(X8c).T * f64(sx_d)[:, None]) @ np.where(Mw, dZc, 0.0)
+    return out
+
+
 def quantise_rows_e4m3(x):
     """Row-wise e4m3 quantisation of a float matrix: s[r] = max|x[r,:]| / 448 (1 for an all-zero row), codes of x / s."""
     x = np.asarray(x, dtype=np.float32)

@@ -822,3 +822,103 @@ def test_use_sparse_path_follows_the_warm_up_story():
     assert not O.use_sparse_path(c0, 0.85) and O.use_sparse_path(c1, 0.85)
     assert O.use_sparse_path({"elements": 100, "nonzero": 10}, 0.9)          # exactly at the threshold counts as reached
     assert not O.use_sparse_path({"elements": 100, "nonzero": 11}, 0.9)
+
+
+def _fp8_rowwise_bwd_case(T=32, D=16, F=64, seed=23, sparsity=0.5, pow2_uniform=False):
+    """Row-wise fp8 forward + the operands of its backward, quantised from float masters the way a caller would: one scale
+    per index of the non-reduced dimension of each GEMM.  pow2_uniform: every scale vector holds one power of two and the
+    masters are clipped to +-256 of it, so that row-wise and per-tensor quantisation of a tensor give the same codes."""
+    inp = _small_inputs(T=T, D=D, F=F, seed=seed, sparsity=sparsity)
+    X, W1, W2, dY = inp["X"], inp["W1"], inp["W2"], inp["dY"]
+    if pow2_uniform:
+        def q(x, axis_len):
+            s = np.float32(2.0 ** np.ceil(np.log2(np.abs(x).max() / 256.0)))
+            return O.f32_to_e4m3_bits(x / s), np.full(axis_len, s, np.float32)
+        X8, sx = q(X, T); W1_8, sw1 = q(W1, F); W2_8, sw2 = q(W2, D)
+        dY8r, sdy_t = q(dY, T); dY8c, sdy_d = dY8r, np.full(D, sdy_t[0], np.float32)
+        W2_8r, sw2_f = W2_8, np.full(F, sw2[0], np.float32); W1_8c, sw1_d = W1_8, np.full(D, sw1[0], np.float32)
+        X8c, sx_d = X8, np.full(D, sx[0], np.float32)
+    else:
+        X8, sx = O.quantise_rows_e4m3(X)                                   # per token
+        W1_8t, sw1 = O.quantise_rows_e4m3(W1.T); W1_8 = np.ascontiguousarray(W1_8t.T)   # per hidden feature
+        W2_8t, sw2 = O.quantise_rows_e4m3(W2.T); W2_8 = np.ascontiguousarray(W2_8t.T)   # per model dimension
+        dY8r, sdy_t = O.quantise_rows_e4m3(dY)
+        dY8ct, sdy_d = O.quantise_rows_e4m3(dY.T); dY8c = np.ascontiguousarray(dY8ct.T)
+        W2_8r, sw2_f = O.quantise_rows_e4m3(W2)
+        W1_8c, sw1_d = O.quantise_rows_e4m3(W1)
+        X8ct, sx_d = O.quantise_rows_e4m3(X.T); X8c = np.ascontiguousarray(X8ct.T)
+    f = O.ffn24_fwd_fp8_rowwise_codes(X8, sx, W1_8, sw1, inp["b1"], W2_8, sw2)
+    bw = dict(dY8r=dY8r, sdy_t=sdy_t, W2_8r=W2_8r, sw2_f=sw2_f, W1_8c=W1_8c, sw1_d=sw1_d, dY8c=dY8c, sdy_d=sdy_d, X8c=X8c, sx_d=sx_d)
+    return inp, f, bw, dict(X8=X8, sx=sx, W1_8=W1_8, sw1=sw1, W2_8=W2_8, sw2=sw2)
+
+
+def test_fp8_rowwise_backward_reduces_to_the_per_tensor_backward():
+    """With one power-of-two scale per tensor (so that the row-wise and the per-tensor codes of a tensor coincide), internal
+    tensors left unrounded and the token-wise mask in the weight gradients, the row-wise backward is the per-tensor fp8
+    backward on the same codes -- which is pinned against torch autograd above."""
+    inp, f, bw, fw = _fp8_rowwise_bwd_case(pow2_uniform=True)
+    g = O.ffn24_bwd_fp8_rowwise_codes(f, **bw, wgrad_mask="tokenwise", quantise_internal=False)
+    sx, sw1, sw2, sdy = float(fw["sx"][0]), float(fw["sw1"][0]), float(fw["sw2"][0]), float(bw["sdy_t"][0])
+    # a per-tensor forward with ANY activation scale has the same Z and metadata; its stored codes differ, so dW2 is taken
+    # from the unquantised activation here and compared with the product of the bf16 activation instead
+    fp = O.ffn24_fwd_fp8_codes(fw["X8"], fw["W1_8"], inp["b1"], fw["W2_8"], sx, sw1, 1.0, sw2)
+    assert np.array_equal(fp["meta"], f["meta"]) and np.array_equal(fp["Z"], f["Z"])
+    p = O.ffn24_bwd_fp8_codes(fp, fw["X8"], fw["W1_8"], fw["W2_8"], bw["dY8r"], sx, sw1, 1.0, sw2, sdy, 1.0, wgrad_mask="tokenwise", quantise_dz=False)
+    assert np.allclose(g["dX"], p["dX"], rtol=1e-12, atol=1e-15) and np.allclose(g["dW1"], p["dW1"], rtol=1e-12, atol=1e-15)
+    assert np.count_nonzero(g["dX"]) > 100
+    H24 = O.decompress24(O.bf16_bits_to_f32(f["Hc_words"]), f["meta"]).astype(np.float64)
+    dYv = O.e4m3_bits_to_f32(bw["dY8c"]).astype(np.float64) * sdy
+    assert np.allclose(g["dW2"], H24.T @ dYv, rtol=1e-12, atol=1e-15)
+
+
+def test_fp8_rowwise_backward_quantises_each_internal_operand_along_its_own_axis():
+    inp, f, bw, fw = _fp8_rowwise_bwd_case(T=64, D=16, F=64, sparsity=0.4)
+    g = O.ffn24_bwd_fp8_rowwise_codes(f, **bw)
+    e = O.ffn24_bwd_fp8_rowwise_codes(f, **bw, quantise_internal=False)
+    Mtok, M_T = g["Mtok"], g["M_T"]
+    # dZ is stored in bf16 before it is quantised, and is zero off the token-wise mask
+    assert np.array_equal(g["dZ16"], O.round_bf16(e["dZ"])) and not g["dZ16"][~Mtok].any()
+    # per token for the dX GEMM: torch's cast of dZ / (row max / 448); every non-zero row uses the full range
+    rows = np.abs(g["dZ16"]).max(axis=1)
+    assert np.array_equal(g["sdz_t"], np.where(rows > 0, rows / np.float32(448), np.float32(1)).astype(np.float32))
+    want = torch.from_numpy((g["dZ16"] / g["sdz_t"][:, None]).astype(np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(g["dZ8r_bits"], want) and ((g["dZ8r_bits"] & 0x7F).max(axis=1)[rows > 0] == 0x7E).all()
+    # per feature for the weight gradients: the decompressed transposed operands, again full range in every non-zero feature
+    Hq = O.decompress24(g["Hc8_t_bits"], g["meta_t"]); Zq = O.decompress24(g["dZc8_t_bits"], g["meta_t"])
+    H24 = O.decompress24(O.bf16_bits_to_f32(f["Hc_words"]), f["meta"])
+    cols_h = np.where(M_T, H24, 0).max(axis=0)
+    assert np.array_equal(g["sh_f"], np.where(H24.max(axis=0) > 0, H24.max(axis=0) / np.float32(448), np.float32(1)).astype(np.float32))
+    hit = (np.where(M_T, H24, 0).max(axis=0) == H24.max(axis=0)) & (cols_h > 0)        # the column's largest entry survives the second prune
+    assert hit.any() and (Hq.max(axis=1)[hit] == 0x7E).all()
+    assert np.array_equal((Hq != 0).T, M_T & (O.f32_to_e4m3_bits(H24 / g["sh_f"][None, :]) != 0))
+    assert np.array_equal(Zq.T & 0x7F != 0, M_T & (O.f32_to_e4m3_bits(g["dZ16"] / g["sdz_f"][None, :]) & 0x7F != 0))
+    # the feature-wise mask is the one the bf16 backward uses (ranked on the bf16 activation, before any quantisation)
+    assert np.array_equal(M_T, O.featurewise24(H24)[2]) and np.all(~(M_T & (H24 != 0)) | Mtok)
+    # the gradients are the products of the decoded operands with their scales (torch), and stay within the format's rounding
+    # (4 significant bits) of the backward whose internal tensors are left unrounded
+    dec = lambda c: torch.from_numpy(np.ascontiguousarray(c)).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    dX = (dec(g["dZ8r_bits"]) @ dec(bw["W1_8c"]).T) * g["sdz_t"].astype(np.float64)[:, None] * bw["sw1_d"].astype(np.float64)[None, :]
+    dW2 = (dec(Hq) @ dec(bw["dY8c"])) * g["sh_f"].astype(np.float64)[:, None] * bw["sdy_d"].astype(np.float64)[None, :]
+    dW1 = (dec(bw["X8c"]).T @ dec(Zq).T) * bw["sx_d"].astype(np.float64)[:, None] * g["sdz_f"].astype(np.float64)[None, :]
+    for k, v in (("dX", dX), ("dW2", dW2), ("dW1", dW1)):
+        assert np.allclose(g[k], v, rtol=1e-12, atol=1e-15), k
+        assert O.fro_rel_err(g[k], e[k]) <= 2.0 ** -4, k
+    assert np.count_nonzero(np.where(M_T, H24, 0)) < np.count_nonzero(H24)
+
+
+def test_fp8_rowwise_backward_scale_equivariance():
+    """Doubling one token's dY scale doubles that token's dH and dZ rows, hence its dZ scale, and leaves its codes alone:
+    that row of dX doubles exactly and no other row moves.  Doubling one model dimension's scale of the column-quantised dY
+    doubles that column of dW2 exactly; doubling one of X's that row of dW1."""
+    inp, f, bw, fw = _fp8_rowwise_bwd_case()
+    a = O.ffn24_bwd_fp8_rowwise_codes(f, **bw)
+    b2 = dict(bw); b2["sdy_t"] = bw["sdy_t"].copy(); b2["sdy_t"][5] *= 2
+    b = O.ffn24_bwd_fp8_rowwise_codes(f, **b2)
+    assert np.array_equal(a["dZ8r_bits"], b["dZ8r_bits"]) and b["sdz_t"][5] == 2 * a["sdz_t"][5]
+    assert np.array_equal(b["dX"][5], 2 * a["dX"][5]) and np.array_equal(np.delete(b["dX"], 5, 0), np.delete(a["dX"], 5, 0))
+    assert np.abs(a["dX"][5]).max() > 0
+    b3 = dict(bw); b3["sdy_d"] = bw["sdy_d"].copy(); b3["sdy_d"][3] *= 2; b3["sx_d"] = bw["sx_d"].copy(); b3["sx_d"][7] *= 2
+    c = O.ffn24_bwd_fp8_rowwise_codes(f, **b3)
+    assert np.array_equal(c["dW2"][:, 3], 2 * a["dW2"][:, 3]) and np.array_equal(np.delete(c["dW2"], 3, 1), np.delete(a["dW2"], 3, 1))
+    assert np.array_equal(c["dW1"][7], 2 * a["dW1"][7]) and np.array_equal(np.delete(c["dW1"], 7, 0), np.delete(a["dW1"], 7, 0))
+    assert np.array_equal(c["dX"], a["dX"])
