@@ -672,8 +672,10 @@ def ffn24_bwd_fp8_rowwise_codes(fwd, dY8r, sdy_t, W2_8r, sw2_f, W1_8c, sw1_d, dY
       sdz_t[t] = max_f |dZ[t,f]| / 448;  dZ8r = e4m3(dZ / sdz_t[t]);   dX[t,d] = sdz_t[t] sw1_d[d] (dZ8r . W1_8c^T)[t,d]
       feature-wise picks on top of the token-wise mask (Sec. 2, last paragraph), ranked on the bf16 activation H24 as in
       ffn24_bwd (quantisation comes after the pick, as in the forward), one mask M_T for H and dZ
-      sh_f[f] = max_t H24[t,f] / 448;  H8c = e4m3(H24 / sh_f[f]);  sdz_f[f] = max_t |dZ[t,f]| / 448;  dZ8c = e4m3(dZ / sdz_f[f])
-      dW2[f,d] = sh_f[f] sdy_d[d] ((H8c * M_T)^T . dY8c)[f,d];   dW1[d,f] = sx_d[d] sdz_f[f] (X8c^T . (dZ8c * M_T))[d,f]
+      the two transposed operands are quantised as they enter their GEMMs, i.e. after the second mask:
+      sh_f[f] = max_t (H24 * M_T)[t,f] / 448;  H8c = e4m3(H24 * M_T / sh_f[f])   (the largest entry of a column always survives M_T)
+      sdz_f[f] = max_t |(dZ * M_T)[t,f]| / 448;  dZ8c = e4m3(dZ * M_T / sdz_f[f])
+      dW2[f,d] = sh_f[f] sdy_d[d] (H8c^T . dY8c)[f,d];   dW1[d,f] = sx_d[d] sdz_f[f] (X8c^T . dZ8c)[d,f]
     fwd = the result of ffn24_fwd_fp8_rowwise_codes.  Switches for pinning only: wgrad_mask="tokenwise" uses the token-wise
     mask in the last line; quantise_internal=False leaves dZ and H24 unrounded (neither bf16 nor e4m3) in all three GEMMs."""
     dec = lambda c: E4M3_VALUES[np.ascontiguousarray(c, dtype=np.uint8)]
@@ -689,8 +691,8 @@ def ffn24_bwd_fp8_rowwise_codes(fwd, dY8r, sdy_t, W2_8r, sw2_f, W1_8c, sw1_d, dY
     if quantise_internal:
         dZ16 = round_bf16(dZ)
         dZ8r_bits, sdz_t = quantise_rows_e4m3(dZ16)
-        dZ8c_bits_t, sdz_f = quantise_rows_e4m3(np.ascontiguousarray(dZ16.T))
-        H8c_bits_t, sh_f = quantise_rows_e4m3(np.ascontiguousarray(H24.T))
+        dZ8c_bits_t, sdz_f = quantise_rows_e4m3(np.ascontiguousarray(np.where(Mw, dZ16, np.float32(0)).T))
+        H8c_bits_t, sh_f = quantise_rows_e4m3(np.ascontiguousarray(np.where(Mw, H24, np.float32(0)).T))
         dZr = dec(dZ8r_bits) * sdz_t.astype(np.float64)[:, None]
         dZc = dec(dZ8c_bits_t).T * sdz_f.astype(np.float64)[None, :]
         Hc = dec(H8c_bits_t).T * sh_f.astype(np.float64)[None, :]

@@ -892,6 +892,9 @@ def test_fp8_rowwise_backward_quantises_each_internal_operand_along_its_own_axis
     assert hit.any() and (Hq.max(axis=1)[hit] == 0x7E).all()
     assert np.array_equal((Hq != 0).T, M_T & (O.f32_to_e4m3_bits(H24 / g["sh_f"][None, :]) != 0))
     assert np.array_equal(Zq.T & 0x7F != 0, M_T & (O.f32_to_e4m3_bits(g["dZ16"] / g["sdz_f"][None, :]) & 0x7F != 0))
+    zcols = np.abs(np.where(M_T, g["dZ16"], 0)).max(axis=0)                            # the scale of dZ^T: over what the second mask left
+    assert np.array_equal(g["sdz_f"], np.where(zcols > 0, zcols / np.float32(448), np.float32(1)).astype(np.float32))
+    assert ((Zq & 0x7F).max(axis=1)[zcols > 0] == 0x7E).all() and (zcols < np.abs(g["dZ16"]).max(axis=0)).any()
     # the feature-wise mask is the one the bf16 backward uses (ranked on the bf16 activation, before any quantisation)
     assert np.array_equal(M_T, O.featurewise24(H24)[2]) and np.all(~(M_T & (H24 != 0)) | Mtok)
     # the gradients are the products of the decoded operands with their scales (torch), and stay within the format's rounding
