@@ -85,9 +85,9 @@ FFN24_API int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F,
  *   Hc8 = e4m3(kept / sh), saturating at +-448, round to nearest even;  Y = bf16(sh sw2 (Hc8 . W2_8))
  * (paper Sec. 2: activation, then sparsification, then FP8 quantisation; per-tensor scales instead of the paper's
  * row-wise ones).  Saved tensors 0 and 1 are then bytes: Hc8 [T][F/2], meta [T][F/8]; tensor 7 is H8 [T][F].
- * ffn_fwd is the dense fp8 baseline of the forward.  With FFN24_TRAINING (and neither FFN24_ROWWISE nor FFN24_SPLIT:
- * FFN24_ERR_DTYPE otherwise) the context also supports ffn24_bwd -- and, with FFN24_DENSE, ffn_bwd -- in fp8, see
- * ffn24_set_bwd_scales. */
+ * ffn_fwd is the dense fp8 baseline of the forward.  With FFN24_TRAINING (not with FFN24_SPLIT: FFN24_ERR_DTYPE) the context
+ * also supports ffn24_bwd -- and, with FFN24_DENSE, ffn_bwd -- in fp8, see ffn24_set_bwd_scales; with FFN24_ROWWISE as well
+ * (then not with FFN24_DENSE) the backward is ffn24_bwd_rowwise. */
 FFN24_API int ffn24_set_scales(ffn24_ctx* ctx, float sx, float sw1, float sh, float sw2);
 
 /* fp8 backward of an FFN24_FP8_E4M3 | FFN24_TRAINING context (paper abstract: FP8 in both the forwards and the
@@ -116,6 +116,36 @@ FFN24_API int ffn24_set_bwd_scales(ffn24_ctx* ctx, float sdy, float sdz);
  * row-wise quantisation of every activation with sh[t] = (largest activation of token t) / 448, dense GEMM; saved tensor
  * 7 is then H8 [T][F] and tensor 11 the sh of that forward. */
 FFN24_API int ffn24_set_row_scales(ffn24_ctx* ctx, const float* sx, const float* sw1, const float* sw2);
+
+/* Backward of a row-wise-scaled forward: an FFN24_FP8_E4M3 | FFN24_ROWWISE | FFN24_TRAINING context (not with FFN24_DENSE or
+ * FFN24_SPLIT), after ffn24_fwd.  Every GEMM of the backward is scaled row-wise, as the paper's precision recipe has it for all
+ * of its FP8 matrix multiplications (caption of the forward-speed-up figure; Sec. 2, the paragraph on the fused backward pointwise
+ * kernel: it includes the transposition and the FP8 scaling): each operand carries one scale per index of its NON-reduced
+ * dimension.  A tensor that enters two GEMMs with different reduced dimensions is therefore quantised twice, by the caller,
+ * from its higher-precision copy -- all pointers are device memory, 16-byte aligned, codes are e4m3 bytes, scales fp32 > 0:
+ *   dY8r [T][D], sdy_t [T]: dY8r[t][d] = e4m3(dY[t][d] / sdy_t[t])      (dH GEMM, reduced over d)
+ *   dY8c [T][D], sdy_d [D]: dY8c[t][d] = e4m3(dY[t][d] / sdy_d[d])      (dW2 GEMM, reduced over t)
+ *   X8c  [T][D], sx_d  [D]: X8c[t][d]  = e4m3(X[t][d]  / sx_d[d])       (dW1 GEMM, reduced over t)
+ *   W2_8r [F][D], sw2_f [F]: W2_8r[f][d] = e4m3(W2[f][d] / sw2_f[f])    (dH GEMM)
+ *   W1_8c [D][F], sw1_d [D]: W1_8c[d][f] = e4m3(W1[d][f] / sw1_d[d])    (dX GEMM, reduced over f)
+ * The tensors the backward makes itself are quantised where they are made, each scale = (largest magnitude) / 448, 1 if all zero:
+ *   dH[t][f] = sdy_t[t] sw2_f[f] (dY8r . W2_8r^T);  dZ = bf16(dH * 2 max(0, Z)) on the kept positions (the derivative taken as
+ *   2 sqrt(h) of the bf16 kept activation the forward saved), compressed with the forward's metadata;
+ *   sdz_t[t] = max_f |dZ[t][f]| / 448;  dZ8r = e4m3(dZ / sdz_t[t]);  dX = bf16(sdz_t[t] sw1_d[d] (dZ8r . W1_8c^T));
+ *   feature-wise 2:4 on top of the token-wise mask, ranked on the bf16 activation (as in the bf16 backward), one mask for H and dZ;
+ *   sh_f[f] = max_t (kept H)[t][f] / 448, sdz_f[f] = max_t |kept dZ[t][f]| / 448 over what the second mask kept;
+ *   dW2 = bf16(sh_f[f] sdy_d[d] (H8c^T . dY8c));  dW1 = bf16(sx_d[d] sdz_f[f] (X8c^T . dZ8c)).
+ * Outputs dX [T][D], dW1 [D][F], dW2 [F][D] are bf16 and overwritten.  Saved tensors afterwards: 2 dZ8r compressed [T][F/2] bytes,
+ * 3 / 4 / 5 the transposed compressed operands (bytes), 13 sdz_t [T], 14 sh_f [F], 15 sdz_f [F] (fp32), 16 the bf16 compressed dZ
+ * [T][F/2] before quantisation.  FFN24_ERR_STATE on any other context or before a forward.  ffn24_bwd refuses a row-wise context. */
+typedef struct {
+  const void* dY8r;  const float* sdy_t;
+  const void* dY8c;  const float* sdy_d;
+  const void* X8c;   const float* sx_d;
+  const void* W2_8r; const float* sw2_f;
+  const void* W1_8c; const float* sw1_d;
+} ffn24_rowwise_bwd_operands;
+FFN24_API int ffn24_bwd_rowwise(ffn24_ctx* ctx, const ffn24_rowwise_bwd_operands* operands, void* dX, void* dW1, void* dW2, void* stream);
 
 /* Fixed token permutation around the FFN (paper Sec. 2, "Optimization 2": features are correlated among consecutive
  * tokens, so the tokens are permuted before entering the FFN and shuffled back after).  perm_host is a HOST array
@@ -249,6 +279,7 @@ FFN24_API int ffn24_policy_use_sparse(ffn24_ctx* ctx, double min_sparsity, int* 
  *   9 per-feature non-zero counts [F] uint32, 10 feature of each split-operand row [F] int32 (FFN24_SPLIT)
  *   11 per-token activation scale sh [T] fp32 (FFN24_ROWWISE)
  *   12 kept activation before quantisation [T][F/2] bf16 (fp8 contexts with FFN24_TRAINING or FFN24_ROWWISE)
+ *   13 sdz_t [T], 14 sh_f [F], 15 sdz_f [F] fp32 and 16 the compressed dZ before quantisation [T][F/2] bf16 (after ffn24_bwd_rowwise)
  * ffn24_saved_bytes gives the size of tensor `which`; ffn24_copy_saved enqueues a copy of it into dst (device memory
  * of exactly that size, 16-byte aligned) in the row-major compressed form described at the top -- inside the context
  * the compressed tensors are kept in a tiled order that the sparse GEMM streams faster.  Returns FFN24_ERR_STATE if
@@ -264,7 +295,9 @@ FFN24_API int ffn24_copy_saved(ffn24_ctx* ctx, int which, void* dst, int64_t dst
  * (up, down, dH, dX, dW2, dW1), 13 the weight pass of a forward or of ffn24_prepare_weights (W1, W2 re-arranged), 14 the two
  * activation transposes of a backward (dY, X), 15 the feature partition of the split, 16 the transpose that brings
  * dW1 into [D][F] after a split (with a split, 5 and 6 are the combined sparse + dense launches of dW2 and dW1),
- * 17 the row-wise fp8 quantisation kernel.  Returns FFN24_ERR_STATE if that kernel has not run with profiling on. */
+ * 17 the row-wise fp8 quantisation kernel of a forward, 18 the one of dZ in ffn24_bwd_rowwise, 19 its two quantisations of the
+ * transposed operands (in ffn24_bwd_rowwise 13 is the re-arrangement of the caller's W2_8r, W1_8c).  Returns FFN24_ERR_STATE if
+ * that kernel has not run with profiling on. */
 FFN24_API int ffn24_set_profiling(ffn24_ctx* ctx, int on);
 FFN24_API int ffn24_kernel_ms(ffn24_ctx* ctx, int kernel, float* ms);
 /* The shader clock (MHz) GEMM kernel `kernel` of the most recent profiled call really ran at: the first 64 workgroups

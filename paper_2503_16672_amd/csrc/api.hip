@@ -7,8 +7,8 @@
 using namespace ffn24;
 
 namespace {
-constexpr int NUM_KERNELS = 18;   // K_QUANT is shared by the 2:4 and the dense row-wise quantisation kernels
-enum { K_UP = 0, K_DOWN, K_DH, K_DX, K_FW, K_DW2, K_DW1, KD_UP, KD_DOWN, KD_DH, KD_DX, KD_DW2, KD_DW1, K_TR_W, K_TR_ACT, K_PART, K_TR_DW1, K_QUANT };
+constexpr int NUM_KERNELS = 20;   // K_QUANT is shared by the 2:4 and the dense row-wise quantisation kernels
+enum { K_UP = 0, K_DOWN, K_DH, K_DX, K_FW, K_DW2, K_DW1, KD_UP, KD_DOWN, KD_DH, KD_DX, KD_DW2, KD_DW1, K_TR_W, K_TR_ACT, K_PART, K_TR_DW1, K_QUANT, K_QUANT_DZ, K_QUANT_T };
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
@@ -47,6 +47,13 @@ struct ffn24_ctx {
   const float *rsx, *rsw1, *rsw2;
   void* Hc16; uint8_t* meta16; uint32_t* rowmax; float* rsh;
   void* Hd16;                  // dense row-wise baseline: every activation as bf16 before quantisation
+  // row-wise-scaled fp8 backward (FFN24_ROWWISE | FFN24_TRAINING): bf16 compressed dZ and the bf16 transposed operands before
+  // their quantisation, the largest magnitude word of each of their rows, the scales derived from those, and the caller's
+  // backward-side weight codes in panel form
+  void* dZc16; void* Hct16; void* dZct16; uint8_t* meta_t16;
+  uint32_t* rowmax_dz; uint32_t* hmax; uint32_t* zmax;
+  float* sdz_t; float* sh_f; float* sdz_f;
+  void* W2rp; void* W1cp;
   // workspace (device)
   void* Hc; uint8_t* meta; void* dZc; void* Hc_t; uint8_t* meta_t; void* dZc_t; void* Hdbg; void* Hd; void* dZd;
   void* W1t; void* W2t; void* Xt; void* dYt; void* Hd_t; void* dZd_t;   // K-contiguous copies of GEMM operands
@@ -90,7 +97,8 @@ int free_all(ffn24_ctx* c) {
   int bad = 0;
   void* bufs[] = {c->Hc, c->meta, c->dZc, c->Hc_t, c->meta_t, c->dZc_t, c->Hdbg, c->Hd, c->dZd,
                   c->W1t, c->W2t, c->Xt, c->dYt, c->Hd_t, c->dZd_t, c->W2p, c->W1p,
-                  c->nnz, c->row_of_feat, c->feat_of_row, c->Hdn_t, c->dZdn_t, c->dW1t, c->Hc16, c->meta16, c->rowmax, c->rsh, c->perm, c->Hd16};
+                  c->nnz, c->row_of_feat, c->feat_of_row, c->Hdn_t, c->dZdn_t, c->dW1t, c->Hc16, c->meta16, c->rowmax, c->rsh, c->perm, c->Hd16,
+                  c->dZc16, c->Hct16, c->dZct16, c->meta_t16, c->rowmax_dz, c->hmax, c->zmax, c->sdz_t, c->sh_f, c->sdz_f, c->W2rp, c->W1cp};
   for (void* b : bufs) if (b && hipFree(b) != hipSuccess) bad = 1;
   if (c->clk && hipFree(c->clk) != hipSuccess) bad = 1;
   if (c->tele && hipFree(c->tele) != hipSuccess) bad = 1;
@@ -174,7 +182,8 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
   if (!out) return FFN24_ERR_NULL;
   if (dtype != FFN24_BF16 && dtype != FFN24_FP8_E4M3) return FFN24_ERR_DTYPE;
   const bool f8 = dtype == FFN24_FP8_E4M3;
-  if (f8 && (flags & FFN24_TRAINING) && (flags & (FFN24_ROWWISE | FFN24_SPLIT))) return FFN24_ERR_DTYPE;   // fp8 training: per-tensor scales, no split
+  if (f8 && (flags & FFN24_TRAINING) && (flags & FFN24_SPLIT)) return FFN24_ERR_DTYPE;                      // fp8 training: no split
+  if (f8 && (flags & FFN24_TRAINING) && (flags & FFN24_ROWWISE) && (flags & FFN24_DENSE)) return FFN24_ERR_DTYPE;   // no dense row-wise backward
   if ((flags & FFN24_SPLIT) && !(flags & FFN24_TRAINING)) return FFN24_ERR_STATE;
   if ((flags & FFN24_ROWWISE) && !f8) return FFN24_ERR_DTYPE;
   if ((flags & FFN24_PERMUTE) && f8) return FFN24_ERR_DTYPE;
@@ -212,9 +221,17 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
          hipMalloc(&c->Hdn_t, tf / 2) == hipSuccess && hipMalloc(&c->dZdn_t, tf / 2) == hipSuccess &&   // up to F/4 dense rows
          hipMalloc(&c->dW1t, 2 * df) == hipSuccess;
   if (ok && (flags & FFN24_PERMUTE)) ok = hipMalloc(reinterpret_cast<void**>(&c->perm), 4 * (size_t)T) == hipSuccess;
+  if (ok && (flags & FFN24_ROWWISE) && !c->Hc16)
+    ok = hipMalloc(&c->Hc16, tf) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->meta16), tf / 8) == hipSuccess;
   if (ok && (flags & FFN24_ROWWISE))
-    ok = hipMalloc(&c->Hc16, tf) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->meta16), tf / 8) == hipSuccess &&
-         hipMalloc(reinterpret_cast<void**>(&c->rowmax), 4 * (size_t)T) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->rsh), 4 * (size_t)T) == hipSuccess;
+    ok = hipMalloc(reinterpret_cast<void**>(&c->rowmax), 4 * (size_t)T) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->rsh), 4 * (size_t)T) == hipSuccess;
+  if (ok && (flags & FFN24_ROWWISE) && (flags & FFN24_TRAINING))
+    ok = hipMalloc(&c->dZc16, tf) == hipSuccess && hipMalloc(&c->Hct16, tf) == hipSuccess && hipMalloc(&c->dZct16, tf) == hipSuccess &&
+         hipMalloc(reinterpret_cast<void**>(&c->meta_t16), tf / 8) == hipSuccess &&
+         hipMalloc(reinterpret_cast<void**>(&c->rowmax_dz), 4 * (size_t)T) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->hmax), 4 * (size_t)F) == hipSuccess &&
+         hipMalloc(reinterpret_cast<void**>(&c->zmax), 4 * (size_t)F) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->sdz_t), 4 * (size_t)T) == hipSuccess &&
+         hipMalloc(reinterpret_cast<void**>(&c->sh_f), 4 * (size_t)F) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->sdz_f), 4 * (size_t)F) == hipSuccess &&
+         hipMalloc(&c->W2rp, df) == hipSuccess && hipMalloc(&c->W1cp, df) == hipSuccess;
   if (ok && (flags & FFN24_DENSE)) ok = hipMalloc(&c->Hd, es * tf) == hipSuccess;
   if (ok && (flags & FFN24_DENSE) && (flags & FFN24_ROWWISE)) ok = hipMalloc(&c->Hd16, 2 * tf) == hipSuccess;
   if (ok && (flags & FFN24_DENSE) && (flags & FFN24_TRAINING))
@@ -401,7 +418,9 @@ int ffn24_saved_bytes(ffn24_ctx* c, int which, int64_t* nbytes) {
     case 7: case 8: *nbytes = es * tf; break;
     case 9: case 10: *nbytes = 4 * c->F; break;
     case 11: *nbytes = 4 * c->T; break;
-    case 12: *nbytes = tf; break;
+    case 12: case 16: *nbytes = tf; break;
+    case 13: *nbytes = 4 * c->T; break;
+    case 14: case 15: *nbytes = 4 * c->F; break;
     default: return FFN24_ERR_SHAPE;
   }
   return FFN24_OK;
@@ -433,10 +452,14 @@ int ffn24_copy_saved(ffn24_ctx* c, int which, void* dst, int64_t dst_bytes, void
     case 9: src = c->nnz; break;
     case 10: src = c->feat_of_row; break;
     case 11: src = c->rsh; break;
+    case 13: src = c->sdz_t; break;
+    case 14: src = c->sh_f; break;
+    case 15: src = c->sdz_f; break;
+    case 16: src = c->dZc16; break;
     default: src = c->Hc16; break;
   }
   if (!src) return FFN24_ERR_STATE;
-  if (which == 12)   // bf16 kept values of an fp8 context: bf16 panel form (64-byte pieces of 64 k)
+  if (which == 12 || which == 16)   // bf16 kept values of an fp8 context: bf16 panel form (64-byte pieces of 64 k)
     return launch_unpanel(src, T, F / 64, 64, dst, s) ? FFN24_ERR_HIP : FFN24_OK;
   if (which >= 9) return hipMemcpyAsync(dst, src, (size_t)need, hipMemcpyDeviceToDevice, s) == hipSuccess ? FFN24_OK : FFN24_ERR_HIP;
   if (which >= 7)   // the dense baseline's H and dZ: dense panel form, 64-byte pieces of 32 (fp8: 64) k
@@ -511,6 +534,7 @@ int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, cons
       if (t.done(launch_quantise_rows(c->Hc16, c->meta16, c->rowmax, T, F, c->Hc, c->meta, c->rsh, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_DOWN, s);
       if (t.done(launch_sp_rowmajor_f8_rowwise(c->Hc, c->meta, c->W2t, T, D, F, c->rsh, c->rsw2, Y, s))) return FFN24_ERR_HIP; }
+    if (c->flags & FFN24_TRAINING) { c->X = X; c->have_fwd24 = 1; }
     return FFN24_OK;
   }
   if (c->f8) {
@@ -567,9 +591,46 @@ int ffn24_fwd_static(const void* X, const void* W1, const float* b1, const void*
   return FFN24_OK;
 }
 
+int ffn24_bwd_rowwise(ffn24_ctx* c, const ffn24_rowwise_bwd_operands* op, void* dX, void* dW1, void* dW2, void* stream) {
+  if (!c || !op) return FFN24_ERR_NULL;
+  if (!c->f8 || !(c->flags & FFN24_ROWWISE) || !(c->flags & FFN24_TRAINING) || !c->have_fwd24) return FFN24_ERR_STATE;
+  int rc = check_device(c);
+  if (rc) return rc;
+  rc = check_ptrs({op->dY8r, op->sdy_t, op->dY8c, op->sdy_d, op->X8c, op->sx_d, op->W2_8r, op->sw2_f, op->W1_8c, op->sw1_d, dX, dW1, dW2});
+  if (rc) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int T = (int)c->T, D = (int)c->D, F = (int)c->F;
+  // the caller's backward-side weight codes into the forms the GEMMs stream: W2 (quantised per hidden feature) as the A operand
+  // of the dH GEMM, W1 (quantised per model dimension) as the B operand of the dX GEMM; the column-quantised dY and X transposed
+  { Timed t(c, K_TR_W, s);
+    int rc1 = launch_panelise8(op->W2_8r, F, D, c->W2rp, 0, s);
+    if (t.done(rc1 ? rc1 : launch_panelise8(op->W1_8c, D, F, c->W1cp, 1, s))) return FFN24_ERR_HIP; }
+  if (launch_zero32(c->rowmax_dz, (size_t)T, s) || launch_zero32(c->hmax, (size_t)F, s) || launch_zero32(c->zmax, (size_t)F, s)) return FFN24_ERR_HIP;
+  { Timed t(c, K_DH, s);
+    if (t.done(launch_dh_gather_f8_rowwise(c->W2rp, op->dY8r, c->Hc16, c->meta16, T, D, F, op->sw2_f, op->sdy_t, c->dZc16, c->rowmax_dz, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_QUANT_DZ, s);
+    if (t.done(launch_quantise_rows(c->dZc16, c->meta16, c->rowmax_dz, T, F, c->dZc, c->meta, c->sdz_t, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_DX, s);
+    if (t.done(launch_sp_rowmajor_f8_rowwise(c->dZc, c->meta, c->W1cp, T, D, F, c->sdz_t, op->sw1_d, dX, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_FW, s);
+    if (t.done(launch_featurewise24_rowmax(c->Hc16, c->meta16, c->dZc16, T, F, c->Hct16, c->meta_t16, c->dZct16, c->hmax, c->zmax, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_QUANT_T, s);
+    int rc1 = launch_quantise_rows(c->Hct16, c->meta_t16, c->hmax, F, T, c->Hc_t, c->meta_t, c->sh_f, s);
+    if (t.done(rc1 ? rc1 : launch_quantise_rows(c->dZct16, c->meta_t16, c->zmax, F, T, c->dZc_t, c->meta_t, c->sdz_f, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_TR_ACT, s);
+    int rc1 = launch_transpose8(op->dY8c, T, D, c->dYt, 2, nullptr, 0, s);
+    if (t.done(rc1 ? rc1 : launch_transpose8(op->X8c, T, D, c->Xt, 2, nullptr, 0, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_DW2, s);
+    if (t.done(launch_sp_rowmajor_f8_rowwise(c->Hc_t, c->meta_t, c->dYt, F, D, T, c->sh_f, op->sdy_d, dW2, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_DW1, s);
+    if (t.done(launch_sp_colmajor_f8_rowwise(c->dZc_t, c->meta_t, c->Xt, F, D, T, c->sdz_f, op->sx_d, dW1, s))) return FFN24_ERR_HIP; }
+  return FFN24_OK;
+}
+
 int ffn24_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void* stream) {
   if (!c) return FFN24_ERR_NULL;
   if (!(c->flags & FFN24_TRAINING) || !c->have_fwd24) return FFN24_ERR_STATE;
+  if (c->flags & FFN24_ROWWISE) return FFN24_ERR_STATE;   // a row-wise context takes ffn24_bwd_rowwise
   int rc = check_device(c);
   if (rc) return rc;
   rc = check_ptrs({dY, dX, dW1, dW2});

@@ -555,6 +555,79 @@ struct EpiRowMajorRowCol {
   }
 };
 
+// C stored transposed, out[n][m] = bf16(acc * rs[m] * cs[n]) with m contiguous (row-wise-scaled fp8 dW1 GEMM: rs = the scale of
+// each hidden feature's row of the transposed dZ operand, cs = the scale of each model dimension's row of the transposed X).
+struct EpiColMajorRowCol {
+  struct Args { __bf16* C; int ldc; const float* rs; const float* cs; };
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+    LaneVec64 lr;
+    lr.load(e.rs, m_lane, 1.f);
+#pragma unroll
+    for (int ni = 0; ni < 4; ni++) {
+      const float cs = e.cs[n_lane + ni];
+      __bf16* row = e.C + (size_t)(n_lane + ni) * e.ldc + m_lane;
+#pragma unroll
+      for (int mi = 0; mi < 4; mi++)
+#pragma unroll
+        for (int q = 0; q < 2; q++) {
+          u32x4 o;
+#pragma unroll
+          for (int d = 0; d < 4; d++) {
+            int i = 16 * mi + 8 * q + 2 * d;
+            o[d] = pack_bf16x2(acc[mi][ni][8 * q + 2 * d] * lr.at(i) * cs, acc[mi][ni][8 * q + 2 * d + 1] * lr.at(i + 1) * cs);
+          }
+          *reinterpret_cast<u32x4*>(row + 16 * mi + 8 * q) = o;
+        }
+    }
+  }
+};
+
+// fp8 backward with ROW-WISE scaling, pointwise part (Sec. 2: the fused backward pointwise step with its FP8 scaling; the
+// precision recipe of the paper's benchmarks scales every FP8 GEMM row-wise): acc = (W2_8r . dY8r) for a lane's 64 features x
+// 4 tokens; dH = rs[f] cs[t] acc (rs = the scale of each hidden feature's row of W2, cs = the scale of each token's row of dY);
+// on the positions the forward kept dZ = dH * 2 sqrt(h), h the bf16 kept value the forward saved (Hc16, meta16: bf16 panel form).
+// Like the activation in the row-wise forward, dZ cannot be quantised here -- the scale of a token row spans many block tiles
+// -- so it is written as bf16, compressed with the forward's metadata (dZc16, bf16 panel form), and every lane raises
+// rowmax[t] to the largest magnitude word of its part of the row; a streaming kernel then quantises with rowmax[t] / 448.
+struct EpiDGatherRw {
+  struct Args { const __bf16* Hc16; const uint8_t* meta16; __bf16* dZc16; int F; const float* rs; const float* cs; uint32_t* rowmax; };
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+    LaneVec64 lr;
+    lr.load(e.rs, m_lane, 1.f);
+#pragma unroll
+    for (int ni = 0; ni < 4; ni++) {
+      size_t t = (size_t)(n_lane + ni);
+      const float cs = e.cs[t];
+      size_t piece = a24_piece((int)t, m_lane >> 6, e.F >> 6);
+      const __bf16* hrow = e.Hc16 + piece * 32;
+      u32x2 mt = *reinterpret_cast<const u32x2*>(e.meta16 + piece * 8);
+      __bf16* zrow = e.dZc16 + piece * 32;
+      uint32_t mx = 0u;
+#pragma unroll
+      for (int mi = 0; mi < 4; mi++) {
+        u32x4 h = *reinterpret_cast<const u32x4*>(hrow + 8 * mi);
+        u32x4 z;
+#pragma unroll
+        for (int a = 0; a < 4; a++) {
+          int gi = 4 * mi + a;
+          uint32_t n4 = (mt[gi >> 3] >> (4 * (gi & 7))) & 15u;
+          uint32_t i0 = n4 & 3u, i1 = n4 >> 2;
+          float x0 = acc[mi][ni][4 * a] * (cs * lr.at(16 * mi + 4 * a)), x1 = acc[mi][ni][4 * a + 1] * (cs * lr.at(16 * mi + 4 * a + 1));
+          float x2 = acc[mi][ni][4 * a + 2] * (cs * lr.at(16 * mi + 4 * a + 2)), x3 = acc[mi][ni][4 * a + 3] * (cs * lr.at(16 * mi + 4 * a + 3));
+          float s0 = i0 == 0 ? x0 : (i0 == 1 ? x1 : x2);
+          float s1 = i1 == 3 ? x3 : (i1 == 2 ? x2 : x1);
+          float g0 = 2.f * __builtin_amdgcn_sqrtf(bf16_lo_to_f32(h[a]));
+          float g1 = 2.f * __builtin_amdgcn_sqrtf(bf16_hi_to_f32(h[a]));
+          z[a] = pack_bf16x2(s0 * g0, s1 * g1);
+          mx = max(mx, max(z[a] & 0x7FFFu, (z[a] >> 16) & 0x7FFFu));
+        }
+        *reinterpret_cast<u32x4*>(zrow + 8 * mi) = z;
+      }
+      if (mx) atomicMax(e.rowmax + t, mx);
+    }
+  }
+};
+
 // fp8 dense up-projection (baseline): H8[t][f] = e4m3( bf16(max(0, zscale acc + b1)^2) / sh ), the [T][F] byte operand
 // of the dense down-projection, in dense panel form (64-byte pieces of 64 k).
 // H16, H8t (optional, a training context): the activation before quantisation as bf16 [T][F] (dense bf16 panel form; the

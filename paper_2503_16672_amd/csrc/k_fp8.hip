@@ -87,4 +87,20 @@ int launch_sp_rowmajor_f8_rowwise(const void* vals8, const uint8_t* meta, const 
   return launch_gemm<true, EpiRowMajorRowCol, true>(g, ea, s);
 }
 
+// row-wise-scaled backward: the dH GEMM with the pointwise part fused (bf16 compressed dZ + row maxima out), and the sparse GEMM
+// with the transposing store and a scale per row and per column (dW1)
+int launch_dh_gather_f8_rowwise(const void* W2rp8, const void* dY8r, const void* Hc16, const uint8_t* meta16, int T, int D, int F,
+                                const float* sw2_f, const float* sdy_t, void* dZc16, uint32_t* rowmax, hipStream_t s) {
+  GemmArgs g{W2rp8, nullptr, dY8r, F, T, D, 1};
+  EpiDGatherRw::Args ea{static_cast<const __bf16*>(Hc16), meta16, static_cast<__bf16*>(dZc16), F, sw2_f, sdy_t, rowmax};
+  return launch_gemm<false, EpiDGatherRw, true>(g, ea, s);
+}
+
+int launch_sp_colmajor_f8_rowwise(const void* vals8, const uint8_t* meta, const void* B8, int M, int N, int K, const float* rs, const float* cs,
+                                  void* Ct, hipStream_t s) {
+  GemmArgs g{vals8, meta, B8, M, N, K, 1, nullptr, 1};
+  EpiColMajorRowCol::Args ea{static_cast<__bf16*>(Ct), M, rs, cs};
+  return launch_gemm<true, EpiColMajorRowCol, true>(g, ea, s);
+}
+
 }  // namespace ffn24

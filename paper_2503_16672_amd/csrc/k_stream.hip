@@ -140,7 +140,8 @@ __global__ void __launch_bounds__(256) featurewise24_kernel(const uint16_t* __re
                                                             uint16_t* __restrict__ Hc_t, uint8_t* __restrict__ meta_t,
                                                             uint16_t* __restrict__ dZc_t, const int* __restrict__ row_of_feat,
                                                             int n_sparse, uint16_t* __restrict__ Hdn_t, uint16_t* __restrict__ dZdn_t,
-                                                            unsigned long long* __restrict__ tele) {
+                                                            unsigned long long* __restrict__ tele, uint32_t* __restrict__ hmax,
+                                                            uint32_t* __restrict__ zmax) {
   __shared__ uint16_t sH[FW_TOK * FW_LD];
   __shared__ uint16_t sZ[FW_TOK * FW_LD];
   int f0 = blockIdx.x * FW_FEAT, t0 = blockIdx.y * FW_TOK;
@@ -230,6 +231,22 @@ __global__ void __launch_bounds__(256) featurewise24_kernel(const uint16_t* __re
     st_stream(reinterpret_cast<u32x2*>(Hc_t + vo), u32x2{hp[0], hp[1]});
     if (has_z) st_stream(reinterpret_cast<u32x2*>(dZc_t + vo), u32x2{zp[0], zp[1]});
     st_stream(meta_t + mo, (uint8_t)(nb[0] | (nb[1] << 4)));
+    if (hmax) {
+      // largest stored magnitude word of this feature's row, for a row-wise quantisation that follows (the eight work items of
+      // a feature are neighbouring lanes: one atomic per feature, tensor and workgroup)
+      static_assert(FW_TOK == 64, "the eight items of a feature are the lanes tid & 7");
+      uint32_t mh = max(max(hp[0] & 0xFFFFu, hp[0] >> 16), max(hp[1] & 0xFFFFu, hp[1] >> 16));
+      uint32_t mz = max(max(zp[0] & 0x7FFFu, (zp[0] >> 16) & 0x7FFFu), max(zp[1] & 0x7FFFu, (zp[1] >> 16) & 0x7FFFu));
+#pragma unroll
+      for (int sft = 1; sft < 8; sft <<= 1) {
+        mh = max(mh, (uint32_t)__shfl_xor((int)mh, sft, 64));
+        mz = max(mz, (uint32_t)__shfl_xor((int)mz, sft, 64));
+      }
+      if ((tid & 7) == 0) {
+        if (mh) atomicMax(hmax + orow, mh);
+        if (mz && has_z) atomicMax(zmax + orow, mz);
+      }
+    }
     kept += min(hp[0] & 0xFFFFu, 1u) + min(hp[0] >> 16, 1u) + min(hp[1] & 0xFFFFu, 1u) + min(hp[1] >> 16, 1u);
   }
   // what the weight-gradient GEMMs still see of the activation (Sec. 2: the second, feature-wise drop): one atomic
@@ -269,7 +286,17 @@ int launch_featurewise24(const void* Hc, const uint8_t* meta, const void* dZc, i
   auto kern = panel ? featurewise24_kernel<true> : featurewise24_kernel<false>;
   hipLaunchKernelGGL(kern, grid, dim3(256), 0, s, static_cast<const uint16_t*>(Hc), meta,
                      static_cast<const uint16_t*>(dZc), T, F, static_cast<uint16_t*>(Hc_t), meta_t, static_cast<uint16_t*>(dZc_t),
-                     nullptr, 0, nullptr, nullptr, tele);
+                     nullptr, 0, nullptr, nullptr, tele, nullptr, nullptr);
+  return (int)hipGetLastError();
+}
+
+// the same (panel form) with the largest stored magnitude word of every output row: hmax, zmax [F], zeroed by the caller
+int launch_featurewise24_rowmax(const void* Hc, const uint8_t* meta, const void* dZc, int T, int F, void* Hc_t, uint8_t* meta_t, void* dZc_t,
+                                uint32_t* hmax, uint32_t* zmax, hipStream_t s) {
+  dim3 grid(F / FW_FEAT, T / FW_TOK);
+  hipLaunchKernelGGL(featurewise24_kernel<true>, grid, dim3(256), 0, s, static_cast<const uint16_t*>(Hc), meta,
+                     static_cast<const uint16_t*>(dZc), T, F, static_cast<uint16_t*>(Hc_t), meta_t, static_cast<uint16_t*>(dZc_t),
+                     nullptr, 0, nullptr, nullptr, nullptr, hmax, zmax);
   return (int)hipGetLastError();
 }
 
@@ -278,7 +305,7 @@ int launch_featurewise24_split(const void* Hc, const uint8_t* meta, const void* 
   dim3 grid(F / FW_FEAT, T / FW_TOK);
   hipLaunchKernelGGL((featurewise24_kernel<true, true>), grid, dim3(256), 0, s, static_cast<const uint16_t*>(Hc), meta,
                      static_cast<const uint16_t*>(dZc), T, F, static_cast<uint16_t*>(Hc_t), meta_t, static_cast<uint16_t*>(dZc_t),
-                     row_of_feat, n_sparse, static_cast<uint16_t*>(Hdn_t), static_cast<uint16_t*>(dZdn_t), tele);
+                     row_of_feat, n_sparse, static_cast<uint16_t*>(Hdn_t), static_cast<uint16_t*>(dZdn_t), tele, nullptr, nullptr);
   return (int)hipGetLastError();
 }
 
@@ -499,6 +526,24 @@ int launch_transpose8(const void* in, int R, int C, void* out, int out_form, voi
   auto kern = out_form == 2 ? transpose8_kernel<2> : (out_form == 1 ? transpose8_kernel<1> : transpose8_kernel<0>);
   hipLaunchKernelGGL(kern, grid, dim3(256), 0, s, static_cast<const uint8_t*>(in), R, C, static_cast<uint8_t*>(out),
                      static_cast<uint8_t*>(in_panel), in_panel_b);
+  return (int)hipGetLastError();
+}
+
+// A byte matrix [R][C] (row-major, C a multiple of 64) copied into the dense fp8 panel form (64-byte pieces of 64 k, K = C) as
+// A operands take it, or, b_form, into the B panel form (rows of every block of 256 in LDS order).  16 bytes per work item.
+__global__ void __launch_bounds__(256) panelise8_kernel(const u32x4* __restrict__ in, int R, int C, uint8_t* __restrict__ out, int b_form) {
+  const int per_row = C >> 4;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)R * per_row) return;
+  int r = (int)(i / per_row), c = (int)(i % per_row) << 4;
+  int prow = b_form ? b_panel_pos(r) : r;
+  st_stream(reinterpret_cast<u32x4*>(out + a24_piece(prow, c >> 6, C >> 6) * 64 + (c & 63)), ld_stream(in + i));
+}
+
+int launch_panelise8(const void* in, int R, int C, void* out, int b_form, hipStream_t s) {
+  size_t n = (size_t)R * (C >> 4);
+  hipLaunchKernelGGL(panelise8_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, static_cast<const u32x4*>(in), R, C,
+                     static_cast<uint8_t*>(out), b_form);
   return (int)hipGetLastError();
 }
 

@@ -112,6 +112,19 @@ int launch_dense_rowmajor_f8_rowwise(const void* A8, const void* B8, int M, int 
 int launch_quantise_rows(const void* Hc16, const uint8_t* meta16, const uint32_t* rowmax, int T, int F, void* Hc8, uint8_t* meta8, float* sh, hipStream_t s);
 int launch_sp_rowmajor_f8_rowwise(const void* vals8, const uint8_t* meta, const void* B8, int M, int N, int K, const float* rs, const float* cs,
                                   void* C, hipStream_t s);
+// row-wise-scaled fp8 backward: dH GEMM (A = W2 quantised per hidden feature, dense fp8 panel form; B = dY quantised per token)
+// with the derivative and the gather fused: bf16 compressed dZ (bf16 panel form) and rowmax[t] = largest magnitude word of a row;
+// the sparse GEMM with the transposing store scaled per row and per column
+int launch_dh_gather_f8_rowwise(const void* W2rp8, const void* dY8r, const void* Hc16, const uint8_t* meta16, int T, int D, int F,
+                                const float* sw2_f, const float* sdy_t, void* dZc16, uint32_t* rowmax, hipStream_t s);
+int launch_sp_colmajor_f8_rowwise(const void* vals8, const uint8_t* meta, const void* B8, int M, int N, int K, const float* rs, const float* cs,
+                                  void* Ct, hipStream_t s);
+// feature-wise kernel on bf16 panel-form operands that also raises hmax[f], zmax[f] (zeroed by the caller) to the largest
+// stored magnitude word of each output row
+int launch_featurewise24_rowmax(const void* Hc, const uint8_t* meta, const void* dZc, int T, int F, void* Hc_t, uint8_t* meta_t, void* dZc_t,
+                                uint32_t* hmax, uint32_t* zmax, hipStream_t s);
+// byte matrix [R][C] (C % 64 == 0, R % 256 == 0) -> dense fp8 panel form, or the B panel form if b_form
+int launch_panelise8(const void* in, int R, int C, void* out, int b_form, hipStream_t s);
 // streaming kernels
 // p[0..n) = 0 (a kernel, not a memset node)
 int launch_zero32(uint32_t* p, size_t n, hipStream_t s);

@@ -25,14 +25,21 @@ FFN24_PERMUTE = 32
 FFN24_TELEMETRY = 64
 
 EXPORTS = (
-    "ffn24_ctx_create", "ffn24_ctx_destroy", "ffn24_set_scales", "ffn24_set_bwd_scales", "ffn24_set_row_scales", "ffn24_set_token_permutation", "ffn24_set_split", "sparsify24", "sparsify24_quantise", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd",
+    "ffn24_ctx_create", "ffn24_ctx_destroy", "ffn24_set_scales", "ffn24_set_bwd_scales", "ffn24_set_row_scales", "ffn24_set_token_permutation", "ffn24_set_split", "sparsify24", "sparsify24_quantise", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd", "ffn24_bwd_rowwise",
     "ffn_fwd", "ffn_bwd", "ffn24_prepare_weights", "ffn24_get_telemetry", "ffn24_policy_use_sparse", "ffn24_saved_bytes", "ffn24_copy_saved", "ffn24_set_profiling", "ffn24_kernel_ms", "ffn24_strerror",
     "ffn24_static_scratch_needed", "ffn24_fwd_static", "ffn24_kernel_mhz", "ffn24_probe_mfma_rate", "ffn24_probe_gemm", "ffn24_probe_copy",
 )
 
 KERNEL_NAMES = ("up_prune24", "down_sp", "dh_gather", "dx_sp", "featurewise24", "dw2_sp", "dw1_sp",
                 "dense_up", "dense_down", "dense_dh", "dense_dx", "dense_dw2", "dense_dw1", "transpose_weights", "transpose_acts",
-                "split_partition", "transpose_dw1", "quantise_rows")
+                "split_partition", "transpose_dw1", "quantise_rows", "quantise_dz_rows", "quantise_transposed")
+
+
+
+class RowwiseBwdOperands(ctypes.Structure):
+    """ffn24_rowwise_bwd_operands of the header: five (codes, scales) pointer pairs."""
+    _fields_ = [(n, ctypes.c_void_p) for n in ("dY8r", "sdy_t", "dY8c", "sdy_d", "X8c", "sx_d", "W2_8r", "sw2_f", "W1_8c", "sw1_d")]
+
 
 _lib = None
 
@@ -58,6 +65,7 @@ def lib() -> ctypes.CDLL:
         L.ffn24_set_split.argtypes = [vp, i64]
         L.ffn24_set_token_permutation.argtypes = [vp, vp]
         L.ffn24_set_row_scales.argtypes = [vp, vp, vp, vp]
+        L.ffn24_bwd_rowwise.argtypes = [vp, ctypes.POINTER(RowwiseBwdOperands), vp, vp, vp, vp]
         L.sparsify24.argtypes = [vp, i64, i64, ci, vp, vp, vp]
         L.sparsify24_quantise.argtypes = [vp, i64, i64, ctypes.c_float, vp, vp, vp]
         L.sparsify24_featurewise.argtypes = [vp, vp, vp, i64, i64, vp, vp, vp, vp]
@@ -328,18 +336,38 @@ class Context:
     def ffn_bwd(self, dY, out=None):
         return self._bwd(lib().ffn_bwd, "ffn_bwd", dY, out)
 
+    def ffn24_bwd_rowwise(self, dY8r, sdy_t, dY8c, sdy_d, X8c, sx_d, W2_8r, sw2_f, W1_8c, sw1_d, out=None):
+        """Backward of a row-wise-scaled forward (see ffn24_bwd_rowwise in the header): e4m3 codes (uint8) and fp32 scale vectors."""
+        dev = dY8r.device
+        if out is None:
+            out = (torch.empty((self.T, self.D), dtype=torch.bfloat16, device=dev),
+                   torch.empty((self.D, self.F), dtype=torch.bfloat16, device=dev),
+                   torch.empty((self.F, self.D), dtype=torch.bfloat16, device=dev))
+        dX, dW1, dW2 = out
+        for t, shape, el, nm in ((dY8r, (self.T, self.D), _BYTE, "dY8r"), (sdy_t, (self.T,), _F32, "sdy_t"), (dY8c, (self.T, self.D), _BYTE, "dY8c"),
+                                 (sdy_d, (self.D,), _F32, "sdy_d"), (X8c, (self.T, self.D), _BYTE, "X8c"), (sx_d, (self.D,), _F32, "sx_d"),
+                                 (W2_8r, (self.F, self.D), _BYTE, "W2_8r"), (sw2_f, (self.F,), _F32, "sw2_f"), (W1_8c, (self.D, self.F), _BYTE, "W1_8c"),
+                                 (sw1_d, (self.D,), _F32, "sw1_d"), (dX, (self.T, self.D), _BF16, "dX"), (dW1, (self.D, self.F), _BF16, "dW1"),
+                                 (dW2, (self.F, self.D), _BF16, "dW2")):
+            _expect(t, shape, el, nm)
+        ops = RowwiseBwdOperands(*(_ptr(t) for t in (dY8r, sdy_t, dY8c, sdy_d, X8c, sx_d, W2_8r, sw2_f, W1_8c, sw1_d)))
+        _check(lib().ffn24_bwd_rowwise(self._h, ctypes.byref(ops), _ptr(dX), _ptr(dW1), _ptr(dW2), _stream()), "ffn24_bwd_rowwise")
+        return dX, dW1, dW2
+
     _SAVED = {"Hc": (0, torch.bfloat16, lambda T, F: (T, F // 2)), "meta": (1, torch.uint8, lambda T, F: (T, F // 8)),
               "dZc": (2, torch.bfloat16, lambda T, F: (T, F // 2)), "Hc_t": (3, torch.bfloat16, lambda T, F: (F, T // 2)),
               "meta_t": (4, torch.uint8, lambda T, F: (F, T // 8)), "dZc_t": (5, torch.bfloat16, lambda T, F: (F, T // 2)),
               "H_dump": (6, torch.bfloat16, lambda T, F: (T, F)), "H_dense": (7, torch.bfloat16, lambda T, F: (T, F)),
               "dZ_dense": (8, torch.bfloat16, lambda T, F: (T, F)),
               "nnz": (9, torch.int32, lambda T, F: (F,)), "feat_of_row": (10, torch.int32, lambda T, F: (F,)),
-              "sh": (11, torch.float32, lambda T, F: (T,)), "Hc16": (12, torch.bfloat16, lambda T, F: (T, F // 2))}
+              "sh": (11, torch.float32, lambda T, F: (T,)), "Hc16": (12, torch.bfloat16, lambda T, F: (T, F // 2)),
+              "sdz_t": (13, torch.float32, lambda T, F: (T,)), "sh_f": (14, torch.float32, lambda T, F: (F,)),
+              "sdz_f": (15, torch.float32, lambda T, F: (F,)), "dZc16": (16, torch.bfloat16, lambda T, F: (T, F // 2))}
 
     def saved(self, name: str) -> torch.Tensor:
         """Row-major copy of a saved tensor of the context (enqueued on the current stream)."""
         which, dtype, shape_fn = self._SAVED[name]
-        if self.dtype == FFN24_FP8_E4M3 and dtype == torch.bfloat16 and name not in ("H_dump", "Hc16"):
+        if self.dtype == FFN24_FP8_E4M3 and dtype == torch.bfloat16 and name not in ("H_dump", "Hc16", "dZc16"):
             dtype = torch.uint8      # e4m3 codes
         n = ctypes.c_int64()
         _check(lib().ffn24_saved_bytes(self._h, which, ctypes.byref(n)), "ffn24_saved_bytes")

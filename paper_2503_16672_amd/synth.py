@@ -126,6 +126,29 @@ def make_inputs_fp8_rowwise(T: int, D: int, F: int, sparsity, seed: int) -> dict
     return out
 
 
+def make_bwd_operands_fp8_rowwise(T: int, D: int, F: int, sparsity, seed: int) -> dict:
+    """The operands of the row-wise-scaled fp8 backward for the workload of make_inputs_fp8_rowwise(T, D, F, sparsity, seed):
+    dY ~ N(0, 1) (seeded) and the float X, W1, W2 of that workload, each quantised with one scale per index of the
+    dimension its backward GEMM does NOT reduce (s = amax / 448 along the reduced one, 1 where that is zero), by torch's CPU cast:
+    dY8r, sdy_t (per token);  dY8c, sdy_d and X8c, sx_d (per model dimension);  W2_8r, sw2_f (per hidden feature);
+    W1_8c, sw1_d (per model dimension).  Codes are uint8 in the tensors' own layouts ([T,D], [F,D], [D,F])."""
+    import torch
+    inp = make_inputs(T, D, F, sparsity, seed, with_dy=True)
+
+    def quant(x, axis):
+        amax = np.abs(x).max(axis=axis, keepdims=True).astype(np.float32)
+        s = np.where(amax > 0, amax / np.float32(448.0), np.float32(1.0)).astype(np.float32)
+        q = torch.from_numpy(np.ascontiguousarray(x / s)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+        return q, s.reshape(-1)
+    out = {}
+    out["dY8r"], out["sdy_t"] = quant(inp["dY"], 1)
+    out["dY8c"], out["sdy_d"] = quant(inp["dY"], 0)
+    out["X8c"], out["sx_d"] = quant(inp["X"], 0)
+    out["W2_8r"], out["sw2_f"] = quant(inp["W2"], 1)
+    out["W1_8c"], out["sw1_d"] = quant(inp["W1"], 1)
+    return out
+
+
 def token_permutation(T: int, seed: int) -> np.ndarray:
     """A fixed pseudo-random permutation of the tokens (int32 [T]): position p inside the FFN holds token perm[p]."""
     return np.random.Generator(np.random.Philox(seed)).permutation(T).astype(np.int32)

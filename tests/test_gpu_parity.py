@@ -1150,6 +1150,105 @@ def test_ffn24_fwd_fp8_rowwise_full_size_sampled(F24):
     _check_fp8_rowwise(F24, w.T, w.D, w.F, w.sparsity, w.seed, rows=rows)
 
 
+def _fp8_rowwise_bwd_case(F24, T, D, Fh, sparsity, seed, rows=None, gsel=None):
+    """Row-wise-scaled fp8 forward + backward against the oracle, staged: (S1) every quantisation step -- the per-token scale
+    and codes of dZ, the feature-wise picks, the per-feature scales and codes of the two transposed operands -- bit-exact
+    from the tensors the GPU itself produced upstream; (S2) dZ and the three gradients against the oracle's arithmetic on the
+    GPU's own upstream tensors; (S3) from the raw inputs by the definition, at 6e-2.  rows / gsel as in _fp8_bwd_case."""
+    inp = synth.make_inputs_fp8_rowwise(T, D, Fh, sparsity, seed)
+    bw = synth.make_bwd_operands_fp8_rowwise(T, D, Fh, sparsity, seed)
+    d = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2", "sx", "sw1", "sw2")}
+    db = {k: torch.from_numpy(v).cuda() for k, v in bw.items()}
+    b1 = torch.from_numpy(inp["b1"]).cuda()
+    ctx = F24.Context(T, D, Fh, F24.FFN24_ROWWISE | F24.FFN24_TRAINING, dtype=F24.FFN24_FP8_E4M3)
+    ctx.set_row_scales(d["sx"], d["sw1"], d["sw2"])
+    Y = ctx.ffn24_fwd(d["X"], d["W1"], b1, d["W2"])
+    dX, dW1, dW2 = ctx.ffn24_bwd_rowwise(db["dY8r"], db["sdy_t"], db["dY8c"], db["sdy_d"], db["X8c"], db["sx_d"], db["W2_8r"], db["sw2_f"],
+                                         db["W1_8c"], db["sw1_d"])
+    torch.cuda.synchronize()
+    dec = lambda c: O.e4m3_bits_to_f32(c).astype(np.float64)
+    s64 = lambda v: np.asarray(v, dtype=np.float32).astype(np.float64)
+    q448 = lambda amax: np.where(amax > 0, amax / np.float32(448.0), np.float32(1.0)).astype(np.float32)
+    rsel = np.arange(T) if rows is None else rows
+    rs_t = torch.from_numpy(rsel).cuda()
+    Hc16_all, meta_all, dZc16_all, dZc8_all = ctx.saved("Hc16"), ctx.saved("meta"), ctx.saved("dZc16"), ctx.saved("dZc")
+    sdz_t = ctx.saved("sdz_t")[rs_t].cpu().numpy()
+    torch.cuda.synchronize()
+    Hc16 = O.bf16_bits_to_f32(words_of(Hc16_all[rs_t])); meta = meta_all[rs_t].cpu().numpy()
+    dZc16 = O.bf16_bits_to_f32(words_of(dZc16_all[rs_t])); dZc8 = dZc8_all[rs_t].cpu().numpy()
+    # ---- token rows.  S2: dZ (bf16) from the GPU's own saved activation and metadata, derivative through the named helper
+    H24 = O.decompress24(Hc16, meta)
+    dH = (dec(bw["dY8r"][rsel]) @ dec(bw["W2_8r"]).T) * s64(bw["sdy_t"][rsel])[:, None] * s64(bw["sw2_f"])[None, :]
+    dZ_st = O.round_bf16(np.where(O.mask_from_meta(meta), dH * O.relu2_derivative_from_stored_activation(H24), 0.0))
+    e_dz = O.max_rel_err(O.decompress24(dZc16, meta), dZ_st); f_dz = O.fro_rel_err(O.decompress24(dZc16, meta), dZ_st)
+    # S1: the per-token scale and the codes, from the GPU's own bf16 dZ
+    assert np.array_equal(sdz_t, q448(np.abs(dZc16).max(axis=1)))
+    assert np.array_equal(dZc8, O.f32_to_e4m3_bits(dZc16 / sdz_t[:, None]))
+    assert ((dZc8 & 0x7F).max(axis=1)[np.abs(dZc16).max(axis=1) > 0] == 0x7E).all()
+    # S2: dX on the GPU's own codes and scales
+    dx_st = (O.decompress24(dec(dZc8), meta) @ dec(bw["W1_8c"]).T) * s64(sdz_t)[:, None] * s64(bw["sw1_d"])[None, :]
+    e_dx = O.max_rel_err(f64(dX[rs_t]), dx_st); r_dx = O.row_rel_err(f64(dX[rs_t]), dx_st)
+    # S3: the same rows from the raw inputs
+    f_raw = O.ffn24_fwd_fp8_rowwise_codes(inp["X"][rsel], inp["sx"][rsel], inp["W1"], inp["sw1"], inp["b1"], inp["W2"], inp["sw2"])
+    bw_r = dict(bw); bw_r["dY8r"] = bw["dY8r"][rsel]; bw_r["sdy_t"] = bw["sdy_t"][rsel]; bw_r["dY8c"] = bw["dY8c"][rsel]; bw_r["X8c"] = bw["X8c"][rsel]
+    g_raw = O.ffn24_bwd_fp8_rowwise_codes(f_raw, **bw_r, wgrad_mask="tokenwise")      # a token slice: only dZ and dX are meaningful
+    e_y = O.max_rel_err(f64(Y[rs_t]), f_raw["Y"]); e_dx_raw = O.max_rel_err(f64(dX[rs_t]), g_raw["dX"]); f_dx_raw = O.fro_rel_err(f64(dX[rs_t]), g_raw["dX"])
+    print(f"  fp8 row-wise bwd rows: dZ staged {e_dz:.2e} (Frobenius {f_dz:.2e})  dX staged {e_dx:.2e} (row {r_dx:.2e})  from raw inputs: Y {e_y:.2e} dX {e_dx_raw:.2e} (Frobenius {f_dx_raw:.2e})", flush=True)
+    assert max(e_dz, f_dz, e_dx, r_dx, e_y, e_dx_raw, f_dx_raw) <= TOL_FP8
+    # ---- hidden-feature groups over all tokens
+    G = Fh // 4
+    gs = np.arange(G) if gsel is None else gsel
+    f4, f2 = _groups_to_cols(gs)
+    f4_t, f2_t = torch.from_numpy(f4).cuda(), torch.from_numpy(f2).cuda()
+    Hc16_g = O.bf16_bits_to_f32(words_of(Hc16_all[:, f2_t])); dZc16_g = O.bf16_bits_to_f32(words_of(dZc16_all[:, f2_t])); meta_g = _meta_of_groups(meta_all, gs)
+    H24_g = O.decompress24(Hc16_g, meta_g); dZ24_g = O.decompress24(dZc16_g, meta_g)                  # bf16 values [T, 4 |gs|]
+    # S1: feature-wise picks on the bf16 activation, then each operand quantised with its own per-feature scale
+    _, mt_ref, M_T = O.featurewise24(H24_g)
+    Hm = np.where(M_T, H24_g, np.float32(0)); Zm = np.where(M_T, dZ24_g, np.float32(0))
+    sh_f_ref = q448(Hm.max(axis=0)); sdz_f_ref = q448(np.abs(Zm).max(axis=0))
+    Hct_ref = O.compress_with_meta(np.ascontiguousarray(O.f32_to_e4m3_bits(Hm / sh_f_ref[None, :]).T), mt_ref)
+    dZct_ref = O.compress_with_meta(np.ascontiguousarray(O.f32_to_e4m3_bits(Zm / sdz_f_ref[None, :]).T), mt_ref)
+    Hc8_t = ctx.saved("Hc_t")[f4_t].cpu().numpy(); dZc8_t = ctx.saved("dZc_t")[f4_t].cpu().numpy(); meta_t = ctx.saved("meta_t")[f4_t].cpu().numpy()
+    sh_f = ctx.saved("sh_f")[f4_t].cpu().numpy(); sdz_f = ctx.saved("sdz_f")[f4_t].cpu().numpy()
+    torch.cuda.synchronize()
+    assert np.array_equal(meta_t, mt_ref) and np.array_equal(sh_f, sh_f_ref) and np.array_equal(sdz_f, sdz_f_ref)
+    assert np.array_equal(Hc8_t, Hct_ref) and np.array_equal(dZc8_t, dZct_ref)
+    # S2: the weight gradients on the GPU's own codes and scales
+    dW2_st = _mm24(dec(Hc8_t), meta_t, dec(bw["dY8c"])) * s64(sh_f)[:, None] * s64(bw["sdy_d"])[None, :]
+    dW1_st = _mm24(dec(dZc8_t), meta_t, dec(bw["X8c"])) * s64(sdz_f)[:, None] * s64(bw["sx_d"])[None, :]
+    e_dw2 = O.max_rel_err(f64(dW2[f4_t]), dW2_st); e_dw1 = O.max_rel_err(f64(dW1[:, f4_t]).T, dW1_st)
+    # S3: the same features from the raw inputs (a feature slice: only the weight gradients are meaningful)
+    f_g = O.ffn24_fwd_fp8_rowwise_codes(inp["X"], inp["sx"], inp["W1"][:, f4], inp["sw1"][f4], inp["b1"][f4], inp["W2"][f4], inp["sw2"])
+    bw_g = dict(bw); bw_g["W2_8r"] = bw["W2_8r"][f4]; bw_g["sw2_f"] = bw["sw2_f"][f4]; bw_g["W1_8c"] = bw["W1_8c"][:, f4]
+    g_g = O.ffn24_bwd_fp8_rowwise_codes(f_g, **bw_g)
+    e_dw2_raw = O.max_rel_err(f64(dW2[f4_t]), g_g["dW2"]); e_dw1_raw = O.max_rel_err(f64(dW1[:, f4_t]), g_g["dW1"])
+    f_dw2_raw = O.fro_rel_err(f64(dW2[f4_t]), g_g["dW2"]); f_dw1_raw = O.fro_rel_err(f64(dW1[:, f4_t]), g_g["dW1"])
+    print(f"  fp8 row-wise bwd features: dW2 staged {e_dw2:.2e} dW1 staged {e_dw1:.2e}  from raw inputs: dW2 {e_dw2_raw:.2e} (Frobenius {f_dw2_raw:.2e}) dW1 {e_dw1_raw:.2e} (Frobenius {f_dw1_raw:.2e})", flush=True)
+    assert max(e_dw2, e_dw1, e_dw2_raw, e_dw1_raw, f_dw2_raw, f_dw1_raw) <= TOL_FP8
+    assert np.count_nonzero(Hm) < np.count_nonzero(H24_g) or T * Fh > (1 << 24)                  # the second prune drops something
+    ctx.close()
+
+
+def test_ffn24_bwd_fp8_rowwise_small(F24):
+    print("fp8 row-wise fwd+bwd T=256 D=512 F=2048", flush=True)
+    _fp8_rowwise_bwd_case(F24, 256, 512, 2048, 0.70, seed=81)
+
+
+def test_ffn24_bwd_fp8_rowwise_multi_tile(F24):
+    print("fp8 row-wise fwd+bwd T=768 D=512 F=1280", flush=True)
+    _fp8_rowwise_bwd_case(F24, 768, 512, 1280, "per_feature", seed=82)
+
+
+@pytest.mark.timeout(900)
+def test_ffn24_bwd_fp8_rowwise_full_size_sampled(F24):
+    w = synth.WORKLOADS["c5"]
+    print(f"fp8 row-wise fwd+bwd full size c5 T={w.T} D={w.D} F={w.F}", flush=True)
+    rng = np.random.default_rng(57)
+    rows = np.sort(rng.choice(w.T, 32, replace=False))
+    gsel = np.sort(rng.choice(w.F // 4, 8, replace=False))
+    _fp8_rowwise_bwd_case(F24, w.T, w.D, w.F, w.sparsity, w.seed, rows=rows, gsel=gsel)
+
+
 def test_fp8_rowwise_rules(F24):
     with pytest.raises(F24.Ffn24Error) as e:
         F24.Context(256, 256, 256, F24.FFN24_ROWWISE)            # row-wise scaling is an fp8 mode
