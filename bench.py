@@ -243,7 +243,7 @@ def main() -> int:
     ap.add_argument("--cpu-tokens", type=int, default=4096, help="token slice the CPU oracle is timed on (about 15 s of CPU work at the default workload)")
     ap.add_argument("--split", type=int, default=0, help="keep this many hidden features (multiple of 256, <= d_ff/4) out of the "
                     "feature-wise 2:4: split weight-gradient GEMMs (bf16 fwd+bwd workloads)")
-    ap.add_argument("--rowwise", action="store_true", help="fp8 workload with row-wise instead of per-tensor scales (2:4 FFN and dense baseline alike)")
+    ap.add_argument("--rowwise", action="store_true", help="fp8 workload with row-wise instead of per-tensor scales (2:4 FFN and dense baseline alike); with --fp8-bwd: forward and backward of the 2:4 FFN with every GEMM scaled row-wise (no dense baseline in that mode)")
     ap.add_argument("--permute", action="store_true", help="run the bf16 workload with a fixed token permutation around the FFN")
     ap.add_argument("--telemetry", action="store_true", help="bf16 workloads: count sparsity and 2:4 drops while running (reported under \"telemetry\")")
     ap.add_argument("--split-sweep", action="store_true", help="time the weight-gradient stage over a range of split sizes")
@@ -270,8 +270,16 @@ def main() -> int:
     fp8 = args.workload == "c5"
     bwd = not args.fwd_only and (not fp8 or args.fp8_bwd)
     rowwise = fp8 and args.rowwise and not bwd
-    no_dense = False
-    if rowwise:
+    rowwise_bwd = fp8 and args.rowwise and bwd     # row-wise scaling in every GEMM of the forward and the backward (2:4 FFN only)
+    no_dense = rowwise_bwd                         # the dense row-wise backward is not built: no baseline in this mode
+    if rowwise_bwd:
+        inp = synth.make_inputs_fp8_rowwise(T, D, F, w.sparsity, w.seed)
+        bwo = synth.make_bwd_operands_fp8_rowwise(T, D, F, w.sparsity, w.seed)
+        dev = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2", "sx", "sw1", "sw2")}
+        devb = {k: torch.from_numpy(v).cuda() for k, v in bwo.items()}
+        ctx = ffn24.Context(T, D, F, ffn24.FFN24_ROWWISE | ffn24.FFN24_TRAINING, dtype=ffn24.FFN24_FP8_E4M3)
+        ctx.set_row_scales(dev["sx"], dev["sw1"], dev["sw2"])
+    elif rowwise:
         inp = synth.make_inputs_fp8_rowwise(T, D, F, w.sparsity, w.seed)
         dev = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2", "sx", "sw1", "sw2")}
         ctx = ffn24.Context(T, D, F, ffn24.FFN24_ROWWISE | ffn24.FFN24_DENSE, dtype=ffn24.FFN24_FP8_E4M3)
@@ -313,7 +321,10 @@ def main() -> int:
 
     def step24():
         ctx.ffn24_fwd(dev["X"], W1a, b1, W2a, Y)
-        if bwd:
+        if rowwise_bwd:
+            ctx.ffn24_bwd_rowwise(devb["dY8r"], devb["sdy_t"], devb["dY8c"], devb["sdy_d"], devb["X8c"], devb["sx_d"], devb["W2_8r"], devb["sw2_f"],
+                                  devb["W1_8c"], devb["sw1_d"], grads)
+        elif bwd:
             ctx.ffn24_bwd(dev["dY"], grads)
 
     def step_dense():
@@ -335,7 +346,7 @@ def main() -> int:
     sec_dense, med_dense, min_dense = (_time_steps(torch, step_dense, args.warmup, args.steps) if not no_dense else (float("nan"),) * 3)
     # separate pass: event pairs around every kernel (on the launch stream) and a clock sample in every GEMM kernel
     ctx.set_profiling(True)
-    k24 = list(range(0, 7 if bwd else 2)) + ([13, 14] if bwd else []) + ([15, 16] if args.split and bwd else []) + ([17] if rowwise else [])
+    k24 = list(range(0, 7 if bwd else 2)) + ([13, 14] if bwd else []) + ([15, 16] if args.split and bwd else []) + ([17] if rowwise or rowwise_bwd else []) + ([18, 19, 20] if rowwise_bwd else [])
     kd = [] if no_dense else list(range(7, 13 if bwd else 9))      # (the dense row-wise quantisation kernel shares id 17 with the 2:4 one)
     acc = {k: [] for k in k24 + kd}
     mhz = {k: [] for k in k24 + kd}
@@ -401,14 +412,15 @@ def main() -> int:
             # reads and writes 2 x 2 bytes per element of its two matrices
             # (the weight pass also writes panel-form copies of W1 and W2 when the context trains: 12 D F bytes then)
             es = 1.0 if fp8 else 2.0
-            if name == "quantise_rows":     # reads the bf16 kept values + metadata, writes codes + metadata (+ one scale per token)
-                gbs = (1.0 + 0.125 + 0.5 + 0.125) * T * F / (ms * 1e-3) / 1e9
+            if name in ("quantise_rows", "quantise_dz_rows", "quantise_transposed"):
+                # reads the bf16 kept values + metadata, writes codes + metadata (+ one scale per row); the transposed pair runs twice
+                gbs = (2.0 if name == "quantise_transposed" else 1.0) * (1.0 + 0.125 + 0.5 + 0.125) * T * F / (ms * 1e-3) / 1e9
                 kernels[name] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / 8000.0, 4)}
                 continue
             if name == "split_partition":
                 kernels[name] = {"ms": round(ms, 4)}
                 continue
-            nbytes = {"featurewise24": (2.0 * es + 0.25) * T * F, "transpose_weights": (6.0 if bwd else 4.0) * es * D * F,
+            nbytes = {"panelise_bwd_weights": 4.0 * D * F, "featurewise24": (2.0 * (2.0 if rowwise_bwd else es) + 0.25) * T * F, "transpose_weights": (6.0 if bwd else 4.0) * es * D * F,
                       "transpose_acts": 4.0 * es * T * D, "transpose_dw1": 4.0 * D * F}[name]
             gbs = nbytes / (ms * 1e-3) / 1e9
             kernels[name] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / 8000.0, 4)}
@@ -432,8 +444,11 @@ def main() -> int:
         from oracle import ffn24_oracle as O
         Ts = min(args.cpu_tokens, T)
         t0 = time.perf_counter()
-        if rowwise:
-            O.ffn24_fwd_fp8_rowwise_codes(inp["X"][:Ts], inp["sx"][:Ts], inp["W1"], inp["sw1"], inp["b1"], inp["W2"], inp["sw2"])
+        if rowwise or rowwise_bwd:
+            f8 = O.ffn24_fwd_fp8_rowwise_codes(inp["X"][:Ts], inp["sx"][:Ts], inp["W1"], inp["sw1"], inp["b1"], inp["W2"], inp["sw2"])
+            if rowwise_bwd:
+                O.ffn24_bwd_fp8_rowwise_codes(f8, bwo["dY8r"][:Ts], bwo["sdy_t"][:Ts], bwo["W2_8r"], bwo["sw2_f"], bwo["W1_8c"], bwo["sw1_d"],
+                                              bwo["dY8c"][:Ts], bwo["sdy_d"], bwo["X8c"][:Ts], bwo["sx_d"])
         elif fp8:
             f8 = O.ffn24_fwd_fp8_codes(inp["X"][:Ts], inp["W1"], inp["b1"], inp["W2"], inp["sx"], inp["sw1"], inp["sh"], inp["sw2"])
             if bwd:
@@ -455,7 +470,7 @@ def main() -> int:
         "dtype": "fp8" if fp8 else "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: 2:4 Squared-ReLU FFN {'fwd+bwd' if bwd else 'fwd'}, T={T} d_model={D} d_ff={F}, target sparsity {w.sparsity}"
                                + (f", {args.split} dense features in the weight gradients" if args.split and bwd else "")
-                               + (", row-wise fp8 scales" if rowwise else "") + (", fixed token permutation" if args.permute and not fp8 else "")
+                               + (", row-wise fp8 scales" if rowwise or rowwise_bwd else "") + (", fixed token permutation" if args.permute and not fp8 else "")
                                + (", weights prepared once" if prepared else ""),
                    "T": T, "d_model": D, "d_ff": F, "parallelism": "single GPU"},
         "frac_of_sparse_mfma_peak": round(value / (2 * peak), 4),

@@ -7,8 +7,8 @@
 using namespace ffn24;
 
 namespace {
-constexpr int NUM_KERNELS = 20;   // K_QUANT is shared by the 2:4 and the dense row-wise quantisation kernels
-enum { K_UP = 0, K_DOWN, K_DH, K_DX, K_FW, K_DW2, K_DW1, KD_UP, KD_DOWN, KD_DH, KD_DX, KD_DW2, KD_DW1, K_TR_W, K_TR_ACT, K_PART, K_TR_DW1, K_QUANT, K_QUANT_DZ, K_QUANT_T };
+constexpr int NUM_KERNELS = 21;   // K_QUANT is shared by the 2:4 and the dense row-wise quantisation kernels
+enum { K_UP = 0, K_DOWN, K_DH, K_DX, K_FW, K_DW2, K_DW1, KD_UP, KD_DOWN, KD_DH, KD_DX, KD_DW2, KD_DW1, K_TR_W, K_TR_ACT, K_PART, K_TR_DW1, K_QUANT, K_QUANT_DZ, K_QUANT_T, K_PANEL_W };
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
@@ -602,7 +602,7 @@ int ffn24_bwd_rowwise(ffn24_ctx* c, const ffn24_rowwise_bwd_operands* op, void* 
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   // the caller's backward-side weight codes into the forms the GEMMs stream: W2 (quantised per hidden feature) as the A operand
   // of the dH GEMM, W1 (quantised per model dimension) as the B operand of the dX GEMM; the column-quantised dY and X transposed
-  { Timed t(c, K_TR_W, s);
+  { Timed t(c, K_PANEL_W, s);
     int rc1 = launch_panelise8(op->W2_8r, F, D, c->W2rp, 0, s);
     if (t.done(rc1 ? rc1 : launch_panelise8(op->W1_8c, D, F, c->W1cp, 1, s))) return FFN24_ERR_HIP; }
   if (launch_zero32(c->rowmax_dz, (size_t)T, s) || launch_zero32(c->hmax, (size_t)F, s) || launch_zero32(c->zmax, (size_t)F, s)) return FFN24_ERR_HIP;

@@ -542,11 +542,13 @@ struct EpiRowMajorRowCol {
   struct Args { __bf16* C; int ldc; const float* rs; const float* cs; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
     const f32x4 cs = *reinterpret_cast<const f32x4*>(e.cs + n_lane);
+    LaneVec64 lr;                                  // the lane's 64 row scales: 16 loads of 16 bytes, not 64 of 4
+    lr.load(e.rs, m_lane, 1.f);
 #pragma unroll
     for (int mi = 0; mi < 4; mi++)
 #pragma unroll
       for (int v = 0; v < 16; v++) {
-        const float r = e.rs[m_lane + 16 * mi + v];
+        const float r = lr.at(16 * mi + v);
         u32x2 o;
         o[0] = pack_bf16x2(acc[mi][0][v] * r * cs[0], acc[mi][1][v] * r * cs[1]);
         o[1] = pack_bf16x2(acc[mi][2][v] * r * cs[2], acc[mi][3][v] * r * cs[3]);

@@ -912,10 +912,31 @@ def test_ffn24_bwd_fp8_full_size_sampled(F24):
 
 
 def test_fp8_context_rules(F24):
-    for extra in (F24.FFN24_SPLIT, F24.FFN24_ROWWISE):      # fp8 training: per-tensor scales, no split
+    for extra in (F24.FFN24_SPLIT, F24.FFN24_ROWWISE | F24.FFN24_DENSE):      # fp8 training: no split, no dense row-wise backward
         with pytest.raises(F24.Ffn24Error) as e:
             F24.Context(256, 256, 256, F24.FFN24_TRAINING | extra, dtype=F24.FFN24_FP8_E4M3)
         assert e.value.code == -4
+    # a row-wise training context takes ffn24_bwd_rowwise only, and only after a forward
+    ctx = F24.Context(256, 256, 256, F24.FFN24_TRAINING | F24.FFN24_ROWWISE, dtype=F24.FFN24_FP8_E4M3)
+    z8 = torch.zeros((256, 256), dtype=torch.uint8, device="cuda"); s1 = torch.ones(256, dtype=torch.float32, device="cuda")
+    with pytest.raises(F24.Ffn24Error) as e:
+        ctx.ffn24_bwd_rowwise(z8, s1, z8, s1, z8, s1, z8, s1, z8, s1)
+    assert e.value.code == -5
+    ctx.set_row_scales(s1, s1, s1)
+    ctx.ffn24_fwd(z8, z8, None, z8)
+    with pytest.raises(F24.Ffn24Error) as e:
+        ctx.ffn24_bwd(z8)
+    assert e.value.code == -5
+    dX, dW1, dW2 = ctx.ffn24_bwd_rowwise(z8, s1, z8, s1, z8, s1, z8, s1, z8, s1)
+    torch.cuda.synchronize()
+    assert not dX.any() and not dW1.any() and not dW2.any()      # all-zero operands: zero gradients, scales 1, nothing divides by zero
+    assert bool((ctx.saved("sdz_t") == 1).all()) and bool((ctx.saved("sh_f") == 1).all())
+    ctx.close()
+    ctx = F24.Context(256, 256, 256, F24.FFN24_TRAINING, dtype=F24.FFN24_FP8_E4M3)
+    with pytest.raises(F24.Ffn24Error) as e:
+        ctx.ffn24_bwd_rowwise(z8, s1, z8, s1, z8, s1, z8, s1, z8, s1)      # not a row-wise context
+    assert e.value.code == -5
+    ctx.close()
     ctx = F24.Context(256, 256, 256, 0, dtype=F24.FFN24_FP8_E4M3)
     with pytest.raises(F24.Ffn24Error) as e:
         ctx.set_bwd_scales(1.0, 1.0)                         # not a training context
