@@ -709,6 +709,38 @@ def ffn24_bwd_fp8_rowwise_codes(fwd, dY8r, sdy_t, W2_8r, sw2_f, W1_8c, sw1_d, dY
     return out
 
 
+def ffn_bwd_fp8_rowwise_codes(fwd, dY8r, sdy_t, W2_8r, sw2_f, W1_8c, sw1_d, dY8c, sdy_d, X8c, sx_d, quantise_internal=True):
+    """Dense counterpart of ffn24_bwd_fp8_rowwise_codes (no masks): the backward of ffn_fwd_fp8_rowwise_codes with every GEMM
+    scaled row-wise.  Same operands from the caller; the internal tensors are quantised where they are made:
+      dH = sdy_t[t] sw2_f[f] (dY8r . W2_8r^T);  dZ = bf16(dH * 2 max(0, Z));
+      sdz_t[t] = max_f |dZ[t,f]| / 448;  dX = sdz_t[t] sw1_d[d] (e4m3(dZ / sdz_t) . W1_8c^T)
+      sh_f[f] = max_t H[t,f] / 448 on the bf16 activation;  sdz_f[f] = max_t |dZ[t,f]| / 448
+      dW2 = sh_f[f] sdy_d[d] (e4m3(H / sh_f)^T . dY8c);   dW1 = sx_d[d] sdz_f[f] (X8c^T . e4m3(dZ / sdz_f))
+    quantise_internal=False (pinning only) leaves dZ and H unrounded in all three GEMMs."""
+    dec = lambda c: E4M3_VALUES[np.ascontiguousarray(c, dtype=np.uint8)]
+    f64 = lambda v: np.asarray(v, dtype=np.float32).astype(np.float64)
+    dH = (dec(dY8r) @ dec(W2_8r).T) * f64(sdy_t)[:, None] * f64(sw2_f)[None, :]
+    dZ = dH * relu2_derivative(fwd["Z"])
+    Hq = np.asarray(fwd["Hq"], dtype=np.float32)
+    out = {"dH": dH, "dZ": dZ}
+    if quantise_internal:
+        dZ16 = round_bf16(dZ)
+        dZ8r_bits, sdz_t = quantise_rows_e4m3(dZ16)
+        dZ8c_bits_t, sdz_f = quantise_rows_e4m3(np.ascontiguousarray(dZ16.T))
+        H8c_bits_t, sh_f = quantise_rows_e4m3(np.ascontiguousarray(Hq.T))
+        dZr = dec(dZ8r_bits) * sdz_t.astype(np.float64)[:, None]
+        dZc = dec(dZ8c_bits_t).T * sdz_f.astype(np.float64)[None, :]
+        Hc = dec(H8c_bits_t).T * sh_f.astype(np.float64)[None, :]
+        out.update({"dZ16": dZ16, "sdz_t": sdz_t, "sdz_f": sdz_f, "sh_f": sh_f, "dZ8r_bits": dZ8r_bits, "H8_t_bits": H8c_bits_t, "dZ8_t_bits": dZ8c_bits_t})
+    else:
+        dZr = dZc = dZ
+        Hc = Hq.astype(np.float64)
+    out["dX"] = (dZr @ dec(W1_8c).T) * f64(sw1_d)[None, :]
+    out["dW2"] = (Hc.T @ dec(dY8c)) * f64(sdy_d)[None, :]
+    out["dW1"] = (dec(X8c).T * f64(sx_d)[:, None]) @ dZc
+    return out
+
+
 def quantise_rows_e4m3(x):
     """Row-wise e4m3 quantisation of a float matrix: s[r] = max|x[r,:]| / 448 (1 for an all-zero row), codes of x / s."""
     x = np.asarray(x, dtype=np.float32)

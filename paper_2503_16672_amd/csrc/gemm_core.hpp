@@ -35,7 +35,8 @@
 //   step 0: matrix ops; the LDS fragment reads of step 1 ride on them
 //   wait for the next stage's DMA, one workgroup barrier
 //   step 1: matrix ops; the DMA of the stage that reuses this buffer and the fragment reads of the next stage's
-//           step 0 ride on them
+//           step 0 ride on them -- the DMA instructions on every other slot only, and for the sparse stage (14 a wave) half
+//           of them on the even slots of the NEXT stage's step 0 (see dma_on_step1 below)
 //
 // Lane layouts of the matrix instructions (measured on gfx950 with one-hot operands):
 //   dense 32x32x16:  A lane l holds row l%32, k = 8*(l/32)..+7;  B lane l holds column l%32, same k;

@@ -925,3 +925,44 @@ def test_fp8_rowwise_backward_scale_equivariance():
     assert np.array_equal(c["dW2"][:, 3], 2 * a["dW2"][:, 3]) and np.array_equal(np.delete(c["dW2"], 3, 1), np.delete(a["dW2"], 3, 1))
     assert np.array_equal(c["dW1"][7], 2 * a["dW1"][7]) and np.array_equal(np.delete(c["dW1"], 7, 0), np.delete(a["dW1"], 7, 0))
     assert np.array_equal(c["dX"], a["dX"])
+
+
+def test_dense_fp8_rowwise_backward_reductions():
+    """(1) With one power-of-two scale per tensor and unrounded internal tensors the dense row-wise backward is the dense
+    per-tensor fp8 backward on the same codes (pinned against autograd above).  (2) Fig. 2 caption: with two of every four
+    hidden features switched off and tokens 1, 3 of every four zeroed neither 2:4 prune drops anything, and the 2:4
+    row-wise backward equals the dense one exactly -- scales, codes and all three gradients.  (3) each internal operand
+    quantised along its own axis by torch's cast."""
+    inp, f24, bw, fw = _fp8_rowwise_bwd_case(pow2_uniform=True)
+    fd = O.ffn_fwd_fp8_rowwise_codes(fw["X8"], fw["sx"], fw["W1_8"], fw["sw1"], inp["b1"], fw["W2_8"], fw["sw2"])
+    g = O.ffn_bwd_fp8_rowwise_codes(fd, **bw, quantise_internal=False)
+    sx, sw1, sw2, sdy = float(fw["sx"][0]), float(fw["sw1"][0]), float(fw["sw2"][0]), float(bw["sdy_t"][0])
+    fp = O.ffn_fwd_fp8_codes(fw["X8"], fw["W1_8"], inp["b1"], fw["W2_8"], sx, sw1, 1.0, sw2)
+    assert np.array_equal(fp["Z"], fd["Z"])
+    p = O.ffn_bwd_fp8_codes(fp, fw["X8"], fw["W1_8"], fw["W2_8"], bw["dY8r"], sx, sw1, 1.0, sw2, sdy, 1.0, quantise_dz=False)
+    assert np.allclose(g["dX"], p["dX"], rtol=1e-12, atol=1e-15) and np.allclose(g["dW1"], p["dW1"], rtol=1e-12, atol=1e-15)
+    dYv = O.e4m3_bits_to_f32(bw["dY8c"]).astype(np.float64) * sdy
+    assert np.allclose(g["dW2"], fd["Hq"].astype(np.float64).T @ dYv, rtol=1e-12, atol=1e-15) and np.count_nonzero(g["dX"]) > 100
+    # (2) the lossless case, with genuinely row-wise scales
+    inp, f24, bw, fw = _fp8_rowwise_bwd_case(T=32, D=16, F=64, sparsity=0.3)
+    b1 = inp["b1"].copy(); b1.reshape(-1, 4)[:, [0, 3]] = -1e9
+    b1 = np.minimum(b1, -1e-3)                                    # zero tokens then give zero activations
+    X8z = fw["X8"].copy(); X8z.reshape(-1, 4, X8z.shape[1])[:, [1, 3]] = 0
+    fs = O.ffn24_fwd_fp8_rowwise_codes(X8z, fw["sx"], fw["W1_8"], fw["sw1"], b1, fw["W2_8"], fw["sw2"])
+    fd = O.ffn_fwd_fp8_rowwise_codes(X8z, fw["sx"], fw["W1_8"], fw["sw1"], b1, fw["W2_8"], fw["sw2"])
+    gs, gd = O.ffn24_bwd_fp8_rowwise_codes(fs, **bw), O.ffn_bwd_fp8_rowwise_codes(fd, **bw)
+    assert np.count_nonzero(fd["Hq"]) > 20
+    for k in ("sdz_t", "sdz_f", "sh_f", "dX", "dW1", "dW2"):
+        assert np.array_equal(gs[k], gd[k]), k
+    # (the dense dZ has -0 where a negative dH meets a zero derivative, the masked one +0: equal as values)
+    assert np.array_equal(O.e4m3_bits_to_f32(gs["dZ8r_bits"]), O.e4m3_bits_to_f32(gd["dZ8r_bits"])) and np.count_nonzero(gd["dZ8r_bits"] & 0x7F) > 20
+    # (3)
+    inp, f24, bw, fw = _fp8_rowwise_bwd_case()
+    fd = O.ffn_fwd_fp8_rowwise_codes(fw["X8"], fw["sx"], fw["W1_8"], fw["sw1"], inp["b1"], fw["W2_8"], fw["sw2"])
+    g = O.ffn_bwd_fp8_rowwise_codes(fd, **bw); e = O.ffn_bwd_fp8_rowwise_codes(fd, **bw, quantise_internal=False)
+    cast = lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(g["dZ8r_bits"], cast(g["dZ16"] / g["sdz_t"][:, None])) and np.array_equal(g["dZ8_t_bits"], cast(g["dZ16"].T / g["sdz_f"][:, None]))
+    assert np.array_equal(g["H8_t_bits"], cast(fd["Hq"].T / g["sh_f"][:, None]))
+    assert np.array_equal(g["sh_f"], (fd["Hq"].max(axis=0) / np.float32(448)).astype(np.float32)) and ((g["H8_t_bits"]).max(axis=1) == 0x7E).all()
+    for k in ("dX", "dW1", "dW2"):
+        assert O.fro_rel_err(g[k], e[k]) <= 2.0 ** -4, k
