@@ -243,7 +243,7 @@ def main() -> int:
     ap.add_argument("--cpu-tokens", type=int, default=4096, help="token slice the CPU oracle is timed on (about 15 s of CPU work at the default workload)")
     ap.add_argument("--split", type=int, default=0, help="keep this many hidden features (multiple of 256, <= d_ff/4) out of the "
                     "feature-wise 2:4: split weight-gradient GEMMs (bf16 fwd+bwd workloads)")
-    ap.add_argument("--rowwise", action="store_true", help="fp8 workload with row-wise instead of per-tensor scales (2:4 FFN and dense baseline alike); with --fp8-bwd: forward and backward of the 2:4 FFN with every GEMM scaled row-wise (no dense baseline in that mode)")
+    ap.add_argument("--rowwise", action="store_true", help="fp8 workload with row-wise instead of per-tensor scales (2:4 FFN and dense baseline alike); with --fp8-bwd: forward and backward with every GEMM scaled row-wise, 2:4 FFN and dense baseline")
     ap.add_argument("--permute", action="store_true", help="run the bf16 workload with a fixed token permutation around the FFN")
     ap.add_argument("--telemetry", action="store_true", help="bf16 workloads: count sparsity and 2:4 drops while running (reported under \"telemetry\")")
     ap.add_argument("--split-sweep", action="store_true", help="time the weight-gradient stage over a range of split sizes")
@@ -271,13 +271,13 @@ def main() -> int:
     bwd = not args.fwd_only and (not fp8 or args.fp8_bwd)
     rowwise = fp8 and args.rowwise and not bwd
     rowwise_bwd = fp8 and args.rowwise and bwd     # row-wise scaling in every GEMM of the forward and the backward (2:4 FFN only)
-    no_dense = rowwise_bwd                         # the dense row-wise backward is not built: no baseline in this mode
+    no_dense = False
     if rowwise_bwd:
         inp = synth.make_inputs_fp8_rowwise(T, D, F, w.sparsity, w.seed)
         bwo = synth.make_bwd_operands_fp8_rowwise(T, D, F, w.sparsity, w.seed)
         dev = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2", "sx", "sw1", "sw2")}
         devb = {k: torch.from_numpy(v).cuda() for k, v in bwo.items()}
-        ctx = ffn24.Context(T, D, F, ffn24.FFN24_ROWWISE | ffn24.FFN24_TRAINING, dtype=ffn24.FFN24_FP8_E4M3)
+        ctx = ffn24.Context(T, D, F, ffn24.FFN24_ROWWISE | ffn24.FFN24_TRAINING | ffn24.FFN24_DENSE, dtype=ffn24.FFN24_FP8_E4M3)
         ctx.set_row_scales(dev["sx"], dev["sw1"], dev["sw2"])
     elif rowwise:
         inp = synth.make_inputs_fp8_rowwise(T, D, F, w.sparsity, w.seed)
@@ -323,13 +323,16 @@ def main() -> int:
         ctx.ffn24_fwd(dev["X"], W1a, b1, W2a, Y)
         if rowwise_bwd:
             ctx.ffn24_bwd_rowwise(devb["dY8r"], devb["sdy_t"], devb["dY8c"], devb["sdy_d"], devb["X8c"], devb["sx_d"], devb["W2_8r"], devb["sw2_f"],
-                                  devb["W1_8c"], devb["sw1_d"], grads)
+                                  devb["W1_8c"], devb["sw1_d"], out=grads)
         elif bwd:
             ctx.ffn24_bwd(dev["dY"], grads)
 
     def step_dense():
         ctx.ffn_fwd(dev["X"], W1a, b1, W2a, Y)
-        if bwd:
+        if rowwise_bwd:
+            ctx.ffn_bwd_rowwise(devb["dY8r"], devb["sdy_t"], devb["dY8c"], devb["sdy_d"], devb["X8c"], devb["sx_d"], devb["W2_8r"], devb["sw2_f"],
+                                devb["W1_8c"], devb["sw1_d"], out=grads)
+        elif bwd:
             ctx.ffn_bwd(dev["dY"], grads)
 
     if args.calib_copy:

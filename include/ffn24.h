@@ -87,7 +87,7 @@ FFN24_API int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F,
  * row-wise ones).  Saved tensors 0 and 1 are then bytes: Hc8 [T][F/2], meta [T][F/8]; tensor 7 is H8 [T][F].
  * ffn_fwd is the dense fp8 baseline of the forward.  With FFN24_TRAINING (not with FFN24_SPLIT: FFN24_ERR_DTYPE) the context
  * also supports ffn24_bwd -- and, with FFN24_DENSE, ffn_bwd -- in fp8, see ffn24_set_bwd_scales; with FFN24_ROWWISE as well
- * (then not with FFN24_DENSE) the backward is ffn24_bwd_rowwise. */
+ * the backwards are ffn24_bwd_rowwise and ffn_bwd_rowwise. */
 FFN24_API int ffn24_set_scales(ffn24_ctx* ctx, float sx, float sw1, float sh, float sw2);
 
 /* fp8 backward of an FFN24_FP8_E4M3 | FFN24_TRAINING context (paper abstract: FP8 in both the forwards and the
@@ -117,8 +117,8 @@ FFN24_API int ffn24_set_bwd_scales(ffn24_ctx* ctx, float sdy, float sdz);
  * 7 is then H8 [T][F] and tensor 11 the sh of that forward. */
 FFN24_API int ffn24_set_row_scales(ffn24_ctx* ctx, const float* sx, const float* sw1, const float* sw2);
 
-/* Backward of a row-wise-scaled forward: an FFN24_FP8_E4M3 | FFN24_ROWWISE | FFN24_TRAINING context (not with FFN24_DENSE or
- * FFN24_SPLIT), after ffn24_fwd.  Every GEMM of the backward is scaled row-wise, as the paper's precision recipe has it for all
+/* Backward of a row-wise-scaled forward: an FFN24_FP8_E4M3 | FFN24_ROWWISE | FFN24_TRAINING context (not with FFN24_SPLIT),
+ * after ffn24_fwd.  Every GEMM of the backward is scaled row-wise, as the paper's precision recipe has it for all
  * of its FP8 matrix multiplications (caption of the forward-speed-up figure; Sec. 2, the paragraph on the fused backward pointwise
  * kernel: it includes the transposition and the FP8 scaling): each operand carries one scale per index of its NON-reduced
  * dimension.  A tensor that enters two GEMMs with different reduced dimensions is therefore quantised twice, by the caller,
@@ -146,6 +146,15 @@ typedef struct {
   const void* W1_8c; const float* sw1_d;
 } ffn24_rowwise_bwd_operands;
 FFN24_API int ffn24_bwd_rowwise(ffn24_ctx* ctx, const ffn24_rowwise_bwd_operands* operands, void* dX, void* dW1, void* dW2, void* stream);
+/* The dense baseline of ffn24_bwd_rowwise: the backward of ffn_fwd on an FFN24_FP8_E4M3 | FFN24_ROWWISE | FFN24_TRAINING |
+ * FFN24_DENSE context (the paper's baseline recipe scales every FP8 GEMM row-wise), same operands, no masks:
+ *   dH = sdy_t[t] sw2_f[f] (dY8r . W2_8r^T);  dZ = bf16(dH * 2 sqrt(h)) at every position, h the bf16 activation the forward kept;
+ *   sdz_t[t] = max_f |dZ| / 448;  dX = bf16(sdz_t[t] sw1_d[d] (e4m3(dZ / sdz_t) . W1_8c^T));
+ *   sh_f[f] = max_t h / 448, sdz_f[f] = max_t |dZ| / 448;  dW2 = bf16(sh_f[f] sdy_d[d] (e4m3(H / sh_f)^T . dY8c));
+ *   dW1 = bf16(sx_d[d] sdz_f[f] (X8c^T . e4m3(dZ / sdz_f))).
+ * Saved tensors afterwards: 8 e4m3(dZ / sdz_t) [T][F] bytes, 13 sdz_t, 14 sh_f, 15 sdz_f, 17 the bf16 dZ [T][F], 18 / 19 the codes of
+ * the transposed activation and of the transposed dZ [F][T].  ffn_bwd refuses a row-wise context. */
+FFN24_API int ffn_bwd_rowwise(ffn24_ctx* ctx, const ffn24_rowwise_bwd_operands* operands, void* dX, void* dW1, void* dW2, void* stream);
 
 /* Fixed token permutation around the FFN (paper Sec. 2, "Optimization 2": features are correlated among consecutive
  * tokens, so the tokens are permuted before entering the FFN and shuffled back after).  perm_host is a HOST array
@@ -280,6 +289,8 @@ FFN24_API int ffn24_policy_use_sparse(ffn24_ctx* ctx, double min_sparsity, int* 
  *   11 per-token activation scale sh [T] fp32 (FFN24_ROWWISE)
  *   12 kept activation before quantisation [T][F/2] bf16 (fp8 contexts with FFN24_TRAINING or FFN24_ROWWISE)
  *   13 sdz_t [T], 14 sh_f [F], 15 sdz_f [F] fp32 and 16 the compressed dZ before quantisation [T][F/2] bf16 (after ffn24_bwd_rowwise)
+ *   17 the dense dZ before quantisation [T][F] bf16, 18 / 19 the codes of the transposed dense activation / dZ [F][T] (after ffn_bwd_rowwise;
+ *   18 / 19 also after ffn_bwd on an fp8 context)
  * ffn24_saved_bytes gives the size of tensor `which`; ffn24_copy_saved enqueues a copy of it into dst (device memory
  * of exactly that size, 16-byte aligned) in the row-major compressed form described at the top -- inside the context
  * the compressed tensors are kept in a tiled order that the sparse GEMM streams faster.  Returns FFN24_ERR_STATE if

@@ -54,6 +54,7 @@ struct ffn24_ctx {
   uint32_t* rowmax_dz; uint32_t* hmax; uint32_t* zmax;
   float* sdz_t; float* sh_f; float* sdz_f;
   void* W2rp; void* W1cp;
+  void* dZd16; void* Hdt16; void* dZdt16;   // dense row-wise backward: bf16 dZ [T][F], and the activation and dZ as [F][T]
   // workspace (device)
   void* Hc; uint8_t* meta; void* dZc; void* Hc_t; uint8_t* meta_t; void* dZc_t; void* Hdbg; void* Hd; void* dZd;
   void* W1t; void* W2t; void* Xt; void* dYt; void* Hd_t; void* dZd_t;   // K-contiguous copies of GEMM operands
@@ -98,7 +99,8 @@ int free_all(ffn24_ctx* c) {
   void* bufs[] = {c->Hc, c->meta, c->dZc, c->Hc_t, c->meta_t, c->dZc_t, c->Hdbg, c->Hd, c->dZd,
                   c->W1t, c->W2t, c->Xt, c->dYt, c->Hd_t, c->dZd_t, c->W2p, c->W1p,
                   c->nnz, c->row_of_feat, c->feat_of_row, c->Hdn_t, c->dZdn_t, c->dW1t, c->Hc16, c->meta16, c->rowmax, c->rsh, c->perm, c->Hd16,
-                  c->dZc16, c->Hct16, c->dZct16, c->meta_t16, c->rowmax_dz, c->hmax, c->zmax, c->sdz_t, c->sh_f, c->sdz_f, c->W2rp, c->W1cp};
+                  c->dZc16, c->Hct16, c->dZct16, c->meta_t16, c->rowmax_dz, c->hmax, c->zmax, c->sdz_t, c->sh_f, c->sdz_f, c->W2rp, c->W1cp,
+                  c->dZd16, c->Hdt16, c->dZdt16};
   for (void* b : bufs) if (b && hipFree(b) != hipSuccess) bad = 1;
   if (c->clk && hipFree(c->clk) != hipSuccess) bad = 1;
   if (c->tele && hipFree(c->tele) != hipSuccess) bad = 1;
@@ -183,7 +185,6 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
   if (dtype != FFN24_BF16 && dtype != FFN24_FP8_E4M3) return FFN24_ERR_DTYPE;
   const bool f8 = dtype == FFN24_FP8_E4M3;
   if (f8 && (flags & FFN24_TRAINING) && (flags & FFN24_SPLIT)) return FFN24_ERR_DTYPE;                      // fp8 training: no split
-  if (f8 && (flags & FFN24_TRAINING) && (flags & FFN24_ROWWISE) && (flags & FFN24_DENSE)) return FFN24_ERR_DTYPE;   // no dense row-wise backward
   if ((flags & FFN24_SPLIT) && !(flags & FFN24_TRAINING)) return FFN24_ERR_STATE;
   if ((flags & FFN24_ROWWISE) && !f8) return FFN24_ERR_DTYPE;
   if ((flags & FFN24_PERMUTE) && f8) return FFN24_ERR_DTYPE;
@@ -232,6 +233,8 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
          hipMalloc(reinterpret_cast<void**>(&c->zmax), 4 * (size_t)F) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->sdz_t), 4 * (size_t)T) == hipSuccess &&
          hipMalloc(reinterpret_cast<void**>(&c->sh_f), 4 * (size_t)F) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->sdz_f), 4 * (size_t)F) == hipSuccess &&
          hipMalloc(&c->W2rp, df) == hipSuccess && hipMalloc(&c->W1cp, df) == hipSuccess;
+  if (ok && (flags & FFN24_ROWWISE) && (flags & FFN24_TRAINING) && (flags & FFN24_DENSE))
+    ok = hipMalloc(&c->dZd16, 2 * tf) == hipSuccess && hipMalloc(&c->Hdt16, 2 * tf) == hipSuccess && hipMalloc(&c->dZdt16, 2 * tf) == hipSuccess;
   if (ok && (flags & FFN24_DENSE)) ok = hipMalloc(&c->Hd, es * tf) == hipSuccess;
   if (ok && (flags & FFN24_DENSE) && (flags & FFN24_ROWWISE)) ok = hipMalloc(&c->Hd16, 2 * tf) == hipSuccess;
   if (ok && (flags & FFN24_DENSE) && (flags & FFN24_TRAINING))
@@ -421,6 +424,8 @@ int ffn24_saved_bytes(ffn24_ctx* c, int which, int64_t* nbytes) {
     case 12: case 16: *nbytes = tf; break;
     case 13: *nbytes = 4 * c->T; break;
     case 14: case 15: *nbytes = 4 * c->F; break;
+    case 17: *nbytes = 2 * tf; break;
+    case 18: case 19: *nbytes = tf; break;
     default: return FFN24_ERR_SHAPE;
   }
   return FFN24_OK;
@@ -456,9 +461,18 @@ int ffn24_copy_saved(ffn24_ctx* c, int which, void* dst, int64_t dst_bytes, void
     case 14: src = c->sh_f; break;
     case 15: src = c->sdz_f; break;
     case 16: src = c->dZc16; break;
+    case 17: src = c->dZd16; break;
+    case 18: src = c->Hd_t; break;
+    case 19: src = c->dZd_t; break;
     default: src = c->Hc16; break;
   }
   if (!src) return FFN24_ERR_STATE;
+  if (which == 17)   // the dense row-wise backward's bf16 dZ [T][F]: dense bf16 panel form (64-byte pieces of 32 k)
+    return launch_unpanel(src, T, F / 32, 64, dst, s) ? FFN24_ERR_HIP : FFN24_OK;
+  if (which == 18 || which == 19) {   // the dense fp8 backward's transposed operands [F][T]: dense fp8 panel form (64-byte pieces of 64 k)
+    if (!c->f8) return FFN24_ERR_STATE;
+    return launch_unpanel(src, F, T / 64, 64, dst, s) ? FFN24_ERR_HIP : FFN24_OK;
+  }
   if (which == 12 || which == 16)   // bf16 kept values of an fp8 context: bf16 panel form (64-byte pieces of 64 k)
     return launch_unpanel(src, T, F / 64, 64, dst, s) ? FFN24_ERR_HIP : FFN24_OK;
   if (which >= 9) return hipMemcpyAsync(dst, src, (size_t)need, hipMemcpyDeviceToDevice, s) == hipSuccess ? FFN24_OK : FFN24_ERR_HIP;
@@ -706,11 +720,12 @@ int ffn_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const 
     // dense baseline with row-wise scales: up-projection (bf16 activations + row maxima), row-wise quantisation, dense GEMM
     if (launch_zero32(c->rowmax, (size_t)T, s)) return FFN24_ERR_HIP;
     { Timed t(c, KD_UP, s);
-      if (t.done(launch_up_relu2_f8_rowwise(c->W1t, X, b1, T, D, F, c->rsx, c->rsw1, c->Hd16, c->rowmax, s))) return FFN24_ERR_HIP; }
+      if (t.done(launch_up_relu2_f8_rowwise(c->W1t, X, b1, T, D, F, c->rsx, c->rsw1, c->Hd16, c->rowmax, c->Hdt16, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_QUANT, s);
       if (t.done(launch_quantise_rows_dense(c->Hd16, c->rowmax, T, F, c->Hd, c->rsh, s))) return FFN24_ERR_HIP; }
     { Timed t(c, KD_DOWN, s);
       if (t.done(launch_dense_rowmajor_f8_rowwise(c->Hd, c->W2t, T, D, F, c->rsh, c->rsw2, Y, s))) return FFN24_ERR_HIP; }
+    if (c->flags & FFN24_TRAINING) { c->X = X; c->have_fwd_dense = 1; }
     return FFN24_OK;
   }
   if (c->f8) {
@@ -731,9 +746,44 @@ int ffn_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const 
   return FFN24_OK;
 }
 
+int ffn_bwd_rowwise(ffn24_ctx* c, const ffn24_rowwise_bwd_operands* op, void* dX, void* dW1, void* dW2, void* stream) {
+  if (!c || !op) return FFN24_ERR_NULL;
+  if (!c->f8 || !(c->flags & FFN24_ROWWISE) || !(c->flags & FFN24_TRAINING) || !(c->flags & FFN24_DENSE) || !c->have_fwd_dense) return FFN24_ERR_STATE;
+  int rc = check_device(c);
+  if (rc) return rc;
+  rc = check_ptrs({op->dY8r, op->sdy_t, op->dY8c, op->sdy_d, op->X8c, op->sx_d, op->W2_8r, op->sw2_f, op->W1_8c, op->sw1_d, dX, dW1, dW2});
+  if (rc) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int T = (int)c->T, D = (int)c->D, F = (int)c->F;
+  { Timed t(c, K_PANEL_W, s);
+    int rc1 = launch_panelise8(op->W2_8r, F, D, c->W2rp, 0, s);
+    if (t.done(rc1 ? rc1 : launch_panelise8(op->W1_8c, D, F, c->W1cp, 1, s))) return FFN24_ERR_HIP; }
+  if (launch_zero32(c->rowmax_dz, (size_t)T, s) || launch_zero32(c->hmax, (size_t)F, s) || launch_zero32(c->zmax, (size_t)F, s)) return FFN24_ERR_HIP;
+  { Timed t(c, KD_DH, s);
+    if (t.done(launch_dh_drelu_f8_rowwise(c->W2rp, op->dY8r, c->Hd16, T, D, F, op->sw2_f, op->sdy_t, c->dZd16, c->dZdt16, c->rowmax_dz, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_QUANT_DZ, s);
+    if (t.done(launch_quantise_rows_dense(c->dZd16, c->rowmax_dz, T, F, c->dZd, c->sdz_t, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_DX, s);
+    if (t.done(launch_dense_rowmajor_f8_rowwise(c->dZd, c->W1cp, T, D, F, c->sdz_t, op->sw1_d, dX, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_QUANT_T, s);      // per-feature maxima of the two transposed bf16 operands, then their quantisation
+    int rc1 = launch_rowmax_dense(c->Hdt16, F, T, c->hmax, s);
+    if (!rc1) rc1 = launch_rowmax_dense(c->dZdt16, F, T, c->zmax, s);
+    if (!rc1) rc1 = launch_quantise_rows_dense(c->Hdt16, c->hmax, F, T, c->Hd_t, c->sh_f, s);
+    if (t.done(rc1 ? rc1 : launch_quantise_rows_dense(c->dZdt16, c->zmax, F, T, c->dZd_t, c->sdz_f, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, K_TR_ACT, s);
+    int rc1 = launch_transpose8(op->dY8c, T, D, c->dYt, 2, nullptr, 0, s);
+    if (t.done(rc1 ? rc1 : launch_transpose8(op->X8c, T, D, c->Xt, 2, nullptr, 0, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_DW2, s);
+    if (t.done(launch_dense_rowmajor_f8_rowwise(c->Hd_t, c->dYt, F, D, T, c->sh_f, op->sdy_d, dW2, s))) return FFN24_ERR_HIP; }
+  { Timed t(c, KD_DW1, s);
+    if (t.done(launch_dense_colmajor_f8_rowwise(c->dZd_t, c->Xt, F, D, T, c->sdz_f, op->sx_d, dW1, s))) return FFN24_ERR_HIP; }
+  return FFN24_OK;
+}
+
 int ffn_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void* stream) {
   if (!c) return FFN24_ERR_NULL;
   if (!(c->flags & FFN24_DENSE) || !(c->flags & FFN24_TRAINING) || !c->have_fwd_dense) return FFN24_ERR_STATE;
+  if (c->flags & FFN24_ROWWISE) return FFN24_ERR_STATE;   // a row-wise context takes ffn_bwd_rowwise
   int rc = check_device(c);
   if (rc) return rc;
   rc = check_ptrs({dY, dX, dW1, dW2});

@@ -503,19 +503,23 @@ struct EpiPrune24Rw {
 // both sides use row-wise scales): z = sx[t] sw1[f] acc + b1[f];  h = bf16(max(0, z)^2), every one of them stored, as the
 // bf16 [T][F] operand in dense panel form (64-byte pieces of 32 k); rowmax[t] is raised to the row's largest word.  A
 // streaming kernel then quantises each row with sh[t] = rowmax[t] / 448.
+// Ht16 (optional, a training context): the same values once more as the bf16 [F][T] operand (dense panel form, K = T) that the
+// backward quantises per hidden feature for its dW2 GEMM.
 struct EpiRelu2Rw {
-  struct Args { __bf16* H16; const float* b1; int F; const float* sx; const float* sw1; uint32_t* rowmax; };
+  struct Args { __bf16* H16; const float* b1; int F; const float* sx; const float* sw1; uint32_t* rowmax; __bf16* Ht16; int T; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
     LaneVec64 lb, lw;
     lb.load(e.b1, m_lane, 0.f);
     lw.load(e.sw1, m_lane, 1.f);
+    uint32_t mx[4] = {0u, 0u, 0u, 0u};
+    float sxt[4];
 #pragma unroll
-    for (int ni = 0; ni < 4; ni++) {
-      const int t = n_lane + ni;
-      const float sxt = e.sx[t];
-      uint32_t mx = 0u;
+    for (int ni = 0; ni < 4; ni++) sxt[ni] = e.sx[n_lane + ni];
 #pragma unroll
-      for (int mi = 0; mi < 4; mi++) {
+    for (int mi = 0; mi < 4; mi++) {
+#pragma unroll
+      for (int ni = 0; ni < 4; ni++) {
+        const int t = n_lane + ni;
         int f = m_lane + 16 * mi;
         __bf16* row = e.H16 + a24_piece(t, f >> 5, e.F >> 5) * 32 + (f & 31);
 #pragma unroll
@@ -524,16 +528,77 @@ struct EpiRelu2Rw {
 #pragma unroll
           for (int d = 0; d < 4; d++) {
             int i = 16 * mi + 8 * q + 2 * d;
-            float r0 = fmaxf(acc[mi][ni][8 * q + 2 * d] * (sxt * lw.at(i)) + lb.at(i), 0.f);
-            float r1 = fmaxf(acc[mi][ni][8 * q + 2 * d + 1] * (sxt * lw.at(i + 1)) + lb.at(i + 1), 0.f);
+            float r0 = fmaxf(acc[mi][ni][8 * q + 2 * d] * (sxt[ni] * lw.at(i)) + lb.at(i), 0.f);
+            float r1 = fmaxf(acc[mi][ni][8 * q + 2 * d + 1] * (sxt[ni] * lw.at(i + 1)) + lb.at(i + 1), 0.f);
+            acc[mi][ni][8 * q + 2 * d] = r0 * r0;
+            acc[mi][ni][8 * q + 2 * d + 1] = r1 * r1;
             o[d] = pack_bf16x2(r0 * r0, r1 * r1);
-            mx = max(mx, max(o[d] & 0xFFFFu, o[d] >> 16));
+            mx[ni] = max(mx[ni], max(o[d] & 0xFFFFu, o[d] >> 16));
           }
           *reinterpret_cast<u32x4*>(row + 8 * q) = o;
         }
       }
-      if (mx) atomicMax(e.rowmax + t, mx);
+      if (e.Ht16) {
+#pragma unroll
+        for (int v = 0; v < 16; v++) {
+          u32x2 o;
+          o[0] = pack_bf16x2(acc[mi][0][v], acc[mi][1][v]);
+          o[1] = pack_bf16x2(acc[mi][2][v], acc[mi][3][v]);
+          *reinterpret_cast<u32x2*>(e.Ht16 + a24_piece(m_lane + 16 * mi + v, n_lane >> 5, e.T >> 5) * 32 + (n_lane & 31)) = o;
+        }
+      }
     }
+#pragma unroll
+    for (int ni = 0; ni < 4; ni++) if (mx[ni]) atomicMax(e.rowmax + n_lane + ni, mx[ni]);
+  }
+};
+
+// Dense fp8 backward with ROW-WISE scaling, pointwise part: dH = rs[f] cs[t] acc (rs = the scale of each hidden feature's row of W2,
+// cs = the scale of each token's row of dY);  dZ = bf16(dH * 2 sqrt(h)), h the bf16 activation the dense forward kept (H16, dense
+// bf16 panel form), at every position.  Stored in bf16 twice, as the [T][F] and the [F][T] operand (dense panel forms) that
+// streaming kernels then quantise per token and per hidden feature; rowmax[t] is raised to the largest magnitude word of the row.
+struct EpiDReluRw {
+  struct Args { const __bf16* H16; __bf16* dZ16; __bf16* dZt16; int F; int T; const float* rs; const float* cs; uint32_t* rowmax; };
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+    LaneVec64 lr;
+    lr.load(e.rs, m_lane, 1.f);
+    uint32_t mx[4] = {0u, 0u, 0u, 0u};
+    float cs[4];
+#pragma unroll
+    for (int ni = 0; ni < 4; ni++) cs[ni] = e.cs[n_lane + ni];
+#pragma unroll
+    for (int mi = 0; mi < 4; mi++) {
+#pragma unroll
+      for (int ni = 0; ni < 4; ni++) {
+        int f = m_lane + 16 * mi;
+        size_t o = a24_piece(n_lane + ni, f >> 5, e.F >> 5) * 32 + (f & 31);
+#pragma unroll
+        for (int q = 0; q < 2; q++) {
+          u32x4 h = *reinterpret_cast<const u32x4*>(e.H16 + o + 8 * q);
+          u32x4 r;
+#pragma unroll
+          for (int d = 0; d < 4; d++) {
+            int i = 16 * mi + 8 * q + 2 * d;
+            float g0 = 2.f * __builtin_amdgcn_sqrtf(bf16_lo_to_f32(h[d]));
+            float g1 = 2.f * __builtin_amdgcn_sqrtf(bf16_hi_to_f32(h[d]));
+            acc[mi][ni][8 * q + 2 * d] *= (cs[ni] * lr.at(i)) * g0;
+            acc[mi][ni][8 * q + 2 * d + 1] *= (cs[ni] * lr.at(i + 1)) * g1;
+            r[d] = pack_bf16x2(acc[mi][ni][8 * q + 2 * d], acc[mi][ni][8 * q + 2 * d + 1]);
+            mx[ni] = max(mx[ni], max(r[d] & 0x7FFFu, (r[d] >> 16) & 0x7FFFu));
+          }
+          *reinterpret_cast<u32x4*>(e.dZ16 + o + 8 * q) = r;
+        }
+      }
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        u32x2 o;
+        o[0] = pack_bf16x2(acc[mi][0][v], acc[mi][1][v]);
+        o[1] = pack_bf16x2(acc[mi][2][v], acc[mi][3][v]);
+        *reinterpret_cast<u32x2*>(e.dZt16 + a24_piece(m_lane + 16 * mi + v, n_lane >> 5, e.T >> 5) * 32 + (n_lane & 31)) = o;
+      }
+    }
+#pragma unroll
+    for (int ni = 0; ni < 4; ni++) if (mx[ni]) atomicMax(e.rowmax + n_lane + ni, mx[ni]);
   }
 };
 

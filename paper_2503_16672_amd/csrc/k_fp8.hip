@@ -68,9 +68,9 @@ int launch_up_prune24_f8_rowwise(const void* W1t8, const void* X8, const float* 
 }
 
 int launch_up_relu2_f8_rowwise(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, const float* sx, const float* sw1,
-                               void* H16, uint32_t* rowmax, hipStream_t s) {
+                               void* H16, uint32_t* rowmax, void* Ht16, hipStream_t s) {
   GemmArgs g{W1t8, nullptr, X8, F, T, D, 1};
-  EpiRelu2Rw::Args ea{static_cast<__bf16*>(H16), b1, F, sx, sw1, rowmax};
+  EpiRelu2Rw::Args ea{static_cast<__bf16*>(H16), b1, F, sx, sw1, rowmax, static_cast<__bf16*>(Ht16), T};
   return launch_gemm<false, EpiRelu2Rw, true>(g, ea, s);
 }
 
@@ -101,6 +101,21 @@ int launch_sp_colmajor_f8_rowwise(const void* vals8, const uint8_t* meta, const 
   GemmArgs g{vals8, meta, B8, M, N, K, 1, nullptr, 1};
   EpiColMajorRowCol::Args ea{static_cast<__bf16*>(Ct), M, rs, cs};
   return launch_gemm<true, EpiColMajorRowCol, true>(g, ea, s);
+}
+
+// dense row-wise-scaled backward: the dH GEMM with the pointwise part fused (bf16 dZ as [T][F] and [F][T], row maxima), and the
+// dense GEMM with the transposing store scaled per row and per column
+int launch_dh_drelu_f8_rowwise(const void* W2rp8, const void* dY8r, const void* H16, int T, int D, int F, const float* sw2_f, const float* sdy_t,
+                               void* dZ16, void* dZt16, uint32_t* rowmax, hipStream_t s) {
+  GemmArgs g{W2rp8, nullptr, dY8r, F, T, D, 1};
+  EpiDReluRw::Args ea{static_cast<const __bf16*>(H16), static_cast<__bf16*>(dZ16), static_cast<__bf16*>(dZt16), F, T, sw2_f, sdy_t, rowmax};
+  return launch_gemm<false, EpiDReluRw, true>(g, ea, s);
+}
+
+int launch_dense_colmajor_f8_rowwise(const void* A8, const void* B8, int M, int N, int K, const float* rs, const float* cs, void* Ct, hipStream_t s) {
+  GemmArgs g{A8, nullptr, B8, M, N, K, 1, nullptr, 1};
+  EpiColMajorRowCol::Args ea{static_cast<__bf16*>(Ct), M, rs, cs};
+  return launch_gemm<false, EpiColMajorRowCol, true>(g, ea, s);
 }
 
 }  // namespace ffn24

@@ -709,6 +709,33 @@ __global__ void __launch_bounds__(256) quantise_rows_dense_kernel(const u32x4* _
   }
 }
 
+// Largest magnitude word of every row of a bf16 matrix [R][C] in dense panel form (64-byte pieces of 32 k): rmax[r] is raised
+// with an atomic (the caller zeroes it).  A workgroup takes one block of 256 rows (one row per work item, so its loads of a
+// panel are one contiguous 16 KiB run) and a slice of the panels.
+constexpr int ROWMAX_SLICES = 32;
+__global__ void __launch_bounds__(256) rowmax_dense_kernel(const u32x4* __restrict__ X16, int R, int C, uint32_t* __restrict__ rmax) {
+  const int np = C >> 5;
+  const int per = (np + ROWMAX_SLICES - 1) / ROWMAX_SLICES;
+  const int k0 = blockIdx.y * per, k1 = min(np, k0 + per);
+  const size_t base = (size_t)blockIdx.x * np * 256 + threadIdx.x;
+  uint32_t m = 0u;
+  for (int kp = k0; kp < k1; kp++) {
+    const u32x4* p = X16 + (base + (size_t)kp * 256) * 4;
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+      u32x4 v = ld_stream(p + c);
+#pragma unroll
+      for (int d = 0; d < 4; d++) m = max(m, max(v[d] & 0x7FFFu, (v[d] >> 16) & 0x7FFFu));
+    }
+  }
+  if (m) atomicMax(rmax + blockIdx.x * 256 + threadIdx.x, m);
+}
+
+int launch_rowmax_dense(const void* X16, int R, int C, uint32_t* rmax, hipStream_t s) {
+  hipLaunchKernelGGL(rowmax_dense_kernel, dim3(R / 256, ROWMAX_SLICES), dim3(256), 0, s, static_cast<const u32x4*>(X16), R, C, rmax);
+  return (int)hipGetLastError();
+}
+
 int launch_quantise_rows_dense(const void* H16, const uint32_t* rowmax, int T, int F, void* H8, float* sh, hipStream_t s) {
   size_t n = (size_t)T * (F >> 6);
   size_t blocks = (n + 255) / 256;

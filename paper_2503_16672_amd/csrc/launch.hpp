@@ -105,8 +105,16 @@ int launch_up_prune24_f8_rowwise(const void* W1t8, const void* X8, const float* 
                                  void* Hc16, uint8_t* meta16, void* Hdbg, uint32_t* rowmax, hipStream_t s);
 // the dense row-wise-scaled baseline: up-projection writing every activation as bf16 (dense panel form) and raising rowmax;
 // quantise_rows_dense turns them into e4m3 (dense fp8 panel form) with sh[t] = rowmax[t] / 448; dense GEMM with sh[t] sw2[n]
+// (Ht16, may be NULL: the activation once more as the bf16 [F][T] operand, dense panel form)
 int launch_up_relu2_f8_rowwise(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, const float* sx, const float* sw1,
-                               void* H16, uint32_t* rowmax, hipStream_t s);
+                               void* H16, uint32_t* rowmax, void* Ht16, hipStream_t s);
+// dense row-wise-scaled backward: dH GEMM with the derivative fused, bf16 dZ out as [T][F] and [F][T] (dense panel forms) and
+// rowmax[t]; per-row maxima of a bf16 dense-panel matrix (rmax zeroed by the caller); dense GEMM with the transposing store and a
+// scale per row and per column
+int launch_dh_drelu_f8_rowwise(const void* W2rp8, const void* dY8r, const void* H16, int T, int D, int F, const float* sw2_f, const float* sdy_t,
+                               void* dZ16, void* dZt16, uint32_t* rowmax, hipStream_t s);
+int launch_rowmax_dense(const void* X16, int R, int C, uint32_t* rmax, hipStream_t s);
+int launch_dense_colmajor_f8_rowwise(const void* A8, const void* B8, int M, int N, int K, const float* rs, const float* cs, void* Ct, hipStream_t s);
 int launch_quantise_rows_dense(const void* H16, const uint32_t* rowmax, int T, int F, void* H8, float* sh, hipStream_t s);
 int launch_dense_rowmajor_f8_rowwise(const void* A8, const void* B8, int M, int N, int K, const float* rs, const float* cs, void* C, hipStream_t s);
 int launch_quantise_rows(const void* Hc16, const uint8_t* meta16, const uint32_t* rowmax, int T, int F, void* Hc8, uint8_t* meta8, float* sh, hipStream_t s);

@@ -25,7 +25,7 @@ FFN24_PERMUTE = 32
 FFN24_TELEMETRY = 64
 
 EXPORTS = (
-    "ffn24_ctx_create", "ffn24_ctx_destroy", "ffn24_set_scales", "ffn24_set_bwd_scales", "ffn24_set_row_scales", "ffn24_set_token_permutation", "ffn24_set_split", "sparsify24", "sparsify24_quantise", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd", "ffn24_bwd_rowwise",
+    "ffn24_ctx_create", "ffn24_ctx_destroy", "ffn24_set_scales", "ffn24_set_bwd_scales", "ffn24_set_row_scales", "ffn24_set_token_permutation", "ffn24_set_split", "sparsify24", "sparsify24_quantise", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd", "ffn24_bwd_rowwise", "ffn_bwd_rowwise",
     "ffn_fwd", "ffn_bwd", "ffn24_prepare_weights", "ffn24_get_telemetry", "ffn24_policy_use_sparse", "ffn24_saved_bytes", "ffn24_copy_saved", "ffn24_set_profiling", "ffn24_kernel_ms", "ffn24_strerror",
     "ffn24_static_scratch_needed", "ffn24_fwd_static", "ffn24_kernel_mhz", "ffn24_probe_mfma_rate", "ffn24_probe_gemm", "ffn24_probe_copy",
 )
@@ -66,6 +66,7 @@ def lib() -> ctypes.CDLL:
         L.ffn24_set_token_permutation.argtypes = [vp, vp]
         L.ffn24_set_row_scales.argtypes = [vp, vp, vp, vp]
         L.ffn24_bwd_rowwise.argtypes = [vp, ctypes.POINTER(RowwiseBwdOperands), vp, vp, vp, vp]
+        L.ffn_bwd_rowwise.argtypes = [vp, ctypes.POINTER(RowwiseBwdOperands), vp, vp, vp, vp]
         L.sparsify24.argtypes = [vp, i64, i64, ci, vp, vp, vp]
         L.sparsify24_quantise.argtypes = [vp, i64, i64, ctypes.c_float, vp, vp, vp]
         L.sparsify24_featurewise.argtypes = [vp, vp, vp, i64, i64, vp, vp, vp, vp]
@@ -336,7 +337,11 @@ class Context:
     def ffn_bwd(self, dY, out=None):
         return self._bwd(lib().ffn_bwd, "ffn_bwd", dY, out)
 
-    def ffn24_bwd_rowwise(self, dY8r, sdy_t, dY8c, sdy_d, X8c, sx_d, W2_8r, sw2_f, W1_8c, sw1_d, out=None):
+    def ffn_bwd_rowwise(self, *operands, out=None):
+        """Dense baseline of ffn24_bwd_rowwise (see ffn_bwd_rowwise in the header); same operands."""
+        return self.ffn24_bwd_rowwise(*operands, out=out, _fn="ffn_bwd_rowwise")
+
+    def ffn24_bwd_rowwise(self, dY8r, sdy_t, dY8c, sdy_d, X8c, sx_d, W2_8r, sw2_f, W1_8c, sw1_d, out=None, _fn="ffn24_bwd_rowwise"):
         """Backward of a row-wise-scaled forward (see ffn24_bwd_rowwise in the header): e4m3 codes (uint8) and fp32 scale vectors."""
         dev = dY8r.device
         if out is None:
@@ -351,7 +356,7 @@ class Context:
                                  (dW2, (self.F, self.D), _BF16, "dW2")):
             _expect(t, shape, el, nm)
         ops = RowwiseBwdOperands(*(_ptr(t) for t in (dY8r, sdy_t, dY8c, sdy_d, X8c, sx_d, W2_8r, sw2_f, W1_8c, sw1_d)))
-        _check(lib().ffn24_bwd_rowwise(self._h, ctypes.byref(ops), _ptr(dX), _ptr(dW1), _ptr(dW2), _stream()), "ffn24_bwd_rowwise")
+        _check(getattr(lib(), _fn)(self._h, ctypes.byref(ops), _ptr(dX), _ptr(dW1), _ptr(dW2), _stream()), _fn)
         return dX, dW1, dW2
 
     _SAVED = {"Hc": (0, torch.bfloat16, lambda T, F: (T, F // 2)), "meta": (1, torch.uint8, lambda T, F: (T, F // 8)),
@@ -362,12 +367,14 @@ class Context:
               "nnz": (9, torch.int32, lambda T, F: (F,)), "feat_of_row": (10, torch.int32, lambda T, F: (F,)),
               "sh": (11, torch.float32, lambda T, F: (T,)), "Hc16": (12, torch.bfloat16, lambda T, F: (T, F // 2)),
               "sdz_t": (13, torch.float32, lambda T, F: (T,)), "sh_f": (14, torch.float32, lambda T, F: (F,)),
-              "sdz_f": (15, torch.float32, lambda T, F: (F,)), "dZc16": (16, torch.bfloat16, lambda T, F: (T, F // 2))}
+              "sdz_f": (15, torch.float32, lambda T, F: (F,)), "dZc16": (16, torch.bfloat16, lambda T, F: (T, F // 2)),
+              "dZ16_dense": (17, torch.bfloat16, lambda T, F: (T, F)), "H_dense_t": (18, torch.uint8, lambda T, F: (F, T)),
+              "dZ_dense_t": (19, torch.uint8, lambda T, F: (F, T))}
 
     def saved(self, name: str) -> torch.Tensor:
         """Row-major copy of a saved tensor of the context (enqueued on the current stream)."""
         which, dtype, shape_fn = self._SAVED[name]
-        if self.dtype == FFN24_FP8_E4M3 and dtype == torch.bfloat16 and name not in ("H_dump", "Hc16", "dZc16"):
+        if self.dtype == FFN24_FP8_E4M3 and dtype == torch.bfloat16 and name not in ("H_dump", "Hc16", "dZc16", "dZ16_dense"):
             dtype = torch.uint8      # e4m3 codes
         n = ctypes.c_int64()
         _check(lib().ffn24_saved_bytes(self._h, which, ctypes.byref(n)), "ffn24_saved_bytes")

@@ -912,10 +912,9 @@ def test_ffn24_bwd_fp8_full_size_sampled(F24):
 
 
 def test_fp8_context_rules(F24):
-    for extra in (F24.FFN24_SPLIT, F24.FFN24_ROWWISE | F24.FFN24_DENSE):      # fp8 training: no split, no dense row-wise backward
-        with pytest.raises(F24.Ffn24Error) as e:
-            F24.Context(256, 256, 256, F24.FFN24_TRAINING | extra, dtype=F24.FFN24_FP8_E4M3)
-        assert e.value.code == -4
+    with pytest.raises(F24.Ffn24Error) as e:                 # fp8 training: no split
+        F24.Context(256, 256, 256, F24.FFN24_TRAINING | F24.FFN24_SPLIT, dtype=F24.FFN24_FP8_E4M3)
+    assert e.value.code == -4
     # a row-wise training context takes ffn24_bwd_rowwise only, and only after a forward
     ctx = F24.Context(256, 256, 256, F24.FFN24_TRAINING | F24.FFN24_ROWWISE, dtype=F24.FFN24_FP8_E4M3)
     z8 = torch.zeros((256, 256), dtype=torch.uint8, device="cuda"); s1 = torch.ones(256, dtype=torch.float32, device="cuda")
@@ -932,10 +931,25 @@ def test_fp8_context_rules(F24):
     assert not dX.any() and not dW1.any() and not dW2.any()      # all-zero operands: zero gradients, scales 1, nothing divides by zero
     assert bool((ctx.saved("sdz_t") == 1).all()) and bool((ctx.saved("sh_f") == 1).all())
     ctx.close()
-    ctx = F24.Context(256, 256, 256, F24.FFN24_TRAINING, dtype=F24.FFN24_FP8_E4M3)
+    ctx = F24.Context(256, 256, 256, F24.FFN24_TRAINING | F24.FFN24_DENSE, dtype=F24.FFN24_FP8_E4M3)
+    for fn in (ctx.ffn24_bwd_rowwise, ctx.ffn_bwd_rowwise):
+        with pytest.raises(F24.Ffn24Error) as e:
+            fn(z8, s1, z8, s1, z8, s1, z8, s1, z8, s1)       # not a row-wise context
+        assert e.value.code == -5
+    ctx.close()
+    ctx = F24.Context(256, 256, 256, F24.FFN24_TRAINING | F24.FFN24_ROWWISE | F24.FFN24_DENSE, dtype=F24.FFN24_FP8_E4M3)
+    ctx.set_row_scales(s1, s1, s1)
+    ctx.ffn24_fwd(z8, z8, None, z8)
     with pytest.raises(F24.Ffn24Error) as e:
-        ctx.ffn24_bwd_rowwise(z8, s1, z8, s1, z8, s1, z8, s1, z8, s1)      # not a row-wise context
+        ctx.ffn_bwd_rowwise(z8, s1, z8, s1, z8, s1, z8, s1, z8, s1)        # the last forward was the 2:4 one
     assert e.value.code == -5
+    ctx.ffn_fwd(z8, z8, None, z8)
+    with pytest.raises(F24.Ffn24Error) as e:
+        ctx.ffn_bwd(z8)
+    assert e.value.code == -5
+    dX, dW1, dW2 = ctx.ffn_bwd_rowwise(z8, s1, z8, s1, z8, s1, z8, s1, z8, s1)
+    torch.cuda.synchronize()
+    assert not dX.any() and not dW1.any() and not dW2.any()
     ctx.close()
     ctx = F24.Context(256, 256, 256, 0, dtype=F24.FFN24_FP8_E4M3)
     with pytest.raises(F24.Ffn24Error) as e:
@@ -1248,6 +1262,87 @@ def _fp8_rowwise_bwd_case(F24, T, D, Fh, sparsity, seed, rows=None, gsel=None):
     assert max(e_dw2, e_dw1, e_dw2_raw, e_dw1_raw, f_dw2_raw, f_dw1_raw) <= TOL_FP8
     assert np.count_nonzero(Hm) < np.count_nonzero(H24_g) or T * Fh > (1 << 24)                  # the second prune drops something
     ctx.close()
+
+
+def _fp8_rowwise_dense_bwd_case(F24, T, D, Fh, sparsity, seed, rows=None, fsel=None):
+    """The dense row-wise-scaled fp8 baseline, forward + backward, staged like the 2:4 one: every quantisation step bit-exact from
+    the GPU's own upstream tensors, the GEMMs against the oracle's arithmetic on the GPU's own operands, and from the raw inputs."""
+    inp = synth.make_inputs_fp8_rowwise(T, D, Fh, sparsity, seed)
+    bw = synth.make_bwd_operands_fp8_rowwise(T, D, Fh, sparsity, seed)
+    d = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2", "sx", "sw1", "sw2")}
+    db = {k: torch.from_numpy(v).cuda() for k, v in bw.items()}
+    b1 = torch.from_numpy(inp["b1"]).cuda()
+    ctx = F24.Context(T, D, Fh, F24.FFN24_ROWWISE | F24.FFN24_TRAINING | F24.FFN24_DENSE | F24.FFN24_DEBUG_DUMP_H, dtype=F24.FFN24_FP8_E4M3)
+    ctx.set_row_scales(d["sx"], d["sw1"], d["sw2"])
+    ops = (db["dY8r"], db["sdy_t"], db["dY8c"], db["sdy_d"], db["X8c"], db["sx_d"], db["W2_8r"], db["sw2_f"], db["W1_8c"], db["sw1_d"])
+    # the activation itself (bf16, before quantisation) comes from the 2:4 forward's dump: same up-projection arithmetic
+    ctx.ffn24_fwd(d["X"], d["W1"], b1, d["W2"])
+    Hd_all = ctx.saved("H_dump")
+    Y = ctx.ffn_fwd(d["X"], d["W1"], b1, d["W2"])
+    dX, dW1, dW2 = ctx.ffn_bwd_rowwise(*ops)
+    torch.cuda.synchronize()
+    dec = lambda c: O.e4m3_bits_to_f32(c).astype(np.float64)
+    s64 = lambda v: np.asarray(v, dtype=np.float32).astype(np.float64)
+    q448 = lambda amax: np.where(amax > 0, amax / np.float32(448.0), np.float32(1.0)).astype(np.float32)
+    rsel = np.arange(T) if rows is None else rows
+    rs_t = torch.from_numpy(rsel).cuda()
+    dZ16_all, dZ8_all = ctx.saved("dZ16_dense"), ctx.saved("dZ_dense")
+    torch.cuda.synchronize()
+    Hq = f64(Hd_all[rs_t]).astype(np.float32); dZ16 = f64(dZ16_all[rs_t]).astype(np.float32); dZ8 = dZ8_all[rs_t].cpu().numpy()
+    sdz_t = ctx.saved("sdz_t")[rs_t].cpu().numpy()
+    # ---- token rows: dZ (bf16) staged on the GPU's own activation, then its per-token scale and codes bit-exact, then dX
+    dH = (dec(bw["dY8r"][rsel]) @ dec(bw["W2_8r"]).T) * s64(bw["sdy_t"][rsel])[:, None] * s64(bw["sw2_f"])[None, :]
+    dZ_st = O.round_bf16(dH * O.relu2_derivative_from_stored_activation(Hq))
+    e_dz = O.max_rel_err(dZ16, dZ_st); f_dz = O.fro_rel_err(dZ16, dZ_st)
+    assert np.array_equal(sdz_t, q448(np.abs(dZ16).max(axis=1)))
+    assert np.array_equal(dZ8 & 0x7F, O.f32_to_e4m3_bits(dZ16 / sdz_t[:, None]) & 0x7F) and np.array_equal(dec(dZ8), dec(O.f32_to_e4m3_bits(dZ16 / sdz_t[:, None])))
+    dx_st = (dec(dZ8) @ dec(bw["W1_8c"]).T) * s64(sdz_t)[:, None] * s64(bw["sw1_d"])[None, :]
+    e_dx = O.max_rel_err(f64(dX[rs_t]), dx_st); r_dx = O.row_rel_err(f64(dX[rs_t]), dx_st)
+    f_raw = O.ffn_fwd_fp8_rowwise_codes(inp["X"][rsel], inp["sx"][rsel], inp["W1"], inp["sw1"], inp["b1"], inp["W2"], inp["sw2"])
+    bw_r = dict(bw); bw_r["dY8r"] = bw["dY8r"][rsel]; bw_r["sdy_t"] = bw["sdy_t"][rsel]; bw_r["dY8c"] = bw["dY8c"][rsel]; bw_r["X8c"] = bw["X8c"][rsel]
+    g_raw = O.ffn_bwd_fp8_rowwise_codes(f_raw, **bw_r)                      # a token slice: only dZ and dX are meaningful
+    e_y = O.max_rel_err(f64(Y[rs_t]), f_raw["Y"]); e_dx_raw = O.max_rel_err(f64(dX[rs_t]), g_raw["dX"]); f_dx_raw = O.fro_rel_err(f64(dX[rs_t]), g_raw["dX"])
+    print(f"  fp8 row-wise dense bwd rows: dZ staged {e_dz:.2e} (Frobenius {f_dz:.2e})  dX staged {e_dx:.2e} (row {r_dx:.2e})  from raw inputs: Y {e_y:.2e} dX {e_dx_raw:.2e} (Frobenius {f_dx_raw:.2e})", flush=True)
+    assert max(e_dz, f_dz, e_dx, r_dx, e_y, e_dx_raw, f_dx_raw) <= TOL_FP8
+    # ---- hidden features over all tokens: per-feature scales and codes of the two transposed operands bit-exact, then dW2 / dW1
+    fs = np.arange(Fh) if fsel is None else fsel
+    fs_t = torch.from_numpy(fs).cuda()
+    H_f = f64(Hd_all[:, fs_t]).astype(np.float32); dZ_f = f64(dZ16_all[:, fs_t]).astype(np.float32)
+    sh_f_ref = q448(H_f.max(axis=0)); sdz_f_ref = q448(np.abs(dZ_f).max(axis=0))
+    H8t = ctx.saved("H_dense_t")[fs_t].cpu().numpy(); dZ8t = ctx.saved("dZ_dense_t")[fs_t].cpu().numpy()
+    sh_f = ctx.saved("sh_f")[fs_t].cpu().numpy(); sdz_f = ctx.saved("sdz_f")[fs_t].cpu().numpy()
+    torch.cuda.synchronize()
+    assert np.array_equal(sh_f, sh_f_ref) and np.array_equal(sdz_f, sdz_f_ref)
+    assert np.array_equal(H8t, O.f32_to_e4m3_bits(H_f / sh_f_ref[None, :]).T)
+    assert np.array_equal(dec(dZ8t), dec(O.f32_to_e4m3_bits(dZ_f / sdz_f_ref[None, :]).T))
+    dW2_st = (dec(H8t) @ dec(bw["dY8c"])) * s64(sh_f)[:, None] * s64(bw["sdy_d"])[None, :]
+    dW1_st = (dec(dZ8t) @ dec(bw["X8c"])) * s64(sdz_f)[:, None] * s64(bw["sx_d"])[None, :]
+    e_dw2 = O.max_rel_err(f64(dW2[fs_t]), dW2_st); e_dw1 = O.max_rel_err(f64(dW1[:, fs_t]).T, dW1_st)
+    f_g = O.ffn_fwd_fp8_rowwise_codes(inp["X"], inp["sx"], inp["W1"][:, fs], inp["sw1"][fs], inp["b1"][fs], inp["W2"][fs], inp["sw2"])
+    bw_g = dict(bw); bw_g["W2_8r"] = bw["W2_8r"][fs]; bw_g["sw2_f"] = bw["sw2_f"][fs]; bw_g["W1_8c"] = bw["W1_8c"][:, fs]
+    g_g = O.ffn_bwd_fp8_rowwise_codes(f_g, **bw_g)                          # a feature slice: only the weight gradients are meaningful
+    e_dw2_raw = O.max_rel_err(f64(dW2[fs_t]), g_g["dW2"]); e_dw1_raw = O.max_rel_err(f64(dW1[:, fs_t]), g_g["dW1"])
+    f_dw2_raw = O.fro_rel_err(f64(dW2[fs_t]), g_g["dW2"]); f_dw1_raw = O.fro_rel_err(f64(dW1[:, fs_t]), g_g["dW1"])
+    print(f"  fp8 row-wise dense bwd features: dW2 staged {e_dw2:.2e} dW1 staged {e_dw1:.2e}  from raw inputs: dW2 {e_dw2_raw:.2e} (Frobenius {f_dw2_raw:.2e}) dW1 {e_dw1_raw:.2e} (Frobenius {f_dw1_raw:.2e})", flush=True)
+    assert max(e_dw2, e_dw1, e_dw2_raw, e_dw1_raw, f_dw2_raw, f_dw1_raw) <= TOL_FP8
+    ctx.close()
+
+
+def test_ffn_dense_bwd_fp8_rowwise_small(F24):
+    print("fp8 row-wise dense fwd+bwd T=256 D=512 F=2048", flush=True)
+    _fp8_rowwise_dense_bwd_case(F24, 256, 512, 2048, 0.70, seed=83)
+    print("fp8 row-wise dense fwd+bwd T=768 D=512 F=1280", flush=True)
+    _fp8_rowwise_dense_bwd_case(F24, 768, 512, 1280, "per_feature", seed=84)
+
+
+@pytest.mark.timeout(900)
+def test_ffn_dense_bwd_fp8_rowwise_full_size_sampled(F24):
+    w = synth.WORKLOADS["c5"]
+    print(f"fp8 row-wise dense fwd+bwd full size c5 T={w.T} D={w.D} F={w.F}", flush=True)
+    rng = np.random.default_rng(58)
+    rows = np.sort(rng.choice(w.T, 32, replace=False))
+    fsel = np.sort(rng.choice(w.F, 32, replace=False))
+    _fp8_rowwise_dense_bwd_case(F24, w.T, w.D, w.F, w.sparsity, w.seed, rows=rows, fsel=fsel)
 
 
 def test_ffn24_bwd_fp8_rowwise_small(F24):
