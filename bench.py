@@ -394,6 +394,32 @@ def main() -> int:
         sparsify = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / 8000.0, 4)}
         del Hs, vals, meta
 
+    # what the caller of the row-wise recipe does before a step (not part of the step, the same for the 2:4 and the dense FFN): the
+    # eight row-wise / column-wise quantisations of its bf16 tensors, with the library's quantiser
+    operand_quant = None
+    if rowwise_bwd:
+        fl = synth.make_inputs(T, D, F, w.sparsity, w.seed, with_dy=True)
+        m16 = {k: torch.from_numpy(fl[k]).to(torch.bfloat16).cuda() for k in ("X", "W1", "W2", "dY")}
+        del fl
+        jobs = (("X", 1), ("W1", 0), ("W2", 0), ("dY", 1), ("dY", 0), ("X", 0), ("W2", 1), ("W1", 1))
+        outs = [(torch.empty(m16[k].shape, dtype=torch.uint8, device="cuda"), torch.empty((m16[k].shape[0] if ax == 1 else m16[k].shape[1],), dtype=torch.float32, device="cuda"))
+                for k, ax in jobs]
+        def quant_all():
+            for (k, ax), (cd, sc_) in zip(jobs, outs):
+                ffn24.quantise_e4m3(m16[k], ax, cd, sc_)
+        for _ in range(3):
+            quant_all()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            quant_all()
+        e1.record(); torch.cuda.synchronize()
+        qms = e0.elapsed_time(e1) / 10
+        qbytes = sum((3.0 if ax == 1 else 5.0) * m16[k].numel() for k, ax in jobs)      # rows: read 2, write 1; columns: read 2 twice, write 1
+        operand_quant = {"ms": round(qms, 4), "GBps": round(qbytes / (qms * 1e-3) / 1e9, 1),
+                         "what": "X per row, W1 and W2 per column (forward); dY per row and per column, X per column, W2 and W1 per row (backward), from bf16"}
+        del m16, outs
+
     tdf = float(T) * D * F
     flops_step = (12.0 if bwd else 4.0) * tdf
     value = flops_step / sec24 / 1e12
@@ -485,6 +511,8 @@ def main() -> int:
     }
     if telemetry:
         out["telemetry"] = telemetry
+    if operand_quant:
+        out["operand_quantisation_outside_the_step"] = operand_quant
     ctx.close()
     print(json.dumps(out))
     return 0

@@ -117,6 +117,16 @@ FFN24_API int ffn24_set_bwd_scales(ffn24_ctx* ctx, float sdy, float sdz);
  * 7 is then H8 [T][F] and tensor 11 the sh of that forward. */
 FFN24_API int ffn24_set_row_scales(ffn24_ctx* ctx, const float* sx, const float* sw1, const float* sw2);
 
+/* Row-wise scaling of a GEMM operand (paper Sec. 2: "FP8 rowwise scaling"): X is a bf16 matrix [rows][cols], row-major, device
+ * memory, cols a multiple of 8.  axis 1: one scale per row, scales[r] = max_c |X[r][c]| / 448 (1 if the row is all zero);
+ * axis 0: one scale per column, scales[c] = max_r |X[r][c]| / 448.  codes[r][c] = e4m3(X[r][c] / scale), round to nearest even
+ * (nothing saturates: the largest entry of every row / column maps to 448).  codes: rows x cols bytes, row-major; scales: fp32,
+ * [rows] or [cols] (with axis 0 the buffer also holds intermediate values until the call's last kernel has run).  These are the
+ * (codes, scales) pairs that ffn24_set_row_scales / ffn24_fwd and ffn24_bwd_rowwise take, made from the caller's bf16 tensors:
+ * X per row, W1 and W2 per column for the forward; dY per row and per column, X per column, W2 and W1 per row for the backward.
+ * Empty matrices are a no-op.  FFN24_ERR_SHAPE for another axis or cols % 8 != 0. */
+FFN24_API int quantise_e4m3(const void* X, int64_t rows, int64_t cols, int axis, void* codes, float* scales, void* stream);
+
 /* Backward of a row-wise-scaled forward: an FFN24_FP8_E4M3 | FFN24_ROWWISE | FFN24_TRAINING context (not with FFN24_SPLIT),
  * after ffn24_fwd.  Every GEMM of the backward is scaled row-wise, as the paper's precision recipe has it for all
  * of its FP8 matrix multiplications (caption of the forward-speed-up figure; Sec. 2, the paragraph on the fused backward pointwise

@@ -500,6 +500,15 @@ int sparsify24(const void* H, int64_t rows, int64_t cols, ffn24_dtype dtype, voi
   return launch_sparsify24(H, rows, cols, values, meta, s) ? FFN24_ERR_HIP : FFN24_OK;
 }
 
+int quantise_e4m3(const void* X, int64_t rows, int64_t cols, int axis, void* codes, float* scales, void* stream) {
+  if (axis != 0 && axis != 1) return FFN24_ERR_SHAPE;
+  if (rows < 0 || cols < 0 || cols % 8 || rows > ((int64_t)1 << 24) || cols > ((int64_t)1 << 24)) return FFN24_ERR_SHAPE;
+  if (rows == 0 || cols == 0) return FFN24_OK;
+  if (!X || !codes || !scales) return FFN24_ERR_NULL;
+  if (misaligned(X) || misaligned(codes) || misaligned(scales)) return FFN24_ERR_ALIGN;
+  return launch_quantise_bf16(X, rows, cols, axis, codes, scales, static_cast<hipStream_t>(stream)) ? FFN24_ERR_HIP : FFN24_OK;
+}
+
 int sparsify24_quantise(const void* H, int64_t rows, int64_t cols, float scale, void* values8, uint8_t* meta, void* stream) {
   if (rows < 0 || cols < 0 || cols % 8) return FFN24_ERR_SHAPE;
   if (!(scale > 0.f)) return FFN24_ERR_SHAPE;

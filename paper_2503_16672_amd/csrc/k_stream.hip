@@ -755,4 +755,99 @@ int launch_quantise_rows(const void* Hc16, const uint8_t* meta16, const uint32_t
   return (int)hipGetLastError();
 }
 
+// Row-wise / column-wise e4m3 quantisation of a bf16 matrix X [R][C] (the operands a caller hands to the row-wise-scaled
+// GEMMs; Sec. 2 of the paper: FP8 row-wise scaling).  scale = (largest magnitude of the row or column) / 448, 1 if that is
+// zero; codes = e4m3(x / scale), row-major [R][C].
+// Per row: one wave per row, two passes over the row (the second one finds it in the caches).
+__global__ void __launch_bounds__(256) quantise_bf16_rows_kernel(const u32x4* __restrict__ X, int64_t R, int C8, u32x2* __restrict__ codes,
+                                                                 float* __restrict__ scales) {
+  const int lane = threadIdx.x & 63;
+  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= R) return;
+  const u32x4* row = X + r * C8;
+  uint32_t m = 0u;
+  for (int c = lane; c < C8; c += 64) {
+    u32x4 v = row[c];
+#pragma unroll
+    for (int d = 0; d < 4; d++) m = max(m, max(v[d] & 0x7FFFu, (v[d] >> 16) & 0x7FFFu));
+  }
+#pragma unroll
+  for (int sft = 1; sft < 64; sft <<= 1) m = max(m, (uint32_t)__shfl_xor((int)m, sft, 64));
+  const float mx = __builtin_bit_cast(float, m << 16);
+  const float s = mx > 0.f ? mx / 448.f : 1.f;
+  if (lane == 0) scales[r] = s;
+  u32x2* out = codes + r * C8;
+  for (int c = lane; c < C8; c += 64) {
+    u32x4 v = row[c];
+    uint32_t q0 = cvt_e4m3x2(bf16_lo_to_f32(v[0]) / s, bf16_hi_to_f32(v[0]) / s, 0u, false);
+    q0 = cvt_e4m3x2(bf16_lo_to_f32(v[1]) / s, bf16_hi_to_f32(v[1]) / s, q0, true);
+    uint32_t q1 = cvt_e4m3x2(bf16_lo_to_f32(v[2]) / s, bf16_hi_to_f32(v[2]) / s, 0u, false);
+    q1 = cvt_e4m3x2(bf16_lo_to_f32(v[3]) / s, bf16_hi_to_f32(v[3]) / s, q1, true);
+    st_stream(out + c, u32x2{q0, q1});
+  }
+}
+
+// Per column, step 1: cmax[c] (zeroed by the caller) is raised to the largest magnitude word of column c.  A work item takes 8
+// consecutive columns of a slab of QC_ROWS rows.
+constexpr int QC_ROWS = 64;
+__global__ void __launch_bounds__(256) colmax_bf16_kernel(const u32x4* __restrict__ X, int64_t R, int C8, uint32_t* __restrict__ cmax) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C8) return;
+  const int64_t r0 = (int64_t)blockIdx.y * QC_ROWS, r1 = r0 + QC_ROWS < R ? r0 + QC_ROWS : R;
+  uint32_t m[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+  for (int64_t r = r0; r < r1; r++) {
+    u32x4 v = ld_stream(X + r * C8 + c);
+#pragma unroll
+    for (int d = 0; d < 4; d++) { m[2 * d] = max(m[2 * d], v[d] & 0x7FFFu); m[2 * d + 1] = max(m[2 * d + 1], (v[d] >> 16) & 0x7FFFu); }
+  }
+#pragma unroll
+  for (int j = 0; j < 8; j++) if (m[j]) atomicMax(cmax + 8 * c + j, m[j]);
+}
+// step 2: codes with the scales taken from the column maxima
+__global__ void __launch_bounds__(256) quantise_bf16_cols_kernel(const u32x4* __restrict__ X, int64_t R, int C8, const u32x4* __restrict__ cmax,
+                                                                 u32x2* __restrict__ codes) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C8) return;
+  const int64_t r0 = (int64_t)blockIdx.y * QC_ROWS, r1 = r0 + QC_ROWS < R ? r0 + QC_ROWS : R;
+  float s[8];
+  u32x4 ma = cmax[2 * c], mb = cmax[2 * c + 1];
+#pragma unroll
+  for (int j = 0; j < 8; j++) {
+    float mx = __builtin_bit_cast(float, (j < 4 ? ma[j] : mb[j - 4]) << 16);
+    s[j] = mx > 0.f ? mx / 448.f : 1.f;
+  }
+  for (int64_t r = r0; r < r1; r++) {
+    u32x4 v = ld_stream(X + r * C8 + c);
+    uint32_t q0 = cvt_e4m3x2(bf16_lo_to_f32(v[0]) / s[0], bf16_hi_to_f32(v[0]) / s[1], 0u, false);
+    q0 = cvt_e4m3x2(bf16_lo_to_f32(v[1]) / s[2], bf16_hi_to_f32(v[1]) / s[3], q0, true);
+    uint32_t q1 = cvt_e4m3x2(bf16_lo_to_f32(v[2]) / s[4], bf16_hi_to_f32(v[2]) / s[5], 0u, false);
+    q1 = cvt_e4m3x2(bf16_lo_to_f32(v[3]) / s[6], bf16_hi_to_f32(v[3]) / s[7], q1, true);
+    st_stream(codes + r * C8 + c, u32x2{q0, q1});
+  }
+}
+// step 3: the column maxima (bf16 words) become the scales, in place
+__global__ void __launch_bounds__(256) scales_from_max_kernel(uint32_t* __restrict__ cmax, int C) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C) return;
+  const float mx = __builtin_bit_cast(float, cmax[c] << 16);
+  cmax[c] = __builtin_bit_cast(uint32_t, mx > 0.f ? mx / 448.f : 1.f);
+}
+
+int launch_quantise_bf16(const void* X, int64_t R, int64_t C, int axis, void* codes, float* scales, hipStream_t s) {
+  const int C8 = (int)(C / 8);
+  if (axis == 1) {
+    hipLaunchKernelGGL(quantise_bf16_rows_kernel, dim3((unsigned)((R + 3) / 4)), dim3(256), 0, s, static_cast<const u32x4*>(X), R, C8,
+                       static_cast<u32x2*>(codes), scales);
+    return (int)hipGetLastError();
+  }
+  uint32_t* cmax = reinterpret_cast<uint32_t*>(scales);
+  if (int rc = launch_zero32(cmax, (size_t)C, s)) return rc;
+  dim3 grid((unsigned)((C8 + 255) / 256), (unsigned)((R + QC_ROWS - 1) / QC_ROWS));
+  hipLaunchKernelGGL(colmax_bf16_kernel, grid, dim3(256), 0, s, static_cast<const u32x4*>(X), R, C8, cmax);
+  hipLaunchKernelGGL(quantise_bf16_cols_kernel, grid, dim3(256), 0, s, static_cast<const u32x4*>(X), R, C8, reinterpret_cast<const u32x4*>(cmax),
+                     static_cast<u32x2*>(codes));
+  hipLaunchKernelGGL(scales_from_max_kernel, dim3((unsigned)((C + 255) / 256)), dim3(256), 0, s, cmax, (int)C);
+  return (int)hipGetLastError();
+}
+
 }  // namespace ffn24

@@ -133,6 +133,9 @@ int launch_featurewise24_rowmax(const void* Hc, const uint8_t* meta, const void*
                                 uint32_t* hmax, uint32_t* zmax, hipStream_t s);
 // byte matrix [R][C] (C % 64 == 0, R % 256 == 0) -> dense fp8 panel form, or the B panel form if b_form
 int launch_panelise8(const void* in, int R, int C, void* out, int b_form, hipStream_t s);
+// bf16 X [R][C] (C % 8 == 0) -> e4m3 codes [R][C] and one scale per row (axis 1, scales [R]) or per column (axis 0, scales [C]; the
+// buffer also holds the column maxima while the call runs)
+int launch_quantise_bf16(const void* X, int64_t R, int64_t C, int axis, void* codes, float* scales, hipStream_t s);
 // streaming kernels
 // p[0..n) = 0 (a kernel, not a memset node)
 int launch_zero32(uint32_t* p, size_t n, hipStream_t s);

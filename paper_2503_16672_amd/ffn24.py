@@ -25,7 +25,7 @@ FFN24_PERMUTE = 32
 FFN24_TELEMETRY = 64
 
 EXPORTS = (
-    "ffn24_ctx_create", "ffn24_ctx_destroy", "ffn24_set_scales", "ffn24_set_bwd_scales", "ffn24_set_row_scales", "ffn24_set_token_permutation", "ffn24_set_split", "sparsify24", "sparsify24_quantise", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd", "ffn24_bwd_rowwise", "ffn_bwd_rowwise",
+    "ffn24_ctx_create", "ffn24_ctx_destroy", "ffn24_set_scales", "ffn24_set_bwd_scales", "ffn24_set_row_scales", "ffn24_set_token_permutation", "ffn24_set_split", "sparsify24", "sparsify24_quantise", "quantise_e4m3", "sparsify24_featurewise", "spmm24", "ffn24_fwd", "ffn24_bwd", "ffn24_bwd_rowwise", "ffn_bwd_rowwise",
     "ffn_fwd", "ffn_bwd", "ffn24_prepare_weights", "ffn24_get_telemetry", "ffn24_policy_use_sparse", "ffn24_saved_bytes", "ffn24_copy_saved", "ffn24_set_profiling", "ffn24_kernel_ms", "ffn24_strerror",
     "ffn24_static_scratch_needed", "ffn24_fwd_static", "ffn24_kernel_mhz", "ffn24_probe_mfma_rate", "ffn24_probe_gemm", "ffn24_probe_copy",
 )
@@ -69,6 +69,7 @@ def lib() -> ctypes.CDLL:
         L.ffn_bwd_rowwise.argtypes = [vp, ctypes.POINTER(RowwiseBwdOperands), vp, vp, vp, vp]
         L.sparsify24.argtypes = [vp, i64, i64, ci, vp, vp, vp]
         L.sparsify24_quantise.argtypes = [vp, i64, i64, ctypes.c_float, vp, vp, vp]
+        L.quantise_e4m3.argtypes = [vp, i64, i64, ci, vp, vp, vp]
         L.sparsify24_featurewise.argtypes = [vp, vp, vp, i64, i64, vp, vp, vp, vp]
         L.spmm24.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp]
         L.ffn24_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp]
@@ -192,6 +193,18 @@ MFMA_KINDS = ("dense bf16 32x32x16", "sparse bf16 32x32x32", "dense fp8 32x32x64
 GEMM_PROBE_VARIANTS = {"all": 0, "no_dma": 1, "no_fragment_reads": 4, "dma_only": 6, "mfma_only": 5, "all_l2_hits": 8, "dma_only_l2_hits": 14,
                        "all_dma_issue_unpaced": 256, "all_quarter_less_fill": 512,
                        "all_persistent_workgroups": 1024}
+
+
+def quantise_e4m3(X, axis: int, codes=None, scales=None):
+    """e4m3 codes and one scale per row (axis 1) or per column (axis 0) of a bf16 CUDA matrix (see quantise_e4m3 in the header)."""
+    R, C = X.shape
+    _expect(X, (R, C), _BF16, "X")
+    codes = torch.empty((R, C), dtype=torch.uint8, device=X.device) if codes is None else codes
+    scales = torch.empty((R if axis == 1 else C,), dtype=torch.float32, device=X.device) if scales is None else scales
+    _expect(codes, (R, C), _BYTE, "codes")
+    _expect(scales, (R if axis == 1 else C,), _F32, "scales")
+    _check(lib().quantise_e4m3(_ptr(X), R, C, axis, _ptr(codes), _ptr(scales), _stream()), "quantise_e4m3")
+    return codes, scales
 
 
 def probe_mfma_rate(kind: int, iters: int = 20000) -> dict:

@@ -20,7 +20,7 @@ def _declared():
 
 def test_header_symbols_are_exported():
     names = _declared()
-    assert len(names) == 31 and "ffn24_fwd" in names and "sparsify24" in names
+    assert len(names) == 32 and "ffn24_fwd" in names and "sparsify24" in names
     lib = ctypes.CDLL(LIB)
     for n in names:
         assert hasattr(lib, n), n
@@ -59,6 +59,10 @@ def test_argument_validation_without_gpu():
     assert L.spmm24(a16, a16, a16, 100, 256, 64, a16, None) == -2
     assert L.spmm24(a16, a16, a16 + 8, 256, 256, 64, a16, None) == -3
     assert L.spmm24(None, a16, a16, 256, 256, 64, a16, None) == -1
+    # row-wise / column-wise quantisation
+    assert L.quantise_e4m3(a16, 4, 16, 2, a16, a16, None) == -2 and L.quantise_e4m3(a16, 4, 12, 1, a16, a16, None) == -2
+    assert L.quantise_e4m3(None, 4, 16, 1, a16, a16, None) == -1 and L.quantise_e4m3(a16 + 2, 4, 16, 1, a16, a16, None) == -3
+    assert L.quantise_e4m3(None, 0, 16, 0, None, None, None) == 0
     # feature-wise
     assert L.sparsify24_featurewise(a16, a16, None, 100, 64, a16, a16, None, None) == -2
     assert L.sparsify24_featurewise(a16, a16, a16, 128, 64, a16, a16, None, None) == -1

@@ -1185,6 +1185,30 @@ def test_ffn24_fwd_fp8_rowwise_full_size_sampled(F24):
     _check_fp8_rowwise(F24, w.T, w.D, w.F, w.sparsity, w.seed, rows=rows)
 
 
+@pytest.mark.parametrize("R,C", [(1, 8), (5, 40), (256, 512), (1000, 4104), (4096, 2048)])
+def test_quantise_e4m3_rows_and_columns_bit_exact(F24, R, C):
+    """The operand quantisers of the row-wise recipe against the oracle's quantise_rows_e4m3 (pinned on the CPU by a hand example
+    and torch's cast): scales and codes bit-exact, along rows and along columns; zero rows / columns get scale 1."""
+    print(f"quantise_e4m3 R={R} C={C}", flush=True)
+    rng = np.random.default_rng(R * 31 + C)
+    x = (rng.standard_normal((R, C)) * np.exp(rng.uniform(-6, 6, size=(R, 1))) * np.exp(rng.uniform(-2, 2, size=(1, C)))).astype(np.float32)
+    if R > 4:
+        x[3] = 0
+        x[:, 5] = 0
+    xb = O.round_bf16(x)
+    X = to_dev_bf16(xb)
+    codes_r, s_r = F24.quantise_e4m3(X, 1)
+    codes_c, s_c = F24.quantise_e4m3(X, 0)
+    torch.cuda.synchronize()
+    ref_r, sr = O.quantise_rows_e4m3(xb)
+    ref_ct, sc = O.quantise_rows_e4m3(np.ascontiguousarray(xb.T))
+    assert np.array_equal(s_r.cpu().numpy(), sr) and np.array_equal(s_c.cpu().numpy(), sc)
+    assert np.array_equal(codes_r.cpu().numpy(), ref_r) and np.array_equal(codes_c.cpu().numpy(), np.ascontiguousarray(ref_ct.T))
+    if R > 4:
+        assert sr[3] == 1 and sc[5] == 1 and not codes_r.cpu().numpy()[3].any()
+    assert ((ref_r & 0x7F).max(axis=1)[np.abs(xb).max(axis=1) > 0] == 0x7E).all()
+
+
 def _fp8_rowwise_bwd_case(F24, T, D, Fh, sparsity, seed, rows=None, gsel=None):
     """Row-wise-scaled fp8 forward + backward against the oracle, staged: (S1) every quantisation step -- the per-token scale
     and codes of dZ, the feature-wise picks, the per-feature scales and codes of the two transposed operands -- bit-exact
