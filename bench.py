@@ -133,6 +133,36 @@ def run_c3(args) -> int:
     return 0
 
 
+def run_vendor_gemms(args) -> int:
+    """Context for the dense baseline: the six GEMMs of a dense fwd+bwd at the workload's shapes through torch.matmul (the vendor's
+    GEMM library), unfused, on operands with the workload's statistics.  Not part of the product or of its baseline."""
+    import torch
+    from paper_2503_16672_amd import synth
+    w = synth.WORKLOADS[args.workload if args.workload in ("c2", "c4") else "c4"]
+    T, D, F = w.T, w.D, w.F
+    inp = synth.make_workload(w.name, with_dy=True)
+    X, W1, W2, dY = (torch.from_numpy(inp[k]).to(torch.bfloat16).cuda() for k in ("X", "W1", "W2", "dY"))
+    b1 = torch.from_numpy(inp["b1"]).cuda()
+    H = (torch.clamp((X @ W1).float() + b1, min=0) ** 2).to(torch.bfloat16)
+    dZ = ((dY @ W2.t()).float() * 2 * torch.sqrt(H.float())).to(torch.bfloat16)
+    cases = (("up X W1", X, W1), ("down H W2", H, W2), ("dH dY W2^T", dY, W2.t()), ("dX dZ W1^T", dZ, W1.t()), ("dW2 H^T dY", H.t(), dY), ("dW1 X^T dZ", X.t(), dZ))
+    out = {"vendor_gemms": f"torch.matmul, bf16, {w.name}: T={T} d_model={D} d_ff={F}", "gemms": {}}
+    total = 0.0
+    for name, a, b in cases:
+        for _ in range(5):
+            a @ b
+        ts = []
+        for _ in range(20):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); a @ b; e1.record(); torch.cuda.synchronize(); ts.append(e0.elapsed_time(e1))
+        ts.sort()
+        out["gemms"][name] = {"ms_median": round(ts[10], 4), "ms_min": round(ts[0], 4), "tflops": round(2.0 * T * D * F / ts[10] / 1e9, 1)}
+        total += ts[10]
+    out["sum_ms"] = round(total, 4)
+    print(json.dumps(out))
+    return 0
+
+
 def run_probe(args) -> int:
     """What the machine delivers, measured with the library's own probe kernels: register-resident matrix-op rates, the
     GEMM core with ingredients of its main loop removed (at the workload's sparse-GEMM and up-projection shapes), and a
@@ -234,6 +264,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--vendor-gemms", action="store_true", help="context only: time the six GEMMs of a dense fwd+bwd through torch.matmul (the vendor library)")
     ap.add_argument("--probe", action="store_true", help="print the machine rates the probe kernels measure (matrix-op issue rate, GEMM "
                     "main-loop decomposition, copy rate) instead of running the workload")
     ap.add_argument("--workload", default="c4", help="c1, c2, c3 (four forward layers), c3_85..c3_98, c4 (default: forward+backward at the 7B FFN dims), c5 (fp8 forward)")
@@ -261,6 +292,8 @@ def main() -> int:
     ffn24.lib()  # fails loudly if libffn24.so is not built; there is no fallback path
     if args.probe:
         return run_probe(args)
+    if args.vendor_gemms:
+        return run_vendor_gemms(args)
     if args.workload == "c3":
         return run_c3(args)
     if args.split_sweep:
