@@ -655,7 +655,8 @@ def ffn_fwd_fp8_rowwise_codes(X8, sx, W1_8, sw1, b1, W2_8, sw2):
     return {"Z": Z, "Hq": Hq, "sh": sh, "H8_bits": H8_bits, "Y": Y}
 
 
-def ffn24_bwd_fp8_rowwise_codes(fwd, dY8r, sdy_t, W2_8r, sw2_f, W1_8c, sw1_d, dY8c, sdy_d, X8c, sx_d, wgrad_mask="featurewise", quantise_internal=True):
+def ffn24_bwd_fp8_rowwise_codes(fwd, dY8r, sdy_t, W2_8r, sw2_f, W1_8c, sw1_d, dY8c, sdy_d, X8c, sx_d, wgrad_mask="featurewise", quantise_internal=True,
+                                dense_features=None):
     """Backward of ffn24_fwd_fp8_rowwise_codes with row-wise scaling in every GEMM (the paper's precision recipe: the caption
     of the forward-speed-up figure has all FP8 matrix multiplications row-wise scaled; Sec. 2, the paragraph on the fused
     backward pointwise kernel: it includes the transposition and the FP8 scaling).  Row-wise scaling of a GEMM: each operand
@@ -676,6 +677,10 @@ def ffn24_bwd_fp8_rowwise_codes(fwd, dY8r, sdy_t, W2_8r, sw2_f, W1_8c, sw1_d, dY
       sh_f[f] = max_t (H24 * M_T)[t,f] / 448;  H8c = e4m3(H24 * M_T / sh_f[f])   (the largest entry of a column always survives M_T)
       sdz_f[f] = max_t |(dZ * M_T)[t,f]| / 448;  dZ8c = e4m3(dZ * M_T / sdz_f[f])
       dW2[f,d] = sh_f[f] sdy_d[d] (H8c^T . dY8c)[f,d];   dW1[d,f] = sx_d[d] sdz_f[f] (X8c^T . dZ8c)[d,f]
+    dense_features (bool [F], optional): the split of Sec. 2, "Optimization 1", as in ffn24_bwd -- for these features the two
+    weight gradients use the token-wise mask only (their rows of the transposed operands stay dense and go through a dense
+    GEMM), for all others the feature-wise mask on top; either way a feature's row is quantised with its own scale, taken
+    over whatever of the row enters the GEMM.
     fwd = the result of ffn24_fwd_fp8_rowwise_codes.  Switches for pinning only: wgrad_mask="tokenwise" uses the token-wise
     mask in the last line; quantise_internal=False leaves dZ and H24 unrounded (neither bf16 nor e4m3) in all three GEMMs."""
     dec = lambda c: E4M3_VALUES[np.ascontiguousarray(c, dtype=np.uint8)]
@@ -687,6 +692,8 @@ def ffn24_bwd_fp8_rowwise_codes(fwd, dY8r, sdy_t, W2_8r, sw2_f, W1_8c, sw1_d, dY
     H24 = decompress24(bf16_bits_to_f32(np.asarray(fwd["Hc_words"], dtype=np.uint16)), meta)
     _, meta_t, M_T = featurewise24(H24)
     Mw = M_T if wgrad_mask == "featurewise" else Mtok
+    if dense_features is not None:
+        Mw = np.where(np.asarray(dense_features, dtype=bool)[None, :], Mtok, Mw)
     out = {"dH": dH, "Mtok": Mtok, "M_T": M_T, "meta_t": meta_t}
     if quantise_internal:
         dZ16 = round_bf16(dZ)
@@ -698,7 +705,8 @@ def ffn24_bwd_fp8_rowwise_codes(fwd, dY8r, sdy_t, W2_8r, sw2_f, W1_8c, sw1_d, dY
         Hc = dec(H8c_bits_t).T * sh_f.astype(np.float64)[None, :]
         out.update({"dZ16": dZ16, "sdz_t": sdz_t, "sdz_f": sdz_f, "sh_f": sh_f, "dZ8r_bits": dZ8r_bits,
                     "dZc8r_bits": compress_with_meta(dZ8r_bits, meta),
-                    "Hc8_t_bits": compress_with_meta(H8c_bits_t, meta_t), "dZc8_t_bits": compress_with_meta(dZ8c_bits_t, meta_t)})
+                    "Hc8_t_bits": compress_with_meta(H8c_bits_t, meta_t), "dZc8_t_bits": compress_with_meta(dZ8c_bits_t, meta_t),
+                    "H8_t_bits": H8c_bits_t, "dZ8_t_bits": dZ8c_bits_t})
     else:
         dZr = dZc = dZ
         Hc = H24.astype(np.float64)

@@ -966,3 +966,45 @@ def test_dense_fp8_rowwise_backward_reductions():
     assert np.array_equal(g["sh_f"], (fd["Hq"].max(axis=0) / np.float32(448)).astype(np.float32)) and ((g["H8_t_bits"]).max(axis=1) == 0x7E).all()
     for k in ("dX", "dW1", "dW2"):
         assert O.fro_rel_err(g[k], e[k]) <= 2.0 ** -4, k
+
+
+def test_fp8_rowwise_backward_split_is_column_separable():
+    """Sec. 2, "Optimization 1" on the row-wise fp8 backward: every hidden feature's rows of dW2 and columns of dW1 depend on
+    that feature's column of H24 and dZ alone (its own mask, its own scales), so with a split they are, feature by feature,
+    those of the run with the token-wise mask (dense features) or of the run with the feature-wise mask on top (the others);
+    dX and the token-wise tensors do not see the split.  The two extremes are the unsplit run and the token-wise run.  One
+    dense and one sparse feature are also recomputed from scratch with torch's e4m3 cast."""
+    inp, f, bw, fw = _fp8_rowwise_bwd_case(T=64, D=16, F=64, sparsity=0.4)
+    F = 64
+    nnz = O.feature_nnz(f["Hq"])
+    dense = O.split_features(nnz, 16)
+    assert dense.sum() == 16 and nnz[dense].min() >= nnz[~dense].max()
+    fw_run = O.ffn24_bwd_fp8_rowwise_codes(f, **bw)
+    tok_run = O.ffn24_bwd_fp8_rowwise_codes(f, **bw, wgrad_mask="tokenwise")
+    sp = O.ffn24_bwd_fp8_rowwise_codes(f, **bw, dense_features=dense)
+    assert np.array_equal(sp["dX"], fw_run["dX"]) and np.array_equal(sp["dZ8r_bits"], fw_run["dZ8r_bits"]) and np.array_equal(sp["sdz_t"], fw_run["sdz_t"])
+    for k, feat_axis in (("dW2", 0), ("dW1", 1)):
+        a = np.moveaxis(sp[k], feat_axis, 0); t = np.moveaxis(tok_run[k], feat_axis, 0); w = np.moveaxis(fw_run[k], feat_axis, 0)
+        assert np.array_equal(a[dense], t[dense]) and np.array_equal(a[~dense], w[~dense]), k
+        assert not np.array_equal(t[dense], w[dense]), k                     # the split matters on this input
+    for k in ("sh_f", "sdz_f"):
+        assert np.array_equal(sp[k][dense], tok_run[k][dense]) and np.array_equal(sp[k][~dense], fw_run[k][~dense]), k
+    assert np.array_equal(sp["H8_t_bits"][dense], tok_run["H8_t_bits"][dense]) and np.array_equal(sp["H8_t_bits"][~dense], fw_run["H8_t_bits"][~dense])
+    none = O.ffn24_bwd_fp8_rowwise_codes(f, **bw, dense_features=np.zeros(F, bool))
+    every = O.ffn24_bwd_fp8_rowwise_codes(f, **bw, dense_features=np.ones(F, bool))
+    for k in ("dW1", "dW2", "sh_f", "sdz_f"):
+        assert np.array_equal(none[k], fw_run[k]) and np.array_equal(every[k], tok_run[k]), k
+    # from scratch, one feature of each kind: mask, scale (max / 448 in float32), torch's cast, product with the decoded dY codes
+    H24 = O.decompress24(O.bf16_bits_to_f32(f["Hc_words"]), f["meta"])
+    dYv = O.e4m3_bits_to_f32(bw["dY8c"]).astype(np.float64) * bw["sdy_d"].astype(np.float64)[None, :]
+    for feat, is_dense in ((int(np.flatnonzero(dense)[0]), True), (int(np.flatnonzero(~dense & (nnz > 8))[0]), False)):
+        col = H24[:, feat].copy()
+        if not is_dense:
+            for g0 in range(0, 64, 4):                                         # keep the two largest of every four tokens, ties to the earlier
+                grp = col[g0:g0 + 4]
+                keep = sorted(sorted(range(4), key=lambda i: (-grp[i], i))[:2])
+                col[g0:g0 + 4] = [grp[i] if i in keep else 0.0 for i in range(4)]
+        s = np.float32(col.max() / np.float32(448)) if col.max() > 0 else np.float32(1)
+        codes = torch.from_numpy((col / s).astype(np.float32)).to(torch.float8_e4m3fn)
+        row = (codes.to(torch.float64).numpy() * np.float64(s)) @ dYv
+        assert np.allclose(sp["dW2"][feat], row, rtol=1e-12, atol=1e-15) and np.abs(row).max() > 0, feat
