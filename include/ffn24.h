@@ -85,7 +85,8 @@ FFN24_API int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F,
  *   Hc8 = e4m3(kept / sh), saturating at +-448, round to nearest even;  Y = bf16(sh sw2 (Hc8 . W2_8))
  * (paper Sec. 2: activation, then sparsification, then FP8 quantisation; per-tensor scales instead of the paper's
  * row-wise ones).  Saved tensors 0 and 1 are then bytes: Hc8 [T][F/2], meta [T][F/8]; tensor 7 is H8 [T][F].
- * ffn_fwd is the dense fp8 baseline of the forward.  With FFN24_TRAINING (not with FFN24_SPLIT: FFN24_ERR_DTYPE) the context
+ * ffn_fwd is the dense fp8 baseline of the forward.  With FFN24_TRAINING (FFN24_SPLIT only together with FFN24_ROWWISE, else
+ * FFN24_ERR_DTYPE) the context
  * also supports ffn24_bwd -- and, with FFN24_DENSE, ffn_bwd -- in fp8, see ffn24_set_bwd_scales; with FFN24_ROWWISE as well
  * the backwards are ffn24_bwd_rowwise and ffn_bwd_rowwise. */
 FFN24_API int ffn24_set_scales(ffn24_ctx* ctx, float sx, float sw1, float sh, float sw2);
@@ -127,8 +128,7 @@ FFN24_API int ffn24_set_row_scales(ffn24_ctx* ctx, const float* sx, const float*
  * Empty matrices are a no-op.  FFN24_ERR_SHAPE for another axis or cols % 8 != 0. */
 FFN24_API int quantise_e4m3(const void* X, int64_t rows, int64_t cols, int axis, void* codes, float* scales, void* stream);
 
-/* Backward of a row-wise-scaled forward: an FFN24_FP8_E4M3 | FFN24_ROWWISE | FFN24_TRAINING context (not with FFN24_SPLIT),
- * after ffn24_fwd.  Every GEMM of the backward is scaled row-wise, as the paper's precision recipe has it for all
+/* Backward of a row-wise-scaled forward: an FFN24_FP8_E4M3 | FFN24_ROWWISE | FFN24_TRAINING context, after ffn24_fwd.  Every GEMM of the backward is scaled row-wise, as the paper's precision recipe has it for all
  * of its FP8 matrix multiplications (caption of the forward-speed-up figure; Sec. 2, the paragraph on the fused backward pointwise
  * kernel: it includes the transposition and the FP8 scaling): each operand carries one scale per index of its NON-reduced
  * dimension.  A tensor that enters two GEMMs with different reduced dimensions is therefore quantised twice, by the caller,
@@ -147,7 +147,13 @@ FFN24_API int quantise_e4m3(const void* X, int64_t rows, int64_t cols, int axis,
  *   dW2 = bf16(sh_f[f] sdy_d[d] (H8c^T . dY8c));  dW1 = bf16(sx_d[d] sdz_f[f] (X8c^T . dZ8c)).
  * Outputs dX [T][D], dW1 [D][F], dW2 [F][D] are bf16 and overwritten.  Saved tensors afterwards: 2 dZ8r compressed [T][F/2] bytes,
  * 3 / 4 / 5 the transposed compressed operands (bytes), 13 sdz_t [T], 14 sh_f [F], 15 sdz_f [F] (fp32), 16 the bf16 compressed dZ
- * [T][F/2] before quantisation.  FFN24_ERR_STATE on any other context or before a forward.  ffn24_bwd refuses a row-wise context. */
+ * [T][F/2] before quantisation.  FFN24_ERR_STATE on any other context or before a forward.  ffn24_bwd refuses a row-wise context.
+ * With FFN24_SPLIT and ffn24_set_split(n_dense > 0) (paper Sec. 2, "Optimization 1"): the n_dense least sparse features keep the
+ * token-wise mask only in the two weight gradients; every feature's row of the transposed operands still has its own scale, taken
+ * over what of the row enters the GEMM; the sparse features' rows are quantised in compressed form, the dense ones as plain rows,
+ * and each weight gradient is one launch of a sparse and a dense fp8 GEMM.  The saved tensors 3 / 4 / 5 then hold the F - n_dense
+ * sparse features in the row order of saved tensor 10, 14 and 15 the scales of all F rows in that order (sparse rows first), and
+ * 20 / 21 the codes of the dense features' rows of the activation / of dZ. */
 typedef struct {
   const void* dY8r;  const float* sdy_t;
   const void* dY8c;  const float* sdy_d;
@@ -185,7 +191,8 @@ FFN24_API int ffn24_set_token_permutation(ffn24_ctx* ctx, const int32_t* perm_ho
  * activation, and all others with the sparse GEMMs as before.  n_dense is a multiple of 256, 0 <= n_dense <= F / 4
  * (0 = no split, the default).  Needs FFN24_SPLIT | FFN24_TRAINING; call it before the forward it shall apply to.
  * Saved tensors 9 (the counts, [F] uint32) and 10 (feature of each operand row, [F] int32: sparse features first,
- * then the dense ones, each in ascending order) are valid after the backward. */
+ * then the dense ones, each in ascending order) are valid after the backward.  bf16 contexts take it with ffn24_bwd, row-wise fp8
+ * contexts with ffn24_bwd_rowwise (see there); a per-tensor fp8 context has no split. */
 FFN24_API int ffn24_set_split(ffn24_ctx* ctx, int64_t n_dense);
 
 /* Free the workspace.  The caller must have synchronised every stream that used the context.  NULL is allowed. */
@@ -301,6 +308,8 @@ FFN24_API int ffn24_policy_use_sparse(ffn24_ctx* ctx, double min_sparsity, int* 
  *   13 sdz_t [T], 14 sh_f [F], 15 sdz_f [F] fp32 and 16 the compressed dZ before quantisation [T][F/2] bf16 (after ffn24_bwd_rowwise)
  *   17 the dense dZ before quantisation [T][F] bf16, 18 / 19 the codes of the transposed dense activation / dZ [F][T] (after ffn_bwd_rowwise;
  *   18 / 19 also after ffn_bwd on an fp8 context)
+ *   20 / 21 the rows of the split's dense features [F/4][T], activation / dZ, of which the first n_dense are valid (bf16, or e4m3
+ *   codes after ffn24_bwd_rowwise; FFN24_SPLIT)
  * ffn24_saved_bytes gives the size of tensor `which`; ffn24_copy_saved enqueues a copy of it into dst (device memory
  * of exactly that size, 16-byte aligned) in the row-major compressed form described at the top -- inside the context
  * the compressed tensors are kept in a tiled order that the sparse GEMM streams faster.  Returns FFN24_ERR_STATE if

@@ -62,6 +62,7 @@ struct ffn24_ctx {
   void* W1p;   // W1 itself in B panel form (B operand of the dX GEMMs)
   // split weight gradients (FFN24_SPLIT)
   uint32_t* nnz; int* row_of_feat; int* feat_of_row; void* Hdn_t; void* dZdn_t; void* dW1t;
+  void* Hdn8_t; void* dZdn8_t;   // row-wise fp8 split: the dense features' rows as e4m3 (Hdn_t, dZdn_t hold them in bf16 first)
   int n_dense;
   // telemetry (FFN24_TELEMETRY): device slots the kernels add to, their sums, and two pinned host snapshots that the
   // forward and the backward fill in turn (an event each tells when a snapshot has landed)
@@ -100,7 +101,7 @@ int free_all(ffn24_ctx* c) {
                   c->W1t, c->W2t, c->Xt, c->dYt, c->Hd_t, c->dZd_t, c->W2p, c->W1p,
                   c->nnz, c->row_of_feat, c->feat_of_row, c->Hdn_t, c->dZdn_t, c->dW1t, c->Hc16, c->meta16, c->rowmax, c->rsh, c->perm, c->Hd16,
                   c->dZc16, c->Hct16, c->dZct16, c->meta_t16, c->rowmax_dz, c->hmax, c->zmax, c->sdz_t, c->sh_f, c->sdz_f, c->W2rp, c->W1cp,
-                  c->dZd16, c->Hdt16, c->dZdt16};
+                  c->dZd16, c->Hdt16, c->dZdt16, c->Hdn8_t, c->dZdn8_t};
   for (void* b : bufs) if (b && hipFree(b) != hipSuccess) bad = 1;
   if (c->clk && hipFree(c->clk) != hipSuccess) bad = 1;
   if (c->tele && hipFree(c->tele) != hipSuccess) bad = 1;
@@ -184,7 +185,7 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
   if (!out) return FFN24_ERR_NULL;
   if (dtype != FFN24_BF16 && dtype != FFN24_FP8_E4M3) return FFN24_ERR_DTYPE;
   const bool f8 = dtype == FFN24_FP8_E4M3;
-  if (f8 && (flags & FFN24_TRAINING) && (flags & FFN24_SPLIT)) return FFN24_ERR_DTYPE;                      // fp8 training: no split
+  if (f8 && (flags & FFN24_SPLIT) && !(flags & FFN24_ROWWISE)) return FFN24_ERR_DTYPE;                      // fp8: the split needs the row-wise recipe
   if ((flags & FFN24_SPLIT) && !(flags & FFN24_TRAINING)) return FFN24_ERR_STATE;
   if ((flags & FFN24_ROWWISE) && !f8) return FFN24_ERR_DTYPE;
   if ((flags & FFN24_PERMUTE) && f8) return FFN24_ERR_DTYPE;
@@ -221,6 +222,7 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
          hipMalloc(reinterpret_cast<void**>(&c->feat_of_row), 4 * (size_t)F) == hipSuccess &&
          hipMalloc(&c->Hdn_t, tf / 2) == hipSuccess && hipMalloc(&c->dZdn_t, tf / 2) == hipSuccess &&   // up to F/4 dense rows
          hipMalloc(&c->dW1t, 2 * df) == hipSuccess;
+  if (ok && f8 && (flags & FFN24_SPLIT)) ok = hipMalloc(&c->Hdn8_t, tf / 4) == hipSuccess && hipMalloc(&c->dZdn8_t, tf / 4) == hipSuccess;
   if (ok && (flags & FFN24_PERMUTE)) ok = hipMalloc(reinterpret_cast<void**>(&c->perm), 4 * (size_t)T) == hipSuccess;
   if (ok && (flags & FFN24_ROWWISE) && !c->Hc16)
     ok = hipMalloc(&c->Hc16, tf) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->meta16), tf / 8) == hipSuccess;
@@ -426,6 +428,7 @@ int ffn24_saved_bytes(ffn24_ctx* c, int which, int64_t* nbytes) {
     case 14: case 15: *nbytes = 4 * c->F; break;
     case 17: *nbytes = 2 * tf; break;
     case 18: case 19: *nbytes = tf; break;
+    case 20: case 21: *nbytes = es * tf / 4; break;
     default: return FFN24_ERR_SHAPE;
   }
   return FFN24_OK;
@@ -464,6 +467,8 @@ int ffn24_copy_saved(ffn24_ctx* c, int which, void* dst, int64_t dst_bytes, void
     case 17: src = c->dZd16; break;
     case 18: src = c->Hd_t; break;
     case 19: src = c->dZd_t; break;
+    case 20: src = c->f8 ? c->Hdn8_t : c->Hdn_t; break;
+    case 21: src = c->f8 ? c->dZdn8_t : c->dZdn_t; break;
     default: src = c->Hc16; break;
   }
   if (!src) return FFN24_ERR_STATE;
@@ -473,6 +478,8 @@ int ffn24_copy_saved(ffn24_ctx* c, int which, void* dst, int64_t dst_bytes, void
     if (!c->f8) return FFN24_ERR_STATE;
     return launch_unpanel(src, F, T / 64, 64, dst, s) ? FFN24_ERR_HIP : FFN24_OK;
   }
+  if (which == 20 || which == 21)   // the split's dense feature rows [F/4][T] (the first n_dense are valid): dense panel form
+    return launch_unpanel(src, F / 4, c->f8 ? T / 64 : T / 32, 64, dst, s) ? FFN24_ERR_HIP : FFN24_OK;
   if (which == 12 || which == 16)   // bf16 kept values of an fp8 context: bf16 panel form (64-byte pieces of 64 k)
     return launch_unpanel(src, T, F / 64, 64, dst, s) ? FFN24_ERR_HIP : FFN24_OK;
   if (which >= 9) return hipMemcpyAsync(dst, src, (size_t)need, hipMemcpyDeviceToDevice, s) == hipSuccess ? FFN24_OK : FFN24_ERR_HIP;
@@ -551,8 +558,10 @@ int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, cons
   if (c->f8 && (c->flags & FFN24_ROWWISE)) {
     // row-wise scaling: up-projection (bf16 kept values + row maxima), row-wise quantisation, scaled sparse GEMM
     if (launch_zero32(c->rowmax, (size_t)T, s)) return FFN24_ERR_HIP;
+    uint32_t* nnz = (c->flags & FFN24_SPLIT) && c->n_dense > 0 ? c->nnz : nullptr;
+    if (nnz && launch_zero32(nnz, (size_t)F, s)) return FFN24_ERR_HIP;
     { Timed t(c, K_UP, s);
-      if (t.done(launch_up_prune24_f8_rowwise(c->W1t, X, b1, T, D, F, c->rsx, c->rsw1, c->Hc16, c->meta16, c->Hdbg, c->rowmax, s))) return FFN24_ERR_HIP; }
+      if (t.done(launch_up_prune24_f8_rowwise(c->W1t, X, b1, T, D, F, c->rsx, c->rsw1, c->Hc16, c->meta16, c->Hdbg, c->rowmax, nnz, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_QUANT, s);
       if (t.done(launch_quantise_rows(c->Hc16, c->meta16, c->rowmax, T, F, c->Hc, c->meta, c->rsh, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_DOWN, s);
@@ -635,6 +644,30 @@ int ffn24_bwd_rowwise(ffn24_ctx* c, const ffn24_rowwise_bwd_operands* op, void* 
     if (t.done(launch_quantise_rows(c->dZc16, c->meta16, c->rowmax_dz, T, F, c->dZc, c->meta, c->sdz_t, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_DX, s);
     if (t.done(launch_sp_rowmajor_f8_rowwise(c->dZc, c->meta, c->W1cp, T, D, F, c->sdz_t, op->sw1_d, dX, s))) return FFN24_ERR_HIP; }
+  if ((c->flags & FFN24_SPLIT) && c->n_dense > 0) {
+    // Sec. 2, "Optimization 1" on the row-wise recipe: the n_dense least sparse features keep the token-wise mask only; every
+    // row of the permuted feature space (sparse rows first) gets its own scale, the sparse rows are quantised in compressed form,
+    // the dense ones as plain rows, and each weight gradient is one launch of a sparse and a dense fp8 GEMM
+    const int nd = c->n_dense, ns = F - nd;
+    { Timed t(c, K_PART, s); if (t.done(launch_split_partition(c->nnz, F, nd, T, c->row_of_feat, c->feat_of_row, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_FW, s);
+      if (t.done(launch_featurewise24_split(c->Hc16, c->meta16, c->dZc16, T, F, c->row_of_feat, ns, c->Hct16, c->meta_t16, c->dZct16, c->Hdn_t, c->dZdn_t,
+                                            nullptr, c->hmax, c->zmax, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_QUANT_T, s);
+      int rc1 = launch_quantise_rows(c->Hct16, c->meta_t16, c->hmax, ns, T, c->Hc_t, c->meta_t, c->sh_f, s);
+      if (!rc1) rc1 = launch_quantise_rows(c->dZct16, c->meta_t16, c->zmax, ns, T, c->dZc_t, c->meta_t, c->sdz_f, s);
+      if (!rc1) rc1 = launch_quantise_rows_dense(c->Hdn_t, c->hmax + ns, nd, T, c->Hdn8_t, c->sh_f + ns, s);
+      if (t.done(rc1 ? rc1 : launch_quantise_rows_dense(c->dZdn_t, c->zmax + ns, nd, T, c->dZdn8_t, c->sdz_f + ns, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_TR_ACT, s);
+      int rc1 = launch_transpose8(op->dY8c, T, D, c->dYt, 2, nullptr, 0, s);
+      if (t.done(rc1 ? rc1 : launch_transpose8(op->X8c, T, D, c->Xt, 2, nullptr, 0, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_DW2, s);
+      if (t.done(launch_split_wgrad_f8_rowwise(c->Hc_t, c->meta_t, ns, c->Hdn8_t, nd, c->dYt, D, T, c->sh_f, op->sdy_d, dW2, D, c->feat_of_row, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_DW1, s);
+      if (t.done(launch_split_wgrad_f8_rowwise(c->dZc_t, c->meta_t, ns, c->dZdn8_t, nd, c->Xt, D, T, c->sdz_f, op->sx_d, c->dW1t, D, c->feat_of_row, s))) return FFN24_ERR_HIP; }
+    { Timed t(c, K_TR_DW1, s); if (t.done(launch_transpose(c->dW1t, F, D, dW1, 0, nullptr, 0, nullptr, s))) return FFN24_ERR_HIP; }
+    return FFN24_OK;
+  }
   { Timed t(c, K_FW, s);
     if (t.done(launch_featurewise24_rowmax(c->Hc16, c->meta16, c->dZc16, T, F, c->Hct16, c->meta_t16, c->dZct16, c->hmax, c->zmax, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_QUANT_T, s);
@@ -691,7 +724,7 @@ int ffn24_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void
     const int nd = c->n_dense, ns = F - nd;
     { Timed t(c, K_PART, s); if (t.done(launch_split_partition(c->nnz, F, nd, T, c->row_of_feat, c->feat_of_row, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_FW, s);
-      if (t.done(launch_featurewise24_split(c->Hc, c->meta, c->dZc, T, F, c->row_of_feat, ns, c->Hc_t, c->meta_t, c->dZc_t, c->Hdn_t, c->dZdn_t, c->tele, s)))
+      if (t.done(launch_featurewise24_split(c->Hc, c->meta, c->dZc, T, F, c->row_of_feat, ns, c->Hc_t, c->meta_t, c->dZc_t, c->Hdn_t, c->dZdn_t, c->tele, nullptr, nullptr, s)))
         return FFN24_ERR_HIP; }
     if (c->tele && (rc = tele_snapshot(c, 1, s))) return rc;
     { Timed t(c, K_TR_ACT, s);

@@ -120,6 +120,33 @@ struct EpiRelu2T {
 };
 using EpiRelu2 = EpiRelu2T<false>;
 
+// Per-feature non-zero counts of the activation epilogues (Sec. 2, "Optimization 1": the column-level sparsity the first GEMM's
+// epilogue can compute for free).  A lane counts its 4 tokens in 8-bit fields, 4 features per register: the packed pair of
+// features 16 mi + 2 d and + 1 goes to fields (2 d) % 4 and (2 d + 1) % 4 of register 4 mi + d / 2.
+__device__ __forceinline__ void nnz_count(uint32_t (&cnt)[16], uint32_t hpk, int mi, int d) {
+  uint32_t lo = min(hpk & 0xFFFFu, 1u), hi = min(hpk >> 16, 1u);
+  cnt[4 * mi + (d >> 1)] += (lo << (16 * (d & 1))) + (hi << (16 * (d & 1) + 8));
+}
+// The 32 lanes that hold the same 64 features add their fields up with a butterfly (<= 128 per field); lane r then adds the
+// totals of features r and r + 32 to nnz [F] with atomics (the caller zeroes it).
+__device__ __forceinline__ void nnz_flush(uint32_t (&cnt)[16], uint32_t* nnz, int m_lane) {
+  int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int i = 0; i < 16; i++)
+#pragma unroll
+    for (int sft = 1; sft < 32; sft <<= 1) cnt[i] += (uint32_t)__shfl_xor((int)cnt[i], sft, 64);
+  int r = lane & 31;
+  uint32_t w0 = 0u, w1 = 0u;
+#pragma unroll
+  for (int i = 0; i < 8; i++) {
+    w0 = (r >> 2) == i ? cnt[i] : w0;
+    w1 = (r >> 2) == i ? cnt[8 + i] : w1;
+  }
+  uint32_t c0 = (w0 >> (8 * (r & 3))) & 0xFFu, c1 = (w1 >> (8 * (r & 3))) & 0xFFu;
+  if (c0) atomicAdd(nnz + m_lane + r, c0);
+  if (c1) atomicAdd(nnz + m_lane + 32 + r, c1);
+}
+
 // Fused up-projection epilogue of the 2:4 FFN (Sec. 2: activation, then sparsification, in one pass):
 // h = bf16(max(0, acc + b1)^2); of every 4 consecutive features of a token keep the 2 largest
 // (ties -> lower index); write the kept pair and its metadata nibble.  The 4 members of a group are the
@@ -158,11 +185,7 @@ struct EpiPrune24T {
           float r0 = fmaxf(acc[mi][ni][2 * d] + b0, 0.f);
           float r1 = fmaxf(acc[mi][ni][2 * d + 1] + b1v, 0.f);
           hpk[d] = pack_bf16x2(r0 * r0, r1 * r1);
-          if constexpr (STATS) {
-            // features 16 mi + 2 d and + 1 of the lane: fields (2 d) % 4 and (2 d + 1) % 4 of register 4 mi + d / 2
-            uint32_t lo = min(hpk[d] & 0xFFFFu, 1u), hi = min(hpk[d] >> 16, 1u);
-            cnt[4 * mi + (d >> 1)] += (lo << (16 * (d & 1))) + (hi << (16 * (d & 1) + 8));
-          }
+          if constexpr (STATS) nnz_count(cnt, hpk[d], mi, d);
         }
         if (e.Hdbg) {
           __bf16* row = e.Hdbg + t * e.F + m_lane + 16 * mi;
@@ -196,24 +219,7 @@ struct EpiPrune24T {
         tele_add2(e.tele, tot | (kept << 16), TELE_NONZERO, TELE_KEPT_TOK, blockIdx.x + (threadIdx.x >> 6));
       }
     }
-    if constexpr (STATS) if (e.nnz) {
-      // totals over the 32 lanes of this lane half (<= 128 per field); then lane r adds features r and r + 32
-      int lane = threadIdx.x & 63;
-#pragma unroll
-      for (int i = 0; i < 16; i++)
-#pragma unroll
-        for (int sft = 1; sft < 32; sft <<= 1) cnt[i] += (uint32_t)__shfl_xor((int)cnt[i], sft, 64);
-      int r = lane & 31;
-      uint32_t w0 = 0u, w1 = 0u;
-#pragma unroll
-      for (int i = 0; i < 8; i++) {
-        w0 = (r >> 2) == i ? cnt[i] : w0;
-        w1 = (r >> 2) == i ? cnt[8 + i] : w1;
-      }
-      uint32_t c0 = (w0 >> (8 * (r & 3))) & 0xFFu, c1 = (w1 >> (8 * (r & 3))) & 0xFFu;
-      if (c0) atomicAdd(e.nnz + m_lane + r, c0);
-      if (c1) atomicAdd(e.nnz + m_lane + 32 + r, c1);
-    }
+    if constexpr (STATS) if (e.nnz) nnz_flush(cnt, e.nnz, m_lane);
   }
 };
 using EpiPrune24 = EpiPrune24T<false>;   // without the statistic (a compile-time switch: the plain kernel carries no trace of it)
@@ -450,9 +456,14 @@ struct EpiColMajorScaled {
 // block tiles -- so they are written as bf16 in the bf16 panel form (Hc, meta), and every lane raises rowmax[t] (bf16
 // word of the largest activation, non-negative, so integer order = value order) with one atomic per token.
 // A streaming kernel then quantises with sh[t] = rowmax[t] / 448 (k_stream.hip).
-struct EpiPrune24Rw {
-  struct Args { __bf16* Hc; uint8_t* meta; __bf16* Hdbg; const float* b1; int F; const float* sx; const float* sw1; uint32_t* rowmax; };
+// STATS: also the per-feature non-zero counts of the activation before pruning, into nnz [F] (as in EpiPrune24T).
+template <bool STATS>
+struct EpiPrune24RwT {
+  struct Args { __bf16* Hc; uint8_t* meta; __bf16* Hdbg; const float* b1; int F; const float* sx; const float* sw1; uint32_t* rowmax; uint32_t* nnz; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+    uint32_t cnt[16];
+#pragma unroll
+    for (int i = 0; i < 16; i++) cnt[i] = 0u;
     LaneVec64 lb, lw;
     lb.load(e.b1, m_lane, 0.f);
     lw.load(e.sw1, m_lane, 1.f);
@@ -473,6 +484,7 @@ struct EpiPrune24Rw {
           float r1 = fmaxf(acc[mi][ni][2 * d + 1] * (sxt * lw.at(16 * mi + 2 * d + 1)) + b1v, 0.f);
           hpk[d] = pack_bf16x2(r0 * r0, r1 * r1);
           mx = max(mx, max(hpk[d] & 0xFFFFu, hpk[d] >> 16));
+          if constexpr (STATS) nnz_count(cnt, hpk[d], mi, d);
         }
         if (e.Hdbg) {
           __bf16* row = e.Hdbg + t * e.F + m_lane + 16 * mi;
@@ -496,8 +508,10 @@ struct EpiPrune24Rw {
       *reinterpret_cast<u32x2*>(e.meta + piece * 8) = u32x2{nib[0], nib[1]};
       if (mx) atomicMax(e.rowmax + t, mx);
     }
+    if constexpr (STATS) nnz_flush(cnt, e.nnz, m_lane);
   }
 };
+using EpiPrune24Rw = EpiPrune24RwT<false>;
 
 // Dense fp8 up-projection with ROW-WISE scaling (the baseline the paper's forward benchmark compares with: all FP8 GEMMs of
 // both sides use row-wise scales): z = sx[t] sw1[f] acc + b1[f];  h = bf16(max(0, z)^2), every one of them stored, as the
@@ -618,6 +632,27 @@ struct EpiRowMajorRowCol {
         o[0] = pack_bf16x2(acc[mi][0][v] * r * cs[0], acc[mi][1][v] * r * cs[1]);
         o[1] = pack_bf16x2(acc[mi][2][v] * r * cs[2], acc[mi][3][v] * r * cs[3]);
         *reinterpret_cast<u32x2*>(e.C + (size_t)(m_lane + 16 * mi + v) * e.ldc + n_lane) = o;
+      }
+  }
+};
+
+// C[rowmap[m]][n] = bf16(acc * rs[m] * cs[n]): the split weight-gradient GEMMs of the row-wise fp8 backward (rows are positions
+// of the permuted feature space, rs their scales in that order; each row goes back to its feature).
+struct EpiRowMajorRowColMapped {
+  struct Args { __bf16* C; int ldc; const float* rs; const float* cs; const int* rowmap; };
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+    const f32x4 cs = *reinterpret_cast<const f32x4*>(e.cs + n_lane);
+    LaneVec64 lr;
+    lr.load(e.rs, m_lane, 1.f);
+#pragma unroll
+    for (int mi = 0; mi < 4; mi++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        const float r = lr.at(16 * mi + v);
+        u32x2 o;
+        o[0] = pack_bf16x2(acc[mi][0][v] * r * cs[0], acc[mi][1][v] * r * cs[1]);
+        o[1] = pack_bf16x2(acc[mi][2][v] * r * cs[2], acc[mi][3][v] * r * cs[3]);
+        *reinterpret_cast<u32x2*>(e.C + (size_t)e.rowmap[m_lane + 16 * mi + v] * e.ldc + n_lane) = o;
       }
   }
 };

@@ -686,15 +686,15 @@ __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(GemmArgs g, typename
 // "Optimization 1": a 2:4 GEMM over most hidden features plus a dense one over the few that are not sparse enough):
 // alone, the small dense GEMM would occupy a fraction of the CUs for as long as a full round of tiles.  The dense
 // tiles, which take longer, come first.
-template <class Epi>
+template <class Epi, bool F8 = false>
 __global__ void __launch_bounds__(GEMM_THREADS) gemm_pair_kernel(GemmArgs gd, typename Epi::Args ead, int nd_tiles,
                                                                   GemmArgs gs, typename Epi::Args eas) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int pid = blockIdx.x;
   ClkSample cs;
   cs.begin(gs);
-  if (pid < nd_tiles) gemm_tile<false, Epi>(gd, ead, smem, pid);
-  else gemm_tile<true, Epi>(gs, eas, smem, pid - nd_tiles);
+  if (pid < nd_tiles) gemm_tile<false, Epi, F8>(gd, ead, smem, pid);
+  else gemm_tile<true, Epi, F8>(gs, eas, smem, pid - nd_tiles);
   cs.end(gs);
 }
 

@@ -61,10 +61,23 @@ int launch_dense_colmajor_f8(const void* A8, int a_panel, const void* B8, int b_
 
 // row-wise-scaled variants (scales per token for the activation operand, per output channel for the weight)
 int launch_up_prune24_f8_rowwise(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, const float* sx, const float* sw1,
-                                 void* Hc16, uint8_t* meta16, void* Hdbg, uint32_t* rowmax, hipStream_t s) {
+                                 void* Hc16, uint8_t* meta16, void* Hdbg, uint32_t* rowmax, uint32_t* nnz, hipStream_t s) {
   GemmArgs g{W1t8, nullptr, X8, F, T, D, 1};
-  EpiPrune24Rw::Args ea{static_cast<__bf16*>(Hc16), meta16, static_cast<__bf16*>(Hdbg), b1, F, sx, sw1, rowmax};
+  EpiPrune24Rw::Args ea{static_cast<__bf16*>(Hc16), meta16, static_cast<__bf16*>(Hdbg), b1, F, sx, sw1, rowmax, nnz};
+  if (nnz) {
+    EpiPrune24RwT<true>::Args eas{static_cast<__bf16*>(Hc16), meta16, static_cast<__bf16*>(Hdbg), b1, F, sx, sw1, rowmax, nnz};
+    return launch_gemm<false, EpiPrune24RwT<true>, true>(g, eas, s);
+  }
   return launch_gemm<false, EpiPrune24Rw, true>(g, ea, s);
+}
+
+int launch_split_wgrad_f8_rowwise(const void* vals8, const uint8_t* meta, int ns, const void* Ad8, int nd, const void* B8, int N, int K,
+                                  const float* rs, const float* cs, void* C, int ldc, const int* rowmap, hipStream_t s) {
+  GemmArgs gs{vals8, meta, B8, ns, N, K, 1, nullptr, 1};
+  GemmArgs gd{Ad8, nullptr, B8, nd, N, K, 1, nullptr, 1};
+  EpiRowMajorRowColMapped::Args eas{static_cast<__bf16*>(C), ldc, rs, cs, rowmap};
+  EpiRowMajorRowColMapped::Args ead{static_cast<__bf16*>(C), ldc, rs + ns, cs, rowmap + ns};
+  return launch_gemm_pair<EpiRowMajorRowColMapped, true>(gd, ead, gs, eas, s);
 }
 
 int launch_up_relu2_f8_rowwise(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, const float* sx, const float* sw1,

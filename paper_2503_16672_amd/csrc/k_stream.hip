@@ -206,6 +206,20 @@ __global__ void __launch_bounds__(256) featurewise24_kernel(const uint16_t* __re
         if (has_z) *reinterpret_cast<u32x4*>(dZdn_t + o) = u32x4{z[0] | (z[1] << 16), z[2] | (z[3] << 16), z[4] | (z[5] << 16), z[6] | (z[7] << 16)};
 #pragma unroll
         for (int j = 0; j < 8; j++) kept += min(h[j], 1u);
+        if (hmax) {   // as below: the eight work items of a feature are neighbouring lanes and take this branch together
+          uint32_t mh = 0u, mz = 0u;
+#pragma unroll
+          for (int j = 0; j < 8; j++) { mh = max(mh, h[j]); mz = max(mz, z[j] & 0x7FFFu); }
+#pragma unroll
+          for (int sft = 1; sft < 8; sft <<= 1) {
+            mh = max(mh, (uint32_t)__shfl_xor((int)mh, sft, 64));
+            mz = max(mz, (uint32_t)__shfl_xor((int)mz, sft, 64));
+          }
+          if ((tid & 7) == 0) {
+            if (mh) atomicMax(hmax + orow, mh);
+            if (mz && has_z) atomicMax(zmax + orow, mz);
+          }
+        }
         continue;
       }
     }
@@ -301,11 +315,12 @@ int launch_featurewise24_rowmax(const void* Hc, const uint8_t* meta, const void*
 }
 
 int launch_featurewise24_split(const void* Hc, const uint8_t* meta, const void* dZc, int T, int F, const int* row_of_feat, int n_sparse,
-                               void* Hc_t, uint8_t* meta_t, void* dZc_t, void* Hdn_t, void* dZdn_t, unsigned long long* tele, hipStream_t s) {
+                               void* Hc_t, uint8_t* meta_t, void* dZc_t, void* Hdn_t, void* dZdn_t, unsigned long long* tele,
+                               uint32_t* hmax, uint32_t* zmax, hipStream_t s) {
   dim3 grid(F / FW_FEAT, T / FW_TOK);
   hipLaunchKernelGGL((featurewise24_kernel<true, true>), grid, dim3(256), 0, s, static_cast<const uint16_t*>(Hc), meta,
                      static_cast<const uint16_t*>(dZc), T, F, static_cast<uint16_t*>(Hc_t), meta_t, static_cast<uint16_t*>(dZc_t),
-                     row_of_feat, n_sparse, static_cast<uint16_t*>(Hdn_t), static_cast<uint16_t*>(dZdn_t), tele, nullptr, nullptr);
+                     row_of_feat, n_sparse, static_cast<uint16_t*>(Hdn_t), static_cast<uint16_t*>(dZdn_t), tele, hmax, zmax);
   return (int)hipGetLastError();
 }
 

@@ -69,9 +69,11 @@ int launch_split_wgrad(const void* vals, const uint8_t* meta, int ns, const void
 // (max_count: an upper bound of every count, the number of tokens)
 int launch_split_partition(const uint32_t* nnz, int F, int n_dense, int max_count, int* row_of_feat, int* feat_of_row, hipStream_t s);
 // feature-wise re-compression with the split: sparse features as in launch_featurewise24 (panel form, row = row_of_feat),
-// dense features as plain [n_dense][T] rows of H24 and dZ24 in dense panel form
+// dense features as plain [n_dense][T] rows of H24 and dZ24 in dense panel form; hmax, zmax (may be NULL, zeroed by the caller):
+// the largest stored magnitude word of every output row, sparse rows [0, n_sparse) first, then the dense ones
 int launch_featurewise24_split(const void* Hc, const uint8_t* meta, const void* dZc, int T, int F, const int* row_of_feat, int n_sparse,
-                               void* Hc_t, uint8_t* meta_t, void* dZc_t, void* Hdn_t, void* dZdn_t, unsigned long long* tele, hipStream_t s);
+                               void* Hc_t, uint8_t* meta_t, void* dZc_t, void* Hdn_t, void* dZdn_t, unsigned long long* tele,
+                               uint32_t* hmax, uint32_t* zmax, hipStream_t s);
 // dense GEMMs: A [M][K] (a_panel: in dense panel form), B [N][K]
 int launch_dense_rowmajor(const void* A, int a_panel, const void* B, int b_panel, int M, int N, int K, void* C, hipStream_t s);
 int launch_dense_colmajor(const void* A, int a_panel, const void* B, int b_panel, int M, int N, int K, void* Ct, hipStream_t s);
@@ -100,9 +102,13 @@ int launch_sp_rowmajor_f8(const void* vals8, const uint8_t* meta, int a_panel, c
 int launch_dense_rowmajor_f8(const void* A8, int a_panel, const void* B8, int b_panel, int M, int N, int K, float scale, void* C, hipStream_t s);
 // row-wise-scaled fp8 forward: sx [T], sw1 [F], sw2 [N]; the up-projection writes bf16 kept values (bf16 panel form)
 // and raises rowmax [T] (bf16 words; zeroed by the caller); quantise_rows turns them into the fp8 panel form with
-// sh[t] = rowmax[t] / 448 (1 for an all-zero row), which it also writes out
+// sh[t] = rowmax[t] / 448 (1 for an all-zero row), which it also writes out; nnz (may be NULL) as in launch_up_prune24
 int launch_up_prune24_f8_rowwise(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, const float* sx, const float* sw1,
-                                 void* Hc16, uint8_t* meta16, void* Hdbg, uint32_t* rowmax, hipStream_t s);
+                                 void* Hc16, uint8_t* meta16, void* Hdbg, uint32_t* rowmax, uint32_t* nnz, hipStream_t s);
+// split weight gradient of the row-wise fp8 backward (operands e4m3 in panel form): as launch_split_wgrad, with the result row m
+// scaled by rs[m] (scales in row order of the permuted feature space, sparse rows first) and column n by cs[n]
+int launch_split_wgrad_f8_rowwise(const void* vals8, const uint8_t* meta, int ns, const void* Ad8, int nd, const void* B8, int N, int K,
+                                  const float* rs, const float* cs, void* C, int ldc, const int* rowmap, hipStream_t s);
 // the dense row-wise-scaled baseline: up-projection writing every activation as bf16 (dense panel form) and raising rowmax;
 // quantise_rows_dense turns them into e4m3 (dense fp8 panel form) with sh[t] = rowmax[t] / 448; dense GEMM with sh[t] sw2[n]
 // (Ht16, may be NULL: the activation once more as the bf16 [F][T] operand, dense panel form)

@@ -20,12 +20,12 @@ static int launch_gemm(const GemmArgs& g_in, const typename Epi::Args& ea, hipSt
 }
 
 // dense GEMM gd and sparse GEMM gs in one launch (gemm_pair_kernel)
-template <class Epi>
+template <class Epi, bool F8 = false>
 static int launch_gemm_pair(const GemmArgs& gd, const typename Epi::Args& ead, const GemmArgs& gs_in, const typename Epi::Args& eas, hipStream_t s) {
   GemmArgs gs = gs_in;
   gs.clk = tl_gemm_clk;
-  auto kern = gemm_pair_kernel<Epi>;
-  constexpr int lds = Geo<true>::LDS_TOTAL > Geo<false>::LDS_TOTAL ? Geo<true>::LDS_TOTAL : Geo<false>::LDS_TOTAL;
+  auto kern = gemm_pair_kernel<Epi, F8>;
+  constexpr int lds = Geo<true, F8>::LDS_TOTAL > Geo<false, F8>::LDS_TOTAL ? Geo<true, F8>::LDS_TOTAL : Geo<false, F8>::LDS_TOTAL;
   static std::atomic<bool> configured[MAX_DEVICES] = {};
   if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds, configured)) return rc;
   int nd_tiles = (gd.M / TILE_M) * (gd.N / TILE_N), ns_tiles = (gs.M / TILE_M) * (gs.N / TILE_N);

@@ -382,7 +382,8 @@ class Context:
               "sdz_t": (13, torch.float32, lambda T, F: (T,)), "sh_f": (14, torch.float32, lambda T, F: (F,)),
               "sdz_f": (15, torch.float32, lambda T, F: (F,)), "dZc16": (16, torch.bfloat16, lambda T, F: (T, F // 2)),
               "dZ16_dense": (17, torch.bfloat16, lambda T, F: (T, F)), "H_dense_t": (18, torch.uint8, lambda T, F: (F, T)),
-              "dZ_dense_t": (19, torch.uint8, lambda T, F: (F, T))}
+              "dZ_dense_t": (19, torch.uint8, lambda T, F: (F, T)),
+              "Hdn_t": (20, torch.bfloat16, lambda T, F: (F // 4, T)), "dZdn_t": (21, torch.bfloat16, lambda T, F: (F // 4, T))}
 
     def saved(self, name: str) -> torch.Tensor:
         """Row-major copy of a saved tensor of the context (enqueued on the current stream)."""

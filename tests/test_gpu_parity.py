@@ -912,7 +912,7 @@ def test_ffn24_bwd_fp8_full_size_sampled(F24):
 
 
 def test_fp8_context_rules(F24):
-    with pytest.raises(F24.Ffn24Error) as e:                 # fp8 training: no split
+    with pytest.raises(F24.Ffn24Error) as e:                 # fp8: the split exists for the row-wise recipe only
         F24.Context(256, 256, 256, F24.FFN24_TRAINING | F24.FFN24_SPLIT, dtype=F24.FFN24_FP8_E4M3)
     assert e.value.code == -4
     # a row-wise training context takes ffn24_bwd_rowwise only, and only after a forward
@@ -1286,6 +1286,101 @@ def _fp8_rowwise_bwd_case(F24, T, D, Fh, sparsity, seed, rows=None, gsel=None):
     assert max(e_dw2, e_dw1, e_dw2_raw, e_dw1_raw, f_dw2_raw, f_dw1_raw) <= TOL_FP8
     assert np.count_nonzero(Hm) < np.count_nonzero(H24_g) or T * Fh > (1 << 24)                  # the second prune drops something
     ctx.close()
+
+
+def _fp8_rowwise_split_case(F24, T, D, Fh, sparsity, seed, n_dense, gsel=None):
+    """Row-wise-scaled fp8 backward with the split of the weight gradients (the least sparse n_dense features keep the
+    token-wise mask only).  The statistic and the partition bit-exact; then, for hidden-feature groups over all tokens: (S1)
+    every feature's scale and codes -- compressed for the sparse features, plain rows for the dense ones -- bit-exact from the
+    GPU's own bf16 tensors; (S2) both weight gradients on those codes; (S3) the same features from the raw inputs by the
+    definition.  dX does not see the split: compared with the unsplit context's, bit for bit."""
+    inp = synth.make_inputs_fp8_rowwise(T, D, Fh, sparsity, seed)
+    bw = synth.make_bwd_operands_fp8_rowwise(T, D, Fh, sparsity, seed)
+    d = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2", "sx", "sw1", "sw2")}
+    db = {k: torch.from_numpy(v).cuda() for k, v in bw.items()}
+    b1 = torch.from_numpy(inp["b1"]).cuda()
+    ops = (db["dY8r"], db["sdy_t"], db["dY8c"], db["sdy_d"], db["X8c"], db["sx_d"], db["W2_8r"], db["sw2_f"], db["W1_8c"], db["sw1_d"])
+    ctx = F24.Context(T, D, Fh, F24.FFN24_ROWWISE | F24.FFN24_TRAINING | F24.FFN24_SPLIT | F24.FFN24_DEBUG_DUMP_H, dtype=F24.FFN24_FP8_E4M3)
+    ctx.set_row_scales(d["sx"], d["sw1"], d["sw2"])
+    ctx.set_split(0)
+    ctx.ffn24_fwd(d["X"], d["W1"], b1, d["W2"])
+    dX0, dW1_0, dW2_0 = ctx.ffn24_bwd_rowwise(*ops)          # n_dense = 0: the unsplit path of the same context
+    dX0 = dX0.clone(); dW2_0 = dW2_0.clone()
+    ctx.set_split(n_dense)
+    ctx.ffn24_fwd(d["X"], d["W1"], b1, d["W2"])
+    dX, dW1, dW2 = ctx.ffn24_bwd_rowwise(*ops)
+    torch.cuda.synchronize()
+    assert torch.equal(dX, dX0) and not torch.equal(dW2, dW2_0)
+    dec = lambda c: O.e4m3_bits_to_f32(c).astype(np.float64)
+    s64 = lambda v: np.asarray(v, dtype=np.float32).astype(np.float64)
+    q448 = lambda amax: np.where(amax > 0, amax / np.float32(448.0), np.float32(1.0)).astype(np.float32)
+    # statistic and partition
+    nnz = ctx.saved("nnz").cpu().numpy().astype(np.int64)
+    Hd = ctx.saved("H_dump")
+    G = Fh // 4
+    gs = np.arange(G) if gsel is None else gsel
+    f4, f2 = _groups_to_cols(gs)
+    f4_t, f2_t = torch.from_numpy(f4).cuda(), torch.from_numpy(f2).cuda()
+    if gsel is None:
+        assert np.array_equal(nnz, O.feature_nnz(f64(Hd)))
+    else:
+        assert np.array_equal(nnz, torch.count_nonzero(Hd, dim=0).cpu().numpy()) and np.array_equal(nnz[f4], O.feature_nnz(f64(Hd[:, f4_t])))
+    dense = O.split_features(nnz, n_dense)
+    feat_of_row = ctx.saved("feat_of_row").cpu().numpy()
+    ns = Fh - n_dense
+    assert np.array_equal(feat_of_row[:ns], np.flatnonzero(~dense)) and np.array_equal(feat_of_row[ns:], np.flatnonzero(dense))
+    row_of_feat = np.empty(Fh, np.int64); row_of_feat[feat_of_row] = np.arange(Fh)
+    # S1: per feature, from the GPU's own bf16 kept values and dZ
+    Hc16_all, meta_all, dZc16_all = ctx.saved("Hc16"), ctx.saved("meta"), ctx.saved("dZc16")
+    Hc16_g = O.bf16_bits_to_f32(words_of(Hc16_all[:, f2_t])); dZc16_g = O.bf16_bits_to_f32(words_of(dZc16_all[:, f2_t])); meta_g = _meta_of_groups(meta_all, gs)
+    H24_g = O.decompress24(Hc16_g, meta_g); dZ24_g = O.decompress24(dZc16_g, meta_g)
+    _, mt_ref, M_T = O.featurewise24(H24_g)
+    Mw = np.where(dense[f4][None, :], True, M_T)
+    Hm = np.where(Mw, H24_g, np.float32(0)); Zm = np.where(Mw, dZ24_g, np.float32(0))
+    sh_ref = q448(Hm.max(axis=0)); sdz_ref = q448(np.abs(Zm).max(axis=0))
+    H8 = np.ascontiguousarray(O.f32_to_e4m3_bits(Hm / sh_ref[None, :]).T); Z8 = np.ascontiguousarray(O.f32_to_e4m3_bits(Zm / sdz_ref[None, :]).T)    # [features, T]
+    rows = torch.from_numpy(row_of_feat[f4]).cuda()
+    sh_f = ctx.saved("sh_f")[rows].cpu().numpy(); sdz_f = ctx.saved("sdz_f")[rows].cpu().numpy()
+    assert np.array_equal(sh_f, sh_ref) and np.array_equal(sdz_f, sdz_ref)
+    isd = dense[f4]
+    srows = torch.from_numpy(row_of_feat[f4][~isd]).cuda(); drows = torch.from_numpy(row_of_feat[f4][isd] - ns).cuda()
+    assert np.array_equal(ctx.saved("meta_t")[srows].cpu().numpy(), mt_ref[~isd])
+    assert np.array_equal(ctx.saved("Hc_t")[srows].cpu().numpy(), O.compress_with_meta(H8[~isd], mt_ref[~isd]))
+    assert np.array_equal(ctx.saved("dZc_t")[srows].cpu().numpy(), O.compress_with_meta(Z8[~isd], mt_ref[~isd]))
+    same = lambda a, b: np.array_equal(a & 0x7F, b & 0x7F) and np.array_equal(a[(a & 0x7F) != 0], b[(b & 0x7F) != 0])   # a zero's sign is free
+    assert same(ctx.saved("Hdn_t")[drows].cpu().numpy(), H8[isd]) and same(ctx.saved("dZdn_t")[drows].cpu().numpy(), Z8[isd])
+    assert 0 < isd.sum() < len(f4)
+    # S2: the weight gradients on those codes and scales
+    dW2_st = (dec(H8) @ dec(bw["dY8c"])) * s64(sh_ref)[:, None] * s64(bw["sdy_d"])[None, :]
+    dW1_st = (dec(Z8) @ dec(bw["X8c"])) * s64(sdz_ref)[:, None] * s64(bw["sx_d"])[None, :]
+    e_dw2 = O.max_rel_err(f64(dW2[f4_t]), dW2_st); e_dw1 = O.max_rel_err(f64(dW1[:, f4_t]).T, dW1_st)
+    r_dw2 = O.row_rel_err(f64(dW2[f4_t]), dW2_st)
+    # S3: the same features from the raw inputs, the partition handed over
+    f_g = O.ffn24_fwd_fp8_rowwise_codes(inp["X"], inp["sx"], inp["W1"][:, f4], inp["sw1"][f4], inp["b1"][f4], inp["W2"][f4], inp["sw2"])
+    bw_g = dict(bw); bw_g["W2_8r"] = bw["W2_8r"][f4]; bw_g["sw2_f"] = bw["sw2_f"][f4]; bw_g["W1_8c"] = bw["W1_8c"][:, f4]
+    g_g = O.ffn24_bwd_fp8_rowwise_codes(f_g, **bw_g, dense_features=dense[f4])
+    e_dw2_raw = O.max_rel_err(f64(dW2[f4_t]), g_g["dW2"]); e_dw1_raw = O.max_rel_err(f64(dW1[:, f4_t]), g_g["dW1"])
+    f_dw2_raw = O.fro_rel_err(f64(dW2[f4_t]), g_g["dW2"]); f_dw1_raw = O.fro_rel_err(f64(dW1[:, f4_t]), g_g["dW1"])
+    print(f"  fp8 row-wise split n_dense={n_dense}: {int(isd.sum())} dense / {len(f4)} features; dW2 staged {e_dw2:.2e} (row {r_dw2:.2e}) dW1 staged {e_dw1:.2e}  "
+          f"from raw inputs: dW2 {e_dw2_raw:.2e} (Frobenius {f_dw2_raw:.2e}) dW1 {e_dw1_raw:.2e} (Frobenius {f_dw1_raw:.2e})", flush=True)
+    assert max(e_dw2, r_dw2, e_dw1, e_dw2_raw, e_dw1_raw, f_dw2_raw, f_dw1_raw) <= TOL_FP8
+    ctx.close()
+
+
+@pytest.mark.parametrize("n_dense", [256, 512])
+def test_fp8_rowwise_split_small(F24, n_dense):
+    print(f"fp8 row-wise split T=512 D=256 F=2048 n_dense={n_dense}", flush=True)
+    _fp8_rowwise_split_case(F24, 512, 256, 2048, "per_feature", seed=67, n_dense=n_dense)
+
+
+@pytest.mark.timeout(900)
+def test_fp8_rowwise_split_full_size_sampled(F24):
+    """c5 with 2048 of the 32768 features (6.25 %) kept dense: statistic and partition bit-exact at full size, scales, codes and
+    weight gradients on a sample of feature groups from both parts."""
+    w = synth.WORKLOADS["c5"]
+    print("fp8 row-wise split full size c5, n_dense=2048", flush=True)
+    rng = np.random.default_rng(52)
+    _fp8_rowwise_split_case(F24, w.T, w.D, w.F, "per_feature", w.seed, 2048, gsel=np.sort(rng.choice(w.F // 4, 96, replace=False)))
 
 
 def _fp8_rowwise_dense_bwd_case(F24, T, D, Fh, sparsity, seed, rows=None, fsel=None):
