@@ -273,7 +273,7 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-tokens", type=int, default=4096, help="token slice the CPU oracle is timed on (about 15 s of CPU work at the default workload)")
     ap.add_argument("--split", type=int, default=0, help="keep this many hidden features (multiple of 256, <= d_ff/4) out of the "
-                    "feature-wise 2:4: split weight-gradient GEMMs (bf16 fwd+bwd workloads)")
+                    "feature-wise 2:4: split weight-gradient GEMMs (bf16 fwd+bwd workloads, and c5 with --fp8-bwd --rowwise)")
     ap.add_argument("--rowwise", action="store_true", help="fp8 workload with row-wise instead of per-tensor scales (2:4 FFN and dense baseline alike); with --fp8-bwd: forward and backward with every GEMM scaled row-wise, 2:4 FFN and dense baseline")
     ap.add_argument("--permute", action="store_true", help="run the bf16 workload with a fixed token permutation around the FFN")
     ap.add_argument("--telemetry", action="store_true", help="bf16 workloads: count sparsity and 2:4 drops while running (reported under \"telemetry\")")
@@ -310,8 +310,11 @@ def main() -> int:
         bwo = synth.make_bwd_operands_fp8_rowwise(T, D, F, w.sparsity, w.seed)
         dev = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2", "sx", "sw1", "sw2")}
         devb = {k: torch.from_numpy(v).cuda() for k, v in bwo.items()}
-        ctx = ffn24.Context(T, D, F, ffn24.FFN24_ROWWISE | ffn24.FFN24_TRAINING | ffn24.FFN24_DENSE, dtype=ffn24.FFN24_FP8_E4M3)
+        ctx = ffn24.Context(T, D, F, ffn24.FFN24_ROWWISE | ffn24.FFN24_TRAINING | ffn24.FFN24_DENSE | (ffn24.FFN24_SPLIT if args.split else 0),
+                            dtype=ffn24.FFN24_FP8_E4M3)
         ctx.set_row_scales(dev["sx"], dev["sw1"], dev["sw2"])
+        if args.split:
+            ctx.set_split(args.split)
     elif rowwise:
         inp = synth.make_inputs_fp8_rowwise(T, D, F, w.sparsity, w.seed)
         dev = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2", "sx", "sw1", "sw2")}

@@ -32,6 +32,16 @@ struct LaneVec64 {
   __device__ __forceinline__ float at(int i) const { return v[i >> 2][i & 3]; }   // feature m_lane + i
 };
 
+// The lane's 64 entries m_lane .. m_lane + 63 of a row map, loaded with 16-byte loads (the map and m_lane are 16-byte aligned).
+struct LaneIdx64 {
+  i32x4 v[16];
+  __device__ __forceinline__ void load(const int* p, int m_lane) {
+#pragma unroll
+    for (int i = 0; i < 16; i++) v[i] = *reinterpret_cast<const i32x4*>(p + m_lane + 4 * i);
+  }
+  __device__ __forceinline__ int at(int i) const { return v[i >> 2][i & 3]; }
+};
+
 // C[m][n], n contiguous: 4 consecutive columns per lane and row -> one 8-byte store per row.
 struct EpiRowMajor {
   struct Args { __bf16* C; int ldc; };
@@ -229,6 +239,8 @@ using EpiPrune24 = EpiPrune24T<false>;   // without the statistic (a compile-tim
 struct EpiRowMajorMapped {
   struct Args { __bf16* C; int ldc; const int* rowmap; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+    LaneIdx64 rows;
+    rows.load(e.rowmap, m_lane);
 #pragma unroll
     for (int mi = 0; mi < 4; mi++)
 #pragma unroll
@@ -236,7 +248,7 @@ struct EpiRowMajorMapped {
         u32x2 o;
         o[0] = pack_bf16x2(acc[mi][0][v], acc[mi][1][v]);
         o[1] = pack_bf16x2(acc[mi][2][v], acc[mi][3][v]);
-        *reinterpret_cast<u32x2*>(e.C + (size_t)e.rowmap[m_lane + 16 * mi + v] * e.ldc + n_lane) = o;
+        *reinterpret_cast<u32x2*>(e.C + (size_t)rows.at(16 * mi + v) * e.ldc + n_lane) = o;
       }
   }
 };
@@ -644,6 +656,8 @@ struct EpiRowMajorRowColMapped {
     const f32x4 cs = *reinterpret_cast<const f32x4*>(e.cs + n_lane);
     LaneVec64 lr;
     lr.load(e.rs, m_lane, 1.f);
+    LaneIdx64 rows;
+    rows.load(e.rowmap, m_lane);
 #pragma unroll
     for (int mi = 0; mi < 4; mi++)
 #pragma unroll
@@ -652,7 +666,7 @@ struct EpiRowMajorRowColMapped {
         u32x2 o;
         o[0] = pack_bf16x2(acc[mi][0][v] * r * cs[0], acc[mi][1][v] * r * cs[1]);
         o[1] = pack_bf16x2(acc[mi][2][v] * r * cs[2], acc[mi][3][v] * r * cs[3]);
-        *reinterpret_cast<u32x2*>(e.C + (size_t)e.rowmap[m_lane + 16 * mi + v] * e.ldc + n_lane) = o;
+        *reinterpret_cast<u32x2*>(e.C + (size_t)rows.at(16 * mi + v) * e.ldc + n_lane) = o;
       }
   }
 };

@@ -372,13 +372,16 @@ __device__ __forceinline__ void mfma_sparse1(const FragS& f, const IdxWords<F8> 
 // the same grid row (column) read the same A (B) panels at the same time, so that what one of them brings in from HBM
 // the others find in the memory-side cache.  Measured against one 8 x 4 patch per XCD with all XCDs side by side
 // along M (every round then streams the whole A operand): 3.5 % on the sparse GEMMs, nothing on the dense ones.
-// Shapes that the grid does not divide fall back to bands of 8 tile-rows, each XCD a contiguous run of tiles.
+// Tile-rows beyond the last whole round (ntm not a multiple of 32: the sparse part of a split weight gradient) and shapes whose
+// tile-columns the grid does not divide fall back to bands of 8 tile-rows, each XCD a contiguous run of tiles.
 template <int PROBE = 0>
 __device__ __forceinline__ void tile_coords(int ntm, int ntn, int pid, int& tm, int& tn) {
   // XCD grid, patch shape; GX * GY = 8 XCDs, PM * PN = 32 CUs
   constexpr int GX = (PROBE & PROBE_WALK_8x1) ? 8 : 4, GY = 8 / GX;
   constexpr int PM = (PROBE & PROBE_PATCH_4x8) ? 4 : ((PROBE & PROBE_PATCH_16x2) ? 16 : 8), PN = 32 / PM;
-  if (!(PROBE & PROBE_WALK_BANDS) && ntm % (PM * GX) == 0 && ntn % (PN * GY) == 0) {
+  int tm0 = 0;   // tile-rows [0, tm0) are walked in rounds, the rest in bands
+  if (!(PROBE & PROBE_WALK_BANDS) && ntn % (PN * GY) == 0) tm0 = ntm - ntm % (PM * GX);
+  if (pid < tm0 * ntn) {
     const int xcd = pid & 7, idx = pid >> 3;
     const int round = idx >> 5, j = idx & 31;
     const int rounds_n = ntn / (PN * GY);
@@ -386,6 +389,8 @@ __device__ __forceinline__ void tile_coords(int ntm, int ntn, int pid, int& tm, 
     tn = ((round % rounds_n) * GY + (xcd / GX)) * PN + (j / PM);
     return;
   }
+  pid -= tm0 * ntn;   // a multiple of 256: the low three bits are still the XCD
+  ntm -= tm0;
   int nb = ntm * ntn;
   if ((nb & 7) == 0) pid = (pid & 7) * (nb >> 3) + (pid >> 3);
   const int GROUP = 8;
@@ -394,7 +399,7 @@ __device__ __forceinline__ void tile_coords(int ntm, int ntn, int pid, int& tm, 
   int first = gid * GROUP;
   int gsz = min(ntm - first, GROUP);
   int in = pid - gid * per_group;
-  tm = first + in % gsz;
+  tm = tm0 + first + in % gsz;
   tn = in / gsz;
 }
 

@@ -329,7 +329,11 @@ int launch_featurewise24_split(const void* Hc, const uint8_t* meta, const void* 
 // bisection over the counts (which sit in LDS); every feature above it is dense, and of those equal to it the first
 // (n_dense - #above) by index.  Sparse features become rows 0 .. F - n_dense - 1, dense ones the rows after, both in
 // ascending feature order.  One workgroup of 1024; F <= 2^20 (beyond 32768 features the counts stay in global memory).
+// In LDS count f sits at word f + f / 32: the ranking passes give every thread a run of consecutive features, and without the
+// padding the lanes' runs would start a multiple of 32 words apart, all in two banks.  The rows are first written over the counts
+// in LDS and leave in feature order, so that the stores to row_of_feat are whole lines and those to feat_of_row nearly so.
 constexpr int PART_LDS_FEATS = 32768;
+__device__ __forceinline__ int part_slot(int f) { return f + (f >> 5); }
 
 __global__ void __launch_bounds__(1024) split_partition_kernel(const uint32_t* __restrict__ nnz_g, int F, int n_dense, uint32_t max_count,
                                                                int* __restrict__ row_of_feat, int* __restrict__ feat_of_row) {
@@ -338,9 +342,9 @@ __global__ void __launch_bounds__(1024) split_partition_kernel(const uint32_t* _
   __shared__ int s_total;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const bool in_lds = F <= PART_LDS_FEATS;
-  if (in_lds) for (int f = tid; f < F; f += 1024) s_nnz[f] = nnz_g[f];
+  if (in_lds) for (int f = tid; f < F; f += 1024) s_nnz[part_slot(f)] = nnz_g[f];
   __syncthreads();
-  const uint32_t* nnz = in_lds ? s_nnz : nnz_g;
+  auto nnz = [&](int f) { return in_lds ? s_nnz[part_slot(f)] : nnz_g[f]; };
   // block-wide sum, and exclusive prefix over threads, of one int per thread (wave shuffles + 16 partials in LDS)
   auto block_scan = [&](int v, int& total) {
     int incl = v;
@@ -362,21 +366,32 @@ __global__ void __launch_bounds__(1024) split_partition_kernel(const uint32_t* _
     __syncthreads();
     return excl;
   };
+  // block-wide sum alone (the bisection needs no prefix): wave shuffles, 16 partials in LDS that every thread adds up itself
+  auto block_sum = [&](int v) {
+#pragma unroll
+    for (int st = 1; st < 64; st <<= 1) v += __shfl_xor(v, st, 64);
+    if (lane == 0) s_part[wave] = v;
+    __syncthreads();
+    int total = 0;
+#pragma unroll
+    for (int w = 0; w < 16; w++) total += s_part[w];
+    __syncthreads();
+    return total;
+  };
   // bisection: invariant #{nnz > hi} <= n_dense and (lo == -1 or #{nnz > lo} > n_dense); strided accesses here
   long long lo = -1, hi = max_count;             // no count exceeds max_count (the number of tokens)
   while (hi - lo > 1) {
     long long mid = (lo + hi) >> 1;
-    int c = 0, total;
-    for (int f = tid; f < F; f += 1024) c += (long long)nnz[f] > mid;
-    block_scan(c, total);
-    if (total <= n_dense) hi = mid; else lo = mid;
+    int c = 0;
+    for (int f = tid; f < F; f += 1024) c += (long long)nnz(f) > mid;
+    if (block_sum(c) <= n_dense) hi = mid; else lo = mid;
   }
   const uint32_t cstar = (uint32_t)hi;
   // consecutive features per thread from here on, so that ranks follow the feature index
   const int per = (F + 1023) / 1024;
   const int f_lo = min(tid * per, F), f_hi = min(f_lo + per, F);
   int above = 0, equal = 0;
-  for (int f = f_lo; f < f_hi; f++) { above += nnz[f] > cstar; equal += nnz[f] == cstar; }
+  for (int f = f_lo; f < f_hi; f++) { above += nnz(f) > cstar; equal += nnz(f) == cstar; }
   int n_above, n_equal;
   block_scan(above, n_above);
   const int take_eq = n_dense - n_above;             // how many of the features equal to c* become dense (by index)
@@ -385,8 +400,8 @@ __global__ void __launch_bounds__(1024) split_partition_kernel(const uint32_t* _
   {
     int e = eq_before;
     for (int f = f_lo; f < f_hi; f++) {
-      bool d = nnz[f] > cstar || (nnz[f] == cstar && e < take_eq);
-      e += nnz[f] == cstar;
+      bool d = nnz(f) > cstar || (nnz(f) == cstar && e < take_eq);
+      e += nnz(f) == cstar;
       dense_here += d;
     }
   }
@@ -395,19 +410,27 @@ __global__ void __launch_bounds__(1024) split_partition_kernel(const uint32_t* _
   const int n_sparse = F - n_dense;
   int e = eq_before, dpos = d_before;
   for (int f = f_lo; f < f_hi; f++) {
-    bool d = nnz[f] > cstar || (nnz[f] == cstar && e < take_eq);
-    e += nnz[f] == cstar;
+    bool d = nnz(f) > cstar || (nnz(f) == cstar && e < take_eq);
+    e += nnz(f) == cstar;
     int row = d ? n_sparse + dpos : f - dpos;
     dpos += d;
-    row_of_feat[f] = row;
-    feat_of_row[row] = f;
+    if (in_lds) s_nnz[part_slot(f)] = (uint32_t)row;   // the thread's own slot: its count is not needed again
+    else { row_of_feat[f] = row; feat_of_row[row] = f; }
+  }
+  if (in_lds) {
+    __syncthreads();
+    for (int f = tid; f < F; f += 1024) {
+      int row = (int)s_nnz[part_slot(f)];
+      row_of_feat[f] = row;
+      feat_of_row[row] = f;
+    }
   }
 }
 
 int launch_split_partition(const uint32_t* nnz, int F, int n_dense, int max_count, int* row_of_feat, int* feat_of_row, hipStream_t s) {
   static std::atomic<bool> configured[MAX_DEVICES] = {};
-  if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(split_partition_kernel), 4 * PART_LDS_FEATS, configured)) return rc;
-  size_t lds = F <= PART_LDS_FEATS ? 4 * (size_t)F : 0;
+  if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(split_partition_kernel), 4 * (PART_LDS_FEATS + PART_LDS_FEATS / 32), configured)) return rc;
+  size_t lds = F <= PART_LDS_FEATS ? 4 * ((size_t)F + (size_t)F / 32) : 0;
   hipLaunchKernelGGL(split_partition_kernel, dim3(1), dim3(1024), lds, s, nnz, F, n_dense, (uint32_t)max_count, row_of_feat, feat_of_row);
   return (int)hipGetLastError();
 }
