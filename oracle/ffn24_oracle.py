@@ -717,6 +717,27 @@ def ffn24_bwd_fp8_rowwise_codes(fwd, dY8r, sdy_t, W2_8r, sw2_f, W1_8c, sw1_d, dY
     return out
 
 
+def ffn24_fwd_bwd_fp8_rowwise_permuted(X8, sx, W1_8, sw1, b1, W2_8, sw2, bw: dict, perm, wgrad_mask="featurewise", dense_features=None):
+    """Row-wise fp8 forward + backward with the fixed token permutation of Sec. 2, "Optimization 2" around the FFN, as
+    ffn24_fwd_bwd_permuted does it for bf16: position p inside the FFN holds token perm[p], so the FFN runs on the rows perm of
+    every per-token operand (X8 and sx; dY8r and sdy_t; the token rows of the column-quantised dY8c and X8c, whose scales belong to
+    model dimensions and stay), Y and dX are scattered back to token order, and the weight gradients keep their layout while
+    their feature-wise 2:4 groups are made of the tokens the permutation puts side by side.  bw = the backward operands of
+    ffn24_bwd_fp8_rowwise_codes by name."""
+    perm = np.asarray(perm, dtype=np.int64)
+    T = np.asarray(X8).shape[0]
+    if sorted(perm.tolist()) != list(range(T)):
+        raise ValueError("perm is not a permutation of the tokens")
+    f = ffn24_fwd_fp8_rowwise_codes(np.asarray(X8)[perm], np.asarray(sx)[perm], W1_8, sw1, b1, W2_8, sw2)
+    bwp = dict(bw)
+    for k in ("dY8r", "sdy_t", "dY8c", "X8c"):
+        bwp[k] = np.asarray(bw[k])[perm]
+    g = ffn24_bwd_fp8_rowwise_codes(f, **bwp, wgrad_mask=wgrad_mask, dense_features=dense_features)
+    Y = np.empty_like(f["Y"]); Y[perm] = f["Y"]
+    dX = np.empty_like(g["dX"]); dX[perm] = g["dX"]
+    return {"fwd": f, "bwd": g, "Y": Y, "dX": dX, "dW1": g["dW1"], "dW2": g["dW2"]}
+
+
 def ffn_bwd_fp8_rowwise_codes(fwd, dY8r, sdy_t, W2_8r, sw2_f, W1_8c, sw1_d, dY8c, sdy_d, X8c, sx_d, quantise_internal=True):
     """Dense counterpart of ffn24_bwd_fp8_rowwise_codes (no masks): the backward of ffn_fwd_fp8_rowwise_codes with every GEMM
     scaled row-wise.  Same operands from the caller; the internal tensors are quantised where they are made:

@@ -1008,3 +1008,30 @@ def test_fp8_rowwise_backward_split_is_column_separable():
         codes = torch.from_numpy((col / s).astype(np.float32)).to(torch.float8_e4m3fn)
         row = (codes.to(torch.float64).numpy() * np.float64(s)) @ dYv
         assert np.allclose(sp["dW2"][feat], row, rtol=1e-12, atol=1e-15) and np.abs(row).max() > 0, feat
+
+
+def test_fp8_rowwise_token_permutation_is_exact_for_everything_but_the_featurewise_groups():
+    """Sec. 2, Optimization 2 on the row-wise fp8 recipe.  Every per-token step -- the forward, dZ with its per-token scale, dX --
+    is computed row by row, so Y and dX come back bit for bit; with the token-wise mask only, a feature's scale is a maximum
+    over tokens and does not see their order, every element gets the same code, and the weight gradients are the same sums in
+    another order; with the feature-wise mask they change, because other tokens share a group of 4.  The identity permutation
+    changes nothing."""
+    inp, f, bw, fw = _fp8_rowwise_bwd_case(T=64, D=16, F=64, sparsity=0.4)
+    perm = synth.token_permutation(64, seed=5)
+    args = (fw["X8"], fw["sx"], fw["W1_8"], fw["sw1"], inp["b1"], fw["W2_8"], fw["sw2"], bw)
+    g_fw = O.ffn24_bwd_fp8_rowwise_codes(f, **bw)
+    g_tw = O.ffn24_bwd_fp8_rowwise_codes(f, **bw, wgrad_mask="tokenwise")
+    p_fw = O.ffn24_fwd_bwd_fp8_rowwise_permuted(*args, perm)
+    p_tw = O.ffn24_fwd_bwd_fp8_rowwise_permuted(*args, perm, wgrad_mask="tokenwise")
+    assert np.array_equal(p_fw["Y"], f["Y"]) and np.array_equal(p_fw["dX"], g_fw["dX"]) and np.abs(g_fw["dX"]).max() > 0
+    assert np.array_equal(p_fw["fwd"]["meta"], f["meta"][perm]) and np.array_equal(p_fw["bwd"]["sdz_t"], g_fw["sdz_t"][perm])
+    for k in ("sh_f", "sdz_f"):
+        assert np.array_equal(p_tw["bwd"][k], g_tw[k]), k              # maxima over tokens
+    np.testing.assert_allclose(p_tw["dW1"], g_tw["dW1"], rtol=0, atol=1e-12 * np.abs(g_tw["dW1"]).max())
+    np.testing.assert_allclose(p_tw["dW2"], g_tw["dW2"], rtol=0, atol=1e-12 * np.abs(g_tw["dW2"]).max())
+    assert np.abs(p_fw["dW2"] - g_fw["dW2"]).max() > 1e-3 * np.abs(g_fw["dW2"]).max()
+    assert not np.array_equal(p_fw["bwd"]["M_T"], g_fw["M_T"][perm])
+    ident = O.ffn24_fwd_bwd_fp8_rowwise_permuted(*args, np.arange(64))
+    assert np.array_equal(ident["dW2"], g_fw["dW2"]) and np.array_equal(ident["dW1"], g_fw["dW1"]) and np.array_equal(ident["Y"], f["Y"])
+    with pytest.raises(ValueError):
+        O.ffn24_fwd_bwd_fp8_rowwise_permuted(*args, np.zeros(64, int))
