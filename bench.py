@@ -275,7 +275,7 @@ def main() -> int:
     ap.add_argument("--split", type=int, default=0, help="keep this many hidden features (multiple of 256, <= d_ff/4) out of the "
                     "feature-wise 2:4: split weight-gradient GEMMs (bf16 fwd+bwd workloads, and c5 with --fp8-bwd --rowwise)")
     ap.add_argument("--rowwise", action="store_true", help="fp8 workload with row-wise instead of per-tensor scales (2:4 FFN and dense baseline alike); with --fp8-bwd: forward and backward with every GEMM scaled row-wise, 2:4 FFN and dense baseline")
-    ap.add_argument("--permute", action="store_true", help="run the bf16 workload with a fixed token permutation around the FFN")
+    ap.add_argument("--permute", action="store_true", help="run the bf16 workload (or c5 with --fp8-bwd --rowwise) with a fixed token permutation around the FFN")
     ap.add_argument("--telemetry", action="store_true", help="bf16 workloads: count sparsity and 2:4 drops while running (reported under \"telemetry\")")
     ap.add_argument("--split-sweep", action="store_true", help="time the weight-gradient stage over a range of split sizes")
     ap.add_argument("--calib-copy", action="store_true",
@@ -310,11 +310,13 @@ def main() -> int:
         bwo = synth.make_bwd_operands_fp8_rowwise(T, D, F, w.sparsity, w.seed)
         dev = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2", "sx", "sw1", "sw2")}
         devb = {k: torch.from_numpy(v).cuda() for k, v in bwo.items()}
-        ctx = ffn24.Context(T, D, F, ffn24.FFN24_ROWWISE | ffn24.FFN24_TRAINING | ffn24.FFN24_DENSE | (ffn24.FFN24_SPLIT if args.split else 0),
-                            dtype=ffn24.FFN24_FP8_E4M3)
+        ctx = ffn24.Context(T, D, F, ffn24.FFN24_ROWWISE | ffn24.FFN24_TRAINING | ffn24.FFN24_DENSE | (ffn24.FFN24_SPLIT if args.split else 0)
+                            | (ffn24.FFN24_PERMUTE if args.permute else 0), dtype=ffn24.FFN24_FP8_E4M3)
         ctx.set_row_scales(dev["sx"], dev["sw1"], dev["sw2"])
         if args.split:
             ctx.set_split(args.split)
+        if args.permute:
+            ctx.set_token_permutation(synth.token_permutation(T, w.seed + 1))
     elif rowwise:
         inp = synth.make_inputs_fp8_rowwise(T, D, F, w.sparsity, w.seed)
         dev = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2", "sx", "sw1", "sw2")}
@@ -535,7 +537,7 @@ def main() -> int:
         "dtype": "fp8" if fp8 else "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: 2:4 Squared-ReLU FFN {'fwd+bwd' if bwd else 'fwd'}, T={T} d_model={D} d_ff={F}, target sparsity {w.sparsity}"
                                + (f", {args.split} dense features in the weight gradients" if args.split and bwd else "")
-                               + (", row-wise fp8 scales" if rowwise or rowwise_bwd else "") + (", fixed token permutation" if args.permute and not fp8 else "")
+                               + (", row-wise fp8 scales" if rowwise or rowwise_bwd else "") + (", fixed token permutation" if args.permute and (not fp8 or rowwise_bwd) else "")
                                + (", weights prepared once" if prepared else ""),
                    "T": T, "d_model": D, "d_ff": F, "parallelism": "single GPU"},
         "frac_of_sparse_mfma_peak": round(value / (2 * peak), 4),

@@ -61,7 +61,7 @@ typedef enum { FFN24_BF16 = 0, FFN24_FP8_E4M3 = 1 } ffn24_dtype;
 #define FFN24_DEBUG_DUMP_H 4 /* ffn24_fwd also stores the rounded activation before pruning, [T][F] */
 #define FFN24_SPLIT 8        /* allocate what the split weight-gradient GEMMs need (with FFN24_TRAINING; see ffn24_set_split) */
 #define FFN24_ROWWISE 16     /* fp8 context with row-wise instead of per-tensor scales (see ffn24_set_row_scales) */
-#define FFN24_PERMUTE 32     /* bf16 context that can run with a token permutation (see ffn24_set_token_permutation) */
+#define FFN24_PERMUTE 32     /* context that can run with a token permutation (bf16, or fp8 with FFN24_ROWWISE; see ffn24_set_token_permutation) */
 #define FFN24_TELEMETRY 64   /* bf16 context whose forwards and backwards count sparsity and drops (see ffn24_get_telemetry) */
 
 typedef struct ffn24_ctx ffn24_ctx; /* opaque; owns only its device workspace */
@@ -180,7 +180,9 @@ FFN24_API int ffn_bwd_rowwise(ffn24_ctx* ctx, const ffn24_rowwise_bwd_operands* 
  * and dY are gathered by the operand DMA of the GEMMs that read them and the rows of Y and dX are scattered by the
  * epilogues of the GEMMs that produce them, so no extra pass over any tensor is made.  Inside, every saved tensor is in
  * permuted token order, and the feature-wise 2:4 groups of the weight gradients are made of the tokens the permutation
- * puts side by side.  Needs FFN24_PERMUTE (bf16 contexts; T d_model < 2^31). */
+ * puts side by side.  Needs FFN24_PERMUTE (bf16 contexts, T d_model < 2^31; row-wise fp8 contexts, T d_model < 2^32, where
+ * ffn24_fwd / ffn24_bwd_rowwise also bring the caller's per-token scales sx and sdy_t into that order; a per-tensor fp8 context
+ * has no permutation: FFN24_ERR_DTYPE at creation). */
 FFN24_API int ffn24_set_token_permutation(ffn24_ctx* ctx, const int32_t* perm_host);
 
 /* Split of the weight-gradient GEMMs (paper Sec. 2, "Optimization 1"): some hidden features are too dense to be

@@ -62,6 +62,7 @@ struct ffn24_ctx {
   void* W1p;   // W1 itself in B panel form (B operand of the dX GEMMs)
   // split weight gradients (FFN24_SPLIT)
   uint32_t* nnz; int* row_of_feat; int* feat_of_row; void* Hdn_t; void* dZdn_t; void* dW1t;
+  float* sx_p; float* sdy_p;     // row-wise fp8 with a token permutation: the caller's per-token scales of X and dY in FFN order
   void* Hdn8_t; void* dZdn8_t;   // row-wise fp8 split: the dense features' rows as e4m3 (Hdn_t, dZdn_t hold them in bf16 first)
   int n_dense;
   // telemetry (FFN24_TELEMETRY): device slots the kernels add to, their sums, and two pinned host snapshots that the
@@ -101,7 +102,7 @@ int free_all(ffn24_ctx* c) {
                   c->W1t, c->W2t, c->Xt, c->dYt, c->Hd_t, c->dZd_t, c->W2p, c->W1p,
                   c->nnz, c->row_of_feat, c->feat_of_row, c->Hdn_t, c->dZdn_t, c->dW1t, c->Hc16, c->meta16, c->rowmax, c->rsh, c->perm, c->Hd16,
                   c->dZc16, c->Hct16, c->dZct16, c->meta_t16, c->rowmax_dz, c->hmax, c->zmax, c->sdz_t, c->sh_f, c->sdz_f, c->W2rp, c->W1cp,
-                  c->dZd16, c->Hdt16, c->dZdt16, c->Hdn8_t, c->dZdn8_t};
+                  c->dZd16, c->Hdt16, c->dZdt16, c->Hdn8_t, c->dZdn8_t, c->sx_p, c->sdy_p};
   for (void* b : bufs) if (b && hipFree(b) != hipSuccess) bad = 1;
   if (c->clk && hipFree(c->clk) != hipSuccess) bad = 1;
   if (c->tele && hipFree(c->tele) != hipSuccess) bad = 1;
@@ -188,10 +189,10 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
   if (f8 && (flags & FFN24_SPLIT) && !(flags & FFN24_ROWWISE)) return FFN24_ERR_DTYPE;                      // fp8: the split needs the row-wise recipe
   if ((flags & FFN24_SPLIT) && !(flags & FFN24_TRAINING)) return FFN24_ERR_STATE;
   if ((flags & FFN24_ROWWISE) && !f8) return FFN24_ERR_DTYPE;
-  if ((flags & FFN24_PERMUTE) && f8) return FFN24_ERR_DTYPE;
+  if ((flags & FFN24_PERMUTE) && f8 && !(flags & FFN24_ROWWISE)) return FFN24_ERR_DTYPE;                    // fp8: the permutation too
   if ((flags & FFN24_TELEMETRY) && f8) return FFN24_ERR_DTYPE;
   // the DMA gathers permuted rows with 32-bit byte offsets from the tensor base
-  if ((flags & FFN24_PERMUTE) && (uint64_t)T * (uint64_t)D * 2u >= (1ull << 32)) return FFN24_ERR_SHAPE;
+  if ((flags & FFN24_PERMUTE) && (uint64_t)T * (uint64_t)D * (f8 ? 1u : 2u) >= (1ull << 32)) return FFN24_ERR_SHAPE;
   if (T <= 0 || D <= 0 || F <= 0 || T % 256 || D % 256 || F % 256) return FFN24_ERR_SHAPE;
   if (T > (1 << 20) || D > (1 << 20) || F > (1 << 20)) return FFN24_ERR_SHAPE;
   ffn24_ctx* c = new (std::nothrow) ffn24_ctx();
@@ -224,6 +225,8 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
          hipMalloc(&c->dW1t, 2 * df) == hipSuccess;
   if (ok && f8 && (flags & FFN24_SPLIT)) ok = hipMalloc(&c->Hdn8_t, tf / 4) == hipSuccess && hipMalloc(&c->dZdn8_t, tf / 4) == hipSuccess;
   if (ok && (flags & FFN24_PERMUTE)) ok = hipMalloc(reinterpret_cast<void**>(&c->perm), 4 * (size_t)T) == hipSuccess;
+  if (ok && (flags & FFN24_PERMUTE) && f8)
+    ok = hipMalloc(reinterpret_cast<void**>(&c->sx_p), 4 * (size_t)T) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->sdy_p), 4 * (size_t)T) == hipSuccess;
   if (ok && (flags & FFN24_ROWWISE) && !c->Hc16)
     ok = hipMalloc(&c->Hc16, tf) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->meta16), tf / 8) == hipSuccess;
   if (ok && (flags & FFN24_ROWWISE))
@@ -560,12 +563,19 @@ int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, cons
     if (launch_zero32(c->rowmax, (size_t)T, s)) return FFN24_ERR_HIP;
     uint32_t* nnz = (c->flags & FFN24_SPLIT) && c->n_dense > 0 ? c->nnz : nullptr;
     if (nnz && launch_zero32(nnz, (size_t)F, s)) return FFN24_ERR_HIP;
+    // token permutation: position p inside the FFN holds token perm[p] -- its row of X8 is gathered by the operand DMA, its
+    // scale by a small kernel; everything in between lives in FFN order, and Y's rows go back to their tokens
+    const int* perm = c->perm_on ? c->perm : nullptr;
+    const float* sx = c->rsx;
+    if (perm) { if (launch_gather_f32(c->rsx, perm, T, c->sx_p, s)) return FFN24_ERR_HIP; sx = c->sx_p; }
     { Timed t(c, K_UP, s);
-      if (t.done(launch_up_prune24_f8_rowwise(c->W1t, X, b1, T, D, F, c->rsx, c->rsw1, c->Hc16, c->meta16, c->Hdbg, c->rowmax, nnz, s))) return FFN24_ERR_HIP; }
+      if (t.done(launch_up_prune24_f8_rowwise(c->W1t, X, b1, T, D, F, sx, c->rsw1, c->Hc16, c->meta16, c->Hdbg, c->rowmax, nnz, perm, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_QUANT, s);
       if (t.done(launch_quantise_rows(c->Hc16, c->meta16, c->rowmax, T, F, c->Hc, c->meta, c->rsh, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_DOWN, s);
-      if (t.done(launch_sp_rowmajor_f8_rowwise(c->Hc, c->meta, c->W2t, T, D, F, c->rsh, c->rsw2, Y, s))) return FFN24_ERR_HIP; }
+      int rc1 = perm ? launch_sp_rowmajor_f8_rowwise_mapped(c->Hc, c->meta, c->W2t, T, D, F, c->rsh, c->rsw2, Y, perm, s)
+                     : launch_sp_rowmajor_f8_rowwise(c->Hc, c->meta, c->W2t, T, D, F, c->rsh, c->rsw2, Y, s);
+      if (t.done(rc1)) return FFN24_ERR_HIP; }
     if (c->flags & FFN24_TRAINING) { c->X = X; c->have_fwd24 = 1; }
     return FFN24_OK;
   }
@@ -638,12 +648,17 @@ int ffn24_bwd_rowwise(ffn24_ctx* c, const ffn24_rowwise_bwd_operands* op, void* 
     int rc1 = launch_panelise8(op->W2_8r, F, D, c->W2rp, 0, s);
     if (t.done(rc1 ? rc1 : launch_panelise8(op->W1_8c, D, F, c->W1cp, 1, s))) return FFN24_ERR_HIP; }
   if (launch_zero32(c->rowmax_dz, (size_t)T, s) || launch_zero32(c->hmax, (size_t)F, s) || launch_zero32(c->zmax, (size_t)F, s)) return FFN24_ERR_HIP;
+  const int* perm = c->perm_on ? c->perm : nullptr;   // as in the forward: dY8r's rows and scales gathered, dX's rows scattered back
+  const float* sdy_t = op->sdy_t;
+  if (perm) { if (launch_gather_f32(op->sdy_t, perm, T, c->sdy_p, s)) return FFN24_ERR_HIP; sdy_t = c->sdy_p; }
   { Timed t(c, K_DH, s);
-    if (t.done(launch_dh_gather_f8_rowwise(c->W2rp, op->dY8r, c->Hc16, c->meta16, T, D, F, op->sw2_f, op->sdy_t, c->dZc16, c->rowmax_dz, s))) return FFN24_ERR_HIP; }
+    if (t.done(launch_dh_gather_f8_rowwise(c->W2rp, op->dY8r, c->Hc16, c->meta16, T, D, F, op->sw2_f, sdy_t, c->dZc16, c->rowmax_dz, perm, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_QUANT_DZ, s);
     if (t.done(launch_quantise_rows(c->dZc16, c->meta16, c->rowmax_dz, T, F, c->dZc, c->meta, c->sdz_t, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_DX, s);
-    if (t.done(launch_sp_rowmajor_f8_rowwise(c->dZc, c->meta, c->W1cp, T, D, F, c->sdz_t, op->sw1_d, dX, s))) return FFN24_ERR_HIP; }
+    int rc1 = perm ? launch_sp_rowmajor_f8_rowwise_mapped(c->dZc, c->meta, c->W1cp, T, D, F, c->sdz_t, op->sw1_d, dX, perm, s)
+                   : launch_sp_rowmajor_f8_rowwise(c->dZc, c->meta, c->W1cp, T, D, F, c->sdz_t, op->sw1_d, dX, s);
+    if (t.done(rc1)) return FFN24_ERR_HIP; }
   if ((c->flags & FFN24_SPLIT) && c->n_dense > 0) {
     // Sec. 2, "Optimization 1" on the row-wise recipe: the n_dense least sparse features keep the token-wise mask only; every
     // row of the permuted feature space (sparse rows first) gets its own scale, the sparse rows are quantised in compressed form,
@@ -659,8 +674,8 @@ int ffn24_bwd_rowwise(ffn24_ctx* c, const ffn24_rowwise_bwd_operands* op, void* 
       if (!rc1) rc1 = launch_quantise_rows_dense(c->Hdn_t, c->hmax + ns, nd, T, c->Hdn8_t, c->sh_f + ns, s);
       if (t.done(rc1 ? rc1 : launch_quantise_rows_dense(c->dZdn_t, c->zmax + ns, nd, T, c->dZdn8_t, c->sdz_f + ns, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_TR_ACT, s);
-      int rc1 = launch_transpose8(op->dY8c, T, D, c->dYt, 2, nullptr, 0, s);
-      if (t.done(rc1 ? rc1 : launch_transpose8(op->X8c, T, D, c->Xt, 2, nullptr, 0, s))) return FFN24_ERR_HIP; }
+      int rc1 = launch_transpose8_rows(op->dY8c, T, D, c->dYt, 2, perm, s);
+      if (t.done(rc1 ? rc1 : launch_transpose8_rows(op->X8c, T, D, c->Xt, 2, perm, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_DW2, s);
       if (t.done(launch_split_wgrad_f8_rowwise(c->Hc_t, c->meta_t, ns, c->Hdn8_t, nd, c->dYt, D, T, c->sh_f, op->sdy_d, dW2, D, c->feat_of_row, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_DW1, s);
@@ -674,8 +689,8 @@ int ffn24_bwd_rowwise(ffn24_ctx* c, const ffn24_rowwise_bwd_operands* op, void* 
     int rc1 = launch_quantise_rows(c->Hct16, c->meta_t16, c->hmax, F, T, c->Hc_t, c->meta_t, c->sh_f, s);
     if (t.done(rc1 ? rc1 : launch_quantise_rows(c->dZct16, c->meta_t16, c->zmax, F, T, c->dZc_t, c->meta_t, c->sdz_f, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_TR_ACT, s);
-    int rc1 = launch_transpose8(op->dY8c, T, D, c->dYt, 2, nullptr, 0, s);
-    if (t.done(rc1 ? rc1 : launch_transpose8(op->X8c, T, D, c->Xt, 2, nullptr, 0, s))) return FFN24_ERR_HIP; }
+    int rc1 = launch_transpose8_rows(op->dY8c, T, D, c->dYt, 2, perm, s);
+    if (t.done(rc1 ? rc1 : launch_transpose8_rows(op->X8c, T, D, c->Xt, 2, perm, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_DW2, s);
     if (t.done(launch_sp_rowmajor_f8_rowwise(c->Hc_t, c->meta_t, c->dYt, F, D, T, c->sh_f, op->sdy_d, dW2, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_DW1, s);

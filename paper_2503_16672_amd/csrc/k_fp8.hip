@@ -61,14 +61,21 @@ int launch_dense_colmajor_f8(const void* A8, int a_panel, const void* B8, int b_
 
 // row-wise-scaled variants (scales per token for the activation operand, per output channel for the weight)
 int launch_up_prune24_f8_rowwise(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, const float* sx, const float* sw1,
-                                 void* Hc16, uint8_t* meta16, void* Hdbg, uint32_t* rowmax, uint32_t* nnz, hipStream_t s) {
-  GemmArgs g{W1t8, nullptr, X8, F, T, D, 1};
+                                 void* Hc16, uint8_t* meta16, void* Hdbg, uint32_t* rowmax, uint32_t* nnz, const int* token_map, hipStream_t s) {
+  GemmArgs g{W1t8, nullptr, X8, F, T, D, 1, token_map};
   EpiPrune24Rw::Args ea{static_cast<__bf16*>(Hc16), meta16, static_cast<__bf16*>(Hdbg), b1, F, sx, sw1, rowmax, nnz};
   if (nnz) {
     EpiPrune24RwT<true>::Args eas{static_cast<__bf16*>(Hc16), meta16, static_cast<__bf16*>(Hdbg), b1, F, sx, sw1, rowmax, nnz};
     return launch_gemm<false, EpiPrune24RwT<true>, true>(g, eas, s);
   }
   return launch_gemm<false, EpiPrune24Rw, true>(g, ea, s);
+}
+
+int launch_sp_rowmajor_f8_rowwise_mapped(const void* vals8, const uint8_t* meta, const void* B8, int M, int N, int K, const float* rs, const float* cs,
+                                         void* C, const int* rowmap, hipStream_t s) {
+  GemmArgs g{vals8, meta, B8, M, N, K, 1, nullptr, 1};
+  EpiRowMajorRowColMapped::Args ea{static_cast<__bf16*>(C), N, rs, cs, rowmap};
+  return launch_gemm<true, EpiRowMajorRowColMapped, true>(g, ea, s);
 }
 
 int launch_split_wgrad_f8_rowwise(const void* vals8, const uint8_t* meta, int ns, const void* Ad8, int nd, const void* B8, int N, int K,
@@ -103,8 +110,8 @@ int launch_sp_rowmajor_f8_rowwise(const void* vals8, const uint8_t* meta, const 
 // row-wise-scaled backward: the dH GEMM with the pointwise part fused (bf16 compressed dZ + row maxima out), and the sparse GEMM
 // with the transposing store and a scale per row and per column (dW1)
 int launch_dh_gather_f8_rowwise(const void* W2rp8, const void* dY8r, const void* Hc16, const uint8_t* meta16, int T, int D, int F,
-                                const float* sw2_f, const float* sdy_t, void* dZc16, uint32_t* rowmax, hipStream_t s) {
-  GemmArgs g{W2rp8, nullptr, dY8r, F, T, D, 1};
+                                const float* sw2_f, const float* sdy_t, void* dZc16, uint32_t* rowmax, const int* token_map, hipStream_t s) {
+  GemmArgs g{W2rp8, nullptr, dY8r, F, T, D, 1, token_map};
   EpiDGatherRw::Args ea{static_cast<const __bf16*>(Hc16), meta16, static_cast<__bf16*>(dZc16), F, sw2_f, sdy_t, rowmax};
   return launch_gemm<false, EpiDGatherRw, true>(g, ea, s);
 }

@@ -532,15 +532,16 @@ int launch_transpose(const void* in, int R, int C, void* out, int out_form, void
 // bytes of a transposed row and writes them out.  OUT_FORM: 0 row-major, 1 dense panel form (64-byte pieces of 64 k,
 // K = R), 2 the B panel form.
 // in_panel (optional): a copy of the input itself in panel form (K = C, 64-byte pieces), made in the same pass; in the
-// B form if in_panel_b.
+// B form if in_panel_b.  in_rowmap (optional): input row r is read from memory row in_rowmap[r] (token permutation).
 template <int OUT_FORM>
 __global__ void __launch_bounds__(256) transpose8_kernel(const uint8_t* __restrict__ in, int R, int C, uint8_t* __restrict__ out,
-                                                         uint8_t* __restrict__ in_panel, int in_panel_b) {
+                                                         uint8_t* __restrict__ in_panel, int in_panel_b, const int* __restrict__ in_rowmap) {
   __shared__ __attribute__((aligned(16))) uint8_t sT[64 * 68];
   int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
   int tid = threadIdx.x;
   int ch = tid & 3, rr = tid >> 2;
-  u32x4 v = *reinterpret_cast<const u32x4*>(in + (size_t)(r0 + rr) * C + c0 + 16 * ch);
+  size_t src_row = in_rowmap ? (size_t)in_rowmap[r0 + rr] : (size_t)(r0 + rr);
+  u32x4 v = *reinterpret_cast<const u32x4*>(in + src_row * C + c0 + 16 * ch);
   if (in_panel) {
     int prow = in_panel_b ? b_panel_pos(r0 + rr) : r0 + rr;
     *reinterpret_cast<u32x4*>(in_panel + a24_piece(prow, c0 >> 6, C >> 6) * 64 + 16 * ch) = v;
@@ -563,7 +564,26 @@ int launch_transpose8(const void* in, int R, int C, void* out, int out_form, voi
   dim3 grid(C / 64, R / 64);
   auto kern = out_form == 2 ? transpose8_kernel<2> : (out_form == 1 ? transpose8_kernel<1> : transpose8_kernel<0>);
   hipLaunchKernelGGL(kern, grid, dim3(256), 0, s, static_cast<const uint8_t*>(in), R, C, static_cast<uint8_t*>(out),
-                     static_cast<uint8_t*>(in_panel), in_panel_b);
+                     static_cast<uint8_t*>(in_panel), in_panel_b, static_cast<const int*>(nullptr));
+  return (int)hipGetLastError();
+}
+
+int launch_transpose8_rows(const void* in, int R, int C, void* out, int out_form, const int* in_rowmap, hipStream_t s) {
+  dim3 grid(C / 64, R / 64);
+  auto kern = out_form == 2 ? transpose8_kernel<2> : (out_form == 1 ? transpose8_kernel<1> : transpose8_kernel<0>);
+  hipLaunchKernelGGL(kern, grid, dim3(256), 0, s, static_cast<const uint8_t*>(in), R, C, static_cast<uint8_t*>(out),
+                     static_cast<uint8_t*>(nullptr), 0, in_rowmap);
+  return (int)hipGetLastError();
+}
+
+// dst[i] = src[map[i]]: a per-token scale vector brought into the order of a token permutation
+__global__ void __launch_bounds__(256) gather_f32_kernel(const float* __restrict__ src, const int* __restrict__ map, int n, float* __restrict__ dst) {
+  int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = src[map[i]];
+}
+
+int launch_gather_f32(const float* src, const int* map, int n, float* dst, hipStream_t s) {
+  hipLaunchKernelGGL(gather_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, src, map, n, dst);
   return (int)hipGetLastError();
 }
 

@@ -107,12 +107,12 @@ def make_inputs_fp8(T: int, D: int, F: int, sparsity, seed: int, sh: float = 16.
     return out
 
 
-def make_inputs_fp8_rowwise(T: int, D: int, F: int, sparsity, seed: int) -> dict:
+def make_inputs_fp8_rowwise(T: int, D: int, F: int, sparsity, seed: int, token_corr=None) -> dict:
     """fp8 workload with row-wise scales: X quantised per token row, W1 and W2 per output channel (column), each with
     s = amax / 448 of its row / column (1 where that is zero), by torch's CPU cast.  Returns codes X [T,D], W1 [D,F],
-    W2 [F,D] (uint8), scales sx [T], sw1 [F], sw2 [D] (float32) and b1."""
+    W2 [F,D] (uint8), scales sx [T], sw1 [F], sw2 [D] (float32) and b1.  token_corr as in make_inputs."""
     import torch
-    inp = make_inputs(T, D, F, sparsity, seed)
+    inp = make_inputs(T, D, F, sparsity, seed, token_corr=token_corr)
 
     def quant(x, axis):
         amax = np.abs(x).max(axis=axis, keepdims=True).astype(np.float32)
@@ -126,14 +126,14 @@ def make_inputs_fp8_rowwise(T: int, D: int, F: int, sparsity, seed: int) -> dict
     return out
 
 
-def make_bwd_operands_fp8_rowwise(T: int, D: int, F: int, sparsity, seed: int) -> dict:
+def make_bwd_operands_fp8_rowwise(T: int, D: int, F: int, sparsity, seed: int, token_corr=None) -> dict:
     """The operands of the row-wise-scaled fp8 backward for the workload of make_inputs_fp8_rowwise(T, D, F, sparsity, seed):
     dY ~ N(0, 1) (seeded) and the float X, W1, W2 of that workload, each quantised with one scale per index of the
     dimension its backward GEMM does NOT reduce (s = amax / 448 along the reduced one, 1 where that is zero), by torch's CPU cast:
     dY8r, sdy_t (per token);  dY8c, sdy_d and X8c, sx_d (per model dimension);  W2_8r, sw2_f (per hidden feature);
     W1_8c, sw1_d (per model dimension).  Codes are uint8 in the tensors' own layouts ([T,D], [F,D], [D,F])."""
     import torch
-    inp = make_inputs(T, D, F, sparsity, seed, with_dy=True)
+    inp = make_inputs(T, D, F, sparsity, seed, with_dy=True, token_corr=token_corr)
 
     def quant(x, axis):
         amax = np.abs(x).max(axis=axis, keepdims=True).astype(np.float32)

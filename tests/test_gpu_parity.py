@@ -1553,6 +1553,111 @@ def test_ffn24_token_permutation_small(F24):
     ctx.close()
 
 
+def _fp8_rowwise_permutation_case(F24, T, D, Fh, sparsity, seed, perm_seed, gsel=None, n_dense=0):
+    """Row-wise fp8 forward + backward with the token permutation, on correlated tokens: Y and dX bit-identical to the run
+    without it; the saved tensors in permuted order (position p holds token perm[p]); feature-wise picks, per-feature scales and
+    codes bit-exact from the GPU's own bf16 tensors; dW2 / dW1 staged and from the raw inputs; the feature-wise drop falls.
+    n_dense > 0: with the split of the weight gradients on top (the partition does not see the order of the tokens)."""
+    inp = synth.make_inputs_fp8_rowwise(T, D, Fh, sparsity, seed, token_corr=(8, 0.9))
+    bw = synth.make_bwd_operands_fp8_rowwise(T, D, Fh, sparsity, seed, token_corr=(8, 0.9))
+    perm = synth.token_permutation(T, seed=perm_seed)
+    d = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2", "sx", "sw1", "sw2")}
+    db = {k: torch.from_numpy(v).cuda() for k, v in bw.items()}
+    b1 = torch.from_numpy(inp["b1"]).cuda()
+    ops = (db["dY8r"], db["sdy_t"], db["dY8c"], db["sdy_d"], db["X8c"], db["sx_d"], db["W2_8r"], db["sw2_f"], db["W1_8c"], db["sw1_d"])
+    ctx = F24.Context(T, D, Fh, F24.FFN24_ROWWISE | F24.FFN24_TRAINING | F24.FFN24_PERMUTE | (F24.FFN24_SPLIT if n_dense else 0), dtype=F24.FFN24_FP8_E4M3)
+    ctx.set_row_scales(d["sx"], d["sw1"], d["sw2"])
+    if n_dense:
+        ctx.set_split(n_dense)
+    Y0 = ctx.ffn24_fwd(d["X"], d["W1"], b1, d["W2"]).clone()
+    dX0, dW1_0, dW2_0 = ctx.ffn24_bwd_rowwise(*ops)
+    dX0 = dX0.clone(); dW2_0 = dW2_0.clone()
+    torch.cuda.synchronize()
+    nz = lambda name: int(torch.count_nonzero(ctx.saved(name) & 0x7F))
+    feat0 = ctx.saved("feat_of_row").clone() if n_dense else None
+    drop0 = 1.0 - nz("Hc_t") / max(1, nz("Hc")) if not n_dense else float("nan")     # (with a split the rows of Hc_t are the sparse features only)
+    ctx.set_token_permutation(perm)
+    with pytest.raises(F24.Ffn24Error):                # a backward needs a forward made with the same setting
+        ctx.ffn24_bwd_rowwise(*ops)
+    Y = ctx.ffn24_fwd(d["X"], d["W1"], b1, d["W2"])
+    dX, dW1, dW2 = ctx.ffn24_bwd_rowwise(*ops)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y0) and torch.equal(dX, dX0) and not torch.equal(dW2, dW2_0)
+    dec = lambda c: O.e4m3_bits_to_f32(c).astype(np.float64)
+    s64 = lambda v: np.asarray(v, dtype=np.float32).astype(np.float64)
+    q448 = lambda amax: np.where(amax > 0, amax / np.float32(448.0), np.float32(1.0)).astype(np.float32)
+    G = Fh // 4
+    gs = np.arange(G) if gsel is None else gsel
+    f4, f2 = _groups_to_cols(gs)
+    f4_t, f2_t = torch.from_numpy(f4).cuda(), torch.from_numpy(f2).cuda()
+    ns = Fh - n_dense
+    if n_dense:
+        feat_of_row = ctx.saved("feat_of_row")
+        assert torch.equal(feat_of_row, feat0)                          # counts are sums over tokens
+        feat_of_row = feat_of_row.cpu().numpy()
+        row_of_feat = np.empty(Fh, np.int64); row_of_feat[feat_of_row] = np.arange(Fh)
+        dense = np.zeros(Fh, bool); dense[feat_of_row[ns:]] = True
+    else:
+        row_of_feat = np.arange(Fh); dense = np.zeros(Fh, bool)
+    # S1, in permuted token order, from the GPU's own bf16 kept values and dZ
+    Hc16_all, meta_all, dZc16_all = ctx.saved("Hc16"), ctx.saved("meta"), ctx.saved("dZc16")
+    Hc16_g = O.bf16_bits_to_f32(words_of(Hc16_all[:, f2_t])); dZc16_g = O.bf16_bits_to_f32(words_of(dZc16_all[:, f2_t])); meta_g = _meta_of_groups(meta_all, gs)
+    H24_g = O.decompress24(Hc16_g, meta_g); dZ24_g = O.decompress24(dZc16_g, meta_g)
+    _, mt_ref, M_T = O.featurewise24(H24_g)
+    isd = dense[f4]
+    Mw = np.where(isd[None, :], True, M_T)
+    Hm = np.where(Mw, H24_g, np.float32(0)); Zm = np.where(Mw, dZ24_g, np.float32(0))
+    sh_ref = q448(Hm.max(axis=0)); sdz_ref = q448(np.abs(Zm).max(axis=0))
+    H8 = np.ascontiguousarray(O.f32_to_e4m3_bits(Hm / sh_ref[None, :]).T); Z8 = np.ascontiguousarray(O.f32_to_e4m3_bits(Zm / sdz_ref[None, :]).T)
+    rows = torch.from_numpy(row_of_feat[f4]).cuda()
+    assert np.array_equal(ctx.saved("sh_f")[rows].cpu().numpy(), sh_ref) and np.array_equal(ctx.saved("sdz_f")[rows].cpu().numpy(), sdz_ref)
+    srows = torch.from_numpy(row_of_feat[f4][~isd]).cuda()
+    assert np.array_equal(ctx.saved("meta_t")[srows].cpu().numpy(), mt_ref[~isd])
+    assert np.array_equal(ctx.saved("Hc_t")[srows].cpu().numpy(), O.compress_with_meta(H8[~isd], mt_ref[~isd]))
+    assert np.array_equal(ctx.saved("dZc_t")[srows].cpu().numpy(), O.compress_with_meta(Z8[~isd], mt_ref[~isd]))
+    # the saved activation is the one of token perm[p] at position p: the unpermuted oracle forward, rows gathered
+    if gsel is None:
+        f_ref = O.ffn24_fwd_fp8_rowwise_codes(inp["X"], inp["sx"], inp["W1"], inp["sw1"], inp["b1"], inp["W2"], inp["sw2"])
+        assert float(np.mean(meta_all.cpu().numpy() == f_ref["meta"][perm])) >= 0.995
+    # S2: weight gradients on those codes; the column-quantised operands enter in permuted token order
+    dW2_st = (dec(H8) @ dec(bw["dY8c"][perm])) * s64(sh_ref)[:, None] * s64(bw["sdy_d"])[None, :]
+    dW1_st = (dec(Z8) @ dec(bw["X8c"][perm])) * s64(sdz_ref)[:, None] * s64(bw["sx_d"])[None, :]
+    e_dw2 = O.max_rel_err(f64(dW2[f4_t]), dW2_st); e_dw1 = O.max_rel_err(f64(dW1[:, f4_t]).T, dW1_st)
+    # S3: the same features from the raw inputs, by the definition with the permutation
+    bw_g = dict(bw); bw_g["W2_8r"] = bw["W2_8r"][f4]; bw_g["sw2_f"] = bw["sw2_f"][f4]; bw_g["W1_8c"] = bw["W1_8c"][:, f4]
+    ref = O.ffn24_fwd_bwd_fp8_rowwise_permuted(inp["X"], inp["sx"], inp["W1"][:, f4], inp["sw1"][f4], inp["b1"][f4], inp["W2"][f4], inp["sw2"], bw_g, perm,
+                                               dense_features=isd if n_dense else None)
+    e_dw2_raw = O.max_rel_err(f64(dW2[f4_t]), ref["dW2"]); e_dw1_raw = O.max_rel_err(f64(dW1[:, f4_t]), ref["dW1"])
+    f_dw2_raw = O.fro_rel_err(f64(dW2[f4_t]), ref["dW2"]); f_dw1_raw = O.fro_rel_err(f64(dW1[:, f4_t]), ref["dW1"])
+    drop1 = 1.0 - nz("Hc_t") / max(1, nz("Hc")) if not n_dense else float("nan")
+    print(f"  fp8 row-wise + permutation (n_dense={n_dense}): dW2 staged {e_dw2:.2e} dW1 staged {e_dw1:.2e}  from raw inputs: dW2 {e_dw2_raw:.2e} (Frobenius {f_dw2_raw:.2e}) "
+          f"dW1 {e_dw1_raw:.2e} (Frobenius {f_dw1_raw:.2e});  feature-wise drop without / with permutation {drop0:.4f} / {drop1:.4f}", flush=True)
+    assert max(e_dw2, e_dw1, e_dw2_raw, e_dw1_raw, f_dw2_raw, f_dw1_raw) <= TOL_FP8
+    if not n_dense:
+        assert drop0 > 2 * drop1
+    ctx.set_token_permutation(None)                    # switching it off again restores the first run exactly
+    ctx.ffn24_fwd(d["X"], d["W1"], b1, d["W2"])
+    _, _, dW2_b = ctx.ffn24_bwd_rowwise(*ops)
+    torch.cuda.synchronize()
+    assert torch.equal(dW2_b, dW2_0)
+    ctx.close()
+
+
+@pytest.mark.parametrize("n_dense", [0, 256])
+def test_fp8_rowwise_token_permutation_small(F24, n_dense):
+    print(f"fp8 row-wise token permutation T=512 D=256 F=1024, correlated tokens, n_dense={n_dense}", flush=True)
+    _fp8_rowwise_permutation_case(F24, 512, 256, 1024, 0.85, seed=83, perm_seed=11, n_dense=n_dense)
+
+
+@pytest.mark.timeout(900)
+def test_fp8_rowwise_token_permutation_full_size(F24):
+    """c5 dims with correlated tokens, the paper's whole recipe at once: row-wise fp8, token permutation, 1536 dense features."""
+    w = synth.WORKLOADS["c5"]
+    print("fp8 row-wise token permutation + split full size c5, correlated tokens", flush=True)
+    rng = np.random.default_rng(53)
+    _fp8_rowwise_permutation_case(F24, w.T, w.D, w.F, "per_feature", w.seed, perm_seed=12, gsel=np.sort(rng.choice(w.F // 4, 96, replace=False)), n_dense=1536)
+
+
 def test_token_permutation_rules(F24):
     ctx = F24.Context(256, 256, 256, F24.FFN24_TRAINING | F24.FFN24_PERMUTE)
     bad = np.arange(256, dtype=np.int32); bad[3] = 7                      # 7 twice, 3 never
