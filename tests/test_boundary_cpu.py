@@ -70,6 +70,7 @@ def test_argument_validation_without_gpu():
     h = ctypes.c_void_p()
     assert L.ffn24_ctx_create(ctypes.byref(h), 100, 512, 2048, 0, 0) == -2
     assert L.ffn24_ctx_create(ctypes.byref(h), 256, 512, 2048, 1, 1 | 8) == -4   # fp8: the split needs the row-wise recipe
+    assert L.ffn24_ctx_create(ctypes.byref(h), 256, 512, 2048, 1, 1 | 32) == -4  # fp8: the token permutation too
     assert L.ffn24_bwd_rowwise(None, None, a16, a16, a16, None) == -1 and L.ffn_bwd_rowwise(None, None, a16, a16, a16, None) == -1
     assert L.ffn24_ctx_create(ctypes.byref(h), 256, 512, 2048, 2, 0) == -4
     assert L.ffn24_set_scales(None, 1.0, 1.0, 1.0, 1.0) == -1
