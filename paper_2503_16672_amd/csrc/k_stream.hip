@@ -335,13 +335,14 @@ int launch_featurewise24_split(const void* Hc, const uint8_t* meta, const void* 
 constexpr int PART_LDS_FEATS = 32768;
 __device__ __forceinline__ int part_slot(int f) { return f + (f >> 5); }
 
+template <bool IN_LDS>
 __global__ void __launch_bounds__(1024) split_partition_kernel(const uint32_t* __restrict__ nnz_g, int F, int n_dense, uint32_t max_count,
                                                                int* __restrict__ row_of_feat, int* __restrict__ feat_of_row) {
   extern __shared__ uint32_t s_nnz[];                // F counts if they fit
   __shared__ int s_part[16];
   __shared__ int s_total;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const bool in_lds = F <= PART_LDS_FEATS;
+  constexpr bool in_lds = IN_LDS;
   if (in_lds) for (int f = tid; f < F; f += 1024) s_nnz[part_slot(f)] = nnz_g[f];
   __syncthreads();
   auto nnz = [&](int f) { return in_lds ? s_nnz[part_slot(f)] : nnz_g[f]; };
@@ -379,11 +380,11 @@ __global__ void __launch_bounds__(1024) split_partition_kernel(const uint32_t* _
     return total;
   };
   // bisection: invariant #{nnz > hi} <= n_dense and (lo == -1 or #{nnz > lo} > n_dense); strided accesses here
-  long long lo = -1, hi = max_count;             // no count exceeds max_count (the number of tokens)
+  int lo = -1, hi = (int)max_count;              // no count exceeds max_count (the number of tokens, at most 2^20)
   while (hi - lo > 1) {
-    long long mid = (lo + hi) >> 1;
+    int mid = (lo + hi) >> 1;
     int c = 0;
-    for (int f = tid; f < F; f += 1024) c += (long long)nnz(f) > mid;
+    for (int f = tid; f < F; f += 1024) c += (int)nnz(f) > mid;
     if (block_sum(c) <= n_dense) hi = mid; else lo = mid;
   }
   const uint32_t cstar = (uint32_t)hi;
@@ -429,9 +430,13 @@ __global__ void __launch_bounds__(1024) split_partition_kernel(const uint32_t* _
 
 int launch_split_partition(const uint32_t* nnz, int F, int n_dense, int max_count, int* row_of_feat, int* feat_of_row, hipStream_t s) {
   static std::atomic<bool> configured[MAX_DEVICES] = {};
-  if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(split_partition_kernel), 4 * (PART_LDS_FEATS + PART_LDS_FEATS / 32), configured)) return rc;
-  size_t lds = F <= PART_LDS_FEATS ? 4 * ((size_t)F + (size_t)F / 32) : 0;
-  hipLaunchKernelGGL(split_partition_kernel, dim3(1), dim3(1024), lds, s, nnz, F, n_dense, (uint32_t)max_count, row_of_feat, feat_of_row);
+  if (F > PART_LDS_FEATS) {
+    hipLaunchKernelGGL(split_partition_kernel<false>, dim3(1), dim3(1024), 0, s, nnz, F, n_dense, (uint32_t)max_count, row_of_feat, feat_of_row);
+    return (int)hipGetLastError();
+  }
+  if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(split_partition_kernel<true>), 4 * (PART_LDS_FEATS + PART_LDS_FEATS / 32), configured)) return rc;
+  hipLaunchKernelGGL(split_partition_kernel<true>, dim3(1), dim3(1024), 4 * ((size_t)F + (size_t)F / 32), s, nnz, F, n_dense, (uint32_t)max_count,
+                     row_of_feat, feat_of_row);
   return (int)hipGetLastError();
 }
 

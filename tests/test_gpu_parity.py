@@ -1088,6 +1088,12 @@ def test_ffn24_split_small(F24, n_dense):
     _check_split(F24, 512, 256, 2048, "per_feature", seed=61, n_dense=n_dense)
 
 
+def test_ffn24_split_more_features_than_the_partition_keeps_in_lds(F24):
+    """Beyond 32768 hidden features the partition kernel reads the counts from global memory instead of LDS."""
+    print("split weight gradients T=256 D=256 F=33024 n_dense=512", flush=True)
+    _check_split(F24, 256, 256, 33024, "per_feature", seed=62, n_dense=512)
+
+
 def test_ffn24_split_rules(F24):
     ctx = F24.Context(256, 256, 1024, F24.FFN24_TRAINING | F24.FFN24_SPLIT)
     for bad in (100, 512, -256):                     # not a multiple of 256; more than F/4; negative
