@@ -387,7 +387,7 @@ def main() -> int:
     sec_dense, med_dense, min_dense = (_time_steps(torch, step_dense, args.warmup, args.steps) if not no_dense else (float("nan"),) * 3)
     # separate pass: event pairs around every kernel (on the launch stream) and a clock sample in every GEMM kernel
     ctx.set_profiling(True)
-    k24 = list(range(0, 7 if bwd else 2)) + ([13, 14] if bwd else []) + ([15, 16] if args.split and bwd else []) + ([17] if rowwise or rowwise_bwd else []) + ([18, 19, 20] if rowwise_bwd else [])
+    k24 = list(range(0, 7 if bwd else 2)) + ([13, 14] if bwd else []) + ([15, 16] if args.split and bwd else []) + ([17] if rowwise or rowwise_bwd else []) + ([18, 19, 20] if rowwise_bwd else []) + ([21] if fp8 else [])
     kd = [] if no_dense else list(range(7, 13 if bwd else 9))      # (the dense row-wise quantisation kernel shares id 17 with the 2:4 one)
     acc = {k: [] for k in k24 + kd}
     mhz = {k: [] for k in k24 + kd}
@@ -487,8 +487,9 @@ def main() -> int:
             if name == "split_partition":
                 kernels[name] = {"ms": round(ms, 4)}
                 continue
-            nbytes = {"panelise_bwd_weights": 4.0 * D * F, "featurewise24": (2.0 * (2.0 if rowwise_bwd else es) + 0.25) * T * F, "transpose_weights": (6.0 if bwd else 4.0) * es * D * F,
-                      "transpose_acts": 4.0 * es * T * D, "transpose_dw1": 4.0 * D * F}[name]
+            nbytes = {"panelise_bwd_weights": 2.0 * D * F + 2.0 * T * D, "panelise_x": 2.0 * T * D, "featurewise24": (2.0 * (2.0 if rowwise_bwd else es) + 0.25) * T * F, "transpose_weights": (6.0 if bwd and not rowwise_bwd else 4.0) * es * D * F,
+                      # (per-tensor fp8: the pass over dY8 also leaves its panel-form copy)
+                      "transpose_acts": (5.0 if fp8 and not rowwise_bwd else 4.0) * es * T * D, "transpose_dw1": 4.0 * D * F}[name]
             gbs = nbytes / (ms * 1e-3) / 1e9
             kernels[name] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / 8000.0, 4)}
     dom = max((n for n in kernel_ms if n in KERNEL_FLOPS and not n.startswith("dense_")), key=lambda n: kernel_ms[n])

@@ -328,7 +328,8 @@ FFN24_API int ffn24_copy_saved(ffn24_ctx* ctx, int which, void* dst, int64_t dst
  * activation transposes of a backward (dY, X), 15 the feature partition of the split, 16 the transpose that brings
  * dW1 into [D][F] after a split (with a split, 5 and 6 are the combined sparse + dense launches of dW2 and dW1),
  * 17 the row-wise fp8 quantisation kernel of a forward, 18 the one of dZ in ffn24_bwd_rowwise, 19 its two quantisations of the
- * transposed operands, 20 its re-arrangement of the caller's W2_8r and W1_8c.  Returns FFN24_ERR_STATE if that kernel has not run
+ * transposed operands, 20 its re-arrangement of the caller's W2_8r and dY8r (ffn_bwd_rowwise: also W1_8c) into the forms the GEMMs stream, 21 the same for
+ * X8 in the forward of an fp8 context.  Returns FFN24_ERR_STATE if that kernel has not run
  * with profiling on. */
 FFN24_API int ffn24_set_profiling(ffn24_ctx* ctx, int on);
 FFN24_API int ffn24_kernel_ms(ffn24_ctx* ctx, int kernel, float* ms);

@@ -7,8 +7,8 @@
 using namespace ffn24;
 
 namespace {
-constexpr int NUM_KERNELS = 21;   // K_QUANT is shared by the 2:4 and the dense row-wise quantisation kernels
-enum { K_UP = 0, K_DOWN, K_DH, K_DX, K_FW, K_DW2, K_DW1, KD_UP, KD_DOWN, KD_DH, KD_DX, KD_DW2, KD_DW1, K_TR_W, K_TR_ACT, K_PART, K_TR_DW1, K_QUANT, K_QUANT_DZ, K_QUANT_T, K_PANEL_W };
+constexpr int NUM_KERNELS = 22;   // K_QUANT is shared by the 2:4 and the dense row-wise quantisation kernels
+enum { K_UP = 0, K_DOWN, K_DH, K_DX, K_FW, K_DW2, K_DW1, KD_UP, KD_DOWN, KD_DH, KD_DX, KD_DW2, KD_DW1, K_TR_W, K_TR_ACT, K_PART, K_TR_DW1, K_QUANT, K_QUANT_DZ, K_QUANT_T, K_PANEL_W, K_PANEL_X };
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
@@ -62,6 +62,7 @@ struct ffn24_ctx {
   void* W1p;   // W1 itself in B panel form (B operand of the dX GEMMs)
   // split weight gradients (FFN24_SPLIT)
   uint32_t* nnz; int* row_of_feat; int* feat_of_row; void* Hdn_t; void* dZdn_t; void* dW1t;
+  void* Xp8; void* dYp8;         // fp8: X8 and dY8 in B panel form (rows in FFN order), what the up-projection and dH GEMMs read
   float* sx_p; float* sdy_p;     // row-wise fp8 with a token permutation: the caller's per-token scales of X and dY in FFN order
   void* Hdn8_t; void* dZdn8_t;   // row-wise fp8 split: the dense features' rows as e4m3 (Hdn_t, dZdn_t hold them in bf16 first)
   int n_dense;
@@ -102,7 +103,7 @@ int free_all(ffn24_ctx* c) {
                   c->W1t, c->W2t, c->Xt, c->dYt, c->Hd_t, c->dZd_t, c->W2p, c->W1p,
                   c->nnz, c->row_of_feat, c->feat_of_row, c->Hdn_t, c->dZdn_t, c->dW1t, c->Hc16, c->meta16, c->rowmax, c->rsh, c->perm, c->Hd16,
                   c->dZc16, c->Hct16, c->dZct16, c->meta_t16, c->rowmax_dz, c->hmax, c->zmax, c->sdz_t, c->sh_f, c->sdz_f, c->W2rp, c->W1cp,
-                  c->dZd16, c->Hdt16, c->dZdt16, c->Hdn8_t, c->dZdn8_t, c->sx_p, c->sdy_p};
+                  c->dZd16, c->Hdt16, c->dZdt16, c->Hdn8_t, c->dZdn8_t, c->sx_p, c->sdy_p, c->Xp8, c->dYp8};
   for (void* b : bufs) if (b && hipFree(b) != hipSuccess) bad = 1;
   if (c->clk && hipFree(c->clk) != hipSuccess) bad = 1;
   if (c->tele && hipFree(c->tele) != hipSuccess) bad = 1;
@@ -132,7 +133,8 @@ int tele_snapshot(ffn24_ctx* c, long long path, hipStream_t s) {
 
 // The weight pass: W1 -> W1^T in dense panel form (A operand of the up-projection), W2 -> W2^T in B panel form (B
 // operand of the down-projection) and, when the context trains, W2 itself in panel form (A operand of the dH GEMM)
-// and W1 itself in B panel form (B operand of the dX GEMM).
+// and W1 itself in B panel form (B operand of the dX GEMM) -- not in a row-wise fp8 context, whose backward takes the
+// caller's differently quantised weight codes instead (W1p, W2p are NULL there).
 int weight_pass(ffn24_ctx* c, const void* W1, const void* W2, hipStream_t s) {
   int D = (int)c->D, F = (int)c->F;
   Timed t(c, K_TR_W, s);
@@ -207,7 +209,11 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
   if (ok && (flags & FFN24_TRAINING))
     ok = hipMalloc(&c->dZc, tf * es / 2) == hipSuccess && hipMalloc(&c->Hc_t, tf * es / 2) == hipSuccess &&
          hipMalloc(reinterpret_cast<void**>(&c->meta_t), tf / 8) == hipSuccess && hipMalloc(&c->dZc_t, tf * es / 2) == hipSuccess &&
-         hipMalloc(&c->Xt, es * td) == hipSuccess && hipMalloc(&c->dYt, es * td) == hipSuccess && hipMalloc(&c->W2p, es * df) == hipSuccess && hipMalloc(&c->W1p, es * df) == hipSuccess;
+         hipMalloc(&c->Xt, es * td) == hipSuccess && hipMalloc(&c->dYt, es * td) == hipSuccess;
+  if (ok && (flags & FFN24_TRAINING) && !(flags & FFN24_ROWWISE))
+    ok = hipMalloc(&c->W2p, es * df) == hipSuccess && hipMalloc(&c->W1p, es * df) == hipSuccess;
+  if (ok && f8) ok = hipMalloc(&c->Xp8, td) == hipSuccess;
+  if (ok && f8 && (flags & FFN24_TRAINING)) ok = hipMalloc(&c->dYp8, td) == hipSuccess;
   // an fp8 training context also keeps the kept activations before quantisation (bf16) for the backward's derivative
   if (ok && f8 && (flags & FFN24_TRAINING))
     ok = hipMalloc(&c->Hc16, tf) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->meta16), tf / 8) == hipSuccess;
@@ -563,26 +569,28 @@ int ffn24_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, cons
     if (launch_zero32(c->rowmax, (size_t)T, s)) return FFN24_ERR_HIP;
     uint32_t* nnz = (c->flags & FFN24_SPLIT) && c->n_dense > 0 ? c->nnz : nullptr;
     if (nnz && launch_zero32(nnz, (size_t)F, s)) return FFN24_ERR_HIP;
-    // token permutation: position p inside the FFN holds token perm[p] -- its row of X8 is gathered by the operand DMA, its
-    // scale by a small kernel; everything in between lives in FFN order, and Y's rows go back to their tokens
+    // token permutation: position p inside the FFN holds token perm[p] -- its row of X8 is gathered by the pass that brings X8
+    // into panel form, its scale by a small kernel; everything in between lives in FFN order, and Y's rows go back to their tokens
     const int* perm = c->perm_on ? c->perm : nullptr;
     const float* sx = c->rsx;
     if (perm) { if (launch_gather_f32(c->rsx, perm, T, c->sx_p, s)) return FFN24_ERR_HIP; sx = c->sx_p; }
+    { Timed t(c, K_PANEL_X, s); if (t.done(launch_panelise8_rows(X, T, D, c->Xp8, 1, perm, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_UP, s);
-      if (t.done(launch_up_prune24_f8_rowwise(c->W1t, X, b1, T, D, F, sx, c->rsw1, c->Hc16, c->meta16, c->Hdbg, c->rowmax, nnz, perm, s))) return FFN24_ERR_HIP; }
+      if (t.done(launch_up_prune24_f8_rowwise(c->W1t, c->Xp8, b1, T, D, F, sx, c->rsw1, c->Hc16, c->meta16, c->Hdbg, c->rowmax, nnz, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_QUANT, s);
       if (t.done(launch_quantise_rows(c->Hc16, c->meta16, c->rowmax, T, F, c->Hc, c->meta, c->rsh, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_DOWN, s);
-      int rc1 = perm ? launch_sp_rowmajor_f8_rowwise_mapped(c->Hc, c->meta, c->W2t, T, D, F, c->rsh, c->rsw2, Y, perm, s)
-                     : launch_sp_rowmajor_f8_rowwise(c->Hc, c->meta, c->W2t, T, D, F, c->rsh, c->rsw2, Y, s);
+      int rc1 = perm ? launch_sp_rowmajor_f8_rowwise_mapped(c->Hc, c->meta, c->W2t, 1, T, D, F, c->rsh, c->rsw2, Y, perm, s)
+                     : launch_sp_rowmajor_f8_rowwise(c->Hc, c->meta, c->W2t, 1, T, D, F, c->rsh, c->rsw2, Y, s);
       if (t.done(rc1)) return FFN24_ERR_HIP; }
     if (c->flags & FFN24_TRAINING) { c->X = X; c->have_fwd24 = 1; }
     return FFN24_OK;
   }
   if (c->f8) {
     const bool train = (c->flags & FFN24_TRAINING) != 0;
+    { Timed t(c, K_PANEL_X, s); if (t.done(launch_panelise8(X, T, D, c->Xp8, 1, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_UP, s);
-      if (t.done(launch_up_prune24_f8(c->W1t, X, b1, T, D, F, c->sx * c->sw1, c->sh, c->Hc, c->meta, c->Hdbg, train ? c->Hc16 : nullptr,
+      if (t.done(launch_up_prune24_f8(c->W1t, c->Xp8, b1, T, D, F, c->sx * c->sw1, c->sh, c->Hc, c->meta, c->Hdbg, train ? c->Hc16 : nullptr,
                                       train ? c->meta16 : nullptr, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_DOWN, s);
       if (t.done(launch_sp_rowmajor_f8(c->Hc, c->meta, 1, c->W2t, 1, T, D, F, c->sh * c->sw2, Y, s))) return FFN24_ERR_HIP; }
@@ -642,22 +650,24 @@ int ffn24_bwd_rowwise(ffn24_ctx* c, const ffn24_rowwise_bwd_operands* op, void* 
   if (rc) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
-  // the caller's backward-side weight codes into the forms the GEMMs stream: W2 (quantised per hidden feature) as the A operand
-  // of the dH GEMM, W1 (quantised per model dimension) as the B operand of the dX GEMM; the column-quantised dY and X transposed
+  // the caller's W2 codes (quantised per hidden feature) into the panel form the dH GEMM streams its A operand in; W1 (quantised
+  // per model dimension) is the B operand of the sparse dX GEMM, whose stages take a whole 128-byte line of every row: it is read
+  // where it lies (measured: no slower than from a panel-form copy, and the copy costs 0.1 ms)
+  // dY8r likewise (the B operand of the dense dH GEMM, 64 bytes of every row a stage), with the rows of a token permutation gathered
+  const int* perm = c->perm_on ? c->perm : nullptr;
   { Timed t(c, K_PANEL_W, s);
     int rc1 = launch_panelise8(op->W2_8r, F, D, c->W2rp, 0, s);
-    if (t.done(rc1 ? rc1 : launch_panelise8(op->W1_8c, D, F, c->W1cp, 1, s))) return FFN24_ERR_HIP; }
+    if (t.done(rc1 ? rc1 : launch_panelise8_rows(op->dY8r, T, D, c->dYp8, 1, perm, s))) return FFN24_ERR_HIP; }
   if (launch_zero32(c->rowmax_dz, (size_t)T, s) || launch_zero32(c->hmax, (size_t)F, s) || launch_zero32(c->zmax, (size_t)F, s)) return FFN24_ERR_HIP;
-  const int* perm = c->perm_on ? c->perm : nullptr;   // as in the forward: dY8r's rows and scales gathered, dX's rows scattered back
-  const float* sdy_t = op->sdy_t;
+  const float* sdy_t = op->sdy_t;                     // as in the forward: the scales of the gathered rows, and dX's rows scattered back
   if (perm) { if (launch_gather_f32(op->sdy_t, perm, T, c->sdy_p, s)) return FFN24_ERR_HIP; sdy_t = c->sdy_p; }
   { Timed t(c, K_DH, s);
-    if (t.done(launch_dh_gather_f8_rowwise(c->W2rp, op->dY8r, c->Hc16, c->meta16, T, D, F, op->sw2_f, sdy_t, c->dZc16, c->rowmax_dz, perm, s))) return FFN24_ERR_HIP; }
+    if (t.done(launch_dh_gather_f8_rowwise(c->W2rp, c->dYp8, c->Hc16, c->meta16, T, D, F, op->sw2_f, sdy_t, c->dZc16, c->rowmax_dz, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_QUANT_DZ, s);
     if (t.done(launch_quantise_rows(c->dZc16, c->meta16, c->rowmax_dz, T, F, c->dZc, c->meta, c->sdz_t, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_DX, s);
-    int rc1 = perm ? launch_sp_rowmajor_f8_rowwise_mapped(c->dZc, c->meta, c->W1cp, T, D, F, c->sdz_t, op->sw1_d, dX, perm, s)
-                   : launch_sp_rowmajor_f8_rowwise(c->dZc, c->meta, c->W1cp, T, D, F, c->sdz_t, op->sw1_d, dX, s);
+    int rc1 = perm ? launch_sp_rowmajor_f8_rowwise_mapped(c->dZc, c->meta, op->W1_8c, 0, T, D, F, c->sdz_t, op->sw1_d, dX, perm, s)
+                   : launch_sp_rowmajor_f8_rowwise(c->dZc, c->meta, op->W1_8c, 0, T, D, F, c->sdz_t, op->sw1_d, dX, s);
     if (t.done(rc1)) return FFN24_ERR_HIP; }
   if ((c->flags & FFN24_SPLIT) && c->n_dense > 0) {
     // Sec. 2, "Optimization 1" on the row-wise recipe: the n_dense least sparse features keep the token-wise mask only; every
@@ -692,7 +702,7 @@ int ffn24_bwd_rowwise(ffn24_ctx* c, const ffn24_rowwise_bwd_operands* op, void* 
     int rc1 = launch_transpose8_rows(op->dY8c, T, D, c->dYt, 2, perm, s);
     if (t.done(rc1 ? rc1 : launch_transpose8_rows(op->X8c, T, D, c->Xt, 2, perm, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_DW2, s);
-    if (t.done(launch_sp_rowmajor_f8_rowwise(c->Hc_t, c->meta_t, c->dYt, F, D, T, c->sh_f, op->sdy_d, dW2, s))) return FFN24_ERR_HIP; }
+    if (t.done(launch_sp_rowmajor_f8_rowwise(c->Hc_t, c->meta_t, c->dYt, 1, F, D, T, c->sh_f, op->sdy_d, dW2, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_DW1, s);
     if (t.done(launch_sp_colmajor_f8_rowwise(c->dZc_t, c->meta_t, c->Xt, F, D, T, c->sdz_f, op->sx_d, dW1, s))) return FFN24_ERR_HIP; }
   return FFN24_OK;
@@ -710,15 +720,15 @@ int ffn24_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   if (c->f8) {
     // fp8 backward (per-tensor scales): every GEMM operand is e4m3, the gradients come out in bf16
+    { Timed t(c, K_TR_ACT, s);   // dY^T for the dW2 GEMM first: the same pass leaves dY8 in panel form for the dH GEMM
+      int rc1 = launch_transpose8(dY, T, D, c->dYt, 2, c->dYp8, 1, s);
+      if (t.done(rc1 ? rc1 : launch_transpose8(c->X, T, D, c->Xt, 2, nullptr, 0, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_DH, s);
-      if (t.done(launch_dh_gather_f8(c->W2p, dY, c->Hc16, c->meta16, T, D, F, c->sdy * c->sw2, c->sdz, c->dZc, s))) return FFN24_ERR_HIP; }
+      if (t.done(launch_dh_gather_f8(c->W2p, c->dYp8, c->Hc16, c->meta16, T, D, F, c->sdy * c->sw2, c->sdz, c->dZc, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_DX, s);
       if (t.done(launch_sp_rowmajor_f8(c->dZc, c->meta, 1, c->W1p, 1, T, D, F, c->sdz * c->sw1, dX, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_FW, s);
       if (t.done(launch_featurewise24_f8(c->Hc, c->meta, c->dZc, T, F, c->Hc_t, c->meta_t, c->dZc_t, s))) return FFN24_ERR_HIP; }
-    { Timed t(c, K_TR_ACT, s);
-      int rc1 = launch_transpose8(dY, T, D, c->dYt, 2, nullptr, 0, s);
-      if (t.done(rc1 ? rc1 : launch_transpose8(c->X, T, D, c->Xt, 2, nullptr, 0, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_DW2, s);
       if (t.done(launch_sp_rowmajor_f8(c->Hc_t, c->meta_t, 1, c->dYt, 1, F, D, T, c->sh * c->sdy, dW2, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_DW1, s);
@@ -776,19 +786,21 @@ int ffn_fwd(ffn24_ctx* c, const void* X, const void* W1, const float* b1, const 
   if (c->f8 && (c->flags & FFN24_ROWWISE)) {
     // dense baseline with row-wise scales: up-projection (bf16 activations + row maxima), row-wise quantisation, dense GEMM
     if (launch_zero32(c->rowmax, (size_t)T, s)) return FFN24_ERR_HIP;
+    { Timed t(c, K_PANEL_X, s); if (t.done(launch_panelise8(X, T, D, c->Xp8, 1, s))) return FFN24_ERR_HIP; }
     { Timed t(c, KD_UP, s);
-      if (t.done(launch_up_relu2_f8_rowwise(c->W1t, X, b1, T, D, F, c->rsx, c->rsw1, c->Hd16, c->rowmax, c->Hdt16, s))) return FFN24_ERR_HIP; }
+      if (t.done(launch_up_relu2_f8_rowwise(c->W1t, c->Xp8, b1, T, D, F, c->rsx, c->rsw1, c->Hd16, c->rowmax, c->Hdt16, s))) return FFN24_ERR_HIP; }
     { Timed t(c, K_QUANT, s);
       if (t.done(launch_quantise_rows_dense(c->Hd16, c->rowmax, T, F, c->Hd, c->rsh, s))) return FFN24_ERR_HIP; }
     { Timed t(c, KD_DOWN, s);
-      if (t.done(launch_dense_rowmajor_f8_rowwise(c->Hd, c->W2t, T, D, F, c->rsh, c->rsw2, Y, s))) return FFN24_ERR_HIP; }
+      if (t.done(launch_dense_rowmajor_f8_rowwise(c->Hd, c->W2t, 1, T, D, F, c->rsh, c->rsw2, Y, s))) return FFN24_ERR_HIP; }
     if (c->flags & FFN24_TRAINING) { c->X = X; c->have_fwd_dense = 1; }
     return FFN24_OK;
   }
   if (c->f8) {
     const bool train = (c->flags & FFN24_TRAINING) != 0;
+    { Timed t(c, K_PANEL_X, s); if (t.done(launch_panelise8(X, T, D, c->Xp8, 1, s))) return FFN24_ERR_HIP; }
     { Timed t(c, KD_UP, s);
-      if (t.done(launch_up_relu2_f8(c->W1t, X, b1, T, D, F, c->sx * c->sw1, c->sh, c->Hd, train ? c->Hd16 : nullptr, train ? c->Hd_t : nullptr, s)))
+      if (t.done(launch_up_relu2_f8(c->W1t, c->Xp8, b1, T, D, F, c->sx * c->sw1, c->sh, c->Hd, train ? c->Hd16 : nullptr, train ? c->Hd_t : nullptr, s)))
         return FFN24_ERR_HIP; }
     { Timed t(c, KD_DOWN, s);
       if (t.done(launch_dense_rowmajor_f8(c->Hd, 1, c->W2t, 1, T, D, F, c->sh * c->sw2, Y, s))) return FFN24_ERR_HIP; }
@@ -814,14 +826,15 @@ int ffn_bwd_rowwise(ffn24_ctx* c, const ffn24_rowwise_bwd_operands* op, void* dX
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   { Timed t(c, K_PANEL_W, s);
     int rc1 = launch_panelise8(op->W2_8r, F, D, c->W2rp, 0, s);
-    if (t.done(rc1 ? rc1 : launch_panelise8(op->W1_8c, D, F, c->W1cp, 1, s))) return FFN24_ERR_HIP; }
+    if (!rc1) rc1 = launch_panelise8(op->W1_8c, D, F, c->W1cp, 1, s);      // (the dense dX GEMM does lose with its B operand row-major: 1.28 -> 1.43 ms)
+    if (t.done(rc1 ? rc1 : launch_panelise8(op->dY8r, T, D, c->dYp8, 1, s))) return FFN24_ERR_HIP; }
   if (launch_zero32(c->rowmax_dz, (size_t)T, s) || launch_zero32(c->hmax, (size_t)F, s) || launch_zero32(c->zmax, (size_t)F, s)) return FFN24_ERR_HIP;
   { Timed t(c, KD_DH, s);
-    if (t.done(launch_dh_drelu_f8_rowwise(c->W2rp, op->dY8r, c->Hd16, T, D, F, op->sw2_f, op->sdy_t, c->dZd16, c->dZdt16, c->rowmax_dz, s))) return FFN24_ERR_HIP; }
+    if (t.done(launch_dh_drelu_f8_rowwise(c->W2rp, c->dYp8, c->Hd16, T, D, F, op->sw2_f, op->sdy_t, c->dZd16, c->dZdt16, c->rowmax_dz, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_QUANT_DZ, s);
     if (t.done(launch_quantise_rows_dense(c->dZd16, c->rowmax_dz, T, F, c->dZd, c->sdz_t, s))) return FFN24_ERR_HIP; }
   { Timed t(c, KD_DX, s);
-    if (t.done(launch_dense_rowmajor_f8_rowwise(c->dZd, c->W1cp, T, D, F, c->sdz_t, op->sw1_d, dX, s))) return FFN24_ERR_HIP; }
+    if (t.done(launch_dense_rowmajor_f8_rowwise(c->dZd, getenv("FFN24_EXP") ? op->W1_8c : c->W1cp, getenv("FFN24_EXP") ? 0 : 1, T, D, F, c->sdz_t, op->sw1_d, dX, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_QUANT_T, s);      // per-feature maxima of the two transposed bf16 operands, then their quantisation
     int rc1 = launch_rowmax_dense(c->Hdt16, F, T, c->hmax, s);
     if (!rc1) rc1 = launch_rowmax_dense(c->dZdt16, F, T, c->zmax, s);
@@ -831,7 +844,7 @@ int ffn_bwd_rowwise(ffn24_ctx* c, const ffn24_rowwise_bwd_operands* op, void* dX
     int rc1 = launch_transpose8(op->dY8c, T, D, c->dYt, 2, nullptr, 0, s);
     if (t.done(rc1 ? rc1 : launch_transpose8(op->X8c, T, D, c->Xt, 2, nullptr, 0, s))) return FFN24_ERR_HIP; }
   { Timed t(c, KD_DW2, s);
-    if (t.done(launch_dense_rowmajor_f8_rowwise(c->Hd_t, c->dYt, F, D, T, c->sh_f, op->sdy_d, dW2, s))) return FFN24_ERR_HIP; }
+    if (t.done(launch_dense_rowmajor_f8_rowwise(c->Hd_t, c->dYt, 1, F, D, T, c->sh_f, op->sdy_d, dW2, s))) return FFN24_ERR_HIP; }
   { Timed t(c, KD_DW1, s);
     if (t.done(launch_dense_colmajor_f8_rowwise(c->dZd_t, c->Xt, F, D, T, c->sdz_f, op->sx_d, dW1, s))) return FFN24_ERR_HIP; }
   return FFN24_OK;
@@ -848,13 +861,13 @@ int ffn_bwd(ffn24_ctx* c, const void* dY, void* dX, void* dW1, void* dW2, void* 
   hipStream_t s = static_cast<hipStream_t>(stream);
   int T = (int)c->T, D = (int)c->D, F = (int)c->F;
   if (c->f8) {
+    { Timed t(c, K_TR_ACT, s);
+      int rc1 = launch_transpose8(dY, T, D, c->dYt, 2, c->dYp8, 1, s);
+      if (t.done(rc1 ? rc1 : launch_transpose8(c->X, T, D, c->Xt, 2, nullptr, 0, s))) return FFN24_ERR_HIP; }
     { Timed t(c, KD_DH, s);
-      if (t.done(launch_dh_drelu_f8(c->W2p, dY, c->Hd16, T, D, F, c->sdy * c->sw2, c->sdz, c->dZd, c->dZd_t, s))) return FFN24_ERR_HIP; }
+      if (t.done(launch_dh_drelu_f8(c->W2p, c->dYp8, c->Hd16, T, D, F, c->sdy * c->sw2, c->sdz, c->dZd, c->dZd_t, s))) return FFN24_ERR_HIP; }
     { Timed t(c, KD_DX, s);
       if (t.done(launch_dense_rowmajor_f8(c->dZd, 1, c->W1p, 1, T, D, F, c->sdz * c->sw1, dX, s))) return FFN24_ERR_HIP; }
-    { Timed t(c, K_TR_ACT, s);
-      int rc1 = launch_transpose8(dY, T, D, c->dYt, 2, nullptr, 0, s);
-      if (t.done(rc1 ? rc1 : launch_transpose8(c->X, T, D, c->Xt, 2, nullptr, 0, s))) return FFN24_ERR_HIP; }
     { Timed t(c, KD_DW2, s);
       if (t.done(launch_dense_rowmajor_f8(c->Hd_t, 1, c->dYt, 1, F, D, T, c->sh * c->sdy, dW2, s))) return FFN24_ERR_HIP; }
     { Timed t(c, KD_DW1, s);

@@ -594,20 +594,27 @@ int launch_gather_f32(const float* src, const int* map, int n, float* dst, hipSt
 
 // A byte matrix [R][C] (row-major, C a multiple of 64) copied into the dense fp8 panel form (64-byte pieces of 64 k, K = C) as
 // A operands take it, or, b_form, into the B panel form (rows of every block of 256 in LDS order).  16 bytes per work item.
-__global__ void __launch_bounds__(256) panelise8_kernel(const u32x4* __restrict__ in, int R, int C, uint8_t* __restrict__ out, int b_form) {
+// in_rowmap (optional): row r is taken from memory row in_rowmap[r] (token permutation).
+__global__ void __launch_bounds__(256) panelise8_kernel(const u32x4* __restrict__ in, int R, int C, uint8_t* __restrict__ out, int b_form,
+                                                        const int* __restrict__ in_rowmap) {
   const int per_row = C >> 4;
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (size_t)R * per_row) return;
-  int r = (int)(i / per_row), c = (int)(i % per_row) << 4;
+  int r = (int)(i / per_row), cq = (int)(i % per_row), c = cq << 4;
   int prow = b_form ? b_panel_pos(r) : r;
-  st_stream(reinterpret_cast<u32x4*>(out + a24_piece(prow, c >> 6, C >> 6) * 64 + (c & 63)), ld_stream(in + i));
+  size_t src = in_rowmap ? (size_t)in_rowmap[r] * per_row + cq : i;
+  st_stream(reinterpret_cast<u32x4*>(out + a24_piece(prow, c >> 6, C >> 6) * 64 + (c & 63)), ld_stream(in + src));
+}
+
+int launch_panelise8_rows(const void* in, int R, int C, void* out, int b_form, const int* in_rowmap, hipStream_t s) {
+  size_t n = (size_t)R * (C >> 4);
+  hipLaunchKernelGGL(panelise8_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, static_cast<const u32x4*>(in), R, C,
+                     static_cast<uint8_t*>(out), b_form, in_rowmap);
+  return (int)hipGetLastError();
 }
 
 int launch_panelise8(const void* in, int R, int C, void* out, int b_form, hipStream_t s) {
-  size_t n = (size_t)R * (C >> 4);
-  hipLaunchKernelGGL(panelise8_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, static_cast<const u32x4*>(in), R, C,
-                     static_cast<uint8_t*>(out), b_form);
-  return (int)hipGetLastError();
+  return launch_panelise8_rows(in, R, C, out, b_form, nullptr, s);
 }
 
 // Feature-wise 2:4 on top of the token-wise mask for the fp8 operands (Sec. 2, last paragraph; the FP8 side of the fused

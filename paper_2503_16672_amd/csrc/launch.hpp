@@ -104,7 +104,7 @@ int launch_dense_rowmajor_f8(const void* A8, int a_panel, const void* B8, int b_
 // and raises rowmax [T] (bf16 words; zeroed by the caller); quantise_rows turns them into the fp8 panel form with
 // sh[t] = rowmax[t] / 448 (1 for an all-zero row), which it also writes out; nnz (may be NULL) as in launch_up_prune24
 int launch_up_prune24_f8_rowwise(const void* W1t8, const void* X8, const float* b1, int T, int D, int F, const float* sx, const float* sw1,
-                                 void* Hc16, uint8_t* meta16, void* Hdbg, uint32_t* rowmax, uint32_t* nnz, const int* token_map, hipStream_t s);
+                                 void* Hc16, uint8_t* meta16, void* Hdbg, uint32_t* rowmax, uint32_t* nnz, hipStream_t s);
 // split weight gradient of the row-wise fp8 backward (operands e4m3 in panel form): as launch_split_wgrad, with the result row m
 // scaled by rs[m] (scales in row order of the permuted feature space, sparse rows first) and column n by cs[n]
 int launch_split_wgrad_f8_rowwise(const void* vals8, const uint8_t* meta, int ns, const void* Ad8, int nd, const void* B8, int N, int K,
@@ -122,18 +122,18 @@ int launch_dh_drelu_f8_rowwise(const void* W2rp8, const void* dY8r, const void* 
 int launch_rowmax_dense(const void* X16, int R, int C, uint32_t* rmax, hipStream_t s);
 int launch_dense_colmajor_f8_rowwise(const void* A8, const void* B8, int M, int N, int K, const float* rs, const float* cs, void* Ct, hipStream_t s);
 int launch_quantise_rows_dense(const void* H16, const uint32_t* rowmax, int T, int F, void* H8, float* sh, hipStream_t s);
-int launch_dense_rowmajor_f8_rowwise(const void* A8, const void* B8, int M, int N, int K, const float* rs, const float* cs, void* C, hipStream_t s);
+int launch_dense_rowmajor_f8_rowwise(const void* A8, const void* B8, int b_panel, int M, int N, int K, const float* rs, const float* cs, void* C, hipStream_t s);
 int launch_quantise_rows(const void* Hc16, const uint8_t* meta16, const uint32_t* rowmax, int T, int F, void* Hc8, uint8_t* meta8, float* sh, hipStream_t s);
-int launch_sp_rowmajor_f8_rowwise(const void* vals8, const uint8_t* meta, const void* B8, int M, int N, int K, const float* rs, const float* cs,
+int launch_sp_rowmajor_f8_rowwise(const void* vals8, const uint8_t* meta, const void* B8, int b_panel, int M, int N, int K, const float* rs, const float* cs,
                                   void* C, hipStream_t s);
 // the same with result row m stored as row rowmap[m] (token permutation: the rows go back to their tokens; rs stays in row order)
-int launch_sp_rowmajor_f8_rowwise_mapped(const void* vals8, const uint8_t* meta, const void* B8, int M, int N, int K, const float* rs, const float* cs,
+int launch_sp_rowmajor_f8_rowwise_mapped(const void* vals8, const uint8_t* meta, const void* B8, int b_panel, int M, int N, int K, const float* rs, const float* cs,
                                          void* C, const int* rowmap, hipStream_t s);
 // row-wise-scaled fp8 backward: dH GEMM (A = W2 quantised per hidden feature, dense fp8 panel form; B = dY quantised per token)
 // with the derivative and the gather fused: bf16 compressed dZ (bf16 panel form) and rowmax[t] = largest magnitude word of a row;
 // the sparse GEMM with the transposing store scaled per row and per column
 int launch_dh_gather_f8_rowwise(const void* W2rp8, const void* dY8r, const void* Hc16, const uint8_t* meta16, int T, int D, int F,
-                                const float* sw2_f, const float* sdy_t, void* dZc16, uint32_t* rowmax, const int* token_map, hipStream_t s);
+                                const float* sw2_f, const float* sdy_t, void* dZc16, uint32_t* rowmax, hipStream_t s);
 int launch_sp_colmajor_f8_rowwise(const void* vals8, const uint8_t* meta, const void* B8, int M, int N, int K, const float* rs, const float* cs,
                                   void* Ct, hipStream_t s);
 // feature-wise kernel on bf16 panel-form operands that also raises hmax[f], zmax[f] (zeroed by the caller) to the largest
@@ -142,6 +142,8 @@ int launch_featurewise24_rowmax(const void* Hc, const uint8_t* meta, const void*
                                 uint32_t* hmax, uint32_t* zmax, hipStream_t s);
 // byte matrix [R][C] (C % 64 == 0, R % 256 == 0) -> dense fp8 panel form, or the B panel form if b_form
 int launch_panelise8(const void* in, int R, int C, void* out, int b_form, hipStream_t s);
+// the same with row r taken from memory row in_rowmap[r] (may be NULL)
+int launch_panelise8_rows(const void* in, int R, int C, void* out, int b_form, const int* in_rowmap, hipStream_t s);
 // bf16 X [R][C] (C % 8 == 0) -> e4m3 codes [R][C] and one scale per row (axis 1, scales [R]) or per column (axis 0, scales [C]; the
 // buffer also holds the column maxima while the call runs)
 int launch_quantise_bf16(const void* X, int64_t R, int64_t C, int axis, void* codes, float* scales, hipStream_t s);

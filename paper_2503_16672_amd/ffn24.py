@@ -32,7 +32,7 @@ EXPORTS = (
 
 KERNEL_NAMES = ("up_prune24", "down_sp", "dh_gather", "dx_sp", "featurewise24", "dw2_sp", "dw1_sp",
                 "dense_up", "dense_down", "dense_dh", "dense_dx", "dense_dw2", "dense_dw1", "transpose_weights", "transpose_acts",
-                "split_partition", "transpose_dw1", "quantise_rows", "quantise_dz_rows", "quantise_transposed", "panelise_bwd_weights")
+                "split_partition", "transpose_dw1", "quantise_rows", "quantise_dz_rows", "quantise_transposed", "panelise_bwd_weights", "panelise_x")
 
 
 
