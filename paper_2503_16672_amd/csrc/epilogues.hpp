@@ -58,13 +58,39 @@ struct EpiRowMajor {
   }
 };
 
-// C stored transposed, out[n][m] with m contiguous: 64 consecutive elements per lane and column.
-struct EpiColMajor {
-  struct Args { __bf16* C; int ldc; };
-  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+// Transposing store of a wave's 128 (m) x 128 (n) part of the tile, out[n][m] with m contiguous, through LDS.  A lane owns 64
+// consecutive m of 4 columns n, i.e. whole 128-byte runs of 4 output rows, but one store instruction of the wave would put 64
+// 16-byte pieces into 64 different lines (32 instructions, 2048 line transactions a wave; on the short-K weight-gradient GEMMs that
+// alone made the transposing kernels 15 % slower than the row-major ones).  So the packed pieces first go to a wave-private 32
+// KiB image [n][m] in the operand ring, which is free by then (row n, 16-byte piece c at piece position c ^ ((n >> 2) & 15), so
+// that the 16 lanes an LDS instruction serves together hit 16 different positions both ways), and leave as 32 instructions that
+// write 4 rows x 256 contiguous bytes each: 8 lines an instruction.
+struct ColMajorStage {
+  static constexpr int WAVE_BYTES = 128 * 256;
+  // piece `c` (0..15: m_local / 8) of row 4 rho + ni
+  static __device__ __forceinline__ void put(char* wbuf, int rho, int ni, int c, u32x4 v) {
+    *reinterpret_cast<u32x4*>(wbuf + (4 * rho + ni) * 256 + ((c ^ (rho & 15)) << 4)) = v;
+  }
+  // out = the wave's corner &C[n_wave][m_wave]
+  static __device__ __forceinline__ void flush(const char* wbuf, __bf16* out, int ldc) {
+    const int lane = threadIdx.x & 63, c = lane & 15, sub = lane >> 4;
 #pragma unroll
-    for (int ni = 0; ni < 4; ni++) {
-      __bf16* row = e.C + (size_t)(n_lane + ni) * e.ldc + m_lane;
+    for (int j = 0; j < 32; j++) {
+      const int r = 4 * j + sub;
+      u32x4 v = *reinterpret_cast<const u32x4*>(wbuf + r * 256 + ((c ^ (j & 15)) << 4));
+      *reinterpret_cast<u32x4*>(out + (size_t)r * ldc + 8 * c) = v;
+    }
+  }
+};
+
+// C stored transposed, out[n][m] with m contiguous (staged through LDS, see ColMajorStage; wbuf = the wave's 32 KiB).
+struct EpiColMajor {
+  static constexpr bool STAGED = true;
+  struct Args { __bf16* C; int ldc; };
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane, char* wbuf) {
+    const int lane = threadIdx.x & 63, rho = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int ni = 0; ni < 4; ni++)
 #pragma unroll
       for (int mi = 0; mi < 4; mi++)
 #pragma unroll
@@ -72,9 +98,9 @@ struct EpiColMajor {
           u32x4 o;
 #pragma unroll
           for (int d = 0; d < 4; d++) o[d] = pack_bf16x2(acc[mi][ni][8 * q + 2 * d], acc[mi][ni][8 * q + 2 * d + 1]);
-          *reinterpret_cast<u32x4*>(row + 16 * mi + 8 * q) = o;
+          ColMajorStage::put(wbuf, rho, ni, 8 * h + 2 * mi + q, o);
         }
-    }
+    ColMajorStage::flush(wbuf, e.C + (size_t)(n_lane - 4 * rho) * e.ldc + (m_lane - 64 * h), e.ldc);
   }
 };
 
@@ -443,11 +469,12 @@ struct EpiDGatherF8 {
 
 // out[n][m] = bf16(scale * acc), m contiguous: the transposing store of EpiColMajor with a scale (fp8 dW1).
 struct EpiColMajorScaled {
+  static constexpr bool STAGED = true;
   struct Args { __bf16* C; int ldc; float scale; };
-  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane, char* wbuf) {
+    const int lane = threadIdx.x & 63, rho = lane & 31, h = lane >> 5;
 #pragma unroll
-    for (int ni = 0; ni < 4; ni++) {
-      __bf16* row = e.C + (size_t)(n_lane + ni) * e.ldc + m_lane;
+    for (int ni = 0; ni < 4; ni++)
 #pragma unroll
       for (int mi = 0; mi < 4; mi++)
 #pragma unroll
@@ -455,9 +482,9 @@ struct EpiColMajorScaled {
           u32x4 o;
 #pragma unroll
           for (int d = 0; d < 4; d++) o[d] = pack_bf16x2(acc[mi][ni][8 * q + 2 * d] * e.scale, acc[mi][ni][8 * q + 2 * d + 1] * e.scale);
-          *reinterpret_cast<u32x4*>(row + 16 * mi + 8 * q) = o;
+          ColMajorStage::put(wbuf, rho, ni, 8 * h + 2 * mi + q, o);
         }
-    }
+    ColMajorStage::flush(wbuf, e.C + (size_t)(n_lane - 4 * rho) * e.ldc + (m_lane - 64 * h), e.ldc);
   }
 };
 
@@ -674,14 +701,15 @@ struct EpiRowMajorRowColMapped {
 // C stored transposed, out[n][m] = bf16(acc * rs[m] * cs[n]) with m contiguous (row-wise-scaled fp8 dW1 GEMM: rs = the scale of
 // each hidden feature's row of the transposed dZ operand, cs = the scale of each model dimension's row of the transposed X).
 struct EpiColMajorRowCol {
+  static constexpr bool STAGED = true;
   struct Args { __bf16* C; int ldc; const float* rs; const float* cs; };
-  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+  static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane, char* wbuf) {
+    const int lane = threadIdx.x & 63, rho = lane & 31, h = lane >> 5;
     LaneVec64 lr;
     lr.load(e.rs, m_lane, 1.f);
 #pragma unroll
     for (int ni = 0; ni < 4; ni++) {
       const float cs = e.cs[n_lane + ni];
-      __bf16* row = e.C + (size_t)(n_lane + ni) * e.ldc + m_lane;
 #pragma unroll
       for (int mi = 0; mi < 4; mi++)
 #pragma unroll
@@ -692,9 +720,10 @@ struct EpiColMajorRowCol {
             int i = 16 * mi + 8 * q + 2 * d;
             o[d] = pack_bf16x2(acc[mi][ni][8 * q + 2 * d] * lr.at(i) * cs, acc[mi][ni][8 * q + 2 * d + 1] * lr.at(i + 1) * cs);
           }
-          *reinterpret_cast<u32x4*>(row + 16 * mi + 8 * q) = o;
+          ColMajorStage::put(wbuf, rho, ni, 8 * h + 2 * mi + q, o);
         }
     }
+    ColMajorStage::flush(wbuf, e.C + (size_t)(n_lane - 4 * rho) * e.ldc + (m_lane - 64 * h), e.ldc);
   }
 };
 

@@ -403,6 +403,10 @@ __device__ __forceinline__ void tile_coords(int ntm, int ntn, int pid, int& tm, 
   tn = in / gsz;
 }
 
+// an epilogue that declares `static constexpr bool STAGED` takes a fifth argument: 32 KiB of LDS private to the wave
+template <class E, class = void> struct epi_is_staged : std::false_type {};
+template <class E> struct epi_is_staged<E, std::void_t<decltype(E::STAGED)>> : std::true_type {};
+
 // Epilogue concept:  struct E { struct Args {...}; static __device__ void run(const Args&, acc, m_lane, n_lane); }
 //   m_lane = global row of acc[0][*][0] for this lane (its 64 rows are m_lane + 16*mi + v),
 //   n_lane = global column of acc[*][0][*] (its 4 columns are n_lane + ni).
@@ -655,7 +659,14 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const typename Epi:
     if (!more) break;
     first = false;
   } else {
-    Epi::run(ea, acc, m_lane, n_lane);
+    if constexpr (epi_is_staged<Epi>::value) {
+      // the epilogue stages its stores through the operand ring: every wave must have read its last fragments first
+      static_assert(G::LDS_TOTAL >= GEMM_THREADS / 64 * 128 * 256, "a 32 KiB staging area per wave");
+      __builtin_amdgcn_s_barrier();
+      Epi::run(ea, acc, m_lane, n_lane, smem + wave * (128 * 256));
+    } else {
+      Epi::run(ea, acc, m_lane, n_lane);
+    }
     break;
   }
   }   // tiles
