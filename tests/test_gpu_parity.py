@@ -1956,3 +1956,60 @@ def test_fwd_bwd_replayed_from_a_hip_graph(F24):
     assert O.max_rel_err(f64(eager[0][0]), Yo) <= TOL_BF16
     del graph
     ctx.close()
+
+
+def test_fp8_rowwise_fwd_bwd_replayed_from_a_hip_graph(F24):
+    """The same for the row-wise fp8 recipe with the split and the token permutation on: the step clears its row maxima and
+    counters with kernels of its own, gathers scales with a kernel, and allocates nothing, so it records into a HIP graph;
+    every replay reproduces the eager step bit for bit."""
+    print("HIP graph: capture the row-wise fp8 fwd+bwd (split + permutation on), replay 4 times", flush=True)
+    T, D, Fh = 512, 256, 2048
+    ctx = F24.Context(T, D, Fh, F24.FFN24_ROWWISE | F24.FFN24_TRAINING | F24.FFN24_SPLIT | F24.FFN24_PERMUTE, dtype=F24.FFN24_FP8_E4M3)
+    ctx.set_split(256)
+    ctx.set_token_permutation(synth.token_permutation(T, seed=8))
+    sets = []
+    for i in range(2):
+        inp = synth.make_inputs_fp8_rowwise(T, D, Fh, "per_feature", seed=210 + i)
+        bw = synth.make_bwd_operands_fp8_rowwise(T, D, Fh, "per_feature", seed=210 + i)
+        d = {k: torch.from_numpy(v).cuda() for k, v in {**inp, **bw}.items()}
+        sets.append(d)
+    buf = {k: torch.empty_like(v) for k, v in sets[0].items()}          # static buffers the graph reads
+    Y = torch.empty((T, D), dtype=torch.bfloat16, device="cuda")
+    grads = (torch.empty((T, D), dtype=torch.bfloat16, device="cuda"), torch.empty((D, Fh), dtype=torch.bfloat16, device="cuda"),
+             torch.empty((Fh, D), dtype=torch.bfloat16, device="cuda"))
+    ctx.set_row_scales(buf["sx"], buf["sw1"], buf["sw2"])
+
+    def load(d):
+        for k in buf:
+            buf[k].copy_(d[k])
+
+    def step():
+        ctx.ffn24_fwd(buf["X"], buf["W1"], buf["b1"], buf["W2"], Y)
+        ctx.ffn24_bwd_rowwise(buf["dY8r"], buf["sdy_t"], buf["dY8c"], buf["sdy_d"], buf["X8c"], buf["sx_d"], buf["W2_8r"], buf["sw2_f"],
+                              buf["W1_8c"], buf["sw1_d"], out=grads)
+
+    eager = []
+    for d in sets:
+        load(d); step(); torch.cuda.synchronize()
+        eager.append([Y.clone()] + [g.clone() for g in grads])
+    assert not torch.equal(eager[0][3], eager[1][3])
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        load(sets[0])
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for rep, which in enumerate((0, 1, 1, 0)):
+        load(sets[which])
+        for t in [Y, *grads]:
+            t.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        junk = torch.randn(1 << 20, device="cuda").sum().item()
+        for name, a, b in zip(("Y", "dX", "dW1", "dW2"), [Y, *grads], eager[which]):
+            assert torch.equal(a, b), f"replay {rep} (inputs {which}): {name} differs from the eager step"
+    del graph
+    ctx.close()
