@@ -834,7 +834,7 @@ int ffn_bwd_rowwise(ffn24_ctx* c, const ffn24_rowwise_bwd_operands* op, void* dX
   { Timed t(c, K_QUANT_DZ, s);
     if (t.done(launch_quantise_rows_dense(c->dZd16, c->rowmax_dz, T, F, c->dZd, c->sdz_t, s))) return FFN24_ERR_HIP; }
   { Timed t(c, KD_DX, s);
-    if (t.done(launch_dense_rowmajor_f8_rowwise(c->dZd, getenv("FFN24_EXP") ? op->W1_8c : c->W1cp, getenv("FFN24_EXP") ? 0 : 1, T, D, F, c->sdz_t, op->sw1_d, dX, s))) return FFN24_ERR_HIP; }
+    if (t.done(launch_dense_rowmajor_f8_rowwise(c->dZd, c->W1cp, 1, T, D, F, c->sdz_t, op->sw1_d, dX, s))) return FFN24_ERR_HIP; }
   { Timed t(c, K_QUANT_T, s);      // per-feature maxima of the two transposed bf16 operands, then their quantisation
     int rc1 = launch_rowmax_dense(c->Hdt16, F, T, c->hmax, s);
     if (!rc1) rc1 = launch_rowmax_dense(c->dZdt16, F, T, c->zmax, s);
