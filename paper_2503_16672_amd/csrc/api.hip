@@ -243,9 +243,9 @@ int ffn24_ctx_create(ffn24_ctx** out, int64_t T, int64_t D, int64_t F, ffn24_dty
          hipMalloc(reinterpret_cast<void**>(&c->rowmax_dz), 4 * (size_t)T) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->hmax), 4 * (size_t)F) == hipSuccess &&
          hipMalloc(reinterpret_cast<void**>(&c->zmax), 4 * (size_t)F) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->sdz_t), 4 * (size_t)T) == hipSuccess &&
          hipMalloc(reinterpret_cast<void**>(&c->sh_f), 4 * (size_t)F) == hipSuccess && hipMalloc(reinterpret_cast<void**>(&c->sdz_f), 4 * (size_t)F) == hipSuccess &&
-         hipMalloc(&c->W2rp, df) == hipSuccess && hipMalloc(&c->W1cp, df) == hipSuccess;
-  if (ok && (flags & FFN24_ROWWISE) && (flags & FFN24_TRAINING) && (flags & FFN24_DENSE))
-    ok = hipMalloc(&c->dZd16, 2 * tf) == hipSuccess && hipMalloc(&c->Hdt16, 2 * tf) == hipSuccess && hipMalloc(&c->dZdt16, 2 * tf) == hipSuccess;
+         hipMalloc(&c->W2rp, df) == hipSuccess;
+  if (ok && (flags & FFN24_ROWWISE) && (flags & FFN24_TRAINING) && (flags & FFN24_DENSE))   // (W1cp: only the dense dX GEMM wants W1_8c in panel form)
+    ok = hipMalloc(&c->W1cp, df) == hipSuccess && hipMalloc(&c->dZd16, 2 * tf) == hipSuccess && hipMalloc(&c->Hdt16, 2 * tf) == hipSuccess && hipMalloc(&c->dZdt16, 2 * tf) == hipSuccess;
   if (ok && (flags & FFN24_DENSE)) ok = hipMalloc(&c->Hd, es * tf) == hipSuccess;
   if (ok && (flags & FFN24_DENSE) && (flags & FFN24_ROWWISE)) ok = hipMalloc(&c->Hd16, 2 * tf) == hipSuccess;
   if (ok && (flags & FFN24_DENSE) && (flags & FFN24_TRAINING))
