@@ -42,6 +42,40 @@ struct LaneIdx64 {
   __device__ __forceinline__ int at(int i) const { return v[i >> 2][i & 3]; }
 };
 
+// What the backward epilogues read back of the forward's saved activation, for the lane's 4 tokens x 64 features, requested in one
+// go before any arithmetic or store: a load placed inside the loops is followed by stores through pointers the compiler must assume
+// may alias, so each one waited out a full memory round trip by itself (16 of them in the 2:4 epilogue, 32 in the dense one -- the
+// latter had made the dense dH kernel 0.4 ms slower than the GEMM alone).
+// 2:4: one 64-byte piece of kept values + 8 metadata bytes per token (bf16 panel form).
+struct LaneSaved24 {
+  u32x4 h[4][4];   // [ni][mi]: the kept values of groups 4 mi .. 4 mi + 3
+  u32x2 mt[4];
+  __device__ __forceinline__ void load(const __bf16* Hc, const uint8_t* meta, int F, int m_lane, int n_lane) {
+#pragma unroll
+    for (int ni = 0; ni < 4; ni++) {
+      size_t piece = a24_piece(n_lane + ni, m_lane >> 6, F >> 6);
+      mt[ni] = *reinterpret_cast<const u32x2*>(meta + piece * 8);
+#pragma unroll
+      for (int mi = 0; mi < 4; mi++) h[ni][mi] = *reinterpret_cast<const u32x4*>(Hc + piece * 32 + 8 * mi);
+    }
+  }
+};
+// dense: the bf16 activation in dense panel form (64-byte pieces of 32 features), 16 features per (mi, ni).
+struct LaneSavedDense {
+  u32x4 h[4][4][2];   // [mi][ni][q]: features 16 mi + 8 q .. + 7 of token ni
+  __device__ __forceinline__ void load(const __bf16* H, int F, int m_lane, int n_lane) {
+#pragma unroll
+    for (int mi = 0; mi < 4; mi++)
+#pragma unroll
+      for (int ni = 0; ni < 4; ni++) {
+        int f = m_lane + 16 * mi;
+        const __bf16* p = H + a24_piece(n_lane + ni, f >> 5, F >> 5) * 32 + (f & 31);
+        h[mi][ni][0] = *reinterpret_cast<const u32x4*>(p);
+        h[mi][ni][1] = *reinterpret_cast<const u32x4*>(p + 8);
+      }
+  }
+};
+
 // C[m][n], n contiguous: 4 consecutive columns per lane and row -> one 8-byte store per row.
 struct EpiRowMajor {
   struct Args { __bf16* C; int ldc; };
@@ -286,6 +320,8 @@ struct EpiRowMajorMapped {
 struct EpiDRelu {
   struct Args { const __bf16* H; __bf16* dZ; __bf16* dZt; int F; int T; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+    LaneSavedDense sv;
+    sv.load(e.H, e.F, m_lane, n_lane);
 #pragma unroll
     for (int mi = 0; mi < 4; mi++) {
 #pragma unroll
@@ -294,7 +330,7 @@ struct EpiDRelu {
         size_t o = a24_piece(n_lane + ni, f >> 5, e.F >> 5) * 32 + (f & 31);
 #pragma unroll
         for (int q = 0; q < 2; q++) {
-          u32x4 h = *reinterpret_cast<const u32x4*>(e.H + o + 8 * q);
+          const u32x4 h = sv.h[mi][ni][q];
           u32x4 r;
 #pragma unroll
           for (int d = 0; d < 4; d++) {
@@ -326,16 +362,17 @@ struct EpiDRelu {
 struct EpiDGather {
   struct Args { const __bf16* Hc; const uint8_t* meta; __bf16* dZc; int F; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+    LaneSaved24 sv;
+    sv.load(e.Hc, e.meta, e.F, m_lane, n_lane);
 #pragma unroll
     for (int ni = 0; ni < 4; ni++) {
       size_t t = (size_t)(n_lane + ni);
       size_t piece = a24_piece((int)t, m_lane >> 6, e.F >> 6);
-      const __bf16* hrow = e.Hc + piece * 32;
-      u32x2 mt = *reinterpret_cast<const u32x2*>(e.meta + piece * 8);
+      const u32x2 mt = sv.mt[ni];
       __bf16* zrow = e.dZc + piece * 32;
 #pragma unroll
       for (int mi = 0; mi < 4; mi++) {
-        u32x4 h = *reinterpret_cast<const u32x4*>(hrow + 8 * mi);
+        const u32x4 h = sv.h[ni][mi];
         u32x4 z;
 #pragma unroll
         for (int a = 0; a < 4; a++) {
@@ -435,16 +472,16 @@ struct EpiPrune24F8 {
 struct EpiDGatherF8 {
   struct Args { const __bf16* Hc16; const uint8_t* meta16; uint8_t* dZc8; int F; float scale; float sdz; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
+    LaneSaved24 sv;
+    sv.load(e.Hc16, e.meta16, e.F, m_lane, n_lane);
 #pragma unroll
     for (int ni = 0; ni < 4; ni++) {
       size_t t = (size_t)(n_lane + ni);
-      size_t piece16 = a24_piece((int)t, m_lane >> 6, e.F >> 6);
-      const __bf16* hrow = e.Hc16 + piece16 * 32;
-      u32x2 mt = *reinterpret_cast<const u32x2*>(e.meta16 + piece16 * 8);
+      const u32x2 mt = sv.mt[ni];
       uint32_t q8[8];
 #pragma unroll
       for (int mi = 0; mi < 4; mi++) {
-        u32x4 h = *reinterpret_cast<const u32x4*>(hrow + 8 * mi);
+        const u32x4 h = sv.h[ni][mi];
 #pragma unroll
         for (int a = 0; a < 4; a++) {
           int gi = 4 * mi + a;
@@ -619,6 +656,8 @@ struct EpiDReluRw {
     float cs[4];
 #pragma unroll
     for (int ni = 0; ni < 4; ni++) cs[ni] = e.cs[n_lane + ni];
+    LaneSavedDense sv;
+    sv.load(e.H16, e.F, m_lane, n_lane);
 #pragma unroll
     for (int mi = 0; mi < 4; mi++) {
 #pragma unroll
@@ -627,7 +666,7 @@ struct EpiDReluRw {
         size_t o = a24_piece(n_lane + ni, f >> 5, e.F >> 5) * 32 + (f & 31);
 #pragma unroll
         for (int q = 0; q < 2; q++) {
-          u32x4 h = *reinterpret_cast<const u32x4*>(e.H16 + o + 8 * q);
+          const u32x4 h = sv.h[mi][ni][q];
           u32x4 r;
 #pragma unroll
           for (int d = 0; d < 4; d++) {
@@ -739,18 +778,22 @@ struct EpiDGatherRw {
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
     LaneVec64 lr;
     lr.load(e.rs, m_lane, 1.f);
+    LaneSaved24 sv;
+    sv.load(e.Hc16, e.meta16, e.F, m_lane, n_lane);
+    float csv[4];
+#pragma unroll
+    for (int ni = 0; ni < 4; ni++) csv[ni] = e.cs[n_lane + ni];
 #pragma unroll
     for (int ni = 0; ni < 4; ni++) {
       size_t t = (size_t)(n_lane + ni);
-      const float cs = e.cs[t];
+      const float cs = csv[ni];
       size_t piece = a24_piece((int)t, m_lane >> 6, e.F >> 6);
-      const __bf16* hrow = e.Hc16 + piece * 32;
-      u32x2 mt = *reinterpret_cast<const u32x2*>(e.meta16 + piece * 8);
+      const u32x2 mt = sv.mt[ni];
       __bf16* zrow = e.dZc16 + piece * 32;
       uint32_t mx = 0u;
 #pragma unroll
       for (int mi = 0; mi < 4; mi++) {
-        u32x4 h = *reinterpret_cast<const u32x4*>(hrow + 8 * mi);
+        const u32x4 h = sv.h[ni][mi];
         u32x4 z;
 #pragma unroll
         for (int a = 0; a < 4; a++) {
@@ -830,17 +873,17 @@ struct EpiDReluF8 {
   struct Args { const __bf16* H16; uint8_t* dZ8; uint8_t* dZ8t; int F; int T; float scale; float sdz; };
   static __device__ __forceinline__ void run(const Args& e, f32x16 (&acc)[4][4], int m_lane, int n_lane) {
     uint32_t qs[4][16];
+    LaneSavedDense sv;
+    sv.load(e.H16, e.F, m_lane, n_lane);
 #pragma unroll
     for (int ni = 0; ni < 4; ni++) {
       uint8_t* row = e.dZ8 + a24_piece(n_lane + ni, m_lane >> 6, e.F >> 6) * 64;
 #pragma unroll
       for (int mi = 0; mi < 4; mi++) {
-        int f = m_lane + 16 * mi;
-        const __bf16* r16 = e.H16 + a24_piece(n_lane + ni, f >> 5, e.F >> 5) * 32 + (f & 31);
         uint32_t q[4];
 #pragma unroll
         for (int hq = 0; hq < 2; hq++) {
-          u32x4 h = *reinterpret_cast<const u32x4*>(r16 + 8 * hq);
+          const u32x4 h = sv.h[mi][ni][hq];
 #pragma unroll
           for (int d = 0; d < 4; d++) {
             float g0 = 2.f * __builtin_amdgcn_sqrtf(bf16_lo_to_f32(h[d]));
