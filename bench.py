@@ -259,6 +259,45 @@ def run_split_sweep(args) -> int:
     return 0
 
 
+def run_fwd_sweep(args) -> int:
+    """FFN forward, 2:4 against dense, over model dimensions and token counts (what the paper's forward-speed-up figure plots:
+    larger models and larger batches gain more), in the paper's precision recipe (fp8 with row-wise scales) and in bf16; d_ff = 4
+    d_model, 90 % zeros, weights prepared once (inference).  Synthetic inputs by the workloads' recipe."""
+    import torch
+    from paper_2503_16672_amd import ffn24, synth
+    points = []
+    for D in (2048, 4096, 8192):
+        F = 4 * D
+        for T in (4096, 8192, 16384):
+            row = {"T": T, "d_model": D, "d_ff": F}
+            for mode in ("fp8_rowwise", "bf16"):
+                if mode == "bf16":
+                    inp = synth.make_inputs(T, D, F, 0.9, seed=7000 + D + T)
+                    dev = {k: torch.from_numpy(inp[k]).to(torch.bfloat16).cuda() for k in ("X", "W1", "W2")}
+                    ctx = ffn24.Context(T, D, F, ffn24.FFN24_DENSE)
+                else:
+                    inp = synth.make_inputs_fp8_rowwise(T, D, F, 0.9, seed=7000 + D + T)
+                    dev = {k: torch.from_numpy(inp[k]).cuda() for k in ("X", "W1", "W2", "sx", "sw1", "sw2")}
+                    ctx = ffn24.Context(T, D, F, ffn24.FFN24_ROWWISE | ffn24.FFN24_DENSE, dtype=ffn24.FFN24_FP8_E4M3)
+                    ctx.set_row_scales(dev["sx"], dev["sw1"], dev["sw2"])
+                b1 = torch.from_numpy(inp["b1"]).cuda()
+                Y = torch.empty((T, D), dtype=torch.bfloat16, device="cuda")
+                ctx.prepare_weights(dev["W1"], dev["W2"])
+                _, m24, _ = _time_steps(torch, lambda: ctx.ffn24_fwd(dev["X"], None, b1, None, Y), args.warmup, args.steps)
+                _, md, _ = _time_steps(torch, lambda: ctx.ffn_fwd(dev["X"], None, b1, None, Y), args.warmup, args.steps)
+                row[mode] = {"ms_24": round(m24 * 1e3, 4), "ms_dense": round(md * 1e3, 4), "speedup": round(md / m24, 4),
+                             "tflops_dense_equivalent": round(4.0 * T * D * F / m24 / 1e12, 1)}
+                ctx.close()
+                del dev, ctx
+                torch.cuda.empty_cache()
+            points.append(row)
+            print(f"# T={T} d_model={D}: {row}", file=sys.stderr, flush=True)
+    print(json.dumps({"metric": "FFN fwd speed-up over the dense FFN", "unit": "x", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                      "data": "synthetic", "config": {"workload": "forward sweep: d_ff = 4 d_model, 90 % zeros, weights prepared once; median of per-call event times"},
+                      "points": points}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -278,6 +317,7 @@ def main() -> int:
     ap.add_argument("--permute", action="store_true", help="run the bf16 workload (or c5 with --fp8-bwd --rowwise) with a fixed token permutation around the FFN")
     ap.add_argument("--telemetry", action="store_true", help="bf16 workloads: count sparsity and 2:4 drops while running (reported under \"telemetry\")")
     ap.add_argument("--split-sweep", action="store_true", help="time the weight-gradient stage over a range of split sizes")
+    ap.add_argument("--fwd-sweep", action="store_true", help="forward speed-up over the dense FFN across model dimensions and token counts (fp8 row-wise and bf16)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy before the steps (the known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -298,6 +338,8 @@ def main() -> int:
         return run_c3(args)
     if args.split_sweep:
         return run_split_sweep(args)
+    if args.fwd_sweep:
+        return run_fwd_sweep(args)
     w = synth.WORKLOADS[args.workload]
     T, D, F = w.T, w.D, w.F
     fp8 = args.workload == "c5"
