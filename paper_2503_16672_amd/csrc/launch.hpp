@@ -167,7 +167,7 @@ int launch_unpanel(const void* src, int rows, int npanels, int piece_bytes, void
 // in_panel (may be NULL): also a panel-form copy of `in` itself (then R % 256 == 0), in the B form if in_panel_b
 // in_rowmap (may be NULL): row r of the input is taken from memory row in_rowmap[r]
 int launch_transpose(const void* in, int R, int C, void* out, int out_form, void* in_panel, int in_panel_b, const int* in_rowmap, hipStream_t s);
-// the same for 1-byte elements (fp8): in [R][C] -> out [C][R]; panel forms: 64-byte pieces of 64 k
+// the same for 1-byte elements (fp8): in [R][C] -> out [C][R] (R % 64 == 0, C % 256 == 0); panel forms: 64-byte pieces of 64 k
 // in_panel (may be NULL): also a panel-form copy of `in` itself (R % 256 == 0, C % 64 == 0), in the B form if in_panel_b
 int launch_transpose8(const void* in, int R, int C, void* out, int out_form, void* in_panel, int in_panel_b, hipStream_t s);
 // the same without the panel copy, input row r taken from memory row in_rowmap[r] (may be NULL)
