@@ -477,50 +477,66 @@ int launch_unpanel(const void* src, int rows, int npanels, int piece_bytes, void
   return (int)hipGetLastError();
 }
 
-// out[c][r] = in[r][c] for a bf16 matrix [R][C], R and C multiples of 64.  One workgroup per 64 x TR_COLS tile: rows are
-// read 128 bytes at a time, scattered into an LDS tile with a 132-byte pitch (conflict-free for this pattern), and
-// written out as 128-byte rows of the transposed matrix.
+// out[c][r] = in[r][c] for a bf16 matrix [R][C], R a multiple of 64 and C of 128.  One workgroup per tile of 64 rows x 128
+// columns: a work item reads 16 bytes of each of 2 consecutive rows (a row's 256 bytes are read by 16 neighbouring work items),
+// pairs the rows' elements column by column with byte permutes, and writes 8 dwords -- 2 elements along r of 8 transposed rows --
+// into an LDS image [c][r] (pitch 33 dwords; a row's dwords are rotated by 4 for the second 64 columns, which spreads a wave's
+// writes over all banks); then 16 bytes of a transposed row per work item go out: 128 rows x 128 bytes.  (One 64 x 64 tile per
+// workgroup with element-wise LDS scatter, the first version, moved 4.3-4.9 TB/s.)
 // OUT_FORM: 0 row-major; 1 the dense panel form of gemm_core.hpp (64-byte pieces of 32 k, K = R), as A operands take it;
 // 2 the B panel form (the same with the rows of every block of 256 in LDS order).
 // in_panel (optional): a copy of the input itself in panel form (K = C), made in the same pass; in_panel_b: in the B form.
 // in_rowmap (optional): input row r is read from memory row in_rowmap[r] (token permutation).
-constexpr int TR_LD = 66, TR_COLS = 64;   // a tile is 64 rows x TR_COLS columns (128 columns, 256-byte row segments in, measured 2-5 % slower)
+constexpr int TR_COLS = 128, TR_LDW = 33;
 
 template <int OUT_FORM>
 __global__ void __launch_bounds__(256) transpose_kernel(const uint16_t* __restrict__ in, int R, int C, uint16_t* __restrict__ out,
                                                         uint16_t* __restrict__ in_panel, int in_panel_b, const int* __restrict__ in_rowmap) {
-  __shared__ __attribute__((aligned(16))) uint16_t sT[TR_COLS * TR_LD];
-  int r0 = blockIdx.y * 64, c0 = blockIdx.x * TR_COLS;
-  int tid = threadIdx.x;
-  constexpr int CH = TR_COLS / 8;            // 16-byte chunks per input row segment
-  int ch = tid % CH, rr = tid / CH;
+  __shared__ uint32_t sT[TR_COLS * TR_LDW];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * TR_COLS;
+  const int tid = threadIdx.x;
+  const int ch = tid & 15;                   // 16-byte chunk of a row segment: columns 8 ch .. 8 ch + 7 of the tile
+  const int rot = ch >> 3;                   // (c >> 6) of every column this work item holds
+  u32x4 v[2][2];
 #pragma unroll
-  for (int i = 0; i < 64 * CH / 256; i++) {
-    int r = rr + (256 / CH) * i;
-    size_t src_row = in_rowmap ? (size_t)in_rowmap[r0 + r] : (size_t)(r0 + r);
-    u32x4 v = ld_stream(reinterpret_cast<const u32x4*>(in + src_row * C + c0 + 8 * ch));
-    if (in_panel) {
-      int c = c0 + 8 * ch;
-      int prow = in_panel_b ? b_panel_pos(r0 + r) : r0 + r;
-      st_stream(reinterpret_cast<u32x4*>(in_panel + a24_piece(prow, c >> 5, C >> 5) * 32 + (c & 31)), v);
+  for (int pass = 0; pass < 2; pass++)
+#pragma unroll
+    for (int i = 0; i < 2; i++) {
+      const int r = r0 + 2 * ((tid >> 4) + 16 * pass) + i;
+      const size_t src_row = in_rowmap ? (size_t)in_rowmap[r] : (size_t)r;
+      v[pass][i] = ld_stream(reinterpret_cast<const u32x4*>(in + src_row * C + c0 + 8 * ch));
     }
 #pragma unroll
-    for (int d = 0; d < 4; d++) {
-      sT[(8 * ch + 2 * d) * TR_LD + r] = (uint16_t)(v[d] & 0xFFFFu);
-      sT[(8 * ch + 2 * d + 1) * TR_LD + r] = (uint16_t)(v[d] >> 16);
+  for (int pass = 0; pass < 2; pass++) {
+    const int rp = (tid >> 4) + 16 * pass;   // pair of rows 2 rp, 2 rp + 1 of the tile
+    if (in_panel) {
+      const int c = c0 + 8 * ch;
+#pragma unroll
+      for (int i = 0; i < 2; i++) {
+        const int r = r0 + 2 * rp + i;
+        const int prow = in_panel_b ? b_panel_pos(r) : r;
+        st_stream(reinterpret_cast<u32x4*>(in_panel + a24_piece(prow, c >> 5, C >> 5) * 32 + (c & 31)), v[pass][i]);
+      }
+    }
+    uint32_t* dst = sT + ((rp + 4 * rot) & 31);
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+      const int c = 8 * ch + 2 * g;
+      dst[c * TR_LDW] = __builtin_amdgcn_perm(v[pass][1][g], v[pass][0][g], 0x05040100u);         // column c: rows 2 rp, 2 rp + 1
+      dst[(c + 1) * TR_LDW] = __builtin_amdgcn_perm(v[pass][1][g], v[pass][0][g], 0x07060302u);   // column c + 1
     }
   }
   __syncthreads();
-  int oc = tid & 7, cc = tid >> 3;           // 16-byte chunk of an output row (8 of the tile's 64 rows), output row
+  const int q = tid & 7;                     // 16-byte chunk of a transposed row: 8 of the tile's 64 rows r
 #pragma unroll
-  for (int i = 0; i < TR_COLS / 32; i++) {
-    int c = cc + 32 * i;
-    const uint32_t* src = reinterpret_cast<const uint32_t*>(&sT[c * TR_LD + 8 * oc]);
-    u32x4 v = {src[0], src[1], src[2], src[3]};
-    int r = r0 + 8 * oc;
-    if constexpr (OUT_FORM == 1) st_stream(reinterpret_cast<u32x4*>(out + a24_piece(c0 + c, r >> 5, R >> 5) * 32 + (r & 31)), v);
-    else if constexpr (OUT_FORM == 2) st_stream(reinterpret_cast<u32x4*>(out + a24_piece(b_panel_pos(c0 + c), r >> 5, R >> 5) * 32 + (r & 31)), v);
-    else st_stream(reinterpret_cast<u32x4*>(out + (size_t)(c0 + c) * R + r), v);
+  for (int p = 0; p < TR_COLS / 32; p++) {
+    const int c = (tid >> 3) + 32 * p;       // transposed row
+    const uint32_t* src = sT + c * TR_LDW + 4 * ((q + (c >> 6)) & 7);
+    u32x4 o = {src[0], src[1], src[2], src[3]};
+    const int r = r0 + 8 * q;
+    if constexpr (OUT_FORM == 1) st_stream(reinterpret_cast<u32x4*>(out + a24_piece(c0 + c, r >> 5, R >> 5) * 32 + (r & 31)), o);
+    else if constexpr (OUT_FORM == 2) st_stream(reinterpret_cast<u32x4*>(out + a24_piece(b_panel_pos(c0 + c), r >> 5, R >> 5) * 32 + (r & 31)), o);
+    else st_stream(reinterpret_cast<u32x4*>(out + (size_t)(c0 + c) * R + r), o);
   }
 }
 

@@ -162,7 +162,7 @@ int launch_featurewise24(const void* Hc, const uint8_t* meta, const void* dZc, i
 int launch_tele_sum(const unsigned long long* tele, long long elements, long long path, long long* out, hipStream_t s);
 // panel form -> row-major copy of a compressed operand: rows x npanels pieces of `piece_bytes` (64 values / 8 or 16 metadata)
 int launch_unpanel(const void* src, int rows, int npanels, int piece_bytes, void* dst, hipStream_t s);
-// in [R][C] -> out [C][R] (R, C % 64 == 0); out_form: 0 row-major, 1 dense panel form (A operands), 2 B panel form
+// in [R][C] -> out [C][R] (R % 64 == 0, C % 128 == 0); out_form: 0 row-major, 1 dense panel form (A operands), 2 B panel form
 // (gemm_core.hpp; both then need C % 256 == 0);
 // in_panel (may be NULL): also a panel-form copy of `in` itself (then R % 256 == 0), in the B form if in_panel_b
 // in_rowmap (may be NULL): row r of the input is taken from memory row in_rowmap[r]
